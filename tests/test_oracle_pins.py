@@ -1,0 +1,365 @@
+"""Pins for the CPU oracle: closed forms, invariants, float64 library routines, brute force.
+
+The paper prints no worked numeric example of the forward pass (section 2.1 defines attention in
+prose only), so the oracle is pinned by what the mathematics fixes.  Each test is chosen so that a
+plausible slip in oracle/ld_oracle.c (dropped gain or scale, eps outside the root, wrong RoPE pairing
+or sign, transposed matrix, off-by-one context, wrong block/slot index, wrong tie-break) fails it.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+from workloads import gen, TINY, make_weights, SEED_BASE
+
+RNG = np.random.default_rng(7)
+
+
+# ------------------------------------------------------------------ RMSNorm
+
+def test_rmsnorm_constant_vector_closed_form():
+    d, c, eps = 256, 3.0, 1e-5
+    g = (1 + 0.1 * RNG.standard_normal(d)).astype(np.float32)
+    out = oracle.rmsnorm(np.full(d, c), g, eps)
+    np.testing.assert_allclose(out, g.astype(np.float64) * c / math.sqrt(c * c + eps), rtol=1e-14)
+
+
+def test_rmsnorm_unit_gain_mean_square():
+    x = RNG.standard_normal(512) * 1e-2          # small x so that eps matters
+    eps = 1e-5
+    out = oracle.rmsnorm(x, np.ones(512, np.float32), eps)
+    ms = np.mean(x * x)
+    assert np.mean(out * out) == pytest.approx(ms / (ms + eps), rel=1e-12)
+
+
+def test_rmsnorm_matches_library():
+    x = torch.from_numpy(RNG.standard_normal(688)); g = torch.from_numpy(RNG.standard_normal(688)).float()
+    ref = F.rms_norm(x, (688,), g.double(), eps=1e-5).numpy()
+    np.testing.assert_allclose(oracle.rmsnorm(x.numpy(), g.numpy(), 1e-5), ref, rtol=1e-13, atol=1e-15)
+
+
+# ------------------------------------------------------------------ RoPE
+
+def test_rope_position_zero_is_identity_and_norm_preserved():
+    u = RNG.standard_normal(128)
+    np.testing.assert_array_equal(oracle.rope_head(u, 0), u)
+    r = oracle.rope_head(u, 1234)
+    half = 64
+    np.testing.assert_allclose(r[:half] ** 2 + r[half:] ** 2, u[:half] ** 2 + u[half:] ** 2, rtol=1e-12)
+
+
+def test_rope_pair_zero_is_plain_rotation_by_position():
+    u = np.zeros(64); u[0] = 1.0                # pair 0 = (u[0], u[32]) has theta_0 = 1
+    r = oracle.rope_head(u, 5)
+    assert r[0] == pytest.approx(math.cos(5.0), abs=1e-15)
+    assert r[32] == pytest.approx(math.sin(5.0), abs=1e-15)
+    assert np.count_nonzero(r) == 2
+
+
+def test_rope_matches_complex_multiplication():
+    hd, pos, base = 128, 977, 10000.0
+    u = RNG.standard_normal(hd)
+    theta = torch.tensor([base ** (-2.0 * i / hd) for i in range(hd // 2)], dtype=torch.float64)
+    z = torch.complex(torch.from_numpy(u[: hd // 2]), torch.from_numpy(u[hd // 2:]))
+    w = z * torch.polar(torch.ones_like(theta), pos * theta)
+    ref = np.concatenate([w.real.numpy(), w.imag.numpy()])
+    np.testing.assert_allclose(oracle.rope_head(u, pos, base), ref, rtol=1e-12, atol=1e-14)
+
+
+def test_rope_scores_depend_on_relative_position_only():
+    q, k = RNG.standard_normal(64), RNG.standard_normal(64)
+    a = oracle.rope_head(q, 40) @ oracle.rope_head(k, 17)
+    b = oracle.rope_head(q, 40 + 300) @ oracle.rope_head(k, 17 + 300)
+    assert a == pytest.approx(b, rel=1e-10)
+    assert abs(a - oracle.rope_head(q, 41) @ oracle.rope_head(k, 17)) > 1e-6
+
+
+# ------------------------------------------------------------------ softmax / attention
+
+def test_softmax_sums_to_one_shift_invariant_and_matches_library():
+    s = RNG.standard_normal(1000) * 5
+    p = oracle.softmax(s)
+    assert p.sum() == pytest.approx(1.0, abs=1e-14)
+    np.testing.assert_allclose(oracle.softmax(s + 123.0), p, rtol=1e-11)
+    np.testing.assert_allclose(p, torch.softmax(torch.from_numpy(s), 0).numpy(), rtol=1e-13)
+    big = oracle.softmax(np.array([1e4, 0.0, -1e4]))     # max subtraction: no overflow
+    np.testing.assert_allclose(big, [1.0, 0.0, 0.0], atol=1e-300)
+
+
+def test_attention_single_token_returns_value_exactly():
+    q, k, v = RNG.standard_normal(128), RNG.standard_normal((1, 128)), RNG.standard_normal((1, 128))
+    np.testing.assert_array_equal(oracle.attention_contig(q, k, v), v[0])
+
+
+def test_attention_equal_keys_gives_mean_of_values():
+    q = RNG.standard_normal(64); k = np.tile(RNG.standard_normal(64), (37, 1)); v = RNG.standard_normal((37, 64))
+    np.testing.assert_allclose(oracle.attention_contig(q, k, v), v.mean(0), rtol=1e-12, atol=1e-14)
+
+
+def test_attention_dominant_key_selects_its_value():
+    q = np.zeros(64); q[3] = 1.0
+    k = np.zeros((9, 64)); k[5, 3] = 1e4
+    v = RNG.standard_normal((9, 64))
+    np.testing.assert_allclose(oracle.attention_contig(q, k, v), v[5], atol=1e-12)
+
+
+def test_attention_is_invariant_to_permuting_key_value_pairs():
+    q, k, v = RNG.standard_normal(128), RNG.standard_normal((50, 128)), RNG.standard_normal((50, 128))
+    p = RNG.permutation(50)
+    np.testing.assert_allclose(oracle.attention_contig(q, k[p], v[p]), oracle.attention_contig(q, k, v), rtol=1e-11)
+
+
+def test_attention_matches_library_sdpa_including_scale():
+    n, hd = 77, 128
+    q, k, v = RNG.standard_normal(hd), RNG.standard_normal((n, hd)), RNG.standard_normal((n, hd))
+    ref = F.scaled_dot_product_attention(torch.from_numpy(q)[None, None, None, :], torch.from_numpy(k)[None, None],
+                                         torch.from_numpy(v)[None, None])[0, 0, 0].numpy()
+    np.testing.assert_allclose(oracle.attention_contig(q, k, v), ref, rtol=1e-11, atol=1e-14)
+
+
+def _paged_case(B, H, Hkv, hd, lens, bits):
+    blk = 16
+    nblk = [(n + blk - 1) // blk for n in lens]
+    total = sum(nblk) + 3
+    perm = gen.permutation(11, 5, total).numpy()
+    table = np.full((B, max(nblk)), -1, np.int32)
+    it = iter(perm)
+    for b in range(B):
+        for j in range(nblk[b]):
+            table[b, j] = next(it)
+    kf = gen.normal(11, 6, (total, Hkv, blk, hd)); vf = gen.normal(11, 7, (total, Hkv, blk, hd))
+    if bits:
+        kf, vf = kf.bfloat16(), vf.bfloat16()
+    return table, kf, vf
+
+
+@pytest.mark.parametrize("bits", [False, True])
+def test_paged_attention_equals_contiguous_gather(bits):
+    B, H, Hkv, hd = 3, 4, 2, 64
+    lens = [1, 17, 48]
+    table, kf, vf = _paged_case(B, H, Hkv, hd, lens, bits)
+    q = RNG.standard_normal((B, H, hd))
+    kp, vp = oracle.to_host_matrix(kf), oracle.to_host_matrix(vf)
+    out = oracle.paged_attention(q, kp, vp, (Hkv * 16 * hd, 16 * hd, hd), table, lens, Hkv)
+    kd, vd = kf.double().numpy(), vf.double().numpy()
+    for b in range(B):
+        for h in range(H):
+            g = h // (H // Hkv)
+            K = np.stack([kd[table[b, j // 16], g, j % 16] for j in range(lens[b])])
+            V = np.stack([vd[table[b, j // 16], g, j % 16] for j in range(lens[b])])
+            ref = torch.softmax(torch.from_numpy(K @ q[b, h]) / math.sqrt(hd), 0).numpy() @ V
+            np.testing.assert_allclose(out[b, h], ref, rtol=1e-11, atol=1e-14)
+
+
+# ------------------------------------------------------------------ SwiGLU, matvec, rounding, argmax
+
+def test_silu_identities():
+    assert oracle.silu(0.0) == 0.0
+    for z in (0.3, 2.0, 11.5):
+        assert oracle.silu(z) - oracle.silu(-z) == pytest.approx(z, rel=1e-14)
+    assert oracle.silu(1.0) == pytest.approx(F.silu(torch.tensor(1.0, dtype=torch.float64)).item(), rel=1e-15)
+
+
+def test_matvec_matches_float64_matmul_and_is_not_transposed():
+    w = RNG.standard_normal((37, 53)).astype(np.float32); x = RNG.standard_normal(53)
+    np.testing.assert_allclose(oracle.matvec(w, x), w.astype(np.float64) @ x, rtol=1e-13, atol=1e-14)
+    onehot = np.zeros((2, 53), np.float32); onehot[0, 7] = 1; onehot[1, 50] = 1
+    np.testing.assert_array_equal(oracle.matvec(onehot, x), x[[7, 50]])
+
+
+def test_matvec_reads_bf16_bit_patterns():
+    w = torch.from_numpy(RNG.standard_normal((19, 64))).bfloat16(); x = RNG.standard_normal(64)
+    np.testing.assert_allclose(oracle.matvec(oracle.to_host_matrix(w), x), w.double().numpy() @ x, rtol=1e-13)
+
+
+def test_round_bf16_is_nearest_even_like_the_library_cast():
+    x = torch.cat([torch.from_numpy(RNG.standard_normal(5000)).float() * 3,
+                   torch.tensor([1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, 1.00390625, 0.0, -2.5, 3e-39])])
+    ref = x.bfloat16().double().numpy()                 # float32 -> bf16 is RNE in torch
+    np.testing.assert_array_equal(oracle.round_bf16(x.double().numpy()), ref)
+    # ties: 1 + 2^-8 is halfway between 1 and 1 + 2^-7 -> even (1.0); 1 + 3*2^-8 -> 1 + 2^-6
+    assert oracle.round_bf16(1.0 + 2 ** -8) == 1.0 and oracle.round_bf16(1.0 + 3 * 2 ** -8) == 1.0 + 2 ** -6
+    # a double just above the tie must round up although its float32 image is the tie itself
+    assert oracle.round_bf16(1.0 + 2 ** -8 + 2 ** -40) == 1.0 + 2 ** -7
+
+
+def test_argmax_lowest_index_on_ties():
+    x = RNG.standard_normal(1000)
+    assert oracle.argmax(x) == int(np.argmax(x))
+    x[[900, 17, 400]] = 99.0
+    assert oracle.argmax(x) == 17
+
+
+# ------------------------------------------------------------------ block allocator (integer exact)
+
+class _PyAlloc:
+    """Brute-force model of the allocator policy: LIFO stack that first yields 0,1,2,..; blocks of a
+    freed sequence are pushed back in reverse logical order."""
+
+    def __init__(self, n):
+        self.free = list(range(n - 1, -1, -1)); self.tab = {}
+
+    def alloc(self, sid, reserve):
+        self.tab[sid] = [self.free.pop() for _ in range((reserve + 15) // 16)]
+
+    def grow(self, sid, n_tokens):
+        while len(self.tab[sid]) * 16 < n_tokens:
+            self.tab[sid].append(self.free.pop())
+
+    def release(self, sid):
+        for b in reversed(self.tab.pop(sid)):
+            self.free.append(b)
+
+
+def _toy_model(layers=1):
+    shape = TINY.with_layers(layers)
+    return shape, oracle.Model(shape, make_weights(shape, 99))
+
+
+def test_allocator_matches_bruteforce_simulation():
+    shape, m = _toy_model()
+    kv = oracle.KV(m, 40, 4, 12); py = _PyAlloc(40)
+    rc, a = kv.alloc(33); py.alloc(a, 33)
+    rc, b = kv.alloc(0); py.alloc(b, 0)
+    assert (a, b) == (0, 1)
+    lens = {a: 0, b: 0}
+    steps = [(a, 35), (b, 17), (a, 20), (b, 1), (b, 15), (a, 9)]
+    for sid, n in steps:
+        kvd = np.zeros((n, shape.n_layers, 2, shape.n_kv_heads, shape.head_dim))
+        assert kv.inject(sid, kvd) == 0
+        lens[sid] += n; py.grow(sid, lens[sid])
+        assert kv.block_table(sid)[1].tolist() == py.tab[sid]
+    kv.free(a); py.release(a)
+    rc, c = kv.alloc(50); py.alloc(c, 50)
+    assert c == a and kv.block_table(c)[1].tolist() == py.tab[c]
+    assert kv.free_blocks() == len(py.free)
+    # out of blocks: state unchanged, error reported
+    before = kv.block_table(b)[1].tolist(), kv.free_blocks()
+    assert kv.inject(b, np.zeros((16 * 60, 1, 2, 4, 64))) in (oracle.E_NOMEM, oracle.E_RANGE)
+    assert (kv.block_table(b)[1].tolist(), kv.free_blocks()) == before
+
+
+def test_block_and_slot_of_every_position():
+    """Token j is found in logical block j // 16, slot j % 16, including positions 15, 16, 17."""
+    shape, m = _toy_model()
+    kv = oracle.KV(m, 8, 1, 8)
+    rc, s = kv.alloc(0)
+    for lb, pb in enumerate([5, 2, 7]):
+        assert kv.map(s, lb, pb) == 0
+    n = 40
+    data = np.arange(n * 2 * 4 * 64, dtype=np.float64).reshape(n, 1, 2, 4, 64)
+    assert kv.inject(s, data) == 0
+    assert kv.block_table(s)[1].tolist() == [5, 2, 7]
+    for pos in (0, 15, 16, 17, 31, 32, 39):
+        for which in (0, 1):
+            np.testing.assert_array_equal(kv.read(s, 0, which, 3, pos)[1], data[pos, 0, which, 3])
+
+
+# ------------------------------------------------------------------ whole decoder
+
+def _torch_forward_all(shape, w, tokens):
+    """Whole-sequence float64 forward with library routines (matmul, rms_norm, sdpa, silu, polar):
+    a formulation with no KV cache and no per-token loop."""
+    T = len(tokens); d, H, Hk, hd = shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim
+    W = lambda t: t.double()
+    x = W(w["embed"])[torch.tensor(tokens)]
+    pos = torch.arange(T, dtype=torch.float64)
+    theta = shape.rope_base ** (-2.0 * torch.arange(hd // 2, dtype=torch.float64) / hd)
+    rot = torch.polar(torch.ones(T, hd // 2, dtype=torch.float64), pos[:, None] * theta[None, :])
+
+    def rope(u):                                     # u [T, heads, hd]
+        z = torch.complex(u[..., : hd // 2], u[..., hd // 2:]) * rot[:, None, :]
+        return torch.cat([z.real, z.imag], -1)
+
+    for l in range(shape.n_layers):
+        h = F.rms_norm(x, (d,), W(w["attn_norm"][l]), eps=shape.rms_eps)
+        qkv = h @ W(w["wqkv"][l]).T
+        q, k, v = qkv.split([H * hd, Hk * hd, Hk * hd], dim=-1)
+        q, k, v = rope(q.view(T, H, hd)), rope(k.view(T, Hk, hd)), v.view(T, Hk, hd)
+        k = k.repeat_interleave(H // Hk, dim=1); v = v.repeat_interleave(H // Hk, dim=1)
+        o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
+                                           v.transpose(0, 1)[None], is_causal=True)[0]
+        x = x + o.transpose(0, 1).reshape(T, H * hd) @ W(w["wo"][l]).T
+        h = F.rms_norm(x, (d,), W(w["ffn_norm"][l]), eps=shape.rms_eps)
+        gu = h @ W(w["wgate_up"][l]).T
+        x = x + (F.silu(gu[:, : shape.d_ffn]) * gu[:, shape.d_ffn:]) @ W(w["wdown"][l]).T
+    return (F.rms_norm(x, (d,), W(w["final_norm"]), eps=shape.rms_eps) @ W(w["lm_head"]).T).numpy()
+
+
+def _prompt(n, vocab, stream=100):
+    return gen.randint(SEED_BASE, stream, 0, vocab - 1, n).numpy().astype(np.int32)
+
+
+def test_decoder_matches_float64_library_rederivation(tiny_weights):
+    shape, w = tiny_weights
+    tok = _prompt(40, shape.vocab)
+    m = oracle.Model(shape, w, kv_round=0)
+    got = m.forward_contig(tok)
+    ref = _torch_forward_all(shape, w, tok.tolist())
+    scale = np.abs(ref).max(axis=1, keepdims=True)
+    assert np.max(np.abs(got - ref) / scale) < 1e-11
+    assert (got.argmax(1) == ref.argmax(1)).all()
+
+
+def test_decoder_gqa_and_bf16_weights_match_library_rederivation():
+    from dataclasses import replace
+    shape = replace(TINY, n_kv_heads=2, dtype="bf16", name="tiny-gqa")
+    w = make_weights(shape, 5)
+    tok = _prompt(21, shape.vocab, 101)
+    got = oracle.Model(shape, w, kv_round=0).forward_contig(tok)
+    ref = _torch_forward_all(shape, w, tok.tolist())
+    assert np.max(np.abs(got - ref)) / np.abs(ref).max() < 1e-11
+
+
+def test_paged_equals_contiguous_and_rounds_follow_the_concatenation(tiny_weights):
+    """Paged cache == contiguous cache bitwise, and a multi-round run (prefill, decode, append an
+    observation, continue) produces at every call the logits of the concatenated sequence
+    prompt ++ generated ++ observation (section 2.2 step (g)), the pending token being fed first."""
+    shape, w = tiny_weights
+    tok = _prompt(37, shape.vocab)
+    m = oracle.Model(shape, w)                 # cache rounded to fp32 for the fp32 shape
+    kv = oracle.KV(m, 16, 3, 8)
+    rc, s = kv.alloc(0)
+    for lb, pb in enumerate([9, 3, 14, 0, 5]):
+        kv.map(s, lb, pb)
+    seq, calls = list(tok), []                 # calls: (index of the position whose logits were returned, logits)
+    rc, t, lg = kv.prefill(s, tok); assert rc == 0
+    calls.append((len(seq) - 1, lg, t))
+    for _ in range(3):
+        seq.append(t)
+        rc, t, lg = kv.decode(s); assert rc == 0
+        calls.append((len(seq) - 1, lg, t))
+    obs = _prompt(20, shape.vocab, 102)
+    seq.append(t); seq.extend(obs.tolist())
+    rc, t, lg = kv.prefill(s, obs); assert rc == 0
+    calls.append((len(seq) - 1, lg, t))
+    seq.append(t)
+    rc, t, lg = kv.decode(s); assert rc == 0
+    calls.append((len(seq) - 1, lg, t))
+    assert kv.length(s) == len(seq)
+    ref = m.forward_contig(np.array(seq, np.int32))
+    for idx, lg, t in calls:
+        assert np.array_equal(lg, ref[idx])
+        assert t == int(np.argmax(ref[idx]))
+    assert kv.block_table(s)[1].tolist() == [9, 3, 14, 0, 5]
+    # decode without a pending token and stepping a stopped sequence are state errors
+    rc, s2 = kv.alloc(0)
+    assert kv.decode(s2)[0] == oracle.E_STATE
+    kv.stop(s); assert kv.decode(s)[0] == oracle.E_STATE
+    assert kv.prefill(s2, np.array([shape.vocab], np.int32))[0] == oracle.E_RANGE
+
+
+def test_wo_and_wdown_zero_make_every_layer_the_identity(tiny_weights):
+    shape, w = tiny_weights
+    w0 = dict(w)
+    w0["wo"] = [torch.zeros_like(t) for t in w["wo"]]; w0["wdown"] = [torch.zeros_like(t) for t in w["wdown"]]
+    tok = _prompt(6, shape.vocab)
+    got = oracle.Model(shape, w0, kv_round=0).forward_contig(tok)
+    E, Wl, g = w["embed"].double().numpy(), w["lm_head"].double().numpy(), w["final_norm"].double().numpy()
+    for p, t in enumerate(tok):
+        x = E[t]
+        ref = Wl @ (x / np.sqrt(np.mean(x * x) + shape.rms_eps) * g)
+        np.testing.assert_allclose(got[p], ref, rtol=1e-12, atol=1e-15)

@@ -1,0 +1,155 @@
+/*
+ * libld: single-GPU decode / chunked-prefill engine over a paged KV cache (gfx950).
+ *
+ * The serving system this library sits under invokes the LLM once per scheduling
+ * iteration, hands every generated token to a streaming parser during decoding, and
+ * later feeds collected tool observations back for prefilling (paper section 3.3,
+ * workflow steps (2), (3), (8); section 2.2 step (g); section 2.1 for the attention /
+ * KV-cache / prefill / decode definitions; section 4.1: temperature 0 = greedy).
+ *
+ * Conventions
+ *  - Every call returns an ld_status; nothing throws or aborts.  On error the out
+ *    parameters and all sequence / allocator state are left unchanged, and
+ *    ld_last_error() returns a thread-local description.
+ *  - "DEVICE" pointers are HIP device memory owned by the caller (allocate it with
+ *    any allocator, e.g. a torch tensor's data_ptr()); it must stay valid until the
+ *    object that received it is destroyed.  "HOST" pointers are borrowed for the
+ *    duration of the call only.  The library owns only host structures and a small
+ *    pinned host staging area.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A step
+ *    call enqueues all of its kernels on that stream, waits for the emitted tokens
+ *    to reach the host, then runs the callbacks on the calling thread.
+ *  - Matrices are row-major with the output index first ([n_out, n_in]), element type
+ *    cfg.dtype.  RMSNorm gains are always float32.
+ *  - Sequence state: n_cached tokens have keys/values in the pool; `pending` is a token
+ *    that was emitted but not fed yet (none right after ld_kv_alloc).
+ */
+#ifndef LD_H
+#define LD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ld_model ld_model; /* opaque, library-owned */
+typedef struct ld_kv ld_kv;       /* opaque, library-owned */
+typedef int32_t ld_seq;           /* sequence handle inside one ld_kv */
+
+typedef enum {
+    LD_OK = 0,
+    LD_E_INVAL = -1, /* bad argument (null pointer, bad handle, bad shape) */
+    LD_E_NOMEM = -2, /* out of KV blocks or sequence slots */
+    LD_E_STATE = -3, /* call not allowed in the sequence's state (no pending token, stopped, ...) */
+    LD_E_HIP = -4,   /* a HIP runtime call failed */
+    LD_E_RANGE = -5  /* token id >= vocab, context beyond max_blocks_per_seq, step larger than workspace */
+} ld_status;
+
+enum { LD_F32 = 0, LD_BF16 = 1 };
+
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    float rms_eps;     /* added to the mean square inside the root */
+    float rope_base;   /* rotary angle of pair i at position p: p * rope_base^(-2i/head_dim) */
+    int32_t dtype;     /* LD_F32 | LD_BF16: element type of matrices AND of the KV pool */
+    int32_t kv_block;  /* tokens per KV block; must be 16 */
+    int32_t max_chunk; /* ld_prefill splits longer inputs into chunks of this many rows */
+} ld_model_config;
+
+/* DEVICE pointers.  Per-layer members are HOST arrays of n_layers DEVICE pointers
+ * (the arrays themselves are copied by ld_model_create).
+ *   embed, lm_head  [vocab, d_model]
+ *   wqkv            [(n_heads + 2 n_kv_heads) * head_dim, d_model]   q rows, then k rows, then v rows
+ *   wo              [d_model, n_heads * head_dim]
+ *   wgate_up        [2 * d_ffn, d_model]                             gate rows, then up rows
+ *   wdown           [d_model, d_ffn]
+ *   attn_norm, ffn_norm, final_norm  [d_model] float32 */
+typedef struct {
+    const void *embed, *lm_head;
+    const float *final_norm;
+    const float *const *attn_norm;
+    const void *const *wqkv;
+    const void *const *wo;
+    const float *const *ffn_norm;
+    const void *const *wgate_up;
+    const void *const *wdown;
+} ld_weights;
+
+/* Called once per emitted token, on the calling thread, in ascending order of the
+ * sequence's index in the step's argument list.  `pos` is the absolute position the
+ * token will occupy once fed.  A non-zero return marks the sequence stopped (early
+ * abort, section 4.3 case #2): stepping it again returns LD_E_STATE until it is freed. */
+typedef int (*ld_token_cb)(void *user, ld_seq seq, int32_t token, int32_t pos);
+
+/* Registers a model (section 3.3 step (a)).  Validates shapes, copies the configuration
+ * and the pointer tables; touches no device memory.  Supported: head_dim 64 or 128,
+ * kv_block 16, d_model and d_ffn multiples of 8, n_heads a multiple of n_kv_heads. */
+ld_status ld_model_create(const ld_model_config *cfg, const ld_weights *w, ld_model **out);
+void ld_model_destroy(ld_model *m);
+
+/* Bytes of the KV pool for n_blocks blocks.  Pool layout (element type cfg.dtype):
+ *   [layer][block][K=0|V=1][kv_head][slot 0..15][head_dim]
+ * Token j of a sequence lives in physical block table[j / 16], slot j % 16. */
+size_t ld_kv_bytes(const ld_model *m, int64_t n_blocks);
+
+/* Bytes of scratch a step of up to max_tokens rows (decode rows + prefill-chunk rows)
+ * over at most max_seqs sequences of at most max_blocks_per_seq blocks needs. */
+size_t ld_workspace_bytes(const ld_model *m, int32_t max_tokens, int32_t max_seqs, int32_t max_blocks_per_seq);
+
+/* Creates the paged cache over caller-owned DEVICE memory: `pool` of ld_kv_bytes(m, n_blocks)
+ * bytes and `ws` of at least ld_workspace_bytes(...) bytes, both 256-byte aligned.  The pool's
+ * contents are not touched.  No device call is made here (pinned staging is created lazily by
+ * the first step).  The free list is a LIFO stack whose first pops return blocks 0, 1, 2, ... */
+ld_status ld_kv_create(ld_model *m, void *pool, int64_t n_blocks, void *ws, size_t ws_bytes,
+                       int32_t max_tokens, int32_t max_seqs, int32_t max_blocks_per_seq, ld_kv **out);
+void ld_kv_destroy(ld_kv *kv);
+
+/* New sequence (lowest free handle), with ceil(reserve_tokens / 16) blocks mapped up front.
+ * LD_E_NOMEM if no handle or not enough free blocks. */
+ld_status ld_kv_alloc(ld_kv *kv, int64_t reserve_tokens, ld_seq *out);
+/* Test hook: map a sequence's logical block to a chosen free physical block (permuted tables).
+ * LD_E_STATE if the logical block is already mapped, LD_E_NOMEM if the physical block is not free. */
+ld_status ld_kv_map(ld_kv *kv, ld_seq seq, int32_t logical_block, int32_t physical_block);
+/* Ends a sequence (finished or aborted early): pushes its blocks back in reverse logical order. */
+ld_status ld_kv_free(ld_kv *kv, ld_seq seq);
+/* Copies the sequence's block table (physical ids of logical blocks 0..n-1) to HOST out[cap]. */
+ld_status ld_kv_block_table(const ld_kv *kv, ld_seq seq, int32_t *out, int32_t cap, int32_t *n);
+/* Number of cached tokens of a sequence (-1 for a bad handle); number of free blocks. */
+int64_t ld_kv_len(const ld_kv *kv, ld_seq seq);
+int64_t ld_kv_free_blocks(const ld_kv *kv);
+/* Test / benchmark hook: declare that the next n_tokens positions of a sequence are already
+ * cached (their blocks are mapped; the caller has written, or will write, their keys and values
+ * straight into the pool using the layout above), and set the pending token (none if < 0). */
+ld_status ld_kv_assume(ld_kv *kv, ld_seq seq, int64_t n_tokens, int32_t pending);
+
+/* Prefill (prompt, or a tool observation appended to a live sequence): feeds
+ * [pending?] ++ tokens[0..n) at positions n_cached.., in chunks of at most cfg.max_chunk
+ * rows; emits argmax(logits of the last row) through cb (may be NULL) and keeps it as
+ * the new pending token.  tokens: HOST.  logits_out: HOST float[vocab] or NULL. */
+ld_status ld_prefill(ld_kv *kv, ld_seq seq, const int32_t *tokens, int32_t n, void *stream,
+                     ld_token_cb cb, void *user, float *logits_out);
+
+/* One decode iteration for n_seqs distinct sequences (each must have a pending token):
+ * feeds the pending token, emits the next one per sequence.  seqs: HOST.
+ * logits_out: HOST float[n_seqs, vocab] or NULL. */
+ld_status ld_decode_step(ld_kv *kv, const ld_seq *seqs, int32_t n_seqs, void *stream,
+                         ld_token_cb cb, void *user, float *logits_out);
+
+/* One mixed iteration of continuous batching: n_dec decoding sequences plus n_pf sequences that
+ * each get [pending?] ++ pf_tokens[i][0..pf_n[i]) prefilled in the same pass (one chunk each,
+ * total rows <= workspace max_tokens).  Every listed sequence emits one token; callbacks run for
+ * dec[0..n_dec) first, then pf[0..n_pf).  All sequences distinct.  All arrays HOST.
+ * logits_out: HOST float[n_dec + n_pf, vocab] or NULL. */
+ld_status ld_step_mixed(ld_kv *kv, const ld_seq *dec, int32_t n_dec, const ld_seq *pf,
+                        const int32_t *const *pf_tokens, const int32_t *pf_n, int32_t n_pf, void *stream,
+                        ld_token_cb cb, void *user, float *logits_out);
+
+/* Text of the last error on this thread ("" if none). */
+const char *ld_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LD_H */

@@ -1,0 +1,75 @@
+/*
+ * libld, kernel-level entry points: each step of the decode / prefill pass as a call of its
+ * own, so that tests and micro-benchmarks can drive one kernel at a time.  ld_prefill /
+ * ld_decode_step / ld_step_mixed are compositions of exactly these launches.
+ *
+ * All data pointers are DEVICE pointers owned by the caller unless marked HOST.  `stream`
+ * is a hipStream_t as void*.  Calls only enqueue work; they return LD_E_INVAL for
+ * unsupported shapes (before launching anything) and LD_E_HIP if the launch failed.
+ * Activations are float32 throughout; `dtype` (LD_F32 | LD_BF16) is the element type of
+ * matrices and of the KV pool.
+ */
+#ifndef LD_KERNELS_H
+#define LD_KERNELS_H
+
+#include "ld.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { LDK_STORE = 0, LDK_ADD = 1, LDK_SWIGLU = 2 };
+
+/* x[t, :] = embed[tok[t], :] widened to float32.  tok values must be < vocab (checked by the
+ * caller of the step functions on the host). */
+ld_status ldk_embed(const void *embed, int32_t dtype, const int32_t *tok, int32_t T, int32_t d, float *x,
+                    void *stream);
+
+/* out[r, i] = x[row, i] / sqrt(mean_j x[row, j]^2 + eps) * g[i], row = row_idx ? row_idx[r] : r. */
+ld_status ldk_rmsnorm(const float *x, const float *g, const int32_t *row_idx, int32_t R, int32_t d, float eps,
+                      float *out, void *stream);
+
+/* Linear layer on T rows: acc[t, n] = sum_k W[n, k] x[t, k], float32 accumulation.
+ *   LDK_STORE : y[t, n]  = acc[t, n]                          W [N, K]
+ *   LDK_ADD   : y[t, n] += acc[t, n]   (residual)             W [N, K]
+ *   LDK_SWIGLU: y[t, n]  = silu(acc[t, n]) * acc[t, N + n]    W [2N, K]  (gate rows, then up rows)
+ * If g != NULL the input is RMS-normalised on the fly: x[t, k] is replaced by
+ * x[t, k] * rsqrt(mean_k x[t, k]^2 + eps) * g[k].
+ * x [T, K], y [T, N] dense row-major.  K must be a multiple of 8. */
+ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *g, float eps, int32_t T,
+                     int32_t N, int32_t K, int32_t epilogue, float *y, void *stream);
+
+/* cos_sin[t, i] = (cos, sin)(pos[t] * rope_base^(-2i/hd)) for i < hd/2, as float32 pairs; the
+ * angle is formed in float64 so that large positions lose no accuracy.  hd is 64 or 128. */
+ld_status ldk_rope_table(const int32_t *pos, int32_t T, int32_t hd, float rope_base, float *cos_sin, void *stream);
+
+/* Rotary embedding + cache append for T rows of a fused projection qkv [T, (H + 2 Hkv) hd]:
+ * rotates every q head and k head of row t in place by the angles in cos_sin[t] (pair i =
+ * elements (i, i + hd/2) of a head), then stores k and v, rounded to `dtype` (nearest even), at
+ *   pool_layer[table[seq_slot[t] * table_stride + pos[t] / 16]][K|V][kv_head][pos[t] % 16][:].
+ * pool_layer is one layer's slice of the pool: [block][2][Hkv][16][hd].  Rows of one call must
+ * address distinct (sequence, position) pairs. */
+ld_status ldk_rope_kv_write(float *qkv, const float *cos_sin, const int32_t *pos, const int32_t *seq_slot,
+                            const int32_t *table, int32_t table_stride, void *pool_layer, int32_t dtype, int32_t T,
+                            int32_t H, int32_t Hkv, int32_t hd, void *stream);
+
+/* Scratch bytes ldk_paged_attention needs for T rows with contexts up to max_ctx. */
+size_t ldk_attention_scratch_bytes(int32_t T, int32_t H, int32_t hd, int32_t max_ctx);
+
+/* Paged attention of T single-token queries (section 2.1): row t, head h attends to cached
+ * positions 0 .. ctx_len[t]-1 of the sequence whose block-table row is seq_slot[t]:
+ *   s_j = q.k_j / sqrt(hd),  p = softmax(s),  out = sum_j p_j v_j.
+ * q row t, head h starts at q + t * q_stride + h * hd; out is dense [T, H, hd].
+ * ctx_len[t] >= 1.  max_ctx >= max_t ctx_len[t] sizes the launch (HOST value). */
+ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
+                              const int32_t *table, int32_t table_stride, const int32_t *seq_slot,
+                              const int32_t *ctx_len, int32_t max_ctx, int32_t T, int32_t H, int32_t Hkv,
+                              int32_t hd, float *out, void *scratch, size_t scratch_bytes, void *stream);
+
+/* out[r] = smallest index of the maximum of logits[r, 0..V). */
+ld_status ldk_argmax(const float *logits, int32_t R, int32_t V, int32_t *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LD_KERNELS_H */

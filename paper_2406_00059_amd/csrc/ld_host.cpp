@@ -1,0 +1,483 @@
+// Host side of libld: model registry, paged-KV block allocator, sequence state machine,
+// step planner (which rows go through one pass), launch sequence, token hand-off to the callback.
+#include "ld_internal.h"
+
+#include <algorithm>
+#include <cstring>
+#include <string>
+#include <vector>
+
+namespace ld {
+
+static thread_local std::string g_err;
+
+void set_error(const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+}
+void clear_error() { g_err.clear(); }
+
+}  // namespace ld
+
+using ld::fail;
+
+struct ld_model {
+    ld_model_config c;
+    const void *embed, *lm_head;
+    const float *final_norm;
+    std::vector<const float *> attn_norm, ffn_norm;
+    std::vector<const void *> wqkv, wo, wgate_up, wdown;
+    int nq() const { return c.n_heads * c.head_dim; }
+    int nkv() const { return c.n_kv_heads * c.head_dim; }
+    int nqkv() const { return nq() + 2 * nkv(); }
+    size_t elem() const { return c.dtype == LD_BF16 ? 2 : 4; }
+    size_t block_elems() const { return (size_t)2 * c.n_kv_heads * c.kv_block * c.head_dim; }
+};
+
+namespace {
+
+struct Seq {
+    bool active = false, stopped = false, has_pending = false;
+    int32_t pending = -1;
+    int64_t n_cached = 0;
+    int32_t n_mapped = 0;          // logical blocks 0..n_mapped-1 may be mapped (holes possible via ld_kv_map)
+    int32_t dirty_lo = 0, dirty_hi = 0;  // table entries [lo, hi) not yet copied to the device
+};
+
+// Layout of the workspace: every region 256-byte aligned.
+struct Workspace {
+    int32_t *table, *meta, *out_tok;
+    float *x, *qkv, *attn, *act, *hn, *logits, *cos_sin;
+    void *att_scratch;
+    size_t att_scratch_bytes;
+    size_t total;
+};
+
+Workspace plan_workspace(const ld_model &m, char *base, int max_tokens, int max_seqs, int max_blocks) {
+    const ld_model_config &c = m.c;
+    Workspace w{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char *p = base ? base + off : nullptr;
+        off += ld::align_up(bytes, 256);
+        return p;
+    };
+    const size_t T = max_tokens;
+    w.table = (int32_t *)take((size_t)max_seqs * max_blocks * 4);
+    w.meta = (int32_t *)take(T * 5 * 4);  // tok | pos | seq_slot | ctx_len | emit_row
+    w.out_tok = (int32_t *)take((size_t)max_seqs * 4);
+    w.x = (float *)take(T * c.d_model * 4);
+    w.qkv = (float *)take(T * m.nqkv() * 4);
+    w.attn = (float *)take(T * m.nq() * 4);
+    w.act = (float *)take(T * c.d_ffn * 4);
+    w.hn = (float *)take((size_t)max_seqs * c.d_model * 4);
+    w.logits = (float *)take((size_t)max_seqs * c.vocab * 4);
+    w.cos_sin = (float *)take(T * c.head_dim * 4);
+    w.att_scratch_bytes = ldk_attention_scratch_bytes(max_tokens, c.n_heads, c.head_dim, max_blocks * c.kv_block);
+    w.att_scratch = take(w.att_scratch_bytes);
+    w.total = off;
+    return w;
+}
+
+// One row of a pass: which token is fed for which sequence at which position.
+struct Row { int32_t tok, pos, seq; };
+
+}  // namespace
+
+struct ld_kv {
+    ld_model *m;
+    char *pool;
+    int64_t n_blocks;
+    int32_t max_tokens, max_seqs, max_blocks;
+    Workspace ws;
+    std::vector<int32_t> free_stack;
+    std::vector<Seq> seqs;
+    std::vector<int32_t> table;  // host copy [max_seqs][max_blocks], -1 = unmapped
+    // pinned staging, created by the first pass
+    int32_t *pin_meta = nullptr, *pin_out = nullptr, *pin_table = nullptr;
+    int32_t *trow(int s) { return table.data() + (size_t)s * max_blocks; }
+    const int32_t *trow(int s) const { return table.data() + (size_t)s * max_blocks; }
+};
+
+namespace {
+
+Seq *get_seq(ld_kv *kv, ld_seq s) {
+    if (!kv || s < 0 || s >= kv->max_seqs || !kv->seqs[s].active) return nullptr;
+    return &kv->seqs[s];
+}
+
+int64_t blocks_for(const ld_kv *kv, int64_t tokens) {
+    const int b = kv->m->c.kv_block;
+    return (tokens + b - 1) / b;
+}
+
+int64_t count_missing(const ld_kv *kv, int s, int64_t need) {
+    int64_t miss = 0;
+    const int32_t *t = kv->trow(s);
+    for (int64_t i = 0; i < need; i++) miss += t[i] < 0;
+    return miss;
+}
+
+// Maps logical blocks 0..need-1 (pops from the free stack).  The caller has checked availability.
+void map_blocks(ld_kv *kv, int s, int64_t need) {
+    int32_t *t = kv->trow(s);
+    Seq &q = kv->seqs[s];
+    for (int64_t i = 0; i < need; i++) {
+        if (t[i] >= 0) continue;
+        t[i] = kv->free_stack.back();
+        kv->free_stack.pop_back();
+        if (q.dirty_lo == q.dirty_hi) { q.dirty_lo = (int32_t)i; q.dirty_hi = (int32_t)i + 1; }
+        else { q.dirty_lo = std::min<int32_t>(q.dirty_lo, i); q.dirty_hi = std::max<int32_t>(q.dirty_hi, i + 1); }
+    }
+    q.n_mapped = std::max<int32_t>(q.n_mapped, (int32_t)need);
+}
+
+ld_status ensure_pinned(ld_kv *kv) {
+    if (kv->pin_meta) return LD_OK;
+    LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_meta, (size_t)kv->max_tokens * 5 * 4, hipHostMallocDefault));
+    LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_out, (size_t)kv->max_seqs * 4, hipHostMallocDefault));
+    LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_table, (size_t)kv->max_seqs * kv->max_blocks * 4, hipHostMallocDefault));
+    return LD_OK;
+}
+
+// Runs one pass over `rows` (all rows' blocks are mapped).  emit[i] = index of the row whose
+// logits / greedy token are wanted, in callback order.  On return pin_out[i] holds the tokens.
+ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, const std::vector<int32_t> &emit, hipStream_t st,
+                   float *logits_out) {
+    const ld_model &m = *kv->m;
+    const ld_model_config &c = m.c;
+    const int T = (int)rows.size(), R = (int)emit.size();
+    ld_status rc = ensure_pinned(kv);
+    if (rc) return rc;
+    const Workspace &w = kv->ws;
+
+    // metadata: tok | pos | seq_slot | ctx_len | emit_row, each T (emit: R) entries at stride T
+    int32_t *pm = kv->pin_meta;
+    int max_ctx = 1;
+    for (int t = 0; t < T; t++) {
+        pm[t] = rows[t].tok;
+        pm[T + t] = rows[t].pos;
+        pm[2 * T + t] = rows[t].seq;
+        pm[3 * T + t] = rows[t].pos + 1;
+        max_ctx = std::max(max_ctx, rows[t].pos + 1);
+    }
+    for (int r = 0; r < R; r++) pm[4 * T + r] = emit[r];
+    LD_HIP_TRY(hipMemcpyAsync(w.meta, pm, (size_t)(4 * T + R) * 4, hipMemcpyHostToDevice, st));
+    const int32_t *d_tok = w.meta, *d_pos = w.meta + T, *d_slot = w.meta + 2 * T, *d_ctx = w.meta + 3 * T,
+                  *d_emit = w.meta + 4 * T;
+
+    // block-table rows that changed since the last pass
+    for (int t = 0; t < T; t++) {
+        Seq &q = kv->seqs[rows[t].seq];
+        if (q.dirty_lo == q.dirty_hi) continue;
+        const size_t o = (size_t)rows[t].seq * kv->max_blocks + q.dirty_lo;
+        const size_t n = q.dirty_hi - q.dirty_lo;
+        memcpy(kv->pin_table + o, kv->table.data() + o, n * 4);
+        LD_HIP_TRY(hipMemcpyAsync(w.table + o, kv->pin_table + o, n * 4, hipMemcpyHostToDevice, st));
+        q.dirty_lo = q.dirty_hi = 0;
+    }
+
+#define LD_TRY(call) do { ld_status s_ = (call); if (s_ != LD_OK) return s_; } while (0)
+    const int d = c.d_model, nq = m.nq(), nqkv = m.nqkv(), H = c.n_heads, Hkv = c.n_kv_heads, hd = c.head_dim;
+    const size_t layer_bytes = (size_t)kv->n_blocks * m.block_elems() * m.elem();
+    LD_TRY(ldk_embed(m.embed, c.dtype, d_tok, T, d, w.x, st));
+    LD_TRY(ldk_rope_table(d_pos, T, hd, c.rope_base, w.cos_sin, st));
+    for (int l = 0; l < c.n_layers; l++) {
+        void *pool_l = kv->pool + (size_t)l * layer_bytes;
+        LD_TRY(ldk_linear(m.wqkv[l], c.dtype, w.x, m.attn_norm[l], c.rms_eps, T, nqkv, d, LDK_STORE, w.qkv, st));
+        LD_TRY(ldk_rope_kv_write(w.qkv, w.cos_sin, d_pos, d_slot, w.table, kv->max_blocks, pool_l, c.dtype, T, H,
+                                 Hkv, hd, st));
+        LD_TRY(ldk_paged_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot, d_ctx, max_ctx, T,
+                                   H, Hkv, hd, w.attn, w.att_scratch, w.att_scratch_bytes, st));
+        LD_TRY(ldk_linear(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, st));
+        LD_TRY(ldk_linear(m.wgate_up[l], c.dtype, w.x, m.ffn_norm[l], c.rms_eps, T, c.d_ffn, d, LDK_SWIGLU, w.act, st));
+        LD_TRY(ldk_linear(m.wdown[l], c.dtype, w.act, nullptr, 0.f, T, d, c.d_ffn, LDK_ADD, w.x, st));
+    }
+    LD_TRY(ldk_rmsnorm(w.x, m.final_norm, d_emit, R, d, c.rms_eps, w.hn, st));
+    LD_TRY(ldk_linear(m.lm_head, c.dtype, w.hn, nullptr, 0.f, R, c.vocab, d, LDK_STORE, w.logits, st));
+    LD_TRY(ldk_argmax(w.logits, R, c.vocab, w.out_tok, st));
+#undef LD_TRY
+    if (R) LD_HIP_TRY(hipMemcpyAsync(kv->pin_out, w.out_tok, (size_t)R * 4, hipMemcpyDeviceToHost, st));
+    if (logits_out && R)
+        LD_HIP_TRY(hipMemcpyAsync(logits_out, w.logits, (size_t)R * c.vocab * 4, hipMemcpyDeviceToHost, st));
+    LD_HIP_TRY(hipStreamSynchronize(st));
+    return LD_OK;
+}
+
+// One planned step: for each listed sequence a run of tokens to feed (pending first); every
+// sequence emits one token from its last row.  Validates, reserves blocks, runs, commits state.
+struct Feed { ld_seq seq; const int32_t *tokens; int32_t n; };
+
+ld_status run_step(ld_kv *kv, const std::vector<Feed> &feeds, void *stream, ld_token_cb cb, void *user,
+                   float *logits_out, const char *who) {
+    const ld_model_config &c = kv->m->c;
+    // --- validate, no state change
+    std::vector<char> seen(kv->max_seqs, 0);
+    int64_t total_rows = 0, total_missing = 0;
+    for (const Feed &f : feeds) {
+        Seq *q = get_seq(kv, f.seq);
+        if (!q) { ld::set_error("%s: bad sequence handle %d", who, f.seq); return LD_E_INVAL; }
+        if (seen[f.seq]) { ld::set_error("%s: sequence %d listed twice", who, f.seq); return LD_E_INVAL; }
+        seen[f.seq] = 1;
+        if (q->stopped) { ld::set_error("%s: sequence %d was stopped by its callback", who, f.seq); return LD_E_STATE; }
+        if (f.n < 0 || (f.n > 0 && !f.tokens)) { ld::set_error("%s: bad token array", who); return LD_E_INVAL; }
+        const int64_t rows = f.n + (q->has_pending ? 1 : 0);
+        if (rows == 0) { ld::set_error("%s: sequence %d has nothing to feed (no pending token)", who, f.seq); return LD_E_STATE; }
+        for (int i = 0; i < f.n; i++)
+            if (f.tokens[i] < 0 || f.tokens[i] >= c.vocab) { ld::set_error("%s: token id %d out of range", who, f.tokens[i]); return LD_E_RANGE; }
+        const int64_t need = blocks_for(kv, q->n_cached + rows);
+        if (need > kv->max_blocks) { ld::set_error("%s: sequence %d would exceed max_blocks_per_seq", who, f.seq); return LD_E_RANGE; }
+        total_missing += count_missing(kv, f.seq, need);
+        total_rows += rows;
+    }
+    if (total_rows > kv->max_tokens) { ld::set_error("%s: %lld rows exceed the workspace's max_tokens %d", who, (long long)total_rows, kv->max_tokens); return LD_E_RANGE; }
+    if ((int64_t)feeds.size() > kv->max_seqs) return fail(LD_E_RANGE, "too many sequences in one step");
+    if (total_missing > (int64_t)kv->free_stack.size()) { ld::set_error("%s: out of KV blocks (%lld needed, %zu free)", who, (long long)total_missing, kv->free_stack.size()); return LD_E_NOMEM; }
+
+    // --- reserve blocks (in argument order, logical order within a sequence) and build rows
+    std::vector<Row> rows;
+    std::vector<int32_t> emit;
+    rows.reserve(total_rows);
+    for (const Feed &f : feeds) {
+        Seq &q = kv->seqs[f.seq];
+        const int64_t n_rows = f.n + (q.has_pending ? 1 : 0);
+        map_blocks(kv, f.seq, blocks_for(kv, q.n_cached + n_rows));
+        int32_t pos = (int32_t)q.n_cached;
+        if (q.has_pending) rows.push_back({q.pending, pos++, f.seq});
+        for (int i = 0; i < f.n; i++) rows.push_back({f.tokens[i], pos++, f.seq});
+        emit.push_back((int32_t)rows.size() - 1);
+    }
+    ld_status rc = run_pass(kv, rows, emit, (hipStream_t)stream, logits_out);
+    if (rc) return rc;
+
+    // --- commit state, then hand the tokens over
+    for (size_t i = 0; i < feeds.size(); i++) {
+        Seq &q = kv->seqs[feeds[i].seq];
+        q.n_cached += feeds[i].n + (q.has_pending ? 1 : 0);
+        q.pending = kv->pin_out[i];
+        q.has_pending = true;
+    }
+    if (cb)
+        for (size_t i = 0; i < feeds.size(); i++) {
+            Seq &q = kv->seqs[feeds[i].seq];
+            if (cb(user, feeds[i].seq, q.pending, (int32_t)q.n_cached) != 0) q.stopped = true;
+        }
+    return LD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ld_last_error(void) { return ld::g_err.c_str(); }
+
+ld_status ld_model_create(const ld_model_config *cfg, const ld_weights *w, ld_model **out) {
+    if (!cfg || !w || !out) return fail(LD_E_INVAL, "ld_model_create: null argument");
+    const ld_model_config &c = *cfg;
+    if (c.n_layers < 0 || c.d_model <= 0 || c.n_heads <= 0 || c.n_kv_heads <= 0 || c.d_ffn <= 0 || c.vocab <= 0 ||
+        c.max_chunk <= 0)
+        return fail(LD_E_INVAL, "ld_model_create: non-positive dimension");
+    if (c.head_dim != 64 && c.head_dim != 128) return fail(LD_E_INVAL, "ld_model_create: head_dim must be 64 or 128");
+    if (c.kv_block != 16) return fail(LD_E_INVAL, "ld_model_create: kv_block must be 16");
+    if (c.n_heads % c.n_kv_heads) return fail(LD_E_INVAL, "ld_model_create: n_heads must be a multiple of n_kv_heads");
+    if (c.d_model % 8 || c.d_ffn % 8) return fail(LD_E_INVAL, "ld_model_create: d_model and d_ffn must be multiples of 8");
+    if (c.dtype != LD_F32 && c.dtype != LD_BF16) return fail(LD_E_INVAL, "ld_model_create: bad dtype");
+    if (!(c.rms_eps > 0.f) || !(c.rope_base > 1.f)) return fail(LD_E_INVAL, "ld_model_create: bad rms_eps / rope_base");
+    if (!w->embed || !w->lm_head || !w->final_norm) return fail(LD_E_INVAL, "ld_model_create: null weight pointer");
+    if (c.n_layers > 0 && (!w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm || !w->wgate_up || !w->wdown))
+        return fail(LD_E_INVAL, "ld_model_create: null per-layer table");
+    for (int l = 0; l < c.n_layers; l++)
+        if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->wgate_up[l] || !w->wdown[l])
+            return fail(LD_E_INVAL, "ld_model_create: null per-layer weight pointer");
+    ld_model *m = new ld_model();
+    m->c = c;
+    m->embed = w->embed; m->lm_head = w->lm_head; m->final_norm = w->final_norm;
+    for (int l = 0; l < c.n_layers; l++) {
+        m->attn_norm.push_back(w->attn_norm[l]); m->ffn_norm.push_back(w->ffn_norm[l]);
+        m->wqkv.push_back(w->wqkv[l]); m->wo.push_back(w->wo[l]);
+        m->wgate_up.push_back(w->wgate_up[l]); m->wdown.push_back(w->wdown[l]);
+    }
+    *out = m;
+    return LD_OK;
+}
+
+void ld_model_destroy(ld_model *m) { delete m; }
+
+size_t ld_kv_bytes(const ld_model *m, int64_t n_blocks) {
+    if (!m || n_blocks <= 0) return 0;
+    return (size_t)m->c.n_layers * n_blocks * m->block_elems() * m->elem();
+}
+
+size_t ld_workspace_bytes(const ld_model *m, int32_t max_tokens, int32_t max_seqs, int32_t max_blocks_per_seq) {
+    if (!m || max_tokens <= 0 || max_seqs <= 0 || max_blocks_per_seq <= 0) return 0;
+    return plan_workspace(*m, nullptr, max_tokens, max_seqs, max_blocks_per_seq).total;
+}
+
+ld_status ld_kv_create(ld_model *m, void *pool, int64_t n_blocks, void *ws, size_t ws_bytes, int32_t max_tokens,
+                       int32_t max_seqs, int32_t max_blocks_per_seq, ld_kv **out) {
+    if (!m || !out || n_blocks <= 0 || max_tokens <= 0 || max_seqs <= 0 || max_blocks_per_seq <= 0)
+        return fail(LD_E_INVAL, "ld_kv_create: bad argument");
+    if (!pool || !ws) return fail(LD_E_INVAL, "ld_kv_create: null pool or workspace");
+    if (n_blocks > INT32_MAX) return fail(LD_E_RANGE, "ld_kv_create: too many blocks");
+    if (((uintptr_t)pool | (uintptr_t)ws) & 255) return fail(LD_E_INVAL, "ld_kv_create: pool and workspace must be 256-byte aligned");
+    const size_t need = ld_workspace_bytes(m, max_tokens, max_seqs, max_blocks_per_seq);
+    if (ws_bytes < need) { ld::set_error("ld_kv_create: workspace of %zu bytes, %zu needed", ws_bytes, need); return LD_E_INVAL; }
+    ld_kv *kv = new ld_kv();
+    kv->m = m; kv->pool = (char *)pool; kv->n_blocks = n_blocks;
+    kv->max_tokens = max_tokens; kv->max_seqs = max_seqs; kv->max_blocks = max_blocks_per_seq;
+    kv->ws = plan_workspace(*m, (char *)ws, max_tokens, max_seqs, max_blocks_per_seq);
+    kv->free_stack.resize(n_blocks);
+    for (int64_t i = 0; i < n_blocks; i++) kv->free_stack[i] = (int32_t)(n_blocks - 1 - i);
+    kv->seqs.resize(max_seqs);
+    kv->table.assign((size_t)max_seqs * max_blocks_per_seq, -1);
+    *out = kv;
+    return LD_OK;
+}
+
+void ld_kv_destroy(ld_kv *kv) {
+    if (!kv) return;
+    if (kv->pin_meta) (void)hipHostFree(kv->pin_meta);
+    if (kv->pin_out) (void)hipHostFree(kv->pin_out);
+    if (kv->pin_table) (void)hipHostFree(kv->pin_table);
+    delete kv;
+}
+
+ld_status ld_kv_alloc(ld_kv *kv, int64_t reserve_tokens, ld_seq *out) {
+    if (!kv || !out || reserve_tokens < 0) return fail(LD_E_INVAL, "ld_kv_alloc: bad argument");
+    int s = 0;
+    while (s < kv->max_seqs && kv->seqs[s].active) s++;
+    if (s == kv->max_seqs) return fail(LD_E_NOMEM, "ld_kv_alloc: no free sequence handle");
+    const int64_t need = blocks_for(kv, reserve_tokens);
+    if (need > kv->max_blocks) return fail(LD_E_RANGE, "ld_kv_alloc: reservation exceeds max_blocks_per_seq");
+    if (need > (int64_t)kv->free_stack.size()) return fail(LD_E_NOMEM, "ld_kv_alloc: out of KV blocks");
+    kv->seqs[s] = Seq();
+    kv->seqs[s].active = true;
+    map_blocks(kv, s, need);
+    *out = s;
+    return LD_OK;
+}
+
+ld_status ld_kv_map(ld_kv *kv, ld_seq seq, int32_t logical, int32_t physical) {
+    Seq *q = get_seq(kv, seq);
+    if (!q || logical < 0 || logical >= kv->max_blocks) return fail(LD_E_INVAL, "ld_kv_map: bad argument");
+    int32_t *t = kv->trow(seq);
+    if (t[logical] >= 0) return fail(LD_E_STATE, "ld_kv_map: logical block already mapped");
+    auto it = std::find(kv->free_stack.begin(), kv->free_stack.end(), physical);
+    if (it == kv->free_stack.end()) return fail(LD_E_NOMEM, "ld_kv_map: physical block is not free");
+    kv->free_stack.erase(it);
+    t[logical] = physical;
+    if (q->dirty_lo == q->dirty_hi) { q->dirty_lo = logical; q->dirty_hi = logical + 1; }
+    else { q->dirty_lo = std::min(q->dirty_lo, logical); q->dirty_hi = std::max(q->dirty_hi, logical + 1); }
+    q->n_mapped = std::max(q->n_mapped, logical + 1);
+    return LD_OK;
+}
+
+ld_status ld_kv_free(ld_kv *kv, ld_seq seq) {
+    Seq *q = get_seq(kv, seq);
+    if (!q) return fail(LD_E_INVAL, "ld_kv_free: bad sequence handle");
+    int32_t *t = kv->trow(seq);
+    for (int i = kv->max_blocks - 1; i >= 0; i--)
+        if (t[i] >= 0) { kv->free_stack.push_back(t[i]); t[i] = -1; }
+    *q = Seq();
+    return LD_OK;
+}
+
+ld_status ld_kv_block_table(const ld_kv *kv, ld_seq seq, int32_t *out, int32_t cap, int32_t *n) {
+    const Seq *q = get_seq(const_cast<ld_kv *>(kv), seq);
+    if (!q || !out || !n) return fail(LD_E_INVAL, "ld_kv_block_table: bad argument");
+    if (cap < q->n_mapped) return fail(LD_E_RANGE, "ld_kv_block_table: output too small");
+    memcpy(out, kv->trow(seq), (size_t)q->n_mapped * 4);
+    *n = q->n_mapped;
+    return LD_OK;
+}
+
+int64_t ld_kv_len(const ld_kv *kv, ld_seq seq) {
+    const Seq *q = get_seq(const_cast<ld_kv *>(kv), seq);
+    return q ? q->n_cached : -1;
+}
+
+int64_t ld_kv_free_blocks(const ld_kv *kv) { return kv ? (int64_t)kv->free_stack.size() : -1; }
+
+ld_status ld_kv_assume(ld_kv *kv, ld_seq seq, int64_t n_tokens, int32_t pending) {
+    Seq *q = get_seq(kv, seq);
+    if (!q || n_tokens < 0) return fail(LD_E_INVAL, "ld_kv_assume: bad argument");
+    if (pending >= kv->m->c.vocab) return fail(LD_E_RANGE, "ld_kv_assume: pending token out of range");
+    const int64_t need = blocks_for(kv, q->n_cached + n_tokens);
+    if (need > kv->max_blocks) return fail(LD_E_RANGE, "ld_kv_assume: exceeds max_blocks_per_seq");
+    if (count_missing(kv, seq, need) > (int64_t)kv->free_stack.size()) return fail(LD_E_NOMEM, "ld_kv_assume: out of KV blocks");
+    map_blocks(kv, seq, need);
+    q->n_cached += n_tokens;
+    if (pending >= 0) { q->pending = pending; q->has_pending = true; }
+    return LD_OK;
+}
+
+ld_status ld_prefill(ld_kv *kv, ld_seq seq, const int32_t *tokens, int32_t n, void *stream, ld_token_cb cb,
+                     void *user, float *logits_out) {
+    if (!kv) return fail(LD_E_INVAL, "ld_prefill: null kv");
+    Seq *q = get_seq(kv, seq);
+    if (!q) return fail(LD_E_INVAL, "ld_prefill: bad sequence handle");
+    if (q->stopped) return fail(LD_E_STATE, "ld_prefill: sequence was stopped by its callback");
+    if (n < 0 || (n > 0 && !tokens)) return fail(LD_E_INVAL, "ld_prefill: bad token array");
+    const ld_model_config &c = kv->m->c;
+    const int chunk = std::min(c.max_chunk, kv->max_tokens);
+    const int64_t total = (int64_t)n + (q->has_pending ? 1 : 0);
+    if (total == 0) return fail(LD_E_INVAL, "ld_prefill: nothing to feed");
+    for (int i = 0; i < n; i++)
+        if (tokens[i] < 0 || tokens[i] >= c.vocab) return fail(LD_E_RANGE, "ld_prefill: token id out of range");
+    // reserve every block of the whole call first, so that a shortage leaves the state untouched
+    const int64_t need = blocks_for(kv, q->n_cached + total);
+    if (need > kv->max_blocks) return fail(LD_E_RANGE, "ld_prefill: sequence would exceed max_blocks_per_seq");
+    if (count_missing(kv, seq, need) > (int64_t)kv->free_stack.size()) return fail(LD_E_NOMEM, "ld_prefill: out of KV blocks");
+    map_blocks(kv, seq, need);
+
+    // all chunks but the last: rows only, nothing emitted
+    std::vector<Row> rows;
+    int64_t fed = 0;      // rows fed so far (of `total`)
+    int32_t consumed = 0; // entries of tokens[] consumed
+    while (total - fed > chunk) {
+        rows.clear();
+        int32_t pos = (int32_t)q->n_cached;
+        if (q->has_pending) rows.push_back({q->pending, pos++, seq});
+        while ((int)rows.size() < chunk) rows.push_back({tokens[consumed++], pos++, seq});
+        std::vector<int32_t> emit;  // none
+        ld_status rc = run_pass(kv, rows, emit, (hipStream_t)stream, nullptr);
+        if (rc) return rc;
+        q->n_cached += rows.size();
+        q->has_pending = false; q->pending = -1;
+        fed += rows.size();
+    }
+    std::vector<Feed> last{{seq, tokens + consumed, n - consumed}};
+    return run_step(kv, last, stream, cb, user, logits_out, "ld_prefill");
+}
+
+ld_status ld_decode_step(ld_kv *kv, const ld_seq *seqs, int32_t n_seqs, void *stream, ld_token_cb cb, void *user,
+                         float *logits_out) {
+    if (!kv || !seqs || n_seqs <= 0) return fail(LD_E_INVAL, "ld_decode_step: bad argument");
+    std::vector<Feed> feeds;
+    for (int i = 0; i < n_seqs; i++) {
+        Seq *q = get_seq(kv, seqs[i]);
+        if (q && !q->has_pending) { ld::set_error("ld_decode_step: sequence %d has no pending token", seqs[i]); return LD_E_STATE; }
+        feeds.push_back({seqs[i], nullptr, 0});
+    }
+    return run_step(kv, feeds, stream, cb, user, logits_out, "ld_decode_step");
+}
+
+ld_status ld_step_mixed(ld_kv *kv, const ld_seq *dec, int32_t n_dec, const ld_seq *pf, const int32_t *const *pf_tokens,
+                        const int32_t *pf_n, int32_t n_pf, void *stream, ld_token_cb cb, void *user, float *logits_out) {
+    if (!kv || n_dec < 0 || n_pf < 0 || n_dec + n_pf == 0 || (n_dec && !dec) || (n_pf && (!pf || !pf_tokens || !pf_n)))
+        return fail(LD_E_INVAL, "ld_step_mixed: bad argument");
+    std::vector<Feed> feeds;
+    for (int i = 0; i < n_dec; i++) {
+        Seq *q = get_seq(kv, dec[i]);
+        if (q && !q->has_pending) { ld::set_error("ld_step_mixed: decoding sequence %d has no pending token", dec[i]); return LD_E_STATE; }
+        feeds.push_back({dec[i], nullptr, 0});
+    }
+    for (int i = 0; i < n_pf; i++) feeds.push_back({pf[i], pf_tokens[i], pf_n[i]});
+    return run_step(kv, feeds, stream, cb, user, logits_out, "ld_step_mixed");
+}
+
+}  // extern "C"

@@ -1,0 +1,30 @@
+// Internal helpers shared by the host state machine and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdarg>
+#include <cstdio>
+#include "ld.h"
+#include "ld_kernels.h"
+
+namespace ld {
+
+void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+void clear_error();
+
+inline ld_status fail(ld_status s, const char *what) {
+    set_error("%s", what);
+    return s;
+}
+
+#define LD_HIP_TRY(expr)                                                                  \
+    do {                                                                                  \
+        hipError_t e_ = (expr);                                                           \
+        if (e_ != hipSuccess) {                                                           \
+            ld::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return LD_E_HIP;                                                              \
+        }                                                                                 \
+    } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace ld

@@ -1,0 +1,536 @@
+// HIP kernels of the decode / chunked-prefill pass for gfx950 (wave64) and their launchers.
+//
+// Numerical scheme: activations, accumulators, softmax statistics and logits are float32;
+// matrices and the KV pool are float32 or bf16.  bf16 -> float32 widening is exact.
+#include "ld_internal.h"
+#include <cmath>
+#include <cstdint>
+
+namespace {
+
+constexpr int WAVE = 64;
+typedef uint16_t bf16_t;
+
+// ---------------------------------------------------------------- element helpers
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// float32 -> bf16, round to nearest even.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// Load 8 consecutive elements (16-byte aligned for bf16, 32-byte for float) as floats.
+__device__ __forceinline__ void load8(const bf16_t *p, float (&v)[8]) {
+    const uint4 u = *reinterpret_cast<const uint4 *>(p);
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void load8(const float *p, float (&v)[8]) {
+    const float4 a = reinterpret_cast<const float4 *>(p)[0];
+    const float4 b = reinterpret_cast<const float4 *>(p)[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
+__device__ __forceinline__ void store_elem(float *p, float v) { *p = v; }
+__device__ __forceinline__ void store_elem(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
+    return v;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---------------------------------------------------------------- embedding gather
+
+template <typename WT>
+__global__ void k_embed(const WT *__restrict__ E, const int32_t *__restrict__ tok, int d, float *__restrict__ x) {
+    const int t = blockIdx.x;
+    const WT *row = E + (int64_t)tok[t] * d;
+    for (int i = threadIdx.x * 8; i < d; i += blockDim.x * 8) {
+        float v[8];
+        load8(row + i, v);
+#pragma unroll
+        for (int e = 0; e < 8; e++) x[(int64_t)t * d + i + e] = v[e];
+    }
+}
+
+// ---------------------------------------------------------------- RMSNorm (stand-alone, with row gather)
+
+__global__ __launch_bounds__(256) void k_rmsnorm(const float *__restrict__ x, const float *__restrict__ g,
+                                                 const int32_t *__restrict__ row_idx, int d, float eps,
+                                                 float *__restrict__ out) {
+    __shared__ float red[4];
+    const int r = blockIdx.x;
+    const float *row = x + (int64_t)(row_idx ? row_idx[r] : r) * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) ss += row[i] * row[i];
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float rstd = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / d + eps);
+    for (int i = threadIdx.x; i < d; i += 256) out[(int64_t)r * d + i] = row[i] * rstd * g[i];
+}
+
+// ---------------------------------------------------------------- linear layer, vector-ALU version
+//
+// One wave owns R output rows (2R matrix rows for the SwiGLU epilogue) for a tile of TT input
+// rows and streams those matrix rows once, 16 bytes per lane per load, lanes striding over K.
+// With NORM the RMS statistics of the input rows are accumulated from the same x loads and the
+// scale 1/rms is applied to the finished dot products (the gain is applied to x on the fly).
+
+template <typename WT, int TT, int R, int EPI, bool NORM>
+__global__ __launch_bounds__(256) void k_linear_valu(const WT *__restrict__ W, const float *__restrict__ x,
+                                                     const float *__restrict__ g, float eps, int T, int N, int K,
+                                                     float *__restrict__ y) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n0 = (blockIdx.x * 4 + wave) * R;
+    const int t0 = blockIdx.y * TT;
+    if (n0 >= N) return;
+    constexpr int NW = (EPI == LDK_SWIGLU) ? 2 * R : R;
+    const WT *wrow[NW];
+#pragma unroll
+    for (int r = 0; r < R; r++) {
+        const int n = min(n0 + r, N - 1);  // clamped rows are computed and dropped
+        wrow[r] = W + (int64_t)n * K;
+        if constexpr (EPI == LDK_SWIGLU) wrow[R + r] = W + (int64_t)(N + n) * K;
+    }
+    float acc[NW][TT];
+    float ss[TT];
+#pragma unroll
+    for (int t = 0; t < TT; t++) {
+        ss[t] = 0.f;
+#pragma unroll
+        for (int r = 0; r < NW; r++) acc[r][t] = 0.f;
+    }
+    for (int k = lane * 8; k < K; k += WAVE * 8) {
+        float wv[NW][8];
+#pragma unroll
+        for (int r = 0; r < NW; r++) load8(wrow[r] + k, wv[r]);
+        float gv[8];
+        if (NORM) load8(g + k, gv);
+#pragma unroll
+        for (int t = 0; t < TT; t++) {
+            float xv[8];
+            if (t0 + t < T) {
+                load8(x + (int64_t)(t0 + t) * K + k, xv);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; e++) xv[e] = 0.f;
+            }
+            if (NORM) {
+#pragma unroll
+                for (int e = 0; e < 8; e++) {
+                    ss[t] = fmaf(xv[e], xv[e], ss[t]);
+                    xv[e] *= gv[e];
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < NW; r++)
+#pragma unroll
+                for (int e = 0; e < 8; e++) acc[r][t] = fmaf(wv[r][e], xv[e], acc[r][t]);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < TT; t++) {
+        float rstd = 1.f;
+        if (NORM) rstd = 1.0f / sqrtf(wave_sum(ss[t]) / K + eps);
+#pragma unroll
+        for (int r = 0; r < NW; r++) acc[r][t] = wave_sum(acc[r][t]) * rstd;
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int t = 0; t < TT; t++) {
+            if (t0 + t >= T) continue;
+#pragma unroll
+            for (int r = 0; r < R; r++) {
+                if (n0 + r >= N) continue;
+                float *dst = y + (int64_t)(t0 + t) * N + n0 + r;
+                if constexpr (EPI == LDK_STORE) *dst = acc[r][t];
+                else if constexpr (EPI == LDK_ADD) *dst += acc[r][t];
+                else {
+                    const float gate = acc[r][t], up = acc[R + r][t];
+                    *dst = gate / (1.0f + __expf(-gate)) * up;
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- rotary tables, RoPE + cache append
+
+// cs[t][i] = (cos, sin)(pos[t] * base^(-2i/hd)), angle formed in float64.
+__global__ void k_rope_table(const int32_t *__restrict__ pos, int hd, double base, float2 *__restrict__ cs) {
+    const int t = blockIdx.x, i = threadIdx.x, half = hd / 2;
+    if (i >= half) return;
+    const double theta = pow(base, -2.0 * (double)i / (double)hd);
+    double s, c;
+    sincos((double)pos[t] * theta, &s, &c);
+    cs[(int64_t)t * half + i] = make_float2((float)c, (float)s);
+}
+
+template <typename KVT>
+__global__ void k_rope_kv_write(float *__restrict__ qkv, const float2 *__restrict__ cs,
+                                const int32_t *__restrict__ pos, const int32_t *__restrict__ seq_slot,
+                                const int32_t *__restrict__ table, int table_stride, KVT *__restrict__ pool,
+                                int H, int Hkv, int hd) {
+    const int t = blockIdx.y, hh = blockIdx.x, i = threadIdx.x, half = hd / 2;
+    if (i >= half) return;
+    const int nqkv = (H + 2 * Hkv) * hd;
+    const float2 c = cs[(int64_t)t * half + i];
+    float *row = qkv + (int64_t)t * nqkv;
+    if (hh < H) {
+        float *u = row + hh * hd;
+        const float a = u[i], b = u[i + half];
+        u[i] = a * c.x - b * c.y;
+        u[i + half] = a * c.y + b * c.x;
+        return;
+    }
+    const int j = hh - H;
+    const float *ku = row + (H + j) * hd;
+    const float *vu = row + (H + Hkv + j) * hd;
+    const float a = ku[i], b = ku[i + half];
+    const int p = pos[t];
+    const int64_t phys = table[(int64_t)seq_slot[t] * table_stride + (p >> 4)];
+    const int64_t block_stride = (int64_t)2 * Hkv * 16 * hd;
+    KVT *kd = pool + phys * block_stride + ((int64_t)j * 16 + (p & 15)) * hd;
+    KVT *vd = kd + (int64_t)Hkv * 16 * hd;
+    store_elem(kd + i, a * c.x - b * c.y);
+    store_elem(kd + i + half, a * c.y + b * c.x);
+    store_elem(vd + i, vu[i]);
+    store_elem(vd + i + half, vu[i + half]);
+}
+
+// ---------------------------------------------------------------- paged decode attention
+//
+// Work item = (row t, head h, chunk c): chunk c covers CB consecutive KV blocks (CB*16 tokens) of
+// the row's context.  A workgroup of 4 waves takes one work item, wave w the blocks w, w+4, ...
+// of the chunk.  Inside a wave, HD/8 adjacent lanes cover one token's head vector with 16-byte
+// loads (8 elements each), so one load instruction brings 64/(HD/8) whole tokens and consecutive
+// lanes read consecutive memory.  Scores are reduced across those lanes with xor shuffles; each
+// lane group keeps its own online-softmax state (m, l, acc) in the log2 domain, merged across
+// groups, waves and finally chunks.
+
+constexpr int ATT_CB = 16;  // KV blocks per chunk (256 tokens)
+
+template <int HD, typename KVT>
+__global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ q, int q_stride,
+                                                      const KVT *__restrict__ pool, int Hkv,
+                                                      const int32_t *__restrict__ table, int table_stride,
+                                                      const int32_t *__restrict__ seq_slot,
+                                                      const int32_t *__restrict__ ctx_len, int H,
+                                                      float scale_log2e, int max_chunks,
+                                                      float *__restrict__ part_o, float *__restrict__ part_ml) {
+    constexpr int LPT = HD / 8;      // lanes per token
+    constexpr int TPI = WAVE / LPT;  // tokens per load instruction
+    constexpr int NI = 16 / TPI;     // load instructions per 16-token block
+    const int c = blockIdx.x, h = blockIdx.y, t = blockIdx.z;
+    const int ctx = ctx_len[t];
+    const int nblk = (ctx + 15) >> 4;
+    const int b_begin = c * ATT_CB;
+    if (b_begin >= nblk) return;
+    const int b_end = min(b_begin + ATT_CB, nblk);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int group = lane / LPT, sub = lane % LPT;
+    const int kvh = h / (H / Hkv);
+    const int64_t block_stride = (int64_t)2 * Hkv * 16 * HD;
+    const int32_t *trow = table + (int64_t)seq_slot[t] * table_stride;
+
+    float qv[8];
+    {
+        const float *qp = q + (int64_t)t * q_stride + h * HD + sub * 8;
+#pragma unroll
+        for (int e = 0; e < 8; e++) qv[e] = qp[e] * scale_log2e;
+    }
+    float m = -INFINITY, l = 0.f, acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) acc[e] = 0.f;
+
+    for (int b = b_begin + wave; b < b_end; b += 4) {
+        const int64_t phys = trow[b];
+        const KVT *kb = pool + phys * block_stride + (int64_t)kvh * 16 * HD + lane * 8;
+        const KVT *vb = kb + (int64_t)Hkv * 16 * HD;
+        float kf[NI][8], vf[NI][8];
+#pragma unroll
+        for (int i = 0; i < NI; i++) load8(kb + i * TPI * HD, kf[i]);
+#pragma unroll
+        for (int i = 0; i < NI; i++) load8(vb + i * TPI * HD, vf[i]);
+        const int ntok = ctx - b * 16;  // valid tokens in this block (may exceed 16)
+        float s[NI];
+        float mb = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < NI; i++) {
+            float d = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; e++) d = fmaf(qv[e], kf[i][e], d);
+#pragma unroll
+            for (int off = 1; off < LPT; off <<= 1) d += __shfl_xor(d, off, WAVE);
+            const bool valid = (i * TPI + group) < ntok;
+            s[i] = valid ? d : -INFINITY;
+            if (!valid) {
+#pragma unroll
+                for (int e = 0; e < 8; e++) vf[i][e] = 0.f;
+            }
+            mb = fmaxf(mb, s[i]);
+        }
+        const float m_new = fmaxf(m, mb);
+        if (m_new > -INFINITY) {
+            const float sc = fast_exp2(m - m_new);
+            l *= sc;
+#pragma unroll
+            for (int e = 0; e < 8; e++) acc[e] *= sc;
+#pragma unroll
+            for (int i = 0; i < NI; i++) {
+                const float p = fast_exp2(s[i] - m_new);
+                l += p;
+#pragma unroll
+                for (int e = 0; e < 8; e++) acc[e] = fmaf(p, vf[i][e], acc[e]);
+            }
+            m = m_new;
+        }
+    }
+    // merge the lane groups of this wave
+#pragma unroll
+    for (int off = LPT; off < WAVE; off <<= 1) {
+        const float m_o = __shfl_xor(m, off, WAVE), l_o = __shfl_xor(l, off, WAVE);
+        const float m_n = fmaxf(m, m_o);
+        const float a = (m_n > -INFINITY) ? fast_exp2(m - m_n) : 0.f;
+        const float bsc = (m_n > -INFINITY) ? fast_exp2(m_o - m_n) : 0.f;
+        l = l * a + l_o * bsc;
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc[e] = acc[e] * a + __shfl_xor(acc[e], off, WAVE) * bsc;
+        m = m_n;
+    }
+    __shared__ float sm_m[4], sm_l[4], sm_acc[4][HD];
+    if (lane < LPT) {
+#pragma unroll
+        for (int e = 0; e < 8; e++) sm_acc[wave][sub * 8 + e] = acc[e];
+        if (lane == 0) { sm_m[wave] = m; sm_l[wave] = l; }
+    }
+    __syncthreads();
+    if (threadIdx.x < HD) {
+        const float M = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));  // finite: wave 0 saw a valid token
+        float o = 0.f, L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; w++) {
+            const float a = fast_exp2(sm_m[w] - M);
+            o += a * sm_acc[w][threadIdx.x];
+            L += a * sm_l[w];
+        }
+        const int64_t item = ((int64_t)t * H + h) * max_chunks + c;
+        part_o[item * HD + threadIdx.x] = o;
+        if (threadIdx.x == 0) { part_ml[item * 2] = M; part_ml[item * 2 + 1] = L; }
+    }
+}
+
+template <int HD>
+__global__ void k_attn_merge(const float *__restrict__ part_o, const float *__restrict__ part_ml,
+                             const int32_t *__restrict__ ctx_len, int H, int max_chunks, float *__restrict__ out) {
+    const int h = blockIdx.x, t = blockIdx.y, d = threadIdx.x;
+    const int nch = ((ctx_len[t] + 15) / 16 + ATT_CB - 1) / ATT_CB;
+    const int64_t base = ((int64_t)t * H + h) * max_chunks;
+    float M = -INFINITY;
+    for (int c = 0; c < nch; c++) M = fmaxf(M, part_ml[(base + c) * 2]);
+    float o = 0.f, L = 0.f;
+    for (int c = 0; c < nch; c++) {
+        const float a = fast_exp2(part_ml[(base + c) * 2] - M);
+        o += a * part_o[(base + c) * HD + d];
+        L += a * part_ml[(base + c) * 2 + 1];
+    }
+    out[((int64_t)t * H + h) * HD + d] = o / L;
+}
+
+// ---------------------------------------------------------------- greedy argmax (lowest index on ties)
+
+__global__ __launch_bounds__(1024) void k_argmax(const float *__restrict__ logits, int V, int32_t *__restrict__ out) {
+    __shared__ float sv[16];
+    __shared__ int si[16];
+    const int r = blockIdx.x;
+    const float *row = logits + (int64_t)r * V;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int i = threadIdx.x; i < V; i += 1024) {
+        const float v = row[i];
+        if (v > bv || bi == 0x7fffffff) { bv = v; bi = i; }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float ov = __shfl_xor(bv, off, WAVE);
+        const int oi = __shfl_xor(bi, off, WAVE);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; w++)
+            if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+        out[r] = bi;
+    }
+}
+
+// ---------------------------------------------------------------- launch helpers
+
+inline ld_status launched(const char *what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        ld::set_error("launch of %s failed: %s", what, hipGetErrorString(e));
+        return LD_E_HIP;
+    }
+    return LD_OK;
+}
+
+template <typename WT, int TT, int R, bool NORM>
+void launch_linear_epi(const WT *W, const float *x, const float *g, float eps, int T, int N, int K, int epi,
+                       float *y, hipStream_t s) {
+    dim3 grid((N + 4 * R - 1) / (4 * R), (T + TT - 1) / TT), block(256);
+    if (epi == LDK_STORE)
+        hipLaunchKernelGGL((k_linear_valu<WT, TT, R, LDK_STORE, NORM>), grid, block, 0, s, W, x, g, eps, T, N, K, y);
+    else if (epi == LDK_ADD)
+        hipLaunchKernelGGL((k_linear_valu<WT, TT, R, LDK_ADD, NORM>), grid, block, 0, s, W, x, g, eps, T, N, K, y);
+    else
+        hipLaunchKernelGGL((k_linear_valu<WT, TT, R, LDK_SWIGLU, NORM>), grid, block, 0, s, W, x, g, eps, T, N, K, y);
+}
+
+template <typename WT, bool NORM>
+void launch_linear(const WT *W, const float *x, const float *g, float eps, int T, int N, int K, int epi, float *y,
+                   hipStream_t s) {
+    // rows per wave: keep at least ~2048 waves in the grid when N allows it
+    const bool wide = (int64_t)N >= 8192 && epi != LDK_SWIGLU;
+    if (T == 1) {
+        if (wide) launch_linear_epi<WT, 1, 4, NORM>(W, x, g, eps, T, N, K, epi, y, s);
+        else launch_linear_epi<WT, 1, 2, NORM>(W, x, g, eps, T, N, K, epi, y, s);
+    } else if (T == 2) {
+        launch_linear_epi<WT, 2, 2, NORM>(W, x, g, eps, T, N, K, epi, y, s);
+    } else if (T <= 4) {
+        launch_linear_epi<WT, 4, 2, NORM>(W, x, g, eps, T, N, K, epi, y, s);
+    } else {
+        launch_linear_epi<WT, 8, 2, NORM>(W, x, g, eps, T, N, K, epi, y, s);
+    }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- C ABI (kernel level)
+
+extern "C" {
+
+ld_status ldk_embed(const void *embed, int32_t dtype, const int32_t *tok, int32_t T, int32_t d, float *x,
+                    void *stream) {
+    if (!embed || !tok || !x || T < 0 || d <= 0 || d % 8) return ld::fail(LD_E_INVAL, "ldk_embed: bad argument");
+    if (T == 0) return LD_OK;
+    hipStream_t s = (hipStream_t)stream;
+    if (dtype == LD_BF16) hipLaunchKernelGGL(k_embed<bf16_t>, dim3(T), dim3(128), 0, s, (const bf16_t *)embed, tok, d, x);
+    else if (dtype == LD_F32) hipLaunchKernelGGL(k_embed<float>, dim3(T), dim3(128), 0, s, (const float *)embed, tok, d, x);
+    else return ld::fail(LD_E_INVAL, "ldk_embed: bad dtype");
+    return launched("k_embed");
+}
+
+ld_status ldk_rmsnorm(const float *x, const float *g, const int32_t *row_idx, int32_t R, int32_t d, float eps,
+                      float *out, void *stream) {
+    if (!x || !g || !out || R < 0 || d <= 0) return ld::fail(LD_E_INVAL, "ldk_rmsnorm: bad argument");
+    if (R == 0) return LD_OK;
+    hipLaunchKernelGGL(k_rmsnorm, dim3(R), dim3(256), 0, (hipStream_t)stream, x, g, row_idx, d, eps, out);
+    return launched("k_rmsnorm");
+}
+
+ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *g, float eps, int32_t T, int32_t N,
+                     int32_t K, int32_t epilogue, float *y, void *stream) {
+    if (!W || !x || !y || T < 0 || N <= 0 || K <= 0 || K % 8 || epilogue < 0 || epilogue > 2)
+        return ld::fail(LD_E_INVAL, "ldk_linear: bad argument (K must be a multiple of 8)");
+    if (T == 0) return LD_OK;
+    hipStream_t s = (hipStream_t)stream;
+    if (dtype == LD_BF16) {
+        if (g) launch_linear<bf16_t, true>((const bf16_t *)W, x, g, eps, T, N, K, epilogue, y, s);
+        else launch_linear<bf16_t, false>((const bf16_t *)W, x, g, eps, T, N, K, epilogue, y, s);
+    } else if (dtype == LD_F32) {
+        if (g) launch_linear<float, true>((const float *)W, x, g, eps, T, N, K, epilogue, y, s);
+        else launch_linear<float, false>((const float *)W, x, g, eps, T, N, K, epilogue, y, s);
+    } else {
+        return ld::fail(LD_E_INVAL, "ldk_linear: bad dtype");
+    }
+    return launched("k_linear");
+}
+
+ld_status ldk_rope_table(const int32_t *pos, int32_t T, int32_t hd, float rope_base, float *cos_sin, void *stream) {
+    if (!pos || !cos_sin || T < 0 || (hd != 64 && hd != 128)) return ld::fail(LD_E_INVAL, "ldk_rope_table: bad argument");
+    if (T == 0) return LD_OK;
+    hipLaunchKernelGGL(k_rope_table, dim3(T), dim3(64), 0, (hipStream_t)stream, pos, hd, (double)rope_base,
+                       (float2 *)cos_sin);
+    return launched("k_rope_table");
+}
+
+ld_status ldk_rope_kv_write(float *qkv, const float *cos_sin, const int32_t *pos, const int32_t *seq_slot,
+                            const int32_t *table, int32_t table_stride, void *pool_layer, int32_t dtype, int32_t T,
+                            int32_t H, int32_t Hkv, int32_t hd, void *stream) {
+    if (!qkv || !cos_sin || !pos || !seq_slot || !table || !pool_layer || T < 0 || H <= 0 || Hkv <= 0 || H % Hkv ||
+        (hd != 64 && hd != 128))
+        return ld::fail(LD_E_INVAL, "ldk_rope_kv_write: bad argument");
+    if (T == 0) return LD_OK;
+    dim3 grid(H + Hkv, T), block(64);
+    hipStream_t s = (hipStream_t)stream;
+    if (dtype == LD_BF16)
+        hipLaunchKernelGGL(k_rope_kv_write<bf16_t>, grid, block, 0, s, qkv, (const float2 *)cos_sin, pos, seq_slot,
+                           table, table_stride, (bf16_t *)pool_layer, H, Hkv, hd);
+    else if (dtype == LD_F32)
+        hipLaunchKernelGGL(k_rope_kv_write<float>, grid, block, 0, s, qkv, (const float2 *)cos_sin, pos, seq_slot,
+                           table, table_stride, (float *)pool_layer, H, Hkv, hd);
+    else return ld::fail(LD_E_INVAL, "ldk_rope_kv_write: bad dtype");
+    return launched("k_rope_kv_write");
+}
+
+static int attn_max_chunks(int max_ctx) { return ((max_ctx + 15) / 16 + ATT_CB - 1) / ATT_CB; }
+
+size_t ldk_attention_scratch_bytes(int32_t T, int32_t H, int32_t hd, int32_t max_ctx) {
+    if (T <= 0 || H <= 0 || hd <= 0 || max_ctx <= 0) return 0;
+    return (size_t)T * H * attn_max_chunks(max_ctx) * (hd + 2) * sizeof(float);
+}
+
+ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
+                              const int32_t *table, int32_t table_stride, const int32_t *seq_slot,
+                              const int32_t *ctx_len, int32_t max_ctx, int32_t T, int32_t H, int32_t Hkv, int32_t hd,
+                              float *out, void *scratch, size_t scratch_bytes, void *stream) {
+    if (!q || !pool_layer || !table || !seq_slot || !ctx_len || !out || !scratch || T < 0 || H <= 0 || Hkv <= 0 ||
+        H % Hkv || (hd != 64 && hd != 128) || max_ctx <= 0)
+        return ld::fail(LD_E_INVAL, "ldk_paged_attention: bad argument");
+    if (T == 0) return LD_OK;
+    if (scratch_bytes < ldk_attention_scratch_bytes(T, H, hd, max_ctx))
+        return ld::fail(LD_E_INVAL, "ldk_paged_attention: scratch too small");
+    const int mc = attn_max_chunks(max_ctx);
+    float *part_o = (float *)scratch;
+    float *part_ml = part_o + (size_t)T * H * mc * hd;
+    const float sl2 = (float)(1.4426950408889634 / std::sqrt((double)hd));
+    dim3 grid(mc, H, T), block(256);
+    hipStream_t s = (hipStream_t)stream;
+#define LD_ATT(HD_, KVT_)                                                                                         \
+    do {                                                                                                          \
+        hipLaunchKernelGGL((k_attn_partial<HD_, KVT_>), grid, block, 0, s, q, q_stride, (const KVT_ *)pool_layer, \
+                           Hkv, table, table_stride, seq_slot, ctx_len, H, sl2, mc, part_o, part_ml);             \
+        hipLaunchKernelGGL((k_attn_merge<HD_>), dim3(H, T), dim3(HD_), 0, s, part_o, part_ml, ctx_len, H, mc, out); \
+    } while (0)
+    if (dtype == LD_BF16 && hd == 128) LD_ATT(128, bf16_t);
+    else if (dtype == LD_BF16 && hd == 64) LD_ATT(64, bf16_t);
+    else if (dtype == LD_F32 && hd == 128) LD_ATT(128, float);
+    else if (dtype == LD_F32 && hd == 64) LD_ATT(64, float);
+    else return ld::fail(LD_E_INVAL, "ldk_paged_attention: bad dtype");
+#undef LD_ATT
+    return launched("k_attn");
+}
+
+ld_status ldk_argmax(const float *logits, int32_t R, int32_t V, int32_t *out, void *stream) {
+    if (!logits || !out || R < 0 || V <= 0) return ld::fail(LD_E_INVAL, "ldk_argmax: bad argument");
+    if (R == 0) return LD_OK;
+    hipLaunchKernelGGL(k_argmax, dim3(R), dim3(1024), 0, (hipStream_t)stream, logits, V, out);
+    return launched("k_argmax");
+}
+
+}  // extern "C"

@@ -1,0 +1,159 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its host logic
+(block allocator, sequence state machine, argument validation) behaves as the header states and as
+the oracle's allocator does (integer-exact).  No kernel is launched here."""
+import ctypes as C
+import glob
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2406_00059_amd as ld
+from workloads import TINY, gen
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 1 << 20     # an aligned non-null "device address" that is never dereferenced on the CPU
+
+
+def _declared():
+    names = []
+    for h in glob.glob(os.path.join(ROOT, "include", "*.h")):
+        src = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names += re.findall(r"\b(ldk?_[a-z0-9_]+)\s*\(", src)
+    return sorted(set(n for n in names if n not in ("ld_token_cb",)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = ld.lib()
+    decl = _declared()
+    assert len(decl) >= 25
+    for name in decl:
+        assert hasattr(L, name), f"{name} declared in include/ but not exported"
+    assert set(decl) == set(ld.binding.EXPORTS)
+
+
+def _cfg(**over):
+    base = dict(n_layers=2, d_model=256, n_heads=4, n_kv_heads=4, head_dim=64, d_ffn=688, vocab=1024,
+                rms_eps=1e-5, rope_base=10000.0, dtype=ld.LD_F32, kv_block=16, max_chunk=256)
+    base.update(over)
+    return ld.ld_model_config(**base)
+
+
+def _weights(L=2):
+    tab = (C.c_void_p * L)(*[FAKE] * L)
+    p = C.cast(tab, C.POINTER(C.c_void_p))
+    w = ld.ld_weights(FAKE, FAKE, FAKE, p, p, p, p, p, p)
+    w._keep = tab
+    return w
+
+
+def _model(**over):
+    return ld.ld_model_create(_cfg(**over), _weights())
+
+
+def _kv(m, n_blocks=40, max_tokens=64, max_seqs=4, max_blocks=12):
+    ws = ld.ld_workspace_bytes(m, max_tokens, max_seqs, max_blocks)
+    assert ws > 0
+    return ld.ld_kv_create(m, FAKE, n_blocks, FAKE, ws, max_tokens, max_seqs, max_blocks)
+
+
+@pytest.mark.parametrize("bad", [dict(head_dim=48), dict(kv_block=32), dict(n_kv_heads=3), dict(d_model=250),
+                                 dict(dtype=7), dict(vocab=0), dict(rms_eps=0.0)])
+def test_model_create_rejects_bad_shapes(bad):
+    with pytest.raises(ld.LdError) as e:
+        _model(**bad)
+    assert e.value.status == ld.LD_E_INVAL and ld.ld_last_error()
+
+
+def test_pool_size_formula():
+    m = _model()
+    # [layer][block][2][kv_head][16][hd] float32
+    assert ld.ld_kv_bytes(m, 10) == 2 * 10 * 2 * 4 * 16 * 64 * 4
+    m2 = _model(dtype=ld.LD_BF16, n_kv_heads=2)
+    assert ld.ld_kv_bytes(m2, 3) == 2 * 3 * 2 * 2 * 16 * 64 * 2
+    with pytest.raises(ld.LdError):
+        ld.ld_kv_create(m, FAKE, 4, FAKE, 16, 8, 2, 2)            # workspace too small
+    with pytest.raises(ld.LdError):
+        ld.ld_kv_create(m, FAKE + 8, 4, FAKE, 1 << 40, 8, 2, 2)   # misaligned pool
+
+
+def test_allocator_matches_oracle_allocator_bit_exact():
+    """Random alloc / map / grow / free traffic: block tables and free counts equal the oracle's."""
+    from workloads import make_weights
+    shape = TINY.with_layers(1)
+    om = oracle.Model(shape, make_weights(shape, 3))
+    okv = oracle.KV(om, 48, 5, 10)
+    m = _model(n_layers=1)
+    kv = _kv(m, n_blocks=48, max_seqs=5, max_blocks=10)
+    r = gen.randint(77, 1, 0, 1 << 30, 400).numpy()
+    live, lens = [], {}
+    zero = lambda n: np.zeros((n, 1, 2, 4, 64))
+    for step in range(100):
+        op = r[4 * step] % 4
+        if op == 0 or not live:
+            res = int(r[4 * step + 1] % 40)
+            rc_o, s_o = okv.alloc(res)
+            rc_g, s_g = ld.ld_kv_alloc(kv, res, check=False)
+            assert rc_o == rc_g
+            if rc_o == 0:
+                assert s_o == s_g
+                live.append(s_o); lens[s_o] = 0
+        elif op == 1:
+            s = live[r[4 * step + 1] % len(live)]
+            n = int(r[4 * step + 2] % 50)
+            rc_o = okv.inject(s, zero(n))
+            rc_g = ld.ld_kv_assume(kv, s, n, -1, check=False)
+            assert rc_o == rc_g, (step, rc_o, rc_g)
+        elif op == 2:
+            s = live[r[4 * step + 1] % len(live)]
+            lb, pb = int(r[4 * step + 2] % 10), int(r[4 * step + 3] % 48)
+            assert okv.map(s, lb, pb) == ld.ld_kv_map(kv, s, lb, pb, check=False)
+        else:
+            s = live.pop(r[4 * step + 1] % len(live))
+            assert okv.free(s) == 0 and ld.ld_kv_free(kv, s) == 0
+        assert okv.free_blocks() == ld.ld_kv_free_blocks(kv)
+        for s in live:
+            assert okv.block_table(s)[1].tolist() == ld.ld_kv_block_table(kv, s).tolist()
+            assert okv.length(s) == ld.ld_kv_len(kv, s)
+    assert step == 99
+
+
+def test_first_pops_are_0_1_2_and_free_returns_blocks_in_logical_order():
+    m = _model()
+    kv = _kv(m)
+    a = ld.ld_kv_alloc(kv, 33)
+    b = ld.ld_kv_alloc(kv, 16)
+    assert ld.ld_kv_block_table(kv, a).tolist() == [0, 1, 2] and ld.ld_kv_block_table(kv, b).tolist() == [3]
+    ld.ld_kv_free(kv, a)
+    c = ld.ld_kv_alloc(kv, 48)
+    assert c == a and ld.ld_kv_block_table(kv, c).tolist() == [0, 1, 2]
+
+
+def test_state_errors_leave_state_unchanged():
+    m = _model()
+    kv = _kv(m, n_blocks=3, max_tokens=64, max_seqs=2, max_blocks=8)
+    s = ld.ld_kv_alloc(kv, 0)
+    # decode with no pending token
+    rc, _ = ld.ld_decode_step(kv, [s], stream=0, check=False)
+    assert rc == ld.LD_E_STATE and "pending" in ld.ld_last_error()
+    # token id out of range, bad handle, duplicate sequence
+    assert ld.ld_prefill(kv, s, [5, 1024], stream=0, check=False)[0] == ld.LD_E_RANGE
+    assert ld.ld_prefill(kv, 1, [5], stream=0, check=False)[0] == ld.LD_E_INVAL
+    ld.ld_kv_assume(kv, s, 5, pending=7)
+    assert ld.ld_decode_step(kv, [s, s], stream=0, check=False)[0] == ld.LD_E_INVAL
+    # out of blocks: 3 blocks = 48 tokens; prefill of 60 must fail without touching anything
+    before = (ld.ld_kv_block_table(kv, s).tolist(), ld.ld_kv_free_blocks(kv), ld.ld_kv_len(kv, s))
+    assert ld.ld_prefill(kv, s, list(range(60)), stream=0, check=False)[0] == ld.LD_E_NOMEM
+    assert (ld.ld_kv_block_table(kv, s).tolist(), ld.ld_kv_free_blocks(kv), ld.ld_kv_len(kv, s)) == before
+    # more rows than the workspace was sized for
+    kv2 = _kv(m, n_blocks=30, max_tokens=8, max_seqs=2, max_blocks=8)
+    s2 = ld.ld_kv_alloc(kv2, 0)
+    t = np.arange(20, dtype=np.int32)
+    rc, _ = ld.ld_step_mixed(kv2, [], [s2], [t], stream=0, check=False)
+    assert rc == ld.LD_E_RANGE
+    # context beyond max_blocks_per_seq
+    assert ld.ld_kv_assume(kv2, s2, 16 * 8 + 1, check=False) == ld.LD_E_RANGE
+    # double free
+    assert ld.ld_kv_free(kv2, s2) == 0 and ld.ld_kv_free(kv2, s2, check=False) == ld.LD_E_INVAL

@@ -1,0 +1,149 @@
+"""End-to-end parity on the GPU through the C ABI: greedy tokens and block tables bit-exact against the
+oracle, logits within the stated tolerance (max-norm relative error per row: 1e-4 on the fp32 shape,
+2e-2 on bf16 shapes), on the tool-call pattern generate -> stop -> append observation -> continue."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2406_00059_amd as ld
+from workloads import TINY, LLAMA7B, SEED_BASE, gen
+from helpers import Pair, Tokens, prompt, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def test_tiny_fp32_prompt32_decode64():
+    """Workload 0: 2-layer fp32 decoder, batch 1, prompt of 32 ids, 64 greedy tokens, KV block 16."""
+    P = Pair(TINY, SEED_BASE + 0, n_blocks=8, max_tokens=64, max_seqs=1, max_blocks=8)
+    s = P.alloc()
+    tok = prompt(SEED_BASE, 100, 32, TINY.vocab)
+    sink = Tokens()
+    rc, t_o, lg_o = P.okv.prefill(s, tok)
+    rc, lg_g = ld.ld_prefill(P.gkv.h, s, tok, callback=sink, logits_vocab=P.V)
+    errs = [rel_err(lg_g, lg_o)]
+    toks_o = [t_o]
+    for _ in range(63):
+        rc, t_o, lg_o = P.okv.decode(s)
+        rc, lg_g = ld.ld_decode_step(P.gkv.h, [s], callback=sink, logits_vocab=P.V)
+        errs.append(rel_err(lg_g[0], lg_o)); toks_o.append(t_o)
+    assert max(errs) <= 1e-4, max(errs)
+    assert [t for _, t, _ in sink.log] == toks_o
+    assert [p for _, _, p in sink.log] == list(range(32, 96))
+    assert P.tables_equal(s) and ld.ld_kv_block_table(P.gkv.h, s).tolist() == [0, 1, 2, 3, 4, 5]
+    assert ld.ld_kv_len(P.gkv.h, s) == 95
+
+
+@pytest.mark.parametrize("shape,tol", [(TINY, 1e-4), (replace(TINY, dtype="bf16", n_kv_heads=2, name="tiny-bf16-gqa"), 2e-2)])
+def test_tool_rounds_with_chunked_observation_prefill(shape, tol):
+    """Three rounds of decode -> observation; the prompt and the observations go through chunked
+    prefill (chunk 8, ragged tails), on a permuted block table."""
+    P = Pair(shape, 11, n_blocks=24, max_tokens=8, max_seqs=2, max_blocks=16, max_chunk=8)
+    s = P.alloc()
+    for lb, pb in enumerate([9, 3, 14, 0, 5, 21, 7]):
+        assert P.okv.map(s, lb, pb) == 0 and ld.ld_kv_map(P.gkv.h, s, lb, pb) == 0
+    sink, toks_o, errs = Tokens(), [], []
+    rc, t, lg_o = P.okv.prefill(s, prompt(11, 1, 29, shape.vocab)); toks_o.append(t)
+    rc, lg = ld.ld_prefill(P.gkv.h, s, prompt(11, 1, 29, shape.vocab), callback=sink, logits_vocab=P.V)
+    errs.append(rel_err(lg, lg_o))
+    for rnd in range(3):
+        for _ in range(6):
+            rc, t, lg_o = P.okv.decode(s); toks_o.append(t)
+            rc, lg = ld.ld_decode_step(P.gkv.h, [s], callback=sink, logits_vocab=P.V)
+            errs.append(rel_err(lg[0], lg_o))
+        obs = prompt(11, 10 + rnd, [7, 8, 19][rnd], shape.vocab)     # 8, 9, 20 rows with the pending token
+        rc, t, lg_o = P.okv.prefill(s, obs); toks_o.append(t)
+        rc, lg = ld.ld_prefill(P.gkv.h, s, obs, callback=sink, logits_vocab=P.V)
+        errs.append(rel_err(lg, lg_o))
+    assert max(errs) <= tol, max(errs)
+    assert sink.last(len(toks_o)) == toks_o
+    assert P.tables_equal(s) and ld.ld_kv_len(P.gkv.h, s) == P.okv.length(s)
+
+
+def test_batched_decode_mixed_step_and_batch_invariance():
+    """Continuous batching on the small bf16 shape: 5 sequences of different lengths decode together;
+    in one step two of them get an observation chunk prefilled in the same pass (pending token first).
+    Every sequence's tokens equal the oracle's, which runs each sequence alone."""
+    shape = replace(TINY, dtype="bf16", name="tiny-bf16")
+    P = Pair(shape, 12, n_blocks=64, max_tokens=64, max_seqs=5, max_blocks=12)
+    seqs = [P.alloc() for _ in range(5)]
+    lens = [5, 16, 17, 33, 48]
+    cur = {}
+    for s, n in zip(seqs, lens):
+        tk = prompt(12, 50 + s, n, shape.vocab)
+        rc, t, _ = P.okv.prefill(s, tk, want_logits=False); cur[s] = t
+        sink = Tokens(); ld.ld_prefill(P.gkv.h, s, tk, callback=sink)
+        assert sink.last() == [t]
+    errs = []
+    for step in range(20):
+        sink = Tokens()
+        if step == 7:
+            pf, dec = [seqs[1], seqs[3]], [seqs[0], seqs[2], seqs[4]]
+            obs = [prompt(12, 70, 21, shape.vocab), prompt(12, 71, 9, shape.vocab)]
+            rc, lg = ld.ld_step_mixed(P.gkv.h, dec, pf, obs, callback=sink, logits_vocab=P.V)
+            order = dec + pf
+            ref = [P.okv.decode(s) for s in dec] + [P.okv.prefill(s, o) for s, o in zip(pf, obs)]
+        else:
+            order = seqs if step % 2 == 0 else seqs[::-1]           # batch order must not matter
+            rc, lg = ld.ld_decode_step(P.gkv.h, order, callback=sink, logits_vocab=P.V)
+            ref = [P.okv.decode(s) for s in order]
+        assert [q for q, _, _ in sink.log] == order
+        for i, (rc_o, t_o, lg_o) in enumerate(ref):
+            errs.append(rel_err(lg[i], lg_o))
+            assert sink.log[i][1] == t_o, (step, i)
+    assert max(errs) <= 2e-2
+    for s in seqs:
+        assert P.tables_equal(s)
+
+
+def test_callback_stop_and_early_abort_frees_blocks():
+    P = Pair(TINY, 13, n_blocks=8, max_tokens=32, max_seqs=2, max_blocks=4)
+    s = P.alloc()
+    sink = Tokens(stop_at=3)
+    ld.ld_prefill(P.gkv.h, s, prompt(13, 1, 20, TINY.vocab), callback=sink)
+    ld.ld_decode_step(P.gkv.h, [s], callback=sink)
+    ld.ld_decode_step(P.gkv.h, [s], callback=sink)                  # third token: callback asks to stop
+    rc, _ = ld.ld_decode_step(P.gkv.h, [s], callback=sink, check=False)
+    assert rc == ld.LD_E_STATE and len(sink.log) == 3
+    free_before = ld.ld_kv_free_blocks(P.gkv.h)
+    ld.ld_kv_free(P.gkv.h, s)
+    assert ld.ld_kv_free_blocks(P.gkv.h) == free_before + 2
+    s2 = ld.ld_kv_alloc(P.gkv.h, 0)
+    assert s2 == s
+
+
+def test_run_twice_is_deterministic():
+    outs = []
+    for _ in range(2):
+        P = Pair(TINY, 14, n_blocks=8, max_tokens=32, max_seqs=1, max_blocks=8)
+        s = P.alloc(); sink = Tokens(); lgs = []
+        rc, lg = ld.ld_prefill(P.gkv.h, s, prompt(14, 1, 24, TINY.vocab), callback=sink, logits_vocab=P.V)
+        lgs.append(lg.copy())
+        for _ in range(16):
+            rc, lg = ld.ld_decode_step(P.gkv.h, [s], callback=sink, logits_vocab=P.V); lgs.append(lg[0].copy())
+        outs.append((sink.log, np.stack(lgs)))
+    assert outs[0][0] == outs[1][0] and np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_7b_width_two_layers_prompt_and_32_greedy_tokens():
+    """7B layer shape (d 4096, 32 x 128 heads, FFN 11008, vocab 32000, bf16) at reduced depth so the
+    oracle finishes in seconds: prompt 48, then 32 greedy tokens identical, logits within 2e-2."""
+    shape = LLAMA7B.with_layers(2)
+    P = Pair(shape, SEED_BASE + 2, n_blocks=8, max_tokens=64, max_seqs=1, max_blocks=8, gen_device="cuda")
+    s = P.alloc()
+    tk = prompt(SEED_BASE + 2, 100, 48, shape.vocab)
+    sink, toks_o, errs, gaps = Tokens(), [], [], []
+    rc, t, lg_o = P.okv.prefill(s, tk); toks_o.append(t)
+    rc, lg = ld.ld_prefill(P.gkv.h, s, tk, callback=sink, logits_vocab=P.V)
+    errs.append(rel_err(lg, lg_o))
+    for _ in range(32):
+        rc, t, lg_o = P.okv.decode(s); toks_o.append(t)
+        rc, lg = ld.ld_decode_step(P.gkv.h, [s], callback=sink, logits_vocab=P.V)
+        errs.append(rel_err(lg[0], lg_o))
+        top2 = np.sort(lg_o)[-2:]; gaps.append((top2[1] - top2[0]) / np.abs(lg_o).max())
+    print("max rel err", max(errs), "min top-2 gap / max|logit|", min(gaps))
+    assert max(errs) <= 2e-2
+    assert sink.last(33) == toks_o
+    assert P.tables_equal(s)

@@ -1,0 +1,199 @@
+"""Per-kernel parity on the GPU: every kernel-level entry point against the oracle's step functions
+on the same seeded inputs, element by element, at sizes spanning several tiles and ragged tails."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2406_00059_amd as ld
+from workloads import gen
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _mat(seed, stream, n, k, dtype):
+    w = gen.normal(seed, stream, (n, k), std=0.05)
+    return w.bfloat16() if dtype == "bf16" else w
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T", [1, 2, 3, 4, 7, 8, 19])
+def test_linear_store_add_and_fused_norm(dtype, T):
+    N, K = 301, 688           # ragged row count, K not a multiple of 512
+    W = _mat(1, 1, N, K, dtype); x = gen.normal(1, 2, (T, K)); g = gen.normal(1, 3, (K,), std=0.1, mean=1.0)
+    y0 = gen.normal(1, 4, (T, N))
+    Wh = oracle.to_host_matrix(W)
+    Wd, xd, gd = W.to(DEV), x.to(DEV), g.to(DEV)
+    y = torch.empty(T, N, device=DEV)
+    ld.ldk_linear(Wd, xd, y, ld.LDK_STORE)
+    ref = np.stack([oracle.matvec(Wh, x[t].numpy()) for t in range(T)])
+    np.testing.assert_allclose(y.cpu().numpy(), ref, rtol=0, atol=2e-6 * np.abs(ref).max())
+    y = y0.to(DEV).clone()
+    ld.ldk_linear(Wd, xd, y, ld.LDK_ADD, g=gd, eps=1e-5)
+    refn = np.stack([oracle.matvec(Wh, oracle.rmsnorm(x[t].numpy(), g.numpy(), 1e-5)) for t in range(T)])
+    np.testing.assert_allclose(y.cpu().numpy(), y0.numpy() + refn, rtol=0, atol=3e-6 * np.abs(refn).max())
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T", [1, 5])
+def test_linear_swiglu(dtype, T):
+    F, K = 173, 256
+    W = _mat(2, 1, 2 * F, K, dtype); x = gen.normal(2, 2, (T, K)); g = gen.normal(2, 3, (K,), std=0.1, mean=1.0)
+    Wh = oracle.to_host_matrix(W)
+    y = torch.empty(T, F, device=DEV)
+    ld.ldk_linear(W.to(DEV), x.to(DEV), y, ld.LDK_SWIGLU, g=g.to(DEV), eps=1e-5)
+    for t in range(T):
+        gu = oracle.matvec(Wh, oracle.rmsnorm(x[t].numpy(), g.numpy(), 1e-5))
+        ref = np.array([oracle.silu(gu[i]) * gu[F + i] for i in range(F)])
+        np.testing.assert_allclose(y[t].cpu().numpy(), ref, rtol=0, atol=3e-6 * np.abs(ref).max())
+
+
+def test_linear_full_7b_shapes_on_sampled_outputs():
+    """The launch shapes of the 7B decode step (T = 1), checked on sampled output rows."""
+    for N, K, epi in [(12288, 4096, ld.LDK_STORE), (4096, 11008, ld.LDK_ADD), (11008, 4096, ld.LDK_SWIGLU),
+                      (32000, 4096, ld.LDK_STORE)]:
+        rows = N * (2 if epi == ld.LDK_SWIGLU else 1)
+        W = gen.normal(3, N, (rows, K), std=0.02, device=DEV).bfloat16()
+        x = gen.normal(3, 7, (1, K), device=DEV)
+        y = torch.zeros(1, N, device=DEV)
+        ld.ldk_linear(W, x, y, epi)
+        idx = gen.randint(3, 9, 0, N - 1, 48).tolist() + [0, N - 1]
+        xh = x[0].cpu().numpy()
+        for n in idx:
+            a = oracle.matvec(oracle.to_host_matrix(W[n:n + 1]), xh)[0]
+            if epi == ld.LDK_SWIGLU:
+                a = oracle.silu(a) * oracle.matvec(oracle.to_host_matrix(W[N + n:N + n + 1]), xh)[0]
+            assert abs(y[0, n].item() - a) <= 1e-5 * max(1.0, abs(a)) + 2e-6 * math.sqrt(K) * 0.02
+
+
+def test_embed_and_rmsnorm_gather():
+    E = _mat(4, 1, 50, 256, "bf16"); tok = torch.tensor([3, 49, 0, 3], dtype=torch.int32)
+    x = torch.empty(4, 256, device=DEV)
+    ld.ldk_embed(E.to(DEV), tok.to(DEV), x)
+    assert torch.equal(x.cpu(), E.float()[tok.long()])
+    g = gen.normal(4, 2, (256,), std=0.1, mean=1.0)
+    idx = torch.tensor([2, 0], dtype=torch.int32)
+    out = torch.empty(2, 256, device=DEV)
+    ld.ldk_rmsnorm(x, g.to(DEV), out, 1e-5, row_idx=idx.to(DEV))
+    for r, src in enumerate([2, 0]):
+        ref = oracle.rmsnorm(x[src].cpu().numpy(), g.numpy(), 1e-5)
+        np.testing.assert_allclose(out[r].cpu().numpy(), ref, rtol=2e-6, atol=1e-7)
+
+
+@pytest.mark.parametrize("dtype,hd", [("f32", 64), ("bf16", 128)])
+def test_rope_and_cache_append_values_and_block_indexing(dtype, hd):
+    H, Hkv, T, nblk = 4, 2, 5, 9
+    nqkv = (H + 2 * Hkv) * hd
+    qkv = gen.normal(5, 1, (T, nqkv))
+    pos = torch.tensor([0, 15, 16, 17, 4000], dtype=torch.int32)
+    slot = torch.tensor([0, 1, 1, 1, 2], dtype=torch.int32)
+    table = torch.full((3, 256), -1, dtype=torch.int32)
+    table[0, 0] = 4; table[1, 0] = 7; table[1, 1] = 2; table[2, 4000 // 16] = 5
+    pdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    pool = torch.full((nblk, 2, Hkv, 16, hd), 777.0, dtype=pdt, device=DEV)
+    cs = torch.empty(T, hd // 2, 2, device=DEV)
+    q = qkv.to(DEV).clone()
+    ld.ldk_rope_table(pos.to(DEV), hd, 10000.0, cs)
+    ld.ldk_rope_kv_write(q, cs, pos.to(DEV), slot.to(DEV), table.to(DEV), pool, H, Hkv, hd)
+    q, pool_h = q.cpu().numpy(), pool.float().cpu().numpy().astype(np.float64)
+    touched = np.zeros(pool_h.shape[:4], bool)
+    for t in range(T):
+        p = int(pos[t]); blk = int(table[slot[t], p // 16]); s = p % 16
+        for h in range(H):
+            ref = oracle.rope_head(qkv[t, h * hd:(h + 1) * hd].numpy(), p)
+            np.testing.assert_allclose(q[t, h * hd:(h + 1) * hd], ref, rtol=0, atol=4e-7 * np.abs(ref).max() + 1e-7)
+        for j in range(Hkv):
+            k = oracle.rope_head(qkv[t, (H + j) * hd:(H + j + 1) * hd].numpy(), p)
+            v = qkv[t, (H + Hkv + j) * hd:(H + Hkv + j + 1) * hd].double().numpy()
+            if dtype == "bf16":
+                np.testing.assert_array_equal(pool_h[blk, 1, j, s], oracle.round_bf16(v))      # v: exact rounding
+                # k is rotated in fp32 before rounding: equal to the oracle's rounding up to one bf16 step
+                kr = oracle.round_bf16(k)
+                assert np.all(np.abs(pool_h[blk, 0, j, s] - kr) <= np.abs(kr) * 2.0 ** -7 + 1e-30)
+                assert np.mean(pool_h[blk, 0, j, s] == kr) > 0.9
+            else:
+                np.testing.assert_array_equal(pool_h[blk, 1, j, s], v)
+                np.testing.assert_allclose(pool_h[blk, 0, j, s], k, rtol=0, atol=4e-7 * np.abs(k).max())
+            touched[blk, :, j, s] = True
+    assert np.all(pool_h[~touched] == 777.0), "a write landed outside the (block, slot) the table names"
+    assert touched.sum() == T * 2 * Hkv
+
+
+def _attention_case(seed, lens, H, Hkv, hd, dtype, spare=5):
+    B = len(lens)
+    nb = [(n + 15) // 16 for n in lens]
+    total = sum(nb) + spare
+    perm = gen.permutation(seed, 1, total).tolist()
+    table = torch.full((B, max(nb)), 0, dtype=torch.int32)
+    it = iter(perm)
+    for b in range(B):
+        for j in range(nb[b]):
+            table[b, j] = next(it)
+    pdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    pool = gen.normal(seed, 2, (total, 2, Hkv, 16, hd), device=DEV).to(pdt)
+    q = gen.normal(seed, 3, (B, H, hd), device=DEV)
+    return table, pool, q
+
+
+def _run_attention(table, pool, q, lens, H, Hkv, hd):
+    B = len(lens)
+    ctx = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    slot = torch.arange(B, dtype=torch.int32, device=DEV)
+    out = torch.empty(B, H, hd, device=DEV)
+    scratch = torch.empty(ld.ldk_attention_scratch_bytes(B, H, hd, max(lens)), dtype=torch.uint8, device=DEV)
+    ld.ldk_paged_attention(q, H * hd, pool, table.to(DEV), slot, ctx, max(lens), H, Hkv, hd, out, scratch)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def _oracle_attention(table, pool, q, lens, Hkv, hd, rows=None):
+    ph = oracle.to_host_matrix(pool.reshape(pool.shape[0], -1))
+    kp = ph.reshape(-1)
+    vp = kp[Hkv * 16 * hd:]                      # V half of each block starts Hkv*16*hd elements later
+    strides = (2 * Hkv * 16 * hd, 16 * hd, hd)
+    qh = q.cpu().numpy()
+    if rows is None:
+        return oracle.paged_attention(qh, kp, vp, strides, table.numpy(), lens, Hkv)
+    sel = np.array(rows)
+    return oracle.paged_attention(qh[sel], kp, vp, strides, table.numpy()[sel], [lens[r] for r in rows], Hkv)
+
+
+@pytest.mark.parametrize("dtype,hd,H,Hkv", [("bf16", 128, 4, 4), ("f32", 64, 4, 4), ("bf16", 128, 8, 2), ("f32", 128, 2, 1)])
+def test_paged_attention_edge_lengths(dtype, hd, H, Hkv):
+    lens = [1, 2, 15, 16, 17, 63, 255, 256, 257, 300, 1025]
+    table, pool, q = _attention_case(21, lens, H, Hkv, hd, dtype)
+    got = _run_attention(table, pool, q, lens, H, Hkv, hd)
+    ref = _oracle_attention(table, pool, q, lens, Hkv, hd)
+    assert np.max(np.abs(got - ref)) <= 2e-6 * np.abs(ref).max() + 1e-6
+    # ctx = 1 returns V of the single cached token
+    v0 = pool[table[0, 0], 1, :, 0, :].float().cpu().numpy()
+    for h in range(H):
+        np.testing.assert_allclose(got[0, h], v0[h // (H // Hkv)], rtol=1e-6, atol=1e-7)
+
+
+def test_paged_attention_microbench_shape_sampled():
+    """Batch 16, 32 heads x 128, contexts uniform in [256, 4096], permuted block table: every
+    (sequence, head) output of 4 sampled sequences against the oracle."""
+    lens = gen.randint(20240601, 1, 256, 4096, 16).tolist()
+    table, pool, q = _attention_case(20240601, lens, 32, 32, 128, "bf16")
+    got = _run_attention(table, pool, q, lens, 32, 32, 128)
+    assert np.isfinite(got).all()
+    rows = [0, 5, int(np.argmax(lens)), int(np.argmin(lens))]
+    ref = _oracle_attention(table, pool, q, lens, 32, 128, rows=rows)
+    err = np.max(np.abs(got[rows] - ref)) / np.abs(ref).max()
+    assert err <= 2e-5, err
+
+
+def test_argmax_ties_and_brute_force():
+    V = 32000
+    lg = gen.normal(6, 1, (5, V))
+    lg[1, [31999, 12, 700]] = 50.0
+    lg[2, :] = 1.5
+    lg[3, V - 1] = 60.0
+    out = torch.empty(5, dtype=torch.int32, device=DEV)
+    ld.ldk_argmax(lg.to(DEV), out)
+    ref = [oracle.argmax(lg[r].numpy()) for r in range(5)]
+    assert out.cpu().tolist() == ref and ref[1] == 12 and ref[2] == 0 and ref[3] == V - 1

@@ -1,0 +1,282 @@
+#!/usr/bin/env python3
+"""Decode throughput of the 7B-shaped bf16 decoder on one MI355X, tool-call pattern.
+
+Workload (batch 1): prompt of 1024 random token ids, then rounds of "greedily emit 256 tokens, append a
+128..512-token random observation through chunked prefill (chunk 256)".  A *step* is one ld_decode_step
+call: the whole decode pass (32 layers + LM head + argmax), the token hand-off to the host and the
+callback.  `value` is decode tokens/s over exactly --steps timed steps; prompt and observation prefills
+run between the timed steps and are reported beside it.  Inputs (weights, tokens) are seeded and
+synthetic and are resident in HBM before timing starts.
+
+Prints ONE JSON line.  `roofline` describes the kernel with the largest share of the step
+(HIP events bracketing every launch of a profiled tail of the same run); `cpu_baseline` is the CPU oracle
+timed on this machine's host cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12          # bytes/s, MI355X HBM3E
+ROUND_TOKENS = 256         # tokens emitted per round (1 by the preceding prefill + 255 decode steps)
+CHUNK = 256
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3 * (ROUND_TOKENS - 1))
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--profile-steps", type=int, default=32, help="extra steps run with per-kernel events")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-batch32", action="store_true", help="skip the batch-32 continuous-batching leg")
+    ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is NOT the benchmark)")
+    return ap.parse_args()
+
+
+def noop_cb(seq, tok, pos):
+    return 0
+
+
+def cpu_baseline(shape, weights, ctx, steps, seed):
+    """The oracle, as it stands, on the host cores: `steps` decode steps at context `ctx` over an injected
+    synthetic KV history (values do not change the work done)."""
+    import numpy as np
+    import oracle
+    from workloads import gen
+    om = oracle.Model(shape, weights)
+    nblk = (ctx + steps + 16) // 16 + 1
+    okv = oracle.KV(om, nblk, 1, nblk)
+    rc, s = okv.alloc(0)
+    hist = gen.normal(seed, 900, (ctx, shape.n_layers, 2, shape.n_kv_heads, shape.head_dim)).bfloat16().double().numpy()
+    assert okv.inject(s, hist, pending=1) == 0
+    del hist
+    okv.decode(s, want_logits=False)          # one untimed step: page in the weights
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        rc, tok, _ = okv.decode(s, want_logits=False)
+        assert rc == 0
+    dt = time.perf_counter() - t0
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": steps / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"{steps} decode steps of the same 7B bf16 decoder at context {ctx} (injected KV history), "
+                      f"batch 1; {dt:.1f} s of CPU work"}
+
+
+def run_batch1(args, ld, torch, shape, weights, model):
+    import numpy as np
+    from workloads import gen, SEED_BASE
+    seed = SEED_BASE + 2
+    K, W = args.steps, args.warmup
+    rounds = max(1, -(-K // (ROUND_TOKENS - 1)))
+    max_ctx = 1024 + rounds * (ROUND_TOKENS + 513) + args.profile_steps + 64
+    nblk_seq = -(-max_ctx // 16)
+    kv = ld.KV(model, nblk_seq + 16, CHUNK, 2, nblk_seq)
+    stream = torch.cuda.current_stream()
+
+    # warm-up on a throw-away sequence
+    ws = ld.ld_kv_alloc(kv.h, 0)
+    ld.ld_prefill(kv.h, ws, gen.randint(seed, 90, 0, shape.vocab - 1, 64).numpy().astype(np.int32), stream, noop_cb)
+    for _ in range(W):
+        ld.ld_decode_step(kv.h, [ws], stream, noop_cb)
+    ld.ld_kv_free(kv.h, ws)
+
+    s = ld.ld_kv_alloc(kv.h, 0)
+    prompt = gen.randint(seed, 100, 0, shape.vocab - 1, 1024).numpy().astype(np.int32)
+    obs_len = gen.randint(seed, 101, 128, 512, rounds).tolist()
+    torch.cuda.synchronize()
+    pf_tokens, pf_time = 0, 0.0
+    t0 = time.perf_counter()
+    ld.ld_prefill(kv.h, s, prompt, stream, noop_cb)
+    pf_time += time.perf_counter() - t0; pf_tokens += prompt.size
+
+    step_ms, step_bytes = [], []
+    Wb, kappa = shape.weight_bytes_per_step, shape.kv_bytes_per_token
+    done = 0
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for r in range(rounds):
+        n = min(ROUND_TOKENS - 1, K - done)
+        for _ in range(n):
+            ctx = ld.ld_kv_len(kv.h, s) + 1
+            t0 = time.perf_counter()
+            ld.ld_decode_step(kv.h, [s], stream, noop_cb)
+            step_ms.append((time.perf_counter() - t0) * 1e3)
+            step_bytes.append(Wb + ctx * kappa)
+        done += n
+        if done >= K and r == rounds - 1 and n < ROUND_TOKENS - 1:
+            break
+        obs = gen.randint(seed, 200 + r, 0, shape.vocab - 1, obs_len[r]).numpy().astype(np.int32)
+        t0 = time.perf_counter()
+        ld.ld_prefill(kv.h, s, obs, stream, noop_cb)
+        pf_time += time.perf_counter() - t0; pf_tokens += obs.size + 1
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_begin
+    assert len(step_ms) == K
+    dec_s = sum(step_ms) / 1e3
+
+    # per-kernel durations: a profiled tail of the same run
+    ld.ld_kv_profile(kv.h, True)
+    ctx_prof = ld.ld_kv_len(kv.h, s) + 1
+    for _ in range(args.profile_steps):
+        ld.ld_decode_step(kv.h, [s], stream, noop_cb)
+    prof = ld.ld_kv_profile_read(kv.h)
+    ld.ld_kv_profile(kv.h, False)
+    e = 2
+    d, f, V = shape.d_model, shape.d_ffn, shape.vocab
+    nqkv = (shape.n_heads + 2 * shape.n_kv_heads) * shape.head_dim
+    alg_bytes = {   # algorithmic bytes per launch: the matrix once, input row(s), gain, output row(s)
+        "qkv": nqkv * d * e + d * 4 * 2 + nqkv * 4,
+        "wo": d * d * e + d * 4 * 3,
+        "gate_up": 2 * f * d * e + d * 4 * 2 + f * 4,
+        "down": d * f * e + f * 4 + d * 4 * 2,
+        "lm_head": V * d * e + d * 4 + V * 4,
+        "attention": (ctx_prof + args.profile_steps // 2) * 2 * shape.n_kv_heads * shape.head_dim * e,
+    }
+    kernels = {}
+    for name, (ms, n) in prof.items():
+        if n:
+            avg = ms / n
+            kernels[name] = {"avg_us": round(avg * 1e3, 2), "launches_per_step": n // args.profile_steps}
+            if name in alg_bytes:
+                kernels[name]["GBps"] = round(alg_bytes[name] / (avg * 1e-3) / 1e9, 1)
+    per_step_ms = {k: v[0] / args.profile_steps for k, v in prof.items()}
+    dominant = max((k for k in per_step_ms if k in alg_bytes), key=lambda k: per_step_ms[k])
+    avg_s = prof[dominant][0] / prof[dominant][1] * 1e-3
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(alg_bytes[dominant] / avg_s / 1e9, 1),
+                "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": round(alg_bytes[dominant] / avg_s / HBM_PEAK, 4),
+                "traffic": None, "avg_launch_us": round(avg_s * 1e6, 2), "bytes_per_launch": alg_bytes[dominant]}
+    out = {
+        "value": K / dec_s, "ms_per_step": statistics.mean(step_ms),
+        "ms_per_step_median": statistics.median(step_ms),
+        "ms_per_step_std": statistics.pstdev(step_ms),
+        "step_hbm_GBps": round(sum(step_bytes) / dec_s / 1e9, 1),
+        "step_hbm_frac": round(sum(step_bytes) / dec_s / HBM_PEAK, 4),
+        "prefill_tokens_per_s": round(pf_tokens / pf_time, 1), "prefill_tokens": pf_tokens,
+        "scenario_s": round(t_total, 3), "final_context": int(ld.ld_kv_len(kv.h, s)),
+        "kernel_sum_ms_per_step": round(sum(per_step_ms.values()), 4),
+        "kernels": kernels, "roofline": roofline,
+    }
+    kv.close()
+    return out
+
+
+def run_batch32(args, ld, torch, shape, model):
+    """Continuous batching at batch 32: contexts uniform in [512, 8192] (synthetic KV history written
+    straight into the pool), 128 steps; every 16th step 4 random sequences get a 256-token observation
+    chunk prefilled in the same pass."""
+    import numpy as np
+    from workloads import gen, SEED_BASE
+    seed = SEED_BASE + 3
+    B, steps = 32, 128
+    lens = gen.randint(seed, 1, 512, 8192, B).tolist()
+    max_ctx = max(lens) + steps + 8 * 257 + 16
+    nblk_seq = -(-max_ctx // 16)
+    total_blocks = sum(-(-(n + steps + 8 * 257) // 16) for n in lens) + 64
+    T_max = (B - 4) + 4 * 257
+    pdt = torch.bfloat16
+    pool = torch.empty((shape.n_layers, total_blocks, 2, shape.n_kv_heads, 16, shape.head_dim), dtype=pdt, device="cuda")
+    for l in range(shape.n_layers):       # N(0,1) history, one layer at a time
+        pool[l] = gen.normal(seed, 1000 + l, tuple(pool[l].shape), device="cuda").to(pdt)
+    kv = ld.KV(model, total_blocks, T_max, B, nblk_seq, pool=pool)
+    stream = torch.cuda.current_stream()
+    seqs = []
+    for b in range(B):
+        s = ld.ld_kv_alloc(kv.h, 0)
+        ld.ld_kv_assume(kv.h, s, lens[b], pending=int(gen.randint(seed, 2, 0, shape.vocab - 1, B)[b]))
+        seqs.append(s)
+    for _ in range(3):                    # warm-up steps (they advance every context by one token)
+        ld.ld_decode_step(kv.h, seqs, stream, noop_cb)
+    torch.cuda.synchronize()
+    pure_ms, mixed_ms, pure_bytes = [], [], []
+    Wb, kappa = shape.weight_bytes_per_step, shape.kv_bytes_per_token
+    t_begin = time.perf_counter()
+    for step in range(1, steps + 1):
+        sum_ctx = sum(ld.ld_kv_len(kv.h, s) + 1 for s in seqs)
+        if step % 16 == 0:
+            pick = gen.permutation(seed, 3000 + step, B)[:4].tolist()
+            pf = [seqs[i] for i in pick]
+            dec = [s for s in seqs if s not in pf]
+            obs = [gen.randint(seed, 4000 + step * 8 + i, 0, shape.vocab - 1, 256).numpy().astype(np.int32) for i in range(4)]
+            t0 = time.perf_counter()
+            ld.ld_step_mixed(kv.h, dec, pf, obs, stream, noop_cb)
+            mixed_ms.append((time.perf_counter() - t0) * 1e3)
+        else:
+            t0 = time.perf_counter()
+            ld.ld_decode_step(kv.h, seqs, stream, noop_cb)
+            pure_ms.append((time.perf_counter() - t0) * 1e3)
+            pure_bytes.append(Wb + sum_ctx * kappa)
+    torch.cuda.synchronize()
+    total = time.perf_counter() - t_begin
+    ld.ld_kv_profile(kv.h, True)
+    for _ in range(4):
+        ld.ld_decode_step(kv.h, seqs, stream, noop_cb)
+    prof = ld.ld_kv_profile_read(kv.h)
+    ld.ld_kv_profile(kv.h, False)
+    sum_ctx = sum(ld.ld_kv_len(kv.h, s) for s in seqs)
+    att_bytes = sum_ctx * 2 * shape.n_kv_heads * shape.head_dim * 2
+    att_avg = prof["attention"][0] / max(prof["attention"][1], 1) * 1e-3
+    out = {
+        "workload": "7B-shaped bf16 decoder, continuous batching at batch 32, contexts U[512,8192], 128 steps, "
+                    "4 sequences get a 256-token observation chunk every 16th step",
+        "decode_tokens_per_s": round(B * len(pure_ms) / (sum(pure_ms) / 1e3), 1),
+        "ms_per_pure_decode_step": round(statistics.mean(pure_ms), 3),
+        "ms_per_mixed_step": round(statistics.mean(mixed_ms), 3),
+        "rows_per_mixed_step": (B - 4) + 4 * 257,
+        "all_tokens_per_s": round((B * steps + 8 * 4 * 256) / total, 1),
+        "step_hbm_frac": round(sum(pure_bytes) / (sum(pure_ms) / 1e3) / HBM_PEAK, 4),
+        "attention_avg_us": round(att_avg * 1e6, 1),
+        "attention_GBps": round(att_bytes / att_avg / 1e9, 1),
+        "attention_hbm_frac": round(att_bytes / att_avg / HBM_PEAK, 4),
+        "kernel_ms_per_step": {k: round(v[0] / 4, 4) for k, v in prof.items()},
+        "sum_context": int(sum_ctx),
+    }
+    kv.close()
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2406_00059_amd as ld
+    from workloads import LLAMA7B, SEED_BASE, make_weights
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    ld.lib()
+    shape = LLAMA7B if not args.layers else LLAMA7B.with_layers(args.layers)
+    torch.cuda.set_device(0)
+    weights = make_weights(shape, SEED_BASE + 2, device="cuda")
+    model = ld.Model(shape, weights, max_chunk=CHUNK)
+
+    res = run_batch1(args, ld, torch, shape, weights, model)
+    b32 = None if args.no_batch32 else run_batch32(args, ld, torch, shape, model)
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(shape, weights, ctx=1024, steps=160, seed=SEED_BASE + 2)
+
+    line = {
+        "metric": "decode tokens/sec + % peak HBM BW, 7B-shape bf16 at batch 1 and 32, 1 MI355X",
+        "value": round(res.pop("value"), 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(res.pop("ms_per_step"), 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "7B-shaped bf16 decoder (32 layers, d 4096, 32x128 heads, FFN 11008, vocab 32000), "
+                               "batch 1, tool-call pattern: prompt 1024, rounds of 256 greedy tokens + 128-512-token "
+                               "observation via chunked prefill (chunk 256); value = decode steps only",
+                   "n_layers": shape.n_layers, "kv_block": 16, "chunk": CHUNK},
+        "roofline": res.pop("roofline"),
+        "cpu_baseline": cpu,
+        "batch1": res,
+        "batch32": b32,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -19,7 +19,7 @@ __all__ = [
     "LDK_STORE", "LDK_ADD", "LDK_SWIGLU", "LIB_PATH", "lib", "LdError", "ld_model_config", "ld_weights",
     "ld_token_cb", "ld_model_create", "ld_model_destroy", "ld_kv_bytes", "ld_workspace_bytes", "ld_kv_create",
     "ld_kv_destroy", "ld_kv_alloc", "ld_kv_map", "ld_kv_free", "ld_kv_block_table", "ld_kv_len",
-    "ld_kv_free_blocks", "ld_kv_assume", "ld_prefill", "ld_decode_step", "ld_step_mixed", "ld_last_error",
+    "ld_kv_free_blocks", "ld_kv_assume", "ld_prefill", "ld_decode_step", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
     "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_rope_table", "ldk_rope_kv_write",
     "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_argmax", "Model", "KV",
 ]
@@ -45,6 +45,13 @@ class ld_weights(C.Structure):
                 ("wgate_up", C.POINTER(C.c_void_p)), ("wdown", C.POINTER(C.c_void_p))]
 
 
+LD_PROF_NAMES = ("qkv", "rope_kv", "attention", "wo", "gate_up", "down", "lm_head", "other")
+
+
+class ld_profile(C.Structure):
+    _fields_ = [("ms", C.c_double * 8), ("launches", C.c_int64 * 8)]
+
+
 ld_token_cb = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int32, C.c_int32, C.c_int32)
 
 _lib = None
@@ -68,6 +75,8 @@ _SIGS = {
     "ld_decode_step": (C.c_int, [_vp, _i32p, C.c_int32, _vp, ld_token_cb, _vp, _f32p]),
     "ld_step_mixed": (C.c_int, [_vp, _i32p, C.c_int32, _i32p, C.POINTER(_i32p), _i32p, C.c_int32, _vp,
                                 ld_token_cb, _vp, _f32p]),
+    "ld_kv_profile": (C.c_int, [_vp, C.c_int32]),
+    "ld_kv_profile_read": (C.c_int, [_vp, _vp]),
     "ld_last_error": (C.c_char_p, []),
     "ldk_embed": (C.c_int, [_vp, C.c_int32, _vp, C.c_int32, C.c_int32, _vp, _vp]),
     "ldk_rmsnorm": (C.c_int, [_vp, _vp, _vp, C.c_int32, C.c_int32, C.c_float, _vp, _vp]),
@@ -237,6 +246,17 @@ def ld_step_mixed(kv, dec, pf, pf_tokens, stream=None, callback=None, logits_voc
     cb = _cb(callback)
     rc = _check(lib().ld_step_mixed(kv, dp, d.size, pp, ptrs, np_, p.size, _stream(stream), cb, None, lp), check)
     return rc, lg
+
+
+def ld_kv_profile(kv, enable):
+    _check(lib().ld_kv_profile(kv, 1 if enable else 0))
+
+
+def ld_kv_profile_read(kv):
+    """{category: (total ms, launches)}"""
+    p = ld_profile()
+    _check(lib().ld_kv_profile_read(kv, C.addressof(p)))
+    return {n: (p.ms[i], p.launches[i]) for i, n in enumerate(LD_PROF_NAMES)}
 
 
 # ------------------------------------------------------------------ kernel-level calls (device tensors)

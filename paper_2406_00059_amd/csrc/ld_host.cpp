@@ -99,6 +99,11 @@ struct ld_kv {
     std::vector<int32_t> table;  // host copy [max_seqs][max_blocks], -1 = unmapped
     // pinned staging, created by the first pass
     int32_t *pin_meta = nullptr, *pin_out = nullptr, *pin_table = nullptr;
+    // optional per-kernel timing
+    bool prof_on = false;
+    ld_profile prof{};
+    std::vector<hipEvent_t> prof_ev;       // pairs (start, stop)
+    std::vector<int> prof_cat;             // category of pair i in the current pass
     int32_t *trow(int s) { return table.data() + (size_t)s * max_blocks; }
     const int32_t *trow(int s) const { return table.data() + (size_t)s * max_blocks; }
 };
@@ -182,29 +187,55 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, const std::vector<in
     }
 
 #define LD_TRY(call) do { ld_status s_ = (call); if (s_ != LD_OK) return s_; } while (0)
+    // With profiling on, bracket the launch with an event pair of the given category.
+    kv->prof_cat.clear();
+#define LD_TIMED(cat, call)                                                                   \
+    do {                                                                                      \
+        if (kv->prof_on) {                                                                    \
+            const size_t i_ = kv->prof_cat.size();                                            \
+            while (kv->prof_ev.size() < 2 * (i_ + 1)) {                                       \
+                hipEvent_t ev_;                                                               \
+                LD_HIP_TRY(hipEventCreate(&ev_));                                              \
+                kv->prof_ev.push_back(ev_);                                                    \
+            }                                                                                 \
+            LD_HIP_TRY(hipEventRecord(kv->prof_ev[2 * i_], st));                              \
+            LD_TRY(call);                                                                     \
+            LD_HIP_TRY(hipEventRecord(kv->prof_ev[2 * i_ + 1], st));                          \
+            kv->prof_cat.push_back(cat);                                                      \
+        } else {                                                                              \
+            LD_TRY(call);                                                                     \
+        }                                                                                     \
+    } while (0)
     const int d = c.d_model, nq = m.nq(), nqkv = m.nqkv(), H = c.n_heads, Hkv = c.n_kv_heads, hd = c.head_dim;
     const size_t layer_bytes = (size_t)kv->n_blocks * m.block_elems() * m.elem();
-    LD_TRY(ldk_embed(m.embed, c.dtype, d_tok, T, d, w.x, st));
-    LD_TRY(ldk_rope_table(d_pos, T, hd, c.rope_base, w.cos_sin, st));
+    LD_TIMED(LD_PROF_OTHER, ldk_embed(m.embed, c.dtype, d_tok, T, d, w.x, st));
+    LD_TIMED(LD_PROF_OTHER, ldk_rope_table(d_pos, T, hd, c.rope_base, w.cos_sin, st));
     for (int l = 0; l < c.n_layers; l++) {
         void *pool_l = kv->pool + (size_t)l * layer_bytes;
-        LD_TRY(ldk_linear(m.wqkv[l], c.dtype, w.x, m.attn_norm[l], c.rms_eps, T, nqkv, d, LDK_STORE, w.qkv, st));
-        LD_TRY(ldk_rope_kv_write(w.qkv, w.cos_sin, d_pos, d_slot, w.table, kv->max_blocks, pool_l, c.dtype, T, H,
+        LD_TIMED(LD_PROF_QKV, ldk_linear(m.wqkv[l], c.dtype, w.x, m.attn_norm[l], c.rms_eps, T, nqkv, d, LDK_STORE, w.qkv, st));
+        LD_TIMED(LD_PROF_ROPE_KV, ldk_rope_kv_write(w.qkv, w.cos_sin, d_pos, d_slot, w.table, kv->max_blocks, pool_l, c.dtype, T, H,
                                  Hkv, hd, st));
-        LD_TRY(ldk_paged_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot, d_ctx, max_ctx, T,
+        LD_TIMED(LD_PROF_ATTENTION, ldk_paged_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot, d_ctx, max_ctx, T,
                                    H, Hkv, hd, w.attn, w.att_scratch, w.att_scratch_bytes, st));
-        LD_TRY(ldk_linear(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, st));
-        LD_TRY(ldk_linear(m.wgate_up[l], c.dtype, w.x, m.ffn_norm[l], c.rms_eps, T, c.d_ffn, d, LDK_SWIGLU, w.act, st));
-        LD_TRY(ldk_linear(m.wdown[l], c.dtype, w.act, nullptr, 0.f, T, d, c.d_ffn, LDK_ADD, w.x, st));
+        LD_TIMED(LD_PROF_WO, ldk_linear(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, st));
+        LD_TIMED(LD_PROF_GATE_UP, ldk_linear(m.wgate_up[l], c.dtype, w.x, m.ffn_norm[l], c.rms_eps, T, c.d_ffn, d, LDK_SWIGLU, w.act, st));
+        LD_TIMED(LD_PROF_DOWN, ldk_linear(m.wdown[l], c.dtype, w.act, nullptr, 0.f, T, d, c.d_ffn, LDK_ADD, w.x, st));
     }
-    LD_TRY(ldk_rmsnorm(w.x, m.final_norm, d_emit, R, d, c.rms_eps, w.hn, st));
-    LD_TRY(ldk_linear(m.lm_head, c.dtype, w.hn, nullptr, 0.f, R, c.vocab, d, LDK_STORE, w.logits, st));
-    LD_TRY(ldk_argmax(w.logits, R, c.vocab, w.out_tok, st));
+    LD_TIMED(LD_PROF_OTHER, ldk_rmsnorm(w.x, m.final_norm, d_emit, R, d, c.rms_eps, w.hn, st));
+    LD_TIMED(LD_PROF_LM_HEAD, ldk_linear(m.lm_head, c.dtype, w.hn, nullptr, 0.f, R, c.vocab, d, LDK_STORE, w.logits, st));
+    LD_TIMED(LD_PROF_OTHER, ldk_argmax(w.logits, R, c.vocab, w.out_tok, st));
+#undef LD_TIMED
 #undef LD_TRY
     if (R) LD_HIP_TRY(hipMemcpyAsync(kv->pin_out, w.out_tok, (size_t)R * 4, hipMemcpyDeviceToHost, st));
     if (logits_out && R)
         LD_HIP_TRY(hipMemcpyAsync(logits_out, w.logits, (size_t)R * c.vocab * 4, hipMemcpyDeviceToHost, st));
     LD_HIP_TRY(hipStreamSynchronize(st));
+    for (size_t i = 0; i < kv->prof_cat.size(); i++) {
+        float ms = 0.f;
+        LD_HIP_TRY(hipEventElapsedTime(&ms, kv->prof_ev[2 * i], kv->prof_ev[2 * i + 1]));
+        kv->prof.ms[kv->prof_cat[i]] += ms;
+        kv->prof.launches[kv->prof_cat[i]] += 1;
+    }
     return LD_OK;
 }
 
@@ -343,6 +374,7 @@ void ld_kv_destroy(ld_kv *kv) {
     if (kv->pin_meta) (void)hipHostFree(kv->pin_meta);
     if (kv->pin_out) (void)hipHostFree(kv->pin_out);
     if (kv->pin_table) (void)hipHostFree(kv->pin_table);
+    for (hipEvent_t e : kv->prof_ev) (void)hipEventDestroy(e);
     delete kv;
 }
 
@@ -412,6 +444,19 @@ ld_status ld_kv_assume(ld_kv *kv, ld_seq seq, int64_t n_tokens, int32_t pending)
     map_blocks(kv, seq, need);
     q->n_cached += n_tokens;
     if (pending >= 0) { q->pending = pending; q->has_pending = true; }
+    return LD_OK;
+}
+
+ld_status ld_kv_profile(ld_kv *kv, int32_t enable) {
+    if (!kv) return fail(LD_E_INVAL, "ld_kv_profile: null kv");
+    kv->prof_on = enable != 0;
+    if (enable) kv->prof = ld_profile{};
+    return LD_OK;
+}
+
+ld_status ld_kv_profile_read(const ld_kv *kv, ld_profile *out) {
+    if (!kv || !out) return fail(LD_E_INVAL, "ld_kv_profile_read: null argument");
+    *out = kv->prof;
     return LD_OK;
 }
 

@@ -53,6 +53,15 @@ ld_status ldk_rope_kv_write(float *qkv, const float *cos_sin, const int32_t *pos
                             const int32_t *table, int32_t table_stride, void *pool_layer, int32_t dtype, int32_t T,
                             int32_t H, int32_t Hkv, int32_t hd, void *stream);
 
+/* Fused projection + rotary embedding + cache append: qkv[t, :] = W rmsnorm(x[t, :]; g, eps) with
+ * W [(H + 2 Hkv) hd, K] (g == NULL: no normalisation), then exactly what ldk_rope_kv_write does.
+ * On return the q part of qkv (first H hd floats of each row) is rotated; the k and v parts of qkv
+ * are unspecified (their values are in the pool).  x [T, K], qkv [T, (H + 2 Hkv) hd]. */
+ld_status ldk_qkv_rope(const void *W, int32_t dtype, const float *x, const float *g, float eps, float *qkv,
+                       const float *cos_sin, const int32_t *pos, const int32_t *seq_slot, const int32_t *table,
+                       int32_t table_stride, void *pool_layer, int32_t T, int32_t K, int32_t H, int32_t Hkv, int32_t hd,
+                       void *stream);
+
 /* Scratch bytes ldk_paged_attention needs for T rows with contexts up to max_ctx. */
 size_t ldk_attention_scratch_bytes(int32_t T, int32_t H, int32_t hd, int32_t max_ctx);
 

@@ -20,7 +20,7 @@ __all__ = [
     "ld_token_cb", "ld_model_create", "ld_model_destroy", "ld_kv_bytes", "ld_workspace_bytes", "ld_kv_create",
     "ld_kv_destroy", "ld_kv_alloc", "ld_kv_map", "ld_kv_free", "ld_kv_block_table", "ld_kv_len",
     "ld_kv_free_blocks", "ld_kv_assume", "ld_prefill", "ld_decode_step", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
-    "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_rope_table", "ldk_rope_kv_write",
+    "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
     "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_argmax", "Model", "KV",
 ]
 
@@ -84,6 +84,8 @@ _SIGS = {
     "ldk_rope_table": (C.c_int, [_vp, C.c_int32, C.c_int32, C.c_float, _vp, _vp]),
     "ldk_rope_kv_write": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_int32, _vp, C.c_int32, C.c_int32, C.c_int32,
                                     C.c_int32, C.c_int32, _vp]),
+    "ldk_qkv_rope": (C.c_int, [_vp, C.c_int32, _vp, _vp, C.c_float, _vp, _vp, _vp, _vp, _vp, C.c_int32, _vp,
+                               C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp]),
     "ldk_attention_scratch_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "ldk_paged_attention": (C.c_int, [_vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, _vp, _vp, C.c_int32,
                                       C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, C.c_size_t, _vp]),
@@ -290,6 +292,13 @@ def ldk_rope_kv_write(qkv, cos_sin, pos, seq_slot, table, pool_layer, H, Hkv, hd
     _check(lib().ldk_rope_kv_write(_ptr(qkv), _ptr(cos_sin), _ptr(pos), _ptr(seq_slot), _ptr(table),
                                    table.shape[1], _ptr(pool_layer), _dt(pool_layer.dtype), qkv.shape[0], H, Hkv,
                                    hd, _stream(stream)))
+
+
+def ldk_qkv_rope(W, x, qkv, cos_sin, pos, seq_slot, table, pool_layer, H, Hkv, hd, g=None, eps=0.0, stream=None):
+    T, K = x.shape
+    _check(lib().ldk_qkv_rope(_ptr(W), _dt(W.dtype), _ptr(x), _ptr(g), eps, _ptr(qkv), _ptr(cos_sin), _ptr(pos),
+                              _ptr(seq_slot), _ptr(table), table.shape[1], _ptr(pool_layer), T, K, H, Hkv, hd,
+                              _stream(stream)))
 
 
 def ldk_attention_scratch_bytes(T, H, hd, max_ctx):

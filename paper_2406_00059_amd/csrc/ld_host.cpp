@@ -77,7 +77,10 @@ Workspace plan_workspace(const ld_model &m, char *base, int max_tokens, int max_
     w.hn = (float *)take((size_t)max_seqs * c.d_model * 4);
     w.logits = (float *)take((size_t)max_seqs * c.vocab * 4);
     w.cos_sin = (float *)take(T * c.head_dim * 4);
-    w.att_scratch_bytes = ldk_attention_scratch_bytes(max_tokens, c.n_heads, c.head_dim, max_blocks * c.kv_block);
+    w.att_scratch_bytes = 0;   // the chunking depends on the row count: size for the worst one
+    for (int t = 1; t <= max_tokens; t++)
+        w.att_scratch_bytes = std::max(w.att_scratch_bytes,
+                                       ldk_attention_scratch_bytes(t, c.n_heads, c.head_dim, max_blocks * c.kv_block));
     w.att_scratch = take(w.att_scratch_bytes);
     w.total = off;
     return w;
@@ -212,9 +215,8 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, const std::vector<in
     LD_TIMED(LD_PROF_OTHER, ldk_rope_table(d_pos, T, hd, c.rope_base, w.cos_sin, st));
     for (int l = 0; l < c.n_layers; l++) {
         void *pool_l = kv->pool + (size_t)l * layer_bytes;
-        LD_TIMED(LD_PROF_QKV, ldk_linear(m.wqkv[l], c.dtype, w.x, m.attn_norm[l], c.rms_eps, T, nqkv, d, LDK_STORE, w.qkv, st));
-        LD_TIMED(LD_PROF_ROPE_KV, ldk_rope_kv_write(w.qkv, w.cos_sin, d_pos, d_slot, w.table, kv->max_blocks, pool_l, c.dtype, T, H,
-                                 Hkv, hd, st));
+        LD_TIMED(LD_PROF_QKV, ldk_qkv_rope(m.wqkv[l], c.dtype, w.x, m.attn_norm[l], c.rms_eps, w.qkv, w.cos_sin, d_pos,
+                                           d_slot, w.table, kv->max_blocks, pool_l, T, d, H, Hkv, hd, st));
         LD_TIMED(LD_PROF_ATTENTION, ldk_paged_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot, d_ctx, max_ctx, T,
                                    H, Hkv, hd, w.attn, w.att_scratch, w.att_scratch_bytes, st));
         LD_TIMED(LD_PROF_WO, ldk_linear(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, st));

@@ -3,53 +3,15 @@
 // Numerical scheme: activations, accumulators, softmax statistics and logits are float32;
 // matrices and the KV pool are float32 or bf16.  bf16 -> float32 widening is exact.
 #include "ld_internal.h"
+#include "ld_device.h"
+#include "ld_gemv.h"
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 
+using namespace ldd;
+
 namespace {
-
-constexpr int WAVE = 64;
-typedef uint16_t bf16_t;
-
-// ---------------------------------------------------------------- element helpers
-
-__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
-
-// float32 -> bf16, round to nearest even.
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);  // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
-}
-
-// Load 8 consecutive elements (16-byte aligned for bf16, 32-byte for float) as floats.
-__device__ __forceinline__ void load8(const bf16_t *p, float (&v)[8]) {
-    const uint4 u = *reinterpret_cast<const uint4 *>(p);
-    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-        v[2 * i] = __uint_as_float(w[i] << 16);
-        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-    }
-}
-__device__ __forceinline__ void load8(const float *p, float (&v)[8]) {
-    const float4 a = reinterpret_cast<const float4 *>(p)[0];
-    const float4 b = reinterpret_cast<const float4 *>(p)[1];
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
-    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
-
-__device__ __forceinline__ void store_elem(float *p, float v) { *p = v; }
-__device__ __forceinline__ void store_elem(bf16_t *p, float v) { *p = f32_to_bf16(v); }
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
-    return v;
-}
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---------------------------------------------------------------- embedding gather
 
@@ -221,7 +183,7 @@ __global__ void k_rope_kv_write(float *__restrict__ qkv, const float2 *__restric
 // lane group keeps its own online-softmax state (m, l, acc) in the log2 domain, merged across
 // groups, waves and finally chunks.
 
-constexpr int ATT_CB = 16;  // KV blocks per chunk (256 tokens)
+// KV blocks per chunk: a multiple of 4 (one per wave), chosen per launch by attn_chunk_blocks().
 
 template <int HD, typename KVT>
 __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ q, int q_stride,
@@ -229,7 +191,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
                                                       const int32_t *__restrict__ table, int table_stride,
                                                       const int32_t *__restrict__ seq_slot,
                                                       const int32_t *__restrict__ ctx_len, int H,
-                                                      float scale_log2e, int max_chunks,
+                                                      float scale_log2e, int max_chunks, int cb,
                                                       float *__restrict__ part_o, float *__restrict__ part_ml) {
     constexpr int LPT = HD / 8;      // lanes per token
     constexpr int TPI = WAVE / LPT;  // tokens per load instruction
@@ -237,9 +199,9 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
     const int c = blockIdx.x, h = blockIdx.y, t = blockIdx.z;
     const int ctx = ctx_len[t];
     const int nblk = (ctx + 15) >> 4;
-    const int b_begin = c * ATT_CB;
+    const int b_begin = c * cb;
     if (b_begin >= nblk) return;
-    const int b_end = min(b_begin + ATT_CB, nblk);
+    const int b_end = min(b_begin + cb, nblk);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int group = lane / LPT, sub = lane % LPT;
     const int kvh = h / (H / Hkv);
@@ -335,9 +297,10 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
 
 template <int HD>
 __global__ void k_attn_merge(const float *__restrict__ part_o, const float *__restrict__ part_ml,
-                             const int32_t *__restrict__ ctx_len, int H, int max_chunks, float *__restrict__ out) {
+                             const int32_t *__restrict__ ctx_len, int H, int max_chunks, int cb,
+                             float *__restrict__ out) {
     const int h = blockIdx.x, t = blockIdx.y, d = threadIdx.x;
-    const int nch = ((ctx_len[t] + 15) / 16 + ATT_CB - 1) / ATT_CB;
+    const int nch = ((ctx_len[t] + 15) / 16 + cb - 1) / cb;
     const int64_t base = ((int64_t)t * H + h) * max_chunks;
     float M = -INFINITY;
     for (int c = 0; c < nch; c++) M = fmaxf(M, part_ml[(base + c) * 2]);
@@ -449,6 +412,10 @@ ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *
         return ld::fail(LD_E_INVAL, "ldk_linear: bad argument (K must be a multiple of 8)");
     if (T == 0) return LD_OK;
     hipStream_t s = (hipStream_t)stream;
+    if (dtype == LD_BF16 && T == 1 && ld::gemv1_supported(N, K, epilogue)) {
+        ld::launch_gemv1((const bf16_t *)W, x, g, eps, N, K, epilogue, y, nullptr, s);
+        return launched("k_gemv1");
+    }
     if (dtype == LD_BF16) {
         if (g) launch_linear<bf16_t, true>((const bf16_t *)W, x, g, eps, T, N, K, epilogue, y, s);
         else launch_linear<bf16_t, false>((const bf16_t *)W, x, g, eps, T, N, K, epilogue, y, s);
@@ -488,11 +455,41 @@ ld_status ldk_rope_kv_write(float *qkv, const float *cos_sin, const int32_t *pos
     return launched("k_rope_kv_write");
 }
 
-static int attn_max_chunks(int max_ctx) { return ((max_ctx + 15) / 16 + ATT_CB - 1) / ATT_CB; }
+ld_status ldk_qkv_rope(const void *W, int32_t dtype, const float *x, const float *g, float eps, float *qkv,
+                       const float *cos_sin, const int32_t *pos, const int32_t *seq_slot, const int32_t *table,
+                       int32_t table_stride, void *pool_layer, int32_t T, int32_t K, int32_t H, int32_t Hkv, int32_t hd,
+                       void *stream) {
+    if (!W || !x || !qkv || !cos_sin || !pos || !seq_slot || !table || !pool_layer || T < 0 || H <= 0 || Hkv <= 0 ||
+        H % Hkv || (hd != 64 && hd != 128) || K <= 0 || K % 8)
+        return ld::fail(LD_E_INVAL, "ldk_qkv_rope: bad argument");
+    if (T == 0) return LD_OK;
+    const int N = (H + 2 * Hkv) * hd;
+    if (dtype == LD_BF16 && T == 1 && ld::gemv1_supported(N, K, ld::GEMV_ROPE_KV)) {
+        ld::RopeKvArgs rk{(const float2 *)cos_sin, pos, seq_slot, table, table_stride, (bf16_t *)pool_layer, H, Hkv, hd};
+        ld::launch_gemv1((const bf16_t *)W, x, g, eps, N, K, ld::GEMV_ROPE_KV, qkv, &rk, (hipStream_t)stream);
+        return launched("k_gemv1 (rope + cache append)");
+    }
+    ld_status rc = ldk_linear(W, dtype, x, g, eps, T, N, K, LDK_STORE, qkv, stream);
+    if (rc != LD_OK) return rc;
+    return ldk_rope_kv_write(qkv, cos_sin, pos, seq_slot, table, table_stride, pool_layer, dtype, T, H, Hkv, hd, stream);
+}
+
+// Chunk size in KV blocks: small chunks when few (row, head) pairs exist, so that the launch still has
+// a few thousand workgroups; at most 64 blocks (1024 tokens) per chunk.
+static int attn_chunk_blocks(int T, int H, int max_ctx) {
+    const int64_t blocks = (int64_t)T * H * ((max_ctx + 15) / 16);
+    int64_t cb = (blocks + 4095) / 4096;
+    cb = (cb + 3) / 4 * 4;
+    return (int)std::min<int64_t>(std::max<int64_t>(cb, 4), 64);
+}
+static int attn_max_chunks(int T, int H, int max_ctx) {
+    const int cb = attn_chunk_blocks(T, H, max_ctx);
+    return ((max_ctx + 15) / 16 + cb - 1) / cb;
+}
 
 size_t ldk_attention_scratch_bytes(int32_t T, int32_t H, int32_t hd, int32_t max_ctx) {
     if (T <= 0 || H <= 0 || hd <= 0 || max_ctx <= 0) return 0;
-    return (size_t)T * H * attn_max_chunks(max_ctx) * (hd + 2) * sizeof(float);
+    return (size_t)T * H * attn_max_chunks(T, H, max_ctx) * (hd + 2) * sizeof(float);
 }
 
 ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
@@ -505,7 +502,7 @@ ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool
     if (T == 0) return LD_OK;
     if (scratch_bytes < ldk_attention_scratch_bytes(T, H, hd, max_ctx))
         return ld::fail(LD_E_INVAL, "ldk_paged_attention: scratch too small");
-    const int mc = attn_max_chunks(max_ctx);
+    const int mc = attn_max_chunks(T, H, max_ctx), cb = attn_chunk_blocks(T, H, max_ctx);
     float *part_o = (float *)scratch;
     float *part_ml = part_o + (size_t)T * H * mc * hd;
     const float sl2 = (float)(1.4426950408889634 / std::sqrt((double)hd));
@@ -514,8 +511,8 @@ ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool
 #define LD_ATT(HD_, KVT_)                                                                                         \
     do {                                                                                                          \
         hipLaunchKernelGGL((k_attn_partial<HD_, KVT_>), grid, block, 0, s, q, q_stride, (const KVT_ *)pool_layer, \
-                           Hkv, table, table_stride, seq_slot, ctx_len, H, sl2, mc, part_o, part_ml);             \
-        hipLaunchKernelGGL((k_attn_merge<HD_>), dim3(H, T), dim3(HD_), 0, s, part_o, part_ml, ctx_len, H, mc, out); \
+                           Hkv, table, table_stride, seq_slot, ctx_len, H, sl2, mc, cb, part_o, part_ml);             \
+        hipLaunchKernelGGL((k_attn_merge<HD_>), dim3(H, T), dim3(HD_), 0, s, part_o, part_ml, ctx_len, H, mc, cb, out); \
     } while (0)
     if (dtype == LD_BF16 && hd == 128) LD_ATT(128, bf16_t);
     else if (dtype == LD_BF16 && hd == 64) LD_ATT(64, bf16_t);

@@ -197,3 +197,42 @@ def test_argmax_ties_and_brute_force():
     ld.ldk_argmax(lg.to(DEV), out)
     ref = [oracle.argmax(lg[r].numpy()) for r in range(5)]
     assert out.cpu().tolist() == ref and ref[1] == 12 and ref[2] == 0 and ref[3] == V - 1
+
+
+@pytest.mark.parametrize("dtype,hd,T", [("bf16", 128, 1), ("bf16", 128, 3), ("f32", 64, 1), ("bf16", 64, 1)])
+def test_fused_qkv_projection_rope_cache_append(dtype, hd, T):
+    """ldk_qkv_rope = RMSNorm + q/k/v projection + rotary embedding + cache append in one call
+    (one fused kernel for a single bf16 row, a composition otherwise)."""
+    H, Hkv, K, nblk = 6, 2, 1160, 7
+    N = (H + 2 * Hkv) * hd
+    W = _mat(8, 1, N, K, dtype); x = gen.normal(8, 2, (T, K)); g = gen.normal(8, 3, (K,), std=0.1, mean=1.0)
+    pos = torch.tensor([37, 16, 95][:T], dtype=torch.int32)
+    slot = torch.tensor([1, 0, 1][:T], dtype=torch.int32)
+    table = torch.tensor([[3, 6, 0, 0, 0, 0], [5, 1, 4, 2, 0, 0]], dtype=torch.int32)   # logical -> physical
+    pdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    pool = torch.full((nblk, 2, Hkv, 16, hd), 512.0, dtype=pdt, device=DEV)
+    cs = torch.empty(T, hd // 2, 2, device=DEV)
+    qkv = torch.zeros(T, N, device=DEV)
+    ld.ldk_rope_table(pos.to(DEV), hd, 10000.0, cs)
+    ld.ldk_qkv_rope(W.to(DEV), x.to(DEV), qkv, cs, pos.to(DEV), slot.to(DEV), table.to(DEV), pool, H, Hkv, hd,
+                    g=g.to(DEV), eps=1e-5)
+    qkv_h, pool_h = qkv.cpu().numpy(), pool.float().cpu().numpy().astype(np.float64)
+    Wh = oracle.to_host_matrix(W)
+    touched = np.zeros(pool_h.shape[:4], bool)
+    for t in range(T):
+        ref = oracle.matvec(Wh, oracle.rmsnorm(x[t].numpy(), g.numpy(), 1e-5))
+        scale = np.abs(ref).max()
+        p = int(pos[t]); blk = int(table[slot[t], p // 16]); s = p % 16
+        for h in range(H):
+            r = oracle.rope_head(ref[h * hd:(h + 1) * hd], p)
+            np.testing.assert_allclose(qkv_h[t, h * hd:(h + 1) * hd], r, rtol=0, atol=4e-6 * scale)
+        for j in range(Hkv):
+            k = oracle.rope_head(ref[(H + j) * hd:(H + j + 1) * hd], p)
+            v = ref[(H + Hkv + j) * hd:(H + Hkv + j + 1) * hd]
+            tol = (2.0 ** -7 if dtype == "bf16" else 4e-6) * scale
+            assert np.max(np.abs(pool_h[blk, 0, j, s] - k)) <= tol and np.max(np.abs(pool_h[blk, 1, j, s] - v)) <= tol
+            if dtype == "bf16":
+                assert np.mean(pool_h[blk, 0, j, s] == oracle.round_bf16(k)) > 0.9
+                assert np.mean(pool_h[blk, 1, j, s] == oracle.round_bf16(v)) > 0.9
+            touched[blk, :, j, s] = True
+    assert np.all(pool_h[~touched] == 512.0) and touched.sum() == T * 2 * Hkv

@@ -29,15 +29,24 @@ ld_status ldk_embed(const void *embed, int32_t dtype, const int32_t *tok, int32_
 ld_status ldk_rmsnorm(const float *x, const float *g, const int32_t *row_idx, int32_t R, int32_t d, float eps,
                       float *out, void *stream);
 
+/* Scratch bytes ldk_linear (ldk_qkv_rope: epilogue LDK_STORE, N = (H + 2 Hkv) hd) can use for T rows
+ * (0 for T < 2): the two-part bf16 image of the input plus split-K partial sums. */
+size_t ldk_linear_scratch_bytes(int32_t T, int32_t N, int32_t K, int32_t epilogue);
+
 /* Linear layer on T rows: acc[t, n] = sum_k W[n, k] x[t, k], float32 accumulation.
  *   LDK_STORE : y[t, n]  = acc[t, n]                          W [N, K]
  *   LDK_ADD   : y[t, n] += acc[t, n]   (residual)             W [N, K]
  *   LDK_SWIGLU: y[t, n]  = silu(acc[t, n]) * acc[t, N + n]    W [2N, K]  (gate rows, then up rows)
  * If g != NULL the input is RMS-normalised on the fly: x[t, k] is replaced by
  * x[t, k] * rsqrt(mean_k x[t, k]^2 + eps) * g[k].
- * x [T, K], y [T, N] dense row-major.  K must be a multiple of 8. */
+ * x [T, K], y [T, N] dense row-major.  K must be a multiple of 8.
+ * Kernel choice: one bf16 row -> bandwidth-bound matrix-vector kernel; several bf16 rows with
+ * K a multiple of 128 and scratch of ldk_linear_scratch_bytes(...) bytes -> matrix cores
+ * (activations split into two bf16 parts, float32 accumulation); otherwise (float32 matrices, no
+ * scratch) a plain vector-ALU kernel.  scratch may be NULL. */
 ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *g, float eps, int32_t T,
-                     int32_t N, int32_t K, int32_t epilogue, float *y, void *stream);
+                     int32_t N, int32_t K, int32_t epilogue, float *y, void *scratch, size_t scratch_bytes,
+                     void *stream);
 
 /* cos_sin[t, i] = (cos, sin)(pos[t] * rope_base^(-2i/hd)) for i < hd/2, as float32 pairs; the
  * angle is formed in float64 so that large positions lose no accuracy.  hd is 64 or 128. */
@@ -60,7 +69,7 @@ ld_status ldk_rope_kv_write(float *qkv, const float *cos_sin, const int32_t *pos
 ld_status ldk_qkv_rope(const void *W, int32_t dtype, const float *x, const float *g, float eps, float *qkv,
                        const float *cos_sin, const int32_t *pos, const int32_t *seq_slot, const int32_t *table,
                        int32_t table_stride, void *pool_layer, int32_t T, int32_t K, int32_t H, int32_t Hkv, int32_t hd,
-                       void *stream);
+                       void *scratch, size_t scratch_bytes, void *stream);
 
 /* Scratch bytes ldk_paged_attention needs for T rows with contexts up to max_ctx. */
 size_t ldk_attention_scratch_bytes(int32_t T, int32_t H, int32_t hd, int32_t max_ctx);

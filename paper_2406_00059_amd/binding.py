@@ -20,7 +20,7 @@ __all__ = [
     "ld_token_cb", "ld_model_create", "ld_model_destroy", "ld_kv_bytes", "ld_workspace_bytes", "ld_kv_create",
     "ld_kv_destroy", "ld_kv_alloc", "ld_kv_map", "ld_kv_free", "ld_kv_block_table", "ld_kv_len",
     "ld_kv_free_blocks", "ld_kv_assume", "ld_prefill", "ld_decode_step", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
-    "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
+    "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
     "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_argmax", "Model", "KV",
 ]
 
@@ -80,12 +80,14 @@ _SIGS = {
     "ld_last_error": (C.c_char_p, []),
     "ldk_embed": (C.c_int, [_vp, C.c_int32, _vp, C.c_int32, C.c_int32, _vp, _vp]),
     "ldk_rmsnorm": (C.c_int, [_vp, _vp, _vp, C.c_int32, C.c_int32, C.c_float, _vp, _vp]),
-    "ldk_linear": (C.c_int, [_vp, C.c_int32, _vp, _vp, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]),
+    "ldk_linear_scratch_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
+    "ldk_linear": (C.c_int, [_vp, C.c_int32, _vp, _vp, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp,
+                             C.c_size_t, _vp]),
     "ldk_rope_table": (C.c_int, [_vp, C.c_int32, C.c_int32, C.c_float, _vp, _vp]),
     "ldk_rope_kv_write": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_int32, _vp, C.c_int32, C.c_int32, C.c_int32,
                                     C.c_int32, C.c_int32, _vp]),
     "ldk_qkv_rope": (C.c_int, [_vp, C.c_int32, _vp, _vp, C.c_float, _vp, _vp, _vp, _vp, _vp, C.c_int32, _vp,
-                               C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp]),
+                               C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, C.c_size_t, _vp]),
     "ldk_attention_scratch_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "ldk_paged_attention": (C.c_int, [_vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, _vp, _vp, C.c_int32,
                                       C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, C.c_size_t, _vp]),
@@ -277,11 +279,19 @@ def ldk_rmsnorm(x, g, out, eps, row_idx=None, stream=None):
     _check(lib().ldk_rmsnorm(_ptr(x), _ptr(g), _ptr(row_idx), R, d, eps, _ptr(out), _stream(stream)))
 
 
-def ldk_linear(W, x, y, epilogue=LDK_STORE, g=None, eps=0.0, stream=None):
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def ldk_linear_scratch_bytes(T, N, K, epilogue=LDK_STORE):
+    return lib().ldk_linear_scratch_bytes(T, N, K, epilogue)
+
+
+def ldk_linear(W, x, y, epilogue=LDK_STORE, g=None, eps=0.0, scratch=None, stream=None):
     T, K = x.shape
     N = y.shape[1]
     _check(lib().ldk_linear(_ptr(W), _dt(W.dtype), _ptr(x), _ptr(g), eps, T, N, K, epilogue, _ptr(y),
-                            _stream(stream)))
+                            _ptr(scratch), _nbytes(scratch), _stream(stream)))
 
 
 def ldk_rope_table(pos, hd, rope_base, cos_sin, stream=None):
@@ -294,11 +304,12 @@ def ldk_rope_kv_write(qkv, cos_sin, pos, seq_slot, table, pool_layer, H, Hkv, hd
                                    hd, _stream(stream)))
 
 
-def ldk_qkv_rope(W, x, qkv, cos_sin, pos, seq_slot, table, pool_layer, H, Hkv, hd, g=None, eps=0.0, stream=None):
+def ldk_qkv_rope(W, x, qkv, cos_sin, pos, seq_slot, table, pool_layer, H, Hkv, hd, g=None, eps=0.0, scratch=None,
+                 stream=None):
     T, K = x.shape
     _check(lib().ldk_qkv_rope(_ptr(W), _dt(W.dtype), _ptr(x), _ptr(g), eps, _ptr(qkv), _ptr(cos_sin), _ptr(pos),
                               _ptr(seq_slot), _ptr(table), table.shape[1], _ptr(pool_layer), T, K, H, Hkv, hd,
-                              _stream(stream)))
+                              _ptr(scratch), _nbytes(scratch), _stream(stream)))
 
 
 def ldk_attention_scratch_bytes(T, H, hd, max_ctx):

@@ -1,0 +1,26 @@
+// Multi-row linear layers on the matrix cores (bf16 matrices): launcher interface.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace ld {
+
+enum { GEMM_STORE = 0, GEMM_ADD = 1, GEMM_SWIGLU = 2 };
+
+// True if the MFMA kernel handles this shape (K a multiple of 128).
+bool gemm_supported(int T, int N, int K);
+
+// Bytes of scratch for the bf16 (high, low) images of a [T, K] activation matrix, and for a whole
+// launch_norm_split + launch_gemm pair (split image followed by the split-K partial sums).
+size_t gemm_split_bytes(int T, int K);
+size_t gemm_scratch_bytes(int T, int N, int K, int epi);
+
+// xs <- split(x * rsqrt(mean x^2 + eps) * g)  (g == nullptr: plain split), row by row:
+// hi = bf16(v), lo = bf16(v - hi), stored as two [T, K] bf16 matrices (hi first).
+void launch_norm_split(const float *x, const float *g, float eps, int T, int K, uint16_t *xs, hipStream_t s);
+
+// y = epilogue(X W^T) with X given by its split image at the start of the scratch area xs
+// (gemm_scratch_bytes bytes); W bf16 [N, K] ([2N, K] for GEMM_SWIGLU).
+void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s);
+
+}  // namespace ld

@@ -1,0 +1,297 @@
+// Linear layers on T >= 2 rows with the matrix cores: Y[T, N] = X[T, K] W[N, K]^T, W bf16.
+//
+// Precision: the float32 activations are split into two bf16 numbers, x = hi + lo (|lo| <= 2^-9 |hi|),
+// and both parts are multiplied with the (exact) bf16 weights and accumulated in float32, so the
+// product carries ~16 significant bits of the activation instead of 8.  In the decode regime the
+// kernel is bound by the weight stream from HBM, where the second MFMA pass is free.
+//
+// Data movement:
+//  - A one-pass prologue kernel applies RMSNorm (optional) and writes the (hi, lo) bf16 images.
+//  - A workgroup of 4 waves owns 128 consecutive output columns (rows of W; 32 per wave) and a tile
+//    of TT*32 rows of X.  W is streamed from global memory straight into MFMA B-operand registers:
+//    lane (n = lane % 32, h = lane / 32) loads 16 bytes of row n; the contraction order over k is
+//    permuted so that the four loads of one 64-wide k-group give every row 128 contiguous bytes
+//    (k = kg*64 + h*32 + j*8 + e for load j), and the X operand is read with the same permutation.
+//  - The X tile (hi and lo) of the current 128-wide K chunk is staged in LDS and shared by the
+//    four waves; rows are padded by 16 bytes against bank conflicts.
+//  - Global loads (W fragments and the next X chunk) are issued one chunk ahead of their use.
+//  - With the token index on the MFMA row side, each accumulator register holds 32 consecutive
+//    output columns of one token, so stores are 128-byte contiguous.
+//  - Workgroups that share a W panel (same columns, different token tiles) are mapped to the same
+//    XCD so that the panel is fetched into one L2 only.
+#include "ld_gemm.h"
+#include "ld_device.h"
+#include <algorithm>
+
+using namespace ldd;
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // native 16-byte vector (keeps arrays of it in registers)
+
+constexpr int KC = 128;          // K chunk staged in LDS
+constexpr int XPAD = 8;          // bf16 elements of row padding in LDS
+constexpr int NW = 4;            // waves per workgroup
+constexpr int N_TILE = 32 * NW;  // output columns per workgroup
+
+__global__ __launch_bounds__(256) void k_norm_split(const float *__restrict__ x, const float *__restrict__ g,
+                                                    float eps, int K, bf16_t *__restrict__ hi,
+                                                    bf16_t *__restrict__ lo) {
+    __shared__ float red[4];
+    const int t = blockIdx.x;
+    const float *row = x + (int64_t)t * K;
+    float rstd = 1.f;
+    if (g) {
+        float ss = 0.f;
+        for (int i = threadIdx.x * 4; i < K; i += 1024) {
+            const float4 v = *reinterpret_cast<const float4 *>(row + i);
+            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        }
+        ss = wave_sum(ss);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+        __syncthreads();
+        rstd = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / K + eps);
+    }
+    for (int i = threadIdx.x * 4; i < K; i += 1024) {
+        float4 v = *reinterpret_cast<const float4 *>(row + i);
+        if (g) {
+            const float4 gv = *reinterpret_cast<const float4 *>(g + i);
+            v.x = v.x * rstd * gv.x; v.y = v.y * rstd * gv.y; v.z = v.z * rstd * gv.z; v.w = v.w * rstd * gv.w;
+        }
+        const float f[4] = {v.x, v.y, v.z, v.w};
+        bf16_t h[4], l[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            h[e] = f32_to_bf16(f[e]);
+            l[e] = f32_to_bf16(f[e] - bf16_to_f32(h[e]));
+        }
+        *reinterpret_cast<uint2 *>(hi + (int64_t)t * K + i) =
+            make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
+        *reinterpret_cast<uint2 *>(lo + (int64_t)t * K + i) =
+            make_uint2((uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16));
+    }
+}
+
+// TT: token tiles of 32 per workgroup.  WR: W fragments per wave (2 for SwiGLU: gate and up rows).
+template <int TT, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
+                                                   const bf16_t *__restrict__ xlo, int T, int N, int K,
+                                                   float *__restrict__ y, int n_ttiles, int ks,
+                                                   float *__restrict__ partial) {
+    constexpr int WR = (EPI == ld::GEMM_SWIGLU) ? 2 : 1;
+    constexpr int TROWS = TT * 32;
+    constexpr int XLD = KC + XPAD;                       // LDS row stride in elements
+    constexpr int XV = TROWS * (KC / 8) * 2 / 256;       // u32x4 per thread to stage one chunk (hi + lo)
+    __shared__ __attribute__((aligned(16))) bf16_t xs[2][TROWS][XLD];
+
+    // XCD-aware decode of the linear block id: blocks b, b+8, b+16, ... run on the same XCD
+    const int b = blockIdx.x, xcd = b & 7, s = b >> 3;
+    const int kz = s % ks, tt_idx = (s / ks) % n_ttiles, nb = (s / (ks * n_ttiles)) * 8 + xcd;
+    const int n_nblocks = (N + N_TILE - 1) / N_TILE;
+    if (nb >= n_nblocks) return;
+    const int t0 = tt_idx * TROWS;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int n0 = nb * N_TILE + wave * 32;
+
+    // W rows of this lane (clamped in range; out-of-range columns are never stored)
+    const bf16_t *wrow[WR];
+#pragma unroll
+    for (int r = 0; r < WR; r++) {
+        const int n = min(n0 + l32, N - 1);
+        wrow[r] = W + ((int64_t)r * N + n) * K + half * 32;
+    }
+    // staging assignment: u32x4 index v -> (part, row, col16)
+    int st_row[XV], st_c16[XV], st_part[XV];
+    const bf16_t *st_src[XV];
+#pragma unroll
+    for (int v = 0; v < XV; v++) {
+        const int idx = threadIdx.x + 256 * v;
+        st_part[v] = idx / (TROWS * (KC / 8));
+        const int rem = idx % (TROWS * (KC / 8));
+        st_row[v] = rem / (KC / 8);
+        st_c16[v] = rem % (KC / 8);
+        const int t = min(t0 + st_row[v], T - 1);        // rows past T are staged from row T-1 and never stored
+        st_src[v] = (st_part[v] ? xlo : xhi) + (int64_t)t * K + st_c16[v] * 8;
+    }
+
+    f32x16 acc[WR][TT];
+#pragma unroll
+    for (int r = 0; r < WR; r++)
+#pragma unroll
+        for (int tt = 0; tt < TT; tt++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) acc[r][tt][i] = 0.f;
+
+    u32x4 wA[WR][8], wB[WR][8], xr[XV];
+    auto load_w = [&](u32x4 (&w)[WR][8], int kc) {
+#pragma unroll
+        for (int r = 0; r < WR; r++)
+#pragma unroll
+            for (int kg = 0; kg < 2; kg++)
+#pragma unroll
+                for (int j = 0; j < 4; j++)
+                    w[r][kg * 4 + j] = *reinterpret_cast<const u32x4 *>(wrow[r] + kc * KC + kg * 64 + j * 8);
+    };
+    auto load_x = [&](u32x4 (&xv)[XV], int kc) {
+#pragma unroll
+        for (int v = 0; v < XV; v++) xv[v] = *reinterpret_cast<const u32x4 *>(st_src[v] + kc * KC);
+    };
+    auto compute = [&](u32x4 (&w)[WR][8]) {
+#pragma unroll
+        for (int kg = 0; kg < 2; kg++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const int k = kg * 64 + half * 32 + j * 8;
+#pragma unroll
+                for (int tt = 0; tt < TT; tt++) {
+                    const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[0][tt * 32 + l32][k]));
+                    const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[1][tt * 32 + l32][k]));
+#pragma unroll
+                    for (int r = 0; r < WR; r++) {
+                        const bf16x8 bw = __builtin_bit_cast(bf16x8, w[r][kg * 4 + j]);
+                        acc[r][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bw, acc[r][tt], 0, 0, 0);
+                        acc[r][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bw, acc[r][tt], 0, 0, 0);
+                    }
+                }
+            }
+    };
+    auto stage = [&](const u32x4 (&xv)[XV]) {
+#pragma unroll
+        for (int v = 0; v < XV; v++)
+            *reinterpret_cast<u32x4 *>(&xs[st_part[v]][st_row[v]][st_c16[v] * 8]) = xv[v];
+    };
+
+    // this workgroup's K slab: chunks [c_begin, n_chunks) of K / KC, split evenly over ks workgroups
+    const int c_begin = (int)((int64_t)kz * (K / KC) / ks), n_chunks = (int)((int64_t)(kz + 1) * (K / KC) / ks);
+    load_x(xr, c_begin);
+    load_w(wA, c_begin);
+    for (int kc = c_begin; kc < n_chunks; kc += 2) {
+        __syncthreads();                 // everyone finished reading the previous chunk from LDS
+        stage(xr);
+        __syncthreads();
+        if (kc + 1 < n_chunks) { load_x(xr, kc + 1); load_w(wB, kc + 1); }
+        compute(wA);
+        if (kc + 1 < n_chunks) {
+            __syncthreads();
+            stage(xr);
+            __syncthreads();
+            if (kc + 2 < n_chunks) { load_x(xr, kc + 2); load_w(wA, kc + 2); }
+            compute(wB);
+        }
+    }
+
+    // accumulator element i of lane (l32, half): token t0 + tt*32 + 8*(i/4) + 4*half + i%4, column n0 + l32
+    const int n = n0 + l32;
+    if (ks > 1) {
+        // split-K: raw partial sums, [kz][t][r * N + n]; a second kernel adds the slabs in fixed order
+        if (n < N) {
+#pragma unroll
+            for (int r = 0; r < WR; r++)
+#pragma unroll
+                for (int tt = 0; tt < TT; tt++)
+#pragma unroll
+                    for (int i = 0; i < 16; i++) {
+                        const int t = t0 + tt * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+                        if (t < T) partial[((int64_t)kz * T + t) * (WR * N) + r * N + n] = acc[r][tt][i];
+                    }
+        }
+        return;
+    }
+    if (n < N) {
+#pragma unroll
+        for (int tt = 0; tt < TT; tt++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const int t = t0 + tt * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+                if (t < T) {
+                    float *dst = y + (int64_t)t * N + n;
+                    if constexpr (EPI == ld::GEMM_STORE) *dst = acc[0][tt][i];
+                    else if constexpr (EPI == ld::GEMM_ADD) *dst += acc[0][tt][i];
+                    else {
+                        const float gate = acc[0][tt][i], up = acc[1][tt][i];
+                        *dst = gate / (1.0f + __expf(-gate)) * up;
+                    }
+                }
+            }
+    }
+}
+
+// Adds the ks K-slab partial sums in slab order and applies the epilogue.  One thread per output.
+template <int EPI>
+__global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__ partial, int T, int N, int ks,
+                                                       float *__restrict__ y) {
+    constexpr int WR = (EPI == ld::GEMM_SWIGLU) ? 2 : 1;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)T * N) return;
+    const int t = (int)(idx / N), n = (int)(idx % N);
+    float a = 0.f, b = 0.f;
+    for (int z = 0; z < ks; z++) {
+        const float *p = partial + ((int64_t)z * T + t) * (WR * N) + n;
+        a += p[0];
+        if (WR == 2) b += p[N];
+    }
+    if constexpr (EPI == ld::GEMM_STORE) y[idx] = a;
+    else if constexpr (EPI == ld::GEMM_ADD) y[idx] += a;
+    else y[idx] = a / (1.0f + __expf(-a)) * b;
+}
+
+int split_factor(int T, int N, int K, int tt_rows) {
+    const int n_ttiles = (T + tt_rows - 1) / tt_rows, n_nblocks = (N + N_TILE - 1) / N_TILE;
+    const int wgs = n_ttiles * n_nblocks;
+    int ks = (768 + wgs - 1) / wgs;          // aim at ~3 workgroups per CU
+    ks = std::min(ks, K / KC / 2);           // at least two chunks per slab
+    ks = std::min(ks, 32);
+    return std::max(ks, 1);
+}
+
+template <int TT>
+void launch_tt(const bf16_t *W, const bf16_t *xs, int T, int N, int K, int epi, float *y, float *partial,
+               hipStream_t s) {
+    const int n_ttiles = (T + TT * 32 - 1) / (TT * 32);
+    const int n_nblocks = (N + N_TILE - 1) / N_TILE;
+    const int ks = split_factor(T, N, K, TT * 32);
+    const int grid = ((n_nblocks + 7) / 8) * 8 * n_ttiles * ks;
+    const bf16_t *hi = xs, *lo = xs + (size_t)T * K;
+    const int rgrid = (int)(((int64_t)T * N + 255) / 256);
+    if (epi == ld::GEMM_STORE) {
+        hipLaunchKernelGGL((k_gemm_mfma<TT, ld::GEMM_STORE>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, n_ttiles, ks, partial);
+        if (ks > 1) hipLaunchKernelGGL((k_splitk_reduce<ld::GEMM_STORE>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
+    } else if (epi == ld::GEMM_ADD) {
+        hipLaunchKernelGGL((k_gemm_mfma<TT, ld::GEMM_ADD>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, n_ttiles, ks, partial);
+        if (ks > 1) hipLaunchKernelGGL((k_splitk_reduce<ld::GEMM_ADD>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
+    } else {
+        hipLaunchKernelGGL((k_gemm_mfma<TT, ld::GEMM_SWIGLU>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, n_ttiles, ks, partial);
+        if (ks > 1) hipLaunchKernelGGL((k_splitk_reduce<ld::GEMM_SWIGLU>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
+    }
+}
+
+}  // namespace
+
+namespace ld {
+
+bool gemm_supported(int T, int N, int K) { return T >= 2 && N > 0 && K > 0 && K % KC == 0; }
+
+static int tile_rows(int T) { return T <= 32 ? 32 : 64; }
+
+size_t gemm_split_bytes(int T, int K) { return (((size_t)2 * T * K * sizeof(bf16_t)) + 255) / 256 * 256; }
+
+size_t gemm_scratch_bytes(int T, int N, int K, int epi) {
+    const int ks = split_factor(T, N, K, tile_rows(T));
+    const size_t part = ks > 1 ? (size_t)ks * T * N * (epi == GEMM_SWIGLU ? 2 : 1) * sizeof(float) : 0;
+    return gemm_split_bytes(T, K) + part;
+}
+
+void launch_norm_split(const float *x, const float *g, float eps, int T, int K, uint16_t *xs, hipStream_t s) {
+    hipLaunchKernelGGL(k_norm_split, dim3(T), dim3(256), 0, s, x, g, eps, K, xs, xs + (size_t)T * K);
+}
+
+void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s) {
+    float *partial = (float *)((char *)xs + gemm_split_bytes(T, K));
+    if (tile_rows(T) == 32) launch_tt<1>(W, xs, T, N, K, epi, y, partial, s);
+    else launch_tt<2>(W, xs, T, N, K, epi, y, partial, s);
+}
+
+}  // namespace ld

@@ -52,8 +52,8 @@ struct Seq {
 struct Workspace {
     int32_t *table, *meta, *out_tok;
     float *x, *qkv, *attn, *act, *hn, *logits, *cos_sin;
-    void *att_scratch;
-    size_t att_scratch_bytes;
+    void *att_scratch, *lin_scratch;
+    size_t att_scratch_bytes, lin_scratch_bytes;
     size_t total;
 };
 
@@ -82,6 +82,16 @@ Workspace plan_workspace(const ld_model &m, char *base, int max_tokens, int max_
         w.att_scratch_bytes = std::max(w.att_scratch_bytes,
                                        ldk_attention_scratch_bytes(t, c.n_heads, c.head_dim, max_blocks * c.kv_block));
     w.att_scratch = take(w.att_scratch_bytes);
+    w.lin_scratch_bytes = 0;   // the split-K factor depends on the row count: size for the worst one
+    for (int t = 2; t <= max_tokens; t++) {
+        size_t b = ldk_linear_scratch_bytes(t, m.nqkv(), c.d_model, LDK_STORE);
+        b = std::max(b, ldk_linear_scratch_bytes(t, c.d_model, m.nq(), LDK_ADD));
+        b = std::max(b, ldk_linear_scratch_bytes(t, c.d_ffn, c.d_model, LDK_SWIGLU));
+        b = std::max(b, ldk_linear_scratch_bytes(t, c.d_model, c.d_ffn, LDK_ADD));
+        if (t <= max_seqs) b = std::max(b, ldk_linear_scratch_bytes(t, c.vocab, c.d_model, LDK_STORE));
+        w.lin_scratch_bytes = std::max(w.lin_scratch_bytes, b);
+    }
+    w.lin_scratch = take(w.lin_scratch_bytes);
     w.total = off;
     return w;
 }
@@ -216,15 +226,17 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, const std::vector<in
     for (int l = 0; l < c.n_layers; l++) {
         void *pool_l = kv->pool + (size_t)l * layer_bytes;
         LD_TIMED(LD_PROF_QKV, ldk_qkv_rope(m.wqkv[l], c.dtype, w.x, m.attn_norm[l], c.rms_eps, w.qkv, w.cos_sin, d_pos,
-                                           d_slot, w.table, kv->max_blocks, pool_l, T, d, H, Hkv, hd, st));
+                                           d_slot, w.table, kv->max_blocks, pool_l, T, d, H, Hkv, hd, w.lin_scratch, w.lin_scratch_bytes, st));
         LD_TIMED(LD_PROF_ATTENTION, ldk_paged_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot, d_ctx, max_ctx, T,
                                    H, Hkv, hd, w.attn, w.att_scratch, w.att_scratch_bytes, st));
-        LD_TIMED(LD_PROF_WO, ldk_linear(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, st));
-        LD_TIMED(LD_PROF_GATE_UP, ldk_linear(m.wgate_up[l], c.dtype, w.x, m.ffn_norm[l], c.rms_eps, T, c.d_ffn, d, LDK_SWIGLU, w.act, st));
-        LD_TIMED(LD_PROF_DOWN, ldk_linear(m.wdown[l], c.dtype, w.act, nullptr, 0.f, T, d, c.d_ffn, LDK_ADD, w.x, st));
+        LD_TIMED(LD_PROF_WO, ldk_linear(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st));
+        LD_TIMED(LD_PROF_GATE_UP, ldk_linear(m.wgate_up[l], c.dtype, w.x, m.ffn_norm[l], c.rms_eps, T, c.d_ffn, d, LDK_SWIGLU, w.act, w.lin_scratch,
+                                               w.lin_scratch_bytes, st));
+        LD_TIMED(LD_PROF_DOWN, ldk_linear(m.wdown[l], c.dtype, w.act, nullptr, 0.f, T, d, c.d_ffn, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st));
     }
     LD_TIMED(LD_PROF_OTHER, ldk_rmsnorm(w.x, m.final_norm, d_emit, R, d, c.rms_eps, w.hn, st));
-    LD_TIMED(LD_PROF_LM_HEAD, ldk_linear(m.lm_head, c.dtype, w.hn, nullptr, 0.f, R, c.vocab, d, LDK_STORE, w.logits, st));
+    LD_TIMED(LD_PROF_LM_HEAD, ldk_linear(m.lm_head, c.dtype, w.hn, nullptr, 0.f, R, c.vocab, d, LDK_STORE, w.logits, w.lin_scratch,
+                                      w.lin_scratch_bytes, st));
     LD_TIMED(LD_PROF_OTHER, ldk_argmax(w.logits, R, c.vocab, w.out_tok, st));
 #undef LD_TIMED
 #undef LD_TRY

@@ -5,6 +5,7 @@
 #include "ld_internal.h"
 #include "ld_device.h"
 #include "ld_gemv.h"
+#include "ld_gemm.h"
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -406,8 +407,12 @@ ld_status ldk_rmsnorm(const float *x, const float *g, const int32_t *row_idx, in
     return launched("k_rmsnorm");
 }
 
+size_t ldk_linear_scratch_bytes(int32_t T, int32_t N, int32_t K, int32_t epilogue) {
+    return (T >= 2 && N > 0 && K >= 128) ? ld::gemm_scratch_bytes(T, N, K, epilogue) : 0;
+}
+
 ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *g, float eps, int32_t T, int32_t N,
-                     int32_t K, int32_t epilogue, float *y, void *stream) {
+                     int32_t K, int32_t epilogue, float *y, void *scratch, size_t scratch_bytes, void *stream) {
     if (!W || !x || !y || T < 0 || N <= 0 || K <= 0 || K % 8 || epilogue < 0 || epilogue > 2)
         return ld::fail(LD_E_INVAL, "ldk_linear: bad argument (K must be a multiple of 8)");
     if (T == 0) return LD_OK;
@@ -415,6 +420,11 @@ ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *
     if (dtype == LD_BF16 && T == 1 && ld::gemv1_supported(N, K, epilogue)) {
         ld::launch_gemv1((const bf16_t *)W, x, g, eps, N, K, epilogue, y, nullptr, s);
         return launched("k_gemv1");
+    }
+    if (dtype == LD_BF16 && scratch && ld::gemm_supported(T, N, K) && scratch_bytes >= ld::gemm_scratch_bytes(T, N, K, epilogue)) {
+        ld::launch_norm_split(x, g, eps, T, K, (uint16_t *)scratch, s);
+        ld::launch_gemm((const bf16_t *)W, (const uint16_t *)scratch, T, N, K, epilogue, y, s);
+        return launched("k_gemm_mfma");
     }
     if (dtype == LD_BF16) {
         if (g) launch_linear<bf16_t, true>((const bf16_t *)W, x, g, eps, T, N, K, epilogue, y, s);
@@ -458,7 +468,7 @@ ld_status ldk_rope_kv_write(float *qkv, const float *cos_sin, const int32_t *pos
 ld_status ldk_qkv_rope(const void *W, int32_t dtype, const float *x, const float *g, float eps, float *qkv,
                        const float *cos_sin, const int32_t *pos, const int32_t *seq_slot, const int32_t *table,
                        int32_t table_stride, void *pool_layer, int32_t T, int32_t K, int32_t H, int32_t Hkv, int32_t hd,
-                       void *stream) {
+                       void *scratch, size_t scratch_bytes, void *stream) {
     if (!W || !x || !qkv || !cos_sin || !pos || !seq_slot || !table || !pool_layer || T < 0 || H <= 0 || Hkv <= 0 ||
         H % Hkv || (hd != 64 && hd != 128) || K <= 0 || K % 8)
         return ld::fail(LD_E_INVAL, "ldk_qkv_rope: bad argument");
@@ -469,7 +479,7 @@ ld_status ldk_qkv_rope(const void *W, int32_t dtype, const float *x, const float
         ld::launch_gemv1((const bf16_t *)W, x, g, eps, N, K, ld::GEMV_ROPE_KV, qkv, &rk, (hipStream_t)stream);
         return launched("k_gemv1 (rope + cache append)");
     }
-    ld_status rc = ldk_linear(W, dtype, x, g, eps, T, N, K, LDK_STORE, qkv, stream);
+    ld_status rc = ldk_linear(W, dtype, x, g, eps, T, N, K, LDK_STORE, qkv, scratch, scratch_bytes, stream);
     if (rc != LD_OK) return rc;
     return ldk_rope_kv_write(qkv, cos_sin, pos, seq_slot, table, table_stride, pool_layer, dtype, T, H, Hkv, hd, stream);
 }

@@ -236,3 +236,52 @@ def test_fused_qkv_projection_rope_cache_append(dtype, hd, T):
                 assert np.mean(pool_h[blk, 1, j, s] == oracle.round_bf16(v)) > 0.9
             touched[blk, :, j, s] = True
     assert np.all(pool_h[~touched] == 512.0) and touched.sum() == T * 2 * Hkv
+
+
+@pytest.mark.parametrize("T", [2, 5, 31, 32, 33, 64, 100, 257])
+@pytest.mark.parametrize("epi", ["store", "add_norm", "swiglu_norm"])
+def test_linear_matrix_core_path(T, epi):
+    """bf16 matrices, several rows, K a multiple of 128, scratch given: the MFMA kernel with split
+    (hi + lo) activations.  Ragged N (not a multiple of the 128-column tile) and ragged T."""
+    N, K = 333, 1152
+    rows = 2 * N if epi == "swiglu_norm" else N
+    W = _mat(9, 1, rows, K, "bf16"); x = gen.normal(9, 2, (T, K)); g = gen.normal(9, 3, (K,), std=0.1, mean=1.0)
+    y0 = gen.normal(9, 4, (T, N))
+    Wh = oracle.to_host_matrix(W)
+    scratch = torch.empty(ld.ldk_linear_scratch_bytes(T, N, K, ld.LDK_SWIGLU), dtype=torch.uint8, device=DEV)
+    y = y0.to(DEV).clone()
+    if epi == "store":
+        ld.ldk_linear(W.to(DEV), x.to(DEV), y, ld.LDK_STORE, scratch=scratch)
+        ref = np.stack([oracle.matvec(Wh, x[t].numpy()) for t in range(T)])
+    elif epi == "add_norm":
+        ld.ldk_linear(W.to(DEV), x.to(DEV), y, ld.LDK_ADD, g=g.to(DEV), eps=1e-5, scratch=scratch)
+        ref = y0.numpy() + np.stack([oracle.matvec(Wh, oracle.rmsnorm(x[t].numpy(), g.numpy(), 1e-5)) for t in range(T)])
+    else:
+        ld.ldk_linear(W.to(DEV), x.to(DEV), y, ld.LDK_SWIGLU, g=g.to(DEV), eps=1e-5, scratch=scratch)
+        gu = np.stack([oracle.matvec(Wh, oracle.rmsnorm(x[t].numpy(), g.numpy(), 1e-5)) for t in range(T)])
+        ref = gu[:, :N] / (1 + np.exp(-gu[:, :N])) * gu[:, N:]
+    err = np.max(np.abs(y.cpu().numpy() - ref)) / np.abs(ref).max()
+    assert err <= 2e-5, err
+
+
+def test_linear_matrix_core_7b_shapes_sampled():
+    """Launch shapes of the batch-32 decode step and of a 256-row prefill chunk, sampled outputs."""
+    for T in (32, 256):
+        for N, K, epi in [(12288, 4096, ld.LDK_STORE), (4096, 11008, ld.LDK_ADD), (11008, 4096, ld.LDK_SWIGLU)]:
+            rows = N * (2 if epi == ld.LDK_SWIGLU else 1)
+            W = gen.normal(3, N, (rows, K), std=0.02, device=DEV).bfloat16()
+            x = gen.normal(3, 7 + T, (T, K), device=DEV)
+            y = torch.zeros(T, N, device=DEV)
+            scratch = torch.empty(ld.ldk_linear_scratch_bytes(T, N, K, epi), dtype=torch.uint8, device=DEV)
+            ld.ldk_linear(W, x, y, epi, scratch=scratch)
+            ns = gen.randint(3, 9, 0, N - 1, 6).tolist() + [0, N - 1]
+            ts = sorted(set(gen.randint(3, 10, 0, T - 1, 5).tolist() + [0, T - 1]))
+            xh = x.cpu().numpy(); yh = y.cpu().numpy()
+            for n in ns:
+                wr = oracle.to_host_matrix(W[n:n + 1]); wu = oracle.to_host_matrix(W[N + n:N + n + 1]) if epi == ld.LDK_SWIGLU else None
+                for t in ts:
+                    a = oracle.matvec(wr, xh[t])[0]
+                    if wu is not None:
+                        a = oracle.silu(a) * oracle.matvec(wu, xh[t])[0]
+                    # two-term bf16 split of the activations: ~2^-17 per element, random-walk over K terms
+                    assert abs(yh[t, n] - a) <= 1e-4 * max(1.0, abs(a)), (T, N, t, n, yh[t, n], a)

@@ -84,6 +84,17 @@ ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool
                               const int32_t *ctx_len, int32_t max_ctx, int32_t T, int32_t H, int32_t Hkv,
                               int32_t hd, float *out, void *scratch, size_t scratch_bytes, void *stream);
 
+/* Attention for prefill segments (section 2.1: "the user prompt can be processed in parallel in a
+ * single iteration"): a segment is a run of rows of one sequence at consecutive positions whose keys
+ * and values are already in the pool; row r at position p attends to cached positions 0 .. p.
+ * tiles: DEVICE int32[n_tiles][4] = (first row, number of rows (1..128), position of the first row,
+ * block-table row of the sequence); a segment longer than 128 rows is given as several tiles.
+ * q and out as in ldk_paged_attention.  Supported: dtype LD_BF16 with hd = 128 (LD_E_INVAL otherwise;
+ * such shapes run their prefill rows through ldk_paged_attention with ctx_len = position + 1). */
+ld_status ldk_prefill_attention(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
+                                const int32_t *table, int32_t table_stride, const int32_t *tiles, int32_t n_tiles,
+                                int32_t H, int32_t Hkv, int32_t hd, float *out, void *stream);
+
 /* out[r] = smallest index of the maximum of logits[r, 0..V). */
 ld_status ldk_argmax(const float *logits, int32_t R, int32_t V, int32_t *out, void *stream);
 

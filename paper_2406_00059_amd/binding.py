@@ -21,7 +21,7 @@ __all__ = [
     "ld_kv_destroy", "ld_kv_alloc", "ld_kv_map", "ld_kv_free", "ld_kv_block_table", "ld_kv_len",
     "ld_kv_free_blocks", "ld_kv_assume", "ld_prefill", "ld_decode_step", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
     "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
-    "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_argmax", "Model", "KV",
+    "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_prefill_attention", "ldk_argmax", "Model", "KV",
 ]
 
 
@@ -91,6 +91,8 @@ _SIGS = {
     "ldk_attention_scratch_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "ldk_paged_attention": (C.c_int, [_vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, _vp, _vp, C.c_int32,
                                       C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, C.c_size_t, _vp]),
+    "ldk_prefill_attention": (C.c_int, [_vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, C.c_int32,
+                                        C.c_int32, C.c_int32, _vp, _vp]),
     "ldk_argmax": (C.c_int, [_vp, C.c_int32, C.c_int32, _vp, _vp]),
 }
 EXPORTS = tuple(_SIGS)
@@ -322,6 +324,12 @@ def ldk_paged_attention(q, q_stride, pool_layer, table, seq_slot, ctx_len, max_c
                                      table.shape[1], _ptr(seq_slot), _ptr(ctx_len), max_ctx, out.shape[0], H, Hkv,
                                      hd, _ptr(out), _ptr(scratch), scratch.numel() * scratch.element_size(),
                                      _stream(stream)))
+
+
+def ldk_prefill_attention(q, q_stride, pool_layer, table, tiles, H, Hkv, hd, out, stream=None):
+    _check(lib().ldk_prefill_attention(_ptr(q), q_stride, _ptr(pool_layer), _dt(pool_layer.dtype), _ptr(table),
+                                       table.shape[1], _ptr(tiles), tiles.shape[0], H, Hkv, hd, _ptr(out),
+                                       _stream(stream)))
 
 
 def ldk_argmax(logits, out, stream=None):

@@ -1,0 +1,16 @@
+// Chunk-prefill attention on the matrix cores: launcher interface.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace ld {
+
+// Supported: bf16 pool, head_dim 128.
+bool prefill_attention_supported(int dtype_is_bf16, int hd);
+
+// tiles: DEVICE int32[n_tiles][4] = (first row, rows <= 128, position of the first row, block-table row).
+// q rows at q + row * q_stride (+ head * 128); out dense [rows, H, 128].
+void launch_prefill_attention(const float *q, int q_stride, const uint16_t *pool, int Hkv, const int32_t *table,
+                              int table_stride, const int32_t *tiles, int n_tiles, int H, float *out, hipStream_t s);
+
+}  // namespace ld

@@ -1,0 +1,206 @@
+// Chunk-prefill attention over the paged KV pool on the matrix cores (bf16 pool, head_dim 128).
+//
+// A prefill segment is a run of consecutive rows of one sequence at consecutive positions; row r
+// (position p_r) attends to every cached position j <= p_r: the earlier context plus, causally, the
+// rows of its own chunk, whose keys/values were appended to the pool just before.
+//
+// Work split: a workgroup (4 waves) takes 128 consecutive rows of a segment and one head; wave w
+// owns rows [32w, 32w+32).  All four waves walk the same KV positions in steps of 32 tokens.
+//
+// Both products are computed transposed, so that the query index is the MFMA column (= lane % 32)
+// everywhere and the online-softmax statistics of a query live in the lanes that hold its scores:
+//   S^T[kv, q] = K[kv, :] . Q[q, :]      A = K rows   (16-byte loads straight from the pool),
+//                                        B = Q        (registers, split into bf16 hi + lo)
+//   O^T[d, q] += V^T[d, kv] P^T[kv, q]   A = V^T      (the V tile is transposed while it is staged
+//                                                      into LDS and shared by the four waves),
+//                                        B = P^T      (the score registers themselves: in the 32x32
+//                                                      accumulator layout a lane already holds, for
+//                                                      its query, exactly the 8 kv slots of an operand)
+// Scores are kept in the log2 domain (q is pre-multiplied by log2(e)/sqrt(hd)); m, l and O are float32.
+#include "ld_attn_prefill.h"
+#include "ld_device.h"
+
+using namespace ldd;
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int HD = 128;
+constexpr int KVB = 32;        // kv positions per step
+constexpr int VLD = KVB + 4;   // LDS row stride of the transposed V tile (elements)
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+}
+
+__global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ q, int q_stride,
+                                                      const bf16_t *__restrict__ pool, int Hkv,
+                                                      const int32_t *__restrict__ table, int table_stride,
+                                                      const int4 *__restrict__ tiles, int H, float scale_log2e,
+                                                      float *__restrict__ out) {
+    __shared__ __attribute__((aligned(16))) bf16_t vt[HD][VLD];
+    const int4 tile = tiles[blockIdx.x];      // x: first row, y: rows (<= 128), z: position of first row, w: seq slot
+    const int h = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int kvh = h / (H / Hkv);
+    const int64_t block_stride = (int64_t)2 * Hkv * 16 * HD;
+    const int32_t *trow = table + (int64_t)tile.w * table_stride;
+
+    // this lane's query: row index inside the tile, validity, absolute position
+    const int qi = wave * 32 + l32;
+    const bool q_valid = qi < tile.y;
+    const int q_pos = tile.z + min(qi, tile.y - 1);
+    const int wg_last_pos = tile.z + tile.y - 1;                       // last position any wave needs
+    const int wave_last_pos = tile.z + min(wave * 32 + 31, tile.y - 1);
+    const bool wave_active = wave * 32 < tile.y;
+
+    // Q operand: for k-step j the lane supplies dims half*64 + j*8 .. +8 of its query (hi and lo parts)
+    bf16x8 qh[8], ql[8];
+    {
+        const float *qp = q + (int64_t)(tile.x + min(qi, tile.y - 1)) * q_stride + h * HD + half * 64;
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            float v[8];
+            load8(qp + j * 8, v);
+            uint32_t hw[4], lw[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const float a = v[2 * e] * scale_log2e, b = v[2 * e + 1] * scale_log2e;
+                const bf16_t ah = f32_to_bf16(a), bh = f32_to_bf16(b);
+                hw[e] = (uint32_t)ah | ((uint32_t)bh << 16);
+                lw[e] = pack_bf16(a - bf16_to_f32(ah), b - bf16_to_f32(bh));
+            }
+            qh[j] = __builtin_bit_cast(bf16x8, (u32x4){hw[0], hw[1], hw[2], hw[3]});
+            ql[j] = __builtin_bit_cast(bf16x8, (u32x4){lw[0], lw[1], lw[2], lw[3]});
+        }
+    }
+
+    f32x16 o[4];   // O^T: dims 32*nt + 8*(i/4) + 4*half + i%4 of this lane's query
+#pragma unroll
+    for (int nt = 0; nt < 4; nt++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) o[nt][i] = 0.f;
+    float m = -INFINITY, l = 0.f;
+
+    for (int kv0 = 0; kv0 <= wg_last_pos; kv0 += KVB) {
+        // ---- stage V^T of positions kv0 .. kv0+31 (clamped to the last needed position) into LDS
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 2; v++) {
+            const int idx = threadIdx.x + 256 * v;          // 512 pieces of 8 dims
+            const int kv = idx >> 4, d0 = (idx & 15) * 8;
+            const int pos = min(kv0 + kv, wg_last_pos);
+            const bf16_t *src = pool + (int64_t)trow[pos >> 4] * block_stride +
+                                (((int64_t)Hkv + kvh) * 16 + (pos & 15)) * HD + d0;
+            const u32x4 w = *reinterpret_cast<const u32x4 *>(src);
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                vt[d0 + 2 * e][kv] = (bf16_t)(w[e] & 0xffffu);
+                vt[d0 + 2 * e + 1][kv] = (bf16_t)(w[e] >> 16);
+            }
+        }
+        __syncthreads();
+        if (!wave_active || kv0 > wave_last_pos) continue;   // nothing visible to this wave's queries
+
+        // ---- S^T = K Q^T for 32 kv positions x 32 queries
+        f32x16 st;
+#pragma unroll
+        for (int i = 0; i < 16; i++) st[i] = 0.f;
+        {
+            const int pos = min(kv0 + l32, wg_last_pos);
+            const bf16_t *kp = pool + (int64_t)trow[pos >> 4] * block_stride + ((int64_t)kvh * 16 + (pos & 15)) * HD +
+                               half * 64;
+            u32x4 kf[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) kf[j] = *reinterpret_cast<const u32x4 *>(kp + j * 8);
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const bf16x8 ka = __builtin_bit_cast(bf16x8, kf[j]);
+                st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qh[j], st, 0, 0, 0);
+                st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, ql[j], st, 0, 0, 0);
+            }
+        }
+        // ---- online softmax; accumulator element i is kv position kv0 + 8*(i/4) + 4*half + i%4
+        float mb = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const int kv_pos = kv0 + 8 * (i / 4) + 4 * half + (i % 4);
+            const bool ok = q_valid && kv_pos <= q_pos;
+            st[i] = ok ? st[i] : -INFINITY;
+            mb = fmaxf(mb, st[i]);
+        }
+        mb = fmaxf(mb, __shfl_xor(mb, 32, WAVE));
+        const float m_new = fmaxf(m, mb);
+        float sc = 1.f;
+        uint32_t ph[8], pl[8];
+        if (m_new > -INFINITY) {
+            sc = fast_exp2(m - m_new);
+            float psum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const float p0 = fast_exp2(st[i] - m_new), p1 = fast_exp2(st[i + 1] - m_new);
+                psum += p0 + p1;
+                const bf16_t h0 = f32_to_bf16(p0), h1 = f32_to_bf16(p1);
+                ph[i / 2] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                pl[i / 2] = pack_bf16(p0 - bf16_to_f32(h0), p1 - bf16_to_f32(h1));
+            }
+            l = l * sc + psum;
+            m = m_new;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; e++) ph[e] = pl[e] = 0u;
+        }
+        // ---- O^T = O^T * sc + V^T P^T
+#pragma unroll
+        for (int nt = 0; nt < 4; nt++) {
+#pragma unroll
+            for (int i = 0; i < 16; i++) o[nt][i] *= sc;
+#pragma unroll
+            for (int mm = 0; mm < 2; mm++) {
+                // slot e of this lane <-> kv = 16*mm + 8*(e/4) + 4*half + e%4
+                const bf16_t *vp = &vt[nt * 32 + l32][16 * mm + 4 * half];
+                const u32x2 v0 = *reinterpret_cast<const u32x2 *>(vp);
+                const u32x2 v1 = *reinterpret_cast<const u32x2 *>(vp + 8);
+                const bf16x8 va = __builtin_bit_cast(bf16x8, (u32x4){v0[0], v0[1], v1[0], v1[1]});
+                const bf16x8 pbh = __builtin_bit_cast(bf16x8, (u32x4){ph[4 * mm], ph[4 * mm + 1], ph[4 * mm + 2], ph[4 * mm + 3]});
+                const bf16x8 pbl = __builtin_bit_cast(bf16x8, (u32x4){pl[4 * mm], pl[4 * mm + 1], pl[4 * mm + 2], pl[4 * mm + 3]});
+                o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbh, o[nt], 0, 0, 0);
+                o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbl, o[nt], 0, 0, 0);
+            }
+        }
+    }
+    // the two halves of a query's scores were summed separately
+    l += __shfl_xor(l, 32, WAVE);
+    if (q_valid) {
+        const float inv = 1.0f / l;
+        float *op = out + (int64_t)(tile.x + qi) * (H * HD) + h * HD;
+#pragma unroll
+        for (int nt = 0; nt < 4; nt++)
+#pragma unroll
+            for (int a = 0; a < 4; a++) {
+                float4 v = make_float4(o[nt][4 * a] * inv, o[nt][4 * a + 1] * inv, o[nt][4 * a + 2] * inv,
+                                       o[nt][4 * a + 3] * inv);
+                *reinterpret_cast<float4 *>(op + nt * 32 + 8 * a + 4 * half) = v;
+            }
+    }
+}
+
+}  // namespace
+
+namespace ld {
+
+bool prefill_attention_supported(int dtype_is_bf16, int hd) { return dtype_is_bf16 && hd == HD; }
+
+void launch_prefill_attention(const float *q, int q_stride, const uint16_t *pool, int Hkv, const int32_t *table,
+                              int table_stride, const int32_t *tiles, int n_tiles, int H, float *out, hipStream_t s) {
+    const float sl2 = 1.4426950408889634f / sqrtf((float)HD);
+    hipLaunchKernelGGL(k_attn_prefill, dim3(n_tiles, H), dim3(256), 0, s, q, q_stride, pool, Hkv, table, table_stride,
+                       (const int4 *)tiles, H, sl2, out);
+}
+
+}  // namespace ld

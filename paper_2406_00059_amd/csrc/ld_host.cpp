@@ -68,7 +68,7 @@ Workspace plan_workspace(const ld_model &m, char *base, int max_tokens, int max_
     };
     const size_t T = max_tokens;
     w.table = (int32_t *)take((size_t)max_seqs * max_blocks * 4);
-    w.meta = (int32_t *)take(T * 5 * 4);  // tok | pos | seq_slot | ctx_len | emit_row
+    w.meta = (int32_t *)take(T * 9 * 4);  // tok | pos | seq_slot | ctx_len | emit_row | prefill tiles (4 ints each)
     w.out_tok = (int32_t *)take((size_t)max_seqs * 4);
     w.x = (float *)take(T * c.d_model * 4);
     w.qkv = (float *)take(T * m.nqkv() * 4);
@@ -156,7 +156,7 @@ void map_blocks(ld_kv *kv, int s, int64_t need) {
 
 ld_status ensure_pinned(ld_kv *kv) {
     if (kv->pin_meta) return LD_OK;
-    LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_meta, (size_t)kv->max_tokens * 5 * 4, hipHostMallocDefault));
+    LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_meta, (size_t)kv->max_tokens * 9 * 4, hipHostMallocDefault));
     LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_out, (size_t)kv->max_seqs * 4, hipHostMallocDefault));
     LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_table, (size_t)kv->max_seqs * kv->max_blocks * 4, hipHostMallocDefault));
     return LD_OK;
@@ -164,8 +164,10 @@ ld_status ensure_pinned(ld_kv *kv) {
 
 // Runs one pass over `rows` (all rows' blocks are mapped).  emit[i] = index of the row whose
 // logits / greedy token are wanted, in callback order.  On return pin_out[i] holds the tokens.
-ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, const std::vector<int32_t> &emit, hipStream_t st,
-                   float *logits_out) {
+// Rows [0, n_single) are one-row segments (decode rows); the rest form multi-row prefill segments,
+// each a run of consecutive rows of one sequence at consecutive positions.
+ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const std::vector<int32_t> &emit,
+                   hipStream_t st, float *logits_out) {
     const ld_model &m = *kv->m;
     const ld_model_config &c = m.c;
     const int T = (int)rows.size(), R = (int)emit.size();
@@ -184,9 +186,25 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, const std::vector<in
         max_ctx = std::max(max_ctx, rows[t].pos + 1);
     }
     for (int r = 0; r < R; r++) pm[4 * T + r] = emit[r];
-    LD_HIP_TRY(hipMemcpyAsync(w.meta, pm, (size_t)(4 * T + R) * 4, hipMemcpyHostToDevice, st));
+    // prefill tiles: (first row, rows <= 128, first position, sequence) for the rows after the decode rows
+    const bool mfma_attn = c.dtype == LD_BF16 && c.head_dim == 128;
+    int n_tiles = 0;
+    int32_t *pt = pm + 5 * T;
+    if (mfma_attn) {
+        for (int t = n_single; t < T;) {
+            int e = t + 1;
+            while (e < T && e - t < 128 && rows[e].seq == rows[t].seq) e++;
+            pt[4 * n_tiles] = t; pt[4 * n_tiles + 1] = e - t; pt[4 * n_tiles + 2] = rows[t].pos; pt[4 * n_tiles + 3] = rows[t].seq;
+            n_tiles++;
+            t = e;
+        }
+    }
+    const int n_dec_rows = mfma_attn ? n_single : T;   // rows that go through the single-query kernel
+    int max_ctx_dec = 1;
+    for (int t = 0; t < n_dec_rows; t++) max_ctx_dec = std::max(max_ctx_dec, rows[t].pos + 1);
+    LD_HIP_TRY(hipMemcpyAsync(w.meta, pm, (size_t)(5 * T + 4 * n_tiles) * 4, hipMemcpyHostToDevice, st));
     const int32_t *d_tok = w.meta, *d_pos = w.meta + T, *d_slot = w.meta + 2 * T, *d_ctx = w.meta + 3 * T,
-                  *d_emit = w.meta + 4 * T;
+                  *d_emit = w.meta + 4 * T, *d_tiles = w.meta + 5 * T;
 
     // block-table rows that changed since the last pass
     for (int t = 0; t < T; t++) {
@@ -227,8 +245,13 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, const std::vector<in
         void *pool_l = kv->pool + (size_t)l * layer_bytes;
         LD_TIMED(LD_PROF_QKV, ldk_qkv_rope(m.wqkv[l], c.dtype, w.x, m.attn_norm[l], c.rms_eps, w.qkv, w.cos_sin, d_pos,
                                            d_slot, w.table, kv->max_blocks, pool_l, T, d, H, Hkv, hd, w.lin_scratch, w.lin_scratch_bytes, st));
-        LD_TIMED(LD_PROF_ATTENTION, ldk_paged_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot, d_ctx, max_ctx, T,
-                                   H, Hkv, hd, w.attn, w.att_scratch, w.att_scratch_bytes, st));
+        if (n_dec_rows)
+            LD_TIMED(LD_PROF_ATTENTION, ldk_paged_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot, d_ctx,
+                                                            max_ctx_dec, n_dec_rows, H, Hkv, hd, w.attn, w.att_scratch,
+                                                            w.att_scratch_bytes, st));
+        if (n_tiles)
+            LD_TIMED(LD_PROF_ATTENTION, ldk_prefill_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_tiles,
+                                                              n_tiles, H, Hkv, hd, w.attn, st));
         LD_TIMED(LD_PROF_WO, ldk_linear(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st));
         LD_TIMED(LD_PROF_GATE_UP, ldk_linear(m.wgate_up[l], c.dtype, w.x, m.ffn_norm[l], c.rms_eps, T, c.d_ffn, d, LDK_SWIGLU, w.act, w.lin_scratch,
                                                w.lin_scratch_bytes, st));
@@ -283,20 +306,29 @@ ld_status run_step(ld_kv *kv, const std::vector<Feed> &feeds, void *stream, ld_t
     if ((int64_t)feeds.size() > kv->max_seqs) return fail(LD_E_RANGE, "too many sequences in one step");
     if (total_missing > (int64_t)kv->free_stack.size()) { ld::set_error("%s: out of KV blocks (%lld needed, %zu free)", who, (long long)total_missing, kv->free_stack.size()); return LD_E_NOMEM; }
 
-    // --- reserve blocks (in argument order, logical order within a sequence) and build rows
+    // --- reserve blocks (in argument order, logical order within a sequence) and build rows:
+    //     one-row feeds first (decode rows), then the multi-row prefill segments
     std::vector<Row> rows;
-    std::vector<int32_t> emit;
+    std::vector<int32_t> emit(feeds.size());
     rows.reserve(total_rows);
     for (const Feed &f : feeds) {
         Seq &q = kv->seqs[f.seq];
-        const int64_t n_rows = f.n + (q.has_pending ? 1 : 0);
-        map_blocks(kv, f.seq, blocks_for(kv, q.n_cached + n_rows));
-        int32_t pos = (int32_t)q.n_cached;
-        if (q.has_pending) rows.push_back({q.pending, pos++, f.seq});
-        for (int i = 0; i < f.n; i++) rows.push_back({f.tokens[i], pos++, f.seq});
-        emit.push_back((int32_t)rows.size() - 1);
+        map_blocks(kv, f.seq, blocks_for(kv, q.n_cached + f.n + (q.has_pending ? 1 : 0)));
     }
-    ld_status rc = run_pass(kv, rows, emit, (hipStream_t)stream, logits_out);
+    int n_single = 0;
+    for (int pass = 0; pass < 2; pass++)
+        for (size_t i = 0; i < feeds.size(); i++) {
+            const Feed &f = feeds[i];
+            Seq &q = kv->seqs[f.seq];
+            const int64_t n_rows = f.n + (q.has_pending ? 1 : 0);
+            if ((n_rows == 1) != (pass == 0)) continue;
+            int32_t pos = (int32_t)q.n_cached;
+            if (q.has_pending) rows.push_back({q.pending, pos++, f.seq});
+            for (int k = 0; k < f.n; k++) rows.push_back({f.tokens[k], pos++, f.seq});
+            emit[i] = (int32_t)rows.size() - 1;
+            if (pass == 0) n_single++;
+        }
+    ld_status rc = run_pass(kv, rows, n_single, emit, (hipStream_t)stream, logits_out);
     if (rc) return rc;
 
     // --- commit state, then hand the tokens over
@@ -503,7 +535,7 @@ ld_status ld_prefill(ld_kv *kv, ld_seq seq, const int32_t *tokens, int32_t n, vo
         if (q->has_pending) rows.push_back({q->pending, pos++, seq});
         while ((int)rows.size() < chunk) rows.push_back({tokens[consumed++], pos++, seq});
         std::vector<int32_t> emit;  // none
-        ld_status rc = run_pass(kv, rows, emit, (hipStream_t)stream, nullptr);
+        ld_status rc = run_pass(kv, rows, 0, emit, (hipStream_t)stream, nullptr);
         if (rc) return rc;
         q->n_cached += rows.size();
         q->has_pending = false; q->pending = -1;

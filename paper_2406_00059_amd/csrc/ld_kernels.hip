@@ -6,6 +6,7 @@
 #include "ld_device.h"
 #include "ld_gemv.h"
 #include "ld_gemm.h"
+#include "ld_attn_prefill.h"
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -531,6 +532,19 @@ ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool
     else return ld::fail(LD_E_INVAL, "ldk_paged_attention: bad dtype");
 #undef LD_ATT
     return launched("k_attn");
+}
+
+ld_status ldk_prefill_attention(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
+                                const int32_t *table, int32_t table_stride, const int32_t *tiles, int32_t n_tiles,
+                                int32_t H, int32_t Hkv, int32_t hd, float *out, void *stream) {
+    if (!q || !pool_layer || !table || !tiles || !out || n_tiles < 0 || H <= 0 || Hkv <= 0 || H % Hkv || q_stride % 4)
+        return ld::fail(LD_E_INVAL, "ldk_prefill_attention: bad argument");
+    if (!ld::prefill_attention_supported(dtype == LD_BF16, hd))
+        return ld::fail(LD_E_INVAL, "ldk_prefill_attention: needs a bf16 pool and head_dim 128");
+    if (n_tiles == 0) return LD_OK;
+    ld::launch_prefill_attention(q, q_stride, (const uint16_t *)pool_layer, Hkv, table, table_stride, tiles, n_tiles, H,
+                                 out, (hipStream_t)stream);
+    return launched("k_attn_prefill");
 }
 
 ld_status ldk_argmax(const float *logits, int32_t R, int32_t V, int32_t *out, void *stream) {

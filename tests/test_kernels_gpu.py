@@ -285,3 +285,31 @@ def test_linear_matrix_core_7b_shapes_sampled():
                         a = oracle.silu(a) * oracle.matvec(wu, xh[t])[0]
                     # two-term bf16 split of the activations: ~2^-17 per element, random-walk over K terms
                     assert abs(yh[t, n] - a) <= 1e-4 * max(1.0, abs(a)), (T, N, t, n, yh[t, n], a)
+
+
+@pytest.mark.parametrize("H,Hkv", [(4, 4), (8, 2)])
+def test_prefill_attention_segments(H, Hkv):
+    """Chunk-prefill attention (matrix cores): segments of different sequences, a fresh prompt (position 0),
+    an observation appended to a long context, a segment longer than one 128-row tile; causal inside
+    the chunk; permuted block table.  Every row against the oracle's single-query attention."""
+    hd = 128
+    segs = [(37, 100), (0, 5), (1000, 300), (255, 1), (16, 32)]          # (first position, rows) per sequence
+    lens = [p + n for p, n in segs]
+    table, pool, _ = _attention_case(31, lens, H, Hkv, hd, "bf16")
+    T = sum(n for _, n in segs)
+    q = gen.normal(31, 9, (T, H, hd), device=DEV)
+    tiles, row_seq, row_pos, r = [], [], [], 0
+    for s, (p0, n) in enumerate(segs):
+        for off in range(0, n, 128):
+            tiles.append([r + off, min(128, n - off), p0 + off, s])
+        row_seq += [s] * n; row_pos += list(range(p0, p0 + n)); r += n
+    out = torch.zeros(T, H, hd, device=DEV)
+    ld.ldk_prefill_attention(q, H * hd, pool, table.to(DEV), torch.tensor(tiles, dtype=torch.int32, device=DEV),
+                             H, Hkv, hd, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    ph = oracle.to_host_matrix(pool.reshape(pool.shape[0], -1)).reshape(-1)
+    ref = oracle.paged_attention(q.cpu().numpy(), ph, ph[Hkv * 16 * hd:], (2 * Hkv * 16 * hd, 16 * hd, hd),
+                                 table.numpy()[row_seq], [p + 1 for p in row_pos], Hkv)
+    err = np.max(np.abs(got - ref), axis=(1, 2)) / np.abs(ref).max()
+    assert err.max() <= 3e-5, (err.max(), int(err.argmax()), row_pos[int(err.argmax())])

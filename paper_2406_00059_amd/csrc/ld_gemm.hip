@@ -22,6 +22,7 @@
 #include "ld_gemm.h"
 #include "ld_device.h"
 #include <algorithm>
+#include <cstdlib>
 
 using namespace ldd;
 
@@ -31,10 +32,9 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // native 16-byte vector (keeps arrays of it in registers)
 
-constexpr int KC = 128;          // K chunk staged in LDS
+constexpr int KC = 128;          // K granularity the launcher requires (largest chunk any variant stages)
 constexpr int XPAD = 8;          // bf16 elements of row padding in LDS
 constexpr int NW = 4;            // waves per workgroup
-constexpr int N_TILE = 32 * NW;  // output columns per workgroup
 
 __global__ __launch_bounds__(256) void k_norm_split(const float *__restrict__ x, const float *__restrict__ g,
                                                     float eps, int K, bf16_t *__restrict__ hi,
@@ -74,74 +74,80 @@ __global__ __launch_bounds__(256) void k_norm_split(const float *__restrict__ x,
     }
 }
 
-// TT: token tiles of 32 per workgroup.  WR: W fragments per wave (2 for SwiGLU: gate and up rows).
-template <int TT, int EPI>
+// TT: token tiles of 32 rows per workgroup.  WC: 32-column tiles per wave.  KCH: K chunk staged in LDS.
+// A wave multiplies TT x WF accumulator tiles per k-step, WF = WC (x 2 for SwiGLU: gate and up rows).
+template <int TT, int WC, int KCH, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
                                                    const bf16_t *__restrict__ xlo, int T, int N, int K,
                                                    float *__restrict__ y, int n_ttiles, int ks,
                                                    float *__restrict__ partial) {
     constexpr int WR = (EPI == ld::GEMM_SWIGLU) ? 2 : 1;
+    constexpr int WF = WC * WR;                          // W fragments per wave per k-step
     constexpr int TROWS = TT * 32;
-    constexpr int XLD = KC + XPAD;                       // LDS row stride in elements
-    constexpr int XV = TROWS * (KC / 8) * 2 / 256;       // u32x4 per thread to stage one chunk (hi + lo)
+    constexpr int NT = 32 * WC * NW;                     // output columns per workgroup
+    constexpr int XLD = KCH + XPAD;                      // LDS row stride in elements
+    constexpr int XV = TROWS * (KCH / 8) * 2 / 256;      // 16-byte pieces per thread to stage one chunk (hi + lo)
+    constexpr int KG = KCH / 64;                         // 64-wide k-groups per chunk
     __shared__ __attribute__((aligned(16))) bf16_t xs[2][TROWS][XLD];
 
     // XCD-aware decode of the linear block id: blocks b, b+8, b+16, ... run on the same XCD
     const int b = blockIdx.x, xcd = b & 7, s = b >> 3;
     const int kz = s % ks, tt_idx = (s / ks) % n_ttiles, nb = (s / (ks * n_ttiles)) * 8 + xcd;
-    const int n_nblocks = (N + N_TILE - 1) / N_TILE;
+    const int n_nblocks = (N + NT - 1) / NT;
     if (nb >= n_nblocks) return;
     const int t0 = tt_idx * TROWS;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
-    const int n0 = nb * N_TILE + wave * 32;
+    const int n0 = nb * NT + wave * (32 * WC);
 
-    // W rows of this lane (clamped in range; out-of-range columns are never stored)
-    const bf16_t *wrow[WR];
+    // W rows of this lane (clamped in range; out-of-range columns are never stored); fragment f = c * WR + r
+    const bf16_t *wrow[WF];
 #pragma unroll
-    for (int r = 0; r < WR; r++) {
-        const int n = min(n0 + l32, N - 1);
-        wrow[r] = W + ((int64_t)r * N + n) * K + half * 32;
-    }
-    // staging assignment: u32x4 index v -> (part, row, col16)
+    for (int c = 0; c < WC; c++)
+#pragma unroll
+        for (int r = 0; r < WR; r++) {
+            const int n = min(n0 + c * 32 + l32, N - 1);
+            wrow[c * WR + r] = W + ((int64_t)r * N + n) * K + half * 32;
+        }
+    // staging assignment: piece v -> (part, row, col16)
     int st_row[XV], st_c16[XV], st_part[XV];
     const bf16_t *st_src[XV];
 #pragma unroll
     for (int v = 0; v < XV; v++) {
         const int idx = threadIdx.x + 256 * v;
-        st_part[v] = idx / (TROWS * (KC / 8));
-        const int rem = idx % (TROWS * (KC / 8));
-        st_row[v] = rem / (KC / 8);
-        st_c16[v] = rem % (KC / 8);
+        st_part[v] = idx / (TROWS * (KCH / 8));
+        const int rem = idx % (TROWS * (KCH / 8));
+        st_row[v] = rem / (KCH / 8);
+        st_c16[v] = rem % (KCH / 8);
         const int t = min(t0 + st_row[v], T - 1);        // rows past T are staged from row T-1 and never stored
         st_src[v] = (st_part[v] ? xlo : xhi) + (int64_t)t * K + st_c16[v] * 8;
     }
 
-    f32x16 acc[WR][TT];
+    f32x16 acc[WF][TT];
 #pragma unroll
-    for (int r = 0; r < WR; r++)
+    for (int f = 0; f < WF; f++)
 #pragma unroll
         for (int tt = 0; tt < TT; tt++)
 #pragma unroll
-            for (int i = 0; i < 16; i++) acc[r][tt][i] = 0.f;
+            for (int i = 0; i < 16; i++) acc[f][tt][i] = 0.f;
 
-    u32x4 wA[WR][8], wB[WR][8], xr[XV];
-    auto load_w = [&](u32x4 (&w)[WR][8], int kc) {
+    u32x4 wA[WF][KG * 4], wB[WF][KG * 4], xr[XV];
+    auto load_w = [&](u32x4 (&w)[WF][KG * 4], int kc) {
 #pragma unroll
-        for (int r = 0; r < WR; r++)
+        for (int f = 0; f < WF; f++)
 #pragma unroll
-            for (int kg = 0; kg < 2; kg++)
+            for (int kg = 0; kg < KG; kg++)
 #pragma unroll
                 for (int j = 0; j < 4; j++)
-                    w[r][kg * 4 + j] = *reinterpret_cast<const u32x4 *>(wrow[r] + kc * KC + kg * 64 + j * 8);
+                    w[f][kg * 4 + j] = *reinterpret_cast<const u32x4 *>(wrow[f] + kc * KCH + kg * 64 + j * 8);
     };
     auto load_x = [&](u32x4 (&xv)[XV], int kc) {
 #pragma unroll
-        for (int v = 0; v < XV; v++) xv[v] = *reinterpret_cast<const u32x4 *>(st_src[v] + kc * KC);
+        for (int v = 0; v < XV; v++) xv[v] = *reinterpret_cast<const u32x4 *>(st_src[v] + kc * KCH);
     };
-    auto compute = [&](u32x4 (&w)[WR][8]) {
+    auto compute = [&](u32x4 (&w)[WF][KG * 4]) {
 #pragma unroll
-        for (int kg = 0; kg < 2; kg++)
+        for (int kg = 0; kg < KG; kg++)
 #pragma unroll
             for (int j = 0; j < 4; j++) {
                 const int k = kg * 64 + half * 32 + j * 8;
@@ -150,10 +156,10 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t *__restrict__ W,
                     const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[0][tt * 32 + l32][k]));
                     const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[1][tt * 32 + l32][k]));
 #pragma unroll
-                    for (int r = 0; r < WR; r++) {
-                        const bf16x8 bw = __builtin_bit_cast(bf16x8, w[r][kg * 4 + j]);
-                        acc[r][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bw, acc[r][tt], 0, 0, 0);
-                        acc[r][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bw, acc[r][tt], 0, 0, 0);
+                    for (int f = 0; f < WF; f++) {
+                        const bf16x8 bw = __builtin_bit_cast(bf16x8, w[f][kg * 4 + j]);
+                        acc[f][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bw, acc[f][tt], 0, 0, 0);
+                        acc[f][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bw, acc[f][tt], 0, 0, 0);
                     }
                 }
             }
@@ -164,8 +170,8 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t *__restrict__ W,
             *reinterpret_cast<u32x4 *>(&xs[st_part[v]][st_row[v]][st_c16[v] * 8]) = xv[v];
     };
 
-    // this workgroup's K slab: chunks [c_begin, n_chunks) of K / KC, split evenly over ks workgroups
-    const int c_begin = (int)((int64_t)kz * (K / KC) / ks), n_chunks = (int)((int64_t)(kz + 1) * (K / KC) / ks);
+    // this workgroup's K slab: chunks [c_begin, n_chunks) of K / KCH, split evenly over ks workgroups
+    const int c_begin = (int)((int64_t)kz * (K / KCH) / ks), n_chunks = (int)((int64_t)(kz + 1) * (K / KCH) / ks);
     load_x(xr, c_begin);
     load_w(wA, c_begin);
     for (int kc = c_begin; kc < n_chunks; kc += 2) {
@@ -183,35 +189,28 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t *__restrict__ W,
         }
     }
 
-    // accumulator element i of lane (l32, half): token t0 + tt*32 + 8*(i/4) + 4*half + i%4, column n0 + l32
-    const int n = n0 + l32;
-    if (ks > 1) {
-        // split-K: raw partial sums, [kz][t][r * N + n]; a second kernel adds the slabs in fixed order
-        if (n < N) {
+    // accumulator element i of lane (l32, half): token t0 + tt*32 + 8*(i/4) + 4*half + i%4, column n0 + 32c + l32
 #pragma unroll
-            for (int r = 0; r < WR; r++)
-#pragma unroll
-                for (int tt = 0; tt < TT; tt++)
-#pragma unroll
-                    for (int i = 0; i < 16; i++) {
-                        const int t = t0 + tt * 32 + 8 * (i / 4) + 4 * half + (i % 4);
-                        if (t < T) partial[((int64_t)kz * T + t) * (WR * N) + r * N + n] = acc[r][tt][i];
-                    }
-        }
-        return;
-    }
-    if (n < N) {
+    for (int c = 0; c < WC; c++) {
+        const int n = n0 + c * 32 + l32;
+        if (n >= N) continue;
 #pragma unroll
         for (int tt = 0; tt < TT; tt++)
 #pragma unroll
             for (int i = 0; i < 16; i++) {
                 const int t = t0 + tt * 32 + 8 * (i / 4) + 4 * half + (i % 4);
-                if (t < T) {
+                if (t >= T) continue;
+                if (ks > 1) {
+                    // split-K: raw partial sums, [kz][t][r * N + n]; a second kernel adds the slabs in fixed order
+#pragma unroll
+                    for (int r = 0; r < WR; r++)
+                        partial[((int64_t)kz * T + t) * (WR * N) + r * N + n] = acc[c * WR + r][tt][i];
+                } else {
                     float *dst = y + (int64_t)t * N + n;
-                    if constexpr (EPI == ld::GEMM_STORE) *dst = acc[0][tt][i];
-                    else if constexpr (EPI == ld::GEMM_ADD) *dst += acc[0][tt][i];
+                    if constexpr (EPI == ld::GEMM_STORE) *dst = acc[c][tt][i];
+                    else if constexpr (EPI == ld::GEMM_ADD) *dst += acc[c][tt][i];
                     else {
-                        const float gate = acc[0][tt][i], up = acc[1][tt][i];
+                        const float gate = acc[c * WR][tt][i], up = acc[c * WR + 1][tt][i];
                         *dst = gate / (1.0f + __expf(-gate)) * up;
                     }
                 }
@@ -238,34 +237,50 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__
     else y[idx] = a / (1.0f + __expf(-a)) * b;
 }
 
-int split_factor(int T, int N, int K, int tt_rows) {
-    const int n_ttiles = (T + tt_rows - 1) / tt_rows, n_nblocks = (N + N_TILE - 1) / N_TILE;
+// Tile shape by row count: up to 32 rows -> 32 x 128 tile, 128-wide K chunks (weight-stream bound);
+// up to 64 rows -> 64 x 128; more -> 128 rows x 256 columns (128 for SwiGLU), 64-wide K chunks.
+struct Shape { int tt, wc, kch; };
+int env_int(const char *name, int dflt) {
+    const char *v = getenv(name);
+    return v ? atoi(v) : dflt;
+}
+Shape pick_shape(int T, int epi) {
+    static const int big_from = env_int("LD_GEMM_BIG_FROM", 65);   // tuning knob: rows from which the big tile is used
+    if (T <= 32) return {1, 1, 128};
+    if (T < big_from) return {2, 1, 128};
+    return {4, epi == ld::GEMM_SWIGLU ? 1 : 2, 64};
+}
+
+int split_factor(int T, int N, int K, int epi) {
+    const Shape sh = pick_shape(T, epi);
+    const int n_ttiles = (T + sh.tt * 32 - 1) / (sh.tt * 32), n_nblocks = (N + 128 * sh.wc - 1) / (128 * sh.wc);
     const int wgs = n_ttiles * n_nblocks;
-    int ks = (768 + wgs - 1) / wgs;          // aim at ~3 workgroups per CU
-    ks = std::min(ks, K / KC / 2);           // at least two chunks per slab
+    int ks = (768 + wgs - 1) / wgs;               // aim at ~3 workgroups per CU
+    ks = std::min(ks, K / sh.kch / 2);            // at least two chunks per slab
+    ks = std::min(ks, K / (8 * T));               // partial sums: at most a quarter of the matrix bytes
     ks = std::min(ks, 32);
     return std::max(ks, 1);
 }
 
-template <int TT>
-void launch_tt(const bf16_t *W, const bf16_t *xs, int T, int N, int K, int epi, float *y, float *partial,
-               hipStream_t s) {
+template <int TT, int WC, int KCH>
+void launch_shape(const bf16_t *W, const bf16_t *xs, int T, int N, int K, int epi, float *y, float *partial,
+                  hipStream_t s) {
     const int n_ttiles = (T + TT * 32 - 1) / (TT * 32);
-    const int n_nblocks = (N + N_TILE - 1) / N_TILE;
-    const int ks = split_factor(T, N, K, TT * 32);
+    const int n_nblocks = (N + 128 * WC - 1) / (128 * WC);
+    const int ks = split_factor(T, N, K, epi);
     const int grid = ((n_nblocks + 7) / 8) * 8 * n_ttiles * ks;
     const bf16_t *hi = xs, *lo = xs + (size_t)T * K;
     const int rgrid = (int)(((int64_t)T * N + 255) / 256);
-    if (epi == ld::GEMM_STORE) {
-        hipLaunchKernelGGL((k_gemm_mfma<TT, ld::GEMM_STORE>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, n_ttiles, ks, partial);
-        if (ks > 1) hipLaunchKernelGGL((k_splitk_reduce<ld::GEMM_STORE>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
-    } else if (epi == ld::GEMM_ADD) {
-        hipLaunchKernelGGL((k_gemm_mfma<TT, ld::GEMM_ADD>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, n_ttiles, ks, partial);
-        if (ks > 1) hipLaunchKernelGGL((k_splitk_reduce<ld::GEMM_ADD>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
-    } else {
-        hipLaunchKernelGGL((k_gemm_mfma<TT, ld::GEMM_SWIGLU>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, n_ttiles, ks, partial);
-        if (ks > 1) hipLaunchKernelGGL((k_splitk_reduce<ld::GEMM_SWIGLU>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
-    }
+#define LD_GEMM(EPI_)                                                                                                  \
+    do {                                                                                                               \
+        hipLaunchKernelGGL((k_gemm_mfma<TT, WC, KCH, EPI_>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, n_ttiles, \
+                           ks, partial);                                                                               \
+        if (ks > 1) hipLaunchKernelGGL((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);   \
+    } while (0)
+    if (epi == ld::GEMM_STORE) LD_GEMM(ld::GEMM_STORE);
+    else if (epi == ld::GEMM_ADD) LD_GEMM(ld::GEMM_ADD);
+    else if constexpr (WC == 1) LD_GEMM(ld::GEMM_SWIGLU);   // SwiGLU always runs with one column tile per wave
+#undef LD_GEMM
 }
 
 }  // namespace
@@ -274,12 +289,10 @@ namespace ld {
 
 bool gemm_supported(int T, int N, int K) { return T >= 2 && N > 0 && K > 0 && K % KC == 0; }
 
-static int tile_rows(int T) { return T <= 32 ? 32 : 64; }
-
 size_t gemm_split_bytes(int T, int K) { return (((size_t)2 * T * K * sizeof(bf16_t)) + 255) / 256 * 256; }
 
 size_t gemm_scratch_bytes(int T, int N, int K, int epi) {
-    const int ks = split_factor(T, N, K, tile_rows(T));
+    const int ks = split_factor(T, N, K, epi);
     const size_t part = ks > 1 ? (size_t)ks * T * N * (epi == GEMM_SWIGLU ? 2 : 1) * sizeof(float) : 0;
     return gemm_split_bytes(T, K) + part;
 }
@@ -290,8 +303,11 @@ void launch_norm_split(const float *x, const float *g, float eps, int T, int K, 
 
 void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s) {
     float *partial = (float *)((char *)xs + gemm_split_bytes(T, K));
-    if (tile_rows(T) == 32) launch_tt<1>(W, xs, T, N, K, epi, y, partial, s);
-    else launch_tt<2>(W, xs, T, N, K, epi, y, partial, s);
+    const Shape sh = pick_shape(T, epi);
+    if (sh.tt == 1) launch_shape<1, 1, 128>(W, xs, T, N, K, epi, y, partial, s);
+    else if (sh.tt == 2) launch_shape<2, 1, 128>(W, xs, T, N, K, epi, y, partial, s);
+    else if (sh.wc == 1) launch_shape<4, 1, 64>(W, xs, T, N, K, epi, y, partial, s);
+    else launch_shape<4, 2, 64>(W, xs, T, N, K, epi, y, partial, s);
 }
 
 }  // namespace ld

@@ -35,6 +35,10 @@ def parse():
     ap.add_argument("--profile-steps", type=int, default=32, help="extra steps run with per-kernel events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-batch32", action="store_true", help="skip the batch-32 continuous-batching leg")
+    ap.add_argument("--only-batch32", action="store_true", help="debug: run only the batch-32 leg (prints its dict)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 256 MiB device-to-device copy (a plain copy kernel of known size, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is NOT the benchmark)")
     return ap.parse_args()
 
@@ -147,10 +151,28 @@ def run_batch1(args, ld, torch, shape, weights, model):
                 kernels[name]["GBps"] = round(alg_bytes[name] / (avg * 1e-3) / 1e9, 1)
     per_step_ms = {k: v[0] / args.profile_steps for k, v in prof.items()}
     dominant = max((k for k in per_step_ms if k in alg_bytes), key=lambda k: per_step_ms[k])
-    avg_s = prof[dominant][0] / prof[dominant][1] * 1e-3
-    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(alg_bytes[dominant] / avg_s / 1e9, 1),
+    # Launch duration of the dominant kernel (the gate/up projection with fused RMSNorm + SwiGLU): the same
+    # launch the step makes, on every layer's weights in turn (13.2 GB apart in total, so nothing is served
+    # from cache), between ONE pair of HIP events on the step's stream; repeated, mean over all launches.
+    assert dominant == "gate_up", dominant
+    xin = torch.randn(1, d, device="cuda"); yout = torch.empty(1, f, device="cuda")
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    L = shape.n_layers
+    for l in range(L):
+        ld.ldk_linear(weights["wgate_up"][l], xin, yout, ld.LDK_SWIGLU, g=weights["ffn_norm"][l], eps=shape.rms_eps)
+    reps = 8
+    ev0.record(stream)
+    for _ in range(reps):
+        for l in range(L):
+            ld.ldk_linear(weights["wgate_up"][l], xin, yout, ld.LDK_SWIGLU, g=weights["ffn_norm"][l], eps=shape.rms_eps)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    avg_s = ev0.elapsed_time(ev1) * 1e-3 / (reps * L)
+    roofline = {"bound": "hbm", "kernel": "k_gemv1 (gate/up projection, fused RMSNorm + SwiGLU)",
+                "achieved": round(alg_bytes[dominant] / avg_s / 1e9, 1),
                 "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": round(alg_bytes[dominant] / avg_s / HBM_PEAK, 4),
-                "traffic": None, "avg_launch_us": round(avg_s * 1e6, 2), "bytes_per_launch": alg_bytes[dominant]}
+                "traffic": None, "avg_launch_us": round(avg_s * 1e6, 2), "bytes_per_launch": alg_bytes[dominant],
+                "launches_timed": reps * L, "share_of_step": round(per_step_ms[dominant] / sum(per_step_ms.values()), 3)}
     out = {
         "value": K / dec_s, "ms_per_step": statistics.mean(step_ms),
         "ms_per_step_median": statistics.median(step_ms),
@@ -255,6 +277,16 @@ def main():
     weights = make_weights(shape, SEED_BASE + 2, device="cuda")
     model = ld.Model(shape, weights, max_chunk=CHUNK)
 
+    if args.calibrate_copy:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        b = torch.empty_like(a)
+        for _ in range(4):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+    if args.only_batch32:
+        print(json.dumps(run_batch32(args, ld, torch, shape, model)))
+        return
     res = run_batch1(args, ld, torch, shape, weights, model)
     b32 = None if args.no_batch32 else run_batch32(args, ld, torch, shape, model)
     cpu = None

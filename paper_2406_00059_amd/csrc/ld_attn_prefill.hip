@@ -87,9 +87,14 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
         for (int i = 0; i < 16; i++) o[nt][i] = 0.f;
     float m = -INFINITY, l = 0.f;
 
-    for (int kv0 = 0; kv0 <= wg_last_pos; kv0 += KVB) {
-        // ---- stage V^T of positions kv0 .. kv0+31 (clamped to the last needed position) into LDS
-        __syncthreads();
+    // K operand rows and V pieces of one 32-position step, loaded one step ahead of their use
+    auto load_k = [&](u32x4 (&kf)[8], int kv0) {
+        const int pos = min(kv0 + l32, wg_last_pos);
+        const bf16_t *kp = pool + (int64_t)trow[pos >> 4] * block_stride + ((int64_t)kvh * 16 + (pos & 15)) * HD + half * 64;
+#pragma unroll
+        for (int j = 0; j < 8; j++) kf[j] = *reinterpret_cast<const u32x4 *>(kp + j * 8);
+    };
+    auto load_v = [&](u32x4 (&vr)[2], int kv0) {
 #pragma unroll
         for (int v = 0; v < 2; v++) {
             const int idx = threadIdx.x + 256 * v;          // 512 pieces of 8 dims
@@ -97,33 +102,46 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
             const int pos = min(kv0 + kv, wg_last_pos);
             const bf16_t *src = pool + (int64_t)trow[pos >> 4] * block_stride +
                                 (((int64_t)Hkv + kvh) * 16 + (pos & 15)) * HD + d0;
-            const u32x4 w = *reinterpret_cast<const u32x4 *>(src);
+            vr[v] = *reinterpret_cast<const u32x4 *>(src);
+        }
+    };
+    u32x4 kf[8], kn[8], vr[2];
+    load_k(kf, 0);
+    load_v(vr, 0);
+
+    for (int kv0 = 0; kv0 <= wg_last_pos; kv0 += KVB) {
+        // ---- stage V^T of positions kv0 .. kv0+31 (clamped to the last needed position) into LDS
+        lds_barrier();
+#pragma unroll
+        for (int v = 0; v < 2; v++) {
+            const int idx = threadIdx.x + 256 * v;
+            const int kv = idx >> 4, d0 = (idx & 15) * 8;
 #pragma unroll
             for (int e = 0; e < 4; e++) {
-                vt[d0 + 2 * e][kv] = (bf16_t)(w[e] & 0xffffu);
-                vt[d0 + 2 * e + 1][kv] = (bf16_t)(w[e] >> 16);
+                vt[d0 + 2 * e][kv] = (bf16_t)(vr[v][e] & 0xffffu);
+                vt[d0 + 2 * e + 1][kv] = (bf16_t)(vr[v][e] >> 16);
             }
         }
-        __syncthreads();
-        if (!wave_active || kv0 > wave_last_pos) continue;   // nothing visible to this wave's queries
+        lds_barrier();
+        const bool more = kv0 + KVB <= wg_last_pos;
+        if (more) { load_k(kn, kv0 + KVB); load_v(vr, kv0 + KVB); }
+        if (!wave_active || kv0 > wave_last_pos) {   // nothing visible to this wave's queries
+            if (more) {
+#pragma unroll
+                for (int j = 0; j < 8; j++) kf[j] = kn[j];
+            }
+            continue;
+        }
 
         // ---- S^T = K Q^T for 32 kv positions x 32 queries
         f32x16 st;
 #pragma unroll
         for (int i = 0; i < 16; i++) st[i] = 0.f;
-        {
-            const int pos = min(kv0 + l32, wg_last_pos);
-            const bf16_t *kp = pool + (int64_t)trow[pos >> 4] * block_stride + ((int64_t)kvh * 16 + (pos & 15)) * HD +
-                               half * 64;
-            u32x4 kf[8];
 #pragma unroll
-            for (int j = 0; j < 8; j++) kf[j] = *reinterpret_cast<const u32x4 *>(kp + j * 8);
-#pragma unroll
-            for (int j = 0; j < 8; j++) {
-                const bf16x8 ka = __builtin_bit_cast(bf16x8, kf[j]);
-                st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qh[j], st, 0, 0, 0);
-                st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, ql[j], st, 0, 0, 0);
-            }
+        for (int j = 0; j < 8; j++) {
+            const bf16x8 ka = __builtin_bit_cast(bf16x8, kf[j]);
+            st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qh[j], st, 0, 0, 0);
+            st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, ql[j], st, 0, 0, 0);
         }
         // ---- online softmax; accumulator element i is kv position kv0 + 8*(i/4) + 4*half + i%4
         float mb = -INFINITY;
@@ -172,6 +190,10 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
                 o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbh, o[nt], 0, 0, 0);
                 o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbl, o[nt], 0, 0, 0);
             }
+        }
+        if (more) {
+#pragma unroll
+            for (int j = 0; j < 8; j++) kf[j] = kn[j];
         }
     }
     // the two halves of a query's scores were summed separately

@@ -46,6 +46,40 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// 16-byte load of data that is read exactly once (weights, cached keys/values): the non-temporal hint
+// keeps the stream from displacing reusable lines in the caches.
+__device__ __forceinline__ u32x4_t load_stream16(const void *p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+}
+
+// load8 with the streaming hint (bf16: one 16-byte load; float: two).
+__device__ __forceinline__ void load8_stream(const bf16_t *p, float (&v)[8]) {
+    const u32x4_t u = load_stream16(p);
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        v[2 * i] = __uint_as_float(u[i] << 16);
+        v[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void load8_stream(const float *p, float (&v)[8]) {
+    const u32x4_t a = load_stream16(p), b = load_stream16(p + 4);
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        v[i] = __uint_as_float(a[i]);
+        v[4 + i] = __uint_as_float(b[i]);
+    }
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also carries a memory fence, which
+// on this target waits for every outstanding global load (vmcnt(0)) and so drains loads that were
+// issued ahead on purpose; this one waits for the LDS/scalar counter only and leaves them in flight.
+// Use it only where the data exchanged between waves goes through LDS.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 

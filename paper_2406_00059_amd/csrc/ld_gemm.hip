@@ -175,15 +175,15 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t *__restrict__ W,
     load_x(xr, c_begin);
     load_w(wA, c_begin);
     for (int kc = c_begin; kc < n_chunks; kc += 2) {
-        __syncthreads();                 // everyone finished reading the previous chunk from LDS
+        lds_barrier();                 // everyone finished reading the previous chunk from LDS
         stage(xr);
-        __syncthreads();
+        lds_barrier();
         if (kc + 1 < n_chunks) { load_x(xr, kc + 1); load_w(wB, kc + 1); }
         compute(wA);
         if (kc + 1 < n_chunks) {
-            __syncthreads();
+            lds_barrier();
             stage(xr);
-            __syncthreads();
+            lds_barrier();
             if (kc + 2 < n_chunks) { load_x(xr, kc + 2); load_w(wA, kc + 2); }
             compute(wB);
         }
@@ -215,6 +215,78 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t *__restrict__ W,
                     }
                 }
             }
+    }
+}
+
+// Up to 32 rows (decode batches): the weight stream is everything, so a workgroup takes 128 rows of W and
+// a 512-wide K slab, requests its whole W slab at once (32 independent 16-byte loads per lane), stages the
+// matching X slab (hi and lo) in LDS meanwhile, and only then starts multiplying: one memory round trip
+// per workgroup, no barrier inside the product loop.  Every (slab, row) partial sum goes to scratch and
+// k_splitk_reduce adds the slabs in fixed order (for SwiGLU the gate and up rows are plain rows here and
+// are paired by the reduce kernel).
+constexpr int SL = 512;   // K slab per workgroup
+
+__global__ __launch_bounds__(256, 2) void k_gemm_skinny(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
+                                                        const bf16_t *__restrict__ xlo, int T, int n_rows, int K,
+                                                        int ks, float *__restrict__ partial) {
+    constexpr int XLD = SL + XPAD;
+    __shared__ __attribute__((aligned(16))) bf16_t xs[2][32][XLD];
+    const int b = blockIdx.x;
+    const int kz = b % ks, nb = b / ks;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int k0 = kz * SL;
+    const int slab = min(SL, K - k0);          // multiple of 128
+    const int n_kg = slab / 64;
+    const int n = nb * 128 + wave * 32 + l32;
+    const bf16_t *wrow = W + (int64_t)min(n, n_rows - 1) * K + k0 + half * 32;
+
+    u32x4 w[32];
+#pragma unroll
+    for (int kg = 0; kg < 8; kg++) {
+        if (kg < n_kg) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) w[kg * 4 + j] = *reinterpret_cast<const u32x4 *>(wrow + kg * 64 + j * 8);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; j++) w[kg * 4 + j] = (u32x4){0u, 0u, 0u, 0u};
+        }
+    }
+    // X slab: 2 parts x 32 rows x 64 pieces of 8 elements = 4096 pieces, 16 per thread
+#pragma unroll
+    for (int v = 0; v < 16; v++) {
+        const int idx = threadIdx.x + 256 * v;
+        const int part = idx >> 11, row = (idx >> 6) & 31, c = idx & 63;
+        if (c * 8 < slab) {
+            const int t = min(row, T - 1);
+            const u32x4 xv = *reinterpret_cast<const u32x4 *>((part ? xlo : xhi) + (int64_t)t * K + k0 + c * 8);
+            *reinterpret_cast<u32x4 *>(&xs[part][row][c * 8]) = xv;
+        }
+    }
+    lds_barrier();
+    f32x16 acc_h, acc_l;
+#pragma unroll
+    for (int i = 0; i < 16; i++) acc_h[i] = acc_l[i] = 0.f;
+#pragma unroll
+    for (int kg = 0; kg < 8; kg++) {
+        if (kg < n_kg) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const int k = kg * 64 + half * 32 + j * 8;
+                const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[0][l32][k]));
+                const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[1][l32][k]));
+                const bf16x8 bw = __builtin_bit_cast(bf16x8, w[kg * 4 + j]);
+                acc_h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bw, acc_h, 0, 0, 0);
+                acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bw, acc_l, 0, 0, 0);
+            }
+        }
+    }
+    if (n < n_rows) {
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const int t = 8 * (i / 4) + 4 * half + (i % 4);
+            if (t < T) partial[((int64_t)kz * T + t) * n_rows + n] = acc_h[i] + acc_l[i];
+        }
     }
 }
 
@@ -252,6 +324,7 @@ Shape pick_shape(int T, int epi) {
 }
 
 int split_factor(int T, int N, int K, int epi) {
+    if (T <= 32) return (K + SL - 1) / SL;        // skinny kernel: one 512-wide slab per workgroup
     const Shape sh = pick_shape(T, epi);
     const int n_ttiles = (T + sh.tt * 32 - 1) / (sh.tt * 32), n_nblocks = (N + 128 * sh.wc - 1) / (128 * sh.wc);
     const int wgs = n_ttiles * n_nblocks;
@@ -259,6 +332,8 @@ int split_factor(int T, int N, int K, int epi) {
     ks = std::min(ks, K / sh.kch / 2);            // at least two chunks per slab
     ks = std::min(ks, K / (8 * T));               // partial sums: at most a quarter of the matrix bytes
     ks = std::min(ks, 32);
+    static const int forced = env_int("LD_GEMM_KS", 0);   // tuning knob
+    if (forced > 0) ks = std::min(forced, K / sh.kch);
     return std::max(ks, 1);
 }
 
@@ -293,7 +368,7 @@ size_t gemm_split_bytes(int T, int K) { return (((size_t)2 * T * K * sizeof(bf16
 
 size_t gemm_scratch_bytes(int T, int N, int K, int epi) {
     const int ks = split_factor(T, N, K, epi);
-    const size_t part = ks > 1 ? (size_t)ks * T * N * (epi == GEMM_SWIGLU ? 2 : 1) * sizeof(float) : 0;
+    const size_t part = (ks > 1 || T <= 32) ? (size_t)ks * T * N * (epi == GEMM_SWIGLU ? 2 : 1) * sizeof(float) : 0;
     return gemm_split_bytes(T, K) + part;
 }
 
@@ -303,6 +378,17 @@ void launch_norm_split(const float *x, const float *g, float eps, int T, int K, 
 
 void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s) {
     float *partial = (float *)((char *)xs + gemm_split_bytes(T, K));
+    if (T <= 32) {
+        const int ks = split_factor(T, N, K, epi), n_rows = N * (epi == GEMM_SWIGLU ? 2 : 1);
+        const bf16_t *hi = xs, *lo = xs + (size_t)T * K;
+        hipLaunchKernelGGL(k_gemm_skinny, dim3(((n_rows + 127) / 128) * ks), dim3(256), 0, s, W, hi, lo, T, n_rows, K, ks,
+                           partial);
+        const int rgrid = (int)(((int64_t)T * N + 255) / 256);
+        if (epi == GEMM_STORE) hipLaunchKernelGGL((k_splitk_reduce<GEMM_STORE>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
+        else if (epi == GEMM_ADD) hipLaunchKernelGGL((k_splitk_reduce<GEMM_ADD>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
+        else hipLaunchKernelGGL((k_splitk_reduce<GEMM_SWIGLU>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
+        return;
+    }
     const Shape sh = pick_shape(T, epi);
     if (sh.tt == 1) launch_shape<1, 1, 128>(W, xs, T, N, K, epi, y, partial, s);
     else if (sh.tt == 2) launch_shape<2, 1, 128>(W, xs, T, N, K, epi, y, partial, s);

@@ -70,7 +70,7 @@ __device__ __forceinline__ bool lane_writes(int lane) {
     return (lane & ((1 << (6 - used)) - 1)) == 0;
 }
 
-__device__ __forceinline__ float dot8(const uint4 &w, const float (&x)[8]) {
+__device__ __forceinline__ float dot8(const u32x4_t &w, const float (&x)[8]) {
     float s = 0.f;
     s = fmaf(__uint_as_float(w.x << 16), x[0], s);
     s = fmaf(__uint_as_float(w.x & 0xffff0000u), x[1], s);
@@ -120,8 +120,8 @@ __global__ __launch_bounds__(GL == 8 ? 1024 : 512) void k_gemv1(const bf16_t *__
         if (!kval[c]) kofs[c] = 0;
     }
 
-    uint4 bufA[G][CPW], bufB[G][CPW];
-    auto issue = [&](uint4 (&buf)[G][CPW], int gi) {
+    u32x4_t bufA[G][CPW], bufB[G][CPW];
+    auto issue = [&](u32x4_t (&buf)[G][CPW], int gi) {
         const int u0 = u_begin + gi * UG;
 #pragma unroll
         for (int r = 0; r < G; r++) {
@@ -130,10 +130,10 @@ __global__ __launch_bounds__(GL == 8 ? 1024 : 512) void k_gemv1(const bf16_t *__
                 const int row = unit_row<EPI>(u, PAIRED ? r / UG : 0, N, half_hd);
                 const bf16_t *p = W + (int64_t)row * K;
 #pragma unroll
-                for (int c = 0; c < CPW; c++) buf[r][c] = *reinterpret_cast<const uint4 *>(p + kofs[c]);
+                for (int c = 0; c < CPW; c++) buf[r][c] = load_stream16(p + kofs[c]);
             } else {
 #pragma unroll
-                for (int c = 0; c < CPW; c++) buf[r][c] = make_uint4(0, 0, 0, 0);
+                for (int c = 0; c < CPW; c++) buf[r][c] = (u32x4_t){0u, 0u, 0u, 0u};
             }
         }
     };
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(GL == 8 ? 1024 : 512) void k_gemv1(const bf16_t *__
     }
     float rstd = 1.f;
 
-    auto consume = [&](uint4 (&buf)[G][CPW], int gi) {
+    auto consume = [&](u32x4_t (&buf)[G][CPW], int gi) {
         float acc[G];
 #pragma unroll
         for (int r = 0; r < G; r++) {
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(GL == 8 ? 1024 : 512) void k_gemv1(const bf16_t *__
         }
         const float tot = transpose_reduce<G>(acc, lane);
         if (lane_writes<G>(lane)) part[gi & 1][wave][row_of_lane<G>(lane)] = tot;
-        __syncthreads();
+        lds_barrier();
         if (NORM && gi == 0) {
             float s2 = 0.f;
             for (int w = 0; w < nwaves; w++) s2 += part_ss[w];

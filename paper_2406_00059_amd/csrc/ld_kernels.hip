@@ -226,9 +226,9 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
         const KVT *vb = kb + (int64_t)Hkv * 16 * HD;
         float kf[NI][8], vf[NI][8];
 #pragma unroll
-        for (int i = 0; i < NI; i++) load8(kb + i * TPI * HD, kf[i]);
+        for (int i = 0; i < NI; i++) load8_stream(kb + i * TPI * HD, kf[i]);
 #pragma unroll
-        for (int i = 0; i < NI; i++) load8(vb + i * TPI * HD, vf[i]);
+        for (int i = 0; i < NI; i++) load8_stream(vb + i * TPI * HD, vf[i]);
         const int ntok = ctx - b * 16;  // valid tokens in this block (may exceed 16)
         float s[NI];
         float mb = -INFINITY;

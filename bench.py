@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device-to-device copy (a plain copy kernel of known size, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--kernel-probe", action="store_true",
+                    help="run only the dominant kernel (gate/up projection, 7B shape, batch 1) 16 times on 4 rotating "
+                         "matrices, plus the calibration copy: the short program the rocprofv3 --pmc runs use")
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is NOT the benchmark)")
     return ap.parse_args()
 
@@ -274,6 +277,21 @@ def main():
     ld.lib()
     shape = LLAMA7B if not args.layers else LLAMA7B.with_layers(args.layers)
     torch.cuda.set_device(0)
+    if args.kernel_probe:
+        d, f = shape.d_model, shape.d_ffn
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        b = torch.empty_like(a)
+        ws = [torch.empty(2 * f, d, device="cuda").normal_(0, 0.02).bfloat16() for _ in range(4)]
+        g = torch.ones(d, device="cuda"); x = torch.randn(1, d, device="cuda"); y = torch.empty(1, f, device="cuda")
+        for i in range(16):
+            ld.ldk_linear(ws[i % 4], x, y, ld.LDK_SWIGLU, g=g, eps=shape.rms_eps)
+            if i % 4 == 0:
+                b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "k_gemv1 gate/up 7B batch 1", "launches": 16,
+                          "algorithmic_bytes_per_launch": 2 * f * d * 2 + d * 8 + f * 4,
+                          "copy_bytes_each_way": 256 << 20, "copies": 4}))
+        return
     weights = make_weights(shape, SEED_BASE + 2, device="cuda")
     model = ld.Model(shape, weights, max_chunk=CHUNK)
 

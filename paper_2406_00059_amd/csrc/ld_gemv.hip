@@ -92,9 +92,9 @@ __device__ __forceinline__ int unit_row(int u, int m, int N, int half_hd) {
 }
 
 // GL = 16-byte loads issued per lane per group: 8 keeps the kernel under 128 VGPRs (up to 16 waves
-// per workgroup, 4 waves per SIMD); 16 needs up to 256 VGPRs and is used with at most 8 waves.
+// per workgroup, 4 waves per SIMD) with two groups in flight.
 template <int CPW, int GL, int EPI, bool NORM>
-__global__ __launch_bounds__(GL == 8 ? 1024 : 512) void k_gemv1(const bf16_t *__restrict__ W, const float *__restrict__ x,
+__global__ __launch_bounds__(1024) void k_gemv1(const bf16_t *__restrict__ W, const float *__restrict__ x,
                                                 const float *__restrict__ g, float eps, int N, int K,
                                                 float *__restrict__ y, ld::RopeKvArgs rk) {
     constexpr bool PAIRED = (EPI == ld::GEMV_SWIGLU || EPI == ld::GEMV_ROPE_KV);
@@ -275,16 +275,15 @@ void launch_gemv1(const uint16_t *W, const float *x, const float *g, float eps, 
     const int cpw = chunks <= MAX_WAVES ? 1 : 2;
     const int waves = (chunks + cpw - 1) / cpw;
     const int n_units = epi == GEMV_ROPE_KV ? N / 2 : N;
-    static const int grid_per_cu = env_int("LD_GEMV_WGS_PER_CU", 2);   // tuning knobs
-    static const int want_gl16 = env_int("LD_GEMV_GL16", 0);
+    // Workgroups per CU (measured on the 7B shapes): long rows (two slabs per wave) like one resident
+    // workgroup, matrices with many outputs like six, the rest two.
+    static const int forced = env_int("LD_GEMV_WGS_PER_CU", 0);   // tuning knob
+    const int grid_per_cu = forced > 0 ? forced : (cpw == 2 ? 1 : (n_units >= 10000 ? 6 : 2));
     int grid = n_cu * grid_per_cu;
     if (grid > n_units) grid = n_units;
     RopeKvArgs none{};
     const RopeKvArgs &r = rk ? *rk : none;
-    if (cpw == 1 && waves <= 8 && want_gl16) {
-        if (g) launch_cpw<1, 16, true>(W, x, g, eps, N, K, epi, y, r, grid, waves * 64, s);
-        else launch_cpw<1, 16, false>(W, x, g, eps, N, K, epi, y, r, grid, waves * 64, s);
-    } else if (cpw == 1) {
+    if (cpw == 1) {
         if (g) launch_cpw<1, 8, true>(W, x, g, eps, N, K, epi, y, r, grid, waves * 64, s);
         else launch_cpw<1, 8, false>(W, x, g, eps, N, K, epi, y, r, grid, waves * 64, s);
     } else {

@@ -414,9 +414,9 @@ size_t ldk_linear_scratch_bytes(int32_t T, int32_t N, int32_t K, int32_t epilogu
 
 ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *g, float eps, int32_t T, int32_t N,
                      int32_t K, int32_t epilogue, float *y, void *scratch, size_t scratch_bytes, void *stream) {
+    if (T == 0) return LD_OK;   // nothing to do: pointers of empty buffers may be null
     if (!W || !x || !y || T < 0 || N <= 0 || K <= 0 || K % 8 || epilogue < 0 || epilogue > 2)
         return ld::fail(LD_E_INVAL, "ldk_linear: bad argument (K must be a multiple of 8)");
-    if (T == 0) return LD_OK;
     hipStream_t s = (hipStream_t)stream;
     if (dtype == LD_BF16 && T == 1 && ld::gemv1_supported(N, K, epilogue)) {
         ld::launch_gemv1((const bf16_t *)W, x, g, eps, N, K, epilogue, y, nullptr, s);
@@ -548,8 +548,8 @@ ld_status ldk_prefill_attention(const float *q, int32_t q_stride, const void *po
 }
 
 ld_status ldk_argmax(const float *logits, int32_t R, int32_t V, int32_t *out, void *stream) {
-    if (!logits || !out || R < 0 || V <= 0) return ld::fail(LD_E_INVAL, "ldk_argmax: bad argument");
     if (R == 0) return LD_OK;
+    if (!logits || !out || R < 0 || V <= 0) return ld::fail(LD_E_INVAL, "ldk_argmax: bad argument");
     hipLaunchKernelGGL(k_argmax, dim3(R), dim3(1024), 0, (hipStream_t)stream, logits, V, out);
     return launched("k_argmax");
 }

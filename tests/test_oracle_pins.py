@@ -363,3 +363,17 @@ def test_wo_and_wdown_zero_make_every_layer_the_identity(tiny_weights):
         x = E[t]
         ref = Wl @ (x / np.sqrt(np.mean(x * x) + shape.rms_eps) * g)
         np.testing.assert_allclose(got[p], ref, rtol=1e-12, atol=1e-15)
+
+
+def test_golden_tiny_tokens_are_reproduced_by_the_oracle():
+    """The stored greedy tokens of workload 0 (written by tests/golden/make_tiny_tokens.py from the oracle)
+    still come out of the oracle: guards the fixture and the generator against silent drift."""
+    import json, os, importlib.util
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_tiny_tokens", os.path.join(here, "make_tiny_tokens.py"))
+    mod = importlib.util.module_from_spec(spec); spec.loader.exec_module(mod)
+    stored = json.load(open(os.path.join(here, "tiny_fp32_tokens.json")))
+    fresh = mod.compute()
+    assert fresh["tokens"] == stored["tokens"] and fresh["prompt"] == stored["prompt"]
+    assert fresh["block_table"] == stored["block_table"] == [0, 1, 2, 3, 4, 5]
+    assert len(set(stored["tokens"])) >= 4         # not a constant sequence

@@ -23,4 +23,10 @@ void launch_norm_split(const float *x, const float *g, float eps, int T, int K, 
 // (gemm_scratch_bytes bytes); W bf16 [N, K] ([2N, K] for GEMM_SWIGLU).
 void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s);
 
+// Skinny product alone (T <= 32 rows, K a multiple of 128): partial[z][t][row] for the skinny_slabs(K)
+// 512-wide K slabs z; the caller adds the slabs in order.
+int skinny_slabs(int K);
+void launch_gemm_skinny(const uint16_t *W, const uint16_t *xhi, const uint16_t *xlo, int T, int n_rows, int K,
+                        float *partial, hipStream_t s);
+
 }  // namespace ld

@@ -376,6 +376,15 @@ void launch_norm_split(const float *x, const float *g, float eps, int T, int K, 
     hipLaunchKernelGGL(k_norm_split, dim3(T), dim3(256), 0, s, x, g, eps, K, xs, xs + (size_t)T * K);
 }
 
+int skinny_slabs(int K) { return (K + SL - 1) / SL; }
+
+void launch_gemm_skinny(const uint16_t *W, const uint16_t *xhi, const uint16_t *xlo, int T, int n_rows, int K,
+                        float *partial, hipStream_t s) {
+    const int ks = skinny_slabs(K);
+    hipLaunchKernelGGL(k_gemm_skinny, dim3(((n_rows + 127) / 128) * ks), dim3(256), 0, s, W, xhi, xlo, T, n_rows, K, ks,
+                       partial);
+}
+
 void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s) {
     float *partial = (float *)((char *)xs + gemm_split_bytes(T, K));
     if (T <= 32) {

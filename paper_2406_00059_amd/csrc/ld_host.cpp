@@ -1,6 +1,7 @@
 // Host side of libld: model registry, paged-KV block allocator, sequence state machine,
 // step planner (which rows go through one pass), launch sequence, token hand-off to the callback.
 #include "ld_internal.h"
+#include "ld_batch.h"
 
 #include <algorithm>
 #include <cstring>
@@ -54,6 +55,8 @@ struct Workspace {
     float *x, *qkv, *attn, *act, *hn, *logits, *cos_sin;
     void *att_scratch, *lin_scratch;
     size_t att_scratch_bytes, lin_scratch_bytes;
+    uint16_t *b_xs;      // decode-batch layer: split operand image, split-K partial sums, norm statistics
+    float *b_partial, *b_ss;
     size_t total;
 };
 
@@ -92,6 +95,12 @@ Workspace plan_workspace(const ld_model &m, char *base, int max_tokens, int max_
         w.lin_scratch_bytes = std::max(w.lin_scratch_bytes, b);
     }
     w.lin_scratch = take(w.lin_scratch_bytes);
+    {
+        const int tb = std::min(max_tokens, 32);
+        w.b_xs = (uint16_t *)take(ld::batch_layer_xs_bytes(tb, c.d_model, c.n_heads, c.head_dim, c.d_ffn));
+        w.b_partial = (float *)take(ld::batch_layer_partial_bytes(tb, c.d_model, c.n_heads, c.n_kv_heads, c.head_dim, c.d_ffn));
+        w.b_ss = (float *)take(ld::batch_layer_ss_bytes(tb, std::max(c.d_model, 1024)));
+    }
     w.total = off;
     return w;
 }
@@ -241,6 +250,34 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const 
     const size_t layer_bytes = (size_t)kv->n_blocks * m.block_elems() * m.elem();
     LD_TIMED(LD_PROF_OTHER, ldk_embed(m.embed, c.dtype, d_tok, T, d, w.x, st));
     LD_TIMED(LD_PROF_OTHER, ldk_rope_table(d_pos, T, hd, c.rope_base, w.cos_sin, st));
+    // Decode batches of 2..32 rows on bf16 weights take the fused batch layer; everything else the
+    // general per-step composition below.
+    const bool batch_path = c.dtype == LD_BF16 && n_tiles == 0 && c.n_layers > 0 &&
+                            ld::batch_layer_supported(T, d, H, Hkv, hd, c.d_ffn);
+    auto timed_void = [](auto &&fn) { fn(); return LD_OK; };
+    if (batch_path) {
+        ld::BatchLayerArgs a{};
+        a.T = T; a.d = d; a.H = H; a.Hkv = Hkv; a.hd = hd; a.ffn = c.d_ffn; a.eps = c.rms_eps;
+        a.x = w.x; a.q = w.qkv; a.q_stride = nqkv; a.xs = w.b_xs; a.partial = w.b_partial; a.ss_part = w.b_ss;
+        a.cos_sin = w.cos_sin; a.pos = d_pos; a.seq_slot = d_slot; a.table = w.table; a.table_stride = kv->max_blocks;
+        LD_TIMED(LD_PROF_OTHER, timed_void([&] { ld::launch_batch_prepare(w.x, m.attn_norm[0], T, d, w.b_xs, w.b_ss, st); }));
+        for (int l = 0; l < c.n_layers; l++) {
+            void *pool_l = kv->pool + (size_t)l * layer_bytes;
+            a.wqkv = (const uint16_t *)m.wqkv[l]; a.wo = (const uint16_t *)m.wo[l];
+            a.wgate_up = (const uint16_t *)m.wgate_up[l]; a.wdown = (const uint16_t *)m.wdown[l];
+            a.attn_norm = m.attn_norm[l]; a.ffn_norm = m.ffn_norm[l];
+            a.next_norm = l + 1 < c.n_layers ? m.attn_norm[l + 1] : nullptr;
+            a.pool = (uint16_t *)pool_l;
+            LD_TIMED(LD_PROF_QKV, timed_void([&] { ld::launch_batch_qkv(a, st); }));
+            LD_TIMED(LD_PROF_ATTENTION, ld::paged_attention_split(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot,
+                                                                  d_ctx, max_ctx_dec, T, H, Hkv, hd, w.b_xs, w.att_scratch,
+                                                                  w.att_scratch_bytes, st));
+            LD_TIMED(LD_PROF_WO, timed_void([&] { ld::launch_batch_wo(a, st); }));
+            LD_TIMED(LD_PROF_GATE_UP, timed_void([&] { ld::launch_batch_gate_up(a, st); }));
+            LD_TIMED(LD_PROF_DOWN, timed_void([&] { ld::launch_batch_down(a, st); }));
+        }
+        LD_HIP_TRY(hipGetLastError());
+    } else
     for (int l = 0; l < c.n_layers; l++) {
         void *pool_l = kv->pool + (size_t)l * layer_bytes;
         LD_TIMED(LD_PROF_QKV, ldk_qkv_rope(m.wqkv[l], c.dtype, w.x, m.attn_norm[l], c.rms_eps, w.qkv, w.cos_sin, d_pos,

@@ -25,6 +25,11 @@ inline ld_status fail(ld_status s, const char *what) {
         }                                                                                 \
     } while (0)
 
+ld_status paged_attention_split(const float *q, int q_stride, const void *pool_layer, int dtype, const int32_t *table,
+                                int table_stride, const int32_t *seq_slot, const int32_t *ctx_len, int max_ctx, int T,
+                                int H, int Hkv, int hd, uint16_t *xs_out, void *scratch, size_t scratch_bytes,
+                                hipStream_t stream);
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace ld

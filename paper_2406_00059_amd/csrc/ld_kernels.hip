@@ -300,7 +300,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
 template <int HD>
 __global__ void k_attn_merge(const float *__restrict__ part_o, const float *__restrict__ part_ml,
                              const int32_t *__restrict__ ctx_len, int H, int max_chunks, int cb,
-                             float *__restrict__ out) {
+                             float *__restrict__ out, bf16_t *__restrict__ xs_out, int T) {
     const int h = blockIdx.x, t = blockIdx.y, d = threadIdx.x;
     const int nch = ((ctx_len[t] + 15) / 16 + cb - 1) / cb;
     const int64_t base = ((int64_t)t * H + h) * max_chunks;
@@ -312,7 +312,14 @@ __global__ void k_attn_merge(const float *__restrict__ part_o, const float *__re
         o += a * part_o[(base + c) * HD + d];
         L += a * part_ml[(base + c) * 2 + 1];
     }
-    out[((int64_t)t * H + h) * HD + d] = o / L;
+    const float r = o / L;
+    if (xs_out) {   // operand of the output projection: split (hi, lo) image [2][T][H * HD]
+        const bf16_t hi = f32_to_bf16(r);
+        xs_out[((int64_t)t * H + h) * HD + d] = hi;
+        xs_out[((int64_t)(T + t) * H + h) * HD + d] = f32_to_bf16(r - bf16_to_f32(hi));
+    } else {
+        out[((int64_t)t * H + h) * HD + d] = r;
+    }
 }
 
 // ---------------------------------------------------------------- greedy argmax (lowest index on ties)
@@ -503,14 +510,15 @@ size_t ldk_attention_scratch_bytes(int32_t T, int32_t H, int32_t hd, int32_t max
     return (size_t)T * H * attn_max_chunks(T, H, max_ctx) * (hd + 2) * sizeof(float);
 }
 
-ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
-                              const int32_t *table, int32_t table_stride, const int32_t *seq_slot,
-                              const int32_t *ctx_len, int32_t max_ctx, int32_t T, int32_t H, int32_t Hkv, int32_t hd,
-                              float *out, void *scratch, size_t scratch_bytes, void *stream) {
-    if (!q || !pool_layer || !table || !seq_slot || !ctx_len || !out || !scratch || T < 0 || H <= 0 || Hkv <= 0 ||
-        H % Hkv || (hd != 64 && hd != 128) || max_ctx <= 0)
-        return ld::fail(LD_E_INVAL, "ldk_paged_attention: bad argument");
+static ld_status paged_attention_impl(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
+                                      const int32_t *table, int32_t table_stride, const int32_t *seq_slot,
+                                      const int32_t *ctx_len, int32_t max_ctx, int32_t T, int32_t H, int32_t Hkv,
+                                      int32_t hd, float *out, uint16_t *xs_out, void *scratch, size_t scratch_bytes,
+                                      void *stream) {
     if (T == 0) return LD_OK;
+    if (!q || !pool_layer || !table || !seq_slot || !ctx_len || (!out && !xs_out) || !scratch || T < 0 || H <= 0 ||
+        Hkv <= 0 || H % Hkv || (hd != 64 && hd != 128) || max_ctx <= 0)
+        return ld::fail(LD_E_INVAL, "ldk_paged_attention: bad argument");
     if (scratch_bytes < ldk_attention_scratch_bytes(T, H, hd, max_ctx))
         return ld::fail(LD_E_INVAL, "ldk_paged_attention: scratch too small");
     const int mc = attn_max_chunks(T, H, max_ctx), cb = attn_chunk_blocks(T, H, max_ctx);
@@ -522,8 +530,9 @@ ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool
 #define LD_ATT(HD_, KVT_)                                                                                         \
     do {                                                                                                          \
         hipLaunchKernelGGL((k_attn_partial<HD_, KVT_>), grid, block, 0, s, q, q_stride, (const KVT_ *)pool_layer, \
-                           Hkv, table, table_stride, seq_slot, ctx_len, H, sl2, mc, cb, part_o, part_ml);             \
-        hipLaunchKernelGGL((k_attn_merge<HD_>), dim3(H, T), dim3(HD_), 0, s, part_o, part_ml, ctx_len, H, mc, cb, out); \
+                           Hkv, table, table_stride, seq_slot, ctx_len, H, sl2, mc, cb, part_o, part_ml);         \
+        hipLaunchKernelGGL((k_attn_merge<HD_>), dim3(H, T), dim3(HD_), 0, s, part_o, part_ml, ctx_len, H, mc, cb, \
+                           out, xs_out, T);                                                                       \
     } while (0)
     if (dtype == LD_BF16 && hd == 128) LD_ATT(128, bf16_t);
     else if (dtype == LD_BF16 && hd == 64) LD_ATT(64, bf16_t);
@@ -532,6 +541,14 @@ ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool
     else return ld::fail(LD_E_INVAL, "ldk_paged_attention: bad dtype");
 #undef LD_ATT
     return launched("k_attn");
+}
+
+ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
+                              const int32_t *table, int32_t table_stride, const int32_t *seq_slot,
+                              const int32_t *ctx_len, int32_t max_ctx, int32_t T, int32_t H, int32_t Hkv, int32_t hd,
+                              float *out, void *scratch, size_t scratch_bytes, void *stream) {
+    return paged_attention_impl(q, q_stride, pool_layer, dtype, table, table_stride, seq_slot, ctx_len, max_ctx, T, H, Hkv,
+                                hd, out, nullptr, scratch, scratch_bytes, stream);
 }
 
 ld_status ldk_prefill_attention(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
@@ -555,3 +572,17 @@ ld_status ldk_argmax(const float *logits, int32_t R, int32_t V, int32_t *out, vo
 }
 
 }  // extern "C"
+
+namespace ld {
+
+// Single-query paged attention whose output is written as the split (hi, lo) bf16 operand of the
+// output projection: xs_out [2][T][H * hd].
+ld_status paged_attention_split(const float *q, int q_stride, const void *pool_layer, int dtype, const int32_t *table,
+                                int table_stride, const int32_t *seq_slot, const int32_t *ctx_len, int max_ctx, int T,
+                                int H, int Hkv, int hd, uint16_t *xs_out, void *scratch, size_t scratch_bytes,
+                                hipStream_t stream) {
+    return paged_attention_impl(q, q_stride, pool_layer, dtype, table, table_stride, seq_slot, ctx_len, max_ctx, T, H, Hkv,
+                                hd, nullptr, xs_out, scratch, scratch_bytes, (void *)stream);
+}
+
+}  // namespace ld

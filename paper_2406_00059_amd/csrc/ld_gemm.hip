@@ -151,16 +151,26 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t *__restrict__ W,
 #pragma unroll
             for (int j = 0; j < 4; j++) {
                 const int k = kg * 64 + half * 32 + j * 8;
+                bf16x8 ah[TT], al[TT];
 #pragma unroll
                 for (int tt = 0; tt < TT; tt++) {
-                    const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[0][tt * 32 + l32][k]));
-                    const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[1][tt * 32 + l32][k]));
+                    ah[tt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[0][tt * 32 + l32][k]));
+                    al[tt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[1][tt * 32 + l32][k]));
+                }
+                // all high parts, then all low parts: consecutive MFMAs never share an accumulator
 #pragma unroll
-                    for (int f = 0; f < WF; f++) {
-                        const bf16x8 bw = __builtin_bit_cast(bf16x8, w[f][kg * 4 + j]);
-                        acc[f][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bw, acc[f][tt], 0, 0, 0);
-                        acc[f][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bw, acc[f][tt], 0, 0, 0);
-                    }
+                for (int f = 0; f < WF; f++) {
+                    const bf16x8 bw = __builtin_bit_cast(bf16x8, w[f][kg * 4 + j]);
+#pragma unroll
+                    for (int tt = 0; tt < TT; tt++)
+                        acc[f][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[tt], bw, acc[f][tt], 0, 0, 0);
+                }
+#pragma unroll
+                for (int f = 0; f < WF; f++) {
+                    const bf16x8 bw = __builtin_bit_cast(bf16x8, w[f][kg * 4 + j]);
+#pragma unroll
+                    for (int tt = 0; tt < TT; tt++)
+                        acc[f][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[tt], bw, acc[f][tt], 0, 0, 0);
                 }
             }
     };
@@ -309,18 +319,19 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__
     else y[idx] = a / (1.0f + __expf(-a)) * b;
 }
 
-// Tile shape by row count: up to 32 rows -> 32 x 128 tile, 128-wide K chunks (weight-stream bound);
-// up to 64 rows -> 64 x 128; more -> 128 rows x 256 columns (128 for SwiGLU), 64-wide K chunks.
+// Tile shape by row count: up to 32 rows -> skinny kernel (the 32 x 128 tile is kept for completeness);
+// up to 64 rows -> 64 x 128, 128-wide K chunks; more -> 64 rows x 256 columns (128 for SwiGLU), 64-wide chunks.
 struct Shape { int tt, wc, kch; };
 int env_int(const char *name, int dflt) {
     const char *v = getenv(name);
     return v ? atoi(v) : dflt;
 }
 Shape pick_shape(int T, int epi) {
-    static const int big_from = env_int("LD_GEMM_BIG_FROM", 65);   // tuning knob: rows from which the big tile is used
     if (T <= 32) return {1, 1, 128};
-    if (T < big_from) return {2, 1, 128};
-    return {4, epi == ld::GEMM_SWIGLU ? 1 : 2, 64};
+    if (T <= 64) return {2, 1, 128};
+    // measured on the 7B shapes at 256 and 1056 rows: 64 x 256 tiles at two waves per SIMD beat
+    // 128 x 256 tiles at one wave per SIMD
+    return {2, epi == ld::GEMM_SWIGLU ? 1 : 2, 64};
 }
 
 int split_factor(int T, int N, int K, int epi) {
@@ -400,9 +411,9 @@ void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int
     }
     const Shape sh = pick_shape(T, epi);
     if (sh.tt == 1) launch_shape<1, 1, 128>(W, xs, T, N, K, epi, y, partial, s);
-    else if (sh.tt == 2) launch_shape<2, 1, 128>(W, xs, T, N, K, epi, y, partial, s);
-    else if (sh.wc == 1) launch_shape<4, 1, 64>(W, xs, T, N, K, epi, y, partial, s);
-    else launch_shape<4, 2, 64>(W, xs, T, N, K, epi, y, partial, s);
+    else if (sh.kch == 128) launch_shape<2, 1, 128>(W, xs, T, N, K, epi, y, partial, s);
+    else if (sh.wc == 1) launch_shape<2, 1, 64>(W, xs, T, N, K, epi, y, partial, s);
+    else launch_shape<2, 2, 64>(W, xs, T, N, K, epi, y, partial, s);
 }
 
 }  // namespace ld

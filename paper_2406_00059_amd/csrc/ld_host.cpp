@@ -352,18 +352,28 @@ ld_status run_step(ld_kv *kv, const std::vector<Feed> &feeds, void *stream, ld_t
         Seq &q = kv->seqs[f.seq];
         map_blocks(kv, f.seq, blocks_for(kv, q.n_cached + f.n + (q.has_pending ? 1 : 0)));
     }
+    // A prefill feed whose row count is one more than a multiple of the 128-row attention tile (a
+    // 256-token observation behind a pending token) sends its first row through the single-query
+    // path, so that the rest fills whole tiles.
+    auto peel_first = [&](int64_t n_rows) { return n_rows > 1 && n_rows % 128 == 1; };
     int n_single = 0;
     for (int pass = 0; pass < 2; pass++)
         for (size_t i = 0; i < feeds.size(); i++) {
             const Feed &f = feeds[i];
             Seq &q = kv->seqs[f.seq];
             const int64_t n_rows = f.n + (q.has_pending ? 1 : 0);
-            if ((n_rows == 1) != (pass == 0)) continue;
-            int32_t pos = (int32_t)q.n_cached;
-            if (q.has_pending) rows.push_back({q.pending, pos++, f.seq});
-            for (int k = 0; k < f.n; k++) rows.push_back({f.tokens[k], pos++, f.seq});
-            emit[i] = (int32_t)rows.size() - 1;
-            if (pass == 0) n_single++;
+            const int32_t pos0 = (int32_t)q.n_cached;
+            auto tok_at = [&](int64_t r) { return q.has_pending ? (r == 0 ? q.pending : f.tokens[r - 1]) : f.tokens[r]; };
+            if (pass == 0) {
+                if (n_rows == 1 || peel_first(n_rows)) {
+                    rows.push_back({tok_at(0), pos0, f.seq});
+                    n_single++;
+                    if (n_rows == 1) emit[i] = (int32_t)rows.size() - 1;
+                }
+            } else if (n_rows > 1) {
+                for (int64_t r = peel_first(n_rows) ? 1 : 0; r < n_rows; r++) rows.push_back({tok_at(r), pos0 + (int32_t)r, f.seq});
+                emit[i] = (int32_t)rows.size() - 1;
+            }
         }
     ld_status rc = run_pass(kv, rows, n_single, emit, (hipStream_t)stream, logits_out);
     if (rc) return rc;

@@ -33,10 +33,6 @@ constexpr int HD = 128;
 constexpr int KVB = 32;        // kv positions per step
 constexpr int VLD = KVB + 4;   // LDS row stride of the transposed V tile (elements)
 
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-    return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
-}
-
 __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ q, int q_stride,
                                                       const bf16_t *__restrict__ pool, int Hkv,
                                                       const int32_t *__restrict__ table, int table_stride,
@@ -70,10 +66,7 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
             uint32_t hw[4], lw[4];
 #pragma unroll
             for (int e = 0; e < 4; e++) {
-                const float a = v[2 * e] * scale_log2e, b = v[2 * e + 1] * scale_log2e;
-                const bf16_t ah = f32_to_bf16(a), bh = f32_to_bf16(b);
-                hw[e] = (uint32_t)ah | ((uint32_t)bh << 16);
-                lw[e] = pack_bf16(a - bf16_to_f32(ah), b - bf16_to_f32(bh));
+                hw[e] = split2_bf16(v[2 * e] * scale_log2e, v[2 * e + 1] * scale_log2e, lw[e]);
             }
             qh[j] = __builtin_bit_cast(bf16x8, (u32x4){hw[0], hw[1], hw[2], hw[3]});
             ql[j] = __builtin_bit_cast(bf16x8, (u32x4){lw[0], lw[1], lw[2], lw[3]});
@@ -163,9 +156,7 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
             for (int i = 0; i < 16; i += 2) {
                 const float p0 = fast_exp2(st[i] - m_new), p1 = fast_exp2(st[i + 1] - m_new);
                 psum += p0 + p1;
-                const bf16_t h0 = f32_to_bf16(p0), h1 = f32_to_bf16(p1);
-                ph[i / 2] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                pl[i / 2] = pack_bf16(p0 - bf16_to_f32(h0), p1 - bf16_to_f32(h1));
+                ph[i / 2] = split2_bf16(p0, p1, pl[i / 2]);
             }
             l = l * sc + psum;
             m = m_new;

@@ -23,14 +23,8 @@ namespace {
 constexpr int RB = 1024;   // columns of one row handled by a workgroup of k_red_add_split (256 threads x 4)
 
 __device__ __forceinline__ void split4(const float (&v)[4], uint2 &hi, uint2 &lo) {
-    bf16_t h[4], l[4];
-#pragma unroll
-    for (int e = 0; e < 4; e++) {
-        h[e] = f32_to_bf16(v[e]);
-        l[e] = f32_to_bf16(v[e] - bf16_to_f32(h[e]));
-    }
-    hi = make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
-    lo = make_uint2((uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16));
+    hi.x = split2_bf16(v[0], v[1], lo.x);
+    hi.y = split2_bf16(v[2], v[3], lo.y);
 }
 
 __device__ __forceinline__ float row_rstd(const float *ss_part, int t, int nssp, int d, float eps) {

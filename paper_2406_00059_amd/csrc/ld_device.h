@@ -12,12 +12,21 @@ typedef uint16_t bf16_t;
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-// float32 -> bf16, round to nearest even.
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);  // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+// float32 -> bf16, round to nearest even (the hardware conversion, v_cvt_pk_bf16_f32).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+
+// Two conversions in one instruction: low half = bf16(a), high half = bf16(b).
+__device__ __forceinline__ uint32_t pack2_bf16(float a, float b) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){a, b}, bf16x2_t));
+}
+
+// x = hi + lo with both parts bf16: returns the packed high parts of (a, b), stores the packed low parts.
+__device__ __forceinline__ uint32_t split2_bf16(float a, float b, uint32_t &lo) {
+    const uint32_t hi = pack2_bf16(a, b);
+    lo = pack2_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
+    return hi;
 }
 
 // Load 8 consecutive elements (16-byte aligned for bf16, 32-byte for float) as floats.

@@ -60,17 +60,10 @@ __global__ __launch_bounds__(256) void k_norm_split(const float *__restrict__ x,
             const float4 gv = *reinterpret_cast<const float4 *>(g + i);
             v.x = v.x * rstd * gv.x; v.y = v.y * rstd * gv.y; v.z = v.z * rstd * gv.z; v.w = v.w * rstd * gv.w;
         }
-        const float f[4] = {v.x, v.y, v.z, v.w};
-        bf16_t h[4], l[4];
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-            h[e] = f32_to_bf16(f[e]);
-            l[e] = f32_to_bf16(f[e] - bf16_to_f32(h[e]));
-        }
-        *reinterpret_cast<uint2 *>(hi + (int64_t)t * K + i) =
-            make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
-        *reinterpret_cast<uint2 *>(lo + (int64_t)t * K + i) =
-            make_uint2((uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16));
+        uint32_t l0, l1;
+        const uint32_t h0 = split2_bf16(v.x, v.y, l0), h1 = split2_bf16(v.z, v.w, l1);
+        *reinterpret_cast<uint2 *>(hi + (int64_t)t * K + i) = make_uint2(h0, h1);
+        *reinterpret_cast<uint2 *>(lo + (int64_t)t * K + i) = make_uint2(l0, l1);
     }
 }
 

@@ -9,7 +9,7 @@ run between the timed steps and are reported beside it.  Inputs (weights, tokens
 synthetic and are resident in HBM before timing starts.
 
 Prints ONE JSON line.  `roofline` describes the kernel with the largest share of the step
-(HIP events bracketing every launch of a profiled tail of the same run); `cpu_baseline` is the CPU oracle
+(HIP events attached to every kernel dispatch during a profiled tail of the same run); `cpu_baseline` is the CPU oracle
 timed on this machine's host cores on a bounded sample of the same workload.
 """
 import argparse
@@ -23,6 +23,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK = 8.0e12          # bytes/s, MI355X HBM3E
+# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE counters, scaled by a
+# 256 MiB copy (profiles/gate_up_gemv_hbm_traffic.md); valid only for the kernel source it was taken on.
+TRAFFIC_BYTES = 180_870_000
+TRAFFIC_KERNEL_MD5 = "93925c9ad74b"
 ROUND_TOKENS = 256         # tokens emitted per round (1 by the preceding prefill + 255 decode steps)
 CHUNK = 256
 
@@ -44,6 +48,17 @@ def parse():
                          "matrices, plus the calibration copy: the short program the rocprofv3 --pmc runs use")
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is NOT the benchmark)")
     return ap.parse_args()
+
+
+def kernel_traffic():
+    """Measured HBM bytes per launch of the dominant kernel, or None if its source changed since."""
+    import hashlib
+    src = os.path.join(ROOT, "paper_2406_00059_amd", "csrc", "ld_gemv.hip")
+    try:
+        h = hashlib.md5(open(src, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    return TRAFFIC_BYTES if h.startswith(TRAFFIC_KERNEL_MD5) else None
 
 
 def noop_cb(seq, tok, pos):
@@ -154,10 +169,12 @@ def run_batch1(args, ld, torch, shape, weights, model):
                 kernels[name]["GBps"] = round(alg_bytes[name] / (avg * 1e-3) / 1e9, 1)
     per_step_ms = {k: v[0] / args.profile_steps for k, v in prof.items()}
     dominant = max((k for k in per_step_ms if k in alg_bytes), key=lambda k: per_step_ms[k])
-    # Launch duration of the dominant kernel (the gate/up projection with fused RMSNorm + SwiGLU): the same
-    # launch the step makes, on every layer's weights in turn (13.2 GB apart in total, so nothing is served
-    # from cache), between ONE pair of HIP events on the step's stream; repeated, mean over all launches.
+    # Duration of the dominant kernel (the gate/up projection with fused RMSNorm + SwiGLU): HIP events
+    # attached to its dispatches on the step's stream during the profiled steps above (kernel start to
+    # kernel end, like a kernel trace).  Beside it: the same launch on every layer's weights in turn between
+    # ONE pair of events, which adds the launch gap between consecutive kernels.
     assert dominant == "gate_up", dominant
+    avg_s = prof[dominant][0] / prof[dominant][1] * 1e-3
     xin = torch.randn(1, d, device="cuda"); yout = torch.empty(1, f, device="cuda")
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     L = shape.n_layers
@@ -170,12 +187,14 @@ def run_batch1(args, ld, torch, shape, weights, model):
             ld.ldk_linear(weights["wgate_up"][l], xin, yout, ld.LDK_SWIGLU, g=weights["ffn_norm"][l], eps=shape.rms_eps)
     ev1.record(stream)
     torch.cuda.synchronize()
-    avg_s = ev0.elapsed_time(ev1) * 1e-3 / (reps * L)
-    roofline = {"bound": "hbm", "kernel": "k_gemv1 (gate/up projection, fused RMSNorm + SwiGLU)",
+    b2b_s = ev0.elapsed_time(ev1) * 1e-3 / (reps * L)
+    roofline = {"bound": "hbm", "kernel": "k_gemv1<1, 8, 2, true> (gate/up projection, fused RMSNorm + SwiGLU)",
                 "achieved": round(alg_bytes[dominant] / avg_s / 1e9, 1),
                 "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": round(alg_bytes[dominant] / avg_s / HBM_PEAK, 4),
-                "traffic": None, "avg_launch_us": round(avg_s * 1e6, 2), "bytes_per_launch": alg_bytes[dominant],
-                "launches_timed": reps * L, "share_of_step": round(per_step_ms[dominant] / sum(per_step_ms.values()), 3)}
+                "traffic": kernel_traffic(), "avg_launch_us": round(avg_s * 1e6, 2),
+                "bytes_per_launch": alg_bytes[dominant], "launches_timed": prof[dominant][1],
+                "back_to_back_us_incl_launch_gap": round(b2b_s * 1e6, 2),
+                "share_of_step_kernel_time": round(per_step_ms[dominant] / sum(per_step_ms.values()), 3)}
     out = {
         "value": K / dec_s, "ms_per_step": statistics.mean(step_ms),
         "ms_per_step_median": statistics.median(step_ms),

@@ -146,15 +146,17 @@ ld_status ld_step_mixed(ld_kv *kv, const ld_seq *dec, int32_t n_dec, const ld_se
                         const int32_t *const *pf_tokens, const int32_t *pf_n, int32_t n_pf, void *stream,
                         ld_token_cb cb, void *user, float *logits_out);
 
-/* Per-kernel timing for benchmarks (off by default).  While enabled, every pass brackets each launch
- * with a pair of HIP events on the step's stream and, after the pass has finished, adds the elapsed
- * device time to its category.  Enabling clears the counters.  The extra events serialise neighbouring
- * kernels slightly, so whole-step throughput is measured with profiling off. */
+/* Per-kernel timing for benchmarks (off by default).  While enabled, every kernel of a pass is launched
+ * with a pair of HIP events attached to its dispatch (on the step's stream), which record the start and
+ * the end of that kernel; after the pass has finished the kernel durations are added to the category of
+ * the step they belong to.  ms[] is therefore pure kernel time (no launch gaps); launches[] counts steps
+ * of the pass (one per layer for the per-layer categories), each of which may be several kernels.
+ * Enabling clears the counters. */
 enum { LD_PROF_QKV = 0, LD_PROF_ROPE_KV = 1, LD_PROF_ATTENTION = 2, LD_PROF_WO = 3, LD_PROF_GATE_UP = 4,
        LD_PROF_DOWN = 5, LD_PROF_LM_HEAD = 6, LD_PROF_OTHER = 7, LD_PROF_N = 8 };
 typedef struct {
     double ms[LD_PROF_N];        /* summed device time per category, milliseconds */
-    int64_t launches[LD_PROF_N]; /* bracketed launches per category */
+    int64_t launches[LD_PROF_N]; /* timed steps per category */
 } ld_profile;
 ld_status ld_kv_profile(ld_kv *kv, int32_t enable);
 ld_status ld_kv_profile_read(const ld_kv *kv, ld_profile *out); /* out: HOST */

@@ -19,6 +19,7 @@
 // Scores are kept in the log2 domain (q is pre-multiplied by log2(e)/sqrt(hd)); m, l and O are float32.
 #include "ld_attn_prefill.h"
 #include "ld_device.h"
+#include "ld_internal.h"
 
 using namespace ldd;
 
@@ -212,7 +213,7 @@ bool prefill_attention_supported(int dtype_is_bf16, int hd) { return dtype_is_bf
 void launch_prefill_attention(const float *q, int q_stride, const uint16_t *pool, int Hkv, const int32_t *table,
                               int table_stride, const int32_t *tiles, int n_tiles, int H, float *out, hipStream_t s) {
     const float sl2 = 1.4426950408889634f / sqrtf((float)HD);
-    hipLaunchKernelGGL(k_attn_prefill, dim3(n_tiles, H), dim3(256), 0, s, q, q_stride, pool, Hkv, table, table_stride,
+    LD_LAUNCH(k_attn_prefill, dim3(n_tiles, H), dim3(256), 0, s, q, q_stride, pool, Hkv, table, table_stride,
                        (const int4 *)tiles, H, sl2, out);
 }
 

@@ -14,6 +14,7 @@
 #include "ld_batch.h"
 #include "ld_gemm.h"
 #include "ld_device.h"
+#include "ld_internal.h"
 #include <algorithm>
 
 using namespace ldd;
@@ -146,7 +147,7 @@ size_t batch_layer_partial_bytes(int T, int d, int H, int Hkv, int hd, int ffn) 
 size_t batch_layer_ss_bytes(int T, int d) { return (size_t)2 * T * (d / RB) * sizeof(float); }
 
 void launch_batch_prepare(const float *x, const float *g, int T, int d, uint16_t *xs, float *ss_part, hipStream_t s) {
-    hipLaunchKernelGGL(k_red_add_split, dim3(d / RB, T), dim3(256), 0, s, nullptr, 0, const_cast<float *>(x), g, T, d, xs,
+    LD_LAUNCH(k_red_add_split, dim3(d / RB, T), dim3(256), 0, s, nullptr, 0, const_cast<float *>(x), g, T, d, xs,
                        ss_part);
 }
 
@@ -154,7 +155,7 @@ void launch_batch_qkv(const BatchLayerArgs &a, hipStream_t s) {
     const int nqkv = (a.H + 2 * a.Hkv) * a.hd, nssp = a.d / RB;
     launch_gemm_skinny(a.wqkv, a.xs, a.xs + (size_t)a.T * a.d, a.T, nqkv, a.d, a.partial, s);
     const int n = a.T * (a.H + 2 * a.Hkv) * 64;
-    hipLaunchKernelGGL(k_red_rope, dim3((n + 255) / 256), dim3(256), 0, s, a.partial, skinny_slabs(a.d), a.ss_part, nssp,
+    LD_LAUNCH(k_red_rope, dim3((n + 255) / 256), dim3(256), 0, s, a.partial, skinny_slabs(a.d), a.ss_part, nssp,
                        a.eps, a.d, a.T, a.H, a.Hkv, (const float2 *)a.cos_sin, a.pos, a.seq_slot, a.table, a.table_stride,
                        a.q, a.q_stride, a.pool);
 }
@@ -163,7 +164,7 @@ void launch_batch_wo(const BatchLayerArgs &a, hipStream_t s) {
     // output projection; residual; operand + statistics of the FFN norm
     const int nq = a.H * a.hd, nssp = a.d / RB;
     launch_gemm_skinny(a.wo, a.xs, a.xs + (size_t)a.T * nq, a.T, a.d, nq, a.partial, s);
-    hipLaunchKernelGGL(k_red_add_split, dim3(nssp, a.T), dim3(256), 0, s, a.partial, skinny_slabs(nq), a.x, a.ffn_norm, a.T,
+    LD_LAUNCH(k_red_add_split, dim3(nssp, a.T), dim3(256), 0, s, a.partial, skinny_slabs(nq), a.x, a.ffn_norm, a.T,
                        a.d, a.xs, a.ss_part + (size_t)a.T * nssp);
 }
 
@@ -172,7 +173,7 @@ void launch_batch_gate_up(const BatchLayerArgs &a, hipStream_t s) {
     const int nssp = a.d / RB;
     launch_gemm_skinny(a.wgate_up, a.xs, a.xs + (size_t)a.T * a.d, a.T, 2 * a.ffn, a.d, a.partial, s);
     const int64_t n = (int64_t)a.T * (a.ffn / 4);
-    hipLaunchKernelGGL(k_red_swiglu_split, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.partial, skinny_slabs(a.d),
+    LD_LAUNCH(k_red_swiglu_split, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.partial, skinny_slabs(a.d),
                        a.ss_part + (size_t)a.T * nssp, nssp, a.eps, a.d, a.T, a.ffn, a.xs);
 }
 
@@ -180,7 +181,7 @@ void launch_batch_down(const BatchLayerArgs &a, hipStream_t s) {
     // down; residual; operand + statistics of the next layer's attention norm
     const int nssp = a.d / RB;
     launch_gemm_skinny(a.wdown, a.xs, a.xs + (size_t)a.T * a.ffn, a.T, a.d, a.ffn, a.partial, s);
-    hipLaunchKernelGGL(k_red_add_split, dim3(nssp, a.T), dim3(256), 0, s, a.partial, skinny_slabs(a.ffn), a.x, a.next_norm,
+    LD_LAUNCH(k_red_add_split, dim3(nssp, a.T), dim3(256), 0, s, a.partial, skinny_slabs(a.ffn), a.x, a.next_norm,
                        a.T, a.d, a.xs, a.ss_part);
 }
 

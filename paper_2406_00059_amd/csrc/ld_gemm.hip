@@ -21,6 +21,7 @@
 //    XCD so that the panel is fetched into one L2 only.
 #include "ld_gemm.h"
 #include "ld_device.h"
+#include "ld_internal.h"
 #include <algorithm>
 #include <cstdlib>
 
@@ -352,9 +353,9 @@ void launch_shape(const bf16_t *W, const bf16_t *xs, int T, int N, int K, int ep
     const int rgrid = (int)(((int64_t)T * N + 255) / 256);
 #define LD_GEMM(EPI_)                                                                                                  \
     do {                                                                                                               \
-        hipLaunchKernelGGL((k_gemm_mfma<TT, WC, KCH, EPI_>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, n_ttiles, \
+        LD_LAUNCH((k_gemm_mfma<TT, WC, KCH, EPI_>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, n_ttiles, \
                            ks, partial);                                                                               \
-        if (ks > 1) hipLaunchKernelGGL((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);   \
+        if (ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);   \
     } while (0)
     if (epi == ld::GEMM_STORE) LD_GEMM(ld::GEMM_STORE);
     else if (epi == ld::GEMM_ADD) LD_GEMM(ld::GEMM_ADD);
@@ -377,7 +378,7 @@ size_t gemm_scratch_bytes(int T, int N, int K, int epi) {
 }
 
 void launch_norm_split(const float *x, const float *g, float eps, int T, int K, uint16_t *xs, hipStream_t s) {
-    hipLaunchKernelGGL(k_norm_split, dim3(T), dim3(256), 0, s, x, g, eps, K, xs, xs + (size_t)T * K);
+    LD_LAUNCH(k_norm_split, dim3(T), dim3(256), 0, s, x, g, eps, K, xs, xs + (size_t)T * K);
 }
 
 int skinny_slabs(int K) { return (K + SL - 1) / SL; }
@@ -385,7 +386,7 @@ int skinny_slabs(int K) { return (K + SL - 1) / SL; }
 void launch_gemm_skinny(const uint16_t *W, const uint16_t *xhi, const uint16_t *xlo, int T, int n_rows, int K,
                         float *partial, hipStream_t s) {
     const int ks = skinny_slabs(K);
-    hipLaunchKernelGGL(k_gemm_skinny, dim3(((n_rows + 127) / 128) * ks), dim3(256), 0, s, W, xhi, xlo, T, n_rows, K, ks,
+    LD_LAUNCH(k_gemm_skinny, dim3(((n_rows + 127) / 128) * ks), dim3(256), 0, s, W, xhi, xlo, T, n_rows, K, ks,
                        partial);
 }
 
@@ -394,12 +395,12 @@ void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int
     if (T <= 32) {
         const int ks = split_factor(T, N, K, epi), n_rows = N * (epi == GEMM_SWIGLU ? 2 : 1);
         const bf16_t *hi = xs, *lo = xs + (size_t)T * K;
-        hipLaunchKernelGGL(k_gemm_skinny, dim3(((n_rows + 127) / 128) * ks), dim3(256), 0, s, W, hi, lo, T, n_rows, K, ks,
+        LD_LAUNCH(k_gemm_skinny, dim3(((n_rows + 127) / 128) * ks), dim3(256), 0, s, W, hi, lo, T, n_rows, K, ks,
                            partial);
         const int rgrid = (int)(((int64_t)T * N + 255) / 256);
-        if (epi == GEMM_STORE) hipLaunchKernelGGL((k_splitk_reduce<GEMM_STORE>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
-        else if (epi == GEMM_ADD) hipLaunchKernelGGL((k_splitk_reduce<GEMM_ADD>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
-        else hipLaunchKernelGGL((k_splitk_reduce<GEMM_SWIGLU>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
+        if (epi == GEMM_STORE) LD_LAUNCH((k_splitk_reduce<GEMM_STORE>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
+        else if (epi == GEMM_ADD) LD_LAUNCH((k_splitk_reduce<GEMM_ADD>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
+        else LD_LAUNCH((k_splitk_reduce<GEMM_SWIGLU>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
         return;
     }
     const Shape sh = pick_shape(T, epi);

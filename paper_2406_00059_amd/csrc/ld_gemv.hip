@@ -23,6 +23,7 @@
 //    the position's angle and write k, v straight into the paged pool).
 #include "ld_gemv.h"
 #include "ld_device.h"
+#include "ld_internal.h"
 #include <cstdlib>
 
 using namespace ldd;
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(1024) void k_gemv1(const bf16_t *__restrict__ W, co
 template <int CPW, int GL, bool NORM>
 void launch_cpw(const bf16_t *W, const float *x, const float *g, float eps, int N, int K, int epi, float *y,
                 const ld::RopeKvArgs &rk, int grid, int threads, hipStream_t s) {
-#define LD_GEMV1(EPI_) hipLaunchKernelGGL((k_gemv1<CPW, GL, EPI_, NORM>), dim3(grid), dim3(threads), 0, s, W, x, g, eps, N, K, y, rk)
+#define LD_GEMV1(EPI_) LD_LAUNCH((k_gemv1<CPW, GL, EPI_, NORM>), dim3(grid), dim3(threads), 0, s, W, x, g, eps, N, K, y, rk)
     switch (epi) {
         case ld::GEMV_STORE: LD_GEMV1(ld::GEMV_STORE); break;
         case ld::GEMV_ADD: LD_GEMV1(ld::GEMV_ADD); break;

@@ -22,6 +22,8 @@ void set_error(const char *fmt, ...) {
 }
 void clear_error() { g_err.clear(); }
 
+thread_local LaunchTimer *g_launch_timer = nullptr;
+
 }  // namespace ld
 
 using ld::fail;
@@ -124,8 +126,23 @@ struct ld_kv {
     // optional per-kernel timing
     bool prof_on = false;
     ld_profile prof{};
-    std::vector<hipEvent_t> prof_ev;       // pairs (start, stop)
-    std::vector<int> prof_cat;             // category of pair i in the current pass
+    struct Timer : ld::LaunchTimer {
+        std::vector<hipEvent_t> ev;        // pairs (start, stop), reused from pass to pass
+        std::vector<int> cat;              // category of pair i in the current pass
+        int current = LD_PROF_OTHER;
+        bool failed = false;
+        void next(hipEvent_t *start, hipEvent_t *stop) override {
+            const size_t i = cat.size();
+            while (ev.size() < 2 * (i + 1)) {
+                hipEvent_t e;
+                if (hipEventCreate(&e) != hipSuccess) { failed = true; return; }
+                ev.push_back(e);
+            }
+            *start = ev[2 * i];
+            *stop = ev[2 * i + 1];
+            cat.push_back(current);
+        }
+    } timer;
     int32_t *trow(int s) { return table.data() + (size_t)s * max_blocks; }
     const int32_t *trow(int s) const { return table.data() + (size_t)s * max_blocks; }
 };
@@ -227,24 +244,18 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const 
     }
 
 #define LD_TRY(call) do { ld_status s_ = (call); if (s_ != LD_OK) return s_; } while (0)
-    // With profiling on, bracket the launch with an event pair of the given category.
-    kv->prof_cat.clear();
-#define LD_TIMED(cat, call)                                                                   \
-    do {                                                                                      \
-        if (kv->prof_on) {                                                                    \
-            const size_t i_ = kv->prof_cat.size();                                            \
-            while (kv->prof_ev.size() < 2 * (i_ + 1)) {                                       \
-                hipEvent_t ev_;                                                               \
-                LD_HIP_TRY(hipEventCreate(&ev_));                                              \
-                kv->prof_ev.push_back(ev_);                                                    \
-            }                                                                                 \
-            LD_HIP_TRY(hipEventRecord(kv->prof_ev[2 * i_], st));                              \
-            LD_TRY(call);                                                                     \
-            LD_HIP_TRY(hipEventRecord(kv->prof_ev[2 * i_ + 1], st));                          \
-            kv->prof_cat.push_back(cat);                                                      \
-        } else {                                                                              \
-            LD_TRY(call);                                                                     \
-        }                                                                                     \
+    // With profiling on, every kernel launched inside `call` gets an event pair attached to its dispatch.
+    kv->timer.cat.clear();
+    struct TimerScope {
+        explicit TimerScope(ld::LaunchTimer *t) { ld::g_launch_timer = t; }
+        ~TimerScope() { ld::g_launch_timer = nullptr; }
+    } timer_scope(kv->prof_on ? &kv->timer : nullptr);
+    int ops[LD_PROF_N] = {0};
+#define LD_TIMED(cat_, call)          \
+    do {                              \
+        kv->timer.current = cat_;     \
+        ops[cat_]++;                  \
+        LD_TRY(call);                 \
     } while (0)
     const int d = c.d_model, nq = m.nq(), nqkv = m.nqkv(), H = c.n_heads, Hkv = c.n_kv_heads, hd = c.head_dim;
     const size_t layer_bytes = (size_t)kv->n_blocks * m.block_elems() * m.elem();
@@ -304,11 +315,14 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const 
     if (logits_out && R)
         LD_HIP_TRY(hipMemcpyAsync(logits_out, w.logits, (size_t)R * c.vocab * 4, hipMemcpyDeviceToHost, st));
     LD_HIP_TRY(hipStreamSynchronize(st));
-    for (size_t i = 0; i < kv->prof_cat.size(); i++) {
-        float ms = 0.f;
-        LD_HIP_TRY(hipEventElapsedTime(&ms, kv->prof_ev[2 * i], kv->prof_ev[2 * i + 1]));
-        kv->prof.ms[kv->prof_cat[i]] += ms;
-        kv->prof.launches[kv->prof_cat[i]] += 1;
+    if (kv->prof_on) {
+        if (kv->timer.failed) return fail(LD_E_HIP, "profiling: hipEventCreate failed");
+        for (size_t i = 0; i < kv->timer.cat.size(); i++) {
+            float ms = 0.f;
+            LD_HIP_TRY(hipEventElapsedTime(&ms, kv->timer.ev[2 * i], kv->timer.ev[2 * i + 1]));
+            kv->prof.ms[kv->timer.cat[i]] += ms;
+        }
+        for (int k = 0; k < LD_PROF_N; k++) kv->prof.launches[k] += ops[k];
     }
     return LD_OK;
 }
@@ -467,7 +481,7 @@ void ld_kv_destroy(ld_kv *kv) {
     if (kv->pin_meta) (void)hipHostFree(kv->pin_meta);
     if (kv->pin_out) (void)hipHostFree(kv->pin_out);
     if (kv->pin_table) (void)hipHostFree(kv->pin_table);
-    for (hipEvent_t e : kv->prof_ev) (void)hipEventDestroy(e);
+    for (hipEvent_t e : kv->timer.ev) (void)hipEventDestroy(e);
     delete kv;
 }
 

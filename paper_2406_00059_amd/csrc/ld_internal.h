@@ -1,6 +1,7 @@
 // Internal helpers shared by the host state machine and the kernel launchers.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <cstdarg>
 #include <cstdio>
 #include "ld.h"
@@ -25,10 +26,31 @@ inline ld_status fail(ld_status s, const char *what) {
         }                                                                                 \
     } while (0)
 
+// Per-kernel timing: while a pass is being profiled, every kernel launch of this thread asks the
+// timer for an event pair that the runtime attaches to the dispatch itself (start and end of the
+// kernel, not of the gap around it).  Null when profiling is off.
+struct LaunchTimer {
+    virtual void next(hipEvent_t *start, hipEvent_t *stop) = 0;
+    virtual ~LaunchTimer() {}
+};
+extern thread_local LaunchTimer *g_launch_timer;
+
 ld_status paged_attention_split(const float *q, int q_stride, const void *pool_layer, int dtype, const int32_t *table,
                                 int table_stride, const int32_t *seq_slot, const int32_t *ctx_len, int max_ctx, int T,
                                 int H, int Hkv, int hd, uint16_t *xs_out, void *scratch, size_t scratch_bytes,
                                 hipStream_t stream);
+
+}  // namespace ld
+
+// Every kernel of the library is launched through this macro.
+#define LD_LAUNCH(kernel, grid, block, shmem, stream, ...)                                        \
+    do {                                                                                          \
+        hipEvent_t ev_s_ = nullptr, ev_e_ = nullptr;                                              \
+        if (ld::g_launch_timer) ld::g_launch_timer->next(&ev_s_, &ev_e_);                         \
+        hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, ev_s_, ev_e_, 0, __VA_ARGS__);  \
+    } while (0)
+
+namespace ld {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

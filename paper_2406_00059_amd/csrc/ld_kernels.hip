@@ -366,11 +366,11 @@ void launch_linear_epi(const WT *W, const float *x, const float *g, float eps, i
                        float *y, hipStream_t s) {
     dim3 grid((N + 4 * R - 1) / (4 * R), (T + TT - 1) / TT), block(256);
     if (epi == LDK_STORE)
-        hipLaunchKernelGGL((k_linear_valu<WT, TT, R, LDK_STORE, NORM>), grid, block, 0, s, W, x, g, eps, T, N, K, y);
+        LD_LAUNCH((k_linear_valu<WT, TT, R, LDK_STORE, NORM>), grid, block, 0, s, W, x, g, eps, T, N, K, y);
     else if (epi == LDK_ADD)
-        hipLaunchKernelGGL((k_linear_valu<WT, TT, R, LDK_ADD, NORM>), grid, block, 0, s, W, x, g, eps, T, N, K, y);
+        LD_LAUNCH((k_linear_valu<WT, TT, R, LDK_ADD, NORM>), grid, block, 0, s, W, x, g, eps, T, N, K, y);
     else
-        hipLaunchKernelGGL((k_linear_valu<WT, TT, R, LDK_SWIGLU, NORM>), grid, block, 0, s, W, x, g, eps, T, N, K, y);
+        LD_LAUNCH((k_linear_valu<WT, TT, R, LDK_SWIGLU, NORM>), grid, block, 0, s, W, x, g, eps, T, N, K, y);
 }
 
 template <typename WT, bool NORM>
@@ -401,8 +401,8 @@ ld_status ldk_embed(const void *embed, int32_t dtype, const int32_t *tok, int32_
     if (!embed || !tok || !x || T < 0 || d <= 0 || d % 8) return ld::fail(LD_E_INVAL, "ldk_embed: bad argument");
     if (T == 0) return LD_OK;
     hipStream_t s = (hipStream_t)stream;
-    if (dtype == LD_BF16) hipLaunchKernelGGL(k_embed<bf16_t>, dim3(T), dim3(128), 0, s, (const bf16_t *)embed, tok, d, x);
-    else if (dtype == LD_F32) hipLaunchKernelGGL(k_embed<float>, dim3(T), dim3(128), 0, s, (const float *)embed, tok, d, x);
+    if (dtype == LD_BF16) LD_LAUNCH(k_embed<bf16_t>, dim3(T), dim3(128), 0, s, (const bf16_t *)embed, tok, d, x);
+    else if (dtype == LD_F32) LD_LAUNCH(k_embed<float>, dim3(T), dim3(128), 0, s, (const float *)embed, tok, d, x);
     else return ld::fail(LD_E_INVAL, "ldk_embed: bad dtype");
     return launched("k_embed");
 }
@@ -411,7 +411,7 @@ ld_status ldk_rmsnorm(const float *x, const float *g, const int32_t *row_idx, in
                       float *out, void *stream) {
     if (!x || !g || !out || R < 0 || d <= 0) return ld::fail(LD_E_INVAL, "ldk_rmsnorm: bad argument");
     if (R == 0) return LD_OK;
-    hipLaunchKernelGGL(k_rmsnorm, dim3(R), dim3(256), 0, (hipStream_t)stream, x, g, row_idx, d, eps, out);
+    LD_LAUNCH(k_rmsnorm, dim3(R), dim3(256), 0, (hipStream_t)stream, x, g, row_idx, d, eps, out);
     return launched("k_rmsnorm");
 }
 
@@ -449,7 +449,7 @@ ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *
 ld_status ldk_rope_table(const int32_t *pos, int32_t T, int32_t hd, float rope_base, float *cos_sin, void *stream) {
     if (!pos || !cos_sin || T < 0 || (hd != 64 && hd != 128)) return ld::fail(LD_E_INVAL, "ldk_rope_table: bad argument");
     if (T == 0) return LD_OK;
-    hipLaunchKernelGGL(k_rope_table, dim3(T), dim3(64), 0, (hipStream_t)stream, pos, hd, (double)rope_base,
+    LD_LAUNCH(k_rope_table, dim3(T), dim3(64), 0, (hipStream_t)stream, pos, hd, (double)rope_base,
                        (float2 *)cos_sin);
     return launched("k_rope_table");
 }
@@ -464,10 +464,10 @@ ld_status ldk_rope_kv_write(float *qkv, const float *cos_sin, const int32_t *pos
     dim3 grid(H + Hkv, T), block(64);
     hipStream_t s = (hipStream_t)stream;
     if (dtype == LD_BF16)
-        hipLaunchKernelGGL(k_rope_kv_write<bf16_t>, grid, block, 0, s, qkv, (const float2 *)cos_sin, pos, seq_slot,
+        LD_LAUNCH(k_rope_kv_write<bf16_t>, grid, block, 0, s, qkv, (const float2 *)cos_sin, pos, seq_slot,
                            table, table_stride, (bf16_t *)pool_layer, H, Hkv, hd);
     else if (dtype == LD_F32)
-        hipLaunchKernelGGL(k_rope_kv_write<float>, grid, block, 0, s, qkv, (const float2 *)cos_sin, pos, seq_slot,
+        LD_LAUNCH(k_rope_kv_write<float>, grid, block, 0, s, qkv, (const float2 *)cos_sin, pos, seq_slot,
                            table, table_stride, (float *)pool_layer, H, Hkv, hd);
     else return ld::fail(LD_E_INVAL, "ldk_rope_kv_write: bad dtype");
     return launched("k_rope_kv_write");
@@ -529,9 +529,9 @@ static ld_status paged_attention_impl(const float *q, int32_t q_stride, const vo
     hipStream_t s = (hipStream_t)stream;
 #define LD_ATT(HD_, KVT_)                                                                                         \
     do {                                                                                                          \
-        hipLaunchKernelGGL((k_attn_partial<HD_, KVT_>), grid, block, 0, s, q, q_stride, (const KVT_ *)pool_layer, \
+        LD_LAUNCH((k_attn_partial<HD_, KVT_>), grid, block, 0, s, q, q_stride, (const KVT_ *)pool_layer, \
                            Hkv, table, table_stride, seq_slot, ctx_len, H, sl2, mc, cb, part_o, part_ml);         \
-        hipLaunchKernelGGL((k_attn_merge<HD_>), dim3(H, T), dim3(HD_), 0, s, part_o, part_ml, ctx_len, H, mc, cb, \
+        LD_LAUNCH((k_attn_merge<HD_>), dim3(H, T), dim3(HD_), 0, s, part_o, part_ml, ctx_len, H, mc, cb, \
                            out, xs_out, T);                                                                       \
     } while (0)
     if (dtype == LD_BF16 && hd == 128) LD_ATT(128, bf16_t);
@@ -567,7 +567,7 @@ ld_status ldk_prefill_attention(const float *q, int32_t q_stride, const void *po
 ld_status ldk_argmax(const float *logits, int32_t R, int32_t V, int32_t *out, void *stream) {
     if (R == 0) return LD_OK;
     if (!logits || !out || R < 0 || V <= 0) return ld::fail(LD_E_INVAL, "ldk_argmax: bad argument");
-    hipLaunchKernelGGL(k_argmax, dim3(R), dim3(1024), 0, (hipStream_t)stream, logits, V, out);
+    LD_LAUNCH(k_argmax, dim3(R), dim3(1024), 0, (hipStream_t)stream, logits, V, out);
     return launched("k_argmax");
 }
 

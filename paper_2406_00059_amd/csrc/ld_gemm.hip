@@ -294,6 +294,153 @@ __global__ __launch_bounds__(256, 2) void k_gemm_skinny(const bf16_t *__restrict
     }
 }
 
+// More than 64 rows (prefill chunks, mixed steps): MFMA-bound.  128 tokens x BN weight rows per workgroup,
+// four waves as 2 (tokens) x 2 (columns), both operands through LDS.  K advances in chunks of 32; the
+// global loads of a chunk are issued FOUR chunks (~4000 MFMA cycles per wave) before their data is
+// written to LDS, in a ring of register sets, which covers L2 latency at one wave per SIMD; LDS is double
+// buffered, one barrier per chunk.  LDS holds 16-byte pieces segment-major ([k-segment][row], segment
+// stride padded by 64 bytes): the operand reads of 16 consecutive lanes are 256 contiguous bytes and the
+// staging writes of a 16-lane group (4 rows x 4 segments) cover all 64 banks once.
+template <int BN, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_big(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
+                                                  const bf16_t *__restrict__ xlo, int T, int N, int K,
+                                                  float *__restrict__ y, int n_ttiles, int ks,
+                                                  float *__restrict__ partial) {
+    constexpr bool SWI = (EPI == ld::GEMM_SWIGLU);
+    constexpr int BM = 128, BK = 32, SEGS = BK / 8, D = 4;
+    constexpr int WCT = BN / 2 / 32;              // 32-column accumulator tiles per wave
+    constexpr int NOUT = SWI ? BN / 2 : BN;       // output columns per workgroup
+    constexpr int XSEG = BM * 16 + 64, WSEG = BN * 16 + 64;   // bytes per k-segment of a stage
+    constexpr int NVX = 4, NVW = BN / 64;         // 16-byte pieces per thread per chunk
+    __shared__ __attribute__((aligned(16))) char xs[2][2][SEGS][XSEG];
+    __shared__ __attribute__((aligned(16))) char ws[2][SEGS][WSEG];
+
+    const int b = blockIdx.x, xcd = b & 7, s = b >> 3;
+    const int kz = s % ks, tt_idx = (s / ks) % n_ttiles, nb = (s / (ks * n_ttiles)) * 8 + xcd;
+    const int n_nblocks = (N + NOUT - 1) / NOUT;
+    if (nb >= n_nblocks) return;
+    const int t0 = tt_idx * BM, n0 = nb * NOUT;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // global source of every piece this thread stages (rows clamped; clamped rows are never stored)
+    const bf16_t *xsrc[NVX], *wsrc[NVW];
+    int xdst[NVX], wdst[NVW];
+#pragma unroll
+    for (int v = 0; v < NVX; v++) {
+        const int p = threadIdx.x + 256 * v, part = p >> 9, r = (p & 511) >> 2, seg = p & 3;
+        xsrc[v] = (part ? xlo : xhi) + (int64_t)min(t0 + r, T - 1) * K + seg * 8;
+        xdst[v] = (part * SEGS + seg) * XSEG + r * 16;
+    }
+#pragma unroll
+    for (int v = 0; v < NVW; v++) {
+        const int p = threadIdx.x + 256 * v, wr = p >> 2, seg = p & 3;
+        int grow;
+        if (SWI) {   // local rows of a wave column: gate tiles, then the up tiles of the same columns
+            const int wcol = wr / (BN / 2), within = wr % (BN / 2);
+            const int col = n0 + wcol * (BN / 4) + (within % (BN / 4));
+            grow = min(col, N - 1) + (within >= BN / 4 ? N : 0);
+        } else {
+            grow = min(n0 + wr, N - 1);
+        }
+        wsrc[v] = W + (int64_t)grow * K + seg * 8;
+        wdst[v] = seg * WSEG + wr * 16;
+    }
+
+    f32x16 acc[2][WCT];
+#pragma unroll
+    for (int tt = 0; tt < 2; tt++)
+#pragma unroll
+        for (int wc = 0; wc < WCT; wc++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) acc[tt][wc][i] = 0.f;
+
+    u32x4 ring[D][NVX + NVW];
+    auto issue = [&](u32x4 (&r)[NVX + NVW], int kc) {
+#pragma unroll
+        for (int v = 0; v < NVX; v++) r[v] = *reinterpret_cast<const u32x4 *>(xsrc[v] + kc * BK);
+#pragma unroll
+        for (int v = 0; v < NVW; v++) r[NVX + v] = *reinterpret_cast<const u32x4 *>(wsrc[v] + kc * BK);
+    };
+    auto stage = [&](const u32x4 (&r)[NVX + NVW], int st) {
+#pragma unroll
+        for (int v = 0; v < NVX; v++) *reinterpret_cast<u32x4 *>(&xs[st][0][0][0] + xdst[v]) = r[v];
+#pragma unroll
+        for (int v = 0; v < NVW; v++) *reinterpret_cast<u32x4 *>(&ws[st][0][0] + wdst[v]) = r[NVX + v];
+    };
+    auto compute = [&](int st) {
+#pragma unroll
+        for (int kstep = 0; kstep < BK / 16; kstep++) {
+            const int seg = kstep * 2 + half;
+            bf16x8 a[2][2], bw[WCT];
+#pragma unroll
+            for (int part = 0; part < 2; part++)
+#pragma unroll
+                for (int tt = 0; tt < 2; tt++)
+                    a[part][tt] = __builtin_bit_cast(
+                        bf16x8, *reinterpret_cast<const u32x4 *>(&xs[st][part][seg][(wm * 64 + tt * 32 + l32) * 16]));
+#pragma unroll
+            for (int wc = 0; wc < WCT; wc++)
+                bw[wc] = __builtin_bit_cast(
+                    bf16x8, *reinterpret_cast<const u32x4 *>(&ws[st][seg][(wn * (BN / 2) + wc * 32 + l32) * 16]));
+#pragma unroll
+            for (int part = 0; part < 2; part++)
+#pragma unroll
+                for (int tt = 0; tt < 2; tt++)
+#pragma unroll
+                    for (int wc = 0; wc < WCT; wc++)
+                        acc[tt][wc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[part][tt], bw[wc], acc[tt][wc], 0, 0, 0);
+        }
+    };
+
+    const int c_begin = (int)((int64_t)kz * (K / BK) / ks), c_end = (int)((int64_t)(kz + 1) * (K / BK) / ks);
+#pragma unroll
+    for (int d = 0; d < D; d++)
+        if (c_begin + d < c_end) issue(ring[d], c_begin + d);
+    for (int c = c_begin; c < c_end; c += D) {
+#pragma unroll
+        for (int d = 0; d < D; d++) {
+            const int cc = c + d;
+            if (cc < c_end) {
+                stage(ring[d], d & 1);
+                lds_barrier();
+                if (cc + D < c_end) issue(ring[d], cc + D);
+                compute(d & 1);
+            }
+        }
+    }
+
+    // accumulator element i of lane (l32, half): token t0 + wm*64 + tt*32 + 8*(i/4) + 4*half + i%4
+    constexpr int WOUT = SWI ? WCT / 2 : WCT;     // output column tiles per wave
+    const int ncols = SWI ? 2 * N : N;            // row length of the partial-sum buffer
+#pragma unroll
+    for (int wc = 0; wc < WOUT; wc++) {
+        const int n = n0 + wn * (NOUT / 2) + wc * 32 + l32;
+        if (n >= N) continue;
+#pragma unroll
+        for (int tt = 0; tt < 2; tt++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const int t = t0 + wm * 64 + tt * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+                if (t >= T) continue;
+                if (ks > 1) {
+                    float *dst = partial + ((int64_t)kz * T + t) * ncols + n;
+                    dst[0] = acc[tt][wc][i];
+                    if constexpr (SWI) dst[N] = acc[tt][wc + WCT / 2][i];
+                } else {
+                    float *dst = y + (int64_t)t * N + n;
+                    if constexpr (EPI == ld::GEMM_STORE) *dst = acc[tt][wc][i];
+                    else if constexpr (EPI == ld::GEMM_ADD) *dst += acc[tt][wc][i];
+                    else {
+                        const float gate = acc[tt][wc][i], up = acc[tt][wc + WCT / 2][i];
+                        *dst = gate / (1.0f + __expf(-gate)) * up;
+                    }
+                }
+            }
+    }
+}
+
 // Adds the ks K-slab partial sums in slab order and applies the epilogue.  One thread per output.
 template <int EPI>
 __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__ partial, int T, int N, int ks,
@@ -316,6 +463,25 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__
 // Tile shape by row count: up to 32 rows -> skinny kernel (the 32 x 128 tile is kept for completeness);
 // up to 64 rows -> 64 x 128, 128-wide K chunks; more -> 64 rows x 256 columns (128 for SwiGLU), 64-wide chunks.
 struct Shape { int tt, wc, kch; };
+
+// Workgroup count and split-K factor of the big-tile kernel for a row count.
+struct BigPlan { int bn, n_ttiles, n_nblocks, ks; };
+BigPlan plan_big(int T, int N, int K, int epi) {
+    const bool swi = epi == ld::GEMM_SWIGLU;
+    BigPlan p;
+    p.n_ttiles = (T + 127) / 128;
+    // 256 weight rows per workgroup when that still gives every CU a workgroup, else 128
+    const int nout256 = swi ? 128 : 256;
+    p.bn = (p.n_ttiles * ((N + nout256 - 1) / nout256) >= 256) ? 256 : 128;
+    const int nout = swi ? p.bn / 2 : p.bn;
+    p.n_nblocks = (N + nout - 1) / nout;
+    const int wgs = p.n_ttiles * p.n_nblocks;
+    int ks = (256 + wgs - 1) / wgs;                // fill the CUs once
+    ks = std::min(ks, K / 32 / 8);                 // at least eight chunks per slab
+    ks = std::min(ks, std::max(1, K / (8 * T)));   // partial sums: at most a quarter of the matrix bytes
+    p.ks = std::max(ks, 1);
+    return p;
+}
 int env_int(const char *name, int dflt) {
     const char *v = getenv(name);
     return v ? atoi(v) : dflt;
@@ -330,6 +496,7 @@ Shape pick_shape(int T, int epi) {
 
 int split_factor(int T, int N, int K, int epi) {
     if (T <= 32) return (K + SL - 1) / SL;        // skinny kernel: one 512-wide slab per workgroup
+    if (T > 64) return plan_big(T, N, K, epi).ks;
     const Shape sh = pick_shape(T, epi);
     const int n_ttiles = (T + sh.tt * 32 - 1) / (sh.tt * 32), n_nblocks = (N + 128 * sh.wc - 1) / (128 * sh.wc);
     const int wgs = n_ttiles * n_nblocks;
@@ -401,6 +568,28 @@ void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int
         if (epi == GEMM_STORE) LD_LAUNCH((k_splitk_reduce<GEMM_STORE>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
         else if (epi == GEMM_ADD) LD_LAUNCH((k_splitk_reduce<GEMM_ADD>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
         else LD_LAUNCH((k_splitk_reduce<GEMM_SWIGLU>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
+        return;
+    }
+    if (T > 64) {
+        const BigPlan p = plan_big(T, N, K, epi);
+        const int grid = ((p.n_nblocks + 7) / 8) * 8 * p.n_ttiles * p.ks;
+        const bf16_t *hi = xs, *lo = xs + (size_t)T * K;
+        const int rgrid = (int)(((int64_t)T * N + 255) / 256);
+#define LD_BIG(BN_, EPI_)                                                                                              \
+    do {                                                                                                               \
+        LD_LAUNCH((k_gemm_big<BN_, EPI_>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, p.n_ttiles, p.ks, partial); \
+        if (p.ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, p.ks, y);       \
+    } while (0)
+        if (p.bn == 256) {
+            if (epi == GEMM_STORE) LD_BIG(256, GEMM_STORE);
+            else if (epi == GEMM_ADD) LD_BIG(256, GEMM_ADD);
+            else LD_BIG(256, GEMM_SWIGLU);
+        } else {
+            if (epi == GEMM_STORE) LD_BIG(128, GEMM_STORE);
+            else if (epi == GEMM_ADD) LD_BIG(128, GEMM_ADD);
+            else LD_BIG(128, GEMM_SWIGLU);
+        }
+#undef LD_BIG
         return;
     }
     const Shape sh = pick_shape(T, epi);

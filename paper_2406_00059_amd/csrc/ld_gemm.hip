@@ -5,20 +5,18 @@
 // product carries ~16 significant bits of the activation instead of 8.  In the decode regime the
 // kernel is bound by the weight stream from HBM, where the second MFMA pass is free.
 //
-// Data movement:
-//  - A one-pass prologue kernel applies RMSNorm (optional) and writes the (hi, lo) bf16 images.
-//  - A workgroup of 4 waves owns 128 consecutive output columns (rows of W; 32 per wave) and a tile
-//    of TT*32 rows of X.  W is streamed from global memory straight into MFMA B-operand registers:
-//    lane (n = lane % 32, h = lane / 32) loads 16 bytes of row n; the contraction order over k is
-//    permuted so that the four loads of one 64-wide k-group give every row 128 contiguous bytes
-//    (k = kg*64 + h*32 + j*8 + e for load j), and the X operand is read with the same permutation.
-//  - The X tile (hi and lo) of the current 128-wide K chunk is staged in LDS and shared by the
-//    four waves; rows are padded by 16 bytes against bank conflicts.
-//  - Global loads (W fragments and the next X chunk) are issued one chunk ahead of their use.
-//  - With the token index on the MFMA row side, each accumulator register holds 32 consecutive
-//    output columns of one token, so stores are 128-byte contiguous.
-//  - Workgroups that share a W panel (same columns, different token tiles) are mapped to the same
-//    XCD so that the panel is fetched into one L2 only.
+// Three kernels by row count, all with the token index on the MFMA row side (an accumulator register
+// then holds 32 consecutive output columns of one token and stores are 128-byte contiguous), all fed
+// by a one-pass prologue (k_norm_split, or the fused producers of ld_batch.hip) that writes the
+// (hi, lo) bf16 images of the activations:
+//  - k_gemm_skinny (2..32 rows): weight-stream bound; slab-resident, see its comment.
+//  - k_gemm_mfma (33..64 rows): W streamed from global memory straight into B-operand registers
+//    (lane (n = lane % 32, h = lane / 32) loads 16 bytes of row n; the contraction order over k is
+//    permuted so that the four loads of a 64-wide k-group give a row 128 contiguous bytes), X staged
+//    through padded LDS, loads issued one chunk ahead.
+//  - k_gemm_big (> 64 rows): MFMA-bound; both operands through LDS, see its comment.
+// Workgroups that share a W panel (same columns, different token tiles) are mapped to the same XCD so
+// that the panel is fetched into one L2 only.  Split-K partial sums are added in fixed slab order.
 #include "ld_gemm.h"
 #include "ld_device.h"
 #include "ld_internal.h"
@@ -460,8 +458,8 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__
     else y[idx] = a / (1.0f + __expf(-a)) * b;
 }
 
-// Tile shape by row count: up to 32 rows -> skinny kernel (the 32 x 128 tile is kept for completeness);
-// up to 64 rows -> 64 x 128, 128-wide K chunks; more -> 64 rows x 256 columns (128 for SwiGLU), 64-wide chunks.
+// Kernel by row count: up to 32 rows -> k_gemm_skinny; 33..64 rows -> k_gemm_mfma with 64 x 128 tiles and
+// 128-wide K chunks; more -> k_gemm_big.
 struct Shape { int tt, wc, kch; };
 
 // Workgroup count and split-K factor of the big-tile kernel for a row count.
@@ -487,11 +485,8 @@ int env_int(const char *name, int dflt) {
     return v ? atoi(v) : dflt;
 }
 Shape pick_shape(int T, int epi) {
-    if (T <= 32) return {1, 1, 128};
-    if (T <= 64) return {2, 1, 128};
-    // measured on the 7B shapes at 256 and 1056 rows: 64 x 256 tiles at two waves per SIMD beat
-    // 128 x 256 tiles at one wave per SIMD
-    return {2, epi == ld::GEMM_SWIGLU ? 1 : 2, 64};
+    (void)T; (void)epi;
+    return {2, 1, 128};   // 33..64 rows: 64 x 128 tiles, 128-wide K chunks
 }
 
 int split_factor(int T, int N, int K, int epi) {
@@ -592,11 +587,7 @@ void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int
 #undef LD_BIG
         return;
     }
-    const Shape sh = pick_shape(T, epi);
-    if (sh.tt == 1) launch_shape<1, 1, 128>(W, xs, T, N, K, epi, y, partial, s);
-    else if (sh.kch == 128) launch_shape<2, 1, 128>(W, xs, T, N, K, epi, y, partial, s);
-    else if (sh.wc == 1) launch_shape<2, 1, 64>(W, xs, T, N, K, epi, y, partial, s);
-    else launch_shape<2, 2, 64>(W, xs, T, N, K, epi, y, partial, s);
+    launch_shape<2, 1, 128>(W, xs, T, N, K, epi, y, partial, s);   // 33..64 rows
 }
 
 }  // namespace ld

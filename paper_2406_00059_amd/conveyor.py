@@ -1,0 +1,281 @@
+"""Host-side tool-aware serving loop on top of the engine's per-token callback.
+
+This is the part of the paper that sits above the engine (sections 3.2 and 3.3): tool developers wrap a tool
+in a plugin that says when it can start and which pieces of decoded data it consumes; a streaming parser
+turns the token stream into completed pieces as they are decoded; a token-granularity scheduler runs the LLM
+one iteration at a time, hands every new token to the parser, starts a tool in a separate process as soon as
+its plugin says it can start (tool partial execution), polls the running tools every iteration, and prefills
+a tool's observation into the sequence when it is available.  With `partial=False` the same code is the
+baseline of section 4.1: a tool starts only when its round has been decoded to the end.
+
+Everything here is host logic: no GPU work happens in this file, the engine does it.  Tools run in forked
+child processes with a duplex pipe (section 3.3 steps (6), (7)); the children never touch the GPU.
+"""
+from __future__ import annotations
+
+import multiprocessing as mp
+import os
+import time
+from dataclasses import dataclass, field
+
+
+# ------------------------------------------------------------------ parser
+
+class StreamParser:
+    """Streaming token parser: tokens in, completed pieces out.
+
+    A piece is the run of tokens up to (not including) a delimiter; it is emitted at once when its delimiter
+    is decoded.  `is_delimiter(token, index)` gets the token and its index inside the round, so synthetic
+    workloads can place delimiters by position (a stand-in for a newline or a closing-quote token)."""
+
+    def __init__(self, is_delimiter):
+        self.is_delimiter = is_delimiter
+        self.cur, self.index, self.pieces = [], 0, []
+
+    def feed(self, token: int):
+        done = []
+        if self.is_delimiter(token, self.index):
+            done.append(self.cur)
+            self.pieces.append(self.cur)
+            self.cur = []
+        else:
+            self.cur.append(token)
+        self.index += 1
+        return done
+
+    def flush(self):
+        """End of the round: the unterminated tail is the last piece."""
+        if self.cur:
+            self.pieces.append(self.cur)
+            self.cur = []
+        return self.pieces
+
+
+# ------------------------------------------------------------------ plugin interface
+
+class ToolPlugin:
+    """What a tool developer writes: when the tool can start and what it does with the decoded pieces.
+
+    `pieces_to_start` completed pieces are enough to start the tool (1: the invocation indicator, e.g. a
+    function name; more: the indicator plus arguments; None: the tool needs the whole round).  `run` is
+    executed in the tool's own process and returns the observation as token ids."""
+
+    name = "tool"
+    pieces_to_start = 1
+
+    def can_start(self, pieces) -> bool:
+        return self.pieces_to_start is not None and len(pieces) >= self.pieces_to_start
+
+    def run(self, pieces):
+        raise NotImplementedError
+
+
+class SyntheticTool(ToolPlugin):
+    """A tool of a set duration that returns a fixed, seeded observation."""
+
+    def __init__(self, duration_s: float, observation, pieces_to_start=1, name="synthetic"):
+        self.duration_s, self.observation = duration_s, [int(t) for t in observation]
+        self.pieces_to_start, self.name = pieces_to_start, name
+
+    def run(self, pieces):
+        time.sleep(self.duration_s)
+        return self.observation
+
+
+def _tool_main(conn, plugin):
+    try:
+        pieces = conn.recv()
+        t0 = time.perf_counter()
+        obs = plugin.run(pieces)
+        conn.send((obs, time.perf_counter() - t0))
+    finally:
+        conn.close()
+        os._exit(0)          # no interpreter tear-down in the child: it shares nothing it may clean up
+
+
+class ToolProcess:
+    """One tool instance in a forked child process, duplex pipe for the command and the observation."""
+
+    def __init__(self, plugin: ToolPlugin, pieces):
+        self.started = time.perf_counter()
+        self.conn, child = mp.get_context("fork").Pipe(duplex=True)
+        self.proc = mp.get_context("fork").Process(target=_tool_main, args=(child, plugin), daemon=True)
+        self.proc.start()
+        child.close()
+        self.conn.send(pieces)
+
+    def poll(self):
+        """(observation, tool seconds) if the tool has finished, else None.  Never blocks."""
+        if self.conn.poll(0):
+            res = self.conn.recv()
+            self.proc.join()
+            return res
+        return None
+
+    def wait(self):
+        res = self.conn.recv()
+        self.proc.join()
+        return res
+
+
+# ------------------------------------------------------------------ requests and the scheduler
+
+@dataclass
+class Round:
+    n_tokens: int                     # tokens generated in this round (the first comes from the prefill)
+    tool: ToolPlugin | None = None    # tool invoked by this round's output (None: final round)
+    delimiter_every: int = 8          # synthetic syntax: every k-th token of the round closes a piece
+
+
+@dataclass
+class Request:
+    prompt: list
+    rounds: list
+    # filled in by the scheduler
+    tokens: list = field(default_factory=list)        # all generated tokens
+    g: list = field(default_factory=list)             # generation seconds per round (prefill + decode)
+    t: list = field(default_factory=list)             # tool seconds per round (as measured in the child)
+    s: list = field(default_factory=list)             # seconds into the round at which the tool was started
+    latency: float = 0.0
+
+
+class Scheduler:
+    """Token-granularity scheduler (section 3.3).  `engine` provides
+         new_sequence() -> seq, prefill(seq, tokens) -> token, decode(seqs) -> tokens, free(seq)."""
+
+    def __init__(self, engine, partial=True):
+        self.engine, self.partial = engine, partial
+
+    def serve(self, requests):
+        eng = self.engine
+        t_start = time.perf_counter()
+        st = []
+        for r in requests:
+            st.append(dict(req=r, seq=eng.new_sequence(), round=0, left=0, parser=None, tool=None, obs=None,
+                           feed=list(r.prompt), round_t0=t_start, t_start=t_start, done=False))
+        while not all(x["done"] for x in st):
+            # (8) poll the plugins: collect observations of tools that have finished
+            for x in st:
+                if x["tool"] is not None and x["obs"] is None:
+                    res = x["tool"].poll()
+                    if res is not None:
+                        x["obs"] = res
+            # (2) prefill whatever is ready: a new prompt, or an observation whose round has ended
+            decoding = []
+            for x in st:
+                if x["done"]:
+                    continue
+                if x["feed"] is None and x["left"] == 0 and x["tool"] is not None and x["obs"] is not None:
+                    obs, tool_s = x["obs"]
+                    x["req"].t.append(tool_s)
+                    x["feed"], x["tool"], x["obs"] = list(obs), None, None
+                    x["round_t0"] = time.perf_counter()
+                if x["feed"] is not None:
+                    rd = x["req"].rounds[x["round"]]
+                    x["parser"] = StreamParser(lambda tok, i, k=rd.delimiter_every: (i + 1) % k == 0)
+                    x["left"] = rd.n_tokens
+                    self._emit(x, eng.prefill(x["seq"], x["feed"]))
+                    x["feed"] = None
+                elif x["left"] > 0:
+                    decoding.append(x)
+            # (2)+(3) one decoding iteration for every sequence that is generating; tokens go to the parsers
+            if decoding:
+                for x, tok in zip(decoding, eng.decode([x["seq"] for x in decoding])):
+                    self._emit(x, tok)
+            elif not any(x["feed"] is not None for x in st if not x["done"]):
+                time.sleep(0.0005)       # every live request waits for a tool: nothing to run on the GPU
+        for x in st:
+            eng.free(x["seq"])
+        return requests
+
+    def _emit(self, x, tok):
+        req, rd = x["req"], x["req"].rounds[x["round"]]
+        req.tokens.append(tok)
+        x["left"] -= 1
+        x["parser"].feed(tok)
+        now = time.perf_counter()
+        last = x["left"] == 0
+        # (4)-(6): start the tool as soon as its plugin can start (partial execution), or at the end of the
+        # round (baseline, and tools that need the whole output)
+        if rd.tool is not None and x["tool"] is None:
+            pieces = x["parser"].pieces
+            if (self.partial and rd.tool.can_start(pieces)) or last:
+                if last:
+                    pieces = x["parser"].flush()
+                x["tool"] = ToolProcess(rd.tool, [list(p) for p in pieces])
+                req.s.append(now - x["round_t0"])
+        if last:
+            req.g.append(now - x["round_t0"])
+            if rd.tool is None:                       # final round: the response is ready (9)
+                x["done"] = True
+                req.latency = now - x["t_start"]
+            else:
+                x["round"] += 1
+
+
+def serve(engine, requests, partial=True):
+    """Runs the requests to completion; every request gets its tokens, per-round g / t / s and its latency
+    (from the start of the call to its final token)."""
+    return Scheduler(engine, partial).serve(requests)
+
+
+# ------------------------------------------------------------------ engines
+
+class LdEngine:
+    """Adapter of the C-ABI engine to the scheduler's interface (argument marshalling only)."""
+
+    def __init__(self, ld, kv_handle, stream=None):
+        self.ld, self.kv, self.stream = ld, kv_handle, stream
+        self._last = {}
+
+    def _cb(self, seq, tok, pos):
+        self._last[seq] = tok
+        return 0
+
+    def new_sequence(self):
+        return self.ld.ld_kv_alloc(self.kv, 0)
+
+    def prefill(self, seq, tokens):
+        self.ld.ld_prefill(self.kv, seq, tokens, self.stream, self._cb)
+        return self._last[seq]
+
+    def decode(self, seqs):
+        self.ld.ld_decode_step(self.kv, seqs, self.stream, self._cb)
+        return [self._last[s] for s in seqs]
+
+    def free(self, seq):
+        self.ld.ld_kv_free(self.kv, seq)
+
+
+class FakeEngine:
+    """A stand-in engine for tests without a GPU: a fixed time per call and tokens that are a pure function
+    of the sequence's history, so two runs over the same inputs produce the same tokens."""
+
+    def __init__(self, per_token_s=0.002, prefill_s=0.004, vocab=1000):
+        self.per_token_s, self.prefill_s, self.vocab = per_token_s, prefill_s, vocab
+        self.hist, self.next_id = {}, 0
+
+    def _next(self, seq):
+        h = 1469598103934665603
+        for t in self.hist[seq][-16:]:
+            h = ((h ^ (t + 1)) * 1099511628211) & ((1 << 64) - 1)
+        tok = (h >> 20) % self.vocab
+        self.hist[seq].append(tok)
+        return tok
+
+    def new_sequence(self):
+        self.next_id += 1
+        self.hist[self.next_id] = []
+        return self.next_id
+
+    def prefill(self, seq, tokens):
+        time.sleep(self.prefill_s)
+        self.hist[seq].extend(tokens)
+        return self._next(seq)
+
+    def decode(self, seqs):
+        time.sleep(self.per_token_s)
+        return [self._next(s) for s in seqs]
+
+    def free(self, seq):
+        self.hist.pop(seq, None)

@@ -1,0 +1,71 @@
+"""Host-side tool-aware serving loop (paper sections 3.2-3.4) without a GPU: parser, plugin interface, tool
+processes, scheduler in baseline and partial-execution mode over a stand-in engine, and the latency bounds of
+Eq. (1) and Eq. (2)."""
+import random
+
+import pytest
+
+from oracle import latency_model as lm
+from paper_2406_00059_amd import conveyor as cv
+
+
+def test_latency_model_bounds_and_best_case_curve():
+    rng = random.Random(3)
+    for _ in range(200):
+        n = rng.randint(1, 4)
+        g = [rng.uniform(0.01, 2.0) for _ in range(n + 1)]
+        t = [rng.uniform(0.0, 3.0) for _ in range(n)]
+        s = [rng.uniform(0.0, gi) for gi in g[:-1]]
+        assert lm.l_best(g, t) <= lm.l_new(g, t, s) + 1e-12 <= lm.l_old(g, t) + 1e-12      # Eq. (2)
+        assert lm.l_new(g, t, [0.0] * n) == pytest.approx(lm.l_best(g, t))                 # started at once
+        assert lm.l_new(g, t, g[:-1]) == pytest.approx(lm.l_old(g, t))                     # started at the end
+    # one round, no trailing generation: the best-case improvement is r = t/g for r <= 1 and 1/r for r >= 1
+    for r in (0.1, 0.5, 1.0, 2.0, 10.0):
+        assert lm.best_improvement([1.0, 0.0], [r]) == pytest.approx(min(r, 1.0 / r))
+
+
+def test_stream_parser_emits_pieces_at_their_delimiter():
+    p = cv.StreamParser(lambda tok, i: tok == 0)
+    out = [p.feed(t) for t in [5, 6, 0, 7, 0, 0, 8]]
+    assert out == [[], [], [[5, 6]], [], [[7]], [[]], []]
+    assert p.flush() == [[5, 6], [7], [], [8]]
+
+
+def test_plugin_start_condition():
+    t = cv.SyntheticTool(0.0, [1, 2], pieces_to_start=2)
+    assert not t.can_start([[1]]) and t.can_start([[1], [2]])
+    whole = cv.SyntheticTool(0.0, [1], pieces_to_start=None)
+    assert not whole.can_start([[1], [2], [3]])
+
+
+def test_tool_process_round_trip():
+    tp = cv.ToolProcess(cv.SyntheticTool(0.05, [9, 8, 7]), [[1, 2]])
+    assert tp.poll() is None
+    obs, secs = tp.wait()
+    assert obs == [9, 8, 7] and 0.04 <= secs < 0.5
+
+
+def _requests(tool_s):
+    obs = list(range(100, 140))
+    return [cv.Request(prompt=list(range(10 + k, 42 + k)),
+                       rounds=[cv.Round(40, cv.SyntheticTool(tool_s, obs, pieces_to_start=1)),
+                               cv.Round(24, cv.SyntheticTool(tool_s / 2, obs[:16], pieces_to_start=2)),
+                               cv.Round(16, None)]) for k in range(2)]
+
+
+@pytest.mark.parametrize("tool_s", [0.03, 0.12])
+def test_partial_execution_keeps_tokens_and_obeys_the_bounds(tool_s):
+    base = cv.serve(cv.FakeEngine(), _requests(tool_s), partial=False)
+    part = cv.serve(cv.FakeEngine(), _requests(tool_s), partial=True)
+    slack = 0.06                     # process start, pipe, polling granularity
+    for b, p in zip(base, part):
+        assert b.tokens == p.tokens and len(p.tokens) == 80          # same LLM output in both modes
+        assert len(p.g) == 3 and len(p.t) == 2 and len(p.s) == 2
+        # baseline: tools start when their round ends; partial: after the first delimiter(s)
+        assert all(abs(si - gi) < 0.02 for si, gi in zip(b.s, b.g))
+        assert all(si < 0.8 * gi for si, gi in zip(p.s, p.g))       # 8 of 40 and 16 of 24 tokens in
+        # measured latencies against the model evaluated on the measured g, t, s
+        assert b.latency == pytest.approx(lm.l_old(b.g, b.t), abs=slack)
+        assert p.latency == pytest.approx(lm.l_new(p.g, p.t, p.s), abs=slack)
+        assert lm.l_best(p.g, p.t) - 1e-3 <= p.latency <= lm.l_old(p.g, p.t) + slack
+    assert sum(p.latency for p in part) < sum(b.latency for b in base)

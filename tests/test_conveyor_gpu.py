@@ -1,0 +1,46 @@
+"""The tool-aware serving loop over the real engine on the GPU: tokens equal the oracle's for the same
+sequence of prefills and decodes, equal between baseline and partial execution (same LLM output in both
+modes, section 4.1), and the measured latencies obey Eq. (2)."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2406_00059_amd as ld
+from oracle import latency_model as lm
+from paper_2406_00059_amd import conveyor as cv
+from workloads import TINY
+from helpers import Pair, prompt
+
+pytestmark = pytest.mark.gpu
+
+
+def _requests(tool_s):
+    obs = prompt(31, 9, 48, TINY.vocab).tolist()
+    return [cv.Request(prompt=prompt(31, k, 40, TINY.vocab).tolist(),
+                       rounds=[cv.Round(48, cv.SyntheticTool(tool_s, obs, pieces_to_start=1)),
+                               cv.Round(32, cv.SyntheticTool(tool_s, obs[:20], pieces_to_start=2)),
+                               cv.Round(16, None)]) for k in range(3)]
+
+
+def test_rounds_with_tools_match_oracle_and_bounds():
+    P = Pair(TINY, 31, n_blocks=64, max_tokens=64, max_seqs=3, max_blocks=16)
+    runs = {}
+    for partial in (False, True):
+        reqs = cv.serve(cv.LdEngine(ld, P.gkv.h), _requests(0.03), partial=partial)
+        runs[partial] = reqs
+    for b, p in zip(runs[False], runs[True]):
+        assert b.tokens == p.tokens and len(p.tokens) == 96
+        assert lm.l_best(p.g, p.t) - 1e-3 <= p.latency <= lm.l_old(p.g, p.t) + 0.08
+        assert p.latency == pytest.approx(lm.l_new(p.g, p.t, p.s), abs=0.08)
+    assert sum(p.latency for p in runs[True]) < sum(b.latency for b in runs[False])
+    # the same call sequence through the oracle, one request at a time
+    for k, r in enumerate(runs[True]):
+        rc, s = P.okv.alloc(0)
+        ref, feed = [], r.prompt
+        for rd in r.rounds:
+            rc, t, _ = P.okv.prefill(s, np.array(feed, np.int32), want_logits=False); ref.append(t)
+            for _ in range(rd.n_tokens - 1):
+                rc, t, _ = P.okv.decode(s, want_logits=False); ref.append(t)
+            feed = rd.tool.observation if rd.tool else None
+        assert ref == r.tokens, k
+        P.okv.free(s)

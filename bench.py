@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-batch32", action="store_true", help="skip the batch-32 continuous-batching leg")
     ap.add_argument("--only-batch32", action="store_true", help="debug: run only the batch-32 leg (prints its dict)")
+    ap.add_argument("--only-13b", action="store_true",
+                    help="run only the 13B-shaped batch-64 workload (~200 GB KV pool, 64 steps of 63 decode rows + one "
+                         "2048-token prefill chunk); prints its dict instead of the benchmark line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device-to-device copy (a plain copy kernel of known size, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -284,6 +287,79 @@ def run_batch32(args, ld, torch, shape, model):
     return out
 
 
+def run_13b(args, ld, torch):
+    """13B-shaped decoder, batch 64, paged pool of ~200 GB: contexts drawn uniform in [1024, 16384] and
+    scaled by a common factor so that they fit the pool; every step one sequence is a finished request that
+    is replaced (its blocks freed, the first 2048-token chunk of a new request prefilled) while the other
+    63 decode one token."""
+    import numpy as np
+    from workloads import LLAMA13B, SEED_BASE, gen, make_weights
+    shape = LLAMA13B if not args.layers else LLAMA13B.with_layers(args.layers)
+    seed = SEED_BASE + 4
+    B, steps, chunk = 64, 64, 2048
+    weights = make_weights(shape, seed, device="cuda")
+    model = ld.Model(shape, weights, max_chunk=chunk)
+    n_blocks = int(200e9 // (shape.kv_bytes_per_token * 16)) if not args.layers else 15258
+    drawn = gen.randint(seed, 1, 1024, 16384, B).tolist()
+    budget = n_blocks * 16 - B * (steps + 16) - (chunk + 16) - B * 16
+    scale = min(1.0, budget / sum(drawn))
+    lens = [max(16, int(n * scale)) for n in drawn]
+    nblk_seq = (max(max(lens), chunk) + steps + 32) // 16 + 1
+    pool = torch.empty((shape.n_layers, n_blocks, 2, shape.n_kv_heads, 16, shape.head_dim), dtype=torch.bfloat16,
+                       device="cuda")
+    for l in range(shape.n_layers):
+        pool[l].normal_(0.0, 1.0)
+    kv = ld.KV(model, n_blocks, B + chunk, B, nblk_seq, pool=pool)
+    stream = torch.cuda.current_stream()
+    pend = gen.randint(seed, 2, 0, shape.vocab - 1, B).tolist()
+    seqs = []
+    for b in range(B):
+        s = ld.ld_kv_alloc(kv.h, 0)
+        ld.ld_kv_assume(kv.h, s, lens[b], pending=pend[b])
+        seqs.append(s)
+    for _ in range(2):
+        ld.ld_decode_step(kv.h, seqs, stream, noop_cb)
+    torch.cuda.synchronize()
+    ms, kv_bytes = [], []
+    t_begin = time.perf_counter()
+    for step in range(steps):
+        k = step % B
+        ld.ld_kv_free(kv.h, seqs[k])
+        seqs[k] = ld.ld_kv_alloc(kv.h, 0)
+        new_tokens = gen.randint(seed, 5000 + step, 0, shape.vocab - 1, chunk).numpy().astype(np.int32)
+        dec = [s for i, s in enumerate(seqs) if i != k]
+        sum_ctx = sum(ld.ld_kv_len(kv.h, s) + 1 for s in dec)
+        t0 = time.perf_counter()
+        ld.ld_step_mixed(kv.h, dec, [seqs[k]], [new_tokens], stream, noop_cb)
+        ms.append((time.perf_counter() - t0) * 1e3)
+        kv_bytes.append(sum_ctx * shape.kv_bytes_per_token)
+    torch.cuda.synchronize()
+    total = time.perf_counter() - t_begin
+    ld.ld_kv_profile(kv.h, True)
+    k = steps % B
+    ld.ld_kv_free(kv.h, seqs[k]); seqs[k] = ld.ld_kv_alloc(kv.h, 0)
+    ld.ld_step_mixed(kv.h, [s for i, s in enumerate(seqs) if i != k], [seqs[k]],
+                     [gen.randint(seed, 9999, 0, shape.vocab - 1, chunk).numpy().astype(np.int32)], stream, noop_cb)
+    prof = ld.ld_kv_profile_read(kv.h)
+    ld.ld_kv_profile(kv.h, False)
+    gemm_flops = (B - 1 + chunk) * 2 * (shape.weight_bytes_per_step / 2)
+    gemm_ms = sum(prof[c][0] for c in ("qkv", "wo", "gate_up", "down", "lm_head"))
+    out = {
+        "workload": "13B-shaped bf16 decoder, batch 64, KV pool of %d blocks (%.1f GB), contexts %d..%d after scaling "
+                    "by %.3f, 64 steps of 63 decode rows + one 2048-token prefill chunk" %
+                    (n_blocks, n_blocks * 16 * shape.kv_bytes_per_token / 1e9, min(lens), max(lens), scale),
+        "ms_per_step": round(statistics.mean(ms), 2), "tokens_per_s": round((B - 1 + chunk) * steps / total, 1),
+        "decode_tokens_per_s": round((B - 1) * steps / total, 1),
+        "kv_GB_per_step": round(statistics.mean(kv_bytes) / 1e9, 1),
+        "kernel_ms_one_step": {c: round(v[0], 3) for c, v in prof.items()},
+        "attention_GBps_if_all_attention_time_were_decode": round(statistics.mean(kv_bytes) / (prof["attention"][0] * 1e-3) / 1e9, 1),
+        "gemm_TFLOPs_nominal": round(gemm_flops / (gemm_ms * 1e-3) / 1e12, 1),
+        "n_layers": shape.n_layers,
+    }
+    kv.close()
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -294,8 +370,11 @@ def main():
     from workloads import LLAMA7B, SEED_BASE, make_weights
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     ld.lib()
-    shape = LLAMA7B if not args.layers else LLAMA7B.with_layers(args.layers)
     torch.cuda.set_device(0)
+    if args.only_13b:
+        print(json.dumps(run_13b(args, ld, torch)))
+        return
+    shape = LLAMA7B if not args.layers else LLAMA7B.with_layers(args.layers)
     if args.kernel_probe:
         d, f = shape.d_model, shape.d_ffn
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)

@@ -292,24 +292,27 @@ __global__ __launch_bounds__(256, 2) void k_gemm_skinny(const bf16_t *__restrict
     }
 }
 
-// More than 64 rows (prefill chunks, mixed steps): MFMA-bound.  128 tokens x BN weight rows per workgroup,
-// four waves as 2 (tokens) x 2 (columns), both operands through LDS.  K advances in chunks of 32; the
-// global loads of a chunk are issued FOUR chunks (~4000 MFMA cycles per wave) before their data is
-// written to LDS, in a ring of register sets, which covers L2 latency at one wave per SIMD; LDS is double
-// buffered, one barrier per chunk.  LDS holds 16-byte pieces segment-major ([k-segment][row], segment
-// stride padded by 64 bytes): the operand reads of 16 consecutive lanes are 256 contiguous bytes and the
-// staging writes of a 16-lane group (4 rows x 4 segments) cover all 64 banks once.
-template <int BN, int EPI>
-__global__ __launch_bounds__(256) void k_gemm_big(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
-                                                  const bf16_t *__restrict__ xlo, int T, int N, int K,
-                                                  float *__restrict__ y, int n_ttiles, int ks,
-                                                  float *__restrict__ partial) {
+// More than 64 rows (prefill chunks, mixed steps): MFMA-bound.  64*WM tokens x BN weight rows per
+// workgroup, 2*WM waves as WM (tokens) x 2 (columns), both operands through LDS.  What limits this kernel is
+// the operand traffic from L2 per flop (the split doubles the X side), so the tile is as large as the
+// accumulators allow: 256 x 256 with eight waves from 512 rows on, 128 x 256 (or x 128) below.  K advances
+// in chunks of 32; the global loads of a chunk are issued D chunks before their data is written to LDS, in
+// a ring of register sets; LDS is double buffered, one barrier per chunk.  LDS holds 16-byte pieces
+// segment-major ([k-segment][row], segment stride padded by 64 bytes): the operand reads of 16 consecutive
+// lanes are 256 contiguous bytes and the staging writes of a 16-lane group (4 rows x 4 segments) cover all
+// 64 banks once.
+template <int WM, int BN, int D, int EPI>
+__global__ __launch_bounds__(128 * WM) void k_gemm_big(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
+                                                       const bf16_t *__restrict__ xlo, int T, int N, int K,
+                                                       float *__restrict__ y, int n_ttiles, int ks,
+                                                       float *__restrict__ partial) {
     constexpr bool SWI = (EPI == ld::GEMM_SWIGLU);
-    constexpr int BM = 128, BK = 32, SEGS = BK / 8, D = 4;
+    constexpr int NT = 128 * WM;                  // threads
+    constexpr int BM = 64 * WM, BK = 32, SEGS = BK / 8;
     constexpr int WCT = BN / 2 / 32;              // 32-column accumulator tiles per wave
     constexpr int NOUT = SWI ? BN / 2 : BN;       // output columns per workgroup
     constexpr int XSEG = BM * 16 + 64, WSEG = BN * 16 + 64;   // bytes per k-segment of a stage
-    constexpr int NVX = 4, NVW = BN / 64;         // 16-byte pieces per thread per chunk
+    constexpr int NVX = 2 * BM * SEGS / NT, NVW = BN * SEGS / NT;   // 16-byte pieces per thread per chunk
     __shared__ __attribute__((aligned(16))) char xs[2][2][SEGS][XSEG];
     __shared__ __attribute__((aligned(16))) char ws[2][SEGS][WSEG];
 
@@ -327,13 +330,13 @@ __global__ __launch_bounds__(256) void k_gemm_big(const bf16_t *__restrict__ W, 
     int xdst[NVX], wdst[NVW];
 #pragma unroll
     for (int v = 0; v < NVX; v++) {
-        const int p = threadIdx.x + 256 * v, part = p >> 9, r = (p & 511) >> 2, seg = p & 3;
+        const int p = threadIdx.x + NT * v, part = p / (BM * SEGS), r = (p % (BM * SEGS)) >> 2, seg = p & 3;
         xsrc[v] = (part ? xlo : xhi) + (int64_t)min(t0 + r, T - 1) * K + seg * 8;
         xdst[v] = (part * SEGS + seg) * XSEG + r * 16;
     }
 #pragma unroll
     for (int v = 0; v < NVW; v++) {
-        const int p = threadIdx.x + 256 * v, wr = p >> 2, seg = p & 3;
+        const int p = threadIdx.x + NT * v, wr = p >> 2, seg = p & 3;
         int grow;
         if (SWI) {   // local rows of a wave column: gate tiles, then the up tiles of the same columns
             const int wcol = wr / (BN / 2), within = wr % (BN / 2);
@@ -401,10 +404,11 @@ __global__ __launch_bounds__(256) void k_gemm_big(const bf16_t *__restrict__ W, 
         for (int d = 0; d < D; d++) {
             const int cc = c + d;
             if (cc < c_end) {
-                stage(ring[d], d & 1);
+                const int st = (D % 2 == 0) ? (d & 1) : ((cc - c_begin) & 1);   // LDS stage alternates per chunk
+                stage(ring[d], st);
                 lds_barrier();
                 if (cc + D < c_end) issue(ring[d], cc + D);
-                compute(d & 1);
+                compute(st);
             }
         }
     }
@@ -462,27 +466,40 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__
 // 128-wide K chunks; more -> k_gemm_big.
 struct Shape { int tt, wc, kch; };
 
-// Workgroup count and split-K factor of the big-tile kernel for a row count.
-struct BigPlan { int bn, n_ttiles, n_nblocks, ks; };
-BigPlan plan_big(int T, int N, int K, int epi) {
-    const bool swi = epi == ld::GEMM_SWIGLU;
-    BigPlan p;
-    p.n_ttiles = (T + 127) / 128;
-    // 256 weight rows per workgroup when that still gives every CU a workgroup, else 128
-    const int nout256 = swi ? 128 : 256;
-    p.bn = (p.n_ttiles * ((N + nout256 - 1) / nout256) >= 256) ? 256 : 128;
-    const int nout = swi ? p.bn / 2 : p.bn;
-    p.n_nblocks = (N + nout - 1) / nout;
-    const int wgs = p.n_ttiles * p.n_nblocks;
-    int ks = (256 + wgs - 1) / wgs;                // fill the CUs once
-    ks = std::min(ks, K / 32 / 8);                 // at least eight chunks per slab
-    ks = std::min(ks, std::max(1, K / (8 * T)));   // partial sums: at most a quarter of the matrix bytes
-    p.ks = std::max(ks, 1);
-    return p;
-}
 int env_int(const char *name, int dflt) {
     const char *v = getenv(name);
     return v ? atoi(v) : dflt;
+}
+// Tile, workgroup count and split-K factor of the big-tile kernel for a row count: the candidate with the
+// smallest estimated time.  A candidate runs ceil(workgroups / 256) rounds of one workgroup per CU (two for
+// the 128 x 128 tile, at half the rate each); the per-CU rates are the measured full-grid rates of the three
+// tiles; split-K adds the write and the ordered re-read of its partial sums.
+struct BigPlan { int wm, bn, n_ttiles, n_nblocks, ks; };
+BigPlan plan_big(int T, int N, int K, int epi) {
+    const bool swi = epi == ld::GEMM_SWIGLU;
+    struct Tile { int wm, bn; double tflops; };           // nominal (unsplit) TFLOP/s of a full grid
+    static const Tile tiles[3] = {{4, 256, 480.0}, {2, 256, 380.0}, {2, 128, 300.0}};
+    BigPlan best{};
+    double best_t = 1e30;
+    const char *forced = getenv("LD_GEMM_BIG");            // tuning knob: "wm,bn,ks"
+    int f_wm = 0, f_bn = 0, f_ks = 0;
+    if (forced && sscanf(forced, "%d,%d,%d", &f_wm, &f_bn, &f_ks) != 3) f_wm = 0;
+    for (const Tile &tl : tiles) {
+        if (f_wm && (tl.wm != f_wm || tl.bn != f_bn)) continue;
+        const int bm = 64 * tl.wm, nout = swi ? tl.bn / 2 : tl.bn;
+        const int n_tt = (T + bm - 1) / bm, n_nb = (N + nout - 1) / nout;
+        const int max_ks = std::max(1, std::min(8, K / 32 / 8));   // at least eight chunks per slab
+        for (int ks = 1; ks <= max_ks; ks++) {
+            if (f_wm && ks != std::min(f_ks, max_ks)) continue;
+            const int64_t wgs = (int64_t)n_tt * n_nb * ks;
+            const int64_t rounds = (wgs + 255) / 256;
+            const double wg_us = 2.0 * bm * tl.bn * (double)(K / ks) / (tl.tflops * 1e6 / 256.0);
+            double t = rounds * wg_us;
+            if (ks > 1) t += 3.0 + (double)T * N * (swi ? 2 : 1) * 4.0 * (2.0 * ks + 1.0) / 3.0e6;
+            if (t < best_t) { best_t = t; best = {tl.wm, tl.bn, n_tt, n_nb, ks}; }
+        }
+    }
+    return best;
 }
 Shape pick_shape(int T, int epi) {
     (void)T; (void)epi;
@@ -570,19 +587,24 @@ void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int
         const int grid = ((p.n_nblocks + 7) / 8) * 8 * p.n_ttiles * p.ks;
         const bf16_t *hi = xs, *lo = xs + (size_t)T * K;
         const int rgrid = (int)(((int64_t)T * N + 255) / 256);
-#define LD_BIG(BN_, EPI_)                                                                                              \
+#define LD_BIG(WM_, BN_, D_, EPI_)                                                                                     \
     do {                                                                                                               \
-        LD_LAUNCH((k_gemm_big<BN_, EPI_>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, p.n_ttiles, p.ks, partial); \
+        LD_LAUNCH((k_gemm_big<WM_, BN_, D_, EPI_>), dim3(grid), dim3(128 * WM_), 0, s, W, hi, lo, T, N, K, y,           \
+                  p.n_ttiles, p.ks, partial);                                                                          \
         if (p.ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, p.ks, y);       \
     } while (0)
-        if (p.bn == 256) {
-            if (epi == GEMM_STORE) LD_BIG(256, GEMM_STORE);
-            else if (epi == GEMM_ADD) LD_BIG(256, GEMM_ADD);
-            else LD_BIG(256, GEMM_SWIGLU);
+        if (p.wm == 4) {
+            if (epi == GEMM_STORE) LD_BIG(4, 256, 3, GEMM_STORE);
+            else if (epi == GEMM_ADD) LD_BIG(4, 256, 3, GEMM_ADD);
+            else LD_BIG(4, 256, 3, GEMM_SWIGLU);
+        } else if (p.bn == 256) {
+            if (epi == GEMM_STORE) LD_BIG(2, 256, 4, GEMM_STORE);
+            else if (epi == GEMM_ADD) LD_BIG(2, 256, 4, GEMM_ADD);
+            else LD_BIG(2, 256, 4, GEMM_SWIGLU);
         } else {
-            if (epi == GEMM_STORE) LD_BIG(128, GEMM_STORE);
-            else if (epi == GEMM_ADD) LD_BIG(128, GEMM_ADD);
-            else LD_BIG(128, GEMM_SWIGLU);
+            if (epi == GEMM_STORE) LD_BIG(2, 128, 4, GEMM_STORE);
+            else if (epi == GEMM_ADD) LD_BIG(2, 128, 4, GEMM_ADD);
+            else LD_BIG(2, 128, 4, GEMM_SWIGLU);
         }
 #undef LD_BIG
         return;

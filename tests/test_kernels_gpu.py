@@ -264,9 +264,34 @@ def test_linear_matrix_core_path(T, epi):
     assert err <= 2e-5, err
 
 
+@pytest.mark.parametrize("plan", ["2,128,1", "2,128,3", "2,256,1", "2,256,2", "4,256,1", "4,256,4"])
+@pytest.mark.parametrize("epi", ["store", "add", "swiglu"])
+def test_linear_big_tile_every_plan(plan, epi, monkeypatch):
+    """The big-tile kernel picks its tile and split-K factor from a cost estimate; here every tile
+    (128 x 128, 128 x 256, 256 x 256 with eight waves) is forced in turn, with and without split-K, on a
+    shape that is ragged in tokens and in output columns, against the oracle on every output."""
+    monkeypatch.setenv("LD_GEMM_BIG", plan)
+    T, N, K = 333, 301, 1152
+    rows = 2 * N if epi == "swiglu" else N
+    W = _mat(11, 1, rows, K, "bf16"); x = gen.normal(11, 2, (T, K)); y0 = gen.normal(11, 4, (T, N))
+    Wh = oracle.to_host_matrix(W)
+    code = {"store": ld.LDK_STORE, "add": ld.LDK_ADD, "swiglu": ld.LDK_SWIGLU}[epi]
+    scratch = torch.empty(ld.ldk_linear_scratch_bytes(T, N, K, code), dtype=torch.uint8, device=DEV)
+    y = y0.to(DEV).clone()
+    ld.ldk_linear(W.to(DEV), x.to(DEV), y, code, scratch=scratch)
+    ref = np.stack([oracle.matvec(Wh, x[t].numpy()) for t in range(T)])
+    if epi == "add":
+        ref = y0.numpy() + ref
+    elif epi == "swiglu":
+        ref = ref[:, :N] / (1 + np.exp(-ref[:, :N])) * ref[:, N:]
+    err = np.max(np.abs(y.cpu().numpy() - ref)) / np.abs(ref).max()
+    assert err <= 2e-5, err
+
+
 def test_linear_matrix_core_7b_shapes_sampled():
-    """Launch shapes of the batch-32 decode step and of a 256-row prefill chunk, sampled outputs."""
-    for T in (32, 256):
+    """Launch shapes of the batch-32 decode step, of a 256-row prefill chunk and of a mixed step
+    (32 decode rows + four 256-row chunks), sampled outputs."""
+    for T in (32, 256, 1056):
         for N, K, epi in [(12288, 4096, ld.LDK_STORE), (4096, 11008, ld.LDK_ADD), (11008, 4096, ld.LDK_SWIGLU)]:
             rows = N * (2 if epi == ld.LDK_SWIGLU else 1)
             W = gen.normal(3, N, (rows, K), std=0.02, device=DEV).bfloat16()

@@ -21,7 +21,7 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + \
                [("rms_eps", C.c_double), ("rope_base", C.c_double),
-                ("wdtype", C.c_int32), ("kv_round", C.c_int32), ("kv_block", C.c_int32)]
+                ("wdtype", C.c_int32), ("kv_round", C.c_int32), ("kv_block", C.c_int32), ("window", C.c_int32)]
 
 
 class Weights(C.Structure):
@@ -47,7 +47,7 @@ def lib():
         L.orc_attention_contig.argtypes = [dp, dp, dp, C.c_int64, C.c_int32, dp]
         L.orc_paged_attention.argtypes = [dp, vp, vp, C.c_int32, C.c_int64, C.c_int64, C.c_int64,
                                           ip, C.c_int32, ip, C.c_int32, C.c_int32, C.c_int32,
-                                          C.c_int32, C.c_int32, dp]
+                                          C.c_int32, C.c_int32, C.c_int32, dp]
         L.orc_model_create.restype = vp; L.orc_model_create.argtypes = [C.POINTER(Config), C.POINTER(Weights)]
         L.orc_model_destroy.argtypes = [vp]
         L.orc_forward_contig.restype = C.c_int32; L.orc_forward_contig.argtypes = [vp, ip, C.c_int64, dp]
@@ -139,15 +139,16 @@ def attention_contig(q, K, V):
     return out
 
 
-def paged_attention(q, kpool, vpool, strides, block_table, ctx_len, n_kv_heads, kv_block=16):
-    """q [B,H,hd]; pools float32 or uint16 (bf16 bits); strides = (block, head, slot) in elements."""
+def paged_attention(q, kpool, vpool, strides, block_table, ctx_len, n_kv_heads, kv_block=16, window=0):
+    """q [B,H,hd]; pools float32 or uint16 (bf16 bits); strides = (block, head, slot) in elements;
+    window > 0: the query (at position ctx_len - 1) sees the last `window` positions only."""
     q = _f64(q); B, H, hd = q.shape
     kp, dt = _wptr(kpool); vp, dt2 = _wptr(vpool)
     assert dt == dt2
     bt = np.ascontiguousarray(block_table, dtype=np.int32); cl = np.ascontiguousarray(ctx_len, dtype=np.int32)
     out = np.empty_like(q)
     lib().orc_paged_attention(_dp(q), kp, vp, dt, strides[0], strides[1], strides[2], _ip(bt), bt.shape[1],
-                              _ip(cl), B, H, n_kv_heads, hd, kv_block, _dp(out))
+                              _ip(cl), B, H, n_kv_heads, hd, kv_block, window, _dp(out))
     return out
 
 
@@ -176,7 +177,7 @@ class Model:
             kv_round = 1 if shape.dtype == "bf16" else 2
         self.cfg = Config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
                           shape.d_ffn, shape.vocab, shape.rms_eps, shape.rope_base, wdtype, kv_round,
-                          shape.kv_block)
+                          shape.kv_block, shape.window)
         arr = lambda name: (C.c_void_p * max(L, 1))(*[a.ctypes.data for a in k[name]])
         self._arrs = {n: arr(n) for n in ("attn_norm", "wqkv", "wo", "ffn_norm", "wgate_up", "wdown")}
         self.w = Weights(k["embed"].ctypes.data, k["lm_head"].ctypes.data, k["final_norm"].ctypes.data,

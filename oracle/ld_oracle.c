@@ -12,7 +12,10 @@
  * section 4.1: temperature 0, i.e. greedy).  The paper does not describe the
  * decoder block; the block used here (RMSNorm, rotary position embedding in the
  * half-split pairing, SwiGLU, no biases, untied LM head) is the one fixed by the
- * workload definitions.
+ * workload definitions.  Section 4.1 names a model family whose attention is
+ * grouped (several query heads per key/value head) and banded: with window W > 0 a
+ * token at position p attends to positions max(0, p - W + 1) .. p only; W = 0 means
+ * every preceding position.  The cache still keeps every position.
  *
  * Arithmetic: every floating-point step is done in double precision, one token at
  * a time, two-pass softmax, plain loops.  Weights are read as fp32 or as bf16 bit
@@ -44,6 +47,7 @@ typedef struct {
     int32_t wdtype;   /* 0: matrices are float32, 1: matrices are bf16 bit patterns (uint16) */
     int32_t kv_round; /* 0: cache keeps doubles, 1: round k,v to bf16 on append, 2: round to fp32 */
     int32_t kv_block; /* tokens per cache block */
+    int32_t window;   /* > 0: attend to the last `window` positions (own position included); 0: all */
 } orc_config;
 
 typedef struct {
@@ -207,17 +211,21 @@ void orc_attention_contig(const double *q, const double *K, const double *V, int
 void orc_paged_attention(const double *q, const void *kpool, const void *vpool, int32_t elem,
                          int64_t stride_block, int64_t stride_head, int64_t stride_slot,
                          const int32_t *block_table, int32_t table_stride, const int32_t *ctx_len,
-                         int32_t B, int32_t H, int32_t Hkv, int32_t hd, int32_t kv_block, double *out)
+                         int32_t B, int32_t H, int32_t Hkv, int32_t hd, int32_t kv_block, int32_t window,
+                         double *out)
 {
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
     for (int b = 0; b < B; b++) {
         for (int h = 0; h < H; h++) {
-            int64_t n = ctx_len[b];
+            /* the query is the token at position ctx_len - 1; it sees positions first .. ctx_len - 1 */
+            int64_t last = ctx_len[b], first = (window > 0 && last > window) ? last - window : 0;
+            int64_t n = last - first;
             int kvh = h / (H / Hkv);
             double *K = malloc(sizeof(double) * n * hd), *V = malloc(sizeof(double) * n * hd);
             for (int64_t j = 0; j < n; j++) {
-                int64_t blk = block_table[(int64_t)b * table_stride + j / kv_block];
-                int64_t off = blk * stride_block + kvh * stride_head + (j % kv_block) * stride_slot;
+                int64_t pos = first + j;
+                int64_t blk = block_table[(int64_t)b * table_stride + pos / kv_block];
+                int64_t off = blk * stride_block + kvh * stride_head + (pos % kv_block) * stride_slot;
                 for (int i = 0; i < hd; i++) {
                     K[j * hd + i] = welem(kpool, elem, off + i);
                     V[j * hd + i] = welem(vpool, elem, off + i);
@@ -235,7 +243,7 @@ void orc_paged_attention(const double *q, const void *kpool, const void *vpool, 
 orc_model *orc_model_create(const orc_config *c, const orc_weights *w)
 {
     if (!c || !w) return NULL;
-    if (c->n_heads % c->n_kv_heads || c->head_dim % 2 || c->kv_block <= 0) return NULL;
+    if (c->n_heads % c->n_kv_heads || c->head_dim % 2 || c->kv_block <= 0 || c->window < 0) return NULL;
     orc_model *m = calloc(1, sizeof(*m));
     m->c = *c;
     m->w = *w;
@@ -280,8 +288,8 @@ static double *kv_row(const orc_config *c, const kv_view *v, int layer, int whic
 }
 
 /* Forward pass of one token at absolute position pos.  Appends its keys and values to
- * the cache, attends over positions 0..pos, and (if logits != NULL) writes the vocab
- * logits of this position. */
+ * the cache, attends over positions 0..pos (the last `window` of them if the model is
+ * banded), and (if logits != NULL) writes the vocab logits of this position. */
 static void forward_token(const orc_model *m, const kv_view *kv, int32_t token, int64_t pos, double *logits)
 {
     const orc_config *c = &m->c;
@@ -290,7 +298,8 @@ static void forward_token(const orc_model *m, const kv_view *kv, int32_t token, 
     double *x = malloc(sizeof(double) * d), *h = malloc(sizeof(double) * d);
     double *qkv = malloc(sizeof(double) * nqkv), *att = malloc(sizeof(double) * nq);
     double *tmp = malloc(sizeof(double) * d), *gu = malloc(sizeof(double) * 2 * F), *a = malloc(sizeof(double) * F);
-    int64_t n = pos + 1;
+    int64_t first = (c->window > 0 && pos + 1 > c->window) ? pos + 1 - c->window : 0;
+    int64_t n = pos + 1 - first;   /* visible positions: first .. pos */
 
     for (int i = 0; i < d; i++) x[i] = welem(m->w.embed, c->wdtype, (int64_t)token * d + i);
 
@@ -313,8 +322,8 @@ static void forward_token(const orc_model *m, const kv_view *kv, int32_t token, 
             const double **kr = malloc(sizeof(*kr) * n), **vr = malloc(sizeof(*vr) * n);
             double *sc = malloc(sizeof(double) * n);
             for (int64_t j = 0; j < n; j++) {
-                kr[j] = kv_row(c, kv, l, 0, kvh, j);
-                vr[j] = kv_row(c, kv, l, 1, kvh, j);
+                kr[j] = kv_row(c, kv, l, 0, kvh, first + j);
+                vr[j] = kv_row(c, kv, l, 1, kvh, first + j);
             }
             attend_rows(q + hh * hd, kr, vr, n, hd, sc, att + hh * hd);
             free(kr); free(vr); free(sc);

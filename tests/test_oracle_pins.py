@@ -280,8 +280,14 @@ def _torch_forward_all(shape, w, tokens):
         q, k, v = qkv.split([H * hd, Hk * hd, Hk * hd], dim=-1)
         q, k, v = rope(q.view(T, H, hd)), rope(k.view(T, Hk, hd)), v.view(T, Hk, hd)
         k = k.repeat_interleave(H // Hk, dim=1); v = v.repeat_interleave(H // Hk, dim=1)
-        o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
-                                           v.transpose(0, 1)[None], is_causal=True)[0]
+        if shape.window > 0:                         # band: key j visible to query i iff i - window < j <= i
+            i = torch.arange(T)
+            mask = (i[None, :] <= i[:, None]) & (i[None, :] > i[:, None] - shape.window)
+            o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
+                                               v.transpose(0, 1)[None], attn_mask=mask)[0]
+        else:
+            o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
+                                               v.transpose(0, 1)[None], is_causal=True)[0]
         x = x + o.transpose(0, 1).reshape(T, H * hd) @ W(w["wo"][l]).T
         h = F.rms_norm(x, (d,), W(w["ffn_norm"][l]), eps=shape.rms_eps)
         gu = h @ W(w["wgate_up"][l]).T
@@ -314,11 +320,71 @@ def test_decoder_gqa_and_bf16_weights_match_library_rederivation():
     assert np.max(np.abs(got - ref)) / np.abs(ref).max() < 1e-11
 
 
-def test_paged_equals_contiguous_and_rounds_follow_the_concatenation(tiny_weights):
+@pytest.mark.parametrize("window", [1, 7, 16, 33])
+def test_banded_decoder_matches_library_rederivation_with_band_mask(window):
+    """Attention band: the float64 whole-sequence re-derivation with an explicit boolean band mask."""
+    from dataclasses import replace
+    shape = replace(TINY, n_kv_heads=2, window=window, name="tiny-band")
+    w = make_weights(shape, 6)
+    tok = _prompt(40, shape.vocab, 102)
+    got = oracle.Model(shape, w, kv_round=0).forward_contig(tok)
+    ref = _torch_forward_all(shape, w, tok.tolist())
+    assert np.max(np.abs(got - ref)) / np.abs(ref).max() < 1e-11
+
+
+def test_band_at_least_as_long_as_the_sequence_changes_nothing_and_shorter_does(tiny_weights):
+    from dataclasses import replace
+    shape, w = tiny_weights
+    tok = _prompt(24, shape.vocab, 103)
+    full = oracle.Model(shape, w, kv_round=0).forward_contig(tok)
+    same = oracle.Model(replace(shape, window=24), w, kv_round=0).forward_contig(tok)
+    np.testing.assert_array_equal(same, full)
+    short = oracle.Model(replace(shape, window=23), w, kv_round=0).forward_contig(tok)
+    np.testing.assert_array_equal(short[:23], full[:23])     # the band first bites at position 23
+    assert np.abs(short[23] - full[23]).max() > 1e-9
+
+
+def test_band_of_one_makes_attention_return_the_own_value(tiny_weights):
+    """window = 1: softmax over the own position only, so the attention output is the token's own
+    value vector and every token's logits are those of a one-token sequence rotated to its position:
+    with rotary embedding acting on q and k only, they do not depend on the position at all."""
+    from dataclasses import replace
+    shape, w = tiny_weights
+    tok = _prompt(6, shape.vocab, 104)
+    got = oracle.Model(replace(shape, window=1), w, kv_round=0).forward_contig(tok)
+    m = oracle.Model(shape, w, kv_round=0)
+    for i, t in enumerate(tok):
+        np.testing.assert_allclose(got[i], m.forward_contig(np.array([t], np.int32))[0], rtol=1e-12, atol=1e-13)
+
+
+def test_paged_attention_band_equals_attention_over_the_last_positions():
+    B, H, Hkv, hd = 3, 4, 2, 64
+    lens = [5, 17, 48]
+    table, kf, vf = _paged_case(B, H, Hkv, hd, lens, False)
+    q = RNG.standard_normal((B, H, hd))
+    kp, vp = oracle.to_host_matrix(kf), oracle.to_host_matrix(vf)
+    kd, vd = kf.double().numpy(), vf.double().numpy()
+    for window in (1, 9, 16, 40, 48, 100):
+        out = oracle.paged_attention(q, kp, vp, (Hkv * 16 * hd, 16 * hd, hd), table, lens, Hkv, window=window)
+        for b in range(B):
+            vis = range(max(0, lens[b] - window), lens[b])
+            for h in range(H):
+                g = h // (H // Hkv)
+                K = np.stack([kd[table[b, j // 16], g, j % 16] for j in vis])
+                V = np.stack([vd[table[b, j // 16], g, j % 16] for j in vis])
+                ref = torch.softmax(torch.from_numpy(K @ q[b, h]) / math.sqrt(hd), 0).numpy() @ V
+                np.testing.assert_allclose(out[b, h], ref, rtol=1e-11, atol=1e-14)
+
+
+@pytest.mark.parametrize("window", [0, 19])
+def test_paged_equals_contiguous_and_rounds_follow_the_concatenation(tiny_weights, window):
     """Paged cache == contiguous cache bitwise, and a multi-round run (prefill, decode, append an
     observation, continue) produces at every call the logits of the concatenated sequence
-    prompt ++ generated ++ observation (section 2.2 step (g)), the pending token being fed first."""
+    prompt ++ generated ++ observation (section 2.2 step (g)), the pending token being fed first.
+    Also with an attention band shorter than the sequence (the band spans block boundaries)."""
+    from dataclasses import replace
     shape, w = tiny_weights
+    shape = replace(shape, window=window)
     tok = _prompt(37, shape.vocab)
     m = oracle.Model(shape, w)                 # cache rounded to fp32 for the fp32 shape
     kv = oracle.KV(m, 16, 3, 8)

@@ -6,5 +6,5 @@ recipes.  None of the transformer arithmetic lives here.
 """
 from .gen import uniform_bits, uniform01, normal, randint, permutation  # noqa: F401
 from .configs import (  # noqa: F401
-    DecoderShape, TINY, LLAMA7B, LLAMA13B, make_weights, SEED_BASE,
+    DecoderShape, TINY, LLAMA7B, LLAMA13B, MISTRAL7B, make_weights, SEED_BASE,
 )

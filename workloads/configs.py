@@ -29,6 +29,7 @@ class DecoderShape:
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
     kv_block: int = 16
+    window: int = 0       # > 0: banded attention over the last `window` positions; 0: all preceding positions
 
     def with_layers(self, n: int) -> "DecoderShape":
         return replace(self, n_layers=n, name=f"{self.name}-{n}L")
@@ -50,6 +51,8 @@ class DecoderShape:
 TINY = DecoderShape("tiny", 2, 256, 4, 4, 64, 688, 1024, "f32")
 LLAMA7B = DecoderShape("7b", 32, 4096, 32, 32, 128, 11008, 32000, "bf16")
 LLAMA13B = DecoderShape("13b", 40, 5120, 40, 40, 128, 13824, 32000, "bf16")
+# grouped key/value heads (4 query heads per KV head) and a 4096-position attention band
+MISTRAL7B = DecoderShape("7b-gqa", 32, 4096, 32, 8, 128, 14336, 32000, "bf16", window=4096)
 
 
 def _matrix(seed, stream, rows, cols, shape: DecoderShape, device):

@@ -56,6 +56,9 @@ typedef struct {
     int32_t dtype;     /* LD_F32 | LD_BF16: element type of matrices AND of the KV pool */
     int32_t kv_block;  /* tokens per KV block; must be 16 */
     int32_t max_chunk; /* ld_prefill splits longer inputs into chunks of this many rows */
+    int32_t window;    /* attention band: > 0, a token at position p attends to positions
+                          max(0, p - window + 1) .. p (the model family of section 4.1); 0: to all of 0 .. p.
+                          The cache keeps every position either way. */
 } ld_model_config;
 
 /* DEVICE pointers.  Per-layer members are HOST arrays of n_layers DEVICE pointers

@@ -71,29 +71,36 @@ ld_status ldk_qkv_rope(const void *W, int32_t dtype, const float *x, const float
                        int32_t table_stride, void *pool_layer, int32_t T, int32_t K, int32_t H, int32_t Hkv, int32_t hd,
                        void *scratch, size_t scratch_bytes, void *stream);
 
-/* Scratch bytes ldk_paged_attention needs for T rows with contexts up to max_ctx. */
-size_t ldk_attention_scratch_bytes(int32_t T, int32_t H, int32_t hd, int32_t max_ctx);
+/* Scratch bytes ldk_paged_attention needs for T rows with contexts up to max_ctx (same H, Hkv, window
+ * as the call). */
+size_t ldk_attention_scratch_bytes(int32_t T, int32_t H, int32_t Hkv, int32_t hd, int32_t max_ctx, int32_t window);
 
 /* Paged attention of T single-token queries (section 2.1): row t, head h attends to cached
  * positions 0 .. ctx_len[t]-1 of the sequence whose block-table row is seq_slot[t]:
  *   s_j = q.k_j / sqrt(hd),  p = softmax(s),  out = sum_j p_j v_j.
  * q row t, head h starts at q + t * q_stride + h * hd; out is dense [T, H, hd].
+ * Query head h reads KV head h / (H / Hkv); the H / Hkv query heads of a KV head are served by one
+ * workgroup (keys and values loaded once) when that ratio is 2, 4 or 8.
+ * window > 0: banded attention, the row (at position ctx_len[t]-1) sees only positions
+ * max(0, ctx_len[t] - window) .. ctx_len[t]-1; window == 0: every cached position.
  * ctx_len[t] >= 1.  max_ctx >= max_t ctx_len[t] sizes the launch (HOST value). */
 ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
                               const int32_t *table, int32_t table_stride, const int32_t *seq_slot,
                               const int32_t *ctx_len, int32_t max_ctx, int32_t T, int32_t H, int32_t Hkv,
-                              int32_t hd, float *out, void *scratch, size_t scratch_bytes, void *stream);
+                              int32_t hd, int32_t window, float *out, void *scratch, size_t scratch_bytes,
+                              void *stream);
 
-/* Attention for prefill segments (section 2.1: "the user prompt can be processed in parallel in a
- * single iteration"): a segment is a run of rows of one sequence at consecutive positions whose keys
- * and values are already in the pool; row r at position p attends to cached positions 0 .. p.
+/* Attention for prefill segments (section 2.1: all tokens of a prompt go through the model in one
+ * iteration): a segment is a run of rows of one sequence at consecutive positions whose keys
+ * and values are already in the pool; row r at position p attends to cached positions 0 .. p
+ * (window > 0: positions max(0, p - window + 1) .. p).
  * tiles: DEVICE int32[n_tiles][4] = (first row, number of rows (1..128), position of the first row,
  * block-table row of the sequence); a segment longer than 128 rows is given as several tiles.
  * q and out as in ldk_paged_attention.  Supported: dtype LD_BF16 with hd = 128 (LD_E_INVAL otherwise;
  * such shapes run their prefill rows through ldk_paged_attention with ctx_len = position + 1). */
 ld_status ldk_prefill_attention(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
                                 const int32_t *table, int32_t table_stride, const int32_t *tiles, int32_t n_tiles,
-                                int32_t H, int32_t Hkv, int32_t hd, float *out, void *stream);
+                                int32_t H, int32_t Hkv, int32_t hd, int32_t window, float *out, void *stream);
 
 /* out[r] = smallest index of the maximum of logits[r, 0..V). */
 ld_status ldk_argmax(const float *logits, int32_t R, int32_t V, int32_t *out, void *stream);

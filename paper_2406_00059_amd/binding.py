@@ -35,7 +35,7 @@ class ld_model_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + \
                [("rms_eps", C.c_float), ("rope_base", C.c_float),
-                ("dtype", C.c_int32), ("kv_block", C.c_int32), ("max_chunk", C.c_int32)]
+                ("dtype", C.c_int32), ("kv_block", C.c_int32), ("max_chunk", C.c_int32), ("window", C.c_int32)]
 
 
 class ld_weights(C.Structure):
@@ -88,11 +88,12 @@ _SIGS = {
                                     C.c_int32, C.c_int32, _vp]),
     "ldk_qkv_rope": (C.c_int, [_vp, C.c_int32, _vp, _vp, C.c_float, _vp, _vp, _vp, _vp, _vp, C.c_int32, _vp,
                                C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, C.c_size_t, _vp]),
-    "ldk_attention_scratch_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
+    "ldk_attention_scratch_bytes": (C.c_size_t, [C.c_int32] * 6),
     "ldk_paged_attention": (C.c_int, [_vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, _vp, _vp, C.c_int32,
-                                      C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, C.c_size_t, _vp]),
+                                      C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, C.c_size_t,
+                                      _vp]),
     "ldk_prefill_attention": (C.c_int, [_vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, C.c_int32,
-                                        C.c_int32, C.c_int32, _vp, _vp]),
+                                        C.c_int32, C.c_int32, C.c_int32, _vp, _vp]),
     "ldk_argmax": (C.c_int, [_vp, C.c_int32, C.c_int32, _vp, _vp]),
 }
 EXPORTS = tuple(_SIGS)
@@ -314,21 +315,21 @@ def ldk_qkv_rope(W, x, qkv, cos_sin, pos, seq_slot, table, pool_layer, H, Hkv, h
                               _ptr(scratch), _nbytes(scratch), _stream(stream)))
 
 
-def ldk_attention_scratch_bytes(T, H, hd, max_ctx):
-    return lib().ldk_attention_scratch_bytes(T, H, hd, max_ctx)
+def ldk_attention_scratch_bytes(T, H, Hkv, hd, max_ctx, window=0):
+    return lib().ldk_attention_scratch_bytes(T, H, Hkv, hd, max_ctx, window)
 
 
 def ldk_paged_attention(q, q_stride, pool_layer, table, seq_slot, ctx_len, max_ctx, H, Hkv, hd, out, scratch,
-                        stream=None):
+                        window=0, stream=None):
     _check(lib().ldk_paged_attention(_ptr(q), q_stride, _ptr(pool_layer), _dt(pool_layer.dtype), _ptr(table),
                                      table.shape[1], _ptr(seq_slot), _ptr(ctx_len), max_ctx, out.shape[0], H, Hkv,
-                                     hd, _ptr(out), _ptr(scratch), scratch.numel() * scratch.element_size(),
+                                     hd, window, _ptr(out), _ptr(scratch), scratch.numel() * scratch.element_size(),
                                      _stream(stream)))
 
 
-def ldk_prefill_attention(q, q_stride, pool_layer, table, tiles, H, Hkv, hd, out, stream=None):
+def ldk_prefill_attention(q, q_stride, pool_layer, table, tiles, H, Hkv, hd, out, window=0, stream=None):
     _check(lib().ldk_prefill_attention(_ptr(q), q_stride, _ptr(pool_layer), _dt(pool_layer.dtype), _ptr(table),
-                                       table.shape[1], _ptr(tiles), tiles.shape[0], H, Hkv, hd, _ptr(out),
+                                       table.shape[1], _ptr(tiles), tiles.shape[0], H, Hkv, hd, window, _ptr(out),
                                        _stream(stream)))
 
 
@@ -347,7 +348,8 @@ class Model:
         L = shape.n_layers
         self.cfg = ld_model_config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
                                    shape.d_ffn, shape.vocab, shape.rms_eps, shape.rope_base,
-                                   LD_BF16 if shape.dtype == "bf16" else LD_F32, shape.kv_block, max_chunk)
+                                   LD_BF16 if shape.dtype == "bf16" else LD_F32, shape.kv_block, max_chunk,
+                                   getattr(shape, "window", 0))
         self._tabs = {k: (C.c_void_p * max(L, 1))(*[t.data_ptr() for t in weights[k]])
                       for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "wgate_up", "wdown")}
         self.w = ld_weights(weights["embed"].data_ptr(), weights["lm_head"].data_ptr(),

@@ -2,7 +2,10 @@
 //
 // A prefill segment is a run of consecutive rows of one sequence at consecutive positions; row r
 // (position p_r) attends to every cached position j <= p_r: the earlier context plus, causally, the
-// rows of its own chunk, whose keys/values were appended to the pool just before.
+// rows of its own chunk, whose keys/values were appended to the pool just before.  With an attention
+// band of W positions it attends to max(0, p_r - W + 1) <= j <= p_r only: the walk over the KV positions
+// starts at the first position the tile's first row sees, and a wave skips the steps that lie wholly
+// before the band of its own first row.
 //
 // Work split: a workgroup (4 waves) takes 128 consecutive rows of a segment and one head; wave w
 // owns rows [32w, 32w+32).  All four waves walk the same KV positions in steps of 32 tokens.
@@ -37,8 +40,8 @@ constexpr int VLD = KVB + 4;   // LDS row stride of the transposed V tile (eleme
 __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ q, int q_stride,
                                                       const bf16_t *__restrict__ pool, int Hkv,
                                                       const int32_t *__restrict__ table, int table_stride,
-                                                      const int4 *__restrict__ tiles, int H, float scale_log2e,
-                                                      float *__restrict__ out) {
+                                                      const int4 *__restrict__ tiles, int H, int window,
+                                                      float scale_log2e, float *__restrict__ out) {
     __shared__ __attribute__((aligned(16))) bf16_t vt[HD][VLD];
     const int4 tile = tiles[blockIdx.x];      // x: first row, y: rows (<= 128), z: position of first row, w: seq slot
     const int h = blockIdx.y;
@@ -55,6 +58,10 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
     const int wg_last_pos = tile.z + tile.y - 1;                       // last position any wave needs
     const int wave_last_pos = tile.z + min(wave * 32 + 31, tile.y - 1);
     const bool wave_active = wave * 32 < tile.y;
+    // band: lowest position visible to this lane's query, to the wave's first query, to the tile's first query
+    const int q_low = window > 0 ? max(q_pos - window + 1, 0) : 0;
+    const int wave_low = window > 0 ? max(tile.z + wave * 32 - window + 1, 0) : 0;
+    const int kv_start = window > 0 ? (max(tile.z - window + 1, 0) & ~(KVB - 1)) : 0;
 
     // Q operand: for k-step j the lane supplies dims half*64 + j*8 .. +8 of its query (hi and lo parts)
     bf16x8 qh[8], ql[8];
@@ -100,10 +107,10 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
         }
     };
     u32x4 kf[8], kn[8], vr[2];
-    load_k(kf, 0);
-    load_v(vr, 0);
+    load_k(kf, kv_start);
+    load_v(vr, kv_start);
 
-    for (int kv0 = 0; kv0 <= wg_last_pos; kv0 += KVB) {
+    for (int kv0 = kv_start; kv0 <= wg_last_pos; kv0 += KVB) {
         // ---- stage V^T of positions kv0 .. kv0+31 (clamped to the last needed position) into LDS
         lds_barrier();
 #pragma unroll
@@ -119,7 +126,7 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
         lds_barrier();
         const bool more = kv0 + KVB <= wg_last_pos;
         if (more) { load_k(kn, kv0 + KVB); load_v(vr, kv0 + KVB); }
-        if (!wave_active || kv0 > wave_last_pos) {   // nothing visible to this wave's queries
+        if (!wave_active || kv0 > wave_last_pos || kv0 + KVB <= wave_low) {   // nothing visible to this wave's queries
             if (more) {
 #pragma unroll
                 for (int j = 0; j < 8; j++) kf[j] = kn[j];
@@ -142,7 +149,7 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
 #pragma unroll
         for (int i = 0; i < 16; i++) {
             const int kv_pos = kv0 + 8 * (i / 4) + 4 * half + (i % 4);
-            const bool ok = q_valid && kv_pos <= q_pos;
+            const bool ok = q_valid && kv_pos <= q_pos && kv_pos >= q_low;
             st[i] = ok ? st[i] : -INFINITY;
             mb = fmaxf(mb, st[i]);
         }
@@ -211,10 +218,11 @@ namespace ld {
 bool prefill_attention_supported(int dtype_is_bf16, int hd) { return dtype_is_bf16 && hd == HD; }
 
 void launch_prefill_attention(const float *q, int q_stride, const uint16_t *pool, int Hkv, const int32_t *table,
-                              int table_stride, const int32_t *tiles, int n_tiles, int H, float *out, hipStream_t s) {
+                              int table_stride, const int32_t *tiles, int n_tiles, int H, int window, float *out,
+                              hipStream_t s) {
     const float sl2 = 1.4426950408889634f / sqrtf((float)HD);
     LD_LAUNCH(k_attn_prefill, dim3(n_tiles, H), dim3(256), 0, s, q, q_stride, pool, Hkv, table, table_stride,
-                       (const int4 *)tiles, H, sl2, out);
+                       (const int4 *)tiles, H, window, sl2, out);
 }
 
 }  // namespace ld

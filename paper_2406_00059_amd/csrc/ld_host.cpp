@@ -85,7 +85,8 @@ Workspace plan_workspace(const ld_model &m, char *base, int max_tokens, int max_
     w.att_scratch_bytes = 0;   // the chunking depends on the row count: size for the worst one
     for (int t = 1; t <= max_tokens; t++)
         w.att_scratch_bytes = std::max(w.att_scratch_bytes,
-                                       ldk_attention_scratch_bytes(t, c.n_heads, c.head_dim, max_blocks * c.kv_block));
+                                       ldk_attention_scratch_bytes(t, c.n_heads, c.n_kv_heads, c.head_dim,
+                                                                   max_blocks * c.kv_block, c.window));
     w.att_scratch = take(w.att_scratch_bytes);
     w.lin_scratch_bytes = 0;   // the split-K factor depends on the row count: size for the worst one
     for (int t = 2; t <= max_tokens; t++) {
@@ -281,8 +282,8 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const 
             a.pool = (uint16_t *)pool_l;
             LD_TIMED(LD_PROF_QKV, timed_void([&] { ld::launch_batch_qkv(a, st); }));
             LD_TIMED(LD_PROF_ATTENTION, ld::paged_attention_split(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot,
-                                                                  d_ctx, max_ctx_dec, T, H, Hkv, hd, w.b_xs, w.att_scratch,
-                                                                  w.att_scratch_bytes, st));
+                                                                  d_ctx, max_ctx_dec, T, H, Hkv, hd, c.window, w.b_xs,
+                                                                  w.att_scratch, w.att_scratch_bytes, st));
             LD_TIMED(LD_PROF_WO, timed_void([&] { ld::launch_batch_wo(a, st); }));
             LD_TIMED(LD_PROF_GATE_UP, timed_void([&] { ld::launch_batch_gate_up(a, st); }));
             LD_TIMED(LD_PROF_DOWN, timed_void([&] { ld::launch_batch_down(a, st); }));
@@ -295,11 +296,11 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const 
                                            d_slot, w.table, kv->max_blocks, pool_l, T, d, H, Hkv, hd, w.lin_scratch, w.lin_scratch_bytes, st));
         if (n_dec_rows)
             LD_TIMED(LD_PROF_ATTENTION, ldk_paged_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot, d_ctx,
-                                                            max_ctx_dec, n_dec_rows, H, Hkv, hd, w.attn, w.att_scratch,
-                                                            w.att_scratch_bytes, st));
+                                                            max_ctx_dec, n_dec_rows, H, Hkv, hd, c.window, w.attn,
+                                                            w.att_scratch, w.att_scratch_bytes, st));
         if (n_tiles)
             LD_TIMED(LD_PROF_ATTENTION, ldk_prefill_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_tiles,
-                                                              n_tiles, H, Hkv, hd, w.attn, st));
+                                                              n_tiles, H, Hkv, hd, c.window, w.attn, st));
         LD_TIMED(LD_PROF_WO, ldk_linear(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st));
         LD_TIMED(LD_PROF_GATE_UP, ldk_linear(m.wgate_up[l], c.dtype, w.x, m.ffn_norm[l], c.rms_eps, T, c.d_ffn, d, LDK_SWIGLU, w.act, w.lin_scratch,
                                                w.lin_scratch_bytes, st));
@@ -425,6 +426,7 @@ ld_status ld_model_create(const ld_model_config *cfg, const ld_weights *w, ld_mo
     if (c.d_model % 8 || c.d_ffn % 8) return fail(LD_E_INVAL, "ld_model_create: d_model and d_ffn must be multiples of 8");
     if (c.dtype != LD_F32 && c.dtype != LD_BF16) return fail(LD_E_INVAL, "ld_model_create: bad dtype");
     if (!(c.rms_eps > 0.f) || !(c.rope_base > 1.f)) return fail(LD_E_INVAL, "ld_model_create: bad rms_eps / rope_base");
+    if (c.window < 0) return fail(LD_E_INVAL, "ld_model_create: negative attention window");
     if (!w->embed || !w->lm_head || !w->final_norm) return fail(LD_E_INVAL, "ld_model_create: null weight pointer");
     if (c.n_layers > 0 && (!w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm || !w->wgate_up || !w->wdown))
         return fail(LD_E_INVAL, "ld_model_create: null per-layer table");

@@ -177,48 +177,62 @@ __global__ void k_rope_kv_write(float *__restrict__ qkv, const float2 *__restric
 
 // ---------------------------------------------------------------- paged decode attention
 //
-// Work item = (row t, head h, chunk c): chunk c covers CB consecutive KV blocks (CB*16 tokens) of
-// the row's context.  A workgroup of 4 waves takes one work item, wave w the blocks w, w+4, ...
-// of the chunk.  Inside a wave, HD/8 adjacent lanes cover one token's head vector with 16-byte
-// loads (8 elements each), so one load instruction brings 64/(HD/8) whole tokens and consecutive
-// lanes read consecutive memory.  Scores are reduced across those lanes with xor shuffles; each
-// lane group keeps its own online-softmax state (m, l, acc) in the log2 domain, merged across
-// groups, waves and finally chunks.
+// Work item = (row t, head group, chunk c).  A head group is the G query heads that share one KV head
+// (G = 1 for ungrouped attention): the keys and values of a block are loaded once and used for all G
+// queries.  Chunk c covers CB consecutive KV blocks (CB*16 tokens) of the VISIBLE part of the row's
+// context: with an attention band of W positions the row (at position ctx-1) sees positions
+// max(0, ctx - W) .. ctx-1 and the walk starts at the block that holds the first of them.  A workgroup
+// of 4 waves takes one work item, wave w the blocks w, w+4, ... of the chunk.  Inside a wave, HD/8
+// adjacent lanes cover one token's head vector with 16-byte loads (8 elements each), so one load
+// instruction brings 64/(HD/8) whole tokens and consecutive lanes read consecutive memory.  Scores are
+// reduced across those lanes with xor shuffles; each lane group keeps its own online-softmax state
+// (m, l, acc) per query in the log2 domain, merged across groups, waves and finally chunks.
 
 // KV blocks per chunk: a multiple of 4 (one per wave), chosen per launch by attn_chunk_blocks().
 
-template <int HD, typename KVT>
+// first visible position and first visible block of a row
+__device__ __forceinline__ int band_first(int ctx, int window) { return (window > 0 && ctx > window) ? ctx - window : 0; }
+
+template <int HD, typename KVT, int G>
 __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ q, int q_stride,
                                                       const KVT *__restrict__ pool, int Hkv,
                                                       const int32_t *__restrict__ table, int table_stride,
                                                       const int32_t *__restrict__ seq_slot,
-                                                      const int32_t *__restrict__ ctx_len, int H,
+                                                      const int32_t *__restrict__ ctx_len, int H, int window,
                                                       float scale_log2e, int max_chunks, int cb,
                                                       float *__restrict__ part_o, float *__restrict__ part_ml) {
     constexpr int LPT = HD / 8;      // lanes per token
     constexpr int TPI = WAVE / LPT;  // tokens per load instruction
     constexpr int NI = 16 / TPI;     // load instructions per 16-token block
-    const int c = blockIdx.x, h = blockIdx.y, t = blockIdx.z;
+    const int c = blockIdx.x, t = blockIdx.z;
+    // G > 1: blockIdx.y is the KV head and the queries are heads kvh*G .. kvh*G+G-1; G == 1: blockIdx.y is the head
+    const int h0 = blockIdx.y * G;
+    const int kvh = (G > 1) ? blockIdx.y : blockIdx.y / (H / Hkv);
     const int ctx = ctx_len[t];
+    const int first = band_first(ctx, window);
     const int nblk = (ctx + 15) >> 4;
-    const int b_begin = c * cb;
+    const int b_begin = (first >> 4) + c * cb;
     if (b_begin >= nblk) return;
     const int b_end = min(b_begin + cb, nblk);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int group = lane / LPT, sub = lane % LPT;
-    const int kvh = h / (H / Hkv);
     const int64_t block_stride = (int64_t)2 * Hkv * 16 * HD;
     const int32_t *trow = table + (int64_t)seq_slot[t] * table_stride;
 
-    float qv[8];
-    {
-        const float *qp = q + (int64_t)t * q_stride + h * HD + sub * 8;
+    float qv[G][8];
 #pragma unroll
-        for (int e = 0; e < 8; e++) qv[e] = qp[e] * scale_log2e;
+    for (int g = 0; g < G; g++) {
+        const float *qp = q + (int64_t)t * q_stride + (h0 + g) * HD + sub * 8;
+#pragma unroll
+        for (int e = 0; e < 8; e++) qv[g][e] = qp[e] * scale_log2e;
     }
-    float m = -INFINITY, l = 0.f, acc[8];
+    float m[G], l[G], acc[G][8];
 #pragma unroll
-    for (int e = 0; e < 8; e++) acc[e] = 0.f;
+    for (int g = 0; g < G; g++) {
+        m[g] = -INFINITY; l[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc[g][e] = 0.f;
+    }
 
     for (int b = b_begin + wave; b < b_end; b += 4) {
         const int64_t phys = trow[b];
@@ -229,80 +243,96 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
         for (int i = 0; i < NI; i++) load8_stream(kb + i * TPI * HD, kf[i]);
 #pragma unroll
         for (int i = 0; i < NI; i++) load8_stream(vb + i * TPI * HD, vf[i]);
-        const int ntok = ctx - b * 16;  // valid tokens in this block (may exceed 16)
-        float s[NI];
-        float mb = -INFINITY;
+        bool valid[NI];
 #pragma unroll
         for (int i = 0; i < NI; i++) {
-            float d = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; e++) d = fmaf(qv[e], kf[i][e], d);
-#pragma unroll
-            for (int off = 1; off < LPT; off <<= 1) d += __shfl_xor(d, off, WAVE);
-            const bool valid = (i * TPI + group) < ntok;
-            s[i] = valid ? d : -INFINITY;
-            if (!valid) {
+            const int pos = b * 16 + i * TPI + group;   // position of this lane group's token
+            valid[i] = pos >= first && pos < ctx;
+            if (!valid[i]) {
 #pragma unroll
                 for (int e = 0; e < 8; e++) vf[i][e] = 0.f;
             }
-            mb = fmaxf(mb, s[i]);
         }
-        const float m_new = fmaxf(m, mb);
-        if (m_new > -INFINITY) {
-            const float sc = fast_exp2(m - m_new);
-            l *= sc;
 #pragma unroll
-            for (int e = 0; e < 8; e++) acc[e] *= sc;
+        for (int g = 0; g < G; g++) {
+            float s[NI];
+            float mb = -INFINITY;
 #pragma unroll
             for (int i = 0; i < NI; i++) {
-                const float p = fast_exp2(s[i] - m_new);
-                l += p;
+                float d = 0.f;
 #pragma unroll
-                for (int e = 0; e < 8; e++) acc[e] = fmaf(p, vf[i][e], acc[e]);
+                for (int e = 0; e < 8; e++) d = fmaf(qv[g][e], kf[i][e], d);
+#pragma unroll
+                for (int off = 1; off < LPT; off <<= 1) d += __shfl_xor(d, off, WAVE);
+                s[i] = valid[i] ? d : -INFINITY;
+                mb = fmaxf(mb, s[i]);
             }
-            m = m_new;
+            const float m_new = fmaxf(m[g], mb);
+            if (m_new > -INFINITY) {
+                const float sc = fast_exp2(m[g] - m_new);
+                l[g] *= sc;
+#pragma unroll
+                for (int e = 0; e < 8; e++) acc[g][e] *= sc;
+#pragma unroll
+                for (int i = 0; i < NI; i++) {
+                    const float p = fast_exp2(s[i] - m_new);
+                    l[g] += p;
+#pragma unroll
+                    for (int e = 0; e < 8; e++) acc[g][e] = fmaf(p, vf[i][e], acc[g][e]);
+                }
+                m[g] = m_new;
+            }
         }
     }
     // merge the lane groups of this wave
 #pragma unroll
-    for (int off = LPT; off < WAVE; off <<= 1) {
-        const float m_o = __shfl_xor(m, off, WAVE), l_o = __shfl_xor(l, off, WAVE);
-        const float m_n = fmaxf(m, m_o);
-        const float a = (m_n > -INFINITY) ? fast_exp2(m - m_n) : 0.f;
-        const float bsc = (m_n > -INFINITY) ? fast_exp2(m_o - m_n) : 0.f;
-        l = l * a + l_o * bsc;
+    for (int g = 0; g < G; g++) {
 #pragma unroll
-        for (int e = 0; e < 8; e++) acc[e] = acc[e] * a + __shfl_xor(acc[e], off, WAVE) * bsc;
-        m = m_n;
+        for (int off = LPT; off < WAVE; off <<= 1) {
+            const float m_o = __shfl_xor(m[g], off, WAVE), l_o = __shfl_xor(l[g], off, WAVE);
+            const float m_n = fmaxf(m[g], m_o);
+            const float a = (m_n > -INFINITY) ? fast_exp2(m[g] - m_n) : 0.f;
+            const float bsc = (m_n > -INFINITY) ? fast_exp2(m_o - m_n) : 0.f;
+            l[g] = l[g] * a + l_o * bsc;
+#pragma unroll
+            for (int e = 0; e < 8; e++) acc[g][e] = acc[g][e] * a + __shfl_xor(acc[g][e], off, WAVE) * bsc;
+            m[g] = m_n;
+        }
     }
-    __shared__ float sm_m[4], sm_l[4], sm_acc[4][HD];
+    __shared__ float sm_m[4][G], sm_l[4][G], sm_acc[4][G][HD];
     if (lane < LPT) {
 #pragma unroll
-        for (int e = 0; e < 8; e++) sm_acc[wave][sub * 8 + e] = acc[e];
-        if (lane == 0) { sm_m[wave] = m; sm_l[wave] = l; }
+        for (int g = 0; g < G; g++) {
+#pragma unroll
+            for (int e = 0; e < 8; e++) sm_acc[wave][g][sub * 8 + e] = acc[g][e];
+            if (lane == 0) { sm_m[wave][g] = m[g]; sm_l[wave][g] = l[g]; }
+        }
     }
     __syncthreads();
-    if (threadIdx.x < HD) {
-        const float M = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));  // finite: wave 0 saw a valid token
+    for (int idx = threadIdx.x; idx < G * HD; idx += 256) {
+        const int g = idx / HD, d = idx % HD;
+        // a wave that saw no visible token keeps m = -inf and weight 0; at least one wave saw one
+        const float M = fmaxf(fmaxf(sm_m[0][g], sm_m[1][g]), fmaxf(sm_m[2][g], sm_m[3][g]));
         float o = 0.f, L = 0.f;
 #pragma unroll
         for (int w = 0; w < 4; w++) {
-            const float a = fast_exp2(sm_m[w] - M);
-            o += a * sm_acc[w][threadIdx.x];
-            L += a * sm_l[w];
+            const float a = fast_exp2(sm_m[w][g] - M);
+            o += a * sm_acc[w][g][d];
+            L += a * sm_l[w][g];
         }
-        const int64_t item = ((int64_t)t * H + h) * max_chunks + c;
-        part_o[item * HD + threadIdx.x] = o;
-        if (threadIdx.x == 0) { part_ml[item * 2] = M; part_ml[item * 2 + 1] = L; }
+        const int64_t item = ((int64_t)t * H + h0 + g) * max_chunks + c;
+        part_o[item * HD + d] = o;
+        if (d == 0) { part_ml[item * 2] = M; part_ml[item * 2 + 1] = L; }
     }
 }
 
 template <int HD>
 __global__ void k_attn_merge(const float *__restrict__ part_o, const float *__restrict__ part_ml,
-                             const int32_t *__restrict__ ctx_len, int H, int max_chunks, int cb,
+                             const int32_t *__restrict__ ctx_len, int H, int window, int max_chunks, int cb,
                              float *__restrict__ out, bf16_t *__restrict__ xs_out, int T) {
     const int h = blockIdx.x, t = blockIdx.y, d = threadIdx.x;
-    const int nch = ((ctx_len[t] + 15) / 16 + cb - 1) / cb;
+    const int ctx = ctx_len[t];
+    const int nch = ((ctx + 15) / 16 - (band_first(ctx, window) >> 4) + cb - 1) / cb;
     const int64_t base = ((int64_t)t * H + h) * max_chunks;
     float M = -INFINITY;
     for (int c = 0; c < nch; c++) M = fmaxf(M, part_ml[(base + c) * 2]);
@@ -492,47 +522,64 @@ ld_status ldk_qkv_rope(const void *W, int32_t dtype, const float *x, const float
     return ldk_rope_kv_write(qkv, cos_sin, pos, seq_slot, table, table_stride, pool_layer, dtype, T, H, Hkv, hd, stream);
 }
 
-// Chunk size in KV blocks: small chunks when few (row, head) pairs exist, so that the launch still has
-// a few thousand workgroups; at most 64 blocks (1024 tokens) per chunk.
-static int attn_chunk_blocks(int T, int H, int max_ctx) {
-    const int64_t blocks = (int64_t)T * H * ((max_ctx + 15) / 16);
+// Most KV blocks a row can see: all of its context, or with a band of W positions the blocks that W
+// consecutive positions can touch.
+static int visible_blocks(int max_ctx, int window) {
+    const int all = (max_ctx + 15) / 16;
+    return window > 0 ? std::min(all, (window + 14) / 16 + 1) : all;
+}
+// Query heads that one workgroup serves: the whole group of a KV head when the group size is 2, 4 or 8.
+static int head_group(int H, int Hkv) {
+    const int r = H / Hkv;
+    return (r == 2 || r == 4 || r == 8) ? r : 1;
+}
+// Chunk size in KV blocks: small chunks when few (row, head group) pairs exist, so that the launch still
+// has a few thousand workgroups; at most 64 blocks (1024 tokens) per chunk.
+static int attn_chunk_blocks(int T, int H, int Hkv, int max_ctx, int window) {
+    const int64_t blocks = (int64_t)T * (H / head_group(H, Hkv)) * visible_blocks(max_ctx, window);
     int64_t cb = (blocks + 4095) / 4096;
     cb = (cb + 3) / 4 * 4;
     return (int)std::min<int64_t>(std::max<int64_t>(cb, 4), 64);
 }
-static int attn_max_chunks(int T, int H, int max_ctx) {
-    const int cb = attn_chunk_blocks(T, H, max_ctx);
-    return ((max_ctx + 15) / 16 + cb - 1) / cb;
+static int attn_max_chunks(int T, int H, int Hkv, int max_ctx, int window) {
+    const int cb = attn_chunk_blocks(T, H, Hkv, max_ctx, window);
+    return (visible_blocks(max_ctx, window) + cb - 1) / cb;
 }
 
-size_t ldk_attention_scratch_bytes(int32_t T, int32_t H, int32_t hd, int32_t max_ctx) {
-    if (T <= 0 || H <= 0 || hd <= 0 || max_ctx <= 0) return 0;
-    return (size_t)T * H * attn_max_chunks(T, H, max_ctx) * (hd + 2) * sizeof(float);
+size_t ldk_attention_scratch_bytes(int32_t T, int32_t H, int32_t Hkv, int32_t hd, int32_t max_ctx, int32_t window) {
+    if (T <= 0 || H <= 0 || Hkv <= 0 || H % Hkv || hd <= 0 || max_ctx <= 0 || window < 0) return 0;
+    return (size_t)T * H * attn_max_chunks(T, H, Hkv, max_ctx, window) * (hd + 2) * sizeof(float);
 }
 
 static ld_status paged_attention_impl(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
                                       const int32_t *table, int32_t table_stride, const int32_t *seq_slot,
                                       const int32_t *ctx_len, int32_t max_ctx, int32_t T, int32_t H, int32_t Hkv,
-                                      int32_t hd, float *out, uint16_t *xs_out, void *scratch, size_t scratch_bytes,
-                                      void *stream) {
+                                      int32_t hd, int32_t window, float *out, uint16_t *xs_out, void *scratch,
+                                      size_t scratch_bytes, void *stream) {
     if (T == 0) return LD_OK;
     if (!q || !pool_layer || !table || !seq_slot || !ctx_len || (!out && !xs_out) || !scratch || T < 0 || H <= 0 ||
-        Hkv <= 0 || H % Hkv || (hd != 64 && hd != 128) || max_ctx <= 0)
+        Hkv <= 0 || H % Hkv || (hd != 64 && hd != 128) || max_ctx <= 0 || window < 0)
         return ld::fail(LD_E_INVAL, "ldk_paged_attention: bad argument");
-    if (scratch_bytes < ldk_attention_scratch_bytes(T, H, hd, max_ctx))
+    if (scratch_bytes < ldk_attention_scratch_bytes(T, H, Hkv, hd, max_ctx, window))
         return ld::fail(LD_E_INVAL, "ldk_paged_attention: scratch too small");
-    const int mc = attn_max_chunks(T, H, max_ctx), cb = attn_chunk_blocks(T, H, max_ctx);
+    const int mc = attn_max_chunks(T, H, Hkv, max_ctx, window), cb = attn_chunk_blocks(T, H, Hkv, max_ctx, window);
+    const int G = head_group(H, Hkv);
     float *part_o = (float *)scratch;
     float *part_ml = part_o + (size_t)T * H * mc * hd;
     const float sl2 = (float)(1.4426950408889634 / std::sqrt((double)hd));
-    dim3 grid(mc, H, T), block(256);
+    dim3 grid(mc, H / G, T), block(256);
     hipStream_t s = (hipStream_t)stream;
-#define LD_ATT(HD_, KVT_)                                                                                         \
-    do {                                                                                                          \
-        LD_LAUNCH((k_attn_partial<HD_, KVT_>), grid, block, 0, s, q, q_stride, (const KVT_ *)pool_layer, \
-                           Hkv, table, table_stride, seq_slot, ctx_len, H, sl2, mc, cb, part_o, part_ml);         \
-        LD_LAUNCH((k_attn_merge<HD_>), dim3(H, T), dim3(HD_), 0, s, part_o, part_ml, ctx_len, H, mc, cb, \
-                           out, xs_out, T);                                                                       \
+#define LD_ATT_G(HD_, KVT_, G_)                                                                                    \
+    LD_LAUNCH((k_attn_partial<HD_, KVT_, G_>), grid, block, 0, s, q, q_stride, (const KVT_ *)pool_layer, Hkv,     \
+              table, table_stride, seq_slot, ctx_len, H, window, sl2, mc, cb, part_o, part_ml)
+#define LD_ATT(HD_, KVT_)                                                                                          \
+    do {                                                                                                           \
+        if (G == 8) LD_ATT_G(HD_, KVT_, 8);                                                                       \
+        else if (G == 4) LD_ATT_G(HD_, KVT_, 4);                                                                  \
+        else if (G == 2) LD_ATT_G(HD_, KVT_, 2);                                                                  \
+        else LD_ATT_G(HD_, KVT_, 1);                                                                              \
+        LD_LAUNCH((k_attn_merge<HD_>), dim3(H, T), dim3(HD_), 0, s, part_o, part_ml, ctx_len, H, window, mc, cb,  \
+                  out, xs_out, T);                                                                                 \
     } while (0)
     if (dtype == LD_BF16 && hd == 128) LD_ATT(128, bf16_t);
     else if (dtype == LD_BF16 && hd == 64) LD_ATT(64, bf16_t);
@@ -540,27 +587,29 @@ static ld_status paged_attention_impl(const float *q, int32_t q_stride, const vo
     else if (dtype == LD_F32 && hd == 64) LD_ATT(64, float);
     else return ld::fail(LD_E_INVAL, "ldk_paged_attention: bad dtype");
 #undef LD_ATT
+#undef LD_ATT_G
     return launched("k_attn");
 }
 
 ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
                               const int32_t *table, int32_t table_stride, const int32_t *seq_slot,
                               const int32_t *ctx_len, int32_t max_ctx, int32_t T, int32_t H, int32_t Hkv, int32_t hd,
-                              float *out, void *scratch, size_t scratch_bytes, void *stream) {
+                              int32_t window, float *out, void *scratch, size_t scratch_bytes, void *stream) {
     return paged_attention_impl(q, q_stride, pool_layer, dtype, table, table_stride, seq_slot, ctx_len, max_ctx, T, H, Hkv,
-                                hd, out, nullptr, scratch, scratch_bytes, stream);
+                                hd, window, out, nullptr, scratch, scratch_bytes, stream);
 }
 
 ld_status ldk_prefill_attention(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
                                 const int32_t *table, int32_t table_stride, const int32_t *tiles, int32_t n_tiles,
-                                int32_t H, int32_t Hkv, int32_t hd, float *out, void *stream) {
-    if (!q || !pool_layer || !table || !tiles || !out || n_tiles < 0 || H <= 0 || Hkv <= 0 || H % Hkv || q_stride % 4)
+                                int32_t H, int32_t Hkv, int32_t hd, int32_t window, float *out, void *stream) {
+    if (!q || !pool_layer || !table || !tiles || !out || n_tiles < 0 || H <= 0 || Hkv <= 0 || H % Hkv || q_stride % 4 ||
+        window < 0)
         return ld::fail(LD_E_INVAL, "ldk_prefill_attention: bad argument");
     if (!ld::prefill_attention_supported(dtype == LD_BF16, hd))
         return ld::fail(LD_E_INVAL, "ldk_prefill_attention: needs a bf16 pool and head_dim 128");
     if (n_tiles == 0) return LD_OK;
     ld::launch_prefill_attention(q, q_stride, (const uint16_t *)pool_layer, Hkv, table, table_stride, tiles, n_tiles, H,
-                                 out, (hipStream_t)stream);
+                                 window, out, (hipStream_t)stream);
     return launched("k_attn_prefill");
 }
 
@@ -579,10 +628,10 @@ namespace ld {
 // output projection: xs_out [2][T][H * hd].
 ld_status paged_attention_split(const float *q, int q_stride, const void *pool_layer, int dtype, const int32_t *table,
                                 int table_stride, const int32_t *seq_slot, const int32_t *ctx_len, int max_ctx, int T,
-                                int H, int Hkv, int hd, uint16_t *xs_out, void *scratch, size_t scratch_bytes,
-                                hipStream_t stream) {
+                                int H, int Hkv, int hd, int window, uint16_t *xs_out, void *scratch,
+                                size_t scratch_bytes, hipStream_t stream) {
     return paged_attention_impl(q, q_stride, pool_layer, dtype, table, table_stride, seq_slot, ctx_len, max_ctx, T, H, Hkv,
-                                hd, nullptr, xs_out, scratch, scratch_bytes, (void *)stream);
+                                hd, window, nullptr, xs_out, scratch, scratch_bytes, (void *)stream);
 }
 
 }  // namespace ld

@@ -36,7 +36,7 @@ def test_library_exports_every_declared_symbol():
 
 def _cfg(**over):
     base = dict(n_layers=2, d_model=256, n_heads=4, n_kv_heads=4, head_dim=64, d_ffn=688, vocab=1024,
-                rms_eps=1e-5, rope_base=10000.0, dtype=ld.LD_F32, kv_block=16, max_chunk=256)
+                rms_eps=1e-5, rope_base=10000.0, dtype=ld.LD_F32, kv_block=16, max_chunk=256, window=0)
     base.update(over)
     return ld.ld_model_config(**base)
 
@@ -60,7 +60,7 @@ def _kv(m, n_blocks=40, max_tokens=64, max_seqs=4, max_blocks=12):
 
 
 @pytest.mark.parametrize("bad", [dict(head_dim=48), dict(kv_block=32), dict(n_kv_heads=3), dict(d_model=250),
-                                 dict(dtype=7), dict(vocab=0), dict(rms_eps=0.0)])
+                                 dict(dtype=7), dict(vocab=0), dict(rms_eps=0.0), dict(window=-1)])
 def test_model_create_rejects_bad_shapes(bad):
     with pytest.raises(ld.LdError) as e:
         _model(**bad)

@@ -36,10 +36,13 @@ def test_tiny_fp32_prompt32_decode64():
     assert ld.ld_kv_len(P.gkv.h, s) == 95
 
 
-@pytest.mark.parametrize("shape,tol", [(TINY, 1e-4), (replace(TINY, dtype="bf16", n_kv_heads=2, name="tiny-bf16-gqa"), 2e-2)])
+@pytest.mark.parametrize("shape,tol", [(TINY, 1e-4), (replace(TINY, dtype="bf16", n_kv_heads=2, name="tiny-bf16-gqa"), 2e-2),
+                                       (replace(TINY, window=21, name="tiny-band"), 1e-4),
+                                       (replace(TINY, dtype="bf16", n_kv_heads=1, window=40, name="tiny-bf16-gqa-band"), 2e-2)])
 def test_tool_rounds_with_chunked_observation_prefill(shape, tol):
     """Three rounds of decode -> observation; the prompt and the observations go through chunked
-    prefill (chunk 8, ragged tails), on a permuted block table."""
+    prefill (chunk 8, ragged tails), on a permuted block table.  Also with grouped KV heads and with an
+    attention band shorter than the sequence (the sequence grows to 90 positions)."""
     P = Pair(shape, 11, n_blocks=24, max_tokens=8, max_seqs=2, max_blocks=16, max_chunk=8)
     s = P.alloc()
     for lb, pb in enumerate([9, 3, 14, 0, 5, 21, 7]):

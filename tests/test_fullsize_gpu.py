@@ -12,7 +12,7 @@ import torch
 
 import oracle
 import paper_2406_00059_amd as ld
-from workloads import TINY, LLAMA7B, LLAMA13B, SEED_BASE, gen, make_weights
+from workloads import TINY, LLAMA7B, LLAMA13B, MISTRAL7B, SEED_BASE, gen, make_weights
 from helpers import Pair, Tokens, prompt, rel_err
 
 pytestmark = pytest.mark.gpu
@@ -83,12 +83,14 @@ def test_7b_batch1_decode_at_context_1024_32_steps():
     assert P.tables_equal(s) and ld.ld_kv_len(P.gkv.h, s) == 1056
 
 
-def test_7b_width_batch32_continuous_batching_with_mixed_step():
+@pytest.mark.parametrize("base", [LLAMA7B, MISTRAL7B], ids=["mha", "gqa-band"])
+def test_7b_width_batch32_continuous_batching_with_mixed_step(base):
     """The batch-32 workload at 7B layer width and reduced depth (2 layers): contexts uniform in
     [512, 8192] (injected), pure decode steps and a mixed step in which 4 sequences get a 256-token
     observation chunk (257 rows with the pending token) prefilled in the same pass.  All 32 sequences'
-    tokens every step; logits within 2e-2."""
-    shape = LLAMA7B.with_layers(2)
+    tokens every step; logits within 2e-2.  Second case: 32 query heads on 8 KV heads and an attention
+    band of 4096 positions (about half of the contexts are longer than the band)."""
+    shape = base.with_layers(2)
     seed = SEED_BASE + 3
     B = 32
     lens = gen.randint(seed, 1, 512, 8192, B).tolist()

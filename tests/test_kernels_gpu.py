@@ -138,30 +138,34 @@ def _attention_case(seed, lens, H, Hkv, hd, dtype, spare=5):
     return table, pool, q
 
 
-def _run_attention(table, pool, q, lens, H, Hkv, hd):
+def _run_attention(table, pool, q, lens, H, Hkv, hd, window=0):
     B = len(lens)
     ctx = torch.tensor(lens, dtype=torch.int32, device=DEV)
     slot = torch.arange(B, dtype=torch.int32, device=DEV)
     out = torch.empty(B, H, hd, device=DEV)
-    scratch = torch.empty(ld.ldk_attention_scratch_bytes(B, H, hd, max(lens)), dtype=torch.uint8, device=DEV)
-    ld.ldk_paged_attention(q, H * hd, pool, table.to(DEV), slot, ctx, max(lens), H, Hkv, hd, out, scratch)
+    scratch = torch.empty(ld.ldk_attention_scratch_bytes(B, H, Hkv, hd, max(lens), window), dtype=torch.uint8,
+                          device=DEV)
+    ld.ldk_paged_attention(q, H * hd, pool, table.to(DEV), slot, ctx, max(lens), H, Hkv, hd, out, scratch,
+                           window=window)
     torch.cuda.synchronize()
     return out.cpu().numpy()
 
 
-def _oracle_attention(table, pool, q, lens, Hkv, hd, rows=None):
+def _oracle_attention(table, pool, q, lens, Hkv, hd, rows=None, window=0):
     ph = oracle.to_host_matrix(pool.reshape(pool.shape[0], -1))
     kp = ph.reshape(-1)
     vp = kp[Hkv * 16 * hd:]                      # V half of each block starts Hkv*16*hd elements later
     strides = (2 * Hkv * 16 * hd, 16 * hd, hd)
     qh = q.cpu().numpy()
     if rows is None:
-        return oracle.paged_attention(qh, kp, vp, strides, table.numpy(), lens, Hkv)
+        return oracle.paged_attention(qh, kp, vp, strides, table.numpy(), lens, Hkv, window=window)
     sel = np.array(rows)
-    return oracle.paged_attention(qh[sel], kp, vp, strides, table.numpy()[sel], [lens[r] for r in rows], Hkv)
+    return oracle.paged_attention(qh[sel], kp, vp, strides, table.numpy()[sel], [lens[r] for r in rows], Hkv,
+                                  window=window)
 
 
-@pytest.mark.parametrize("dtype,hd,H,Hkv", [("bf16", 128, 4, 4), ("f32", 64, 4, 4), ("bf16", 128, 8, 2), ("f32", 128, 2, 1)])
+@pytest.mark.parametrize("dtype,hd,H,Hkv", [("bf16", 128, 4, 4), ("f32", 64, 4, 4), ("bf16", 128, 8, 2), ("f32", 128, 2, 1),
+                                            ("bf16", 128, 16, 2), ("bf16", 64, 6, 2), ("bf16", 128, 32, 8)])
 def test_paged_attention_edge_lengths(dtype, hd, H, Hkv):
     lens = [1, 2, 15, 16, 17, 63, 255, 256, 257, 300, 1025]
     table, pool, q = _attention_case(21, lens, H, Hkv, hd, dtype)
@@ -172,6 +176,37 @@ def test_paged_attention_edge_lengths(dtype, hd, H, Hkv):
     v0 = pool[table[0, 0], 1, :, 0, :].float().cpu().numpy()
     for h in range(H):
         np.testing.assert_allclose(got[0, h], v0[h // (H // Hkv)], rtol=1e-6, atol=1e-7)
+
+
+@pytest.mark.parametrize("window", [1, 5, 16, 17, 100, 256, 4096])
+@pytest.mark.parametrize("dtype,hd,H,Hkv", [("bf16", 128, 8, 2), ("f32", 64, 4, 4)])
+def test_paged_attention_band(dtype, hd, H, Hkv, window):
+    """Attention band: the row sees its last `window` positions only; bands that start inside a block, at a
+    block boundary, that are longer than the context, and of a single position."""
+    lens = [1, 2, 15, 16, 17, 63, 255, 256, 257, 300, 1025]
+    table, pool, q = _attention_case(22, lens, H, Hkv, hd, dtype)
+    got = _run_attention(table, pool, q, lens, H, Hkv, hd, window=window)
+    ref = _oracle_attention(table, pool, q, lens, Hkv, hd, window=window)
+    assert np.max(np.abs(got - ref)) <= 2e-6 * np.abs(ref).max() + 1e-6
+    if window == 1:      # the own value
+        for b, n in enumerate(lens):
+            v = pool[table[b, (n - 1) // 16], 1, :, (n - 1) % 16, :].float().cpu().numpy()
+            for h in range(H):
+                np.testing.assert_allclose(got[b, h], v[h // (H // Hkv)], rtol=1e-6, atol=1e-7)
+
+
+def test_paged_attention_grouped_band_serving_shape_sampled():
+    """Batch 32, 32 query heads on 8 KV heads, contexts uniform in [512, 8192], band of 4096 positions:
+    sampled rows (the longest, the shortest, one just over the band) against the oracle."""
+    lens = gen.randint(20240602, 1, 512, 8192, 32).tolist()
+    lens[3] = 4097
+    table, pool, q = _attention_case(20240602, lens, 32, 8, 128, "bf16")
+    got = _run_attention(table, pool, q, lens, 32, 8, 128, window=4096)
+    assert np.isfinite(got).all()
+    rows = [3, 9, int(np.argmax(lens)), int(np.argmin(lens))]
+    ref = _oracle_attention(table, pool, q, lens, 8, 128, rows=rows, window=4096)
+    err = np.max(np.abs(got[rows] - ref)) / np.abs(ref).max()
+    assert err <= 2e-5, err
 
 
 def test_paged_attention_microbench_shape_sampled():
@@ -312,11 +347,14 @@ def test_linear_matrix_core_7b_shapes_sampled():
                     assert abs(yh[t, n] - a) <= 1e-4 * max(1.0, abs(a)), (T, N, t, n, yh[t, n], a)
 
 
+@pytest.mark.parametrize("window", [0, 1, 40, 128, 200, 5000])
 @pytest.mark.parametrize("H,Hkv", [(4, 4), (8, 2)])
-def test_prefill_attention_segments(H, Hkv):
+def test_prefill_attention_segments(H, Hkv, window):
     """Chunk-prefill attention (matrix cores): segments of different sequences, a fresh prompt (position 0),
     an observation appended to a long context, a segment longer than one 128-row tile; causal inside
-    the chunk; permuted block table.  Every row against the oracle's single-query attention."""
+    the chunk; permuted block table; with and without an attention band (shorter than a wave's 32 rows,
+    shorter and longer than a tile, longer than every context).  Every row against the oracle's
+    single-query attention."""
     hd = 128
     segs = [(37, 100), (0, 5), (1000, 300), (255, 1), (16, 32)]          # (first position, rows) per sequence
     lens = [p + n for p, n in segs]
@@ -330,11 +368,11 @@ def test_prefill_attention_segments(H, Hkv):
         row_seq += [s] * n; row_pos += list(range(p0, p0 + n)); r += n
     out = torch.zeros(T, H, hd, device=DEV)
     ld.ldk_prefill_attention(q, H * hd, pool, table.to(DEV), torch.tensor(tiles, dtype=torch.int32, device=DEV),
-                             H, Hkv, hd, out)
+                             H, Hkv, hd, out, window=window)
     torch.cuda.synchronize()
     got = out.cpu().numpy()
     ph = oracle.to_host_matrix(pool.reshape(pool.shape[0], -1)).reshape(-1)
     ref = oracle.paged_attention(q.cpu().numpy(), ph, ph[Hkv * 16 * hd:], (2 * Hkv * 16 * hd, 16 * hd, hd),
-                                 table.numpy()[row_seq], [p + 1 for p in row_pos], Hkv)
+                                 table.numpy()[row_seq], [p + 1 for p in row_pos], Hkv, window=window)
     err = np.max(np.abs(got - ref), axis=(1, 2)) / np.abs(ref).max()
     assert err.max() <= 3e-5, (err.max(), int(err.argmax()), row_pos[int(err.argmax())])

@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-batch32", action="store_true", help="skip the batch-32 continuous-batching leg")
     ap.add_argument("--only-batch32", action="store_true", help="debug: run only the batch-32 leg (prints its dict)")
+    ap.add_argument("--only-gqa", action="store_true",
+                    help="run only the batch-32 leg on the grouped-KV 7B shape (8 KV heads, attention band 4096); "
+                         "prints its dict")
     ap.add_argument("--only-13b", action="store_true",
                     help="run only the 13B-shaped batch-64 workload (~200 GB KV pool, 64 steps of 63 decode rows + one "
                          "2048-token prefill chunk); prints its dict instead of the benchmark line")
@@ -242,9 +245,10 @@ def run_batch32(args, ld, torch, shape, model):
     torch.cuda.synchronize()
     pure_ms, mixed_ms, pure_bytes = [], [], []
     Wb, kappa = shape.weight_bytes_per_step, shape.kv_bytes_per_token
+    visible = (lambda n: min(n, shape.window)) if shape.window else (lambda n: n)   # positions a decode row reads
     t_begin = time.perf_counter()
     for step in range(1, steps + 1):
-        sum_ctx = sum(ld.ld_kv_len(kv.h, s) + 1 for s in seqs)
+        sum_ctx = sum(visible(ld.ld_kv_len(kv.h, s) + 1) for s in seqs)
         if step % 16 == 0:
             pick = gen.permutation(seed, 3000 + step, B)[:4].tolist()
             pf = [seqs[i] for i in pick]
@@ -265,12 +269,13 @@ def run_batch32(args, ld, torch, shape, model):
         ld.ld_decode_step(kv.h, seqs, stream, noop_cb)
     prof = ld.ld_kv_profile_read(kv.h)
     ld.ld_kv_profile(kv.h, False)
-    sum_ctx = sum(ld.ld_kv_len(kv.h, s) for s in seqs)
+    sum_ctx = sum(visible(ld.ld_kv_len(kv.h, s)) for s in seqs)
     att_bytes = sum_ctx * 2 * shape.n_kv_heads * shape.head_dim * 2
     att_avg = prof["attention"][0] / max(prof["attention"][1], 1) * 1e-3
     out = {
-        "workload": "7B-shaped bf16 decoder, continuous batching at batch 32, contexts U[512,8192], 128 steps, "
-                    "4 sequences get a 256-token observation chunk every 16th step",
+        "workload": f"{shape.name}-shaped bf16 decoder ({shape.n_heads} heads on {shape.n_kv_heads} KV heads, "
+                    f"attention band {shape.window or 'none'}), continuous batching at batch 32, contexts U[512,8192], "
+                    "128 steps, 4 sequences get a 256-token observation chunk every 16th step",
         "decode_tokens_per_s": round(B * len(pure_ms) / (sum(pure_ms) / 1e3), 1),
         "ms_per_pure_decode_step": round(statistics.mean(pure_ms), 3),
         "ms_per_mixed_step": round(statistics.mean(mixed_ms), 3),
@@ -281,7 +286,7 @@ def run_batch32(args, ld, torch, shape, model):
         "attention_GBps": round(att_bytes / att_avg / 1e9, 1),
         "attention_hbm_frac": round(att_bytes / att_avg / HBM_PEAK, 4),
         "kernel_ms_per_step": {k: round(v[0] / 4, 4) for k, v in prof.items()},
-        "sum_context": int(sum_ctx),
+        "sum_visible_context": int(sum_ctx),
     }
     kv.close()
     return out
@@ -367,12 +372,17 @@ def main():
         sys.exit(2)
     import torch
     import paper_2406_00059_amd as ld
-    from workloads import LLAMA7B, SEED_BASE, make_weights
+    from workloads import LLAMA7B, MISTRAL7B, SEED_BASE, make_weights
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     ld.lib()
     torch.cuda.set_device(0)
     if args.only_13b:
         print(json.dumps(run_13b(args, ld, torch)))
+        return
+    if args.only_gqa:
+        shape = MISTRAL7B if not args.layers else MISTRAL7B.with_layers(args.layers)
+        weights = make_weights(shape, SEED_BASE + 5, device="cuda")
+        print(json.dumps(run_batch32(args, ld, torch, shape, ld.Model(shape, weights, max_chunk=CHUNK))))
         return
     shape = LLAMA7B if not args.layers else LLAMA7B.with_layers(args.layers)
     if args.kernel_probe:

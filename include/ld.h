@@ -93,8 +93,11 @@ ld_status ld_model_create(const ld_model_config *cfg, const ld_weights *w, ld_mo
 void ld_model_destroy(ld_model *m);
 
 /* Bytes of the KV pool for n_blocks blocks.  Pool layout (element type cfg.dtype):
- *   [layer][block][K=0|V=1][kv_head][slot 0..15][head_dim]
- * Token j of a sequence lives in physical block table[j / 16], slot j % 16. */
+ *   keys    [layer][block][0][kv_head][slot 0..15][head_dim]
+ *   values  [layer][block][1][kv_head][head_dim][slot 0..15]     (transposed inside the block)
+ * Token j of a sequence lives in physical block table[j / 16], slot j % 16.  A key row is
+ * contiguous over head_dim; the 16 positions of one value dimension are contiguous, which is the
+ * operand order of the probability-weighted sum over positions. */
 size_t ld_kv_bytes(const ld_model *m, int64_t n_blocks);
 
 /* Bytes of scratch a step of up to max_tokens rows (decode rows + prefill-chunk rows)

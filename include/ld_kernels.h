@@ -54,10 +54,11 @@ ld_status ldk_rope_table(const int32_t *pos, int32_t T, int32_t hd, float rope_b
 
 /* Rotary embedding + cache append for T rows of a fused projection qkv [T, (H + 2 Hkv) hd]:
  * rotates every q head and k head of row t in place by the angles in cos_sin[t] (pair i =
- * elements (i, i + hd/2) of a head), then stores k and v, rounded to `dtype` (nearest even), at
- *   pool_layer[table[seq_slot[t] * table_stride + pos[t] / 16]][K|V][kv_head][pos[t] % 16][:].
- * pool_layer is one layer's slice of the pool: [block][2][Hkv][16][hd].  Rows of one call must
- * address distinct (sequence, position) pairs. */
+ * elements (i, i + hd/2) of a head), then stores k and v, rounded to `dtype` (nearest even), into
+ * block b = table[seq_slot[t] * table_stride + pos[t] / 16], slot s = pos[t] % 16 of pool_layer:
+ *   pool_layer[b][0][kv_head][s][:] = k,     pool_layer[b][1][kv_head][:][s] = v   (values transposed).
+ * pool_layer is one layer's slice of the pool: keys [block][0][Hkv][16][hd], values [block][1][Hkv][hd][16].
+ * Rows of one call must address distinct (sequence, position) pairs. */
 ld_status ldk_rope_kv_write(float *qkv, const float *cos_sin, const int32_t *pos, const int32_t *seq_slot,
                             const int32_t *table, int32_t table_stride, void *pool_layer, int32_t dtype, int32_t T,
                             int32_t H, int32_t Hkv, int32_t hd, void *stream);

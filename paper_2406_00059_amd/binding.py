@@ -378,7 +378,8 @@ class KV:
         sh = model.shape
         pdtype = torch.bfloat16 if sh.dtype == "bf16" else torch.float32
         nbytes = ld_kv_bytes(model.h, n_blocks)
-        # [layer][block][K|V][kv_head][slot][head_dim]
+        # [layer][block][K|V][kv_head][16 * head_dim]: a head's keys are [slot][head_dim], its values are
+        # stored transposed, [head_dim][slot] (the tensor's last two dimensions only size the memory)
         self.pool = pool if pool is not None else torch.zeros(
             (sh.n_layers, n_blocks, 2, sh.n_kv_heads, sh.kv_block, sh.head_dim), dtype=pdtype, device=device)
         assert self.pool.numel() * self.pool.element_size() == nbytes

@@ -14,11 +14,16 @@
 // everywhere and the online-softmax statistics of a query live in the lanes that hold its scores:
 //   S^T[kv, q] = K[kv, :] . Q[q, :]      A = K rows   (16-byte loads straight from the pool),
 //                                        B = Q        (registers, split into bf16 hi + lo)
-//   O^T[d, q] += V^T[d, kv] P^T[kv, q]   A = V^T      (the V tile is transposed while it is staged
-//                                                      into LDS and shared by the four waves),
+//   O^T[d, q] += V^T[d, kv] P^T[kv, q]   A = V^T      (the pool stores the values of a block transposed,
+//                                                      [dim][16 positions], so the tile is copied into
+//                                                      LDS in 16-byte pieces and shared by the four waves),
 //                                        B = P^T      (the score registers themselves: in the 32x32
 //                                                      accumulator layout a lane already holds, for
 //                                                      its query, exactly the 8 kv slots of an operand)
+// Row r of a score tile is NOT position kv0 + r: within each 16 rows, bits 2 and 3 of the row index are
+// swapped (row r <-> position 16 (r/16) + tau(r%16), tau(r) = (r & 3) | (r & 4) << 1 | (r & 8) >> 1), so
+// that the 8 accumulator registers a lane feeds into one value MFMA are 8 CONSECUTIVE positions, i.e. one
+// 16-byte piece of the transposed value tile.
 // Scores are kept in the log2 domain (q is pre-multiplied by log2(e)/sqrt(hd)); m, l and O are float32.
 #include "ld_attn_prefill.h"
 #include "ld_device.h"
@@ -31,11 +36,12 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int HD = 128;
 constexpr int KVB = 32;        // kv positions per step
-constexpr int VLD = KVB + 4;   // LDS row stride of the transposed V tile (elements)
+constexpr int VLD = KVB + 8;   // LDS row stride of the transposed V tile (elements): 80 bytes, 16-byte aligned
+
+__device__ __forceinline__ int tau(int r) { return (r & 19) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
 __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ q, int q_stride,
                                                       const bf16_t *__restrict__ pool, int Hkv,
@@ -48,7 +54,7 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int kvh = h / (H / Hkv);
-    const int64_t block_stride = (int64_t)2 * Hkv * 16 * HD;
+    const int64_t block_stride = kv_block_elems(Hkv, HD);
     const int32_t *trow = table + (int64_t)tile.w * table_stride;
 
     // this lane's query: row index inside the tile, validity, absolute position
@@ -90,19 +96,17 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
 
     // K operand rows and V pieces of one 32-position step, loaded one step ahead of their use
     auto load_k = [&](u32x4 (&kf)[8], int kv0) {
-        const int pos = min(kv0 + l32, wg_last_pos);
-        const bf16_t *kp = pool + (int64_t)trow[pos >> 4] * block_stride + ((int64_t)kvh * 16 + (pos & 15)) * HD + half * 64;
+        const int pos = min(kv0 + tau(l32), wg_last_pos);
+        const bf16_t *kp = pool + (int64_t)trow[pos >> 4] * block_stride + kv_k_offset(HD, kvh, pos & 15, half * 64);
 #pragma unroll
         for (int j = 0; j < 8; j++) kf[j] = *reinterpret_cast<const u32x4 *>(kp + j * 8);
     };
     auto load_v = [&](u32x4 (&vr)[2], int kv0) {
 #pragma unroll
-        for (int v = 0; v < 2; v++) {
-            const int idx = threadIdx.x + 256 * v;          // 512 pieces of 8 dims
-            const int kv = idx >> 4, d0 = (idx & 15) * 8;
-            const int pos = min(kv0 + kv, wg_last_pos);
-            const bf16_t *src = pool + (int64_t)trow[pos >> 4] * block_stride +
-                                (((int64_t)Hkv + kvh) * 16 + (pos & 15)) * HD + d0;
+        for (int v = 0; v < 2; v++) {                       // block v of the step: 256 pieces of 8 positions
+            const int d = threadIdx.x >> 1, h8 = (threadIdx.x & 1) * 8;
+            const int pos = min(kv0 + 16 * v, wg_last_pos);   // a block past the last needed position is never used
+            const bf16_t *src = pool + (int64_t)trow[pos >> 4] * block_stride + kv_v_offset(Hkv, HD, kvh, h8, d);
             vr[v] = *reinterpret_cast<const u32x4 *>(src);
         }
     };
@@ -114,15 +118,8 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
         // ---- stage V^T of positions kv0 .. kv0+31 (clamped to the last needed position) into LDS
         lds_barrier();
 #pragma unroll
-        for (int v = 0; v < 2; v++) {
-            const int idx = threadIdx.x + 256 * v;
-            const int kv = idx >> 4, d0 = (idx & 15) * 8;
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-                vt[d0 + 2 * e][kv] = (bf16_t)(vr[v][e] & 0xffffu);
-                vt[d0 + 2 * e + 1][kv] = (bf16_t)(vr[v][e] >> 16);
-            }
-        }
+        for (int v = 0; v < 2; v++)
+            *reinterpret_cast<u32x4 *>(&vt[threadIdx.x >> 1][16 * v + (threadIdx.x & 1) * 8]) = vr[v];
         lds_barrier();
         const bool more = kv0 + KVB <= wg_last_pos;
         if (more) { load_k(kn, kv0 + KVB); load_v(vr, kv0 + KVB); }
@@ -144,11 +141,12 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
             st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qh[j], st, 0, 0, 0);
             st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, ql[j], st, 0, 0, 0);
         }
-        // ---- online softmax; accumulator element i is kv position kv0 + 8*(i/4) + 4*half + i%4
+        // ---- online softmax; accumulator element i is row 8*(i/4) + 4*half + i%4 of the tile, which holds
+        // position kv0 + 16*(i/8) + 8*half + i%8
         float mb = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 16; i++) {
-            const int kv_pos = kv0 + 8 * (i / 4) + 4 * half + (i % 4);
+            const int kv_pos = kv0 + 16 * (i / 8) + 8 * half + (i % 8);
             const bool ok = q_valid && kv_pos <= q_pos && kv_pos >= q_low;
             st[i] = ok ? st[i] : -INFINITY;
             mb = fmaxf(mb, st[i]);
@@ -179,11 +177,9 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
             for (int i = 0; i < 16; i++) o[nt][i] *= sc;
 #pragma unroll
             for (int mm = 0; mm < 2; mm++) {
-                // slot e of this lane <-> kv = 16*mm + 8*(e/4) + 4*half + e%4
-                const bf16_t *vp = &vt[nt * 32 + l32][16 * mm + 4 * half];
-                const u32x2 v0 = *reinterpret_cast<const u32x2 *>(vp);
-                const u32x2 v1 = *reinterpret_cast<const u32x2 *>(vp + 8);
-                const bf16x8 va = __builtin_bit_cast(bf16x8, (u32x4){v0[0], v0[1], v1[0], v1[1]});
+                // slot e of this lane <-> position kv0 + 16*mm + 8*half + e
+                const bf16x8 va = __builtin_bit_cast(
+                    bf16x8, *reinterpret_cast<const u32x4 *>(&vt[nt * 32 + l32][16 * mm + 8 * half]));
                 const bf16x8 pbh = __builtin_bit_cast(bf16x8, (u32x4){ph[4 * mm], ph[4 * mm + 1], ph[4 * mm + 2], ph[4 * mm + 3]});
                 const bf16x8 pbl = __builtin_bit_cast(bf16x8, (u32x4){pl[4 * mm], pl[4 * mm + 1], pl[4 * mm + 2], pl[4 * mm + 3]});
                 o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbh, o[nt], 0, 0, 0);

@@ -94,9 +94,15 @@ __global__ __launch_bounds__(256) void k_red_rope(const float *__restrict__ part
     } else {
         const int which = hh < H + Hkv ? 0 : 1, j = hh - H - which * Hkv, p = pos[t];
         const int64_t phys = table[(int64_t)seq_slot[t] * table_stride + (p >> 4)];
-        bf16_t *dst = pool + phys * ((int64_t)2 * Hkv * 16 * HD) + (((int64_t)which * Hkv + j) * 16 + (p & 15)) * HD;
-        dst[i] = f32_to_bf16(a);
-        dst[i + HALF] = f32_to_bf16(b);
+        bf16_t *blk = pool + phys * kv_block_elems(Hkv, HD);
+        const int slot = p & 15;
+        if (which == 0) {
+            blk[kv_k_offset(HD, j, slot, i)] = f32_to_bf16(a);
+            blk[kv_k_offset(HD, j, slot, i + HALF)] = f32_to_bf16(b);
+        } else {
+            blk[kv_v_offset(Hkv, HD, j, slot, i)] = f32_to_bf16(a);
+            blk[kv_v_offset(Hkv, HD, j, slot, i + HALF)] = f32_to_bf16(b);
+        }
     }
 }
 

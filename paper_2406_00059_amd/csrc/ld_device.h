@@ -81,12 +81,52 @@ __device__ __forceinline__ void load8_stream(const float *p, float (&v)[8]) {
     }
 }
 
+// N = 2 or 4 consecutive elements with the streaming hint, as floats (aligned to N elements).
+template <int N>
+__device__ __forceinline__ void loadn_stream(const bf16_t *p, float (&v)[N]) {
+    typedef uint32_t uN __attribute__((ext_vector_type(N / 2)));
+    static_assert(N == 4, "bf16: four elements (8 bytes)");
+    const uN u = __builtin_nontemporal_load(reinterpret_cast<const uN *>(p));
+#pragma unroll
+    for (int i = 0; i < N / 2; i++) {
+        v[2 * i] = __uint_as_float(u[i] << 16);
+        v[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+    }
+}
+template <>
+__device__ __forceinline__ void loadn_stream<2>(const bf16_t *p, float (&v)[2]) {
+    const uint32_t u = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
+    v[0] = __uint_as_float(u << 16);
+    v[1] = __uint_as_float(u & 0xffff0000u);
+}
+template <int N>
+__device__ __forceinline__ void loadn_stream(const float *p, float (&v)[N]) {
+    typedef float fN __attribute__((ext_vector_type(N)));
+    const fN u = __builtin_nontemporal_load(reinterpret_cast<const fN *>(p));
+#pragma unroll
+    for (int i = 0; i < N; i++) v[i] = u[i];
+}
+
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also carries a memory fence, which
 // on this target waits for every outstanding global load (vmcnt(0)) and so drains loads that were
 // issued ahead on purpose; this one waits for the LDS/scalar counter only and leaves them in flight.
 // Use it only where the data exchanged between waves goes through LDS.
 __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// ---------------------------------------------------------------- layout of one KV block
+// A block holds 16 positions of every KV head: the keys position-major, [kv_head][slot][hd], then the
+// values TRANSPOSED, [kv_head][hd][slot].  A key row (one position, hd elements) is contiguous, which is
+// the operand shape of q.k; a value row of the transposed part holds the 16 positions of one dimension,
+// contiguous, which is the operand shape of the probability-weighted sum on the matrix cores (the
+// contraction runs over positions) and costs the scalar kernels nothing.  Offsets in elements:
+__device__ __forceinline__ int64_t kv_block_elems(int Hkv, int hd) { return (int64_t)2 * Hkv * 16 * hd; }
+__device__ __forceinline__ int64_t kv_k_offset(int hd, int kvh, int slot, int dim) {
+    return ((int64_t)kvh * 16 + slot) * hd + dim;
+}
+__device__ __forceinline__ int64_t kv_v_offset(int Hkv, int hd, int kvh, int slot, int dim) {
+    return (int64_t)Hkv * 16 * hd + ((int64_t)kvh * hd + dim) * 16 + slot;
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

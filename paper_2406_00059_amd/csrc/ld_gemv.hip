@@ -214,10 +214,15 @@ __global__ __launch_bounds__(1024) void k_gemv1(const bf16_t *__restrict__ W, co
                     const int j = hh - rk.H - which * rk.Hkv;
                     const int p = rk.pos[0];
                     const int64_t phys = rk.table[(int64_t)rk.seq_slot[0] * rk.table_stride + (p >> 4)];
-                    bf16_t *dst = rk.pool + phys * ((int64_t)2 * rk.Hkv * 16 * hd) +
-                                  (((int64_t)which * rk.Hkv + j) * 16 + (p & 15)) * hd;
-                    dst[i] = f32_to_bf16(a);
-                    dst[i + half_hd] = f32_to_bf16(b);
+                    bf16_t *blk = rk.pool + phys * kv_block_elems(rk.Hkv, hd);
+                    const int slot = p & 15;
+                    if (which == 0) {
+                        blk[kv_k_offset(hd, j, slot, i)] = f32_to_bf16(a);
+                        blk[kv_k_offset(hd, j, slot, i + half_hd)] = f32_to_bf16(b);
+                    } else {
+                        blk[kv_v_offset(rk.Hkv, hd, j, slot, i)] = f32_to_bf16(a);
+                        blk[kv_v_offset(rk.Hkv, hd, j, slot, i + half_hd)] = f32_to_bf16(b);
+                    }
                 }
             }
         }

@@ -166,13 +166,12 @@ __global__ void k_rope_kv_write(float *__restrict__ qkv, const float2 *__restric
     const float a = ku[i], b = ku[i + half];
     const int p = pos[t];
     const int64_t phys = table[(int64_t)seq_slot[t] * table_stride + (p >> 4)];
-    const int64_t block_stride = (int64_t)2 * Hkv * 16 * hd;
-    KVT *kd = pool + phys * block_stride + ((int64_t)j * 16 + (p & 15)) * hd;
-    KVT *vd = kd + (int64_t)Hkv * 16 * hd;
-    store_elem(kd + i, a * c.x - b * c.y);
-    store_elem(kd + i + half, a * c.y + b * c.x);
-    store_elem(vd + i, vu[i]);
-    store_elem(vd + i + half, vu[i + half]);
+    KVT *blk = pool + phys * kv_block_elems(Hkv, hd);
+    const int slot = p & 15;
+    store_elem(blk + kv_k_offset(hd, j, slot, i), a * c.x - b * c.y);
+    store_elem(blk + kv_k_offset(hd, j, slot, i + half), a * c.y + b * c.x);
+    store_elem(blk + kv_v_offset(Hkv, hd, j, slot, i), vu[i]);
+    store_elem(blk + kv_v_offset(Hkv, hd, j, slot, i + half), vu[i + half]);
 }
 
 // ---------------------------------------------------------------- paged decode attention
@@ -182,10 +181,12 @@ __global__ void k_rope_kv_write(float *__restrict__ qkv, const float2 *__restric
 // queries.  Chunk c covers CB consecutive KV blocks (CB*16 tokens) of the VISIBLE part of the row's
 // context: with an attention band of W positions the row (at position ctx-1) sees positions
 // max(0, ctx - W) .. ctx-1 and the walk starts at the block that holds the first of them.  A workgroup
-// of 4 waves takes one work item, wave w the blocks w, w+4, ... of the chunk.  Inside a wave, HD/8
-// adjacent lanes cover one token's head vector with 16-byte loads (8 elements each), so one load
-// instruction brings 64/(HD/8) whole tokens and consecutive lanes read consecutive memory.  Scores are
-// reduced across those lanes with xor shuffles; each lane group keeps its own online-softmax state
+// of 4 waves takes one work item, wave w the blocks w, w+4, ... of the chunk.  Inside a wave, a lane
+// group of HD/8 adjacent lanes covers one key row with 16-byte loads (8 elements each) and owns a fixed
+// run of a block's 16 positions (4 of them for head_dim 128); scores are reduced across the group with
+// xor shuffles.  The values of a block are stored transposed ([dim][position]), so the same group reads,
+// for each of its dimensions, exactly its own positions in one small load, and one load instruction of
+// the wave still covers a contiguous run of memory.  Each lane group keeps its own online-softmax state
 // (m, l, acc) per query in the log2 domain, merged across groups, waves and finally chunks.
 
 // KV blocks per chunk: a multiple of 4 (one per wave), chosen per launch by attn_chunk_blocks().
@@ -201,9 +202,10 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
                                                       const int32_t *__restrict__ ctx_len, int H, int window,
                                                       float scale_log2e, int max_chunks, int cb,
                                                       float *__restrict__ part_o, float *__restrict__ part_ml) {
-    constexpr int LPT = HD / 8;      // lanes per token
-    constexpr int TPI = WAVE / LPT;  // tokens per load instruction
-    constexpr int NI = 16 / TPI;     // load instructions per 16-token block
+    constexpr int LPT = HD / 8;      // lanes per key row = lanes of a lane group
+    constexpr int NG = WAVE / LPT;   // lane groups per wave
+    constexpr int NI = 16 / NG;      // positions of a block per lane group: group g owns slots NI*g .. NI*g+NI-1
+    constexpr int NV = HD / LPT;     // value dimensions per lane (= 8): dims sub, sub + LPT, ...
     const int c = blockIdx.x, t = blockIdx.z;
     // G > 1: blockIdx.y is the KV head and the queries are heads kvh*G .. kvh*G+G-1; G == 1: blockIdx.y is the head
     const int h0 = blockIdx.y * G;
@@ -216,7 +218,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
     const int b_end = min(b_begin + cb, nblk);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int group = lane / LPT, sub = lane % LPT;
-    const int64_t block_stride = (int64_t)2 * Hkv * 16 * HD;
+    const int64_t block_stride = kv_block_elems(Hkv, HD);
     const int32_t *trow = table + (int64_t)seq_slot[t] * table_stride;
 
     float qv[G][8];
@@ -226,31 +228,37 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
 #pragma unroll
         for (int e = 0; e < 8; e++) qv[g][e] = qp[e] * scale_log2e;
     }
-    float m[G], l[G], acc[G][8];
+    // Online softmax in the log2 domain, one state per lane group and query: the group's LPT lanes split a
+    // key row for the scores and the value dimensions for the weighted sum, always over the group's own
+    // NI positions of a block, so that no probability ever crosses a lane group.
+    float m[G], l[G], acc[G][NV];
 #pragma unroll
     for (int g = 0; g < G; g++) {
         m[g] = -INFINITY; l[g] = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; e++) acc[g][e] = 0.f;
+        for (int v = 0; v < NV; v++) acc[g][v] = 0.f;
     }
 
     for (int b = b_begin + wave; b < b_end; b += 4) {
-        const int64_t phys = trow[b];
-        const KVT *kb = pool + phys * block_stride + (int64_t)kvh * 16 * HD + lane * 8;
-        const KVT *vb = kb + (int64_t)Hkv * 16 * HD;
-        float kf[NI][8], vf[NI][8];
+        const KVT *blk = pool + (int64_t)trow[b] * block_stride;
+        // keys: row of slot NI*group + i, elements sub*8 .. +8; a load instruction reads NG rows of 16*LPT bytes
+        const KVT *kb = blk + kv_k_offset(HD, kvh, NI * group, sub * 8);
+        // values (transposed): dimension sub + LPT*v, slots NI*group .. +NI; a load instruction reads
+        // LPT dimensions x 16 slots = one contiguous run
+        const KVT *vb = blk + kv_v_offset(Hkv, HD, kvh, NI * group, sub);
+        float kf[NI][8], vf[NV][NI];
 #pragma unroll
-        for (int i = 0; i < NI; i++) load8_stream(kb + i * TPI * HD, kf[i]);
+        for (int i = 0; i < NI; i++) load8_stream(kb + i * HD, kf[i]);
 #pragma unroll
-        for (int i = 0; i < NI; i++) load8_stream(vb + i * TPI * HD, vf[i]);
+        for (int v = 0; v < NV; v++) loadn_stream<NI>(vb + v * LPT * 16, vf[v]);
         bool valid[NI];
 #pragma unroll
         for (int i = 0; i < NI; i++) {
-            const int pos = b * 16 + i * TPI + group;   // position of this lane group's token
+            const int pos = b * 16 + NI * group + i;
             valid[i] = pos >= first && pos < ctx;
-            if (!valid[i]) {
+            if (!valid[i]) {        // an unwritten slot may hold anything
 #pragma unroll
-                for (int e = 0; e < 8; e++) vf[i][e] = 0.f;
+                for (int v = 0; v < NV; v++) vf[v][i] = 0.f;
             }
         }
 #pragma unroll
@@ -272,13 +280,13 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
                 const float sc = fast_exp2(m[g] - m_new);
                 l[g] *= sc;
 #pragma unroll
-                for (int e = 0; e < 8; e++) acc[g][e] *= sc;
+                for (int v = 0; v < NV; v++) acc[g][v] *= sc;
 #pragma unroll
                 for (int i = 0; i < NI; i++) {
                     const float p = fast_exp2(s[i] - m_new);
                     l[g] += p;
 #pragma unroll
-                    for (int e = 0; e < 8; e++) acc[g][e] = fmaf(p, vf[i][e], acc[g][e]);
+                    for (int v = 0; v < NV; v++) acc[g][v] = fmaf(p, vf[v][i], acc[g][v]);
                 }
                 m[g] = m_new;
             }
@@ -295,7 +303,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
             const float bsc = (m_n > -INFINITY) ? fast_exp2(m_o - m_n) : 0.f;
             l[g] = l[g] * a + l_o * bsc;
 #pragma unroll
-            for (int e = 0; e < 8; e++) acc[g][e] = acc[g][e] * a + __shfl_xor(acc[g][e], off, WAVE) * bsc;
+            for (int v = 0; v < NV; v++) acc[g][v] = acc[g][v] * a + __shfl_xor(acc[g][v], off, WAVE) * bsc;
             m[g] = m_n;
         }
     }
@@ -304,14 +312,14 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
 #pragma unroll
         for (int g = 0; g < G; g++) {
 #pragma unroll
-            for (int e = 0; e < 8; e++) sm_acc[wave][g][sub * 8 + e] = acc[g][e];
+            for (int v = 0; v < NV; v++) sm_acc[wave][g][sub + LPT * v] = acc[g][v];
             if (lane == 0) { sm_m[wave][g] = m[g]; sm_l[wave][g] = l[g]; }
         }
     }
     __syncthreads();
     for (int idx = threadIdx.x; idx < G * HD; idx += 256) {
         const int g = idx / HD, d = idx % HD;
-        // a wave that saw no visible token keeps m = -inf and weight 0; at least one wave saw one
+        // a wave that saw no visible position keeps m = -inf and weight 0; wave 0 always sees one
         const float M = fmaxf(fmaxf(sm_m[0][g], sm_m[1][g]), fmaxf(sm_m[2][g], sm_m[3][g]));
         float o = 0.f, L = 0.f;
 #pragma unroll

@@ -53,3 +53,21 @@ class Tokens:
 
     def last(self, n=1):
         return [t for _, t, _ in self.log[-n:]]
+
+
+def device_pool(logical):
+    """KV blocks [..., K|V, kv_head, slot, hd] (the indexing the oracle uses) -> the memory image the
+    library reads: the keys as they are, the values of a head transposed to [hd][slot].  Same shape
+    and bytes; the last two dimensions of the value half then only size the memory."""
+    out = logical.clone()
+    v = logical[..., 1, :, :, :]
+    out[..., 1, :, :, :] = v.transpose(-1, -2).reshape(v.shape)
+    return out
+
+
+def logical_pool(dev):
+    """Inverse of device_pool: a pool the library wrote -> [..., K|V, kv_head, slot, hd]."""
+    out = dev.clone()
+    v = dev[..., 1, :, :, :]
+    out[..., 1, :, :, :] = v.reshape(*v.shape[:-2], v.shape[-1], v.shape[-2]).transpose(-1, -2)
+    return out

@@ -28,8 +28,12 @@ def inject_history(P, s, n, seed, stream, pending):
     table = torch.from_numpy(ld.ld_kv_block_table(P.gkv.h, s).astype(np.int64)).cuda()
     pos = torch.arange(start, start + n, device="cuda")
     blk, slot = table[pos // 16], pos % 16
-    # pool [layer][block][K|V][head][slot][hd]  <-  hist [n][layer][K|V][head][hd]
-    P.gkv.pool[:, blk, :, :, slot, :] = hist          # advanced indices (blk, slot) lead: [n, layer, K|V, head, hd]
+    # keys: pool [layer][block][K][head][slot][hd]  <-  hist [n][layer][K][head][hd]
+    pool = P.gkv.pool
+    pool[:, blk, 0, :, slot, :] = hist[:, :, 0]       # advanced indices (blk, slot) lead: [n, layer, head, hd]
+    # values are stored transposed: [layer][block][V][head][hd][slot]
+    L, NB, _, Hk, _, hd = pool.shape
+    pool[:, :, 1].view(L, NB, Hk, hd, 16)[:, blk, :, :, slot] = hist[:, :, 1]
     assert P.tables_equal(s)
 
 

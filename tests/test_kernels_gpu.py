@@ -9,6 +9,7 @@ import torch
 import oracle
 import paper_2406_00059_amd as ld
 from workloads import gen
+from helpers import device_pool, logical_pool
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -98,7 +99,7 @@ def test_rope_and_cache_append_values_and_block_indexing(dtype, hd):
     q = qkv.to(DEV).clone()
     ld.ldk_rope_table(pos.to(DEV), hd, 10000.0, cs)
     ld.ldk_rope_kv_write(q, cs, pos.to(DEV), slot.to(DEV), table.to(DEV), pool, H, Hkv, hd)
-    q, pool_h = q.cpu().numpy(), pool.float().cpu().numpy().astype(np.float64)
+    q, pool_h = q.cpu().numpy(), logical_pool(pool).float().cpu().numpy().astype(np.float64)
     touched = np.zeros(pool_h.shape[:4], bool)
     for t in range(T):
         p = int(pos[t]); blk = int(table[slot[t], p // 16]); s = p % 16
@@ -145,8 +146,8 @@ def _run_attention(table, pool, q, lens, H, Hkv, hd, window=0):
     out = torch.empty(B, H, hd, device=DEV)
     scratch = torch.empty(ld.ldk_attention_scratch_bytes(B, H, Hkv, hd, max(lens), window), dtype=torch.uint8,
                           device=DEV)
-    ld.ldk_paged_attention(q, H * hd, pool, table.to(DEV), slot, ctx, max(lens), H, Hkv, hd, out, scratch,
-                           window=window)
+    ld.ldk_paged_attention(q, H * hd, device_pool(pool), table.to(DEV), slot, ctx, max(lens), H, Hkv, hd, out,
+                           scratch, window=window)
     torch.cuda.synchronize()
     return out.cpu().numpy()
 
@@ -251,7 +252,7 @@ def test_fused_qkv_projection_rope_cache_append(dtype, hd, T):
     ld.ldk_rope_table(pos.to(DEV), hd, 10000.0, cs)
     ld.ldk_qkv_rope(W.to(DEV), x.to(DEV), qkv, cs, pos.to(DEV), slot.to(DEV), table.to(DEV), pool, H, Hkv, hd,
                     g=g.to(DEV), eps=1e-5)
-    qkv_h, pool_h = qkv.cpu().numpy(), pool.float().cpu().numpy().astype(np.float64)
+    qkv_h, pool_h = qkv.cpu().numpy(), logical_pool(pool).float().cpu().numpy().astype(np.float64)
     Wh = oracle.to_host_matrix(W)
     touched = np.zeros(pool_h.shape[:4], bool)
     for t in range(T):
@@ -367,7 +368,7 @@ def test_prefill_attention_segments(H, Hkv, window):
             tiles.append([r + off, min(128, n - off), p0 + off, s])
         row_seq += [s] * n; row_pos += list(range(p0, p0 + n)); r += n
     out = torch.zeros(T, H, hd, device=DEV)
-    ld.ldk_prefill_attention(q, H * hd, pool, table.to(DEV), torch.tensor(tiles, dtype=torch.int32, device=DEV),
+    ld.ldk_prefill_attention(q, H * hd, device_pool(pool), table.to(DEV), torch.tensor(tiles, dtype=torch.int32, device=DEV),
                              H, Hkv, hd, out, window=window)
     torch.cuda.synchronize()
     got = out.cpu().numpy()

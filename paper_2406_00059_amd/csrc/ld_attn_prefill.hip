@@ -8,15 +8,17 @@
 // before the band of its own first row.
 //
 // Work split: a workgroup (4 waves) takes 128 consecutive rows of a segment and one head; wave w
-// owns rows [32w, 32w+32).  All four waves walk the same KV positions in steps of 32 tokens.
+// owns rows [32w, 32w+32).  All four waves walk the same KV positions in steps of 32 tokens; the key
+// rows and the (transposed) value tile of a step are copied into LDS once, in 16-byte pieces that were
+// loaded into registers one step earlier, and shared by the four waves.  LDS is double buffered: one
+// barrier per step.  Two workgroups fit a CU, so that one wave's softmax overlaps another's MFMAs.
 //
 // Both products are computed transposed, so that the query index is the MFMA column (= lane % 32)
 // everywhere and the online-softmax statistics of a query live in the lanes that hold its scores:
-//   S^T[kv, q] = K[kv, :] . Q[q, :]      A = K rows   (16-byte loads straight from the pool),
+//   S^T[kv, q] = K[kv, :] . Q[q, :]      A = K rows   (LDS),
 //                                        B = Q        (registers, split into bf16 hi + lo)
-//   O^T[d, q] += V^T[d, kv] P^T[kv, q]   A = V^T      (the pool stores the values of a block transposed,
-//                                                      [dim][16 positions], so the tile is copied into
-//                                                      LDS in 16-byte pieces and shared by the four waves),
+//   O^T[d, q] += V^T[d, kv] P^T[kv, q]   A = V^T      (LDS; the pool stores the values of a block
+//                                                      transposed, [dim][16 positions]),
 //                                        B = P^T      (the score registers themselves: in the 32x32
 //                                                      accumulator layout a lane already holds, for
 //                                                      its query, exactly the 8 kv slots of an operand)
@@ -38,17 +40,19 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int HD = 128;
-constexpr int KVB = 32;        // kv positions per step
-constexpr int VLD = KVB + 8;   // LDS row stride of the transposed V tile (elements): 80 bytes, 16-byte aligned
+constexpr int KVB = 32;          // kv positions per step
+constexpr int KLD = HD + 8;      // LDS row stride of the key tile (elements): 272 bytes, conflict-free 16-byte reads
+constexpr int VLD = KVB + 8;     // LDS row stride of the transposed value tile (elements): 80 bytes
 
 __device__ __forceinline__ int tau(int r) { return (r & 19) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
-__global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ q, int q_stride,
-                                                      const bf16_t *__restrict__ pool, int Hkv,
-                                                      const int32_t *__restrict__ table, int table_stride,
-                                                      const int4 *__restrict__ tiles, int H, int window,
-                                                      float scale_log2e, float *__restrict__ out) {
-    __shared__ __attribute__((aligned(16))) bf16_t vt[HD][VLD];
+__global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict__ q, int q_stride,
+                                                         const bf16_t *__restrict__ pool, int Hkv,
+                                                         const int32_t *__restrict__ table, int table_stride,
+                                                         const int4 *__restrict__ tiles, int H, int window,
+                                                         float scale_log2e, float *__restrict__ out) {
+    __shared__ __attribute__((aligned(16))) bf16_t ks[2][KVB][KLD];
+    __shared__ __attribute__((aligned(16))) bf16_t vt[2][HD][VLD];
     const int4 tile = tiles[blockIdx.x];      // x: first row, y: rows (<= 128), z: position of first row, w: seq slot
     const int h = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -94,52 +98,50 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
         for (int i = 0; i < 16; i++) o[nt][i] = 0.f;
     float m = -INFINITY, l = 0.f;
 
-    // K operand rows and V pieces of one 32-position step, loaded one step ahead of their use
-    auto load_k = [&](u32x4 (&kf)[8], int kv0) {
-        const int pos = min(kv0 + tau(l32), wg_last_pos);
-        const bf16_t *kp = pool + (int64_t)trow[pos >> 4] * block_stride + kv_k_offset(HD, kvh, pos & 15, half * 64);
+    // The pieces this thread copies per step: key rows (position kr, 16-byte piece kc of the row) and
+    // value pieces (dimension vd, positions 8*vh .. +8 of block v of the step).
+    const int kr = threadIdx.x >> 4, kc = (threadIdx.x & 15) * 8;       // + 16 rows for the second piece
+    const int vd = threadIdx.x >> 1, vh = (threadIdx.x & 1) * 8;
+    u32x4 kreg[2], vreg[2];
+    auto load_step = [&](int kv0) {
 #pragma unroll
-        for (int j = 0; j < 8; j++) kf[j] = *reinterpret_cast<const u32x4 *>(kp + j * 8);
-    };
-    auto load_v = [&](u32x4 (&vr)[2], int kv0) {
-#pragma unroll
-        for (int v = 0; v < 2; v++) {                       // block v of the step: 256 pieces of 8 positions
-            const int d = threadIdx.x >> 1, h8 = (threadIdx.x & 1) * 8;
-            const int pos = min(kv0 + 16 * v, wg_last_pos);   // a block past the last needed position is never used
-            const bf16_t *src = pool + (int64_t)trow[pos >> 4] * block_stride + kv_v_offset(Hkv, HD, kvh, h8, d);
-            vr[v] = *reinterpret_cast<const u32x4 *>(src);
+        for (int v = 0; v < 2; v++) {
+            // a block past the last needed position is read again from the last needed block; never used
+            const int pos = min(kv0 + 16 * v, wg_last_pos);
+            const bf16_t *blk = pool + (int64_t)trow[pos >> 4] * block_stride;
+            kreg[v] = *reinterpret_cast<const u32x4 *>(blk + kv_k_offset(HD, kvh, kr, kc));
+            vreg[v] = *reinterpret_cast<const u32x4 *>(blk + kv_v_offset(Hkv, HD, kvh, vh, vd));
         }
     };
-    u32x4 kf[8], kn[8], vr[2];
-    load_k(kf, kv_start);
-    load_v(vr, kv_start);
-
-    for (int kv0 = kv_start; kv0 <= wg_last_pos; kv0 += KVB) {
-        // ---- stage V^T of positions kv0 .. kv0+31 (clamped to the last needed position) into LDS
-        lds_barrier();
+    auto stage = [&](int st) {
 #pragma unroll
-        for (int v = 0; v < 2; v++)
-            *reinterpret_cast<u32x4 *>(&vt[threadIdx.x >> 1][16 * v + (threadIdx.x & 1) * 8]) = vr[v];
-        lds_barrier();
-        const bool more = kv0 + KVB <= wg_last_pos;
-        if (more) { load_k(kn, kv0 + KVB); load_v(vr, kv0 + KVB); }
-        if (!wave_active || kv0 > wave_last_pos || kv0 + KVB <= wave_low) {   // nothing visible to this wave's queries
-            if (more) {
-#pragma unroll
-                for (int j = 0; j < 8; j++) kf[j] = kn[j];
-            }
-            continue;
+        for (int v = 0; v < 2; v++) {
+            *reinterpret_cast<u32x4 *>(&ks[st][16 * v + kr][kc]) = kreg[v];
+            *reinterpret_cast<u32x4 *>(&vt[st][vd][16 * v + vh]) = vreg[v];
         }
+    };
+    load_step(kv_start);
 
-        // ---- S^T = K Q^T for 32 kv positions x 32 queries
-        f32x16 st;
+    int st = 0;
+    for (int kv0 = kv_start; kv0 <= wg_last_pos; kv0 += KVB, st ^= 1) {
+        // Stage this step, then fetch the next one.  One barrier per step: a wave that writes buffer st for
+        // step n has passed the barrier of step n-1, which every wave reaches only after it has finished
+        // reading buffer st for step n-2.
+        stage(st);
+        lds_barrier();
+        if (kv0 + KVB <= wg_last_pos) load_step(kv0 + KVB);
+        if (!wave_active || kv0 > wave_last_pos || kv0 + KVB <= wave_low) continue;   // nothing visible to this wave
+
+        // ---- S^T = K Q^T for 32 kv positions x 32 queries; tile row l32 is position kv0 + tau(l32)
+        f32x16 sc_t;
 #pragma unroll
-        for (int i = 0; i < 16; i++) st[i] = 0.f;
+        for (int i = 0; i < 16; i++) sc_t[i] = 0.f;
+        const bf16_t *krow = &ks[st][tau(l32)][half * 64];
 #pragma unroll
         for (int j = 0; j < 8; j++) {
-            const bf16x8 ka = __builtin_bit_cast(bf16x8, kf[j]);
-            st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qh[j], st, 0, 0, 0);
-            st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, ql[j], st, 0, 0, 0);
+            const bf16x8 ka = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(krow + j * 8));
+            sc_t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qh[j], sc_t, 0, 0, 0);
+            sc_t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, ql[j], sc_t, 0, 0, 0);
         }
         // ---- online softmax; accumulator element i is row 8*(i/4) + 4*half + i%4 of the tile, which holds
         // position kv0 + 16*(i/8) + 8*half + i%8
@@ -148,8 +150,8 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
         for (int i = 0; i < 16; i++) {
             const int kv_pos = kv0 + 16 * (i / 8) + 8 * half + (i % 8);
             const bool ok = q_valid && kv_pos <= q_pos && kv_pos >= q_low;
-            st[i] = ok ? st[i] : -INFINITY;
-            mb = fmaxf(mb, st[i]);
+            sc_t[i] = ok ? sc_t[i] : -INFINITY;
+            mb = fmaxf(mb, sc_t[i]);
         }
         mb = fmaxf(mb, __shfl_xor(mb, 32, WAVE));
         const float m_new = fmaxf(m, mb);
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
             float psum = 0.f;
 #pragma unroll
             for (int i = 0; i < 16; i += 2) {
-                const float p0 = fast_exp2(st[i] - m_new), p1 = fast_exp2(st[i + 1] - m_new);
+                const float p0 = fast_exp2(sc_t[i] - m_new), p1 = fast_exp2(sc_t[i + 1] - m_new);
                 psum += p0 + p1;
                 ph[i / 2] = split2_bf16(p0, p1, pl[i / 2]);
             }
@@ -170,25 +172,24 @@ __global__ __launch_bounds__(256) void k_attn_prefill(const float *__restrict__ 
 #pragma unroll
             for (int e = 0; e < 8; e++) ph[e] = pl[e] = 0u;
         }
-        // ---- O^T = O^T * sc + V^T P^T
+        // ---- O^T = O^T * sc + V^T P^T; the rescale is skipped when no query of the wave raised its maximum
+        const bool rescale = __any(sc != 1.f);
 #pragma unroll
         for (int nt = 0; nt < 4; nt++) {
+            if (rescale) {
 #pragma unroll
-            for (int i = 0; i < 16; i++) o[nt][i] *= sc;
+                for (int i = 0; i < 16; i++) o[nt][i] *= sc;
+            }
 #pragma unroll
             for (int mm = 0; mm < 2; mm++) {
                 // slot e of this lane <-> position kv0 + 16*mm + 8*half + e
                 const bf16x8 va = __builtin_bit_cast(
-                    bf16x8, *reinterpret_cast<const u32x4 *>(&vt[nt * 32 + l32][16 * mm + 8 * half]));
+                    bf16x8, *reinterpret_cast<const u32x4 *>(&vt[st][nt * 32 + l32][16 * mm + 8 * half]));
                 const bf16x8 pbh = __builtin_bit_cast(bf16x8, (u32x4){ph[4 * mm], ph[4 * mm + 1], ph[4 * mm + 2], ph[4 * mm + 3]});
                 const bf16x8 pbl = __builtin_bit_cast(bf16x8, (u32x4){pl[4 * mm], pl[4 * mm + 1], pl[4 * mm + 2], pl[4 * mm + 3]});
                 o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbh, o[nt], 0, 0, 0);
                 o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbl, o[nt], 0, 0, 0);
             }
-        }
-        if (more) {
-#pragma unroll
-            for (int j = 0; j < 8; j++) kf[j] = kn[j];
         }
     }
     // the two halves of a query's scores were summed separately

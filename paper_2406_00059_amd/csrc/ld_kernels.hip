@@ -7,6 +7,7 @@
 #include "ld_gemv.h"
 #include "ld_gemm.h"
 #include "ld_attn_prefill.h"
+#include "ld_attn_decode.h"
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -536,27 +537,33 @@ static int visible_blocks(int max_ctx, int window) {
     const int all = (max_ctx + 15) / 16;
     return window > 0 ? std::min(all, (window + 14) / 16 + 1) : all;
 }
-// Query heads that one workgroup serves: the whole group of a KV head when the group size is 2, 4 or 8.
-static int head_group(int H, int Hkv) {
+// Query heads that one workgroup serves.  mfma: the matrix-core kernel takes the whole group of a KV head
+// (2 .. 16 heads); otherwise the scalar kernel takes it when the group size is 2, 4 or 8.
+static int head_group(int H, int Hkv, bool mfma) {
     const int r = H / Hkv;
+    if (mfma) return r;
     return (r == 2 || r == 4 || r == 8) ? r : 1;
 }
 // Chunk size in KV blocks: small chunks when few (row, head group) pairs exist, so that the launch still
-// has a few thousand workgroups; at most 64 blocks (1024 tokens) per chunk.
-static int attn_chunk_blocks(int T, int H, int Hkv, int max_ctx, int window) {
-    const int64_t blocks = (int64_t)T * (H / head_group(H, Hkv)) * visible_blocks(max_ctx, window);
+// has a few thousand workgroups; at most 64 blocks (1024 tokens) per chunk; a multiple of 4 (one block
+// per wave and round), of 8 for the matrix-core kernel (two blocks per wave and round).
+static int attn_chunk_blocks(int T, int H, int Hkv, int max_ctx, int window, bool mfma) {
+    const int64_t blocks = (int64_t)T * (H / head_group(H, Hkv, mfma)) * visible_blocks(max_ctx, window);
+    const int q = mfma ? 8 : 4;
     int64_t cb = (blocks + 4095) / 4096;
-    cb = (cb + 3) / 4 * 4;
-    return (int)std::min<int64_t>(std::max<int64_t>(cb, 4), 64);
+    cb = (cb + q - 1) / q * q;
+    return (int)std::min<int64_t>(std::max<int64_t>(cb, q), 64);
 }
-static int attn_max_chunks(int T, int H, int Hkv, int max_ctx, int window) {
-    const int cb = attn_chunk_blocks(T, H, Hkv, max_ctx, window);
+static int attn_max_chunks(int T, int H, int Hkv, int max_ctx, int window, bool mfma) {
+    const int cb = attn_chunk_blocks(T, H, Hkv, max_ctx, window, mfma);
     return (visible_blocks(max_ctx, window) + cb - 1) / cb;
 }
 
 size_t ldk_attention_scratch_bytes(int32_t T, int32_t H, int32_t Hkv, int32_t hd, int32_t max_ctx, int32_t window) {
     if (T <= 0 || H <= 0 || Hkv <= 0 || H % Hkv || hd <= 0 || max_ctx <= 0 || window < 0) return 0;
-    return (size_t)T * H * attn_max_chunks(T, H, Hkv, max_ctx, window) * (hd + 2) * sizeof(float);
+    int mc = attn_max_chunks(T, H, Hkv, max_ctx, window, false);     // enough for either kernel
+    if (ld::grouped_decode_supported(1, hd, H, Hkv)) mc = std::max(mc, attn_max_chunks(T, H, Hkv, max_ctx, window, true));
+    return (size_t)T * H * mc * (hd + 2) * sizeof(float);
 }
 
 static ld_status paged_attention_impl(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
@@ -570,13 +577,22 @@ static ld_status paged_attention_impl(const float *q, int32_t q_stride, const vo
         return ld::fail(LD_E_INVAL, "ldk_paged_attention: bad argument");
     if (scratch_bytes < ldk_attention_scratch_bytes(T, H, Hkv, hd, max_ctx, window))
         return ld::fail(LD_E_INVAL, "ldk_paged_attention: scratch too small");
-    const int mc = attn_max_chunks(T, H, Hkv, max_ctx, window), cb = attn_chunk_blocks(T, H, Hkv, max_ctx, window);
-    const int G = head_group(H, Hkv);
+    const bool mfma = ld::grouped_decode_supported(dtype == LD_BF16, hd, H, Hkv);
+    const int mc = attn_max_chunks(T, H, Hkv, max_ctx, window, mfma);
+    const int cb = attn_chunk_blocks(T, H, Hkv, max_ctx, window, mfma);
+    const int G = head_group(H, Hkv, mfma);
     float *part_o = (float *)scratch;
     float *part_ml = part_o + (size_t)T * H * mc * hd;
     const float sl2 = (float)(1.4426950408889634 / std::sqrt((double)hd));
     dim3 grid(mc, H / G, T), block(256);
     hipStream_t s = (hipStream_t)stream;
+    if (mfma) {
+        ld::launch_grouped_decode_partial(q, q_stride, (const uint16_t *)pool_layer, Hkv, table, table_stride, seq_slot,
+                                          ctx_len, T, H, window, mc, cb, part_o, part_ml, s);
+        LD_LAUNCH((k_attn_merge<128>), dim3(H, T), dim3(128), 0, s, part_o, part_ml, ctx_len, H, window, mc, cb, out,
+                  xs_out, T);
+        return launched("k_attn (grouped)");
+    }
 #define LD_ATT_G(HD_, KVT_, G_)                                                                                    \
     LD_LAUNCH((k_attn_partial<HD_, KVT_, G_>), grid, block, 0, s, q, q_stride, (const KVT_ *)pool_layer, Hkv,     \
               table, table_stride, seq_slot, ctx_len, H, window, sl2, mc, cb, part_o, part_ml)

@@ -139,6 +139,13 @@ def _attention_case(seed, lens, H, Hkv, hd, dtype, spare=5):
     return table, pool, q
 
 
+def _attn_tol(dtype, hd, H, Hkv):
+    """Relative tolerance of decode attention: the scalar kernel computes in float32 (2e-6); grouped heads
+    on a bf16 pool with head_dim 128 run on the matrix cores with q and the probabilities split into two
+    bf16 terms, which leaves 2^-17 = 7.6e-6 per operand element (3e-5 with the accumulation)."""
+    return 3e-5 if (dtype == "bf16" and hd == 128 and 2 <= H // Hkv <= 16) else 2e-6
+
+
 def _run_attention(table, pool, q, lens, H, Hkv, hd, window=0):
     B = len(lens)
     ctx = torch.tensor(lens, dtype=torch.int32, device=DEV)
@@ -172,11 +179,11 @@ def test_paged_attention_edge_lengths(dtype, hd, H, Hkv):
     table, pool, q = _attention_case(21, lens, H, Hkv, hd, dtype)
     got = _run_attention(table, pool, q, lens, H, Hkv, hd)
     ref = _oracle_attention(table, pool, q, lens, Hkv, hd)
-    assert np.max(np.abs(got - ref)) <= 2e-6 * np.abs(ref).max() + 1e-6
+    assert np.max(np.abs(got - ref)) <= _attn_tol(dtype, hd, H, Hkv) * np.abs(ref).max() + 1e-6
     # ctx = 1 returns V of the single cached token
     v0 = pool[table[0, 0], 1, :, 0, :].float().cpu().numpy()
     for h in range(H):
-        np.testing.assert_allclose(got[0, h], v0[h // (H // Hkv)], rtol=1e-6, atol=1e-7)
+        np.testing.assert_allclose(got[0, h], v0[h // (H // Hkv)], rtol=1e-5, atol=1e-7)
 
 
 @pytest.mark.parametrize("window", [1, 5, 16, 17, 100, 256, 4096])
@@ -188,12 +195,12 @@ def test_paged_attention_band(dtype, hd, H, Hkv, window):
     table, pool, q = _attention_case(22, lens, H, Hkv, hd, dtype)
     got = _run_attention(table, pool, q, lens, H, Hkv, hd, window=window)
     ref = _oracle_attention(table, pool, q, lens, Hkv, hd, window=window)
-    assert np.max(np.abs(got - ref)) <= 2e-6 * np.abs(ref).max() + 1e-6
+    assert np.max(np.abs(got - ref)) <= _attn_tol(dtype, hd, H, Hkv) * np.abs(ref).max() + 1e-6
     if window == 1:      # the own value
         for b, n in enumerate(lens):
             v = pool[table[b, (n - 1) // 16], 1, :, (n - 1) % 16, :].float().cpu().numpy()
             for h in range(H):
-                np.testing.assert_allclose(got[b, h], v[h // (H // Hkv)], rtol=1e-6, atol=1e-7)
+                np.testing.assert_allclose(got[b, h], v[h // (H // Hkv)], rtol=1e-5, atol=1e-7)
 
 
 def test_paged_attention_grouped_band_serving_shape_sampled():

@@ -335,22 +335,47 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
     }
 }
 
+// Merges the chunk partials of one (row, head): 256 threads = 256/HD thread groups, group g takes the
+// chunks g, g + 256/HD, ...; the chunk maxima and sums go through LDS first so that the loop over the
+// partial outputs has no dependent loads.
 template <int HD>
-__global__ void k_attn_merge(const float *__restrict__ part_o, const float *__restrict__ part_ml,
-                             const int32_t *__restrict__ ctx_len, int H, int window, int max_chunks, int cb,
-                             float *__restrict__ out, bf16_t *__restrict__ xs_out, int T) {
-    const int h = blockIdx.x, t = blockIdx.y, d = threadIdx.x;
+__global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ part_o, const float *__restrict__ part_ml,
+                                                    const int32_t *__restrict__ ctx_len, int H, int window,
+                                                    int max_chunks, int cb, float *__restrict__ out,
+                                                    bf16_t *__restrict__ xs_out, int T) {
+    constexpr int NGRP = 256 / HD, MAXC = 512;   // MAXC: chunks whose statistics fit the LDS cache
+    __shared__ float sm_m[MAXC], sm_l[MAXC], sm_o[NGRP][HD], sm_L[NGRP], sm_red[4];
+    const int h = blockIdx.x, t = blockIdx.y, d = threadIdx.x % HD, grp = threadIdx.x / HD;
     const int ctx = ctx_len[t];
     const int nch = ((ctx + 15) / 16 - (band_first(ctx, window) >> 4) + cb - 1) / cb;
     const int64_t base = ((int64_t)t * H + h) * max_chunks;
-    float M = -INFINITY;
-    for (int c = 0; c < nch; c++) M = fmaxf(M, part_ml[(base + c) * 2]);
-    float o = 0.f, L = 0.f;
-    for (int c = 0; c < nch; c++) {
-        const float a = fast_exp2(part_ml[(base + c) * 2] - M);
-        o += a * part_o[(base + c) * HD + d];
-        L += a * part_ml[(base + c) * 2 + 1];
+    float mx = -INFINITY;
+    for (int c = threadIdx.x; c < nch; c += 256) {
+        const float2 ml = *reinterpret_cast<const float2 *>(part_ml + (base + c) * 2);
+        if (c < MAXC) { sm_m[c] = ml.x; sm_l[c] = ml.y; }
+        mx = fmaxf(mx, ml.x);
     }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, WAVE));
+    if ((threadIdx.x & 63) == 0) sm_red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    const float M = fmaxf(fmaxf(sm_red[0], sm_red[1]), fmaxf(sm_red[2], sm_red[3]));
+    float o = 0.f, L = 0.f;
+#pragma unroll 4
+    for (int c = grp; c < nch; c += NGRP) {
+        const float mc = c < MAXC ? sm_m[c] : part_ml[(base + c) * 2];
+        const float lc = c < MAXC ? sm_l[c] : part_ml[(base + c) * 2 + 1];
+        const float a = fast_exp2(mc - M);
+        o += a * part_o[(base + c) * HD + d];
+        L += a * lc;
+    }
+    sm_o[grp][d] = o;
+    if (d == 0) sm_L[grp] = L;
+    __syncthreads();
+    if (grp != 0) return;
+    o = 0.f; L = 0.f;
+#pragma unroll
+    for (int g = 0; g < NGRP; g++) { o += sm_o[g][d]; L += sm_L[g]; }   // fixed order
     const float r = o / L;
     if (xs_out) {   // operand of the output projection: split (hi, lo) image [2][T][H * HD]
         const bf16_t hi = f32_to_bf16(r);
@@ -545,12 +570,13 @@ static int head_group(int H, int Hkv, bool mfma) {
     return (r == 2 || r == 4 || r == 8) ? r : 1;
 }
 // Chunk size in KV blocks: small chunks when few (row, head group) pairs exist, so that the launch still
-// has a few thousand workgroups; at most 64 blocks (1024 tokens) per chunk; a multiple of 4 (one block
-// per wave and round), of 8 for the matrix-core kernel (two blocks per wave and round).
+// has about two workgroups per CU (measured: a workgroup's fixed cost, table lookup, first loads, merge,
+// makes finer chunks slower); at most 64 blocks (1024 tokens) per chunk; a multiple of 4 (one block per
+// wave and round), of 8 for the matrix-core kernel (two blocks per wave and round).
 static int attn_chunk_blocks(int T, int H, int Hkv, int max_ctx, int window, bool mfma) {
     const int64_t blocks = (int64_t)T * (H / head_group(H, Hkv, mfma)) * visible_blocks(max_ctx, window);
     const int q = mfma ? 8 : 4;
-    int64_t cb = (blocks + 4095) / 4096;
+    int64_t cb = (blocks + 511) / 512;
     cb = (cb + q - 1) / q * q;
     return (int)std::min<int64_t>(std::max<int64_t>(cb, q), 64);
 }
@@ -559,10 +585,22 @@ static int attn_max_chunks(int T, int H, int Hkv, int max_ctx, int window, bool 
     return (visible_blocks(max_ctx, window) + cb - 1) / cb;
 }
 
+// Most chunks any launch with contexts up to max_ctx can use.  The chunk size follows the launch's own
+// longest context, so the chunk count is not monotonic in it: bound it over all shorter contexts.  With nb
+// visible blocks, cb >= T * units * nb / 512 gives nb / cb <= 512 / (T * units) unless cb hit its cap of
+// 64, where the count is nb / 64; and cb >= q gives nb / q.
+static int attn_chunk_bound(int T, int H, int Hkv, int max_ctx, int window, bool mfma) {
+    const int q = mfma ? 8 : 4;
+    const int64_t units = (int64_t)T * (H / head_group(H, Hkv, mfma));
+    const int64_t nb = visible_blocks(max_ctx, window);
+    const int64_t by_target = std::max<int64_t>(512 / units + 1, (nb + 63) / 64), by_min = (nb + q - 1) / q;
+    return (int)std::max<int64_t>(1, std::min(by_target, by_min));
+}
+
 size_t ldk_attention_scratch_bytes(int32_t T, int32_t H, int32_t Hkv, int32_t hd, int32_t max_ctx, int32_t window) {
     if (T <= 0 || H <= 0 || Hkv <= 0 || H % Hkv || hd <= 0 || max_ctx <= 0 || window < 0) return 0;
-    int mc = attn_max_chunks(T, H, Hkv, max_ctx, window, false);     // enough for either kernel
-    if (ld::grouped_decode_supported(1, hd, H, Hkv)) mc = std::max(mc, attn_max_chunks(T, H, Hkv, max_ctx, window, true));
+    int mc = attn_chunk_bound(T, H, Hkv, max_ctx, window, false);     // enough for either kernel
+    if (ld::grouped_decode_supported(1, hd, H, Hkv)) mc = std::max(mc, attn_chunk_bound(T, H, Hkv, max_ctx, window, true));
     return (size_t)T * H * mc * (hd + 2) * sizeof(float);
 }
 
@@ -575,10 +613,10 @@ static ld_status paged_attention_impl(const float *q, int32_t q_stride, const vo
     if (!q || !pool_layer || !table || !seq_slot || !ctx_len || (!out && !xs_out) || !scratch || T < 0 || H <= 0 ||
         Hkv <= 0 || H % Hkv || (hd != 64 && hd != 128) || max_ctx <= 0 || window < 0)
         return ld::fail(LD_E_INVAL, "ldk_paged_attention: bad argument");
-    if (scratch_bytes < ldk_attention_scratch_bytes(T, H, Hkv, hd, max_ctx, window))
-        return ld::fail(LD_E_INVAL, "ldk_paged_attention: scratch too small");
     const bool mfma = ld::grouped_decode_supported(dtype == LD_BF16, hd, H, Hkv);
     const int mc = attn_max_chunks(T, H, Hkv, max_ctx, window, mfma);
+    if (scratch_bytes < (size_t)T * H * mc * (hd + 2) * sizeof(float))
+        return ld::fail(LD_E_INVAL, "ldk_paged_attention: scratch too small");
     const int cb = attn_chunk_blocks(T, H, Hkv, max_ctx, window, mfma);
     const int G = head_group(H, Hkv, mfma);
     float *part_o = (float *)scratch;
@@ -589,7 +627,7 @@ static ld_status paged_attention_impl(const float *q, int32_t q_stride, const vo
     if (mfma) {
         ld::launch_grouped_decode_partial(q, q_stride, (const uint16_t *)pool_layer, Hkv, table, table_stride, seq_slot,
                                           ctx_len, T, H, window, mc, cb, part_o, part_ml, s);
-        LD_LAUNCH((k_attn_merge<128>), dim3(H, T), dim3(128), 0, s, part_o, part_ml, ctx_len, H, window, mc, cb, out,
+        LD_LAUNCH((k_attn_merge<128>), dim3(H, T), dim3(256), 0, s, part_o, part_ml, ctx_len, H, window, mc, cb, out,
                   xs_out, T);
         return launched("k_attn (grouped)");
     }
@@ -602,7 +640,7 @@ static ld_status paged_attention_impl(const float *q, int32_t q_stride, const vo
         else if (G == 4) LD_ATT_G(HD_, KVT_, 4);                                                                  \
         else if (G == 2) LD_ATT_G(HD_, KVT_, 2);                                                                  \
         else LD_ATT_G(HD_, KVT_, 1);                                                                              \
-        LD_LAUNCH((k_attn_merge<HD_>), dim3(H, T), dim3(HD_), 0, s, part_o, part_ml, ctx_len, H, window, mc, cb,  \
+        LD_LAUNCH((k_attn_merge<HD_>), dim3(H, T), dim3(256), 0, s, part_o, part_ml, ctx_len, H, window, mc, cb,  \
                   out, xs_out, T);                                                                                 \
     } while (0)
     if (dtype == LD_BF16 && hd == 128) LD_ATT(128, bf16_t);

@@ -203,6 +203,27 @@ def test_paged_attention_band(dtype, hd, H, Hkv, window):
                 np.testing.assert_allclose(got[b, h], v[h // (H // Hkv)], rtol=1e-5, atol=1e-7)
 
 
+@pytest.mark.parametrize("H,Hkv", [(32, 32), (32, 8)])
+def test_paged_attention_scratch_sized_for_the_cap_serves_every_shorter_context(H, Hkv):
+    """The chunking follows the launch's longest context; scratch sized once for the cap must do for all
+    shorter ones (the chunk count is not monotonic in the context length)."""
+    hd, cap = 128, 16384
+    lens_all = [1, 100, 1030, 2052, 3074, 4103, 5125, 7169, 9220, 13315, 16384]
+    table, pool, q = _attention_case(23, [cap], H, Hkv, hd, "bf16")
+    dpool = device_pool(pool)
+    for T in (1, 3, 8):
+        scratch = torch.empty(ld.ldk_attention_scratch_bytes(T, H, Hkv, hd, cap, 0), dtype=torch.uint8, device=DEV)
+        qq = q.expand(T, H, hd).contiguous()
+        slot = torch.zeros(T, dtype=torch.int32, device=DEV)
+        out = torch.empty(T, H, hd, device=DEV)
+        for n in lens_all:
+            ctx = torch.full((T,), n, dtype=torch.int32, device=DEV)
+            ld.ldk_paged_attention(qq, H * hd, dpool, table.to(DEV), slot, ctx, n, H, Hkv, hd, out, scratch)
+        torch.cuda.synchronize()
+        ref = _oracle_attention(table, pool, q, [lens_all[-1]], Hkv, hd)
+        assert np.max(np.abs(out[0].cpu().numpy() - ref[0])) <= 3e-5 * np.abs(ref).max() + 1e-6
+
+
 def test_paged_attention_grouped_band_serving_shape_sampled():
     """Batch 32, 32 query heads on 8 KV heads, contexts uniform in [512, 8192], band of 4096 positions:
     sampled rows (the longest, the shortest, one just over the band) against the oracle."""

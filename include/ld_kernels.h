@@ -98,10 +98,16 @@ ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool
  * tiles: DEVICE int32[n_tiles][4] = (first row, number of rows (1..128), position of the first row,
  * block-table row of the sequence); a segment longer than 128 rows is given as several tiles.
  * q and out as in ldk_paged_attention.  Supported: dtype LD_BF16 with hd = 128 (LD_E_INVAL otherwise;
- * such shapes run their prefill rows through ldk_paged_attention with ctx_len = position + 1). */
+ * such shapes run their prefill rows through ldk_paged_attention with ctx_len = position + 1).
+ * max_pos (HOST value) >= the position of every row.  When few tiles face a long context the KV range of
+ * a tile is split over several workgroups whose partial results go through scratch (DEVICE, up to
+ * ldk_prefill_attention_scratch_bytes() bytes are used) and are merged in split order; scratch == NULL or a
+ * smaller buffer only limits the split, never the result. */
+size_t ldk_prefill_attention_scratch_bytes(void);
 ld_status ldk_prefill_attention(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
                                 const int32_t *table, int32_t table_stride, const int32_t *tiles, int32_t n_tiles,
-                                int32_t H, int32_t Hkv, int32_t hd, int32_t window, float *out, void *stream);
+                                int32_t H, int32_t Hkv, int32_t hd, int32_t window, int32_t max_pos, float *out,
+                                void *scratch, size_t scratch_bytes, void *stream);
 
 /* out[r] = smallest index of the maximum of logits[r, 0..V). */
 ld_status ldk_argmax(const float *logits, int32_t R, int32_t V, int32_t *out, void *stream);

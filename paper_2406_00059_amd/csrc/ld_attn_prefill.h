@@ -11,8 +11,11 @@ bool prefill_attention_supported(int dtype_is_bf16, int hd);
 // tiles: DEVICE int32[n_tiles][4] = (first row, rows <= 128, position of the first row, block-table row).
 // q rows at q + row * q_stride (+ head * 128); out dense [rows, H, 128].
 // window > 0: a row at position p sees positions max(0, p - window + 1) .. p; 0: positions 0 .. p.
+// max_pos (HOST): largest position of any row, sizes the KV split.  scratch (may be null: no split): up to
+// prefill_attention_scratch_bytes() bytes for the partial results of split tiles.
+size_t prefill_attention_scratch_bytes();
 void launch_prefill_attention(const float *q, int q_stride, const uint16_t *pool, int Hkv, const int32_t *table,
-                              int table_stride, const int32_t *tiles, int n_tiles, int H, int window, float *out,
-                              hipStream_t s);
+                              int table_stride, const int32_t *tiles, int n_tiles, int H, int window, int max_pos,
+                              float *out, void *scratch, size_t scratch_bytes, hipStream_t s);
 
 }  // namespace ld

@@ -27,6 +27,11 @@
 // that the 8 accumulator registers a lane feeds into one value MFMA are 8 CONSECUTIVE positions, i.e. one
 // 16-byte piece of the transposed value tile.
 // Scores are kept in the log2 domain (q is pre-multiplied by log2(e)/sqrt(hd)); m, l and O are float32.
+//
+// Few tiles with long contexts (an observation appended to one long sequence) would leave most CUs idle
+// and make every workgroup walk the whole context, so the KV range of a tile can be split over gridDim.z
+// workgroups; each then writes its unnormalised output with its maximum and sum, and a merge kernel
+// combines the splits in fixed order.
 #include "ld_attn_prefill.h"
 #include "ld_device.h"
 #include "ld_internal.h"
@@ -50,7 +55,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
                                                          const bf16_t *__restrict__ pool, int Hkv,
                                                          const int32_t *__restrict__ table, int table_stride,
                                                          const int4 *__restrict__ tiles, int H, int window,
-                                                         float scale_log2e, float *__restrict__ out) {
+                                                         float scale_log2e, float *__restrict__ out,
+                                                         float *__restrict__ part_o, float *__restrict__ part_ml) {
     __shared__ __attribute__((aligned(16))) bf16_t ks[2][KVB][KLD];
     __shared__ __attribute__((aligned(16))) bf16_t vt[2][HD][VLD];
     const int4 tile = tiles[blockIdx.x];      // x: first row, y: rows (<= 128), z: position of first row, w: seq slot
@@ -120,16 +126,21 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
             *reinterpret_cast<u32x4 *>(&vt[st][vd][16 * v + vh]) = vreg[v];
         }
     };
-    load_step(kv_start);
+    // this workgroup's share of the tile's steps (all of them when the grid has one split)
+    const int n_splits = gridDim.z, split = blockIdx.z;
+    const int n_steps = (wg_last_pos - kv_start) / KVB + 1, per = (n_steps + n_splits - 1) / n_splits;
+    const int kv_begin = kv_start + split * per * KVB;
+    const int kv_end = min(kv_begin + per * KVB, wg_last_pos + 1);      // exclusive; may be <= kv_begin (empty share)
+    if (kv_begin < kv_end) load_step(kv_begin);
 
     int st = 0;
-    for (int kv0 = kv_start; kv0 <= wg_last_pos; kv0 += KVB, st ^= 1) {
+    for (int kv0 = kv_begin; kv0 < kv_end; kv0 += KVB, st ^= 1) {
         // Stage this step, then fetch the next one.  One barrier per step: a wave that writes buffer st for
         // step n has passed the barrier of step n-1, which every wave reaches only after it has finished
         // reading buffer st for step n-2.
         stage(st);
         lds_barrier();
-        if (kv0 + KVB <= wg_last_pos) load_step(kv0 + KVB);
+        if (kv0 + KVB < kv_end) load_step(kv0 + KVB);
         if (!wave_active || kv0 > wave_last_pos || kv0 + KVB <= wave_low) continue;   // nothing visible to this wave
 
         // ---- S^T = K Q^T for 32 kv positions x 32 queries; tile row l32 is position kv0 + tau(l32)
@@ -194,6 +205,20 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
     }
     // the two halves of a query's scores were summed separately
     l += __shfl_xor(l, 32, WAVE);
+    if (n_splits > 1) {      // unnormalised share: [tile][row in tile][head][split][HD] and (m, l)
+        if (q_valid) {
+            const int64_t item = (((int64_t)blockIdx.x * 128 + qi) * H + h) * n_splits + split;
+            float *op = part_o + item * HD;
+#pragma unroll
+            for (int nt = 0; nt < 4; nt++)
+#pragma unroll
+                for (int a = 0; a < 4; a++)
+                    *reinterpret_cast<float4 *>(op + nt * 32 + 8 * a + 4 * half) =
+                        make_float4(o[nt][4 * a], o[nt][4 * a + 1], o[nt][4 * a + 2], o[nt][4 * a + 3]);
+            if (half == 0) { part_ml[item * 2] = m; part_ml[item * 2 + 1] = l; }
+        }
+        return;
+    }
     if (q_valid) {
         const float inv = 1.0f / l;
         float *op = out + (int64_t)(tile.x + qi) * (H * HD) + h * HD;
@@ -208,18 +233,62 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
     }
 }
 
+// One workgroup per (tile row slot, head): adds the splits of a row in split order.  A split that saw no
+// visible position of the row has m = -inf and weight 0; split 0 or a later one always saw one.
+__global__ __launch_bounds__(128) void k_attn_prefill_merge(const int4 *__restrict__ tiles, int H, int n_splits,
+                                                            const float *__restrict__ part_o,
+                                                            const float *__restrict__ part_ml,
+                                                            float *__restrict__ out) {
+    const int4 tile = tiles[blockIdx.y >> 7];
+    const int r = blockIdx.y & 127, h = blockIdx.x, d = threadIdx.x;
+    if (r >= tile.y) return;
+    const int64_t base = ((int64_t)blockIdx.y * H + h) * n_splits;
+    float M = -INFINITY;
+    for (int z = 0; z < n_splits; z++) M = fmaxf(M, part_ml[(base + z) * 2]);
+    float o = 0.f, L = 0.f;
+    for (int z = 0; z < n_splits; z++) {
+        const float a = fast_exp2(part_ml[(base + z) * 2] - M);
+        o += a * part_o[(base + z) * HD + d];
+        L += a * part_ml[(base + z) * 2 + 1];
+    }
+    out[((int64_t)(tile.x + r) * H + h) * HD + d] = o / L;
+}
+
 }  // namespace
 
 namespace ld {
 
 bool prefill_attention_supported(int dtype_is_bf16, int hd) { return dtype_is_bf16 && hd == HD; }
 
+// Splits of the KV range per tile: enough to give the launch about two workgroups per CU, at least 8 steps
+// (256 positions) each, at most 8, and only as many as the scratch holds.
+int prefill_attention_splits(int n_tiles, int H, int max_pos, int window, size_t scratch_bytes) {
+    const int span = window > 0 ? std::min(max_pos + 1, window + 128) : max_pos + 1;   // positions a tile walks
+    int s = 512 / std::max(1, n_tiles * H);
+    s = std::min(s, (span / KVB) / 8);
+    s = std::min(s, 8);
+    const size_t per_split = (size_t)n_tiles * 128 * H * (HD + 2) * sizeof(float);
+    if (per_split) s = (int)std::min<size_t>(s, scratch_bytes / per_split);
+    return std::max(s, 1);
+}
+
+size_t prefill_attention_scratch_bytes() {
+    // splits > 1 only while n_tiles * H * splits <= 512; 128 rows per tile
+    return (size_t)512 * 128 * (HD + 2) * sizeof(float);
+}
+
 void launch_prefill_attention(const float *q, int q_stride, const uint16_t *pool, int Hkv, const int32_t *table,
-                              int table_stride, const int32_t *tiles, int n_tiles, int H, int window, float *out,
-                              hipStream_t s) {
+                              int table_stride, const int32_t *tiles, int n_tiles, int H, int window, int max_pos,
+                              float *out, void *scratch, size_t scratch_bytes, hipStream_t s) {
     const float sl2 = 1.4426950408889634f / sqrtf((float)HD);
-    LD_LAUNCH(k_attn_prefill, dim3(n_tiles, H), dim3(256), 0, s, q, q_stride, pool, Hkv, table, table_stride,
-                       (const int4 *)tiles, H, window, sl2, out);
+    const int ns = scratch ? prefill_attention_splits(n_tiles, H, max_pos, window, scratch_bytes) : 1;
+    float *part_o = (float *)scratch;
+    float *part_ml = part_o ? part_o + (size_t)n_tiles * 128 * H * ns * HD : nullptr;
+    LD_LAUNCH(k_attn_prefill, dim3(n_tiles, H, ns), dim3(256), 0, s, q, q_stride, pool, Hkv, table, table_stride,
+              (const int4 *)tiles, H, window, sl2, out, part_o, part_ml);
+    if (ns > 1)
+        LD_LAUNCH(k_attn_prefill_merge, dim3(H, n_tiles * 128), dim3(128), 0, s, (const int4 *)tiles, H, ns, part_o,
+                  part_ml, out);
 }
 
 }  // namespace ld

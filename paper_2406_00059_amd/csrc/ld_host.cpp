@@ -87,6 +87,8 @@ Workspace plan_workspace(const ld_model &m, char *base, int max_tokens, int max_
         w.att_scratch_bytes = std::max(w.att_scratch_bytes,
                                        ldk_attention_scratch_bytes(t, c.n_heads, c.n_kv_heads, c.head_dim,
                                                                    max_blocks * c.kv_block, c.window));
+    if (c.dtype == LD_BF16 && c.head_dim == 128 && max_tokens > 1)   // split partials of chunk-prefill attention
+        w.att_scratch_bytes = std::max(w.att_scratch_bytes, ldk_prefill_attention_scratch_bytes());
     w.att_scratch = take(w.att_scratch_bytes);
     w.lin_scratch_bytes = 0;   // the split-K factor depends on the row count: size for the worst one
     for (int t = 2; t <= max_tokens; t++) {
@@ -300,7 +302,8 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const 
                                                             w.att_scratch, w.att_scratch_bytes, st));
         if (n_tiles)
             LD_TIMED(LD_PROF_ATTENTION, ldk_prefill_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_tiles,
-                                                              n_tiles, H, Hkv, hd, c.window, w.attn, st));
+                                                              n_tiles, H, Hkv, hd, c.window, max_ctx - 1, w.attn,
+                                                              w.att_scratch, w.att_scratch_bytes, st));
         LD_TIMED(LD_PROF_WO, ldk_linear(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st));
         LD_TIMED(LD_PROF_GATE_UP, ldk_linear(m.wgate_up[l], c.dtype, w.x, m.ffn_norm[l], c.rms_eps, T, c.d_ffn, d, LDK_SWIGLU, w.act, w.lin_scratch,
                                                w.lin_scratch_bytes, st));

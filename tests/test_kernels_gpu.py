@@ -376,14 +376,16 @@ def test_linear_matrix_core_7b_shapes_sampled():
                     assert abs(yh[t, n] - a) <= 1e-4 * max(1.0, abs(a)), (T, N, t, n, yh[t, n], a)
 
 
+@pytest.mark.parametrize("split", [False, True], ids=["whole", "kv-split"])
 @pytest.mark.parametrize("window", [0, 1, 40, 128, 200, 5000])
 @pytest.mark.parametrize("H,Hkv", [(4, 4), (8, 2)])
-def test_prefill_attention_segments(H, Hkv, window):
+def test_prefill_attention_segments(H, Hkv, window, split):
     """Chunk-prefill attention (matrix cores): segments of different sequences, a fresh prompt (position 0),
     an observation appended to a long context, a segment longer than one 128-row tile; causal inside
     the chunk; permuted block table; with and without an attention band (shorter than a wave's 32 rows,
     shorter and longer than a tile, longer than every context).  Every row against the oracle's
-    single-query attention."""
+    single-query attention.  With scratch the KV range of a tile is split over several workgroups and merged
+    (some shares are empty or wholly masked for some rows); without it every tile walks its whole range."""
     hd = 128
     segs = [(37, 100), (0, 5), (1000, 300), (255, 1), (16, 32)]          # (first position, rows) per sequence
     lens = [p + n for p, n in segs]
@@ -396,8 +398,9 @@ def test_prefill_attention_segments(H, Hkv, window):
             tiles.append([r + off, min(128, n - off), p0 + off, s])
         row_seq += [s] * n; row_pos += list(range(p0, p0 + n)); r += n
     out = torch.zeros(T, H, hd, device=DEV)
+    scratch = torch.empty(ld.ldk_prefill_attention_scratch_bytes(), dtype=torch.uint8, device=DEV) if split else None
     ld.ldk_prefill_attention(q, H * hd, device_pool(pool), table.to(DEV), torch.tensor(tiles, dtype=torch.int32, device=DEV),
-                             H, Hkv, hd, out, window=window)
+                             H, Hkv, hd, out, max(row_pos), window=window, scratch=scratch)
     torch.cuda.synchronize()
     got = out.cpu().numpy()
     ph = oracle.to_host_matrix(pool.reshape(pool.shape[0], -1)).reshape(-1)

@@ -66,6 +66,9 @@ def lib():
         L.orc_prefill.restype = C.c_int32; L.orc_prefill.argtypes = [vp, C.c_int32, ip, C.c_int64, dp, ip]
         L.orc_decode.restype = C.c_int32; L.orc_decode.argtypes = [vp, C.c_int32, dp, ip]
         L.orc_seq_stop.restype = C.c_int32; L.orc_seq_stop.argtypes = [vp, C.c_int32]
+        L.orc_kv_swap_doubles.restype = C.c_int64; L.orc_kv_swap_doubles.argtypes = [vp, C.c_int32]
+        L.orc_kv_swap_out.restype = C.c_int32; L.orc_kv_swap_out.argtypes = [vp, C.c_int32, dp]
+        L.orc_kv_swap_in.restype = C.c_int32; L.orc_kv_swap_in.argtypes = [vp, C.c_int32, dp]
         _lib = L
     return _lib
 
@@ -255,6 +258,18 @@ class KV:
 
     def stop(self, seq):
         return lib().orc_seq_stop(self.h, seq)
+
+    def swap_out(self, seq):
+        """-> (rc, store): the sequence's keys/values as a float64 array, its blocks back on the free list."""
+        n = lib().orc_kv_swap_doubles(self.h, seq)
+        if n < 0:
+            return E_INVAL, None
+        store = np.empty(max(n, 1), dtype=np.float64)
+        rc = lib().orc_kv_swap_out(self.h, seq, _dp(store))
+        return rc, store
+
+    def swap_in(self, seq, store):
+        return lib().orc_kv_swap_in(self.h, seq, _dp(np.ascontiguousarray(store, dtype=np.float64)))
 
     def __del__(self):
         if getattr(self, "h", None):

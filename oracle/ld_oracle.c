@@ -372,6 +372,7 @@ typedef struct {
     int64_t n_cached;
     int32_t n_mapped;
     int32_t *table;
+    int swapped;      /* keys/values live outside the pool; no block is held */
 } orc_seq;
 
 typedef struct {
@@ -440,7 +441,7 @@ int32_t orc_kv_alloc(orc_kv *kv, int64_t reserve_tokens, int32_t *out)
     q->n_mapped = 0;
     int rc = ensure_blocks(kv, q, (reserve_tokens + bs - 1) / bs);
     if (rc) return rc;
-    q->active = 1; q->stopped = 0; q->has_pending = 0; q->pending = -1; q->n_cached = 0;
+    q->active = 1; q->stopped = 0; q->has_pending = 0; q->pending = -1; q->n_cached = 0; q->swapped = 0;
     *out = s;
     return ORC_OK;
 }
@@ -467,7 +468,7 @@ int32_t orc_kv_free(orc_kv *kv, int32_t s)
     if (!q) return ORC_E_INVAL;
     for (int i = kv->max_blocks_per_seq - 1; i >= 0; i--)
         if (q->table[i] >= 0) { kv->free_stack[kv->n_free++] = q->table[i]; q->table[i] = -1; }
-    q->active = 0; q->n_mapped = 0;
+    q->active = 0; q->n_mapped = 0; q->swapped = 0;
     return ORC_OK;
 }
 
@@ -491,6 +492,7 @@ int32_t orc_kv_inject(orc_kv *kv, int32_t s, const double *kvdata, int64_t n, in
     orc_seq *q = get_seq(kv, s);
     const orc_config *c = &kv->m->c;
     if (!q || n < 0) return ORC_E_INVAL;
+    if (q->swapped) return ORC_E_STATE;
     int rc = ensure_blocks(kv, q, (q->n_cached + n + c->kv_block - 1) / c->kv_block);
     if (rc) return rc;
     kv_view v = {0};
@@ -513,9 +515,69 @@ int32_t orc_kv_read(orc_kv *kv, int32_t s, int32_t layer, int32_t which, int32_t
     orc_seq *q = get_seq(kv, s);
     const orc_config *c = &kv->m->c;
     if (!q || pos < 0 || pos >= q->n_cached) return ORC_E_INVAL;
+    if (q->swapped) return ORC_E_STATE;
     kv_view v = {0};
     v.paged = 1; v.pool = kv->pool; v.n_blocks = kv->n_blocks; v.table = q->table;
     memcpy(out, kv_row(c, &v, layer, which, kvh, pos), sizeof(double) * c->head_dim);
+    return ORC_OK;
+}
+
+/* KV retention across a tool call (section 2.2 describes systems that keep, swap to host memory or
+ * discard the cache of a request that waits for a tool): swapping a sequence out moves the keys and values of its cached
+ * positions from the pool into `store` and returns every block it holds to the free list in the order
+ * orc_kv_free uses; the token state (length, pending token) stays.  Swapping in takes blocks for the
+ * cached length in the order a reservation would and copies the contents back.  While swapped out the
+ * sequence cannot be stepped.  store: [logical block][layer][2][kv_head][slot][hd] doubles,
+ * orc_kv_swap_doubles() of them. */
+static int64_t seq_token_blocks(const orc_kv *kv, const orc_seq *q)
+{
+    int bs = kv->m->c.kv_block;
+    return (q->n_cached + bs - 1) / bs;
+}
+static size_t block_doubles(const orc_kv *kv)
+{
+    const orc_config *c = &kv->m->c;
+    return (size_t)2 * c->n_kv_heads * c->kv_block * c->head_dim;
+}
+int64_t orc_kv_swap_doubles(orc_kv *kv, int32_t s)
+{
+    orc_seq *q = get_seq(kv, s);
+    if (!q) return -1;
+    return seq_token_blocks(kv, q) * kv->m->c.n_layers * (int64_t)block_doubles(kv);
+}
+int32_t orc_kv_swap_out(orc_kv *kv, int32_t s, double *store)
+{
+    orc_seq *q = get_seq(kv, s);
+    if (!q || !store) return ORC_E_INVAL;
+    if (q->swapped) return ORC_E_STATE;
+    size_t per = block_doubles(kv);
+    int L = kv->m->c.n_layers;
+    int64_t nb = seq_token_blocks(kv, q);
+    for (int64_t j = 0; j < nb; j++)
+        for (int l = 0; l < L; l++)
+            memcpy(store + (j * L + l) * per, kv->pool + ((size_t)l * kv->n_blocks + q->table[j]) * per,
+                   sizeof(double) * per);
+    for (int i = kv->max_blocks_per_seq - 1; i >= 0; i--)
+        if (q->table[i] >= 0) { kv->free_stack[kv->n_free++] = q->table[i]; q->table[i] = -1; }
+    q->n_mapped = 0;
+    q->swapped = 1;
+    return ORC_OK;
+}
+int32_t orc_kv_swap_in(orc_kv *kv, int32_t s, const double *store)
+{
+    orc_seq *q = get_seq(kv, s);
+    if (!q || !store) return ORC_E_INVAL;
+    if (!q->swapped) return ORC_E_STATE;
+    int64_t nb = seq_token_blocks(kv, q);
+    int rc = ensure_blocks(kv, q, nb);
+    if (rc) return rc;
+    size_t per = block_doubles(kv);
+    int L = kv->m->c.n_layers;
+    for (int64_t j = 0; j < nb; j++)
+        for (int l = 0; l < L; l++)
+            memcpy(kv->pool + ((size_t)l * kv->n_blocks + q->table[j]) * per, store + (j * L + l) * per,
+                   sizeof(double) * per);
+    q->swapped = 0;
     return ORC_OK;
 }
 
@@ -540,7 +602,7 @@ int32_t orc_prefill(orc_kv *kv, int32_t s, const int32_t *tokens, int64_t n, dou
 {
     orc_seq *q = get_seq(kv, s);
     if (!q || n < 0 || (n == 0 && !q->has_pending)) return ORC_E_INVAL;
-    if (q->stopped) return ORC_E_STATE;
+    if (q->stopped || q->swapped) return ORC_E_STATE;
     int64_t tot = n + (q->has_pending ? 1 : 0);
     int32_t *all = malloc(sizeof(int32_t) * tot);
     int64_t k = 0;
@@ -562,7 +624,7 @@ int32_t orc_decode(orc_kv *kv, int32_t s, double *logits_out, int32_t *next)
 {
     orc_seq *q = get_seq(kv, s);
     if (!q) return ORC_E_INVAL;
-    if (q->stopped || !q->has_pending) return ORC_E_STATE;
+    if (q->stopped || q->swapped || !q->has_pending) return ORC_E_STATE;
     return orc_prefill(kv, s, NULL, 0, logits_out, next);
 }
 

@@ -418,6 +418,44 @@ def test_paged_equals_contiguous_and_rounds_follow_the_concatenation(tiny_weight
     assert kv.prefill(s2, np.array([shape.vocab], np.int32))[0] == oracle.E_RANGE
 
 
+def test_swap_out_and_in_keeps_the_sequence_and_follows_the_allocator(tiny_weights):
+    """KV retention (section 2.2): a sequence swapped out and back continues bit-identically to a twin that
+    stayed in the pool, also when its blocks were taken by another sequence meanwhile (so it comes back on
+    different physical blocks); the store holds exactly the rows the cache held; blocks return to the free
+    list in the order a free would return them; a swapped-out sequence cannot be stepped; a swap-in without
+    enough free blocks fails and changes nothing."""
+    shape, w = tiny_weights
+    m = oracle.Model(shape, w)
+    tok = _prompt(37, shape.vocab, 105)
+    kv, twin = oracle.KV(m, 8, 3, 6), oracle.KV(m, 8, 3, 6)
+    (_, s), (_, s2) = kv.alloc(0), twin.alloc(0)
+    for k in (kv, twin):
+        assert k.prefill(0, tok)[0] == 0
+        for _ in range(2):
+            assert k.decode(0)[0] == 0
+    assert kv.block_table(s)[1].tolist() == [0, 1, 2] and kv.free_blocks() == 5
+    rows = {(l, wh, h, p): kv.read(s, l, wh, h, p)[1] for l in (0, 1) for wh in (0, 1) for h in (0, 3) for p in (0, 15, 16, 38)}
+    rc, store = kv.swap_out(s)
+    assert rc == 0 and kv.free_blocks() == 8 and kv.length(s) == 39 and kv.block_table(s)[1].tolist() == []
+    st = store.reshape(3, shape.n_layers, 2, shape.n_kv_heads, 16, shape.head_dim)
+    for (l, wh, h, p), row in rows.items():
+        np.testing.assert_array_equal(st[p // 16, l, wh, h, p % 16], row)
+    assert kv.decode(s)[0] == oracle.E_STATE and kv.prefill(s, tok[:2])[0] == oracle.E_STATE
+    assert kv.swap_out(s)[0] == oracle.E_STATE
+    # the freed blocks come back in logical order to the next taker
+    rc, other = kv.alloc(6 * 16)
+    assert kv.block_table(other)[1].tolist() == [0, 1, 2, 3, 4, 5] and kv.free_blocks() == 2
+    assert kv.swap_in(s, store) == oracle.E_NOMEM and kv.free_blocks() == 2 and kv.decode(s)[0] == oracle.E_STATE
+    kv.free(other)
+    rc, filler = kv.alloc(2 * 16)                      # takes blocks 0, 1: the sequence returns on 2, 3, 4
+    assert kv.swap_in(s, store) == 0 and kv.block_table(s)[1].tolist() == [2, 3, 4]
+    assert kv.swap_in(s, store) == oracle.E_STATE
+    for _ in range(12):                                # crosses into a new block on both sides
+        (rc_a, t_a, lg_a), (rc_b, t_b, lg_b) = kv.decode(s), twin.decode(s2)
+        assert rc_a == rc_b == 0 and t_a == t_b
+        np.testing.assert_array_equal(lg_a, lg_b)
+
+
 def test_wo_and_wdown_zero_make_every_layer_the_identity(tiny_weights):
     shape, w = tiny_weights
     w0 = dict(w)

@@ -125,6 +125,22 @@ ld_status ld_kv_block_table(const ld_kv *kv, ld_seq seq, int32_t *out, int32_t c
 /* Number of cached tokens of a sequence (-1 for a bad handle); number of free blocks. */
 int64_t ld_kv_len(const ld_kv *kv, ld_seq seq);
 int64_t ld_kv_free_blocks(const ld_kv *kv);
+/* KV retention across a tool call (section 2.2: a request that waits for a tool can keep its cache
+ * on the GPU, swap it to host memory, or discard it and prefill again).  Discarding is ld_kv_free
+ * followed by a prefill of the token history; swapping is this pair.
+ * ld_kv_swap_out copies the keys and values of the sequence's cached positions to HOST memory
+ * (ld_kv_swap_bytes(kv, seq) bytes, layout [logical block][layer][block bytes]; pinned memory makes the
+ * copy asynchronous) and returns every block the sequence holds to the free list in the order
+ * ld_kv_free uses.  The handle, the token count and the pending token stay; until ld_kv_swap_in the
+ * sequence cannot be stepped, mapped or extended (LD_E_STATE).  ld_kv_swap_in takes blocks for the
+ * cached length as a reservation would (LD_E_NOMEM, nothing changed, if there are too few) and copies
+ * the contents back.  Both calls only enqueue copies on `stream`: the host buffer holds the data once
+ * the stream has passed them, must stay untouched until the swap-in's copies are done, and freed
+ * blocks must not be written by work on OTHER streams before the swap-out's copies are done. */
+size_t ld_kv_swap_bytes(const ld_kv *kv, ld_seq seq);
+ld_status ld_kv_swap_out(ld_kv *kv, ld_seq seq, void *host_buf, size_t bytes, void *stream);
+ld_status ld_kv_swap_in(ld_kv *kv, ld_seq seq, const void *host_buf, size_t bytes, void *stream);
+
 /* Test / benchmark hook: declare that the next n_tokens positions of a sequence are already
  * cached (their blocks are mapped; the caller has written, or will write, their keys and values
  * straight into the pool using the layout above), and set the pending token (none if < 0). */

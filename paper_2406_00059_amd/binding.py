@@ -19,7 +19,7 @@ __all__ = [
     "LDK_STORE", "LDK_ADD", "LDK_SWIGLU", "LIB_PATH", "lib", "LdError", "ld_model_config", "ld_weights",
     "ld_token_cb", "ld_model_create", "ld_model_destroy", "ld_kv_bytes", "ld_workspace_bytes", "ld_kv_create",
     "ld_kv_destroy", "ld_kv_alloc", "ld_kv_map", "ld_kv_free", "ld_kv_block_table", "ld_kv_len",
-    "ld_kv_free_blocks", "ld_kv_assume", "ld_prefill", "ld_decode_step", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
+    "ld_kv_free_blocks", "ld_kv_assume", "ld_kv_swap_bytes", "ld_kv_swap_out", "ld_kv_swap_in", "ld_prefill", "ld_decode_step", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
     "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
     "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_prefill_attention_scratch_bytes",
     "ldk_prefill_attention", "ldk_argmax", "Model", "KV",
@@ -72,6 +72,9 @@ _SIGS = {
     "ld_kv_len": (C.c_int64, [_vp, C.c_int32]),
     "ld_kv_free_blocks": (C.c_int64, [_vp]),
     "ld_kv_assume": (C.c_int, [_vp, C.c_int32, C.c_int64, C.c_int32]),
+    "ld_kv_swap_bytes": (C.c_size_t, [_vp, C.c_int32]),
+    "ld_kv_swap_out": (C.c_int, [_vp, C.c_int32, _vp, C.c_size_t, _vp]),
+    "ld_kv_swap_in": (C.c_int, [_vp, C.c_int32, _vp, C.c_size_t, _vp]),
     "ld_prefill": (C.c_int, [_vp, C.c_int32, _i32p, C.c_int32, _vp, ld_token_cb, _vp, _f32p]),
     "ld_decode_step": (C.c_int, [_vp, _i32p, C.c_int32, _vp, ld_token_cb, _vp, _f32p]),
     "ld_step_mixed": (C.c_int, [_vp, _i32p, C.c_int32, _i32p, C.POINTER(_i32p), _i32p, C.c_int32, _vp,
@@ -210,6 +213,19 @@ def ld_kv_free_blocks(kv):
 
 def ld_kv_assume(kv, seq, n_tokens, pending=-1, check=True):
     return _check(lib().ld_kv_assume(kv, seq, n_tokens, pending), check)
+
+
+def ld_kv_swap_bytes(kv, seq):
+    return lib().ld_kv_swap_bytes(kv, seq)
+
+
+def ld_kv_swap_out(kv, seq, host_buf, stream=None, check=True):
+    """host_buf: a CPU uint8 tensor (pinned for an asynchronous copy) of at least ld_kv_swap_bytes bytes."""
+    return _check(lib().ld_kv_swap_out(kv, seq, _ptr(host_buf), _nbytes(host_buf), _stream(stream)), check)
+
+
+def ld_kv_swap_in(kv, seq, host_buf, stream=None, check=True):
+    return _check(lib().ld_kv_swap_in(kv, seq, _ptr(host_buf), _nbytes(host_buf), _stream(stream)), check)
 
 
 def _cb(callback):

@@ -8,6 +8,10 @@ its plugin says it can start (tool partial execution), polls the running tools e
 a tool's observation into the sequence when it is available.  With `partial=False` the same code is the
 baseline of section 4.1: a tool starts only when its round has been decoded to the end.
 
+While a request waits for its tool, its KV cache can stay on the GPU, be swapped to host memory, or be
+discarded and recomputed (the options section 2.2 describes for systems that manage the cache across tool
+calls); `retention` selects one, or lets `choose_retention` pick by the predicted tool time.
+
 Everything here is host logic: no GPU work happens in this file, the engine does it.  Tools run in forked
 child processes with a duplex pipe (section 3.3 steps (6), (7)); the children never touch the GPU.
 """
@@ -136,15 +140,37 @@ class Request:
     g: list = field(default_factory=list)             # generation seconds per round (prefill + decode)
     t: list = field(default_factory=list)             # tool seconds per round (as measured in the child)
     s: list = field(default_factory=list)             # seconds into the round at which the tool was started
+    retained: list = field(default_factory=list)      # per tool wait: "keep" | "swap" | "discard" | None (no wait)
     latency: float = 0.0
+
+
+def choose_retention(ctx_tokens, tool_s, kv_bytes_per_token, swap_bytes_per_s, prefill_tokens_per_s):
+    """What to do with the cache of a request that is about to wait `tool_s` seconds for its tool, by the
+    GPU memory it wastes (bytes x seconds held without being read), as in the systems section 2.2 cites:
+      keep:    M * tool_s                                  M = ctx_tokens * kv_bytes_per_token
+      swap:    M * (2 M / swap_bytes_per_s)               held during the copy out and the copy back;
+                                                          only if the copy out fits into the wait
+      discard: M * (ctx_tokens / prefill_tokens_per_s)    held while it is being recomputed
+    The smallest wins; ties go to the earlier entry."""
+    M = ctx_tokens * kv_bytes_per_token
+    t_copy = M / swap_bytes_per_s
+    cost = {"keep": M * tool_s, "discard": M * (ctx_tokens / prefill_tokens_per_s)}
+    if t_copy <= tool_s:
+        cost["swap"] = M * 2 * t_copy
+    order = ["keep", "swap", "discard"]
+    return min((k for k in order if k in cost), key=lambda k: (cost[k], order.index(k)))
 
 
 class Scheduler:
     """Token-granularity scheduler (section 3.3).  `engine` provides
          new_sequence() -> seq, prefill(seq, tokens) -> token, decode(seqs) -> tokens, free(seq)."""
 
-    def __init__(self, engine, partial=True):
-        self.engine, self.partial = engine, partial
+    def __init__(self, engine, partial=True, retention="keep", predict_tool_s=None, rates=None):
+        """retention: "keep" | "swap" | "discard" | "auto".  "auto" asks choose_retention with
+        predict_tool_s(plugin) seconds and rates = dict(kv_bytes_per_token, swap_bytes_per_s,
+        prefill_tokens_per_s).  "swap" needs engine.swap_out / engine.swap_in."""
+        self.engine, self.partial, self.retention = engine, partial, retention
+        self.predict_tool_s, self.rates = predict_tool_s, rates or {}
 
     def serve(self, requests):
         eng = self.engine
@@ -152,7 +178,8 @@ class Scheduler:
         st = []
         for r in requests:
             st.append(dict(req=r, seq=eng.new_sequence(), round=0, left=0, parser=None, tool=None, obs=None,
-                           feed=list(r.prompt), round_t0=t_start, t_start=t_start, done=False))
+                           feed=list(r.prompt), round_t0=t_start, t_start=t_start, done=False,
+                           history=[], away=None, plugin=None))
         while not all(x["done"] for x in st):
             # (8) poll the plugins: collect observations of tools that have finished
             for x in st:
@@ -170,10 +197,21 @@ class Scheduler:
                     x["req"].t.append(tool_s)
                     x["feed"], x["tool"], x["obs"] = list(obs), None, None
                     x["round_t0"] = time.perf_counter()
+                    if x["away"] == "swap":
+                        eng.swap_in(x["seq"])
+                    elif x["away"] == "discard":      # recompute: everything fed or generated so far, then the observation
+                        x["seq"] = eng.new_sequence()
+                        x["feed"] = x["history"] + x["feed"]
+                        x["history"] = []
+                    x["away"] = None
+                elif (x["feed"] is None and x["left"] == 0 and x["tool"] is not None and x["obs"] is None
+                      and x["away"] is None and not x["done"]):
+                    x["away"] = self._retain(x)       # the round is over and its tool still runs
                 if x["feed"] is not None:
                     rd = x["req"].rounds[x["round"]]
                     x["parser"] = StreamParser(lambda tok, i, k=rd.delimiter_every: (i + 1) % k == 0)
                     x["left"] = rd.n_tokens
+                    x["history"].extend(x["feed"])
                     self._emit(x, eng.prefill(x["seq"], x["feed"]))
                     x["feed"] = None
                 elif x["left"] > 0:
@@ -188,9 +226,22 @@ class Scheduler:
             eng.free(x["seq"])
         return requests
 
+    def _retain(self, x):
+        """Called once per tool wait, when the round has been decoded and the observation is not there yet."""
+        how = self.retention
+        if how == "auto":
+            how = choose_retention(len(x["history"]), self.predict_tool_s(x["plugin"]), **self.rates)
+        if how == "swap":
+            self.engine.swap_out(x["seq"])
+        elif how == "discard":
+            self.engine.free(x["seq"])
+        x["req"].retained.append(how)
+        return how
+
     def _emit(self, x, tok):
         req, rd = x["req"], x["req"].rounds[x["round"]]
         req.tokens.append(tok)
+        x["history"].append(tok)
         x["left"] -= 1
         x["parser"].feed(tok)
         now = time.perf_counter()
@@ -203,6 +254,7 @@ class Scheduler:
                 if last:
                     pieces = x["parser"].flush()
                 x["tool"] = ToolProcess(rd.tool, [list(p) for p in pieces])
+                x["plugin"] = rd.tool
                 req.s.append(now - x["round_t0"])
         if last:
             req.g.append(now - x["round_t0"])
@@ -213,10 +265,10 @@ class Scheduler:
                 x["round"] += 1
 
 
-def serve(engine, requests, partial=True):
+def serve(engine, requests, partial=True, **kw):
     """Runs the requests to completion; every request gets its tokens, per-round g / t / s and its latency
     (from the start of the call to its final token)."""
-    return Scheduler(engine, partial).serve(requests)
+    return Scheduler(engine, partial, **kw).serve(requests)
 
 
 # ------------------------------------------------------------------ engines
@@ -226,7 +278,7 @@ class LdEngine:
 
     def __init__(self, ld, kv_handle, stream=None):
         self.ld, self.kv, self.stream = ld, kv_handle, stream
-        self._last = {}
+        self._last, self._host, self._done = {}, {}, []
 
     def _cb(self, seq, tok, pos):
         self._last[seq] = tok
@@ -236,7 +288,8 @@ class LdEngine:
         return self.ld.ld_kv_alloc(self.kv, 0)
 
     def prefill(self, seq, tokens):
-        self.ld.ld_prefill(self.kv, seq, tokens, self.stream, self._cb)
+        self.ld.ld_prefill(self.kv, seq, tokens, self.stream, self._cb)   # returns after its tokens reached the host
+        self._done.clear()                            # so every copy enqueued before it has finished
         return self._last[seq]
 
     def decode(self, seqs):
@@ -244,7 +297,18 @@ class LdEngine:
         return [self._last[s] for s in seqs]
 
     def free(self, seq):
+        self._host.pop(seq, None)
         self.ld.ld_kv_free(self.kv, seq)
+
+    def swap_out(self, seq):
+        import torch                                  # pinned host memory only
+        buf = torch.empty(max(self.ld.ld_kv_swap_bytes(self.kv, seq), 1), dtype=torch.uint8, pin_memory=True)
+        self.ld.ld_kv_swap_out(self.kv, seq, buf, self.stream)
+        self._host[seq] = buf                         # stays alive until the copy back has been enqueued and run
+
+    def swap_in(self, seq):
+        self.ld.ld_kv_swap_in(self.kv, seq, self._host[seq], self.stream)
+        self._done.append(self._host.pop(seq))        # released by the next prefill's synchronisation
 
 
 class FakeEngine:
@@ -253,7 +317,7 @@ class FakeEngine:
 
     def __init__(self, per_token_s=0.002, prefill_s=0.004, vocab=1000):
         self.per_token_s, self.prefill_s, self.vocab = per_token_s, prefill_s, vocab
-        self.hist, self.next_id = {}, 0
+        self.hist, self.next_id, self.swapped = {}, 0, set()
 
     def _next(self, seq):
         h = 1469598103934665603
@@ -269,6 +333,7 @@ class FakeEngine:
         return self.next_id
 
     def prefill(self, seq, tokens):
+        assert seq not in self.swapped
         time.sleep(self.prefill_s)
         self.hist[seq].extend(tokens)
         return self._next(seq)
@@ -279,3 +344,9 @@ class FakeEngine:
 
     def free(self, seq):
         self.hist.pop(seq, None)
+
+    def swap_out(self, seq):
+        self.swapped.add(seq)
+
+    def swap_in(self, seq):
+        self.swapped.remove(seq)

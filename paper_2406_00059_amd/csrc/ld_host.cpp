@@ -45,6 +45,7 @@ namespace {
 
 struct Seq {
     bool active = false, stopped = false, has_pending = false;
+    bool swapped = false;          // keys/values live in a caller's host buffer; no block is held
     int32_t pending = -1;
     int64_t n_cached = 0;
     int32_t n_mapped = 0;          // logical blocks 0..n_mapped-1 may be mapped (holes possible via ld_kv_map)
@@ -347,6 +348,7 @@ ld_status run_step(ld_kv *kv, const std::vector<Feed> &feeds, void *stream, ld_t
         if (seen[f.seq]) { ld::set_error("%s: sequence %d listed twice", who, f.seq); return LD_E_INVAL; }
         seen[f.seq] = 1;
         if (q->stopped) { ld::set_error("%s: sequence %d was stopped by its callback", who, f.seq); return LD_E_STATE; }
+        if (q->swapped) { ld::set_error("%s: sequence %d is swapped out", who, f.seq); return LD_E_STATE; }
         if (f.n < 0 || (f.n > 0 && !f.tokens)) { ld::set_error("%s: bad token array", who); return LD_E_INVAL; }
         const int64_t rows = f.n + (q->has_pending ? 1 : 0);
         if (rows == 0) { ld::set_error("%s: sequence %d has nothing to feed (no pending token)", who, f.seq); return LD_E_STATE; }
@@ -508,6 +510,7 @@ ld_status ld_kv_alloc(ld_kv *kv, int64_t reserve_tokens, ld_seq *out) {
 ld_status ld_kv_map(ld_kv *kv, ld_seq seq, int32_t logical, int32_t physical) {
     Seq *q = get_seq(kv, seq);
     if (!q || logical < 0 || logical >= kv->max_blocks) return fail(LD_E_INVAL, "ld_kv_map: bad argument");
+    if (q->swapped) return fail(LD_E_STATE, "ld_kv_map: sequence is swapped out");
     int32_t *t = kv->trow(seq);
     if (t[logical] >= 0) return fail(LD_E_STATE, "ld_kv_map: logical block already mapped");
     auto it = std::find(kv->free_stack.begin(), kv->free_stack.end(), physical);
@@ -546,9 +549,62 @@ int64_t ld_kv_len(const ld_kv *kv, ld_seq seq) {
 
 int64_t ld_kv_free_blocks(const ld_kv *kv) { return kv ? (int64_t)kv->free_stack.size() : -1; }
 
+// Bytes of one block over all layers is n_layers pieces of block_bytes, one per layer slice of the pool.
+static size_t block_bytes(const ld_kv *kv) {
+    const ld_model_config &c = kv->m->c;
+    return (size_t)2 * c.n_kv_heads * c.kv_block * c.head_dim * (c.dtype == LD_BF16 ? 2 : 4);
+}
+
+size_t ld_kv_swap_bytes(const ld_kv *kv, ld_seq seq) {
+    const Seq *q = get_seq(const_cast<ld_kv *>(kv), seq);
+    if (!q) return 0;
+    return (size_t)blocks_for(kv, q->n_cached) * kv->m->c.n_layers * block_bytes(kv);
+}
+
+ld_status ld_kv_swap_out(ld_kv *kv, ld_seq seq, void *host_buf, size_t bytes, void *stream) {
+    Seq *q = get_seq(kv, seq);
+    if (!q || (!host_buf && q->n_cached > 0)) return fail(LD_E_INVAL, "ld_kv_swap_out: bad argument");
+    if (q->swapped) return fail(LD_E_STATE, "ld_kv_swap_out: sequence is already swapped out");
+    if (bytes < ld_kv_swap_bytes(kv, seq)) return fail(LD_E_RANGE, "ld_kv_swap_out: host buffer too small");
+    const size_t bb = block_bytes(kv);
+    const int L = kv->m->c.n_layers;
+    const int64_t nb = blocks_for(kv, q->n_cached);
+    int32_t *t = kv->trow(seq);
+    // one strided copy per logical block: its n_layers pieces lie one layer slice apart in the pool
+    for (int64_t j = 0; j < nb; j++)
+        LD_HIP_TRY(hipMemcpy2DAsync((char *)host_buf + (size_t)j * L * bb, bb, kv->pool + (size_t)t[j] * bb,
+                                    (size_t)kv->n_blocks * bb, bb, L, hipMemcpyDeviceToHost, (hipStream_t)stream));
+    for (int i = kv->max_blocks - 1; i >= 0; i--)
+        if (t[i] >= 0) { kv->free_stack.push_back(t[i]); t[i] = -1; }
+    q->n_mapped = 0;
+    q->dirty_lo = q->dirty_hi = 0;
+    q->swapped = true;
+    return LD_OK;
+}
+
+ld_status ld_kv_swap_in(ld_kv *kv, ld_seq seq, const void *host_buf, size_t bytes, void *stream) {
+    Seq *q = get_seq(kv, seq);
+    if (!q || (!host_buf && q->n_cached > 0)) return fail(LD_E_INVAL, "ld_kv_swap_in: bad argument");
+    if (!q->swapped) return fail(LD_E_STATE, "ld_kv_swap_in: sequence is not swapped out");
+    if (bytes < ld_kv_swap_bytes(kv, seq)) return fail(LD_E_RANGE, "ld_kv_swap_in: host buffer too small");
+    const int64_t nb = blocks_for(kv, q->n_cached);
+    if (nb > (int64_t)kv->free_stack.size()) return fail(LD_E_NOMEM, "ld_kv_swap_in: out of KV blocks");
+    map_blocks(kv, seq, nb);
+    const size_t bb = block_bytes(kv);
+    const int L = kv->m->c.n_layers;
+    const int32_t *t = kv->trow(seq);
+    for (int64_t j = 0; j < nb; j++)
+        LD_HIP_TRY(hipMemcpy2DAsync(kv->pool + (size_t)t[j] * bb, (size_t)kv->n_blocks * bb,
+                                    (const char *)host_buf + (size_t)j * L * bb, bb, bb, L, hipMemcpyHostToDevice,
+                                    (hipStream_t)stream));
+    q->swapped = false;
+    return LD_OK;
+}
+
 ld_status ld_kv_assume(ld_kv *kv, ld_seq seq, int64_t n_tokens, int32_t pending) {
     Seq *q = get_seq(kv, seq);
     if (!q || n_tokens < 0) return fail(LD_E_INVAL, "ld_kv_assume: bad argument");
+    if (q->swapped) return fail(LD_E_STATE, "ld_kv_assume: sequence is swapped out");
     if (pending >= kv->m->c.vocab) return fail(LD_E_RANGE, "ld_kv_assume: pending token out of range");
     const int64_t need = blocks_for(kv, q->n_cached + n_tokens);
     if (need > kv->max_blocks) return fail(LD_E_RANGE, "ld_kv_assume: exceeds max_blocks_per_seq");
@@ -578,6 +634,7 @@ ld_status ld_prefill(ld_kv *kv, ld_seq seq, const int32_t *tokens, int32_t n, vo
     Seq *q = get_seq(kv, seq);
     if (!q) return fail(LD_E_INVAL, "ld_prefill: bad sequence handle");
     if (q->stopped) return fail(LD_E_STATE, "ld_prefill: sequence was stopped by its callback");
+    if (q->swapped) return fail(LD_E_STATE, "ld_prefill: sequence is swapped out");
     if (n < 0 || (n > 0 && !tokens)) return fail(LD_E_INVAL, "ld_prefill: bad token array");
     const ld_model_config &c = kv->m->c;
     const int chunk = std::min(c.max_chunk, kv->max_tokens);

@@ -157,3 +157,26 @@ def test_state_errors_leave_state_unchanged():
     assert ld.ld_kv_assume(kv2, s2, 16 * 8 + 1, check=False) == ld.LD_E_RANGE
     # double free
     assert ld.ld_kv_free(kv2, s2) == 0 and ld.ld_kv_free(kv2, s2, check=False) == ld.LD_E_INVAL
+
+
+def test_swap_state_machine_without_cached_tokens():
+    """Swap-out / swap-in of a sequence that holds reserved blocks but no tokens moves no data, so the
+    state machine and the allocator effects can be checked without a GPU: blocks go back as a free would
+    return them, the handle stays, the sequence refuses work until swapped in, errors change nothing."""
+    m = _model()
+    kv = _kv(m, n_blocks=6, max_tokens=16, max_seqs=3, max_blocks=6)
+    a = ld.ld_kv_alloc(kv, 40)                       # blocks 0, 1, 2 reserved, no token cached
+    assert ld.ld_kv_swap_bytes(kv, a) == 0 and ld.ld_kv_free_blocks(kv) == 3
+    assert ld.ld_kv_swap_in(kv, a, None, stream=0, check=False) == ld.LD_E_STATE      # not swapped out
+    assert ld.ld_kv_swap_out(kv, a, None, stream=0) == 0
+    assert ld.ld_kv_free_blocks(kv) == 6 and ld.ld_kv_block_table(kv, a).tolist() == [] and ld.ld_kv_len(kv, a) == 0
+    assert ld.ld_kv_swap_out(kv, a, None, stream=0, check=False) == ld.LD_E_STATE
+    assert ld.ld_kv_assume(kv, a, 5, check=False) == ld.LD_E_STATE
+    assert ld.ld_kv_map(kv, a, 0, 4, check=False) == ld.LD_E_STATE
+    assert ld.ld_prefill(kv, a, [1, 2], stream=0, check=False)[0] == ld.LD_E_STATE and "swapped" in ld.ld_last_error()
+    b = ld.ld_kv_alloc(kv, 48)                       # the freed blocks come back in logical order
+    assert b != a and ld.ld_kv_block_table(kv, b).tolist() == [0, 1, 2]
+    assert ld.ld_kv_swap_in(kv, a, None, stream=0) == 0 and ld.ld_kv_block_table(kv, a).tolist() == []
+    ld.ld_kv_assume(kv, a, 20, pending=3)            # usable again: takes blocks 3, 4
+    assert ld.ld_kv_block_table(kv, a).tolist() == [3, 4] and ld.ld_kv_swap_bytes(kv, a) == 2 * 2 * (2 * 4 * 16 * 64 * 4)
+    assert ld.ld_kv_free(kv, a) == 0 and ld.ld_kv_free_blocks(kv) == 3

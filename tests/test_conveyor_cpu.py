@@ -69,3 +69,40 @@ def test_partial_execution_keeps_tokens_and_obeys_the_bounds(tool_s):
         assert p.latency == pytest.approx(lm.l_new(p.g, p.t, p.s), abs=slack)
         assert lm.l_best(p.g, p.t) - 1e-3 <= p.latency <= lm.l_old(p.g, p.t) + slack
     assert sum(p.latency for p in part) < sum(b.latency for b in base)
+
+
+def test_retention_choice_thresholds():
+    """choose_retention by wasted byte-seconds: keep for short waits, swap once the wait exceeds the copy
+    out and the copy back, discard when recomputing is cheaper than both; closed-form crossing points."""
+    kw = dict(kv_bytes_per_token=512 * 1024, swap_bytes_per_s=50e9, prefill_tokens_per_s=16000.0)
+    ctx = 2048
+    M = ctx * kw["kv_bytes_per_token"]
+    t_copy = M / kw["swap_bytes_per_s"]                 # 21.5 ms one way
+    t_recompute = ctx / kw["prefill_tokens_per_s"]      # 128 ms
+    assert 2 * t_copy < t_recompute
+    assert cv.choose_retention(ctx, 0.5 * t_copy, **kw) == "keep"          # the copy out does not even fit
+    assert cv.choose_retention(ctx, 1.9 * t_copy, **kw) == "keep"          # cheaper to hold than to move twice
+    assert cv.choose_retention(ctx, 2.0 * t_copy, **kw) == "keep"          # tie -> keep
+    assert cv.choose_retention(ctx, 2.1 * t_copy, **kw) == "swap"
+    assert cv.choose_retention(ctx, 100.0, **kw) == "swap"
+    slow = dict(kw, swap_bytes_per_s=1e9)               # a slow link: recomputing beats swapping
+    assert cv.choose_retention(ctx, 0.9 * t_recompute, **slow) == "keep"
+    assert cv.choose_retention(ctx, 1.1 * t_recompute, **slow) == "discard"
+    assert cv.choose_retention(ctx, 100.0, **slow) == "discard"
+
+
+@pytest.mark.parametrize("retention", ["keep", "swap", "discard", "auto"])
+def test_retention_modes_do_not_change_the_output(retention):
+    """Baseline mode with a long tool (every round waits): whatever happens to the cache during the wait,
+    the tokens are those of the run that keeps it; every wait records what was done."""
+    ref = cv.serve(cv.FakeEngine(), _requests(0.05), partial=False)
+    eng = cv.FakeEngine()
+    kw = {}
+    if retention == "auto":   # 50 ms tools against a 2 x 1 ms copy and a 100 ms recompute -> swap
+        kw = dict(predict_tool_s=lambda plugin: plugin.duration_s,
+                  rates=dict(kv_bytes_per_token=1e6, swap_bytes_per_s=50e9, prefill_tokens_per_s=500.0))
+    got = cv.serve(eng, _requests(0.05), partial=False, retention=retention, **kw)
+    for r, g in zip(ref, got):
+        assert r.tokens == g.tokens
+        assert g.retained == [("swap" if retention == "auto" else retention)] * 2
+    assert not eng.swapped and not eng.hist            # everything swapped back in and freed

@@ -44,3 +44,15 @@ def test_rounds_with_tools_match_oracle_and_bounds():
             feed = rd.tool.observation if rd.tool else None
         assert ref == r.tokens, k
         P.okv.free(s)
+
+
+def test_swapping_the_cache_during_tool_waits_changes_nothing():
+    """Baseline mode (every round waits for its tool) with the cache swapped to host memory during each
+    wait: the tokens are those of the
+    run that keeps the cache resident, every wait was a swap, and all blocks are free at the end."""
+    P = Pair(TINY, 31, n_blocks=64, max_tokens=64, max_seqs=3, max_blocks=16)
+    keep = cv.serve(cv.LdEngine(ld, P.gkv.h), _requests(0.03), partial=False)
+    swap = cv.serve(cv.LdEngine(ld, P.gkv.h), _requests(0.03), partial=False, retention="swap")
+    for a, b in zip(keep, swap):
+        assert a.tokens == b.tokens and b.retained == ["swap", "swap"] and a.retained == ["keep", "keep"]
+    assert ld.ld_kv_free_blocks(P.gkv.h) == 64

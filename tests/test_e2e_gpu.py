@@ -150,3 +150,46 @@ def test_7b_width_two_layers_prompt_and_32_greedy_tokens():
     assert max(errs) <= 2e-2
     assert sink.last(33) == toks_o
     assert P.tables_equal(s)
+
+
+@pytest.mark.parametrize("shape,tol", [(TINY, 1e-4), (replace(TINY, dtype="bf16", n_kv_heads=2, name="tiny-bf16-gqa"), 2e-2)])
+@pytest.mark.parametrize("pinned", [True, False])
+def test_swap_out_and_in_across_a_tool_wait(shape, tol, pinned):
+    """KV retention (section 2.2): a sequence is swapped to host memory while it waits, another sequence
+    takes its blocks and overwrites them, then it is swapped back onto different physical blocks and goes
+    on.  Block tables, free counts and status codes equal the oracle's at every point; tokens equal the
+    oracle's; a swap-in without enough free blocks fails on both sides and changes nothing."""
+    P = Pair(shape, 13, n_blocks=8, max_tokens=64, max_seqs=3, max_blocks=6, max_chunk=16)
+    s = P.alloc()
+    tk = prompt(13, 1, 37, shape.vocab)
+    sink = Tokens()
+    P.okv.prefill(s, tk, want_logits=False); ld.ld_prefill(P.gkv.h, s, tk, callback=sink)
+    for _ in range(2):
+        rc, t, _ = P.okv.decode(s, want_logits=False); ld.ld_decode_step(P.gkv.h, [s], callback=sink)
+        assert sink.last() == [t]
+    nbytes = ld.ld_kv_swap_bytes(P.gkv.h, s)
+    esz = 2 if shape.dtype == "bf16" else 4
+    assert nbytes == 3 * shape.n_layers * 2 * shape.n_kv_heads * 16 * shape.head_dim * esz
+    host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=pinned)
+    rc_o, store = P.okv.swap_out(s)
+    assert rc_o == 0 and ld.ld_kv_swap_out(P.gkv.h, s, host) == 0
+    assert ld.ld_kv_free_blocks(P.gkv.h) == P.okv.free_blocks() == 8 and P.tables_equal(s)
+    assert ld.ld_decode_step(P.gkv.h, [s], check=False)[0] == ld.LD_E_STATE and P.okv.decode(s)[0] == oracle.E_STATE
+    # another request runs on the freed blocks (and overwrites them)
+    other = P.alloc()
+    tk2 = prompt(13, 2, 90, shape.vocab)
+    rc, t2, _ = P.okv.prefill(other, tk2, want_logits=False); ld.ld_prefill(P.gkv.h, other, tk2, callback=sink)
+    assert sink.last() == [t2] and P.tables_equal(other) and ld.ld_kv_free_blocks(P.gkv.h) == 2
+    assert ld.ld_kv_swap_in(P.gkv.h, s, host, check=False) == ld.LD_E_NOMEM and P.okv.swap_in(s, store) == oracle.E_NOMEM
+    assert ld.ld_kv_free_blocks(P.gkv.h) == 2 and ld.ld_decode_step(P.gkv.h, [s], check=False)[0] == ld.LD_E_STATE
+    P.okv.free(other); ld.ld_kv_free(P.gkv.h, other)
+    filler = P.alloc(2 * 16)
+    assert P.okv.swap_in(s, store) == 0 and ld.ld_kv_swap_in(P.gkv.h, s, host) == 0
+    assert P.tables_equal(s) and ld.ld_kv_block_table(P.gkv.h, s).tolist() == [2, 3, 4]
+    errs = []
+    for _ in range(12):
+        rc, t, lg_o = P.okv.decode(s)
+        rc, lg = ld.ld_decode_step(P.gkv.h, [s], callback=sink, logits_vocab=P.V)
+        errs.append(rel_err(lg[0], lg_o))
+        assert sink.last() == [t]
+    assert max(errs) <= tol and P.tables_equal(s) and ld.ld_kv_len(P.gkv.h, s) == P.okv.length(s)

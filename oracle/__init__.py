@@ -66,6 +66,7 @@ def lib():
         L.orc_prefill.restype = C.c_int32; L.orc_prefill.argtypes = [vp, C.c_int32, ip, C.c_int64, dp, ip]
         L.orc_decode.restype = C.c_int32; L.orc_decode.argtypes = [vp, C.c_int32, dp, ip]
         L.orc_seq_stop.restype = C.c_int32; L.orc_seq_stop.argtypes = [vp, C.c_int32]
+        L.orc_kv_fork.restype = C.c_int32; L.orc_kv_fork.argtypes = [vp, C.c_int32, C.c_int64, ip]
         L.orc_kv_swap_doubles.restype = C.c_int64; L.orc_kv_swap_doubles.argtypes = [vp, C.c_int32]
         L.orc_kv_swap_out.restype = C.c_int32; L.orc_kv_swap_out.argtypes = [vp, C.c_int32, dp]
         L.orc_kv_swap_in.restype = C.c_int32; L.orc_kv_swap_in.argtypes = [vp, C.c_int32, dp]
@@ -258,6 +259,11 @@ class KV:
 
     def stop(self, seq):
         return lib().orc_seq_stop(self.h, seq)
+
+    def fork(self, parent, n_tokens):
+        s = C.c_int32(-1)
+        rc = lib().orc_kv_fork(self.h, parent, n_tokens, C.byref(s))
+        return rc, s.value
 
     def swap_out(self, seq):
         """-> (rc, store): the sequence's keys/values as a float64 array, its blocks back on the free list."""

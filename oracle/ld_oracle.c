@@ -381,6 +381,7 @@ typedef struct {
     int32_t max_seqs, max_blocks_per_seq;
     double *pool;
     int32_t *free_stack; int64_t n_free;
+    int32_t *refs;    /* sequences holding each block (prefix sharing); 0 = on the free list */
     orc_seq *seqs;
 } orc_kv;
 
@@ -393,6 +394,7 @@ orc_kv *orc_kv_create(const orc_model *m, int64_t n_blocks, int32_t max_seqs, in
     size_t per_block = (size_t)2 * c->n_kv_heads * c->kv_block * c->head_dim;
     kv->pool = calloc((size_t)c->n_layers * n_blocks * per_block, sizeof(double));
     kv->free_stack = malloc(sizeof(int32_t) * n_blocks);
+    kv->refs = calloc(n_blocks, sizeof(int32_t));
     for (int64_t i = 0; i < n_blocks; i++) kv->free_stack[i] = (int32_t)(n_blocks - 1 - i);
     kv->n_free = n_blocks;
     kv->seqs = calloc(max_seqs, sizeof(orc_seq));
@@ -408,7 +410,7 @@ void orc_kv_destroy(orc_kv *kv)
 {
     if (!kv) return;
     for (int s = 0; s < kv->max_seqs; s++) free(kv->seqs[s].table);
-    free(kv->seqs); free(kv->free_stack); free(kv->pool); free(kv);
+    free(kv->seqs); free(kv->free_stack); free(kv->refs); free(kv->pool); free(kv);
 }
 
 static orc_seq *get_seq(orc_kv *kv, int32_t s)
@@ -425,9 +427,21 @@ static int ensure_blocks(orc_kv *kv, orc_seq *q, int64_t need)
     for (int64_t i = 0; i < need; i++) if (q->table[i] < 0) missing++;
     if (missing > kv->n_free) return ORC_E_NOMEM;
     for (int64_t i = 0; i < need; i++)
-        if (q->table[i] < 0) q->table[i] = kv->free_stack[--kv->n_free];
+        if (q->table[i] < 0) { q->table[i] = kv->free_stack[--kv->n_free]; kv->refs[q->table[i]] = 1; }
     if (need > q->n_mapped) q->n_mapped = (int32_t)need;
     return ORC_OK;
+}
+
+/* Drop every block a sequence holds, last logical block first; a block goes back to the free list when
+ * its last holder drops it. */
+static void release_blocks(orc_kv *kv, orc_seq *q)
+{
+    for (int i = kv->max_blocks_per_seq - 1; i >= 0; i--)
+        if (q->table[i] >= 0) {
+            if (--kv->refs[q->table[i]] == 0) kv->free_stack[kv->n_free++] = q->table[i];
+            q->table[i] = -1;
+        }
+    q->n_mapped = 0;
 }
 
 int32_t orc_kv_alloc(orc_kv *kv, int64_t reserve_tokens, int32_t *out)
@@ -457,6 +471,7 @@ int32_t orc_kv_map(orc_kv *kv, int32_t s, int32_t logical, int32_t physical)
     if (at < 0) return ORC_E_NOMEM;
     memmove(kv->free_stack + at, kv->free_stack + at + 1, sizeof(int32_t) * (kv->n_free - at - 1));
     kv->n_free--;
+    kv->refs[physical] = 1;
     q->table[logical] = physical;
     if (logical + 1 > q->n_mapped) q->n_mapped = logical + 1;
     return ORC_OK;
@@ -466,9 +481,8 @@ int32_t orc_kv_free(orc_kv *kv, int32_t s)
 {
     orc_seq *q = get_seq(kv, s);
     if (!q) return ORC_E_INVAL;
-    for (int i = kv->max_blocks_per_seq - 1; i >= 0; i--)
-        if (q->table[i] >= 0) { kv->free_stack[kv->n_free++] = q->table[i]; q->table[i] = -1; }
-    q->active = 0; q->n_mapped = 0; q->swapped = 0;
+    release_blocks(kv, q);
+    q->active = 0; q->swapped = 0;
     return ORC_OK;
 }
 
@@ -557,9 +571,7 @@ int32_t orc_kv_swap_out(orc_kv *kv, int32_t s, double *store)
         for (int l = 0; l < L; l++)
             memcpy(store + (j * L + l) * per, kv->pool + ((size_t)l * kv->n_blocks + q->table[j]) * per,
                    sizeof(double) * per);
-    for (int i = kv->max_blocks_per_seq - 1; i >= 0; i--)
-        if (q->table[i] >= 0) { kv->free_stack[kv->n_free++] = q->table[i]; q->table[i] = -1; }
-    q->n_mapped = 0;
+    release_blocks(kv, q);
     q->swapped = 1;
     return ORC_OK;
 }
@@ -578,6 +590,39 @@ int32_t orc_kv_swap_in(orc_kv *kv, int32_t s, const double *store)
             memcpy(kv->pool + ((size_t)l * kv->n_blocks + q->table[j]) * per, store + (j * L + l) * per,
                    sizeof(double) * per);
     q->swapped = 0;
+    return ORC_OK;
+}
+
+/* Prefix sharing (section 2.1 serves many requests at once; section 4.3 puts the same tool descriptions
+ * into every prompt): a new sequence that starts with the first n_tokens cached positions of `parent`.
+ * Blocks that the prefix fills completely are shared (their holder count goes up; nothing ever writes a
+ * full block again); a last, partly filled block is copied into a block of the child's own, because both
+ * sequences will append into their copy.  The child has no pending token. */
+int32_t orc_kv_fork(orc_kv *kv, int32_t parent, int64_t n_tokens, int32_t *out)
+{
+    orc_seq *p = get_seq(kv, parent);
+    if (!p || !out || n_tokens < 0 || n_tokens > p->n_cached) return ORC_E_INVAL;
+    if (p->swapped) return ORC_E_STATE;
+    int s = 0;
+    while (s < kv->max_seqs && kv->seqs[s].active) s++;
+    if (s == kv->max_seqs) return ORC_E_NOMEM;
+    int bs = kv->m->c.kv_block;
+    int64_t full = n_tokens / bs, tail = n_tokens % bs;
+    if (tail && kv->n_free < 1) return ORC_E_NOMEM;
+    orc_seq *q = &kv->seqs[s];
+    q->active = 1; q->stopped = 0; q->has_pending = 0; q->pending = -1; q->swapped = 0;
+    q->n_cached = n_tokens; q->n_mapped = (int32_t)(full + (tail ? 1 : 0));
+    for (int64_t j = 0; j < full; j++) { q->table[j] = p->table[j]; kv->refs[p->table[j]]++; }
+    if (tail) {
+        int32_t nb = kv->free_stack[--kv->n_free];
+        kv->refs[nb] = 1;
+        q->table[full] = nb;
+        size_t per = block_doubles(kv);
+        for (int l = 0; l < kv->m->c.n_layers; l++)
+            memcpy(kv->pool + ((size_t)l * kv->n_blocks + nb) * per,
+                   kv->pool + ((size_t)l * kv->n_blocks + p->table[full]) * per, sizeof(double) * per);
+    }
+    *out = s;
     return ORC_OK;
 }
 

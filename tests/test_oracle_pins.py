@@ -456,6 +456,56 @@ def test_swap_out_and_in_keeps_the_sequence_and_follows_the_allocator(tiny_weigh
         np.testing.assert_array_equal(lg_a, lg_b)
 
 
+def test_fork_shares_full_blocks_and_equals_recomputing_the_prefix(tiny_weights):
+    """Prefix sharing: a child forked from the first n positions of a parent continues exactly like a
+    sequence that was fed the same prefix from scratch (a cached row depends on the tokens before it only);
+    full blocks are shared by reference, a partly filled last block is copied; a shared block returns to the
+    free list only when its last holder lets go; the parent's later appends and its death do not touch the
+    child."""
+    shape, w = tiny_weights
+    m = oracle.Model(shape, w)
+    prefix, tail_a, tail_b = _prompt(40, shape.vocab, 106), _prompt(9, shape.vocab, 107), _prompt(5, shape.vocab, 108)
+    kv, ref = oracle.KV(m, 12, 4, 6), oracle.KV(m, 12, 4, 6)
+    rc, parent = kv.alloc(0)
+    assert kv.prefill(parent, np.concatenate([prefix, tail_a]))[0] == 0          # 49 positions: blocks 0..3
+    assert kv.block_table(parent)[1].tolist() == [0, 1, 2, 3]
+    # fork inside a block: 2 full blocks shared, the third copied into block 4
+    rc, child = kv.fork(parent, 40)
+    assert rc == 0 and kv.block_table(child)[1].tolist() == [0, 1, 4] and kv.length(child) == 40 and kv.free_blocks() == 7
+    # fork at a block boundary: nothing copied, nothing popped
+    rc, child2 = kv.fork(parent, 32)
+    assert rc == 0 and kv.block_table(child2)[1].tolist() == [0, 1] and kv.free_blocks() == 7
+    assert kv.fork(parent, 50)[0] == oracle.E_INVAL and kv.decode(child)[0] == oracle.E_STATE   # no pending token
+    # the parent goes on and then dies; its own blocks are recycled and overwritten by a stranger
+    for _ in range(20):
+        kv.decode(parent)
+    kv.free(parent)
+    assert kv.free_blocks() == 6 + 3                       # it had grown into block 5; 2, 3, 5 came back, 0, 1 are still held
+    rc, stranger = kv.alloc(0)
+    kv.prefill(stranger, _prompt(48, shape.vocab, 109))
+    # the child against a from-scratch sequence with the same tokens
+    rc, solo = ref.alloc(0)
+    rc_a, t_a, lg_a = kv.prefill(child, tail_b)
+    rc_b, t_b, lg_b = ref.prefill(solo, np.concatenate([prefix, tail_b]))
+    assert rc_a == rc_b == 0 and t_a == t_b
+    np.testing.assert_array_equal(lg_a, lg_b)
+    for _ in range(10):
+        (rc_a, t_a, lg_a), (rc_b, t_b, lg_b) = kv.decode(child), ref.decode(solo)
+        assert t_a == t_b
+        np.testing.assert_array_equal(lg_a, lg_b)
+    # last holders: child2 still pins blocks 0, 1 after the child is gone; then they return, last logical first
+    kv.free(child); kv.free(stranger)
+    assert kv.free_blocks() == 10
+    kv.free(child2)
+    assert kv.free_blocks() == 12
+    rc, again = kv.alloc(32)
+    assert kv.block_table(again)[1].tolist() == [0, 1]
+    # no block for the copied tail: the fork fails and changes nothing
+    small = oracle.KV(m, 3, 2, 6)
+    rc, p2 = small.alloc(0); small.prefill(p2, prefix)
+    assert small.free_blocks() == 0 and small.fork(p2, 33)[0] == oracle.E_NOMEM and small.fork(p2, 32)[0] == 0
+
+
 def test_wo_and_wdown_zero_make_every_layer_the_identity(tiny_weights):
     shape, w = tiny_weights
     w0 = dict(w)

@@ -141,6 +141,16 @@ size_t ld_kv_swap_bytes(const ld_kv *kv, ld_seq seq);
 ld_status ld_kv_swap_out(ld_kv *kv, ld_seq seq, void *host_buf, size_t bytes, void *stream);
 ld_status ld_kv_swap_in(ld_kv *kv, ld_seq seq, const void *host_buf, size_t bytes, void *stream);
 
+/* Prefix sharing (section 2.1: many requests are served at once; section 4.1: every prompt carries the
+ * same tool descriptions): a new sequence (lowest free handle) that starts with the first n_tokens cached
+ * positions of `parent` (0 <= n_tokens <= its length).  Blocks the prefix fills completely are shared: both
+ * sequences' tables name the same physical block, which returns to the free list when its last holder
+ * frees or swaps it out; nothing ever writes a full block again.  A partly filled last block is copied
+ * (all layers, device to device, enqueued on `stream`) into a block of the child's own, taken from the
+ * free list (LD_E_NOMEM, nothing changed, if there is none).  The child has no pending token: continue it
+ * with ld_prefill. */
+ld_status ld_kv_fork(ld_kv *kv, ld_seq parent, int64_t n_tokens, void *stream, ld_seq *out);
+
 /* Test / benchmark hook: declare that the next n_tokens positions of a sequence are already
  * cached (their blocks are mapped; the caller has written, or will write, their keys and values
  * straight into the pool using the layout above), and set the pending token (none if < 0). */

@@ -19,7 +19,7 @@ __all__ = [
     "LDK_STORE", "LDK_ADD", "LDK_SWIGLU", "LIB_PATH", "lib", "LdError", "ld_model_config", "ld_weights",
     "ld_token_cb", "ld_model_create", "ld_model_destroy", "ld_kv_bytes", "ld_workspace_bytes", "ld_kv_create",
     "ld_kv_destroy", "ld_kv_alloc", "ld_kv_map", "ld_kv_free", "ld_kv_block_table", "ld_kv_len",
-    "ld_kv_free_blocks", "ld_kv_assume", "ld_kv_swap_bytes", "ld_kv_swap_out", "ld_kv_swap_in", "ld_prefill", "ld_decode_step", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
+    "ld_kv_free_blocks", "ld_kv_assume", "ld_kv_swap_bytes", "ld_kv_swap_out", "ld_kv_swap_in", "ld_kv_fork", "ld_prefill", "ld_decode_step", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
     "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
     "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_prefill_attention_scratch_bytes",
     "ldk_prefill_attention", "ldk_argmax", "Model", "KV",
@@ -72,6 +72,7 @@ _SIGS = {
     "ld_kv_len": (C.c_int64, [_vp, C.c_int32]),
     "ld_kv_free_blocks": (C.c_int64, [_vp]),
     "ld_kv_assume": (C.c_int, [_vp, C.c_int32, C.c_int64, C.c_int32]),
+    "ld_kv_fork": (C.c_int, [_vp, C.c_int32, C.c_int64, _vp, C.POINTER(C.c_int32)]),
     "ld_kv_swap_bytes": (C.c_size_t, [_vp, C.c_int32]),
     "ld_kv_swap_out": (C.c_int, [_vp, C.c_int32, _vp, C.c_size_t, _vp]),
     "ld_kv_swap_in": (C.c_int, [_vp, C.c_int32, _vp, C.c_size_t, _vp]),
@@ -213,6 +214,13 @@ def ld_kv_free_blocks(kv):
 
 def ld_kv_assume(kv, seq, n_tokens, pending=-1, check=True):
     return _check(lib().ld_kv_assume(kv, seq, n_tokens, pending), check)
+
+
+def ld_kv_fork(kv, parent, n_tokens, stream=None, check=True):
+    """-> handle of the child (or the status code when check=False and the call failed)."""
+    out = C.c_int32(-1)
+    rc = _check(lib().ld_kv_fork(kv, parent, n_tokens, _stream(stream), C.byref(out)), check)
+    return out.value if rc == LD_OK else rc
 
 
 def ld_kv_swap_bytes(kv, seq):

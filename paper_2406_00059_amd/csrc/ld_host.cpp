@@ -123,6 +123,7 @@ struct ld_kv {
     int32_t max_tokens, max_seqs, max_blocks;
     Workspace ws;
     std::vector<int32_t> free_stack;
+    std::vector<int32_t> refs;   // sequences holding each block (prefix sharing); 0 = on the free stack
     std::vector<Seq> seqs;
     std::vector<int32_t> table;  // host copy [max_seqs][max_blocks], -1 = unmapped
     // pinned staging, created by the first pass
@@ -178,10 +179,24 @@ void map_blocks(ld_kv *kv, int s, int64_t need) {
         if (t[i] >= 0) continue;
         t[i] = kv->free_stack.back();
         kv->free_stack.pop_back();
+        kv->refs[t[i]] = 1;
         if (q.dirty_lo == q.dirty_hi) { q.dirty_lo = (int32_t)i; q.dirty_hi = (int32_t)i + 1; }
         else { q.dirty_lo = std::min<int32_t>(q.dirty_lo, i); q.dirty_hi = std::max<int32_t>(q.dirty_hi, i + 1); }
     }
     q.n_mapped = std::max<int32_t>(q.n_mapped, (int32_t)need);
+}
+
+// Drops every block a sequence holds, last logical block first; a block returns to the free stack when its
+// last holder drops it.
+void release_blocks(ld_kv *kv, int s) {
+    int32_t *t = kv->trow(s);
+    for (int i = kv->max_blocks - 1; i >= 0; i--)
+        if (t[i] >= 0) {
+            if (--kv->refs[t[i]] == 0) kv->free_stack.push_back(t[i]);
+            t[i] = -1;
+        }
+    kv->seqs[s].n_mapped = 0;
+    kv->seqs[s].dirty_lo = kv->seqs[s].dirty_hi = 0;
 }
 
 ld_status ensure_pinned(ld_kv *kv) {
@@ -476,6 +491,7 @@ ld_status ld_kv_create(ld_model *m, void *pool, int64_t n_blocks, void *ws, size
     kv->max_tokens = max_tokens; kv->max_seqs = max_seqs; kv->max_blocks = max_blocks_per_seq;
     kv->ws = plan_workspace(*m, (char *)ws, max_tokens, max_seqs, max_blocks_per_seq);
     kv->free_stack.resize(n_blocks);
+    kv->refs.assign(n_blocks, 0);
     for (int64_t i = 0; i < n_blocks; i++) kv->free_stack[i] = (int32_t)(n_blocks - 1 - i);
     kv->seqs.resize(max_seqs);
     kv->table.assign((size_t)max_seqs * max_blocks_per_seq, -1);
@@ -516,6 +532,7 @@ ld_status ld_kv_map(ld_kv *kv, ld_seq seq, int32_t logical, int32_t physical) {
     auto it = std::find(kv->free_stack.begin(), kv->free_stack.end(), physical);
     if (it == kv->free_stack.end()) return fail(LD_E_NOMEM, "ld_kv_map: physical block is not free");
     kv->free_stack.erase(it);
+    kv->refs[physical] = 1;
     t[logical] = physical;
     if (q->dirty_lo == q->dirty_hi) { q->dirty_lo = logical; q->dirty_hi = logical + 1; }
     else { q->dirty_lo = std::min(q->dirty_lo, logical); q->dirty_hi = std::max(q->dirty_hi, logical + 1); }
@@ -526,9 +543,7 @@ ld_status ld_kv_map(ld_kv *kv, ld_seq seq, int32_t logical, int32_t physical) {
 ld_status ld_kv_free(ld_kv *kv, ld_seq seq) {
     Seq *q = get_seq(kv, seq);
     if (!q) return fail(LD_E_INVAL, "ld_kv_free: bad sequence handle");
-    int32_t *t = kv->trow(seq);
-    for (int i = kv->max_blocks - 1; i >= 0; i--)
-        if (t[i] >= 0) { kv->free_stack.push_back(t[i]); t[i] = -1; }
+    release_blocks(kv, seq);
     *q = Seq();
     return LD_OK;
 }
@@ -574,10 +589,7 @@ ld_status ld_kv_swap_out(ld_kv *kv, ld_seq seq, void *host_buf, size_t bytes, vo
     for (int64_t j = 0; j < nb; j++)
         LD_HIP_TRY(hipMemcpy2DAsync((char *)host_buf + (size_t)j * L * bb, bb, kv->pool + (size_t)t[j] * bb,
                                     (size_t)kv->n_blocks * bb, bb, L, hipMemcpyDeviceToHost, (hipStream_t)stream));
-    for (int i = kv->max_blocks - 1; i >= 0; i--)
-        if (t[i] >= 0) { kv->free_stack.push_back(t[i]); t[i] = -1; }
-    q->n_mapped = 0;
-    q->dirty_lo = q->dirty_hi = 0;
+    release_blocks(kv, seq);
     q->swapped = true;
     return LD_OK;
 }
@@ -598,6 +610,36 @@ ld_status ld_kv_swap_in(ld_kv *kv, ld_seq seq, const void *host_buf, size_t byte
                                     (const char *)host_buf + (size_t)j * L * bb, bb, bb, L, hipMemcpyHostToDevice,
                                     (hipStream_t)stream));
     q->swapped = false;
+    return LD_OK;
+}
+
+ld_status ld_kv_fork(ld_kv *kv, ld_seq parent, int64_t n_tokens, void *stream, ld_seq *out) {
+    Seq *p = get_seq(kv, parent);
+    if (!p || !out || n_tokens < 0 || n_tokens > p->n_cached) return fail(LD_E_INVAL, "ld_kv_fork: bad argument");
+    if (p->swapped) return fail(LD_E_STATE, "ld_kv_fork: parent is swapped out");
+    int s = 0;
+    while (s < kv->max_seqs && kv->seqs[s].active) s++;
+    if (s == kv->max_seqs) return fail(LD_E_NOMEM, "ld_kv_fork: no free sequence handle");
+    const int bs = kv->m->c.kv_block;
+    const int64_t full = n_tokens / bs, tail = n_tokens % bs;
+    if (tail && kv->free_stack.empty()) return fail(LD_E_NOMEM, "ld_kv_fork: no block for the copied tail");
+    const int32_t *pt = kv->trow(parent);
+    int32_t *t = kv->trow(s);
+    Seq &q = kv->seqs[s];
+    q = Seq();
+    q.active = true;
+    q.n_cached = n_tokens;
+    for (int64_t j = 0; j < full; j++) { t[j] = pt[j]; kv->refs[pt[j]]++; }
+    q.n_mapped = (int32_t)full;
+    if (full) { q.dirty_lo = 0; q.dirty_hi = (int32_t)full; }
+    if (tail) {
+        map_blocks(kv, s, full + 1);    // pops one block for logical block `full`
+        const size_t bb = block_bytes(kv);
+        LD_HIP_TRY(hipMemcpy2DAsync(kv->pool + (size_t)t[full] * bb, (size_t)kv->n_blocks * bb,
+                                    kv->pool + (size_t)pt[full] * bb, (size_t)kv->n_blocks * bb, bb, kv->m->c.n_layers,
+                                    hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    }
+    *out = s;
     return LD_OK;
 }
 

@@ -180,3 +180,32 @@ def test_swap_state_machine_without_cached_tokens():
     ld.ld_kv_assume(kv, a, 20, pending=3)            # usable again: takes blocks 3, 4
     assert ld.ld_kv_block_table(kv, a).tolist() == [3, 4] and ld.ld_kv_swap_bytes(kv, a) == 2 * 2 * (2 * 4 * 16 * 64 * 4)
     assert ld.ld_kv_free(kv, a) == 0 and ld.ld_kv_free_blocks(kv) == 3
+
+
+def test_fork_at_block_boundaries_shares_blocks_by_holder_count():
+    """Prefix sharing without a GPU (a fork at a block boundary copies nothing): shared blocks appear in
+    both tables, return to the free list only with their last holder, last logical block first."""
+    m = _model()
+    kv = _kv(m, n_blocks=8, max_tokens=16, max_seqs=4, max_blocks=6)
+    p = ld.ld_kv_alloc(kv, 0)
+    ld.ld_kv_assume(kv, p, 50, pending=1)                               # blocks 0..3
+    c1 = ld.ld_kv_fork(kv, p, 32, stream=0)
+    c2 = ld.ld_kv_fork(kv, p, 48, stream=0)
+    assert (c1, c2) == (1, 2) and ld.ld_kv_block_table(kv, c1).tolist() == [0, 1]
+    assert ld.ld_kv_block_table(kv, c2).tolist() == [0, 1, 2] and ld.ld_kv_free_blocks(kv) == 4
+    assert ld.ld_kv_len(kv, c1) == 32 and ld.ld_kv_len(kv, c2) == 48
+    assert ld.ld_kv_fork(kv, p, 51, stream=0, check=False) == ld.LD_E_INVAL
+    assert ld.ld_decode_step(kv, [c1], stream=0, check=False)[0] == ld.LD_E_STATE     # a child has no pending token
+    ld.ld_kv_free(kv, p)
+    assert ld.ld_kv_free_blocks(kv) == 5                                # only block 3 came back
+    ld.ld_kv_assume(kv, c1, 16, pending=2)                              # c1 grows into a block of its own
+    assert ld.ld_kv_block_table(kv, c1).tolist() == [0, 1, 3]
+    ld.ld_kv_free(kv, c2)
+    assert ld.ld_kv_free_blocks(kv) == 5                                # block 2 back, 0 and 1 still held by c1
+    ld.ld_kv_free(kv, c1)
+    assert ld.ld_kv_free_blocks(kv) == 8
+    again = ld.ld_kv_alloc(kv, 48)
+    assert ld.ld_kv_block_table(kv, again).tolist() == [0, 1, 3]        # LIFO: c1's blocks, logical order
+    # a swapped-out parent cannot be forked
+    ld.ld_kv_swap_out(kv, again, None, stream=0)
+    assert ld.ld_kv_fork(kv, again, 0, stream=0, check=False) == ld.LD_E_STATE

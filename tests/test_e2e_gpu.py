@@ -193,3 +193,46 @@ def test_swap_out_and_in_across_a_tool_wait(shape, tol, pinned):
         errs.append(rel_err(lg[0], lg_o))
         assert sink.last() == [t]
     assert max(errs) <= tol and P.tables_equal(s) and ld.ld_kv_len(P.gkv.h, s) == P.okv.length(s)
+
+
+@pytest.mark.parametrize("shape,tol", [(TINY, 1e-4), (replace(TINY, dtype="bf16", n_kv_heads=2, name="tiny-bf16-gqa"), 2e-2)])
+def test_fork_from_a_shared_prefix(shape, tol):
+    """Prefix sharing: children forked from a parent's cached prefix (inside a block: the partial block is
+    copied on the device; at a block boundary: nothing is copied) continue with their own tokens while
+    the parent goes on, dies, and a stranger overwrites its blocks.  Tables, free counts and tokens equal
+    the oracle's, logits within tolerance, also in one batched decode of both children."""
+    P = Pair(shape, 14, n_blocks=12, max_tokens=64, max_seqs=4, max_blocks=6, max_chunk=16)
+    parent = P.alloc()
+    pre = prompt(14, 1, 49, shape.vocab)
+    sink = Tokens()
+    rc, t, _ = P.okv.prefill(parent, pre, want_logits=False); ld.ld_prefill(P.gkv.h, parent, pre, callback=sink)
+    assert sink.last() == [t]
+    kids = []
+    for n in (40, 32):
+        rc, co = P.okv.fork(parent, n)
+        cg = ld.ld_kv_fork(P.gkv.h, parent, n)
+        assert rc == 0 and co == cg and P.tables_equal(cg) and ld.ld_kv_len(P.gkv.h, cg) == n
+        kids.append(cg)
+    assert ld.ld_kv_block_table(P.gkv.h, kids[0]).tolist() == [0, 1, 4] and ld.ld_kv_free_blocks(P.gkv.h) == P.okv.free_blocks() == 7
+    for _ in range(20):                                   # the parent overwrites positions 49.. of its own block 3, 4
+        rc, t, _ = P.okv.decode(parent, want_logits=False); ld.ld_decode_step(P.gkv.h, [parent], callback=sink)
+        assert sink.last() == [t]
+    P.okv.free(parent); ld.ld_kv_free(P.gkv.h, parent)
+    stranger = P.alloc()
+    tk = prompt(14, 5, 48, shape.vocab)
+    P.okv.prefill(stranger, tk, want_logits=False); ld.ld_prefill(P.gkv.h, stranger, tk, callback=sink)
+    assert P.tables_equal(stranger) and ld.ld_kv_free_blocks(P.gkv.h) == P.okv.free_blocks()
+    errs = []
+    for k, c in enumerate(kids):
+        suf = prompt(14, 10 + k, 5 + 3 * k, shape.vocab)
+        rc, t, lg_o = P.okv.prefill(c, suf)
+        rc, lg = ld.ld_prefill(P.gkv.h, c, suf, callback=sink, logits_vocab=P.V)
+        errs.append(rel_err(lg, lg_o))
+        assert sink.last() == [t]
+    for _ in range(12):
+        ref = [P.okv.decode(c) for c in kids]
+        rc, lg = ld.ld_decode_step(P.gkv.h, kids, callback=sink, logits_vocab=P.V)
+        assert sink.last(2) == [r[1] for r in ref]
+        errs += [rel_err(lg[i], ref[i][2]) for i in range(2)]
+    assert max(errs) <= tol
+    assert all(P.tables_equal(c) for c in kids) and ld.ld_kv_free_blocks(P.gkv.h) == P.okv.free_blocks()

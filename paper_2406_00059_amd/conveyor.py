@@ -165,21 +165,33 @@ class Scheduler:
     """Token-granularity scheduler (section 3.3).  `engine` provides
          new_sequence() -> seq, prefill(seq, tokens) -> token, decode(seqs) -> tokens, free(seq)."""
 
-    def __init__(self, engine, partial=True, retention="keep", predict_tool_s=None, rates=None):
+    def __init__(self, engine, partial=True, retention="keep", predict_tool_s=None, rates=None, shared_prefix=0):
         """retention: "keep" | "swap" | "discard" | "auto".  "auto" asks choose_retention with
         predict_tool_s(plugin) seconds and rates = dict(kv_bytes_per_token, swap_bytes_per_s,
-        prefill_tokens_per_s).  "swap" needs engine.swap_out / engine.swap_in."""
+        prefill_tokens_per_s).  "swap" needs engine.swap_out / engine.swap_in.
+        shared_prefix = k > 0: all prompts start with the same k tokens (system prompt, tool descriptions);
+        they are prefilled once and every request forks from that cache (engine.fork)."""
         self.engine, self.partial, self.retention = engine, partial, retention
-        self.predict_tool_s, self.rates = predict_tool_s, rates or {}
+        self.predict_tool_s, self.rates, self.shared_prefix = predict_tool_s, rates or {}, shared_prefix
 
     def serve(self, requests):
         eng = self.engine
         t_start = time.perf_counter()
         st = []
+        k, template = self.shared_prefix, None
+        if k and requests:
+            head = list(requests[0].prompt[:k])
+            assert all(list(r.prompt[:k]) == head and len(r.prompt) > k for r in requests), "prompts must share the prefix"
+            template = eng.new_sequence()
+            eng.prefill(template, head)               # its emitted token is not used
         for r in requests:
-            st.append(dict(req=r, seq=eng.new_sequence(), round=0, left=0, parser=None, tool=None, obs=None,
-                           feed=list(r.prompt), round_t0=t_start, t_start=t_start, done=False,
-                           history=[], away=None, plugin=None))
+            seq = eng.fork(template, k) if template is not None else eng.new_sequence()
+            st.append(dict(req=r, seq=seq, round=0, left=0, parser=None, tool=None, obs=None,
+                           feed=list(r.prompt[k:] if template is not None else r.prompt), round_t0=t_start,
+                           t_start=t_start, done=False,
+                           history=list(r.prompt[:k]) if template is not None else [], away=None, plugin=None))
+        if template is not None:
+            eng.free(template)                        # the shared blocks live on with their holders
         while not all(x["done"] for x in st):
             # (8) poll the plugins: collect observations of tools that have finished
             for x in st:
@@ -300,6 +312,9 @@ class LdEngine:
         self._host.pop(seq, None)
         self.ld.ld_kv_free(self.kv, seq)
 
+    def fork(self, parent, n_tokens):
+        return self.ld.ld_kv_fork(self.kv, parent, n_tokens, self.stream)
+
     def swap_out(self, seq):
         import torch                                  # pinned host memory only
         buf = torch.empty(max(self.ld.ld_kv_swap_bytes(self.kv, seq), 1), dtype=torch.uint8, pin_memory=True)
@@ -344,6 +359,11 @@ class FakeEngine:
 
     def free(self, seq):
         self.hist.pop(seq, None)
+
+    def fork(self, parent, n_tokens):
+        child = self.new_sequence()
+        self.hist[child] = self.hist[parent][:n_tokens]
+        return child
 
     def swap_out(self, seq):
         self.swapped.add(seq)

@@ -111,3 +111,17 @@ def test_retention_modes_do_not_change_the_output(retention):
         assert r.tokens == g.tokens
         assert g.retained == [("swap" if retention == "auto" else retention)] * 2
     assert not eng.swapped and not eng.hist            # everything swapped back in and freed
+
+
+def test_shared_prompt_prefix_is_prefilled_once_and_changes_nothing():
+    def reqs():
+        head = list(range(500, 524))
+        return [cv.Request(prompt=head + list(range(10 + k, 20 + k)),
+                           rounds=[cv.Round(24, cv.SyntheticTool(0.02, [7, 8, 9], pieces_to_start=1)), cv.Round(8, None)])
+                for k in range(3)]
+    ref = cv.serve(cv.FakeEngine(), reqs())
+    eng = cv.FakeEngine()
+    got = cv.serve(eng, reqs(), shared_prefix=24)
+    assert [r.tokens for r in ref] == [g.tokens for g in got] and not eng.hist
+    with pytest.raises(AssertionError):
+        cv.serve(cv.FakeEngine(), reqs(), shared_prefix=30)        # the prompts differ from token 24 on

@@ -61,3 +61,29 @@ def test_swapping_the_cache_during_tool_waits_changes_nothing():
     for a, b in zip(keep, swap):
         assert a.tokens == b.tokens and b.retained == ["swap", "swap"] and a.retained == ["keep", "keep"]
     assert ld.ld_kv_free_blocks(P.gkv.h) == 64
+
+
+def test_shared_prompt_prefix_on_the_engine():
+    """Three requests whose prompts share their first 24 tokens: the prefix is prefilled once and forked;
+    the tokens equal those of the oracle replaying the same calls (fork included), and all blocks are free
+    afterwards."""
+    P = Pair(TINY, 31, n_blocks=64, max_tokens=64, max_seqs=4, max_blocks=16)
+    head = prompt(31, 50, 24, TINY.vocab).tolist()
+    obs = prompt(31, 51, 20, TINY.vocab).tolist()
+    reqs = [cv.Request(prompt=head + prompt(31, 60 + k, 10 + k, TINY.vocab).tolist(),
+                       rounds=[cv.Round(24, cv.SyntheticTool(0.01, obs, pieces_to_start=1)), cv.Round(8, None)])
+            for k in range(3)]
+    cv.serve(cv.LdEngine(ld, P.gkv.h), reqs, shared_prefix=24)
+    assert ld.ld_kv_free_blocks(P.gkv.h) == 64
+    rc, tmpl = P.okv.alloc(0)
+    P.okv.prefill(tmpl, np.array(head, np.int32), want_logits=False)
+    for r in reqs:
+        rc, s = P.okv.fork(tmpl, 24)
+        ref, feed = [], r.prompt[24:]
+        for rd in r.rounds:
+            rc, t, _ = P.okv.prefill(s, np.array(feed, np.int32), want_logits=False); ref.append(t)
+            for _ in range(rd.n_tokens - 1):
+                rc, t, _ = P.okv.decode(s, want_logits=False); ref.append(t)
+            feed = rd.tool.observation if rd.tool else None
+        assert ref == r.tokens
+        P.okv.free(s)

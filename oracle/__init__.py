@@ -66,6 +66,11 @@ def lib():
         L.orc_prefill.restype = C.c_int32; L.orc_prefill.argtypes = [vp, C.c_int32, ip, C.c_int64, dp, ip]
         L.orc_decode.restype = C.c_int32; L.orc_decode.argtypes = [vp, C.c_int32, dp, ip]
         L.orc_seq_stop.restype = C.c_int32; L.orc_seq_stop.argtypes = [vp, C.c_int32]
+        L.orc_uniform.restype = C.c_double; L.orc_uniform.argtypes = [C.c_uint64, C.c_uint64]
+        L.orc_sample_gumbel.restype = C.c_int32
+        L.orc_sample_gumbel.argtypes = [dp, C.c_int64, C.c_double, C.c_uint64, C.c_int64]
+        L.orc_seq_set_sampling.restype = C.c_int32
+        L.orc_seq_set_sampling.argtypes = [vp, C.c_int32, C.c_double, C.c_uint64]
         L.orc_kv_fork.restype = C.c_int32; L.orc_kv_fork.argtypes = [vp, C.c_int32, C.c_int64, ip]
         L.orc_kv_swap_doubles.restype = C.c_int64; L.orc_kv_swap_doubles.argtypes = [vp, C.c_int32]
         L.orc_kv_swap_out.restype = C.c_int32; L.orc_kv_swap_out.argtypes = [vp, C.c_int32, dp]
@@ -134,6 +139,15 @@ def matvec(w, x):
     y = np.empty(w.shape[0], dtype=np.float64)
     lib().orc_matvec(p, dt, w.shape[0], w.shape[1], _dp(x), _dp(y))
     return y
+
+
+def uniform(seed, counter):
+    return lib().orc_uniform(seed, counter)
+
+
+def sample_gumbel(logits, temperature, seed, pos):
+    x = _f64(logits)
+    return lib().orc_sample_gumbel(_dp(x), x.size, temperature, seed, pos)
 
 
 def attention_contig(q, K, V):
@@ -259,6 +273,9 @@ class KV:
 
     def stop(self, seq):
         return lib().orc_seq_stop(self.h, seq)
+
+    def set_sampling(self, seq, temperature, seed):
+        return lib().orc_seq_set_sampling(self.h, seq, temperature, seed)
 
     def fork(self, parent, n_tokens):
         s = C.c_int32(-1)

@@ -174,6 +174,34 @@ int32_t orc_argmax(const double *x, int64_t n)
     return (int32_t)best;
 }
 
+/* Sampling at temperature T > 0 (the paper decodes at temperature 0, section 4.1; this is the same
+ * decision with noise): the token is argmax_i (logit_i / T + g_i) with independent standard Gumbel noise
+ * g_i = -log(-log(u_i)), which draws i with probability softmax(logits / T)_i.  The uniforms come from a
+ * counter-based generator, so a draw is a pure function of (seed, counter): u = (k + 1/2) / 2^23 with k
+ * the top 23 bits of the SplitMix64 output function applied to seed + (counter + 1) * 0x9E3779B97F4A7C15
+ * (Steele, Lea, Flood 2014).  The counter of vocabulary entry i for the token that will sit at position
+ * pos is pos * n + i.  Smallest index on ties, as for the plain argmax. */
+double orc_uniform(uint64_t seed, uint64_t counter)
+{
+    uint64_t z = seed + (counter + 1) * 0x9E3779B97F4A7C15ULL;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    z = z ^ (z >> 31);
+    return ((double)(z >> 41) + 0.5) / 8388608.0;
+}
+
+int32_t orc_sample_gumbel(const double *logits, int64_t n, double temperature, uint64_t seed, int64_t pos)
+{
+    int64_t best = 0;
+    double best_v = 0.0;
+    for (int64_t i = 0; i < n; i++) {
+        double u = orc_uniform(seed, (uint64_t)pos * (uint64_t)n + (uint64_t)i);
+        double v = logits[i] / temperature - log(-log(u));
+        if (i == 0 || v > best_v) { best = i; best_v = v; }
+    }
+    return (int32_t)best;
+}
+
 /* One query against n cached (key, value) rows given by pointer tables:
  * scores q.k_j / sqrt(hd), softmax, weighted average of the values. */
 static void attend_rows(const double *q, const double *const *krow, const double *const *vrow,
@@ -373,6 +401,7 @@ typedef struct {
     int32_t n_mapped;
     int32_t *table;
     int swapped;      /* keys/values live outside the pool; no block is held */
+    double temperature; uint64_t seed;   /* temperature 0: greedy */
 } orc_seq;
 
 typedef struct {
@@ -456,6 +485,7 @@ int32_t orc_kv_alloc(orc_kv *kv, int64_t reserve_tokens, int32_t *out)
     int rc = ensure_blocks(kv, q, (reserve_tokens + bs - 1) / bs);
     if (rc) return rc;
     q->active = 1; q->stopped = 0; q->has_pending = 0; q->pending = -1; q->n_cached = 0; q->swapped = 0;
+    q->temperature = 0.0; q->seed = 0;
     *out = s;
     return ORC_OK;
 }
@@ -611,6 +641,7 @@ int32_t orc_kv_fork(orc_kv *kv, int32_t parent, int64_t n_tokens, int32_t *out)
     if (tail && kv->n_free < 1) return ORC_E_NOMEM;
     orc_seq *q = &kv->seqs[s];
     q->active = 1; q->stopped = 0; q->has_pending = 0; q->pending = -1; q->swapped = 0;
+    q->temperature = 0.0; q->seed = 0;
     q->n_cached = n_tokens; q->n_mapped = (int32_t)(full + (tail ? 1 : 0));
     for (int64_t j = 0; j < full; j++) { q->table[j] = p->table[j]; kv->refs[p->table[j]]++; }
     if (tail) {
@@ -656,12 +687,25 @@ int32_t orc_prefill(orc_kv *kv, int32_t s, const int32_t *tokens, int64_t n, dou
     double *lg = malloc(sizeof(double) * kv->m->c.vocab);
     int rc = feed_tokens(kv, q, all, tot, lg);
     if (rc == ORC_OK) {
-        q->pending = orc_argmax(lg, kv->m->c.vocab); q->has_pending = 1;
+        /* the emitted token will sit at position n_cached */
+        q->pending = q->temperature > 0.0
+                         ? orc_sample_gumbel(lg, kv->m->c.vocab, q->temperature, q->seed, q->n_cached)
+                         : orc_argmax(lg, kv->m->c.vocab);
+        q->has_pending = 1;
         if (next) *next = q->pending;
         if (logits_out) memcpy(logits_out, lg, sizeof(double) * kv->m->c.vocab);
     }
     free(all); free(lg);
     return rc;
+}
+
+/* Temperature and seed of a sequence's token choice (temperature 0: greedy, the default). */
+int32_t orc_seq_set_sampling(orc_kv *kv, int32_t s, double temperature, uint64_t seed)
+{
+    orc_seq *q = get_seq(kv, s);
+    if (!q || !(temperature >= 0.0)) return ORC_E_INVAL;
+    q->temperature = temperature; q->seed = seed;
+    return ORC_OK;
 }
 
 /* Decode: feed the pending token, emit the next one. */

@@ -193,6 +193,53 @@ def test_argmax_lowest_index_on_ties():
     assert oracle.argmax(x) == 17
 
 
+def test_counter_based_uniform_moments_range_and_independence_of_counters():
+    u = np.array([oracle.uniform(12345, c) for c in range(40000)])
+    assert u.min() > 0.0 and u.max() < 1.0
+    assert abs(u.mean() - 0.5) < 4 * math.sqrt(1 / 12 / u.size)
+    assert abs(u.var() - 1 / 12) < 0.002
+    assert abs(np.corrcoef(u[:-1], u[1:])[0, 1]) < 0.02                       # neighbouring counters
+    v = np.array([oracle.uniform(12346, c) for c in range(40000)])
+    assert abs(np.corrcoef(u, v)[0, 1]) < 0.02                                # neighbouring seeds
+    assert oracle.uniform(7, 99) == oracle.uniform(7, 99)
+    assert set(np.round(u * 2 ** 23 - 0.5, 6) % 1) == {0.0}                   # the grid (k + 1/2) / 2^23
+
+
+def test_gumbel_sampling_draws_from_the_softmax_at_the_given_temperature():
+    """argmax(logits / T + Gumbel noise) is a draw from softmax(logits / T): the empirical frequencies over
+    many positions (= independent counters) match within 4.5 standard deviations for every outcome; as
+    T -> 0 the draw is the argmax; a draw is a pure function of (seed, position)."""
+    lg = np.array([1.2, -0.3, 0.0, 2.5, 2.4, -4.0, 0.7, 1.9])
+    for T in (0.7, 1.0, 2.0):
+        p = np.exp(lg / T) / np.exp(lg / T).sum()
+        n = 30000
+        cnt = np.bincount([oracle.sample_gumbel(lg, T, 777, pos) for pos in range(n)], minlength=lg.size)
+        z = (cnt - n * p) / np.sqrt(n * p * (1 - p))
+        assert np.abs(z).max() < 4.5, (T, z)
+    assert all(oracle.sample_gumbel(lg, 1e-4, 5, pos) == 3 for pos in range(500))
+    a = [oracle.sample_gumbel(lg, 1.0, 5, pos) for pos in range(200)]
+    assert a == [oracle.sample_gumbel(lg, 1.0, 5, pos) for pos in range(200)]
+    assert a != [oracle.sample_gumbel(lg, 1.0, 6, pos) for pos in range(200)]
+
+
+def test_sequence_sampling_state(tiny_weights):
+    """A sequence at temperature 0 is greedy whatever its seed; at temperature > 0 its emitted tokens are
+    the sampler's draws on its own logits at the position the token will take."""
+    shape, w = tiny_weights
+    m = oracle.Model(shape, w)
+    kv = oracle.KV(m, 8, 2, 4)
+    tok = _prompt(20, shape.vocab, 110)
+    (_, a), (_, b) = kv.alloc(0), kv.alloc(0)
+    assert kv.set_sampling(a, 0.0, 99) == 0 and kv.set_sampling(b, 0.8, 4242) == 0 and kv.set_sampling(b, -1.0, 1) == oracle.E_INVAL
+    rc, ta, lga = kv.prefill(a, tok)
+    rc, tb, lgb = kv.prefill(b, tok)
+    np.testing.assert_array_equal(lga, lgb)
+    assert ta == int(np.argmax(lga)) and tb == oracle.sample_gumbel(lgb, 0.8, 4242, 20)
+    for _ in range(5):
+        rc, tb, lgb = kv.decode(b)
+        assert tb == oracle.sample_gumbel(lgb, 0.8, 4242, kv.length(b))
+
+
 # ------------------------------------------------------------------ block allocator (integer exact)
 
 class _PyAlloc:

@@ -151,6 +151,11 @@ ld_status ld_kv_swap_in(ld_kv *kv, ld_seq seq, const void *host_buf, size_t byte
  * with ld_prefill. */
 ld_status ld_kv_fork(ld_kv *kv, ld_seq parent, int64_t n_tokens, void *stream, ld_seq *out);
 
+/* Token choice of a sequence: temperature 0 (the default, and what section 4.1 uses) emits the greedy
+ * token; temperature > 0 draws from softmax(logits / temperature) as ldk_sample does, with the position
+ * the emitted token will take as the counter, so a run is reproducible from (seed, tokens fed). */
+ld_status ld_kv_set_sampling(ld_kv *kv, ld_seq seq, float temperature, uint64_t seed);
+
 /* Test / benchmark hook: declare that the next n_tokens positions of a sequence are already
  * cached (their blocks are mapped; the caller has written, or will write, their keys and values
  * straight into the pool using the layout above), and set the pending token (none if < 0). */

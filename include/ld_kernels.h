@@ -112,6 +112,15 @@ ld_status ldk_prefill_attention(const float *q, int32_t q_stride, const void *po
 /* out[r] = smallest index of the maximum of logits[r, 0..V). */
 ld_status ldk_argmax(const float *logits, int32_t R, int32_t V, int32_t *out, void *stream);
 
+/* Token choice with temperature (section 4.1 decodes at temperature 0 = ldk_argmax; this is the same
+ * decision with noise): out[r] = smallest index of the maximum of logits[r, i] / temperature[r] + g(r, i),
+ * g = -log(-log(u)) standard Gumbel noise, which draws i with probability softmax(logits[r] / temperature[r]).
+ * u = (k + 1/2) / 2^23 with k the top 23 bits of the SplitMix64 output function applied to
+ * seed[r] + (pos[r] * V + i + 1) * 0x9E3779B97F4A7C15: a pure function of (seed, pos, i).  Rows with
+ * temperature[r] == 0 are the plain argmax.  temperature, seed, pos: DEVICE arrays of R entries. */
+ld_status ldk_sample(const float *logits, int32_t R, int32_t V, const float *temperature, const uint64_t *seed,
+                     const int32_t *pos, int32_t *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,10 +19,10 @@ __all__ = [
     "LDK_STORE", "LDK_ADD", "LDK_SWIGLU", "LIB_PATH", "lib", "LdError", "ld_model_config", "ld_weights",
     "ld_token_cb", "ld_model_create", "ld_model_destroy", "ld_kv_bytes", "ld_workspace_bytes", "ld_kv_create",
     "ld_kv_destroy", "ld_kv_alloc", "ld_kv_map", "ld_kv_free", "ld_kv_block_table", "ld_kv_len",
-    "ld_kv_free_blocks", "ld_kv_assume", "ld_kv_swap_bytes", "ld_kv_swap_out", "ld_kv_swap_in", "ld_kv_fork", "ld_prefill", "ld_decode_step", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
+    "ld_kv_free_blocks", "ld_kv_assume", "ld_kv_swap_bytes", "ld_kv_swap_out", "ld_kv_swap_in", "ld_kv_fork", "ld_kv_set_sampling", "ld_prefill", "ld_decode_step", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
     "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
     "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_prefill_attention_scratch_bytes",
-    "ldk_prefill_attention", "ldk_argmax", "Model", "KV",
+    "ldk_prefill_attention", "ldk_argmax", "ldk_sample", "Model", "KV",
 ]
 
 
@@ -72,6 +72,8 @@ _SIGS = {
     "ld_kv_len": (C.c_int64, [_vp, C.c_int32]),
     "ld_kv_free_blocks": (C.c_int64, [_vp]),
     "ld_kv_assume": (C.c_int, [_vp, C.c_int32, C.c_int64, C.c_int32]),
+    "ld_kv_set_sampling": (C.c_int, [_vp, C.c_int32, C.c_float, C.c_uint64]),
+    "ldk_sample": (C.c_int, [_vp, C.c_int32, C.c_int32, _vp, _vp, _vp, _vp, _vp]),
     "ld_kv_fork": (C.c_int, [_vp, C.c_int32, C.c_int64, _vp, C.POINTER(C.c_int32)]),
     "ld_kv_swap_bytes": (C.c_size_t, [_vp, C.c_int32]),
     "ld_kv_swap_out": (C.c_int, [_vp, C.c_int32, _vp, C.c_size_t, _vp]),
@@ -214,6 +216,16 @@ def ld_kv_free_blocks(kv):
 
 def ld_kv_assume(kv, seq, n_tokens, pending=-1, check=True):
     return _check(lib().ld_kv_assume(kv, seq, n_tokens, pending), check)
+
+
+def ld_kv_set_sampling(kv, seq, temperature, seed, check=True):
+    return _check(lib().ld_kv_set_sampling(kv, seq, temperature, seed), check)
+
+
+def ldk_sample(logits, temperature, seed, pos, out, stream=None):
+    """temperature float32 [R], seed int64 [R] (bit pattern of the unsigned seed), pos int32 [R], on the device."""
+    R, V = logits.shape
+    _check(lib().ldk_sample(_ptr(logits), R, V, _ptr(temperature), _ptr(seed), _ptr(pos), _ptr(out), _stream(stream)))
 
 
 def ld_kv_fork(kv, parent, n_tokens, stream=None, check=True):

@@ -46,6 +46,8 @@ namespace {
 struct Seq {
     bool active = false, stopped = false, has_pending = false;
     bool swapped = false;          // keys/values live in a caller's host buffer; no block is held
+    float temperature = 0.f;       // 0: greedy
+    uint64_t seed = 0;
     int32_t pending = -1;
     int64_t n_cached = 0;
     int32_t n_mapped = 0;          // logical blocks 0..n_mapped-1 may be mapped (holes possible via ld_kv_map)
@@ -74,7 +76,8 @@ Workspace plan_workspace(const ld_model &m, char *base, int max_tokens, int max_
     };
     const size_t T = max_tokens;
     w.table = (int32_t *)take((size_t)max_seqs * max_blocks * 4);
-    w.meta = (int32_t *)take(T * 9 * 4);  // tok | pos | seq_slot | ctx_len | emit_row | prefill tiles (4 ints each)
+    // tok | pos | seq_slot | ctx_len | emit_row | prefill tiles (4 ints each) | sampling (seed 2, temperature, pos per emitting row)
+    w.meta = (int32_t *)take((T * 9 + 2 + (size_t)max_seqs * 4) * 4);
     w.out_tok = (int32_t *)take((size_t)max_seqs * 4);
     w.x = (float *)take(T * c.d_model * 4);
     w.qkv = (float *)take(T * m.nqkv() * 4);
@@ -201,7 +204,8 @@ void release_blocks(ld_kv *kv, int s) {
 
 ld_status ensure_pinned(ld_kv *kv) {
     if (kv->pin_meta) return LD_OK;
-    LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_meta, (size_t)kv->max_tokens * 9 * 4, hipHostMallocDefault));
+    LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_meta, ((size_t)kv->max_tokens * 9 + 2 + (size_t)kv->max_seqs * 4) * 4,
+                             hipHostMallocDefault));
     LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_out, (size_t)kv->max_seqs * 4, hipHostMallocDefault));
     LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_table, (size_t)kv->max_seqs * kv->max_blocks * 4, hipHostMallocDefault));
     return LD_OK;
@@ -247,7 +251,23 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const 
     const int n_dec_rows = mfma_attn ? n_single : T;   // rows that go through the single-query kernel
     int max_ctx_dec = 1;
     for (int t = 0; t < n_dec_rows; t++) max_ctx_dec = std::max(max_ctx_dec, rows[t].pos + 1);
-    LD_HIP_TRY(hipMemcpyAsync(w.meta, pm, (size_t)(5 * T + 4 * n_tiles) * 4, hipMemcpyHostToDevice, st));
+    // sampling parameters of the emitting rows, only when some sequence samples: seeds (8-byte aligned),
+    // temperatures, position the emitted token will take
+    bool sampling = false;
+    for (int r = 0; r < R; r++) sampling = sampling || kv->seqs[rows[emit[r]].seq].temperature > 0.f;
+    const int samp_off = (5 * T + 4 * n_tiles + 1) & ~1;
+    int meta_ints = 5 * T + 4 * n_tiles;
+    if (sampling) {
+        uint64_t *ps = reinterpret_cast<uint64_t *>(pm + samp_off);
+        float *ptemp = reinterpret_cast<float *>(pm + samp_off + 2 * R);
+        int32_t *ppos = pm + samp_off + 3 * R;
+        for (int r = 0; r < R; r++) {
+            const Seq &sq = kv->seqs[rows[emit[r]].seq];
+            ps[r] = sq.seed; ptemp[r] = sq.temperature; ppos[r] = rows[emit[r]].pos + 1;
+        }
+        meta_ints = samp_off + 4 * R;
+    }
+    LD_HIP_TRY(hipMemcpyAsync(w.meta, pm, (size_t)meta_ints * 4, hipMemcpyHostToDevice, st));
     const int32_t *d_tok = w.meta, *d_pos = w.meta + T, *d_slot = w.meta + 2 * T, *d_ctx = w.meta + 3 * T,
                   *d_emit = w.meta + 4 * T, *d_tiles = w.meta + 5 * T;
 
@@ -328,7 +348,12 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const 
     LD_TIMED(LD_PROF_OTHER, ldk_rmsnorm(w.x, m.final_norm, d_emit, R, d, c.rms_eps, w.hn, st));
     LD_TIMED(LD_PROF_LM_HEAD, ldk_linear(m.lm_head, c.dtype, w.hn, nullptr, 0.f, R, c.vocab, d, LDK_STORE, w.logits, w.lin_scratch,
                                       w.lin_scratch_bytes, st));
-    LD_TIMED(LD_PROF_OTHER, ldk_argmax(w.logits, R, c.vocab, w.out_tok, st));
+    if (sampling)
+        LD_TIMED(LD_PROF_OTHER, ldk_sample(w.logits, R, c.vocab, reinterpret_cast<const float *>(w.meta + samp_off + 2 * R),
+                                           reinterpret_cast<const uint64_t *>(w.meta + samp_off), w.meta + samp_off + 3 * R,
+                                           w.out_tok, st));
+    else
+        LD_TIMED(LD_PROF_OTHER, ldk_argmax(w.logits, R, c.vocab, w.out_tok, st));
 #undef LD_TIMED
 #undef LD_TRY
     if (R) LD_HIP_TRY(hipMemcpyAsync(kv->pin_out, w.out_tok, (size_t)R * 4, hipMemcpyDeviceToHost, st));
@@ -610,6 +635,14 @@ ld_status ld_kv_swap_in(ld_kv *kv, ld_seq seq, const void *host_buf, size_t byte
                                     (const char *)host_buf + (size_t)j * L * bb, bb, bb, L, hipMemcpyHostToDevice,
                                     (hipStream_t)stream));
     q->swapped = false;
+    return LD_OK;
+}
+
+ld_status ld_kv_set_sampling(ld_kv *kv, ld_seq seq, float temperature, uint64_t seed) {
+    Seq *q = get_seq(kv, seq);
+    if (!q || !(temperature >= 0.f)) return fail(LD_E_INVAL, "ld_kv_set_sampling: bad argument");
+    q->temperature = temperature;
+    q->seed = seed;
     return LD_OK;
 }
 

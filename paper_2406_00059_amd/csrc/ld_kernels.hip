@@ -414,6 +414,55 @@ __global__ __launch_bounds__(1024) void k_argmax(const float *__restrict__ logit
     }
 }
 
+// ---------------------------------------------------------------- token choice with temperature
+//
+// argmax_i (logit_i / T + g_i), g_i = -log(-log(u_i)) standard Gumbel noise: a draw from softmax(logits / T).
+// u_i = (k + 1/2) / 2^23, k = top 23 bits of the SplitMix64 output function applied to
+// seed + (counter + 1) * 0x9E3779B97F4A7C15, counter = pos * V + i: a pure function of (seed, pos, i), exact in
+// float32.  Rows with temperature 0 are the plain argmax.  Lowest index on ties.
+
+__device__ __forceinline__ float gumbel_noise(uint64_t seed, uint64_t counter) {
+    uint64_t z = seed + (counter + 1) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    const float u = ((float)(uint32_t)(z >> 41) + 0.5f) * (1.0f / 8388608.0f);
+    return -logf(-logf(u));
+}
+
+__global__ __launch_bounds__(1024) void k_sample(const float *__restrict__ logits, int V,
+                                                 const float *__restrict__ temperature,
+                                                 const uint64_t *__restrict__ seed, const int32_t *__restrict__ pos,
+                                                 int32_t *__restrict__ out) {
+    __shared__ float sv[16];
+    __shared__ int si[16];
+    const int r = blockIdx.x;
+    const float *row = logits + (int64_t)r * V;
+    const float temp = temperature[r];
+    const float inv_t = temp > 0.f ? 1.0f / temp : 1.0f;
+    const uint64_t sd = seed[r], c0 = (uint64_t)pos[r] * (uint64_t)V;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int i = threadIdx.x; i < V; i += 1024) {
+        float v = row[i];
+        if (temp > 0.f) v = v * inv_t + gumbel_noise(sd, c0 + i);
+        if (v > bv || bi == 0x7fffffff) { bv = v; bi = i; }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float ov = __shfl_xor(bv, off, WAVE);
+        const int oi = __shfl_xor(bi, off, WAVE);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; w++)
+            if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+        out[r] = bi;
+    }
+}
+
 // ---------------------------------------------------------------- launch helpers
 
 inline ld_status launched(const char *what) {
@@ -683,6 +732,15 @@ ld_status ldk_argmax(const float *logits, int32_t R, int32_t V, int32_t *out, vo
     if (!logits || !out || R < 0 || V <= 0) return ld::fail(LD_E_INVAL, "ldk_argmax: bad argument");
     LD_LAUNCH(k_argmax, dim3(R), dim3(1024), 0, (hipStream_t)stream, logits, V, out);
     return launched("k_argmax");
+}
+
+ld_status ldk_sample(const float *logits, int32_t R, int32_t V, const float *temperature, const uint64_t *seed,
+                     const int32_t *pos, int32_t *out, void *stream) {
+    if (R == 0) return LD_OK;
+    if (!logits || !temperature || !seed || !pos || !out || R < 0 || V <= 0)
+        return ld::fail(LD_E_INVAL, "ldk_sample: bad argument");
+    LD_LAUNCH(k_sample, dim3(R), dim3(1024), 0, (hipStream_t)stream, logits, V, temperature, seed, pos, out);
+    return launched("k_sample");
 }
 
 }  // extern "C"

@@ -236,3 +236,37 @@ def test_fork_from_a_shared_prefix(shape, tol):
         errs += [rel_err(lg[i], ref[i][2]) for i in range(2)]
     assert max(errs) <= tol
     assert all(P.tables_equal(c) for c in kids) and ld.ld_kv_free_blocks(P.gkv.h) == P.okv.free_blocks()
+
+
+def test_sampled_and_greedy_sequences_in_one_batch():
+    """Two sequences with the same prompt, one greedy, one at temperature 0.8: the sampled one emits the
+    oracle's draws (same seed, same positions) through prefill, batched decode and an observation; the
+    greedy one is untouched by its neighbour."""
+    shape = TINY
+    P = Pair(shape, 15, n_blocks=32, max_tokens=64, max_seqs=2, max_blocks=8)
+    a, b = P.alloc(), P.alloc()
+    assert P.okv.set_sampling(b, 0.8, 2 ** 63 + 12345) == 0 and ld.ld_kv_set_sampling(P.gkv.h, b, 0.8, 2 ** 63 + 12345) == 0
+    assert ld.ld_kv_set_sampling(P.gkv.h, b, -0.5, 1, check=False) == ld.LD_E_INVAL
+    tk = prompt(15, 1, 21, shape.vocab)
+    sink = Tokens()
+    toks = {a: [], b: []}
+    for s in (a, b):
+        rc, t, _ = P.okv.prefill(s, tk, want_logits=False); toks[s].append(t)
+        ld.ld_prefill(P.gkv.h, s, tk, callback=sink)
+        assert sink.last() == [t]
+    for step in range(24):
+        ref = [P.okv.decode(s, want_logits=False)[1] for s in (a, b)]
+        ld.ld_decode_step(P.gkv.h, [a, b], callback=sink)
+        assert sink.last(2) == ref, step
+        toks[a].append(ref[0]); toks[b].append(ref[1])
+    obs = prompt(15, 2, 9, shape.vocab)
+    rc, t, _ = P.okv.prefill(b, obs, want_logits=False); ld.ld_prefill(P.gkv.h, b, obs, callback=sink)
+    assert sink.last() == [t]
+    assert toks[a] != toks[b]                                # the temperature does change the text
+    # the greedy sequence alone gives the same tokens
+    Q = Pair(shape, 15, n_blocks=32, max_tokens=64, max_seqs=1, max_blocks=8)
+    s = Q.alloc(); solo = Tokens()
+    ld.ld_prefill(Q.gkv.h, s, tk, callback=solo)
+    for _ in range(24):
+        ld.ld_decode_step(Q.gkv.h, [s], callback=solo)
+    assert [t for _, t, _ in solo.log] == toks[a]

@@ -263,6 +263,37 @@ def test_argmax_ties_and_brute_force():
     assert out.cpu().tolist() == ref and ref[1] == 12 and ref[2] == 0 and ref[3] == V - 1
 
 
+def test_sampling_kernel_draws_the_oracles_tokens():
+    """Gumbel-max token choice: for every row the kernel's draw equals the oracle's for the same (seed,
+    position); rows with temperature 0 are the plain argmax; over many positions the draws of a small
+    vocabulary follow softmax(logits / T)."""
+    V, R = 32000, 12
+    lg = gen.normal(7, 1, (R, V)) * 3.0
+    temps = [0.0, 0.3, 0.7, 1.0, 1.5, 2.0] * 2
+    seeds = [int(x) for x in gen.randint(7, 2, 0, 2 ** 40, R).tolist()]
+    seeds[3] = 2 ** 64 - 5                                   # a seed above 2^63: unsigned arithmetic
+    pos = [0, 1, 17, 4095, 8191, 100000, 5, 6, 7, 8, 9, 10]
+    out = torch.empty(R, dtype=torch.int32, device=DEV)
+    seed_t = torch.tensor([s - 2 ** 64 if s >= 2 ** 63 else s for s in seeds], dtype=torch.int64, device=DEV)
+    ld.ldk_sample(lg.to(DEV), torch.tensor(temps, device=DEV), seed_t, torch.tensor(pos, dtype=torch.int32, device=DEV), out)
+    got = out.cpu().tolist()
+    for r in range(R):
+        ref = oracle.sample_gumbel(lg[r].numpy(), temps[r], seeds[r], pos[r]) if temps[r] > 0 else oracle.argmax(lg[r].numpy())
+        assert got[r] == ref, (r, got[r], ref)
+    assert len(set(got[1:6])) > 1                            # the noise does move the choice
+    # frequencies on a small vocabulary
+    small = torch.tensor([1.2, -0.3, 0.0, 2.5, 2.4, -4.0, 0.7, 1.9])
+    n = 20000
+    out = torch.empty(n, dtype=torch.int32, device=DEV)
+    ld.ldk_sample(small.repeat(n, 1).to(DEV), torch.full((n,), 0.7, device=DEV), torch.full((n,), 777, dtype=torch.int64, device=DEV),
+                  torch.arange(n, dtype=torch.int32, device=DEV), out)
+    cnt = np.bincount(out.cpu().numpy(), minlength=8)
+    p = np.exp(small.numpy() / 0.7); p /= p.sum()
+    assert np.abs((cnt - n * p) / np.sqrt(n * p * (1 - p))).max() < 4.5
+    ref = [oracle.sample_gumbel(small.numpy(), 0.7, 777, i) for i in range(2000)]
+    assert out.cpu().tolist()[:2000] == ref
+
+
 @pytest.mark.parametrize("dtype,hd,T", [("bf16", 128, 1), ("bf16", 128, 3), ("f32", 64, 1), ("bf16", 64, 1)])
 def test_fused_qkv_projection_rope_cache_append(dtype, hd, T):
     """ldk_qkv_rope = RMSNorm + q/k/v projection + rotary embedding + cache append in one call

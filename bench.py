@@ -179,7 +179,7 @@ def run_batch1(args, ld, torch, shape, weights, model):
     # attached to its dispatches on the step's stream during the profiled steps above (kernel start to
     # kernel end, like a kernel trace).  Beside it: the same launch on every layer's weights in turn between
     # ONE pair of events, which adds the launch gap between consecutive kernels.
-    assert dominant == "gate_up", dominant
+    assert dominant == "gate_up", (dominant, {k: round(v["avg_us"], 1) for k, v in kernels.items()})
     avg_s = prof[dominant][0] / prof[dominant][1] * 1e-3
     xin = torch.randn(1, d, device="cuda"); yout = torch.empty(1, f, device="cuda")
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -443,6 +443,191 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_big(const bf16_t *__restrict_
     }
 }
 
+// The same tile scheme with the operands copied from global memory straight into LDS
+// (global_load_lds_dwordx4: lane l of a wave writes its 16 bytes at the wave's LDS base + 16 l), so that no
+// operand byte passes through registers on its way to LDS and the registers of the prefetch ring are free.
+// A stage holds the tile's rows row-major, 64 bytes (one K chunk of 32) per row: X hi rows, X lo rows, W
+// rows.  One copy instruction of a wave covers 16 rows x 4 sixteen-byte pieces (1 KB of LDS, 64 contiguous
+// bytes of 16 rows in memory).  Piece `seg` of row r sits in slot seg ^ ((r >> 2) & 3) of the row, which
+// makes the operand reads of 16 consecutive rows hit 16 different bank groups; the swizzle costs nothing
+// because a lane may fetch any global piece into its fixed slot.  S stages; the copies of chunk c + S - 1
+// are issued right after the barrier of chunk c, when every wave has finished reading the stage they
+// overwrite; before the barrier of chunk c a wave waits until its own copies of chunk c have landed
+// (s_waitcnt vmcnt with the number of younger copies still allowed in flight).
+template <int WM, int BN, int S, int EPI>
+__global__ __launch_bounds__(128 * WM) void k_gemm_dma(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
+                                                       const bf16_t *__restrict__ xlo, int T, int N, int K,
+                                                       float *__restrict__ y, int n_ttiles, int ks,
+                                                       float *__restrict__ partial) {
+    constexpr bool SWI = (EPI == ld::GEMM_SWIGLU);
+    constexpr int NW = 2 * WM;                    // waves
+    constexpr int BM = 64 * WM, BK = 32;
+    constexpr int WCT = BN / 2 / 32;              // 32-column accumulator tiles per wave
+    constexpr int NOUT = SWI ? BN / 2 : BN;       // output columns per workgroup
+    constexpr int ROWS = 2 * BM + BN;             // rows of a stage: X hi, X lo, W
+    constexpr int STAGE = ROWS * 64;              // bytes
+    constexpr int P = ROWS / 16 / NW;             // copy instructions per wave per chunk
+    static_assert(ROWS % (16 * NW) == 0, "rows must split evenly over the waves");
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+    const int b = blockIdx.x, xcd = b & 7, s = b >> 3;
+    const int kz = s % ks, tt_idx = (s / ks) % n_ttiles, nb = (s / (ks * n_ttiles)) * 8 + xcd;
+    const int n_nblocks = (N + NOUT - 1) / NOUT;
+    if (nb >= n_nblocks) return;
+    const int t0 = tt_idx * BM, n0 = nb * NOUT;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // global source of the piece this lane fetches in copy j of a chunk (rows clamped; clamped rows are never stored)
+    const bf16_t *src[P];
+#pragma unroll
+    for (int j = 0; j < P; j++) {
+        const int vr = (wave * P + j) * 16 + (lane >> 2);          // row of the stage
+        const int slot = lane & 3;
+        const int seg = slot ^ ((vr >> 2) & 3);
+        const bf16_t *rowp;
+        if (vr < 2 * BM) {
+            const int r = vr % BM;
+            rowp = (vr < BM ? xhi : xlo) + (int64_t)min(t0 + r, T - 1) * K;
+        } else {
+            const int wr = vr - 2 * BM;
+            int grow;
+            if (SWI) {   // local rows of a wave column: gate tiles, then the up tiles of the same columns
+                const int wcol = wr / (BN / 2), within = wr % (BN / 2);
+                const int col = n0 + wcol * (BN / 4) + (within % (BN / 4));
+                grow = min(col, N - 1) + (within >= BN / 4 ? N : 0);
+            } else {
+                grow = min(n0 + wr, N - 1);
+            }
+            rowp = W + (int64_t)grow * K;
+        }
+        src[j] = rowp + seg * 8;
+    }
+    auto copy_chunk = [&](int kc, int st) {
+#pragma unroll
+        for (int j = 0; j < P; j++)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(src[j] + kc * BK),
+                (__attribute__((address_space(3))) void *)(lds + st * STAGE + (wave * P + j) * 1024), 16, 0, 0);
+    };
+
+    f32x16 acc[2][WCT];
+#pragma unroll
+    for (int tt = 0; tt < 2; tt++)
+#pragma unroll
+        for (int wc = 0; wc < WCT; wc++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) acc[tt][wc][i] = 0.f;
+
+    struct Frags { bf16x8 a[2][2], bw[WCT]; };
+    auto load_frags = [&](Frags &f, int st, int kstep) {
+        const char *base = lds + st * STAGE;
+        const int seg = kstep * 2 + half;
+#pragma unroll
+        for (int part = 0; part < 2; part++)
+#pragma unroll
+            for (int tt = 0; tt < 2; tt++) {
+                const int r = wm * 64 + tt * 32 + l32;       // BM is a multiple of 16: (r >> 2) & 3 is the stage row's
+                f.a[part][tt] = __builtin_bit_cast(
+                    bf16x8, *reinterpret_cast<const u32x4 *>(base + (part * BM + r) * 64 + ((seg ^ ((r >> 2) & 3)) * 16)));
+            }
+#pragma unroll
+        for (int wc = 0; wc < WCT; wc++) {
+            const int r = wn * (BN / 2) + wc * 32 + l32;
+            f.bw[wc] = __builtin_bit_cast(
+                bf16x8, *reinterpret_cast<const u32x4 *>(base + (2 * BM + r) * 64 + ((seg ^ ((r >> 2) & 3)) * 16)));
+        }
+    };
+    auto mfmas = [&](const Frags &f) {
+#pragma unroll
+        for (int part = 0; part < 2; part++)
+#pragma unroll
+            for (int tt = 0; tt < 2; tt++)
+#pragma unroll
+                for (int wc = 0; wc < WCT; wc++)
+                    acc[tt][wc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[part][tt], f.bw[wc], acc[tt][wc], 0, 0, 0);
+    };
+    // Wait until this wave's copies of the oldest outstanding chunk have landed; `younger` later chunks
+    // (P copies each) may stay in flight.  The count is an immediate, so only the steady-state values are
+    // spelled out; near the end of a slab waiting for everything is exact enough.
+    auto wait_copies = [&](int younger) {
+        if (younger >= S - 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * P) : "memory");
+        else if (S >= 4 && younger == S - 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S >= 4 ? S - 3 : 0) * P) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
+
+    // Software pipeline.  The operand registers of a K step are read from LDS while the MFMAs of the step
+    // before run; the barrier that makes chunk c + 1 visible sits in the middle of chunk c's arithmetic.
+    // After that barrier every wave has finished reading chunk c - 1, whose stage the copies of chunk
+    // c + S - 1 then overwrite (S stages hold chunks c - 1 .. c + S - 2 until then).
+    const int c_begin = (int)((int64_t)kz * (K / BK) / ks), c_end = (int)((int64_t)(kz + 1) * (K / BK) / ks);
+    const int n_chunks = c_end - c_begin;
+#pragma unroll
+    for (int d = 0; d < S - 1; d++)
+        if (d < n_chunks) copy_chunk(c_begin + d, d);
+    wait_copies(min(n_chunks, S - 1) - 1);
+    asm volatile("s_barrier" ::: "memory");
+    Frags f0, f1;
+    load_frags(f0, 0, 0);
+    int st = 0;
+    // issue order inside a half step: one operand read after every second MFMA, so that the reads are in
+    // flight under the arithmetic of the half step before the one that needs them
+    auto interleave = [&]() {
+#pragma unroll
+        for (int k = 0; k < 4 + WCT; k++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // 2 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+        }
+    };
+    for (int i = 0; i + 1 < n_chunks; i++) {      // every chunk but the last: the next one always exists
+        load_frags(f1, st, 1);
+        mfmas(f0);
+        interleave();
+        const int st1 = st + 1 == S ? 0 : st + 1;
+        // copies outstanding now: chunks i+1 .. min(i+S-2, n-1); younger than chunk i+1: that many minus one
+        wait_copies(min(i + S - 2, n_chunks - 1) - (i + 1));
+        asm volatile("s_barrier" ::: "memory");
+        if (i + S - 1 < n_chunks) copy_chunk(c_begin + i + S - 1, st == 0 ? S - 1 : st - 1);
+        load_frags(f0, st1, 0);
+        mfmas(f1);
+        interleave();
+        st = st1;
+    }
+    load_frags(f1, st, 1);
+    mfmas(f0);
+    mfmas(f1);
+
+    // accumulator element i of lane (l32, half): token t0 + wm*64 + tt*32 + 8*(i/4) + 4*half + i%4
+    constexpr int WOUT = SWI ? WCT / 2 : WCT;     // output column tiles per wave
+    const int ncols = SWI ? 2 * N : N;            // row length of the partial-sum buffer
+#pragma unroll
+    for (int wc = 0; wc < WOUT; wc++) {
+        const int n = n0 + wn * (NOUT / 2) + wc * 32 + l32;
+        if (n >= N) continue;
+#pragma unroll
+        for (int tt = 0; tt < 2; tt++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const int t = t0 + wm * 64 + tt * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+                if (t >= T) continue;
+                if (ks > 1) {
+                    float *dst = partial + ((int64_t)kz * T + t) * ncols + n;
+                    dst[0] = acc[tt][wc][i];
+                    if constexpr (SWI) dst[N] = acc[tt][wc + WCT / 2][i];
+                } else {
+                    float *dst = y + (int64_t)t * N + n;
+                    if constexpr (EPI == ld::GEMM_STORE) *dst = acc[tt][wc][i];
+                    else if constexpr (EPI == ld::GEMM_ADD) *dst += acc[tt][wc][i];
+                    else {
+                        const float gate = acc[tt][wc][i], up = acc[tt][wc + WCT / 2][i];
+                        *dst = gate / (1.0f + __expf(-gate)) * up;
+                    }
+                }
+            }
+    }
+}
+
 // Adds the ks K-slab partial sums in slab order and applies the epilogue.  One thread per output.
 template <int EPI>
 __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__ partial, int T, int N, int ks,
@@ -478,7 +663,7 @@ struct BigPlan { int wm, bn, n_ttiles, n_nblocks, ks; };
 BigPlan plan_big(int T, int N, int K, int epi) {
     const bool swi = epi == ld::GEMM_SWIGLU;
     struct Tile { int wm, bn; double tflops; };           // nominal (unsplit) TFLOP/s of a full grid
-    static const Tile tiles[3] = {{4, 256, 480.0}, {2, 256, 380.0}, {2, 128, 300.0}};
+    static const Tile tiles[3] = {{4, 256, 520.0}, {2, 256, 410.0}, {2, 128, 300.0}};
     BigPlan best{};
     double best_t = 1e30;
     const char *forced = getenv("LD_GEMM_BIG");            // tuning knob: "wm,bn,ks"
@@ -593,6 +778,32 @@ void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int
                   p.n_ttiles, p.ks, partial);                                                                          \
         if (p.ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, p.ks, y);       \
     } while (0)
+#define LD_DMA(WM_, BN_, S_, EPI_)                                                                                     \
+    do {                                                                                                               \
+        constexpr int lds_bytes = (2 * 64 * WM_ + BN_) * 64 * S_;                                                      \
+        static bool attr_set = false;                                                                                  \
+        if (!attr_set) {                                                                                               \
+            (void)hipFuncSetAttribute((const void *)k_gemm_dma<WM_, BN_, S_, EPI_>,                                    \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);                          \
+            attr_set = true;                                                                                           \
+        }                                                                                                              \
+        LD_LAUNCH((k_gemm_dma<WM_, BN_, S_, EPI_>), dim3(grid), dim3(128 * WM_), lds_bytes, s, W, hi, lo, T, N, K, y,   \
+                  p.n_ttiles, p.ks, partial);                                                                          \
+        if (p.ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, p.ks, y);       \
+    } while (0)
+        // 256-row weight tiles: operands copied straight into LDS (the slab needs a few chunks to fill the stages)
+        if (p.bn == 256 && (K / 32) / p.ks >= 4) {
+            if (p.wm == 4) {
+                if (epi == GEMM_STORE) LD_DMA(4, 256, 3, GEMM_STORE);
+                else if (epi == GEMM_ADD) LD_DMA(4, 256, 3, GEMM_ADD);
+                else LD_DMA(4, 256, 3, GEMM_SWIGLU);
+            } else {
+                if (epi == GEMM_STORE) LD_DMA(2, 256, 4, GEMM_STORE);
+                else if (epi == GEMM_ADD) LD_DMA(2, 256, 4, GEMM_ADD);
+                else LD_DMA(2, 256, 4, GEMM_SWIGLU);
+            }
+            return;
+        }
         if (p.wm == 4) {
             if (epi == GEMM_STORE) LD_BIG(4, 256, 3, GEMM_STORE);
             else if (epi == GEMM_ADD) LD_BIG(4, 256, 3, GEMM_ADD);

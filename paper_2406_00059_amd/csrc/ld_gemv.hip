@@ -107,6 +107,14 @@ __global__ __launch_bounds__(1024) void k_gemv1(const bf16_t *__restrict__ W, co
     const int u_begin = (int)((int64_t)blockIdx.x * n_units / gridDim.x);
     const int u_end = (int)((int64_t)(blockIdx.x + 1) * n_units / gridDim.x);
     const int n_groups = (u_end - u_begin + UG - 1) / UG;
+    // cache append: position and physical block are looked up once, up front, so that the chain of dependent
+    // loads (position -> block table) overlaps the weight stream instead of ending every output group
+    int kv_pos = 0;
+    int64_t kv_phys = 0;
+    if constexpr (EPI == ld::GEMV_ROPE_KV) {
+        kv_pos = rk.pos[0];
+        kv_phys = rk.table[(int64_t)rk.seq_slot[0] * rk.table_stride + (kv_pos >> 4)];
+    }
 
     __shared__ float part[2][MAX_WAVES][MAX_GL];
     __shared__ float part_ss[MAX_WAVES];
@@ -212,10 +220,8 @@ __global__ __launch_bounds__(1024) void k_gemv1(const bf16_t *__restrict__ W, co
                 } else {
                     const int which = hh < rk.H + rk.Hkv ? 0 : 1;
                     const int j = hh - rk.H - which * rk.Hkv;
-                    const int p = rk.pos[0];
-                    const int64_t phys = rk.table[(int64_t)rk.seq_slot[0] * rk.table_stride + (p >> 4)];
-                    bf16_t *blk = rk.pool + phys * kv_block_elems(rk.Hkv, hd);
-                    const int slot = p & 15;
+                    bf16_t *blk = rk.pool + kv_phys * kv_block_elems(rk.Hkv, hd);
+                    const int slot = kv_pos & 15;
                     if (which == 0) {
                         blk[kv_k_offset(hd, j, slot, i)] = f32_to_bf16(a);
                         blk[kv_k_offset(hd, j, slot, i + half_hd)] = f32_to_bf16(b);

@@ -107,15 +107,6 @@ __global__ __launch_bounds__(1024) void k_gemv1(const bf16_t *__restrict__ W, co
     const int u_begin = (int)((int64_t)blockIdx.x * n_units / gridDim.x);
     const int u_end = (int)((int64_t)(blockIdx.x + 1) * n_units / gridDim.x);
     const int n_groups = (u_end - u_begin + UG - 1) / UG;
-    // cache append: position and physical block are looked up once, up front, so that the chain of dependent
-    // loads (position -> block table) overlaps the weight stream instead of ending every output group
-    int kv_pos = 0;
-    int64_t kv_phys = 0;
-    if constexpr (EPI == ld::GEMV_ROPE_KV) {
-        kv_pos = rk.pos[0];
-        kv_phys = rk.table[(int64_t)rk.seq_slot[0] * rk.table_stride + (kv_pos >> 4)];
-    }
-
     __shared__ float part[2][MAX_WAVES][MAX_GL];
     __shared__ float part_ss[MAX_WAVES];
 
@@ -148,6 +139,16 @@ __global__ __launch_bounds__(1024) void k_gemv1(const bf16_t *__restrict__ W, co
     };
     if (n_groups > 0) issue(bufA, 0);
 
+    // cache append: position and physical block are looked up once, right after the first weight loads are
+    // on their way, so that the chain of dependent loads (position -> block table) overlaps the weight
+    // stream instead of ending every output group
+    int kv_pos = 0;
+    int64_t kv_phys = 0;
+    if constexpr (EPI == ld::GEMV_ROPE_KV) {
+        kv_pos = rk.pos[0];
+        kv_phys = rk.table[(int64_t)rk.seq_slot[0] * rk.table_stride + (kv_pos >> 4)];
+    }
+
     // this wave's slice of the input (gain applied), and its share of the sum of squares
     float xs[CPW][8];
     float ss = 0.f;
@@ -176,6 +177,13 @@ __global__ __launch_bounds__(1024) void k_gemv1(const bf16_t *__restrict__ W, co
     float rstd = 1.f;
 
     auto consume = [&](u32x4_t (&buf)[G][CPW], int gi) {
+        // the old value for the residual add is requested before the arithmetic, not after the barrier
+        const int u = u_begin + gi * UG + (int)threadIdx.x;
+        const bool mine = threadIdx.x < UG && u < u_end;
+        float pre0 = 0.f;
+        if constexpr (EPI == ld::GEMV_ADD) {
+            if (mine) pre0 = y[u];
+        }
         float acc[G];
 #pragma unroll
         for (int r = 0; r < G; r++) {
@@ -191,8 +199,7 @@ __global__ __launch_bounds__(1024) void k_gemv1(const bf16_t *__restrict__ W, co
             for (int w = 0; w < nwaves; w++) s2 += part_ss[w];
             rstd = 1.0f / sqrtf(s2 / K + eps);
         }
-        const int u = u_begin + gi * UG + (int)threadIdx.x;
-        if (threadIdx.x < UG && u < u_end) {
+        if (mine) {
             float a = 0.f, b = 0.f;
             for (int w = 0; w < nwaves; w++) {
                 a += part[gi & 1][w][threadIdx.x];
@@ -203,7 +210,7 @@ __global__ __launch_bounds__(1024) void k_gemv1(const bf16_t *__restrict__ W, co
             if constexpr (EPI == ld::GEMV_STORE) {
                 y[u] = a;
             } else if constexpr (EPI == ld::GEMV_ADD) {
-                y[u] += a;
+                y[u] = pre0 + a;
             } else if constexpr (EPI == ld::GEMV_SWIGLU) {
                 y[u] = a / (1.0f + __expf(-a)) * b;
             } else {

@@ -345,9 +345,15 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const 
                                                w.lin_scratch_bytes, st));
         LD_TIMED(LD_PROF_DOWN, ldk_linear(m.wdown[l], c.dtype, w.act, nullptr, 0.f, T, d, c.d_ffn, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st));
     }
-    LD_TIMED(LD_PROF_OTHER, ldk_rmsnorm(w.x, m.final_norm, d_emit, R, d, c.rms_eps, w.hn, st));
-    LD_TIMED(LD_PROF_LM_HEAD, ldk_linear(m.lm_head, c.dtype, w.hn, nullptr, 0.f, R, c.vocab, d, LDK_STORE, w.logits, w.lin_scratch,
-                                      w.lin_scratch_bytes, st));
+    if (T == 1 && R == 1) {
+        // one row, and it emits: the final norm rides in the LM head's own pass over x (as in every layer)
+        LD_TIMED(LD_PROF_LM_HEAD, ldk_linear(m.lm_head, c.dtype, w.x, m.final_norm, c.rms_eps, 1, c.vocab, d, LDK_STORE, w.logits,
+                                             w.lin_scratch, w.lin_scratch_bytes, st));
+    } else {
+        LD_TIMED(LD_PROF_OTHER, ldk_rmsnorm(w.x, m.final_norm, d_emit, R, d, c.rms_eps, w.hn, st));
+        LD_TIMED(LD_PROF_LM_HEAD, ldk_linear(m.lm_head, c.dtype, w.hn, nullptr, 0.f, R, c.vocab, d, LDK_STORE, w.logits,
+                                             w.lin_scratch, w.lin_scratch_bytes, st));
+    }
     if (sampling)
         LD_TIMED(LD_PROF_OTHER, ldk_sample(w.logits, R, c.vocab, reinterpret_cast<const float *>(w.meta + samp_off + 2 * R),
                                            reinterpret_cast<const uint64_t *>(w.meta + samp_off), w.meta + samp_off + 3 * R,

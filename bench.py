@@ -26,7 +26,7 @@ HBM_PEAK = 8.0e12          # bytes/s, MI355X HBM3E
 # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE counters, scaled by a
 # 256 MiB copy (profiles/gate_up_gemv_hbm_traffic.md); valid only for the kernel source it was taken on.
 TRAFFIC_BYTES = 180_870_000
-TRAFFIC_KERNEL_MD5 = "e104d8df9308"
+TRAFFIC_KERNEL_MD5 = "0468ef4efdc5"
 ROUND_TOKENS = 256         # tokens emitted per round (1 by the preceding prefill + 255 decode steps)
 CHUNK = 256
 

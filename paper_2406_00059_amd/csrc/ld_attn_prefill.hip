@@ -269,6 +269,7 @@ int prefill_attention_splits(int n_tiles, int H, int max_pos, int window, size_t
     s = std::min(s, 8);
     const size_t per_split = (size_t)n_tiles * 128 * H * (HD + 2) * sizeof(float);
     if (per_split) s = (int)std::min<size_t>(s, scratch_bytes / per_split);
+    if (n_tiles * 128 > 65535) s = 1;       // the merge launch has one grid row per tile row slot
     return std::max(s, 1);
 }
 

@@ -270,3 +270,101 @@ def test_sampled_and_greedy_sequences_in_one_batch():
     for _ in range(24):
         ld.ld_decode_step(Q.gkv.h, [s], callback=solo)
     assert [t for _, t, _ in solo.log] == toks[a]
+
+
+@pytest.mark.parametrize("shape,tol,seed", [
+    (TINY, 1e-4, 1), (TINY, 1e-4, 2),
+    (replace(TINY, dtype="bf16", n_kv_heads=2, name="tiny-bf16-gqa"), 2e-2, 3),
+    (replace(TINY, dtype="bf16", n_kv_heads=1, window=40, name="tiny-bf16-gqa-band"), 2e-2, 4),
+    (replace(TINY, window=21, name="tiny-band"), 1e-4, 5)])
+def test_random_schedule_of_every_operation(shape, tol, seed):
+    """All the sequence operations interleaved by a seeded schedule, the oracle and the library driven in
+    lockstep: new requests (greedy or sampled) with chunked prompts, batched decode in random order, mixed
+    steps, observations, forks at random prefix lengths, swap out / in, frees.  After every operation the
+    free-block counts, block tables and lengths agree; every emitted token equals the oracle's and every
+    logits row is within tolerance."""
+    rng = np.random.default_rng(seed)
+    P = Pair(shape, 16 + seed, n_blocks=64, max_tokens=64, max_seqs=6, max_blocks=10, max_chunk=16)
+    h, V = P.gkv.h, shape.vocab
+    run, away = [], {}                                   # decodable sequences; swapped ones -> (host buffer, oracle store)
+    sink, errs, stream, counts = Tokens(), [], [0], {}
+
+    def fresh(n):
+        stream[0] += 1
+        return prompt(100 + seed, stream[0], n, V)
+
+    def room(s, extra):
+        return ld.ld_kv_len(h, s) + 1 + extra <= 150
+
+    def sampling(s):
+        t = float(rng.choice([0.0, 0.0, 0.6, 1.0]))
+        sd = int(rng.integers(0, 2 ** 63))
+        assert P.okv.set_sampling(s, t, sd) == 0 and ld.ld_kv_set_sampling(h, s, t, sd) == 0
+
+    def feed(s, toks):
+        rc, t, lg_o = P.okv.prefill(s, toks)
+        rc_g, lg = ld.ld_prefill(h, s, toks, callback=sink, logits_vocab=V)
+        assert rc == 0 and sink.last() == [t]
+        errs.append(rel_err(lg, lg_o))
+
+    for it in range(140):
+        ops = ["new"] * (len(run) + len(away) < 6) + ["decode", "decode", "mixed", "obs", "fork"] * bool(run) \
+            + ["out"] * bool(run) + ["in", "in"] * bool(away) + ["free"] * (len(run) + len(away) > 2)
+        op = str(rng.choice(ops))
+        counts[op] = counts.get(op, 0) + 1
+        if op == "new":
+            s = P.alloc(); sampling(s); feed(s, fresh(int(rng.integers(1, 45)))); run.append(s)
+        elif op == "decode":
+            order = [s for s in rng.permutation(run).tolist() if room(s, 0)][: int(rng.integers(1, 7))]
+            if not order:
+                continue
+            ref = [P.okv.decode(s) for s in order]
+            rc, lg = ld.ld_decode_step(h, order, callback=sink, logits_vocab=V)
+            assert [(q, t) for q, t, _ in sink.log[-len(order):]] == [(s, r[1]) for s, r in zip(order, ref)], (it, op)
+            errs += [rel_err(lg[i], r[2]) for i, r in enumerate(ref)]
+        elif op == "mixed":
+            order = rng.permutation(run).tolist()
+            n_pf = int(rng.integers(1, min(3, len(order)) + 1))
+            pf = [s for s in order[:n_pf] if room(s, 12)]
+            dec = [s for s in order[n_pf:] if room(s, 0)]
+            if not pf:
+                continue
+            obs = [fresh(int(rng.integers(1, 13))) for _ in pf]
+            ref = [P.okv.decode(s) for s in dec] + [P.okv.prefill(s, o) for s, o in zip(pf, obs)]
+            rc, lg = ld.ld_step_mixed(h, dec, pf, obs, callback=sink, logits_vocab=V)
+            assert [(q, t) for q, t, _ in sink.log[-len(ref):]] == [(s, r[1]) for s, r in zip(dec + pf, ref)], (it, op)
+            errs += [rel_err(lg[i], r[2]) for i, r in enumerate(ref)]
+        elif op == "obs":
+            s = int(rng.choice(run))
+            if room(s, 40):
+                feed(s, fresh(int(rng.integers(1, 41))))
+        elif op == "fork":
+            parent = int(rng.choice(run))
+            if len(run) + len(away) >= 6:
+                continue
+            n = int(rng.integers(1, ld.ld_kv_len(h, parent) + 1))
+            rc, co = P.okv.fork(parent, n)
+            cg = ld.ld_kv_fork(h, parent, n)
+            assert rc == 0 and co == cg and ld.ld_kv_len(h, cg) == n
+            sampling(cg); feed(cg, fresh(int(rng.integers(1, 9)))); run.append(cg)
+        elif op == "out":
+            s = int(rng.choice(run))
+            host = torch.empty(ld.ld_kv_swap_bytes(h, s), dtype=torch.uint8, pin_memory=bool(rng.integers(0, 2)))
+            rc, store = P.okv.swap_out(s)
+            assert rc == 0 and ld.ld_kv_swap_out(h, s, host) == 0
+            run.remove(s); away[s] = (host, store)
+        elif op == "in":
+            s = int(rng.choice(list(away)))
+            host, store = away.pop(s)
+            assert P.okv.swap_in(s, store) == 0 and ld.ld_kv_swap_in(h, s, host) == 0
+            run.append(s)
+        elif op == "free":
+            s = int(rng.choice(run + list(away)))
+            assert P.okv.free(s) == 0
+            ld.ld_kv_free(h, s)
+            run.remove(s) if s in run else away.pop(s)
+        assert ld.ld_kv_free_blocks(h) == P.okv.free_blocks(), (it, op)
+        for s in run + list(away):
+            assert P.tables_equal(s) and ld.ld_kv_len(h, s) == P.okv.length(s), (it, op, s)
+    assert max(errs) <= tol, max(errs)
+    assert min(counts.get(k, 0) for k in ("new", "decode", "mixed", "obs", "fork", "out", "in", "free")) >= 2, counts

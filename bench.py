@@ -2,10 +2,12 @@
 """Decode throughput of the 7B-shaped bf16 decoder on one MI355X, tool-call pattern.
 
 Workload (batch 1): prompt of 1024 random token ids, then rounds of "greedily emit 256 tokens, append a
-128..512-token random observation through chunked prefill (chunk 256)".  A *step* is one ld_decode_step
-call: the whole decode pass (32 layers + LM head + argmax), the token hand-off to the host and the
-callback.  `value` is decode tokens/s over exactly --steps timed steps; prompt and observation prefills
-run between the timed steps and are reported beside it.  Inputs (weights, tokens) are seeded and
+128..512-token random observation through chunked prefill (chunk 256)".  A *step* is one decode iteration:
+the whole decode pass (32 layers + LM head + argmax), the token hand-off to the host and the callback.  The
+steps of a round run inside one ld_decode_run call, which enqueues step k+1 before it hands over the token
+of step k (the callback still sees every token, one step behind the GPU).  `value` is decode tokens/s over
+exactly --steps timed steps; prompt and observation prefills run between the rounds and are reported
+beside it.  Inputs (weights, tokens) are seeded and
 synthetic and are resident in HBM before timing starts.
 
 Prints ONE JSON line.  `roofline` describes the kernel with the largest share of the step
@@ -110,8 +112,7 @@ def run_batch1(args, ld, torch, shape, weights, model):
     # warm-up on a throw-away sequence
     ws = ld.ld_kv_alloc(kv.h, 0)
     ld.ld_prefill(kv.h, ws, gen.randint(seed, 90, 0, shape.vocab - 1, 64).numpy().astype(np.int32), stream, noop_cb)
-    for _ in range(W):
-        ld.ld_decode_step(kv.h, [ws], stream, noop_cb)
+    ld.ld_decode_run(kv.h, [ws], W, stream, noop_cb)
     ld.ld_kv_free(kv.h, ws)
 
     s = ld.ld_kv_alloc(kv.h, 0)
@@ -130,12 +131,13 @@ def run_batch1(args, ld, torch, shape, weights, model):
     t_begin = time.perf_counter()
     for r in range(rounds):
         n = min(ROUND_TOKENS - 1, K - done)
-        for _ in range(n):
-            ctx = ld.ld_kv_len(kv.h, s) + 1
-            t0 = time.perf_counter()
-            ld.ld_decode_step(kv.h, [s], stream, noop_cb)
-            step_ms.append((time.perf_counter() - t0) * 1e3)
-            step_bytes.append(Wb + ctx * kappa)
+        ctx = ld.ld_kv_len(kv.h, s) + 1
+        stamps = [time.perf_counter()]
+        rc, got = ld.ld_decode_run(kv.h, [s], n, stream, lambda q, tok, pos: stamps.append(time.perf_counter()) and 0)
+        stamps[-1] = time.perf_counter()                     # the call returns right after the last callback
+        assert got == n
+        step_ms += [(b - a) * 1e3 for a, b in zip(stamps, stamps[1:])]
+        step_bytes += [Wb + (ctx + i) * kappa for i in range(n)]
         done += n
         if done >= K and r == rounds - 1 and n < ROUND_TOKENS - 1:
             break
@@ -247,8 +249,8 @@ def run_batch32(args, ld, torch, shape, model):
     Wb, kappa = shape.weight_bytes_per_step, shape.kv_bytes_per_token
     visible = (lambda n: min(n, shape.window)) if shape.window else (lambda n: n)   # positions a decode row reads
     t_begin = time.perf_counter()
-    for step in range(1, steps + 1):
-        sum_ctx = sum(visible(ld.ld_kv_len(kv.h, s) + 1) for s in seqs)
+    step = 1
+    while step <= steps:
         if step % 16 == 0:
             pick = gen.permutation(seed, 3000 + step, B)[:4].tolist()
             pf = [seqs[i] for i in pick]
@@ -257,11 +259,17 @@ def run_batch32(args, ld, torch, shape, model):
             t0 = time.perf_counter()
             ld.ld_step_mixed(kv.h, dec, pf, obs, stream, noop_cb)
             mixed_ms.append((time.perf_counter() - t0) * 1e3)
+            step += 1
         else:
+            n = min(16 - step % 16, steps - step + 1)        # the pure decode steps up to the next mixed one
+            lens_now = [ld.ld_kv_len(kv.h, s) + 1 for s in seqs]
             t0 = time.perf_counter()
-            ld.ld_decode_step(kv.h, seqs, stream, noop_cb)
-            pure_ms.append((time.perf_counter() - t0) * 1e3)
-            pure_bytes.append(Wb + sum_ctx * kappa)
+            rc, got = ld.ld_decode_run(kv.h, seqs, n, stream, noop_cb)
+            dt = (time.perf_counter() - t0) * 1e3
+            assert got == n
+            pure_ms += [dt / n] * n
+            pure_bytes += [Wb + sum(visible(c + i) for c in lens_now) * kappa for i in range(n)]
+            step += n
     torch.cuda.synchronize()
     total = time.perf_counter() - t_begin
     ld.ld_kv_profile(kv.h, True)

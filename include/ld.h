@@ -82,8 +82,13 @@ typedef struct {
 
 /* Called once per emitted token, on the calling thread, in ascending order of the
  * sequence's index in the step's argument list.  `pos` is the absolute position the
- * token will occupy once fed.  A non-zero return marks the sequence stopped (early
- * abort, section 4.3 case #2): stepping it again returns LD_E_STATE until it is freed. */
+ * token will occupy once fed.  Return LD_CB_CONTINUE to go on.  LD_CB_PAUSE ends a multi-step
+ * run (ld_decode_run) after the current step and leaves the sequence as it is (a tool call is
+ * complete and its observation comes next); in single-step calls it means the same as
+ * LD_CB_CONTINUE.  Any other value marks the sequence stopped (early abort, section 4.3 case #2):
+ * stepping it again returns LD_E_STATE until it is freed.  The callback must not call into the
+ * library for the same cache. */
+enum { LD_CB_CONTINUE = 0, LD_CB_ABORT = 1, LD_CB_PAUSE = 2 };
 typedef int (*ld_token_cb)(void *user, ld_seq seq, int32_t token, int32_t pos);
 
 /* Registers a model (section 3.3 step (a)).  Validates shapes, copies the configuration
@@ -173,6 +178,21 @@ ld_status ld_prefill(ld_kv *kv, ld_seq seq, const int32_t *tokens, int32_t n, vo
  * logits_out: HOST float[n_seqs, vocab] or NULL. */
 ld_status ld_decode_step(ld_kv *kv, const ld_seq *seqs, int32_t n_seqs, void *stream,
                          ld_token_cb cb, void *user, float *logits_out);
+
+/* Up to max_steps decode iterations for the same n_seqs sequences, with the callback one step behind the
+ * GPU (section 3.3: every decoding iteration hands its tokens to the parser while the model goes on
+ * decoding): step k+1 is enqueued before the tokens of step k are handed over, its input tokens read on the
+ * device from what step k emitted, so parsing, the callback and the launch work of the next step overlap
+ * the current step instead of leaving the GPU idle between steps.  Tokens, callback order and the state of
+ * every sequence after the call are exactly those of *steps_done successive ld_decode_step calls.
+ * The run ends after max_steps steps, after the first step in which a callback returns non-zero
+ * (LD_CB_PAUSE: the sequence stays live; other values: it is stopped), or before a step whose blocks cannot
+ * be reserved (then *steps_done < max_steps and no callback asked for the end; with no step done at all the
+ * error itself is returned).  When a callback ends the run, the one step already enqueued beyond it is
+ * discarded: its block reservations are returned and the call waits for it to drain, which costs one step
+ * of GPU time; give max_steps the exact count when it is known.  steps_done: HOST, may be NULL. */
+ld_status ld_decode_run(ld_kv *kv, const ld_seq *seqs, int32_t n_seqs, int32_t max_steps, void *stream,
+                        ld_token_cb cb, void *user, int32_t *steps_done);
 
 /* One mixed iteration of continuous batching: n_dec decoding sequences plus n_pf sequences that
  * each get [pending?] ++ pf_tokens[i][0..pf_n[i]) prefilled in the same pass (one chunk each,

@@ -11,15 +11,17 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libld.so")
 
 LD_OK, LD_E_INVAL, LD_E_NOMEM, LD_E_STATE, LD_E_HIP, LD_E_RANGE = 0, -1, -2, -3, -4, -5
+LD_CB_CONTINUE, LD_CB_ABORT, LD_CB_PAUSE = 0, 1, 2
 LD_F32, LD_BF16 = 0, 1
 LDK_STORE, LDK_ADD, LDK_SWIGLU = 0, 1, 2
 
 __all__ = [
     "LD_OK", "LD_E_INVAL", "LD_E_NOMEM", "LD_E_STATE", "LD_E_HIP", "LD_E_RANGE", "LD_F32", "LD_BF16",
+    "LD_CB_CONTINUE", "LD_CB_ABORT", "LD_CB_PAUSE",
     "LDK_STORE", "LDK_ADD", "LDK_SWIGLU", "LIB_PATH", "lib", "LdError", "ld_model_config", "ld_weights",
     "ld_token_cb", "ld_model_create", "ld_model_destroy", "ld_kv_bytes", "ld_workspace_bytes", "ld_kv_create",
     "ld_kv_destroy", "ld_kv_alloc", "ld_kv_map", "ld_kv_free", "ld_kv_block_table", "ld_kv_len",
-    "ld_kv_free_blocks", "ld_kv_assume", "ld_kv_swap_bytes", "ld_kv_swap_out", "ld_kv_swap_in", "ld_kv_fork", "ld_kv_set_sampling", "ld_prefill", "ld_decode_step", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
+    "ld_kv_free_blocks", "ld_kv_assume", "ld_kv_swap_bytes", "ld_kv_swap_out", "ld_kv_swap_in", "ld_kv_fork", "ld_kv_set_sampling", "ld_prefill", "ld_decode_step", "ld_decode_run", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
     "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
     "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_prefill_attention_scratch_bytes",
     "ldk_prefill_attention", "ldk_argmax", "ldk_sample", "Model", "KV",
@@ -80,6 +82,7 @@ _SIGS = {
     "ld_kv_swap_in": (C.c_int, [_vp, C.c_int32, _vp, C.c_size_t, _vp]),
     "ld_prefill": (C.c_int, [_vp, C.c_int32, _i32p, C.c_int32, _vp, ld_token_cb, _vp, _f32p]),
     "ld_decode_step": (C.c_int, [_vp, _i32p, C.c_int32, _vp, ld_token_cb, _vp, _f32p]),
+    "ld_decode_run": (C.c_int, [_vp, _i32p, C.c_int32, C.c_int32, _vp, ld_token_cb, _vp, _i32p]),
     "ld_step_mixed": (C.c_int, [_vp, _i32p, C.c_int32, _i32p, C.POINTER(_i32p), _i32p, C.c_int32, _vp,
                                 ld_token_cb, _vp, _f32p]),
     "ld_kv_profile": (C.c_int, [_vp, C.c_int32]),
@@ -249,10 +252,14 @@ def ld_kv_swap_in(kv, seq, host_buf, stream=None, check=True):
 
 
 def _cb(callback):
-    """Wrap a Python callable (seq, token, pos) -> truthy-to-stop as an ld_token_cb (or a null one)."""
+    """Wrap a Python callable (seq, token, pos) as an ld_token_cb (or a null one): LD_CB_PAUSE passes through,
+    any other truthy value stops the sequence."""
     if callback is None:
         return C.cast(None, ld_token_cb)
-    return ld_token_cb(lambda user, seq, tok, pos: 1 if callback(seq, tok, pos) else 0)
+    def call(user, seq, tok, pos):
+        r = callback(seq, tok, pos)
+        return LD_CB_PAUSE if r is not True and r == LD_CB_PAUSE else (LD_CB_ABORT if r else LD_CB_CONTINUE)
+    return ld_token_cb(call)
 
 
 def _logits_buf(want, rows, vocab):
@@ -278,6 +285,15 @@ def ld_decode_step(kv, seqs, stream=None, callback=None, logits_vocab=0, check=T
     cb = _cb(callback)
     rc = _check(lib().ld_decode_step(kv, sp, s.size, _stream(stream), cb, None, lp), check)
     return rc, lg
+
+
+def ld_decode_run(kv, seqs, max_steps, stream=None, callback=None, check=True):
+    """Returns (status, steps done)."""
+    s, sp = _i32(seqs)
+    cb = _cb(callback)
+    done = C.c_int32(0)
+    rc = _check(lib().ld_decode_run(kv, sp, s.size, max_steps, _stream(stream), cb, None, C.byref(done)), check)
+    return rc, done.value
 
 
 def ld_step_mixed(kv, dec, pf, pf_tokens, stream=None, callback=None, logits_vocab=0, check=True):

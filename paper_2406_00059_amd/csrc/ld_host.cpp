@@ -129,8 +129,12 @@ struct ld_kv {
     std::vector<int32_t> refs;   // sequences holding each block (prefix sharing); 0 = on the free stack
     std::vector<Seq> seqs;
     std::vector<int32_t> table;  // host copy [max_seqs][max_blocks], -1 = unmapped
-    // pinned staging, created by the first pass
+    // pinned staging, created by the first pass.  Metadata and emitted tokens are double-buffered (two
+    // slots) so that a step can be prepared while the previous one is still in flight; step_ev[slot] marks
+    // the end of the pass that used the slot.
     int32_t *pin_meta = nullptr, *pin_out = nullptr, *pin_table = nullptr;
+    hipEvent_t step_ev[2] = {nullptr, nullptr};
+    size_t meta_ints() const { return (size_t)max_tokens * 9 + 2 + (size_t)max_seqs * 4; }
     // optional per-kernel timing
     bool prof_on = false;
     ld_profile prof{};
@@ -204,19 +208,21 @@ void release_blocks(ld_kv *kv, int s) {
 
 ld_status ensure_pinned(ld_kv *kv) {
     if (kv->pin_meta) return LD_OK;
-    LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_meta, ((size_t)kv->max_tokens * 9 + 2 + (size_t)kv->max_seqs * 4) * 4,
-                             hipHostMallocDefault));
-    LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_out, (size_t)kv->max_seqs * 4, hipHostMallocDefault));
+    LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_out, (size_t)2 * kv->max_seqs * 4, hipHostMallocDefault));
     LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_table, (size_t)kv->max_seqs * kv->max_blocks * 4, hipHostMallocDefault));
+    for (hipEvent_t &e : kv->step_ev) LD_HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_meta, 2 * kv->meta_ints() * 4, hipHostMallocDefault));
     return LD_OK;
 }
 
-// Runs one pass over `rows` (all rows' blocks are mapped).  emit[i] = index of the row whose
-// logits / greedy token are wanted, in callback order.  On return pin_out[i] holds the tokens.
-// Rows [0, n_single) are one-row segments (decode rows); the rest form multi-row prefill segments,
-// each a run of consecutive rows of one sequence at consecutive positions.
-ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const std::vector<int32_t> &emit,
-                   hipStream_t st, float *logits_out) {
+// Enqueues one pass over `rows` (all rows' blocks are mapped) without waiting for it.  emit[i] = index of
+// the row whose logits / greedy token are wanted, in callback order; once step_ev[slot] has passed,
+// pin_out[slot * max_seqs + i] holds the tokens.  Rows [0, n_single) are one-row segments (decode rows);
+// the rest form multi-row prefill segments, each a run of consecutive rows of one sequence at consecutive
+// positions.  tok_from_prev: row t's input token is the token that the previous pass on this stream
+// emitted for its row t (read on the device), not rows[t].tok.
+ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const std::vector<int32_t> &emit,
+                       hipStream_t st, float *logits_out, int slot, bool tok_from_prev, int *ops) {
     const ld_model &m = *kv->m;
     const ld_model_config &c = m.c;
     const int T = (int)rows.size(), R = (int)emit.size();
@@ -225,7 +231,7 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const 
     const Workspace &w = kv->ws;
 
     // metadata: tok | pos | seq_slot | ctx_len | emit_row, each T (emit: R) entries at stride T
-    int32_t *pm = kv->pin_meta;
+    int32_t *pm = kv->pin_meta + (size_t)slot * kv->meta_ints();
     int max_ctx = 1;
     for (int t = 0; t < T; t++) {
         pm[t] = rows[t].tok;
@@ -268,7 +274,7 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const 
         meta_ints = samp_off + 4 * R;
     }
     LD_HIP_TRY(hipMemcpyAsync(w.meta, pm, (size_t)meta_ints * 4, hipMemcpyHostToDevice, st));
-    const int32_t *d_tok = w.meta, *d_pos = w.meta + T, *d_slot = w.meta + 2 * T, *d_ctx = w.meta + 3 * T,
+    const int32_t *d_tok = tok_from_prev ? w.out_tok : w.meta, *d_pos = w.meta + T, *d_slot = w.meta + 2 * T, *d_ctx = w.meta + 3 * T,
                   *d_emit = w.meta + 4 * T, *d_tiles = w.meta + 5 * T;
 
     // block-table rows that changed since the last pass
@@ -289,7 +295,6 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const 
         explicit TimerScope(ld::LaunchTimer *t) { ld::g_launch_timer = t; }
         ~TimerScope() { ld::g_launch_timer = nullptr; }
     } timer_scope(kv->prof_on ? &kv->timer : nullptr);
-    int ops[LD_PROF_N] = {0};
 #define LD_TIMED(cat_, call)          \
     do {                              \
         kv->timer.current = cat_;     \
@@ -362,9 +367,20 @@ ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const 
         LD_TIMED(LD_PROF_OTHER, ldk_argmax(w.logits, R, c.vocab, w.out_tok, st));
 #undef LD_TIMED
 #undef LD_TRY
-    if (R) LD_HIP_TRY(hipMemcpyAsync(kv->pin_out, w.out_tok, (size_t)R * 4, hipMemcpyDeviceToHost, st));
+    if (R)
+        LD_HIP_TRY(hipMemcpyAsync(kv->pin_out + (size_t)slot * kv->max_seqs, w.out_tok, (size_t)R * 4, hipMemcpyDeviceToHost, st));
     if (logits_out && R)
         LD_HIP_TRY(hipMemcpyAsync(logits_out, w.logits, (size_t)R * c.vocab * 4, hipMemcpyDeviceToHost, st));
+    LD_HIP_TRY(hipEventRecord(kv->step_ev[slot], st));
+    return LD_OK;
+}
+
+// One pass, waited for: on return pin_out[i] holds the tokens.
+ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const std::vector<int32_t> &emit,
+                   hipStream_t st, float *logits_out) {
+    int ops[LD_PROF_N] = {0};
+    ld_status rc = enqueue_pass(kv, rows, n_single, emit, st, logits_out, 0, false, ops);
+    if (rc) return rc;
     LD_HIP_TRY(hipStreamSynchronize(st));
     if (kv->prof_on) {
         if (kv->timer.failed) return fail(LD_E_HIP, "profiling: hipEventCreate failed");
@@ -454,7 +470,8 @@ ld_status run_step(ld_kv *kv, const std::vector<Feed> &feeds, void *stream, ld_t
     if (cb)
         for (size_t i = 0; i < feeds.size(); i++) {
             Seq &q = kv->seqs[feeds[i].seq];
-            if (cb(user, feeds[i].seq, q.pending, (int32_t)q.n_cached) != 0) q.stopped = true;
+            const int r = cb(user, feeds[i].seq, q.pending, (int32_t)q.n_cached);
+            if (r != LD_CB_CONTINUE && r != LD_CB_PAUSE) q.stopped = true;
         }
     return LD_OK;
 }
@@ -535,6 +552,8 @@ void ld_kv_destroy(ld_kv *kv) {
     if (kv->pin_meta) (void)hipHostFree(kv->pin_meta);
     if (kv->pin_out) (void)hipHostFree(kv->pin_out);
     if (kv->pin_table) (void)hipHostFree(kv->pin_table);
+    for (hipEvent_t e : kv->step_ev)
+        if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : kv->timer.ev) (void)hipEventDestroy(e);
     delete kv;
 }
@@ -759,6 +778,124 @@ ld_status ld_decode_step(ld_kv *kv, const ld_seq *seqs, int32_t n_seqs, void *st
         feeds.push_back({seqs[i], nullptr, 0});
     }
     return run_step(kv, feeds, stream, cb, user, logits_out, "ld_decode_step");
+}
+
+ld_status ld_decode_run(ld_kv *kv, const ld_seq *seqs, int32_t n_seqs, int32_t max_steps, void *stream, ld_token_cb cb,
+                        void *user, int32_t *steps_done) {
+    if (steps_done) *steps_done = 0;
+    if (!kv || !seqs || n_seqs <= 0 || max_steps < 0) return fail(LD_E_INVAL, "ld_decode_run: bad argument");
+    if (n_seqs > kv->max_seqs || n_seqs > kv->max_tokens) return fail(LD_E_RANGE, "ld_decode_run: too many sequences in one step");
+    std::vector<char> seen(kv->max_seqs, 0);
+    for (int i = 0; i < n_seqs; i++) {
+        Seq *q = get_seq(kv, seqs[i]);
+        if (!q) { ld::set_error("ld_decode_run: bad sequence handle %d", seqs[i]); return LD_E_INVAL; }
+        if (seen[seqs[i]]) { ld::set_error("ld_decode_run: sequence %d listed twice", seqs[i]); return LD_E_INVAL; }
+        seen[seqs[i]] = 1;
+        if (q->stopped || q->swapped || !q->has_pending) {
+            ld::set_error("ld_decode_run: sequence %d is stopped, swapped out or has no pending token", seqs[i]);
+            return LD_E_STATE;
+        }
+    }
+    if (max_steps == 0) return LD_OK;
+    hipStream_t st = (hipStream_t)stream;
+    ld_status rc = ensure_pinned(kv);
+    if (rc) return rc;
+
+    // Step k is prepared while step k-1 runs: its rows sit one position further, its blocks are reserved
+    // now, and its input tokens are read on the device from what step k-1 emits.  Every reservation is
+    // recorded so that a step that turns out to be unwanted can be taken back exactly.
+    struct Undo { int32_t seq, logical, n_mapped_before; };
+    std::vector<Undo> undo[2];
+    std::vector<Row> rows(n_seqs);
+    std::vector<int32_t> emit(n_seqs);
+    for (int i = 0; i < n_seqs; i++) emit[i] = i;
+    int enq = 0, done = 0;
+    bool end = false;            // a callback ended the run, or the next step cannot be prepared
+    int ops[LD_PROF_N] = {0};
+    auto prepare = [&](int k) -> ld_status {
+        const int ahead = k - done;
+        int64_t missing = 0;
+        for (int i = 0; i < n_seqs; i++) {
+            const Seq &q = kv->seqs[seqs[i]];
+            const int64_t need = blocks_for(kv, q.n_cached + ahead + 1);
+            if (need > kv->max_blocks) { ld::set_error("ld_decode_run: sequence %d would exceed max_blocks_per_seq", seqs[i]); return LD_E_RANGE; }
+            missing += count_missing(kv, seqs[i], need);
+        }
+        if (missing > (int64_t)kv->free_stack.size()) {
+            ld::set_error("ld_decode_run: out of KV blocks (%lld needed, %zu free)", (long long)missing, kv->free_stack.size());
+            return LD_E_NOMEM;
+        }
+        std::vector<Undo> &u = undo[k & 1];
+        u.clear();
+        for (int i = 0; i < n_seqs; i++) {
+            Seq &q = kv->seqs[seqs[i]];
+            const int64_t need = blocks_for(kv, q.n_cached + ahead + 1);
+            const int32_t *t = kv->trow(seqs[i]);
+            for (int64_t j = 0; j < need; j++)
+                if (t[j] < 0) u.push_back({seqs[i], (int32_t)j, q.n_mapped});
+            map_blocks(kv, seqs[i], need);
+            rows[i] = {q.pending, (int32_t)(q.n_cached + ahead), seqs[i]};
+        }
+        return enqueue_pass(kv, rows, n_seqs, emit, st, nullptr, k & 1, ahead > 0, ops);
+    };
+    // With per-kernel timing on, the events of a pass are read after it: no step is prepared ahead.
+    const int depth = kv->prof_on ? 1 : 2;
+    rc = prepare(0);
+    if (rc) return rc;
+    enq = 1;
+    for (;;) {
+        if (!end && enq < max_steps && enq - done < depth) {
+            rc = prepare(enq);
+            if (rc == LD_OK) enq++;
+            else if (rc == LD_E_NOMEM || rc == LD_E_RANGE) end = true;   // the steps in flight are still delivered
+            else { (void)hipStreamSynchronize(st); return rc; }
+        }
+        if (done == enq) break;
+        LD_HIP_TRY(hipEventSynchronize(kv->step_ev[done & 1]));
+        if (kv->prof_on) {
+            if (kv->timer.failed) return fail(LD_E_HIP, "profiling: hipEventCreate failed");
+            for (size_t i = 0; i < kv->timer.cat.size(); i++) {
+                float ms = 0.f;
+                LD_HIP_TRY(hipEventElapsedTime(&ms, kv->timer.ev[2 * i], kv->timer.ev[2 * i + 1]));
+                kv->prof.ms[kv->timer.cat[i]] += ms;
+            }
+            for (int k = 0; k < LD_PROF_N; k++) { kv->prof.launches[k] += ops[k]; ops[k] = 0; }
+        }
+        const int32_t *out = kv->pin_out + (size_t)(done & 1) * kv->max_seqs;
+        for (int i = 0; i < n_seqs; i++) {
+            Seq &q = kv->seqs[seqs[i]];
+            q.n_cached += 1;
+            q.pending = out[i];
+        }
+        done++;
+        if (steps_done) *steps_done = done;
+        if (cb)
+            for (int i = 0; i < n_seqs; i++) {
+                Seq &q = kv->seqs[seqs[i]];
+                const int r = cb(user, seqs[i], q.pending, (int32_t)q.n_cached);
+                if (r == LD_CB_CONTINUE) continue;
+                end = true;
+                if (r != LD_CB_PAUSE) q.stopped = true;
+            }
+        if (end && enq > done) {
+            // The step prepared ahead is not wanted: return its blocks, last taken first, so that the allocator
+            // is where `done` single steps would have left it.  The step still executes; what it writes lands in
+            // the slot the pending token will take anyway, or in a block that is free again, so it has to finish
+            // before anyone can be given that block.
+            std::vector<Undo> &u = undo[done & 1];
+            for (auto it = u.rbegin(); it != u.rend(); ++it) {
+                int32_t *t = kv->trow(it->seq);
+                const int32_t b = t[it->logical];
+                t[it->logical] = -1;
+                kv->refs[b] = 0;
+                kv->free_stack.push_back(b);
+                kv->seqs[it->seq].n_mapped = it->n_mapped_before;
+            }
+            enq = done;
+            LD_HIP_TRY(hipStreamSynchronize(st));
+        }
+    }
+    return LD_OK;
 }
 
 ld_status ld_step_mixed(ld_kv *kv, const ld_seq *dec, int32_t n_dec, const ld_seq *pf, const int32_t *const *pf_tokens,

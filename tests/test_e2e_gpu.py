@@ -368,3 +368,98 @@ def test_random_schedule_of_every_operation(shape, tol, seed):
             assert P.tables_equal(s) and ld.ld_kv_len(h, s) == P.okv.length(s), (it, op, s)
     assert max(errs) <= tol, max(errs)
     assert min(counts.get(k, 0) for k in ("new", "decode", "mixed", "obs", "fork", "out", "in", "free")) >= 2, counts
+
+
+@pytest.mark.parametrize("shape", [TINY, replace(TINY, dtype="bf16", n_kv_heads=2, name="tiny-bf16-gqa"),
+                                   replace(TINY, window=21, name="tiny-band")])
+def test_decode_run_equals_single_steps(shape):
+    """Multi-step runs with the callback one step behind the GPU (section 3.3): tokens, callback order, block
+    tables, free counts and lengths equal the oracle's sequential steps -- through block boundaries, with a
+    sampled sequence in the batch, when a callback pauses the run (the step enqueued ahead is taken back,
+    including the blocks it had reserved), when one aborts its sequence, and with per-kernel timing on."""
+    P = Pair(shape, 21, n_blocks=40, max_tokens=64, max_seqs=4, max_blocks=8)
+    h, V = P.gkv.h, shape.vocab
+    seqs = [P.alloc() for _ in range(4)]
+    assert P.okv.set_sampling(seqs[2], 0.7, 99) == 0 and ld.ld_kv_set_sampling(h, seqs[2], 0.7, 99) == 0
+    sink = Tokens()
+    for s, n in zip(seqs, [5, 14, 15, 31]):                         # sequences 1 and 2 cross into a new block early
+        tk = prompt(21, 10 + s, n, V)
+        rc, t, _ = P.okv.prefill(s, tk, want_logits=False); ld.ld_prefill(h, s, tk, callback=sink)
+        assert sink.last() == [t]
+
+    def oracle_steps(order, n):
+        out = []
+        for _ in range(n):
+            out += [(s, P.okv.decode(s, want_logits=False)[1]) for s in order]
+        return out
+
+    def same_state(order):
+        assert ld.ld_kv_free_blocks(h) == P.okv.free_blocks()
+        for s in order:
+            assert P.tables_equal(s) and ld.ld_kv_len(h, s) == P.okv.length(s)
+
+    # a full run, no stop
+    log = Tokens()
+    rc, done = ld.ld_decode_run(h, seqs, 20, callback=log)
+    assert done == 20 and [(q, t) for q, t, _ in log.log] == oracle_steps(seqs, 20)
+    same_state(seqs)
+    # positions in callback order
+    assert [p for q, _, p in log.log if q == seqs[0]] == list(range(6, 26))
+    # pause at a step where the step enqueued ahead has reserved a new block: sequence 0 sits at length 25 + 7 = 32
+    order = seqs[::-1]
+    calls = []
+    def pause(seq, tok, pos):
+        calls.append((seq, tok))
+        return ld.LD_CB_PAUSE if (seq == seqs[1] and len(calls) > 4 * 6) else 0
+    rc, done = ld.ld_decode_run(h, order, 30, callback=pause)
+    assert done == 7 and calls == oracle_steps(order, 7)
+    assert ld.ld_kv_len(h, seqs[0]) == 32
+    same_state(seqs)
+    # everyone is still live; single steps and runs mix freely
+    ref = oracle_steps(seqs, 1)
+    one = Tokens(); ld.ld_decode_step(h, seqs, callback=one)
+    assert [(q, t) for q, t, _ in one.log] == ref
+    # abort: the sequence is stopped, the others keep their state, the run has ended after that step
+    calls.clear()
+    def abort(seq, tok, pos):
+        calls.append((seq, tok))
+        return len(calls) == 4 * 3 - 1                               # third step, third sequence in the list
+    rc, done = ld.ld_decode_run(h, seqs, 9, callback=abort)
+    assert done == 3 and calls == oracle_steps(seqs, 3)
+    same_state(seqs)
+    assert ld.ld_decode_run(h, seqs, 2, check=False)[0] == ld.LD_E_STATE
+    live = [s for s in seqs if s != seqs[2]]
+    # per-kernel timing on: same tokens (steps are then not prepared ahead)
+    ld.ld_kv_profile(h, 1)
+    log = Tokens()
+    rc, done = ld.ld_decode_run(h, live, 5, callback=log)
+    ld.ld_kv_profile(h, 0)
+    assert done == 5 and [(q, t) for q, t, _ in log.log] == oracle_steps(live, 5)
+    assert ld.ld_decode_run(h, live, 0)[1] == 0 and ld.ld_decode_run(h, live[:1], 1)[1] == 1
+    oracle_steps(live[:1], 1)
+    same_state(live)
+
+
+def test_decode_run_stops_before_a_step_it_cannot_reserve():
+    """The pool runs dry in the middle of a run: the steps that fit are delivered, the call reports how many, and
+    the next call returns the allocation error without changing anything -- as single steps would."""
+    P = Pair(TINY, 22, n_blocks=4, max_tokens=16, max_seqs=2, max_blocks=4)
+    h = P.gkv.h
+    a, b = P.alloc(), P.alloc()
+    for s, n in ((a, 20), (b, 12)):                                  # a holds 2 blocks, b holds 1: one block left
+        tk = prompt(22, s, n, TINY.vocab)
+        P.okv.prefill(s, tk, want_logits=False); ld.ld_prefill(h, s, tk)
+    log = Tokens()
+    rc, done = ld.ld_decode_run(h, [a, b], 40, callback=log)
+    # b needs its second block at length 16 (step 5), a its third at length 32 (step 13): that one is missing
+    assert rc == 0 and done == 12
+    ref = []
+    for _ in range(12):
+        ref += [(s, P.okv.decode(s, want_logits=False)[1]) for s in (a, b)]
+    assert [(q, t) for q, t, _ in log.log] == ref
+    assert ld.ld_kv_free_blocks(h) == P.okv.free_blocks() == 0 and P.tables_equal(a) and P.tables_equal(b)
+    rc, done = ld.ld_decode_run(h, [a, b], 40, check=False)
+    assert rc == ld.LD_E_NOMEM and done == 0 and ld.ld_kv_len(h, a) == 32 and ld.ld_kv_len(h, b) == 24
+    assert P.okv.decode(a)[0] == oracle.E_NOMEM
+    rc, done = ld.ld_decode_run(h, [b], 3)                           # b alone still has room in its block
+    assert done == 3

@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--kernel-probe", action="store_true",
                     help="run only the dominant kernel (gate/up projection, 7B shape, batch 1) 16 times on 4 rotating "
                          "matrices, plus the calibration copy: the short program the rocprofv3 --pmc runs use")
+    ap.add_argument("--attention-probe", action="store_true",
+                    help="launch only the batch-32 decode attention (+ 256 MiB copies), for the HBM-traffic counter runs")
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is NOT the benchmark)")
     return ap.parse_args()
 
@@ -407,6 +409,32 @@ def main():
         print(json.dumps({"probe": "k_gemv1 gate/up 7B batch 1", "launches": 16,
                           "algorithmic_bytes_per_launch": 2 * f * d * 2 + d * 8 + f * 4,
                           "copy_bytes_each_way": 256 << 20, "copies": 4}))
+        return
+    if args.attention_probe:
+        from workloads import gen
+        B, H, Hkv, hd = 32, shape.n_heads, shape.n_kv_heads, shape.head_dim
+        lens = gen.randint(SEED_BASE + 3, 1, 512, 8192, B).tolist()       # the batch-32 leg's contexts
+        nblk = [-(-n // 16) for n in lens]
+        pool = torch.empty(sum(nblk), 2, Hkv, 16, hd, device="cuda").normal_(0, 1).bfloat16()
+        table = torch.full((B, max(nblk)), -1, dtype=torch.int32)
+        o = 0
+        for b in range(B):
+            table[b, :nblk[b]] = torch.arange(o, o + nblk[b], dtype=torch.int32); o += nblk[b]
+        table = table.cuda()
+        slot = torch.arange(B, dtype=torch.int32, device="cuda")
+        ctx = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        q = torch.randn(B, H * hd, device="cuda"); out = torch.empty(B, H * hd, device="cuda")
+        scratch = torch.empty(ld.ldk_attention_scratch_bytes(B, H, Hkv, hd, max(lens)), dtype=torch.uint8, device="cuda")
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        b2 = torch.empty_like(a)
+        for i in range(8):
+            ld.ldk_paged_attention(q, H * hd, pool, table, slot, ctx, max(lens), H, Hkv, hd, out, scratch)
+            if i % 2 == 0:
+                b2.copy_(a)                  # also evicts the pool from the last-level cache between launches
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "decode attention, 7B shape, batch 32, contexts U[512,8192]", "launches": 8,
+                          "algorithmic_bytes_per_launch": sum(lens) * 2 * Hkv * hd * 2 + 2 * B * H * hd * 4,
+                          "sum_context": sum(lens), "copy_bytes_each_way": 256 << 20, "copies": 4}))
         return
     weights = make_weights(shape, SEED_BASE + 2, device="cuda")
     model = ld.Model(shape, weights, max_chunk=CHUNK)

@@ -798,8 +798,7 @@ ld_status ld_decode_run(ld_kv *kv, const ld_seq *seqs, int32_t n_seqs, int32_t m
     }
     if (max_steps == 0) return LD_OK;
     hipStream_t st = (hipStream_t)stream;
-    ld_status rc = ensure_pinned(kv);
-    if (rc) return rc;
+    ld_status rc = LD_OK;
 
     // Step k is prepared while step k-1 runs: its rows sit one position further, its blocks are reserved
     // now, and its input tokens are read on the device from what step k-1 emits.  Every reservation is

@@ -159,6 +159,26 @@ def test_state_errors_leave_state_unchanged():
     assert ld.ld_kv_free(kv2, s2) == 0 and ld.ld_kv_free(kv2, s2, check=False) == ld.LD_E_INVAL
 
 
+def test_decode_run_rejects_bad_calls_before_touching_anything():
+    m = _model()
+    kv = _kv(m, n_blocks=3, max_tokens=64, max_seqs=2, max_blocks=2)
+    s = ld.ld_kv_alloc(kv, 0)
+    assert ld.ld_decode_run(kv, [s], 4, stream=0, check=False) == (ld.LD_E_STATE, 0)        # nothing pending
+    ld.ld_kv_assume(kv, s, 5, pending=7)
+    assert ld.ld_decode_run(kv, [s, s], 4, stream=0, check=False)[0] == ld.LD_E_INVAL      # listed twice
+    assert ld.ld_decode_run(kv, [s, 1], 4, stream=0, check=False)[0] == ld.LD_E_INVAL      # dead handle
+    assert ld.ld_decode_run(kv, [s], -1, stream=0, check=False)[0] == ld.LD_E_INVAL
+    assert ld.ld_decode_run(kv, [s], 0, stream=0) == (ld.LD_OK, 0)                          # no step asked for
+    # the very first step cannot get its block: the error itself comes back, nothing moved
+    kv2 = _kv(m, n_blocks=2, max_tokens=64, max_seqs=2, max_blocks=4)
+    a, b = ld.ld_kv_alloc(kv2, 0), ld.ld_kv_alloc(kv2, 0)
+    ld.ld_kv_assume(kv2, a, 16, pending=7)
+    ld.ld_kv_assume(kv2, b, 5, pending=7)
+    assert ld.ld_kv_free_blocks(kv2) == 0
+    assert ld.ld_decode_run(kv2, [a], 4, stream=0, check=False) == (ld.LD_E_NOMEM, 0)
+    assert ld.ld_kv_len(kv2, a) == 16 and ld.ld_kv_block_table(kv2, a).tolist() == [0]
+
+
 def test_swap_state_machine_without_cached_tokens():
     """Swap-out / swap-in of a sequence that holds reserved blocks but no tokens moves no data, so the
     state machine and the allocator effects can be checked without a GPU: blocks go back as a free would

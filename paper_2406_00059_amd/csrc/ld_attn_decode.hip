@@ -8,9 +8,9 @@
 //
 // Work item = (row t, KV head, chunk c) as in the scalar kernel; a workgroup of 4 waves takes one item,
 // wave w the 32-position steps w, w+4, ... of the chunk.  Nothing goes through LDS but the final merge
-// of the four waves: keys and (transposed) values are loaded straight into MFMA operand registers, two
-// steps (32 KB per wave) at a time; two workgroups share a CU, so one wave's loads overlap another's
-// arithmetic.
+// of the four waves: keys and (transposed) values are loaded straight into MFMA operand registers, in two
+// register sets of one step (16 KB per wave) each, refilled as soon as a step has been multiplied; two
+// workgroups share a CU.
 //
 //   S^T[pos, q]  = K[pos, :] . Q[q, :]       one 16 x 16 tile per block: A = key rows (lane l: slot l % 16,
 //                                            dims 32 j + 8 (l / 16) .. +8 in k-step j), B = Q (hi + lo)
@@ -185,15 +185,21 @@ __global__ __launch_bounds__(256, 2) void k_attn_decode_grouped(const float *__r
         }
     };
 
-    // steps of this wave: blocks b_begin + 2 (wave + 4 n), two steps per round
-    for (int b = b_begin + 2 * wave; b < b_end; b += 16) {
+    // steps of this wave: blocks b_begin + 2 (wave + 4 n).  Two register sets: the loads of the step after
+    // next are issued before the next step is multiplied, so 16 .. 32 KB per wave are in flight all the time.
+    {
         Step sa, sb;
-        const bool second = b + 8 < b_end;
-        load_k(sa, b);
-        load_v(sa, b);
-        if (second) { load_k(sb, b + 8); load_v(sb, b + 8); }
-        compute(sa, b);
-        if (second) compute(sb, b + 8);
+        int b = b_begin + 2 * wave;
+        if (b < b_end) { load_k(sa, b); load_v(sa, b); }
+        for (; b < b_end; b += 16) {
+            const bool second = b + 8 < b_end;
+            if (second) { load_k(sb, b + 8); load_v(sb, b + 8); }
+            compute(sa, b);
+            if (second) {
+                if (b + 16 < b_end) { load_k(sa, b + 16); load_v(sa, b + 16); }
+                compute(sb, b + 8);
+            }
+        }
     }
 
     // column statistics: l was summed per lane over its own rows

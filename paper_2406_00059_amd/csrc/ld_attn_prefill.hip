@@ -77,6 +77,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
     // band: lowest position visible to this lane's query, to the wave's first query, to the tile's first query
     const int q_low = window > 0 ? max(q_pos - window + 1, 0) : 0;
     const int wave_low = window > 0 ? max(tile.z + wave * 32 - window + 1, 0) : 0;
+    const int wave_first_pos = tile.z + wave * 32;                      // position of the wave's first query
+    const int wave_low_hi = window > 0 ? max(wave_last_pos - window + 1, 0) : 0;   // lowest position its last query sees
     const int kv_start = window > 0 ? (max(tile.z - window + 1, 0) & ~(KVB - 1)) : 0;
 
     // Q operand: for k-step j the lane supplies dims half*64 + j*8 .. +8 of its query (hi and lo parts)
@@ -108,22 +110,25 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
     // value pieces (dimension vd, positions 8*vh .. +8 of block v of the step).
     const int kr = threadIdx.x >> 4, kc = (threadIdx.x & 15) * 8;       // + 16 rows for the second piece
     const int vd = threadIdx.x >> 1, vh = (threadIdx.x & 1) * 8;
-    u32x4 kreg[2], vreg[2];
-    auto load_step = [&](int kv0) {
+    // Global loads run PF steps ahead of the arithmetic, in PF register sets: with one or two workgroups on
+    // a CU the arithmetic of a single step is much shorter than the memory latency it would have to cover.
+    constexpr int PF = 3;
+    u32x4 kreg[PF][2], vreg[PF][2];
+    auto load_step = [&](int set, int kv0) {
 #pragma unroll
         for (int v = 0; v < 2; v++) {
             // a block past the last needed position is read again from the last needed block; never used
             const int pos = min(kv0 + 16 * v, wg_last_pos);
             const bf16_t *blk = pool + (int64_t)trow[pos >> 4] * block_stride;
-            kreg[v] = *reinterpret_cast<const u32x4 *>(blk + kv_k_offset(HD, kvh, kr, kc));
-            vreg[v] = *reinterpret_cast<const u32x4 *>(blk + kv_v_offset(Hkv, HD, kvh, vh, vd));
+            kreg[set][v] = *reinterpret_cast<const u32x4 *>(blk + kv_k_offset(HD, kvh, kr, kc));
+            vreg[set][v] = *reinterpret_cast<const u32x4 *>(blk + kv_v_offset(Hkv, HD, kvh, vh, vd));
         }
     };
-    auto stage = [&](int st) {
+    auto stage = [&](int st, int set) {
 #pragma unroll
         for (int v = 0; v < 2; v++) {
-            *reinterpret_cast<u32x4 *>(&ks[st][16 * v + kr][kc]) = kreg[v];
-            *reinterpret_cast<u32x4 *>(&vt[st][vd][16 * v + vh]) = vreg[v];
+            *reinterpret_cast<u32x4 *>(&ks[st][16 * v + kr][kc]) = kreg[set][v];
+            *reinterpret_cast<u32x4 *>(&vt[st][vd][16 * v + vh]) = vreg[set][v];
         }
     };
     // this workgroup's share of the tile's steps (all of them when the grid has one split)
@@ -131,17 +136,11 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
     const int n_steps = (wg_last_pos - kv_start) / KVB + 1, per = (n_steps + n_splits - 1) / n_splits;
     const int kv_begin = kv_start + split * per * KVB;
     const int kv_end = min(kv_begin + per * KVB, wg_last_pos + 1);      // exclusive; may be <= kv_begin (empty share)
-    if (kv_begin < kv_end) load_step(kv_begin);
+#pragma unroll
+    for (int pf = 0; pf < PF; pf++)
+        if (kv_begin + pf * KVB < kv_end) load_step(pf, kv_begin + pf * KVB);
 
-    int st = 0;
-    for (int kv0 = kv_begin; kv0 < kv_end; kv0 += KVB, st ^= 1) {
-        // Stage this step, then fetch the next one.  One barrier per step: a wave that writes buffer st for
-        // step n has passed the barrier of step n-1, which every wave reaches only after it has finished
-        // reading buffer st for step n-2.
-        stage(st);
-        lds_barrier();
-        if (kv0 + KVB < kv_end) load_step(kv0 + KVB);
-        if (!wave_active || kv0 > wave_last_pos || kv0 + KVB <= wave_low) continue;   // nothing visible to this wave
+    auto compute = [&](int kv0, int st) {
 
         // ---- S^T = K Q^T for 32 kv positions x 32 queries; tile row l32 is position kv0 + tau(l32)
         f32x16 sc_t;
@@ -157,15 +156,26 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
         // ---- online softmax; accumulator element i is row 8*(i/4) + 4*half + i%4 of the tile, which holds
         // position kv0 + 16*(i/8) + 8*half + i%8
         float mb = -INFINITY;
+        if (kv0 + KVB - 1 <= wave_first_pos && kv0 >= wave_low_hi) {
+            // every position of the step is visible to every query of the wave (the common case away from
+            // the diagonal and the band edge): no masks; rows past the tile compute on a copy of the last row
 #pragma unroll
-        for (int i = 0; i < 16; i++) {
-            const int kv_pos = kv0 + 16 * (i / 8) + 8 * half + (i % 8);
-            const bool ok = q_valid && kv_pos <= q_pos && kv_pos >= q_low;
-            sc_t[i] = ok ? sc_t[i] : -INFINITY;
-            mb = fmaxf(mb, sc_t[i]);
+            for (int i = 0; i < 16; i++) mb = fmaxf(mb, sc_t[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const int kv_pos = kv0 + 16 * (i / 8) + 8 * half + (i % 8);
+                const bool ok = q_valid && kv_pos <= q_pos && kv_pos >= q_low;
+                sc_t[i] = ok ? sc_t[i] : -INFINITY;
+                mb = fmaxf(mb, sc_t[i]);
+            }
         }
         mb = fmaxf(mb, __shfl_xor(mb, 32, WAVE));
-        const float m_new = fmaxf(m, mb);
+        // m is the reference the exponents are taken against, not necessarily the running maximum: it moves up
+        // only when the maximum has outgrown it by more than 2^8, so p stays below 256 and the accumulators
+        // are rescaled on few steps instead of most.  o, l and m stay consistent, which is all the final
+        // division and the split merge need.
+        const float m_new = mb > m + 8.f ? mb : m;
         float sc = 1.f;
         uint32_t ph[8], pl[8];
         if (m_new > -INFINITY) {
@@ -200,6 +210,24 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
                 const bf16x8 pbl = __builtin_bit_cast(bf16x8, (u32x4){pl[4 * mm], pl[4 * mm + 1], pl[4 * mm + 2], pl[4 * mm + 3]});
                 o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbh, o[nt], 0, 0, 0);
                 o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbl, o[nt], 0, 0, 0);
+            }
+        }
+    };
+
+    int st = 0;
+    for (int base = kv_begin; base < kv_end; base += PF * KVB) {
+#pragma unroll
+        for (int u = 0; u < PF; u++) {
+            const int kv0 = base + u * KVB;
+            if (kv0 < kv_end) {      // uniform over the workgroup
+                // Stage this step, then fetch the step PF ahead into the set just emptied.  One barrier per
+                // step: a wave that writes buffer st for step n has passed the barrier of step n-1, which
+                // every wave reaches only after it has finished reading buffer st for step n-2.
+                stage(st, u);
+                lds_barrier();
+                if (kv0 + PF * KVB < kv_end) load_step(u, kv0 + PF * KVB);
+                if (wave_active && kv0 <= wave_last_pos && kv0 + KVB > wave_low) compute(kv0, st);   // else nothing visible to this wave
+                st ^= 1;
             }
         }
     }

@@ -42,10 +42,7 @@ __global__ __launch_bounds__(256) void k_red_add_split(const float *__restrict__
     __shared__ float red[4];
     const int t = blockIdx.y, n = blockIdx.x * RB + threadIdx.x * 4;
     float4 v = *reinterpret_cast<const float4 *>(x + (int64_t)t * d + n);
-    for (int z = 0; z < ks; z++) {
-        const float4 p = *reinterpret_cast<const float4 *>(partial + ((int64_t)z * T + t) * d + n);
-        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
-    }
+    if (ks) v = slab_sum(reinterpret_cast<const float4 *>(partial + (int64_t)t * d + n), (int64_t)T * d / 4, ks, v);
     if (ks) *reinterpret_cast<float4 *>(x + (int64_t)t * d + n) = v;
     if (!g) return;
     const float4 gv = *reinterpret_cast<const float4 *>(g + n);
@@ -72,12 +69,8 @@ __global__ __launch_bounds__(256) void k_red_rope(const float *__restrict__ part
     const int idx = blockIdx.x * 256 + threadIdx.x;
     if (idx >= T * heads * HALF) return;
     const int i = idx % HALF, hh = (idx / HALF) % heads, t = idx / (HALF * heads);
-    float a = 0.f, b = 0.f;
-    for (int z = 0; z < ks; z++) {
-        const float *p = partial + ((int64_t)z * T + t) * nqkv + hh * HD + i;
-        a += p[0];
-        b += p[HALF];
-    }
+    const float *p0 = partial + (int64_t)t * nqkv + hh * HD + i;
+    float a = slab_sum(p0, (int64_t)T * nqkv, ks, 0.f), b = slab_sum(p0 + HALF, (int64_t)T * nqkv, ks, 0.f);
     const float rstd = row_rstd(ss_part, t, nssp, d, eps);
     a *= rstd;
     b *= rstd;
@@ -113,13 +106,9 @@ __global__ __launch_bounds__(256) void k_red_swiglu_split(const float *__restric
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)T * (F / 4)) return;
     const int t = (int)(idx / (F / 4)), n = (int)(idx % (F / 4)) * 4;
-    float4 gs = make_float4(0, 0, 0, 0), us = gs;
-    for (int z = 0; z < ks; z++) {
-        const float *p = partial + ((int64_t)z * T + t) * (2 * F) + n;
-        const float4 a = *reinterpret_cast<const float4 *>(p), b = *reinterpret_cast<const float4 *>(p + F);
-        gs.x += a.x; gs.y += a.y; gs.z += a.z; gs.w += a.w;
-        us.x += b.x; us.y += b.y; us.z += b.z; us.w += b.w;
-    }
+    const float4 *p0 = reinterpret_cast<const float4 *>(partial + (int64_t)t * (2 * F) + n);
+    const float4 gs = slab_sum(p0, (int64_t)T * (2 * F) / 4, ks, make_float4(0, 0, 0, 0));
+    const float4 us = slab_sum(p0 + F / 4, (int64_t)T * (2 * F) / 4, ks, make_float4(0, 0, 0, 0));
     const float rstd = row_rstd(ss_part, t, nssp, d, eps);
     const float gg[4] = {gs.x * rstd, gs.y * rstd, gs.z * rstd, gs.w * rstd};
     const float uu[4] = {us.x * rstd, us.y * rstd, us.z * rstd, us.w * rstd};

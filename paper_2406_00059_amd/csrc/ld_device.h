@@ -131,5 +131,30 @@ __device__ __forceinline__ int64_t kv_v_offset(int Hkv, int hd, int kvh, int slo
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// acc + p[0] + p[stride] + ... + p[(ks - 1) stride], added in that order (split-K slabs: the order is part of
+// the result).  The loads of eight (then four) slabs are issued together; a plain loop would pay one memory
+// latency per slab.
+template <typename V>
+__device__ __forceinline__ V slab_sum(const V *p, int64_t stride, int ks, V acc) {
+    int z = 0;
+    for (; z + 8 <= ks; z += 8) {
+        V v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) v[u] = p[(z + u) * stride];
+#pragma unroll
+        for (int u = 0; u < 8; u++) acc += v[u];
+    }
+    if (z + 4 <= ks) {
+        V v[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) v[u] = p[(z + u) * stride];
+#pragma unroll
+        for (int u = 0; u < 4; u++) acc += v[u];
+        z += 4;
+    }
+    for (; z < ks; z++) acc += p[z * stride];
+    return acc;
+}
+
 
 }  // namespace ldd

@@ -636,12 +636,9 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)T * N) return;
     const int t = (int)(idx / N), n = (int)(idx % N);
-    float a = 0.f, b = 0.f;
-    for (int z = 0; z < ks; z++) {
-        const float *p = partial + ((int64_t)z * T + t) * (WR * N) + n;
-        a += p[0];
-        if (WR == 2) b += p[N];
-    }
+    const float *p0 = partial + (int64_t)t * (WR * N) + n;
+    const float a = slab_sum(p0, (int64_t)T * (WR * N), ks, 0.f);
+    const float b = WR == 2 ? slab_sum(p0 + N, (int64_t)T * (WR * N), ks, 0.f) : 0.f;
     if constexpr (EPI == ld::GEMM_STORE) y[idx] = a;
     else if constexpr (EPI == ld::GEMM_ADD) y[idx] += a;
     else y[idx] = a / (1.0f + __expf(-a)) * b;

@@ -229,3 +229,11 @@ def test_fork_at_block_boundaries_shares_blocks_by_holder_count():
     # a swapped-out parent cannot be forked
     ld.ld_kv_swap_out(kv, again, None, stream=0)
     assert ld.ld_kv_fork(kv, again, 0, stream=0, check=False) == ld.LD_E_STATE
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asking for more exits with a message instead of a number."""
+    import subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and not r.stdout.strip().startswith("{")

@@ -39,7 +39,7 @@ def test_linear_store_add_and_fused_norm(dtype, T):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("T", [1, 5])
+@pytest.mark.parametrize("T", [1, 2, 3, 4, 5])
 def test_linear_swiglu(dtype, T):
     F, K = 173, 256
     W = _mat(2, 1, 2 * F, K, dtype); x = gen.normal(2, 2, (T, K)); g = gen.normal(2, 3, (K,), std=0.1, mean=1.0)
@@ -294,15 +294,16 @@ def test_sampling_kernel_draws_the_oracles_tokens():
     assert out.cpu().tolist()[:2000] == ref
 
 
-@pytest.mark.parametrize("dtype,hd,T", [("bf16", 128, 1), ("bf16", 128, 3), ("f32", 64, 1), ("bf16", 64, 1)])
+@pytest.mark.parametrize("dtype,hd,T", [("bf16", 128, 1), ("bf16", 128, 2), ("bf16", 128, 3), ("bf16", 128, 4), ("f32", 64, 1),
+                                        ("bf16", 64, 1), ("bf16", 64, 4)])
 def test_fused_qkv_projection_rope_cache_append(dtype, hd, T):
     """ldk_qkv_rope = RMSNorm + q/k/v projection + rotary embedding + cache append in one call
     (one fused kernel for a single bf16 row, a composition otherwise)."""
     H, Hkv, K, nblk = 6, 2, 1160, 7
     N = (H + 2 * Hkv) * hd
     W = _mat(8, 1, N, K, dtype); x = gen.normal(8, 2, (T, K)); g = gen.normal(8, 3, (K,), std=0.1, mean=1.0)
-    pos = torch.tensor([37, 16, 95][:T], dtype=torch.int32)
-    slot = torch.tensor([1, 0, 1][:T], dtype=torch.int32)
+    pos = torch.tensor([37, 16, 95, 0][:T], dtype=torch.int32)
+    slot = torch.tensor([1, 0, 1, 0][:T], dtype=torch.int32)
     table = torch.tensor([[3, 6, 0, 0, 0, 0], [5, 1, 4, 2, 0, 0]], dtype=torch.int32)   # logical -> physical
     pdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     pool = torch.full((nblk, 2, Hkv, 16, hd), 512.0, dtype=pdt, device=DEV)
@@ -331,6 +332,31 @@ def test_fused_qkv_projection_rope_cache_append(dtype, hd, T):
                 assert np.mean(pool_h[blk, 1, j, s] == oracle.round_bf16(v)) > 0.9
             touched[blk, :, j, s] = True
     assert np.all(pool_h[~touched] == 512.0) and touched.sum() == T * 2 * Hkv
+
+
+@pytest.mark.parametrize("K", [4096, 5120, 8192, 11008, 13824])
+@pytest.mark.parametrize("T", [2, 3, 4])
+def test_linear_two_to_four_rows_every_row_length(T, K):
+    """Decode batches of 2 .. 4 rows at the row lengths of the 7B and 13B shapes (model and FFN widths:
+    8 to 27 K slabs of the small-batch matrix-core kernel), all three epilogues, ragged output counts."""
+    N = 77
+    W = _mat(12, K, 2 * N, K, "bf16"); x = gen.normal(12, 2, (T, K)); g = gen.normal(12, 3, (K,), std=0.1, mean=1.0)
+    y0 = gen.normal(12, 4, (T, N))
+    Wh = oracle.to_host_matrix(W)
+    Wd, xd, gd = W.to(DEV), x.to(DEV), g.to(DEV)
+    scratch = torch.empty(ld.ldk_linear_scratch_bytes(T, N, K, ld.LDK_SWIGLU), dtype=torch.uint8, device=DEV)
+    gu = np.stack([oracle.matvec(Wh, oracle.rmsnorm(x[t].numpy(), g.numpy(), 1e-5)) for t in range(T)])
+    y = torch.empty(T, N, device=DEV)
+    ld.ldk_linear(Wd, xd, y, ld.LDK_SWIGLU, g=gd, eps=1e-5, scratch=scratch)
+    ref = gu[:, :N] / (1 + np.exp(-gu[:, :N])) * gu[:, N:]
+    assert np.max(np.abs(y.cpu().numpy() - ref)) <= 2e-5 * np.abs(ref).max()
+    y = y0.to(DEV).clone()
+    ld.ldk_linear(Wd[:N], xd, y, ld.LDK_ADD, g=gd, eps=1e-5, scratch=scratch)
+    assert np.max(np.abs(y.cpu().numpy() - (y0.numpy() + gu[:, :N]))) <= 2e-5 * np.abs(gu).max()
+    plain = np.stack([oracle.matvec(Wh, x[t].numpy()) for t in range(T)])
+    y = torch.empty(T, 2 * N, device=DEV)
+    ld.ldk_linear(Wd, xd, y, ld.LDK_STORE, scratch=scratch)
+    assert np.max(np.abs(y.cpu().numpy() - plain)) <= 2e-5 * np.abs(plain).max()
 
 
 @pytest.mark.parametrize("T", [2, 5, 31, 32, 33, 64, 100, 257])

@@ -72,6 +72,7 @@ def lib():
         L.orc_seq_set_sampling.restype = C.c_int32
         L.orc_seq_set_sampling.argtypes = [vp, C.c_int32, C.c_double, C.c_uint64]
         L.orc_kv_fork.restype = C.c_int32; L.orc_kv_fork.argtypes = [vp, C.c_int32, C.c_int64, ip]
+        L.orc_kv_trim.restype = C.c_int32; L.orc_kv_trim.argtypes = [vp, C.c_int32, ip]
         L.orc_kv_swap_doubles.restype = C.c_int64; L.orc_kv_swap_doubles.argtypes = [vp, C.c_int32]
         L.orc_kv_swap_out.restype = C.c_int32; L.orc_kv_swap_out.argtypes = [vp, C.c_int32, dp]
         L.orc_kv_swap_in.restype = C.c_int32; L.orc_kv_swap_in.argtypes = [vp, C.c_int32, dp]
@@ -281,6 +282,12 @@ class KV:
         s = C.c_int32(-1)
         rc = lib().orc_kv_fork(self.h, parent, n_tokens, C.byref(s))
         return rc, s.value
+
+    def trim(self, seq):
+        """-> (rc, blocks released): gives up the blocks below the attention band."""
+        n = C.c_int32(0)
+        rc = lib().orc_kv_trim(self.h, seq, C.byref(n))
+        return rc, n.value
 
     def swap_out(self, seq):
         """-> (rc, store): the sequence's keys/values as a float64 array, its blocks back on the free list."""

@@ -399,6 +399,7 @@ typedef struct {
     int32_t pending;
     int64_t n_cached;
     int32_t n_mapped;
+    int32_t first_block;  /* logical blocks below it were released by orc_kv_trim (attention band) */
     int32_t *table;
     int swapped;      /* keys/values live outside the pool; no block is held */
     double temperature; uint64_t seed;   /* temperature 0: greedy */
@@ -448,14 +449,14 @@ static orc_seq *get_seq(orc_kv *kv, int32_t s)
     return &kv->seqs[s];
 }
 
-/* Make sure logical blocks 0..need-1 of a sequence have physical blocks. */
+/* Make sure logical blocks first_block..need-1 of a sequence have physical blocks. */
 static int ensure_blocks(orc_kv *kv, orc_seq *q, int64_t need)
 {
     if (need > kv->max_blocks_per_seq) return ORC_E_RANGE;
     int64_t missing = 0;
-    for (int64_t i = 0; i < need; i++) if (q->table[i] < 0) missing++;
+    for (int64_t i = q->first_block; i < need; i++) if (q->table[i] < 0) missing++;
     if (missing > kv->n_free) return ORC_E_NOMEM;
-    for (int64_t i = 0; i < need; i++)
+    for (int64_t i = q->first_block; i < need; i++)
         if (q->table[i] < 0) { q->table[i] = kv->free_stack[--kv->n_free]; kv->refs[q->table[i]] = 1; }
     if (need > q->n_mapped) q->n_mapped = (int32_t)need;
     return ORC_OK;
@@ -473,6 +474,30 @@ static void release_blocks(orc_kv *kv, orc_seq *q)
     q->n_mapped = 0;
 }
 
+/* Sliding-window memory (the model family of section 4.1 attends to a band of W positions): the blocks
+ * whose positions all lie below n_cached - W + 1 can be seen by no later query of the sequence (the next
+ * one sits at position n_cached) and are given up, lowest logical block first; a shared block returns to
+ * the free list when its last holder gives it up.  Without a band nothing is released. */
+int32_t orc_kv_trim(orc_kv *kv, int32_t s, int32_t *released)
+{
+    orc_seq *q = get_seq(kv, s);
+    if (!q || !released) return ORC_E_INVAL;
+    if (q->swapped) return ORC_E_STATE;
+    *released = 0;
+    const orc_config *c = &kv->m->c;
+    int64_t low = q->n_cached - c->window + 1;
+    if (c->window <= 0 || low <= 0) return ORC_OK;
+    int64_t keep_from = low / c->kv_block;
+    for (int64_t i = q->first_block; i < keep_from; i++)
+        if (q->table[i] >= 0) {
+            if (--kv->refs[q->table[i]] == 0) kv->free_stack[kv->n_free++] = q->table[i];
+            q->table[i] = -1;
+            (*released)++;
+        }
+    if (keep_from > q->first_block) q->first_block = (int32_t)keep_from;
+    return ORC_OK;
+}
+
 int32_t orc_kv_alloc(orc_kv *kv, int64_t reserve_tokens, int32_t *out)
 {
     if (reserve_tokens < 0) return ORC_E_INVAL;
@@ -481,7 +506,7 @@ int32_t orc_kv_alloc(orc_kv *kv, int64_t reserve_tokens, int32_t *out)
     if (s == kv->max_seqs) return ORC_E_NOMEM;
     orc_seq *q = &kv->seqs[s];
     int bs = kv->m->c.kv_block;
-    q->n_mapped = 0;
+    q->n_mapped = 0; q->first_block = 0;
     int rc = ensure_blocks(kv, q, (reserve_tokens + bs - 1) / bs);
     if (rc) return rc;
     q->active = 1; q->stopped = 0; q->has_pending = 0; q->pending = -1; q->n_cached = 0; q->swapped = 0;
@@ -559,7 +584,7 @@ int32_t orc_kv_read(orc_kv *kv, int32_t s, int32_t layer, int32_t which, int32_t
     orc_seq *q = get_seq(kv, s);
     const orc_config *c = &kv->m->c;
     if (!q || pos < 0 || pos >= q->n_cached) return ORC_E_INVAL;
-    if (q->swapped) return ORC_E_STATE;
+    if (q->swapped || pos < (int64_t)q->first_block * c->kv_block) return ORC_E_STATE;
     kv_view v = {0};
     v.paged = 1; v.pool = kv->pool; v.n_blocks = kv->n_blocks; v.table = q->table;
     memcpy(out, kv_row(c, &v, layer, which, kvh, pos), sizeof(double) * c->head_dim);
@@ -597,7 +622,7 @@ int32_t orc_kv_swap_out(orc_kv *kv, int32_t s, double *store)
     size_t per = block_doubles(kv);
     int L = kv->m->c.n_layers;
     int64_t nb = seq_token_blocks(kv, q);
-    for (int64_t j = 0; j < nb; j++)
+    for (int64_t j = q->first_block; j < nb; j++)      /* released blocks: their part of the store is not written */
         for (int l = 0; l < L; l++)
             memcpy(store + (j * L + l) * per, kv->pool + ((size_t)l * kv->n_blocks + q->table[j]) * per,
                    sizeof(double) * per);
@@ -615,7 +640,7 @@ int32_t orc_kv_swap_in(orc_kv *kv, int32_t s, const double *store)
     if (rc) return rc;
     size_t per = block_doubles(kv);
     int L = kv->m->c.n_layers;
-    for (int64_t j = 0; j < nb; j++)
+    for (int64_t j = q->first_block; j < nb; j++)
         for (int l = 0; l < L; l++)
             memcpy(kv->pool + ((size_t)l * kv->n_blocks + q->table[j]) * per, store + (j * L + l) * per,
                    sizeof(double) * per);
@@ -638,12 +663,17 @@ int32_t orc_kv_fork(orc_kv *kv, int32_t parent, int64_t n_tokens, int32_t *out)
     if (s == kv->max_seqs) return ORC_E_NOMEM;
     int bs = kv->m->c.kv_block;
     int64_t full = n_tokens / bs, tail = n_tokens % bs;
+    if (p->first_block > 0) {   /* the child's next query must not need a block the parent has released */
+        int64_t low = n_tokens - kv->m->c.window + 1;
+        if ((low < 0 ? 0 : low) / bs < p->first_block) return ORC_E_STATE;
+    }
     if (tail && kv->n_free < 1) return ORC_E_NOMEM;
     orc_seq *q = &kv->seqs[s];
     q->active = 1; q->stopped = 0; q->has_pending = 0; q->pending = -1; q->swapped = 0;
     q->temperature = 0.0; q->seed = 0;
     q->n_cached = n_tokens; q->n_mapped = (int32_t)(full + (tail ? 1 : 0));
-    for (int64_t j = 0; j < full; j++) { q->table[j] = p->table[j]; kv->refs[p->table[j]]++; }
+    q->first_block = p->first_block;
+    for (int64_t j = p->first_block; j < full; j++) { q->table[j] = p->table[j]; kv->refs[p->table[j]]++; }
     if (tail) {
         int32_t nb = kv->free_stack[--kv->n_free];
         kv->refs[nb] = 1;

@@ -6,6 +6,7 @@ plausible slip in oracle/ld_oracle.c (dropped gain or scale, eps outside the roo
 or sign, transposed matrix, off-by-one context, wrong block/slot index, wrong tie-break) fails it.
 """
 import math
+from dataclasses import replace
 
 import numpy as np
 import pytest
@@ -551,6 +552,92 @@ def test_fork_shares_full_blocks_and_equals_recomputing_the_prefix(tiny_weights)
     small = oracle.KV(m, 3, 2, 6)
     rc, p2 = small.alloc(0); small.prefill(p2, prefix)
     assert small.free_blocks() == 0 and small.fork(p2, 33)[0] == oracle.E_NOMEM and small.fork(p2, 32)[0] == 0
+
+
+def test_trim_releases_exactly_the_blocks_below_the_band_and_changes_no_output(tiny_weights):
+    """Sliding-window memory: with a band of W positions, trimming after every step gives up exactly the
+    blocks whose 16 positions all lie below n - W + 1 (brute force over positions), the sequence then holds
+    ceil(n/16) - floor(max(0, n-W+1)/16) blocks, and tokens and logits are bitwise those of a twin that
+    never trims -- also after a stranger has overwritten the released blocks.  Without a band nothing is
+    released."""
+    shape, w = tiny_weights
+    W = 21
+    banded = replace(shape, window=W)
+    m = oracle.Model(banded, w)
+    kv, ref = oracle.KV(m, 12, 3, 10), oracle.KV(m, 12, 3, 10)
+    (_, s), (_, r) = kv.alloc(0), ref.alloc(0)
+    tk = _prompt(50, shape.vocab, 120)
+    assert kv.prefill(s, tk)[1] == ref.prefill(r, tk)[1]
+    rc, n_rel = kv.trim(s)
+    n = 50
+    assert rc == 0 and n_rel == (n - W + 1) // 16 == 1 and kv.block_table(s)[1].tolist() == [-1, 1, 2, 3]
+    assert kv.trim(s) == (0, 0)                                  # nothing more to give
+    rc, stranger = kv.alloc(0)
+    assert kv.prefill(stranger, _prompt(16, shape.vocab, 121))[0] == 0 and kv.block_table(stranger)[1].tolist() == [0]
+    for step in range(60):
+        (rc_a, t_a, lg_a), (rc_b, t_b, lg_b) = kv.decode(s), ref.decode(r)
+        assert rc_a == rc_b == 0 and t_a == t_b
+        np.testing.assert_array_equal(lg_a, lg_b)
+        n += 1
+        rc, n_rel = kv.trim(s)
+        tab = kv.block_table(s)[1].tolist()
+        visible_from = n - W + 1                                  # lowest position the next query sees
+        for blk, phys in enumerate(tab):
+            all_below = all(p < visible_from for p in range(16 * blk, 16 * blk + 16))
+            assert (phys == -1) == all_below, (step, blk)
+        assert sum(p >= 0 for p in tab) == -(-n // 16) - max(0, n - W + 1) // 16
+    # the untrimmed twin holds every block of its 110 positions
+    assert ref.free_blocks() == 12 - 7 and kv.free_blocks() == 12 - 1 - 2
+    # an observation chunk after trimming: its rows see back to n - W + 1, all of which is still there
+    obs = _prompt(30, shape.vocab, 122)
+    (rc_a, t_a, lg_a), (rc_b, t_b, lg_b) = kv.prefill(s, obs), ref.prefill(r, obs)
+    assert t_a == t_b
+    np.testing.assert_array_equal(lg_a, lg_b)
+    # no band: nothing is released
+    kv0 = oracle.KV(oracle.Model(shape, w), 12, 1, 10)
+    rc, s0 = kv0.alloc(0)
+    kv0.prefill(s0, tk)
+    assert kv0.trim(s0) == (0, 0) and kv0.free_blocks() == 12 - 4
+
+
+def test_trim_with_shared_blocks_swap_and_fork(tiny_weights):
+    """A shared block returns to the free list only when its last holder trims it; a trimmed sequence swaps
+    out and in (only the blocks it still holds travel) and goes on unchanged; a fork below what the parent
+    has released is refused, one inside the band shares only the blocks that are left."""
+    shape, w = tiny_weights
+    banded = replace(shape, window=20)
+    m = oracle.Model(banded, w)
+    kv, ref = oracle.KV(m, 16, 4, 10), oracle.KV(m, 16, 4, 10)
+    (_, p), (_, r) = kv.alloc(0), ref.alloc(0)
+    tk = _prompt(70, shape.vocab, 123)
+    kv.prefill(p, tk); ref.prefill(r, tk)                          # blocks 0..4
+    rc, child = kv.fork(p, 64)                                     # shares blocks 0..3
+    assert rc == 0 and kv.free_blocks() == 16 - 5
+    assert kv.trim(p) == (0, 3) and kv.free_blocks() == 16 - 5     # 70 - 20 + 1 = 51: blocks 0, 1, 2 go, still held by the child
+    assert kv.trim(child) == (0, 2) and kv.free_blocks() == 16 - 5 + 2   # 64 - 20 + 1 = 45: blocks 0, 1; block 2 still held
+    assert kv.block_table(child)[1].tolist() == [-1, -1, 2, 3]
+    kv.free(child)
+    assert kv.free_blocks() == 16 - 2                              # the parent holds 3 and 4
+    # forks from the trimmed parent
+    assert kv.fork(p, 40)[0] == oracle.E_STATE                     # would need block 1
+    rc, c2 = kv.fork(p, 68)                                        # 68 - 20 + 1 = 49 -> block 3 on: shares block 3, copies the tail
+    assert rc == 0 and kv.block_table(c2)[1].tolist()[:4] == [-1, -1, -1, 3]
+    rc, r2 = ref.fork(r, 68)
+    suf = _prompt(7, shape.vocab, 124)
+    (rc_a, t_a, lg_a), (rc_b, t_b, lg_b) = kv.prefill(c2, suf), ref.prefill(r2, suf)
+    assert rc_a == rc_b == 0 and t_a == t_b
+    np.testing.assert_array_equal(lg_a, lg_b)
+    # swap the trimmed parent out and in
+    held = kv.free_blocks()
+    rc, store = kv.swap_out(p)
+    assert rc == 0 and kv.trim(p)[0] == oracle.E_STATE
+    # block 3 was shared with the fork and stays with it; the parent comes back on two blocks of its own
+    assert kv.swap_in(p, store) == 0 and kv.free_blocks() == held - 1 and kv.block_table(p)[1].tolist()[:3] == [-1, -1, -1]
+    for _ in range(25):
+        (rc_a, t_a, lg_a), (rc_b, t_b, lg_b) = kv.decode(p), ref.decode(r)
+        assert t_a == t_b
+        np.testing.assert_array_equal(lg_a, lg_b)
+        kv.trim(p)
 
 
 def test_wo_and_wdown_zero_make_every_layer_the_identity(tiny_weights):

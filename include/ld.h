@@ -156,6 +156,16 @@ ld_status ld_kv_swap_in(ld_kv *kv, ld_seq seq, const void *host_buf, size_t byte
  * with ld_prefill. */
 ld_status ld_kv_fork(ld_kv *kv, ld_seq parent, int64_t n_tokens, void *stream, ld_seq *out);
 
+/* Sliding-window memory (models with an attention band, cfg.window > 0): gives up the blocks of `seq` whose
+ * 16 positions all lie below n_cached - window + 1, the lowest position the sequence's next query can see
+ * (later queries see less), lowest logical block first; a block shared with other sequences (ld_kv_fork)
+ * returns to the free stack when its last holder gives it up.  Their block-table entries read -1 afterwards
+ * and no kernel dereferences them.  *released = blocks given up by this call (0 without a band).
+ * A trimmed sequence swaps out and in as before (only the blocks it still holds travel; the buffer layout
+ * and ld_kv_swap_bytes are unchanged); ld_kv_fork from it returns LD_E_STATE when the child's first query
+ * would need a released block.  LD_E_STATE while swapped out.  released: HOST. */
+ld_status ld_kv_trim(ld_kv *kv, ld_seq seq, int32_t *released);
+
 /* Token choice of a sequence: temperature 0 (the default, and what section 4.1 uses) emits the greedy
  * token; temperature > 0 draws from softmax(logits / temperature) as ldk_sample does, with the position
  * the emitted token will take as the counter, so a run is reproducible from (seed, tokens fed). */

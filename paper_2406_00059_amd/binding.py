@@ -21,7 +21,7 @@ __all__ = [
     "LDK_STORE", "LDK_ADD", "LDK_SWIGLU", "LIB_PATH", "lib", "LdError", "ld_model_config", "ld_weights",
     "ld_token_cb", "ld_model_create", "ld_model_destroy", "ld_kv_bytes", "ld_workspace_bytes", "ld_kv_create",
     "ld_kv_destroy", "ld_kv_alloc", "ld_kv_map", "ld_kv_free", "ld_kv_block_table", "ld_kv_len",
-    "ld_kv_free_blocks", "ld_kv_assume", "ld_kv_swap_bytes", "ld_kv_swap_out", "ld_kv_swap_in", "ld_kv_fork", "ld_kv_set_sampling", "ld_prefill", "ld_decode_step", "ld_decode_run", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
+    "ld_kv_free_blocks", "ld_kv_assume", "ld_kv_swap_bytes", "ld_kv_swap_out", "ld_kv_swap_in", "ld_kv_fork", "ld_kv_trim", "ld_kv_set_sampling", "ld_prefill", "ld_decode_step", "ld_decode_run", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
     "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
     "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_prefill_attention_scratch_bytes",
     "ldk_prefill_attention", "ldk_argmax", "ldk_sample", "Model", "KV",
@@ -81,6 +81,7 @@ _SIGS = {
     "ld_kv_swap_out": (C.c_int, [_vp, C.c_int32, _vp, C.c_size_t, _vp]),
     "ld_kv_swap_in": (C.c_int, [_vp, C.c_int32, _vp, C.c_size_t, _vp]),
     "ld_prefill": (C.c_int, [_vp, C.c_int32, _i32p, C.c_int32, _vp, ld_token_cb, _vp, _f32p]),
+    "ld_kv_trim": (C.c_int, [_vp, C.c_int32, _i32p]),
     "ld_decode_step": (C.c_int, [_vp, _i32p, C.c_int32, _vp, ld_token_cb, _vp, _f32p]),
     "ld_decode_run": (C.c_int, [_vp, _i32p, C.c_int32, C.c_int32, _vp, ld_token_cb, _vp, _i32p]),
     "ld_step_mixed": (C.c_int, [_vp, _i32p, C.c_int32, _i32p, C.POINTER(_i32p), _i32p, C.c_int32, _vp,
@@ -285,6 +286,13 @@ def ld_decode_step(kv, seqs, stream=None, callback=None, logits_vocab=0, check=T
     cb = _cb(callback)
     rc = _check(lib().ld_decode_step(kv, sp, s.size, _stream(stream), cb, None, lp), check)
     return rc, lg
+
+
+def ld_kv_trim(kv, seq, check=True):
+    """Returns the number of blocks released (or the status if it failed and check is False)."""
+    n = C.c_int32(0)
+    rc = _check(lib().ld_kv_trim(kv, seq, C.byref(n)), check)
+    return n.value if rc == LD_OK else rc
 
 
 def ld_decode_run(kv, seqs, max_steps, stream=None, callback=None, check=True):

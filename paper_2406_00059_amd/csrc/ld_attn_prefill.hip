@@ -80,6 +80,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
     const int wave_first_pos = tile.z + wave * 32;                      // position of the wave's first query
     const int wave_low_hi = window > 0 ? max(wave_last_pos - window + 1, 0) : 0;   // lowest position its last query sees
     const int kv_start = window > 0 ? (max(tile.z - window + 1, 0) & ~(KVB - 1)) : 0;
+    // first position of the lowest block any row of the tile sees: block-table entries below it may belong
+    // to blocks the sequence has given up (ld_kv_trim) and are never dereferenced
+    const int first_held_pos = window > 0 ? (max(tile.z - window + 1, 0) & ~15) : 0;
 
     // Q operand: for k-step j the lane supplies dims half*64 + j*8 .. +8 of its query (hi and lo parts)
     bf16x8 qh[8], ql[8];
@@ -117,18 +120,31 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
     auto load_step = [&](int set, int kv0) {
 #pragma unroll
         for (int v = 0; v < 2; v++) {
-            // a block past the last needed position is read again from the last needed block; never used
-            const int pos = min(kv0 + 16 * v, wg_last_pos);
+            // a block past the last needed position is read again from the last needed block, one below
+            // the first visible block from that block; never used
+            const int pos = max(min(kv0 + 16 * v, wg_last_pos), first_held_pos);
             const bf16_t *blk = pool + (int64_t)trow[pos >> 4] * block_stride;
             kreg[set][v] = *reinterpret_cast<const u32x4 *>(blk + kv_k_offset(HD, kvh, kr, kc));
             vreg[set][v] = *reinterpret_cast<const u32x4 *>(blk + kv_v_offset(Hkv, HD, kvh, vh, vd));
         }
     };
-    auto stage = [&](int st, int set) {
+    // Values of positions past the tile's last row were never written (the rest of the last block, or the
+    // second block of a step that ends the walk): they may hold anything, also NaN, and a probability of zero
+    // does not neutralise a NaN, so they are staged as zeros.  (Keys need nothing: their scores are replaced,
+    // not multiplied.)
+    auto stage = [&](int st, int set, int kv0) {
 #pragma unroll
         for (int v = 0; v < 2; v++) {
             *reinterpret_cast<u32x4 *>(&ks[st][16 * v + kr][kc]) = kreg[set][v];
-            *reinterpret_cast<u32x4 *>(&vt[st][vd][16 * v + vh]) = vreg[set][v];
+            u32x4 vv = vreg[set][v];
+            const int p0 = kv0 + 16 * v + vh;      // position of this piece's first element
+            if (p0 + 7 > wg_last_pos) {
+#pragma unroll
+                for (int e = 0; e < 4; e++)
+                    vv[e] = (p0 + 2 * e <= wg_last_pos ? vv[e] & 0x0000ffffu : 0u) |
+                            (p0 + 2 * e + 1 <= wg_last_pos ? vv[e] & 0xffff0000u : 0u);
+            }
+            *reinterpret_cast<u32x4 *>(&vt[st][vd][16 * v + vh]) = vv;
         }
     };
     // this workgroup's share of the tile's steps (all of them when the grid has one split)
@@ -223,7 +239,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
                 // Stage this step, then fetch the step PF ahead into the set just emptied.  One barrier per
                 // step: a wave that writes buffer st for step n has passed the barrier of step n-1, which
                 // every wave reaches only after it has finished reading buffer st for step n-2.
-                stage(st, u);
+                stage(st, u, kv0);
                 lds_barrier();
                 if (kv0 + PF * KVB < kv_end) load_step(u, kv0 + PF * KVB);
                 if (wave_active && kv0 <= wave_last_pos && kv0 + KVB > wave_low) compute(kv0, st);   // else nothing visible to this wave

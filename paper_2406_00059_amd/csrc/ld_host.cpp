@@ -51,6 +51,7 @@ struct Seq {
     int32_t pending = -1;
     int64_t n_cached = 0;
     int32_t n_mapped = 0;          // logical blocks 0..n_mapped-1 may be mapped (holes possible via ld_kv_map)
+    int32_t first_block = 0;       // logical blocks below it were released by ld_kv_trim (attention band)
     int32_t dirty_lo = 0, dirty_hi = 0;  // table entries [lo, hi) not yet copied to the device
 };
 
@@ -174,15 +175,15 @@ int64_t blocks_for(const ld_kv *kv, int64_t tokens) {
 int64_t count_missing(const ld_kv *kv, int s, int64_t need) {
     int64_t miss = 0;
     const int32_t *t = kv->trow(s);
-    for (int64_t i = 0; i < need; i++) miss += t[i] < 0;
+    for (int64_t i = kv->seqs[s].first_block; i < need; i++) miss += t[i] < 0;
     return miss;
 }
 
-// Maps logical blocks 0..need-1 (pops from the free stack).  The caller has checked availability.
+// Maps logical blocks first_block..need-1 (pops from the free stack).  The caller has checked availability.
 void map_blocks(ld_kv *kv, int s, int64_t need) {
     int32_t *t = kv->trow(s);
     Seq &q = kv->seqs[s];
-    for (int64_t i = 0; i < need; i++) {
+    for (int64_t i = q.first_block; i < need; i++) {
         if (t[i] >= 0) continue;
         t[i] = kv->free_stack.back();
         kv->free_stack.pop_back();
@@ -636,7 +637,7 @@ ld_status ld_kv_swap_out(ld_kv *kv, ld_seq seq, void *host_buf, size_t bytes, vo
     const int64_t nb = blocks_for(kv, q->n_cached);
     int32_t *t = kv->trow(seq);
     // one strided copy per logical block: its n_layers pieces lie one layer slice apart in the pool
-    for (int64_t j = 0; j < nb; j++)
+    for (int64_t j = q->first_block; j < nb; j++)      // released blocks: their part of the buffer is not written
         LD_HIP_TRY(hipMemcpy2DAsync((char *)host_buf + (size_t)j * L * bb, bb, kv->pool + (size_t)t[j] * bb,
                                     (size_t)kv->n_blocks * bb, bb, L, hipMemcpyDeviceToHost, (hipStream_t)stream));
     release_blocks(kv, seq);
@@ -650,16 +651,36 @@ ld_status ld_kv_swap_in(ld_kv *kv, ld_seq seq, const void *host_buf, size_t byte
     if (!q->swapped) return fail(LD_E_STATE, "ld_kv_swap_in: sequence is not swapped out");
     if (bytes < ld_kv_swap_bytes(kv, seq)) return fail(LD_E_RANGE, "ld_kv_swap_in: host buffer too small");
     const int64_t nb = blocks_for(kv, q->n_cached);
-    if (nb > (int64_t)kv->free_stack.size()) return fail(LD_E_NOMEM, "ld_kv_swap_in: out of KV blocks");
+    if (count_missing(kv, seq, nb) > (int64_t)kv->free_stack.size()) return fail(LD_E_NOMEM, "ld_kv_swap_in: out of KV blocks");
     map_blocks(kv, seq, nb);
     const size_t bb = block_bytes(kv);
     const int L = kv->m->c.n_layers;
     const int32_t *t = kv->trow(seq);
-    for (int64_t j = 0; j < nb; j++)
+    for (int64_t j = q->first_block; j < nb; j++)
         LD_HIP_TRY(hipMemcpy2DAsync(kv->pool + (size_t)t[j] * bb, (size_t)kv->n_blocks * bb,
                                     (const char *)host_buf + (size_t)j * L * bb, bb, bb, L, hipMemcpyHostToDevice,
                                     (hipStream_t)stream));
     q->swapped = false;
+    return LD_OK;
+}
+
+ld_status ld_kv_trim(ld_kv *kv, ld_seq seq, int32_t *released) {
+    Seq *q = get_seq(kv, seq);
+    if (!q || !released) return fail(LD_E_INVAL, "ld_kv_trim: bad argument");
+    if (q->swapped) return fail(LD_E_STATE, "ld_kv_trim: sequence is swapped out");
+    *released = 0;
+    const ld_model_config &c = kv->m->c;
+    const int64_t low = q->n_cached - c.window + 1;      // lowest position the next query (at n_cached) sees
+    if (c.window <= 0 || low <= 0) return LD_OK;
+    const int64_t keep_from = low / c.kv_block;
+    int32_t *t = kv->trow(seq);
+    for (int64_t i = q->first_block; i < keep_from; i++)
+        if (t[i] >= 0) {
+            if (--kv->refs[t[i]] == 0) kv->free_stack.push_back(t[i]);
+            t[i] = -1;
+            ++*released;
+        }
+    if (keep_from > q->first_block) q->first_block = (int32_t)keep_from;
     return LD_OK;
 }
 
@@ -680,6 +701,10 @@ ld_status ld_kv_fork(ld_kv *kv, ld_seq parent, int64_t n_tokens, void *stream, l
     if (s == kv->max_seqs) return fail(LD_E_NOMEM, "ld_kv_fork: no free sequence handle");
     const int bs = kv->m->c.kv_block;
     const int64_t full = n_tokens / bs, tail = n_tokens % bs;
+    if (p->first_block > 0) {   // the child's next query must not need a block the parent has released
+        const int64_t low = std::max<int64_t>(n_tokens - kv->m->c.window + 1, 0);
+        if (low / bs < p->first_block) return fail(LD_E_STATE, "ld_kv_fork: the prefix reaches below the blocks the parent still holds");
+    }
     if (tail && kv->free_stack.empty()) return fail(LD_E_NOMEM, "ld_kv_fork: no block for the copied tail");
     const int32_t *pt = kv->trow(parent);
     int32_t *t = kv->trow(s);
@@ -687,9 +712,11 @@ ld_status ld_kv_fork(ld_kv *kv, ld_seq parent, int64_t n_tokens, void *stream, l
     q = Seq();
     q.active = true;
     q.n_cached = n_tokens;
-    for (int64_t j = 0; j < full; j++) { t[j] = pt[j]; kv->refs[pt[j]]++; }
+    const int32_t fb = p->first_block;
+    q.first_block = fb;
+    for (int64_t j = fb; j < full; j++) { t[j] = pt[j]; kv->refs[pt[j]]++; }
     q.n_mapped = (int32_t)full;
-    if (full) { q.dirty_lo = 0; q.dirty_hi = (int32_t)full; }
+    if (full > fb) { q.dirty_lo = fb; q.dirty_hi = (int32_t)full; }
     if (tail) {
         map_blocks(kv, s, full + 1);    // pops one block for logical block `full`
         const size_t bb = block_bytes(kv);
@@ -830,7 +857,7 @@ ld_status ld_decode_run(ld_kv *kv, const ld_seq *seqs, int32_t n_seqs, int32_t m
             Seq &q = kv->seqs[seqs[i]];
             const int64_t need = blocks_for(kv, q.n_cached + ahead + 1);
             const int32_t *t = kv->trow(seqs[i]);
-            for (int64_t j = 0; j < need; j++)
+            for (int64_t j = q.first_block; j < need; j++)
                 if (t[j] < 0) u.push_back({seqs[i], (int32_t)j, q.n_mapped});
             map_blocks(kv, seqs[i], need);
             rows[i] = {q.pending, (int32_t)(q.n_cached + ahead), seqs[i]};

@@ -135,6 +135,15 @@ def _attention_case(seed, lens, H, Hkv, hd, dtype, spare=5):
             table[b, j] = next(it)
     pdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     pool = gen.normal(seed, 2, (total, 2, Hkv, 16, hd), device=DEV).to(pdt)
+    # slots past a sequence's last position were never written: they may hold anything, so they hold NaN here
+    # (a masked probability of zero times NaN would still poison the output), and so do the blocks no table
+    # entry names
+    used = torch.zeros(total, dtype=torch.bool)
+    for b in range(B):
+        used[table[b, :nb[b]].long()] = True
+        if lens[b] % 16:
+            pool[table[b, nb[b] - 1], :, :, lens[b] % 16:, :] = float("nan")
+    pool[(~used).to(DEV)] = float("nan")
     q = gen.normal(seed, 3, (B, H, hd), device=DEV)
     return table, pool, q
 

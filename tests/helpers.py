@@ -25,6 +25,7 @@ class Pair:
         self.okv = oracle.KV(self.omodel, n_blocks, max_seqs, max_blocks)
         self.gmodel = ld.Model(shape, weights_to(w, "cuda"), max_chunk=max_chunk)
         self.gkv = ld.KV(self.gmodel, n_blocks, max_tokens, max_seqs, max_blocks)
+        self.gkv.pool.fill_(float("nan"))       # a caller's pool is uninitialised memory: every slot not yet written is NaN
         self.V = shape.vocab
 
     def alloc(self, reserve=0):

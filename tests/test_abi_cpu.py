@@ -231,6 +231,68 @@ def test_fork_at_block_boundaries_shares_blocks_by_holder_count():
     assert ld.ld_kv_fork(kv, again, 0, stream=0, check=False) == ld.LD_E_STATE
 
 
+def test_trim_follows_the_oracle_allocator_bit_exact():
+    """Sliding-window memory without a GPU: a seeded schedule of growing, trimming, forking at block
+    boundaries and freeing, run on the oracle's allocator and the library's side by side: released counts,
+    status codes, block tables (released entries read -1) and free counts are identical at every step."""
+    from dataclasses import replace
+    from workloads import make_weights
+    W = 37
+    shape = replace(TINY, window=W)
+    om = oracle.Model(shape, make_weights(TINY, 3))
+    okv = oracle.KV(om, 24, 4, 12)
+    m = _model(window=W, n_layers=shape.n_layers, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim)
+    kv = _kv(m, n_blocks=24, max_tokens=16, max_seqs=4, max_blocks=12)
+    rng = np.random.default_rng(5)
+    live = []
+    zeros = lambda n: np.zeros((n, shape.n_layers, 2, shape.n_kv_heads, shape.head_dim))
+    counts = {}
+    for it in range(300):
+        op = str(rng.choice(["new"] * (len(live) < 4) + ["grow", "grow", "trim", "trim", "fork"] * bool(live) + ["free"] * (len(live) > 1)))
+        if op == "new":
+            rc, so = okv.alloc(0); sg = ld.ld_kv_alloc(kv, 0)
+            assert rc == 0 and so == sg
+            live.append(sg)
+        elif op == "grow":
+            s = int(rng.choice(live)); n = int(rng.integers(1, 40))
+            rc_o = okv.inject(s, zeros(n), pending=1)
+            rc_g = ld.ld_kv_assume(kv, s, n, pending=1, check=False)
+            assert rc_o == rc_g, (it, rc_o, rc_g)
+        elif op == "trim":
+            s = int(rng.choice(live))
+            rc_o, n_o = okv.trim(s)
+            n_g = ld.ld_kv_trim(kv, s)
+            assert rc_o == 0 and n_o == n_g, (it, n_o, n_g)
+            counts["released"] = counts.get("released", 0) + n_o
+        elif op == "fork":
+            if len(live) == 4:
+                continue
+            p_ = int(rng.choice(live))
+            n = 16 * int(rng.integers(0, ld.ld_kv_len(kv, p_) // 16 + 1))
+            rc_o, co = okv.fork(p_, n)
+            cg = ld.ld_kv_fork(kv, p_, n, stream=0, check=False)
+            assert (rc_o == 0 and co == cg) or (rc_o != 0 and cg == rc_o), (it, rc_o, co, cg)
+            if rc_o == 0:
+                live.append(cg)
+            else:
+                counts["fork_refused"] = counts.get("fork_refused", 0) + 1
+        else:
+            s = int(rng.choice(live))
+            assert okv.free(s) == 0 and ld.ld_kv_free(kv, s) == 0
+            live.remove(s)
+        counts[op] = counts.get(op, 0) + 1
+        assert ld.ld_kv_free_blocks(kv) == okv.free_blocks(), (it, op)
+        for s in live:
+            assert ld.ld_kv_block_table(kv, s).tolist() == okv.block_table(s)[1].tolist(), (it, op, s)
+    assert counts["released"] > 10 and counts.get("fork_refused", 0) > 0, counts
+    # a swapped-out sequence cannot be trimmed (one without cached tokens swaps without a copy)
+    for s in live:
+        ld.ld_kv_free(kv, s)
+    e = ld.ld_kv_alloc(kv, 32)
+    ld.ld_kv_swap_out(kv, e, None, stream=0)
+    assert ld.ld_kv_trim(kv, e, check=False) == ld.LD_E_STATE
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The benchmark measures one GPU; asking for more exits with a message instead of a number."""
     import subprocess, sys

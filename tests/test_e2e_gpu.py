@@ -463,3 +463,60 @@ def test_decode_run_stops_before_a_step_it_cannot_reserve():
     assert P.okv.decode(a)[0] == oracle.E_NOMEM
     rc, done = ld.ld_decode_run(h, [b], 3)                           # b alone still has room in its block
     assert done == 3
+
+
+@pytest.mark.parametrize("shape,tol", [(replace(TINY, window=21, name="tiny-band"), 1e-4),
+                                       (replace(TINY, dtype="bf16", n_kv_heads=1, window=40, name="tiny-bf16-gqa-band"), 2e-2)])
+def test_sliding_window_memory_trim(shape, tol):
+    """Sequences with an attention band give up the blocks below it (ld_kv_trim) after every step: released
+    counts, tables and free counts equal the oracle's, tokens equal and logits within tolerance -- while a
+    stranger takes the released blocks and overwrites them, through a chunked observation, a fork from the
+    trimmed parent (refused below the band, shared above), and a swap out and in of the trimmed sequence."""
+    P = Pair(shape, 31, n_blocks=20, max_tokens=32, max_seqs=4, max_blocks=12, max_chunk=16)
+    h, V = P.gkv.h, shape.vocab
+    s = P.alloc()
+    sink, errs = Tokens(), []
+
+    def trim(q):
+        rc, n_o = P.okv.trim(q)
+        assert rc == 0 and ld.ld_kv_trim(h, q) == n_o
+        assert P.tables_equal(q) and ld.ld_kv_free_blocks(h) == P.okv.free_blocks()
+        return n_o
+
+    def feed(q, toks):
+        rc, t, lg_o = P.okv.prefill(q, toks)
+        rc_g, lg = ld.ld_prefill(h, q, toks, callback=sink, logits_vocab=V)
+        assert rc == 0 and sink.last() == [t]
+        errs.append(rel_err(lg, lg_o))
+
+    feed(s, prompt(31, 1, 70, V))
+    assert trim(s) == (70 - shape.window + 1) // 16
+    other = P.alloc()
+    feed(other, prompt(31, 2, 48, V))                     # lands on the released blocks first (LIFO)
+    released = 0
+    for step in range(40):
+        ref = [P.okv.decode(q) for q in (s, other)]
+        rc, lg = ld.ld_decode_step(h, [s, other], callback=sink, logits_vocab=V)
+        assert sink.last(2) == [r[1] for r in ref], step
+        errs += [rel_err(lg[i], ref[i][2]) for i in range(2)]
+        released += trim(s) + trim(other)
+    assert released >= 3
+    feed(s, prompt(31, 3, 37, V))                         # observation in chunks of 16 behind the trimmed prefix
+    trim(s)
+    n = ld.ld_kv_len(h, s)
+    assert ld.ld_kv_fork(h, s, 32, check=False) == ld.LD_E_STATE and P.okv.fork(s, 32)[0] == oracle.E_STATE
+    rc, co = P.okv.fork(s, n)                             # its next query sees exactly what the parent's does
+    cg = ld.ld_kv_fork(h, s, n)
+    assert rc == 0 and co == cg and P.tables_equal(cg) and ld.ld_kv_free_blocks(h) == P.okv.free_blocks()
+    feed(cg, prompt(31, 4, 9, V))
+    host = torch.empty(ld.ld_kv_swap_bytes(h, s), dtype=torch.uint8, pin_memory=True)
+    rc, store = P.okv.swap_out(s)
+    assert rc == 0 and ld.ld_kv_swap_out(h, s, host) == 0 and ld.ld_kv_free_blocks(h) == P.okv.free_blocks()
+    assert P.okv.swap_in(s, store) == 0 and ld.ld_kv_swap_in(h, s, host) == 0 and P.tables_equal(s)
+    for step in range(20):
+        ref = [P.okv.decode(q) for q in (cg, s)]
+        rc, lg = ld.ld_decode_step(h, [cg, s], callback=sink, logits_vocab=V)
+        assert sink.last(2) == [r[1] for r in ref], step
+        errs += [rel_err(lg[i], ref[i][2]) for i in range(2)]
+        trim(cg); trim(s)
+    assert max(errs) <= tol, max(errs)

@@ -109,6 +109,17 @@ def test_7b_width_batch32_continuous_batching_with_mixed_step(base):
     errs = []
     for step in range(1, 7):
         sink = Tokens()
+        if step in (3, 4) and shape.window:
+            # sliding-window memory: every sequence gives up the blocks below its band, before a decode step and
+            # before the mixed step (whose chunk kernel walks from the band's first block)
+            n_rel = 0
+            for s in seqs:
+                rc_o, n_o = P.okv.trim(s)
+                assert rc_o == 0 and ld.ld_kv_trim(P.gkv.h, s) == n_o
+                n_rel += n_o
+            assert ld.ld_kv_free_blocks(P.gkv.h) == P.okv.free_blocks()
+            if step == 3:       # two steps in: each sequence holds n + 2 positions
+                assert n_rel == sum(max(0, n + 2 - shape.window + 1) // 16 for n in lens) > 1000
         if step == 4:
             pick = gen.permutation(seed, 3000 + step, B)[:4].tolist()
             pf = [seqs[i] for i in pick]; dec = [s for s in seqs if s not in pf]

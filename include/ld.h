@@ -111,7 +111,8 @@ size_t ld_workspace_bytes(const ld_model *m, int32_t max_tokens, int32_t max_seq
 
 /* Creates the paged cache over caller-owned DEVICE memory: `pool` of ld_kv_bytes(m, n_blocks)
  * bytes and `ws` of at least ld_workspace_bytes(...) bytes, both 256-byte aligned.  The pool's
- * contents are not touched.  No device call is made here (pinned staging is created lazily by
+ * contents are not touched and need not be initialised: a slot is read only after a step has written
+ * it (what an unwritten slot holds, NaN patterns included, never reaches a result).  No device call is made here (pinned staging is created lazily by
  * the first step).  The free list is a LIFO stack whose first pops return blocks 0, 1, 2, ... */
 ld_status ld_kv_create(ld_model *m, void *pool, int64_t n_blocks, void *ws, size_t ws_bytes,
                        int32_t max_tokens, int32_t max_seqs, int32_t max_blocks_per_seq, ld_kv **out);

@@ -656,7 +656,7 @@ int env_int(const char *name, int dflt) {
 // smallest estimated time.  A candidate runs ceil(workgroups / 256) rounds of one workgroup per CU (two for
 // the 128 x 128 tile, at half the rate each); the per-CU rates are the measured full-grid rates of the three
 // tiles; split-K adds the write and the ordered re-read of its partial sums.
-struct BigPlan { int wm, bn, n_ttiles, n_nblocks, ks; };
+struct BigPlan { int wm, bn, n_ttiles, n_nblocks, ks; double est_us; };
 BigPlan plan_big(int T, int N, int K, int epi) {
     const bool swi = epi == ld::GEMM_SWIGLU;
     struct Tile { int wm, bn; double tflops; };           // nominal (unsplit) TFLOP/s of a full grid
@@ -678,7 +678,7 @@ BigPlan plan_big(int T, int N, int K, int epi) {
             const double wg_us = 2.0 * bm * tl.bn * (double)(K / ks) / (tl.tflops * 1e6 / 256.0);
             double t = rounds * wg_us;
             if (ks > 1) t += 3.0 + (double)T * N * (swi ? 2 : 1) * 4.0 * (2.0 * ks + 1.0) / 3.0e6;
-            if (t < best_t) { best_t = t; best = {tl.wm, tl.bn, n_tt, n_nb, ks}; }
+            if (t < best_t) { best_t = t; best = {tl.wm, tl.bn, n_tt, n_nb, ks, t}; }
         }
     }
     return best;
@@ -704,13 +704,12 @@ int split_factor(int T, int N, int K, int epi) {
 }
 
 template <int TT, int WC, int KCH>
-void launch_shape(const bf16_t *W, const bf16_t *xs, int T, int N, int K, int epi, float *y, float *partial,
-                  hipStream_t s) {
+void launch_shape(const bf16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
+                  float *partial, hipStream_t s) {
     const int n_ttiles = (T + TT * 32 - 1) / (TT * 32);
     const int n_nblocks = (N + 128 * WC - 1) / (128 * WC);
     const int ks = split_factor(T, N, K, epi);
     const int grid = ((n_nblocks + 7) / 8) * 8 * n_ttiles * ks;
-    const bf16_t *hi = xs, *lo = xs + (size_t)T * K;
     const int rgrid = (int)(((int64_t)T * N + 255) / 256);
 #define LD_GEMM(EPI_)                                                                                                  \
     do {                                                                                                               \
@@ -732,9 +731,27 @@ bool gemm_supported(int T, int N, int K) { return T >= 2 && N > 0 && K > 0 && K 
 
 size_t gemm_split_bytes(int T, int K) { return (((size_t)2 * T * K * sizeof(bf16_t)) + 255) / 256 * 256; }
 
-size_t gemm_scratch_bytes(int T, int N, int K, int epi) {
+// Rows that would only start one more, nearly empty 256-row tile (a mixed step's 4 x 257 + 28 rows, a 2048-row
+// chunk beside 63 decode rows) are cut off and go through the small-batch kernels: the weights are streamed
+// once more, which costs less than a tile of padding.  Returns the number of such tail rows (0: no cut),
+// decided by the same cost model that picks the tile.
+int tail_rows(int T, int N, int K, int epi) {
+    const int r = T % 256;
+    static const int enabled = env_int("LD_GEMM_TAIL", 1);   // tuning knob: 0 keeps every row in the tiled kernel
+    if (!enabled || T <= 256 || r == 0 || r > 64 || getenv("LD_GEMM_BIG")) return 0;
+    const double whole = plan_big(T, N, K, epi).est_us, main_part = plan_big(T - r, N, K, epi).est_us;
+    const double tail = (double)N * (epi == GEMM_SWIGLU ? 2 : 1) * K * 2.0 / 4.0e6 + 12.0;   // ~4 TB/s + two launches
+    return main_part + tail < whole ? r : 0;
+}
+
+static size_t partial_bytes(int T, int N, int K, int epi) {
     const int ks = split_factor(T, N, K, epi);
-    const size_t part = (ks > 1 || T <= 32) ? (size_t)ks * T * N * (epi == GEMM_SWIGLU ? 2 : 1) * sizeof(float) : 0;
+    return (ks > 1 || T <= 32) ? (size_t)ks * T * N * (epi == GEMM_SWIGLU ? 2 : 1) * sizeof(float) : 0;
+}
+
+size_t gemm_scratch_bytes(int T, int N, int K, int epi) {
+    const int r = tail_rows(T, N, K, epi);
+    const size_t part = r ? std::max(partial_bytes(T - r, N, K, epi), partial_bytes(r, N, K, epi)) : partial_bytes(T, N, K, epi);
     return gemm_split_bytes(T, K) + part;
 }
 
@@ -751,11 +768,10 @@ void launch_gemm_skinny(const uint16_t *W, const uint16_t *xhi, const uint16_t *
                        partial);
 }
 
-void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s) {
-    float *partial = (float *)((char *)xs + gemm_split_bytes(T, K));
+static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
+                      float *partial, hipStream_t s) {
     if (T <= 32) {
         const int ks = split_factor(T, N, K, epi), n_rows = N * (epi == GEMM_SWIGLU ? 2 : 1);
-        const bf16_t *hi = xs, *lo = xs + (size_t)T * K;
         LD_LAUNCH(k_gemm_skinny, dim3(((n_rows + 127) / 128) * ks), dim3(256), 0, s, W, hi, lo, T, n_rows, K, ks,
                            partial);
         const int rgrid = (int)(((int64_t)T * N + 255) / 256);
@@ -767,7 +783,6 @@ void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int
     if (T > 64) {
         const BigPlan p = plan_big(T, N, K, epi);
         const int grid = ((p.n_nblocks + 7) / 8) * 8 * p.n_ttiles * p.ks;
-        const bf16_t *hi = xs, *lo = xs + (size_t)T * K;
         const int rgrid = (int)(((int64_t)T * N + 255) / 256);
 #define LD_BIG(WM_, BN_, D_, EPI_)                                                                                     \
     do {                                                                                                               \
@@ -817,7 +832,16 @@ void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int
 #undef LD_BIG
         return;
     }
-    launch_shape<2, 1, 128>(W, xs, T, N, K, epi, y, partial, s);   // 33..64 rows
+    launch_shape<2, 1, 128>(W, hi, lo, T, N, K, epi, y, partial, s);   // 33..64 rows
+}
+
+void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s) {
+    float *partial = (float *)((char *)xs + gemm_split_bytes(T, K));
+    const bf16_t *hi = xs, *lo = xs + (size_t)T * K;
+    const int r = tail_rows(T, N, K, epi);
+    gemm_rows(W, hi, lo, T - r, N, K, epi, y, partial, s);
+    // the tail reuses the partial-sum scratch: the stream orders it behind the main part's reduction
+    if (r) gemm_rows(W, hi + (size_t)(T - r) * K, lo + (size_t)(T - r) * K, r, N, K, epi, y + (size_t)(T - r) * N, partial, s);
 }
 
 }  // namespace ld

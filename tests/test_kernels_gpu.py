@@ -419,9 +419,11 @@ def test_linear_big_tile_every_plan(plan, epi, monkeypatch):
 
 
 def test_linear_matrix_core_7b_shapes_sampled():
-    """Launch shapes of the batch-32 decode step, of a 256-row prefill chunk and of a mixed step
-    (32 decode rows + four 256-row chunks), sampled outputs."""
-    for T in (32, 256, 1056):
+    """Launch shapes of the batch-32 decode step, of a 256-row prefill chunk, of a mixed step (32 decode rows
+    + four 256-row chunks) and of a 2048-row chunk beside 63 decode rows, sampled outputs.  The last two have
+    a tail of 32 / 63 rows past the last full 256-row tile, which is cut off and computed by the small-batch
+    kernels: the rows on both sides of the cut are among the samples."""
+    for T in (32, 256, 1056, 2111):
         for N, K, epi in [(12288, 4096, ld.LDK_STORE), (4096, 11008, ld.LDK_ADD), (11008, 4096, ld.LDK_SWIGLU)]:
             rows = N * (2 if epi == ld.LDK_SWIGLU else 1)
             W = gen.normal(3, N, (rows, K), std=0.02, device=DEV).bfloat16()
@@ -430,7 +432,7 @@ def test_linear_matrix_core_7b_shapes_sampled():
             scratch = torch.empty(ld.ldk_linear_scratch_bytes(T, N, K, epi), dtype=torch.uint8, device=DEV)
             ld.ldk_linear(W, x, y, epi, scratch=scratch)
             ns = gen.randint(3, 9, 0, N - 1, 6).tolist() + [0, N - 1]
-            ts = sorted(set(gen.randint(3, 10, 0, T - 1, 5).tolist() + [0, T - 1]))
+            ts = sorted(set(gen.randint(3, 10, 0, T - 1, 5).tolist() + [0, T - 1, max(T - T % 256 - 1, 0), min(T - T % 256, T - 1)]))
             xh = x.cpu().numpy(); yh = y.cpu().numpy()
             for n in ns:
                 wr = oracle.to_host_matrix(W[n:n + 1]); wu = oracle.to_host_matrix(W[N + n:N + n + 1]) if epi == ld.LDK_SWIGLU else None

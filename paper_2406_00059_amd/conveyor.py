@@ -165,13 +165,16 @@ class Scheduler:
     """Token-granularity scheduler (section 3.3).  `engine` provides
          new_sequence() -> seq, prefill(seq, tokens) -> token, decode(seqs) -> tokens, free(seq)."""
 
-    def __init__(self, engine, partial=True, retention="keep", predict_tool_s=None, rates=None, shared_prefix=0):
+    def __init__(self, engine, partial=True, retention="keep", predict_tool_s=None, rates=None, shared_prefix=0,
+                 trim=False):
         """retention: "keep" | "swap" | "discard" | "auto".  "auto" asks choose_retention with
         predict_tool_s(plugin) seconds and rates = dict(kv_bytes_per_token, swap_bytes_per_s,
         prefill_tokens_per_s).  "swap" needs engine.swap_out / engine.swap_in.
         shared_prefix = k > 0: all prompts start with the same k tokens (system prompt, tool descriptions);
-        they are prefilled once and every request forks from that cache (engine.fork)."""
-        self.engine, self.partial, self.retention = engine, partial, retention
+        they are prefilled once and every request forks from that cache (engine.fork).
+        trim: after every prefill (prompt or observation) the sequence gives up the cache blocks below its
+        attention band (engine.trim; models with a band only)."""
+        self.engine, self.partial, self.retention, self.trim = engine, partial, retention, trim
         self.predict_tool_s, self.rates, self.shared_prefix = predict_tool_s, rates or {}, shared_prefix
 
     def serve(self, requests):
@@ -226,6 +229,8 @@ class Scheduler:
                     x["history"].extend(x["feed"])
                     self._emit(x, eng.prefill(x["seq"], x["feed"]))
                     x["feed"] = None
+                    if self.trim:                     # blocks that fell out of the attention band go back to the pool
+                        eng.trim(x["seq"])
                 elif x["left"] > 0:
                     decoding.append(x)
             # (2)+(3) one decoding iteration for every sequence that is generating; tokens go to the parsers
@@ -315,6 +320,10 @@ class LdEngine:
     def fork(self, parent, n_tokens):
         return self.ld.ld_kv_fork(self.kv, parent, n_tokens, self.stream)
 
+    def trim(self, seq):
+        """Sliding-window memory: give up the blocks below the attention band (nothing without a band)."""
+        return self.ld.ld_kv_trim(self.kv, seq)
+
     def swap_out(self, seq):
         import torch                                  # pinned host memory only
         buf = torch.empty(max(self.ld.ld_kv_swap_bytes(self.kv, seq), 1), dtype=torch.uint8, pin_memory=True)
@@ -364,6 +373,9 @@ class FakeEngine:
         child = self.new_sequence()
         self.hist[child] = self.hist[parent][:n_tokens]
         return child
+
+    def trim(self, seq):
+        return 0
 
     def swap_out(self, seq):
         self.swapped.add(seq)

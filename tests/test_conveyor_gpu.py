@@ -87,3 +87,23 @@ def test_shared_prompt_prefix_on_the_engine():
             feed = rd.tool.observation if rd.tool else None
         assert ref == r.tokens
         P.okv.free(s)
+
+
+def test_trimming_below_the_attention_band_changes_nothing():
+    """A banded model served with and without sliding-window memory: the same tokens, and with trimming the
+    pool's low-water mark of free blocks is higher (the sequences hold only their bands)."""
+    from dataclasses import replace
+    shape = replace(TINY, window=24, name="tiny-band")
+    P = Pair(shape, 32, n_blocks=64, max_tokens=64, max_seqs=3, max_blocks=16)
+
+    class Watch(cv.LdEngine):
+        low = 10 ** 9
+        def decode(self, seqs):
+            self.low = min(self.low, ld.ld_kv_free_blocks(self.kv))
+            return super().decode(seqs)
+
+    plain, trimmed = Watch(ld, P.gkv.h), Watch(ld, P.gkv.h)
+    a = cv.serve(plain, _requests(0.0), partial=False)
+    b = cv.serve(trimmed, _requests(0.0), partial=False, trim=True)
+    assert [r.tokens for r in a] == [r.tokens for r in b] and all(len(r.tokens) == 96 for r in b)
+    assert trimmed.low > plain.low and ld.ld_kv_free_blocks(P.gkv.h) == 64

@@ -368,7 +368,7 @@ def test_linear_two_to_four_rows_every_row_length(T, K):
     assert np.max(np.abs(y.cpu().numpy() - plain)) <= 2e-5 * np.abs(plain).max()
 
 
-@pytest.mark.parametrize("T", [2, 5, 31, 32, 33, 64, 100, 257])
+@pytest.mark.parametrize("T", [2, 5, 31, 32, 33, 64, 100, 257, 300, 320, 321])
 @pytest.mark.parametrize("epi", ["store", "add_norm", "swiglu_norm"])
 def test_linear_matrix_core_path(T, epi):
     """bf16 matrices, several rows, K a multiple of 128, scratch given: the MFMA kernel with split

@@ -71,7 +71,7 @@ def test_7b_full_depth_prompt_and_decode():
 
 def test_7b_batch1_decode_at_context_1024_32_steps():
     """The benchmark's batch-1 launch configuration: 32-layer 7B shape, context 1024 (injected history),
-    32 greedy decode steps: tokens identical, logits within 2e-2."""
+    32 greedy decode steps: tokens identical, logits within 2e-2; then 16 more in one ld_decode_run."""
     P = Pair(LLAMA7B, SEED_BASE + 2, n_blocks=72, max_tokens=8, max_seqs=1, max_blocks=72, gen_device="cuda")
     s = P.alloc()
     inject_history(P, s, 1024, SEED_BASE + 2, 900, pending=17)
@@ -85,6 +85,12 @@ def test_7b_batch1_decode_at_context_1024_32_steps():
     assert max(errs) <= 2e-2
     assert sink.last(32) == toks_o
     assert P.tables_equal(s) and ld.ld_kv_len(P.gkv.h, s) == 1056
+    # the same steps as the benchmark issues them: one multi-step run, the callback one step behind the GPU
+    more = [P.okv.decode(s, want_logits=False)[1] for _ in range(16)]
+    run = Tokens()
+    rc, done = ld.ld_decode_run(P.gkv.h, [s], 16, callback=run)
+    assert done == 16 and [t for _, t, _ in run.log] == more and [p for _, _, p in run.log] == list(range(1057, 1073))
+    assert P.tables_equal(s) and ld.ld_kv_len(P.gkv.h, s) == 1072
 
 
 @pytest.mark.parametrize("base", [LLAMA7B, MISTRAL7B], ids=["mha", "gqa-band"])

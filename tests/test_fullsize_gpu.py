@@ -143,6 +143,13 @@ def test_7b_width_batch32_continuous_batching_with_mixed_step(base):
             assert sink.log[i][1] == t_o, (step, i, errs[-1])
     print("batch 32: max logits rel err", max(errs))
     assert max(errs) <= 2e-2
+    # three more steps the way the benchmark issues them (one multi-step run over all 32 sequences)
+    ref = []
+    for _ in range(3):
+        ref += [(s, P.okv.decode(s, want_logits=False)[1]) for s in seqs]
+    run = Tokens()
+    rc, done = ld.ld_decode_run(P.gkv.h, seqs, 3, callback=run)
+    assert done == 3 and [(q, t) for q, t, _ in run.log] == ref
     for s in seqs:
         assert P.tables_equal(s)
 

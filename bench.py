@@ -378,7 +378,7 @@ def run_13b(args, ld, torch):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        print("bench.py: this library runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
     import paper_2406_00059_amd as ld

@@ -305,7 +305,7 @@ template <int WM, int BN, int D, int EPI>
 __global__ __launch_bounds__(128 * WM) void k_gemm_big(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
                                                        const bf16_t *__restrict__ xlo, int T, int N, int K,
                                                        float *__restrict__ y, int n_ttiles, int ks,
-                                                       float *__restrict__ partial) {
+                                                       float *__restrict__ partial, int col0, int col1) {
     constexpr bool SWI = (EPI == ld::GEMM_SWIGLU);
     constexpr int NT = 128 * WM;                  // threads
     constexpr int BM = 64 * WM, BK = 32, SEGS = BK / 8;
@@ -318,9 +318,9 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_big(const bf16_t *__restrict_
 
     const int b = blockIdx.x, xcd = b & 7, s = b >> 3;
     const int kz = s % ks, tt_idx = (s / ks) % n_ttiles, nb = (s / (ks * n_ttiles)) * 8 + xcd;
-    const int n_nblocks = (N + NOUT - 1) / NOUT;
+    const int n_nblocks = (col1 - col0 + NOUT - 1) / NOUT;   // this launch covers output columns [col0, col1)
     if (nb >= n_nblocks) return;
-    const int t0 = tt_idx * BM, n0 = nb * NOUT;
+    const int t0 = tt_idx * BM, n0 = col0 + nb * NOUT;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
@@ -419,7 +419,7 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_big(const bf16_t *__restrict_
 #pragma unroll
     for (int wc = 0; wc < WOUT; wc++) {
         const int n = n0 + wn * (NOUT / 2) + wc * 32 + l32;
-        if (n >= N) continue;
+        if (n >= col1) continue;
 #pragma unroll
         for (int tt = 0; tt < 2; tt++)
 #pragma unroll
@@ -458,7 +458,7 @@ template <int WM, int BN, int S, int EPI>
 __global__ __launch_bounds__(128 * WM) void k_gemm_dma(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
                                                        const bf16_t *__restrict__ xlo, int T, int N, int K,
                                                        float *__restrict__ y, int n_ttiles, int ks,
-                                                       float *__restrict__ partial) {
+                                                       float *__restrict__ partial, int col0, int col1) {
     constexpr bool SWI = (EPI == ld::GEMM_SWIGLU);
     constexpr int NW = 2 * WM;                    // waves
     constexpr int BM = 64 * WM, BK = 32;
@@ -472,9 +472,9 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_dma(const bf16_t *__restrict_
 
     const int b = blockIdx.x, xcd = b & 7, s = b >> 3;
     const int kz = s % ks, tt_idx = (s / ks) % n_ttiles, nb = (s / (ks * n_ttiles)) * 8 + xcd;
-    const int n_nblocks = (N + NOUT - 1) / NOUT;
+    const int n_nblocks = (col1 - col0 + NOUT - 1) / NOUT;   // this launch covers output columns [col0, col1)
     if (nb >= n_nblocks) return;
-    const int t0 = tt_idx * BM, n0 = nb * NOUT;
+    const int t0 = tt_idx * BM, n0 = col0 + nb * NOUT;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
@@ -604,7 +604,7 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_dma(const bf16_t *__restrict_
 #pragma unroll
     for (int wc = 0; wc < WOUT; wc++) {
         const int n = n0 + wn * (NOUT / 2) + wc * 32 + l32;
-        if (n >= N) continue;
+        if (n >= col1) continue;
 #pragma unroll
         for (int tt = 0; tt < 2; tt++)
 #pragma unroll
@@ -631,17 +631,19 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_dma(const bf16_t *__restrict_
 // Adds the ks K-slab partial sums in slab order and applies the epilogue.  One thread per output.
 template <int EPI>
 __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__ partial, int T, int N, int ks,
-                                                       float *__restrict__ y) {
+                                                       float *__restrict__ y, int col0, int col1) {
     constexpr int WR = (EPI == ld::GEMM_SWIGLU) ? 2 : 1;
+    const int nc = col1 - col0;                    // output columns [col0, col1) of N
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (int64_t)T * N) return;
-    const int t = (int)(idx / N), n = (int)(idx % N);
+    if (idx >= (int64_t)T * nc) return;
+    const int t = (int)(idx / nc), n = col0 + (int)(idx % nc);
     const float *p0 = partial + (int64_t)t * (WR * N) + n;
     const float a = slab_sum(p0, (int64_t)T * (WR * N), ks, 0.f);
     const float b = WR == 2 ? slab_sum(p0 + N, (int64_t)T * (WR * N), ks, 0.f) : 0.f;
-    if constexpr (EPI == ld::GEMM_STORE) y[idx] = a;
-    else if constexpr (EPI == ld::GEMM_ADD) y[idx] += a;
-    else y[idx] = a / (1.0f + __expf(-a)) * b;
+    float *dst = y + (int64_t)t * N + n;
+    if constexpr (EPI == ld::GEMM_STORE) *dst = a;
+    else if constexpr (EPI == ld::GEMM_ADD) *dst += a;
+    else *dst = a / (1.0f + __expf(-a)) * b;
 }
 
 // Kernel by row count: up to 32 rows -> k_gemm_skinny; 33..64 rows -> k_gemm_mfma with 64 x 128 tiles and
@@ -656,7 +658,7 @@ int env_int(const char *name, int dflt) {
 // smallest estimated time.  A candidate runs ceil(workgroups / 256) rounds of one workgroup per CU (two for
 // the 128 x 128 tile, at half the rate each); the per-CU rates are the measured full-grid rates of the three
 // tiles; split-K adds the write and the ordered re-read of its partial sums.
-struct BigPlan { int wm, bn, n_ttiles, n_nblocks, ks; double est_us; };
+struct BigPlan { int wm, bn, n_ttiles, n_nblocks, ks; double est_us; int nb_a, ks_b; };   // nb_a > 0: two phases
 BigPlan plan_big(int T, int N, int K, int epi) {
     const bool swi = epi == ld::GEMM_SWIGLU;
     struct Tile { int wm, bn; double tflops; };           // nominal (unsplit) TFLOP/s of a full grid
@@ -678,7 +680,24 @@ BigPlan plan_big(int T, int N, int K, int epi) {
             const double wg_us = 2.0 * bm * tl.bn * (double)(K / ks) / (tl.tflops * 1e6 / 256.0);
             double t = rounds * wg_us;
             if (ks > 1) t += 3.0 + (double)T * N * (swi ? 2 : 1) * 4.0 * (2.0 * ks + 1.0) / 3.0e6;
-            if (t < best_t) { best_t = t; best = {tl.wm, tl.bn, n_tt, n_nb, ks, t}; }
+            if (t < best_t) { best_t = t; best = {tl.wm, tl.bn, n_tt, n_nb, ks, t, 0, 0}; }
+        }
+        // Two phases: the column blocks that fill a whole round run unsplit; the remaining blocks, which would
+        // leave most CUs idle for a second round, run with a split K (their partial sums only).  Only between one
+        // and two rounds of the 256 x 256 tile: with more rounds the workgroups stagger and the last round
+        // costs less than the model's whole round (measured: no gain, or a loss with the smaller tiles).
+        static const int two_phase = env_int("LD_GEMM_TWO_PHASE", 1);   // tuning knob
+        const int64_t n_all = (int64_t)n_tt * n_nb;
+        if (two_phase && !f_wm && tl.wm == 4 && n_all > 256 && n_all < 512) {
+            const int nb_a = (int)(n_all / 256 * 256 / n_tt), nb_b = n_nb - nb_a;
+            const double wg_us = 2.0 * bm * tl.bn * (double)K / (tl.tflops * 1e6 / 256.0);
+            const double t_a = (double)(((int64_t)nb_a * n_tt + 255) / 256) * wg_us;
+            for (int ks = 2; ks <= max_ks && nb_a > 0 && nb_b > 0; ks++) {
+                const int64_t rounds_b = ((int64_t)nb_b * n_tt * ks + 255) / 256;
+                const double cols_b = (double)std::min(N - nb_a * nout, nb_b * nout);
+                const double t = t_a + rounds_b * wg_us / ks + 6.0 + (double)T * cols_b * (swi ? 2 : 1) * 4.0 * (2.0 * ks + 1.0) / 3.0e6;
+                if (t < best_t) { best_t = t; best = {tl.wm, tl.bn, n_tt, n_nb, 1, t, nb_a, ks}; }
+            }
         }
     }
     return best;
@@ -690,7 +709,7 @@ Shape pick_shape(int T, int epi) {
 
 int split_factor(int T, int N, int K, int epi) {
     if (T <= 32) return (K + SL - 1) / SL;        // skinny kernel: one 512-wide slab per workgroup
-    if (T > 64) return plan_big(T, N, K, epi).ks;
+    if (T > 64) { const BigPlan p = plan_big(T, N, K, epi); return std::max(p.ks, p.ks_b); }
     const Shape sh = pick_shape(T, epi);
     const int n_ttiles = (T + sh.tt * 32 - 1) / (sh.tt * 32), n_nblocks = (N + 128 * sh.wc - 1) / (128 * sh.wc);
     const int wgs = n_ttiles * n_nblocks;
@@ -715,7 +734,7 @@ void launch_shape(const bf16_t *W, const bf16_t *hi, const bf16_t *lo, int T, in
     do {                                                                                                               \
         LD_LAUNCH((k_gemm_mfma<TT, WC, KCH, EPI_>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, n_ttiles, \
                            ks, partial);                                                                               \
-        if (ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);   \
+        if (ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N);   \
     } while (0)
     if (epi == ld::GEMM_STORE) LD_GEMM(ld::GEMM_STORE);
     else if (epi == ld::GEMM_ADD) LD_GEMM(ld::GEMM_ADD);
@@ -768,27 +787,18 @@ void launch_gemm_skinny(const uint16_t *W, const uint16_t *xhi, const uint16_t *
                        partial);
 }
 
-static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
-                      float *partial, hipStream_t s) {
-    if (T <= 32) {
-        const int ks = split_factor(T, N, K, epi), n_rows = N * (epi == GEMM_SWIGLU ? 2 : 1);
-        LD_LAUNCH(k_gemm_skinny, dim3(((n_rows + 127) / 128) * ks), dim3(256), 0, s, W, hi, lo, T, n_rows, K, ks,
-                           partial);
-        const int rgrid = (int)(((int64_t)T * N + 255) / 256);
-        if (epi == GEMM_STORE) LD_LAUNCH((k_splitk_reduce<GEMM_STORE>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
-        else if (epi == GEMM_ADD) LD_LAUNCH((k_splitk_reduce<GEMM_ADD>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
-        else LD_LAUNCH((k_splitk_reduce<GEMM_SWIGLU>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y);
-        return;
-    }
-    if (T > 64) {
-        const BigPlan p = plan_big(T, N, K, epi);
-        const int grid = ((p.n_nblocks + 7) / 8) * 8 * p.n_ttiles * p.ks;
-        const int rgrid = (int)(((int64_t)T * N + 255) / 256);
+// One launch of the big-tile kernel over output columns [col0, col1) with split factor ks (+ its reduction).
+static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
+                            float *partial, int wm, int bn, int n_ttiles, int ks, int col0, int col1, hipStream_t s) {
+    const int nout = epi == GEMM_SWIGLU ? bn / 2 : bn;
+    const int n_nblocks = (col1 - col0 + nout - 1) / nout;
+    const int grid = ((n_nblocks + 7) / 8) * 8 * n_ttiles * ks;
+    const int rgrid = (int)(((int64_t)T * (col1 - col0) + 255) / 256);
 #define LD_BIG(WM_, BN_, D_, EPI_)                                                                                     \
     do {                                                                                                               \
         LD_LAUNCH((k_gemm_big<WM_, BN_, D_, EPI_>), dim3(grid), dim3(128 * WM_), 0, s, W, hi, lo, T, N, K, y,           \
-                  p.n_ttiles, p.ks, partial);                                                                          \
-        if (p.ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, p.ks, y);       \
+                  n_ttiles, ks, partial, col0, col1);                                                                  \
+        if (ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1); \
     } while (0)
 #define LD_DMA(WM_, BN_, S_, EPI_)                                                                                     \
     do {                                                                                                               \
@@ -800,36 +810,61 @@ static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int
             attr_set = true;                                                                                           \
         }                                                                                                              \
         LD_LAUNCH((k_gemm_dma<WM_, BN_, S_, EPI_>), dim3(grid), dim3(128 * WM_), lds_bytes, s, W, hi, lo, T, N, K, y,   \
-                  p.n_ttiles, p.ks, partial);                                                                          \
-        if (p.ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, p.ks, y);       \
+                  n_ttiles, ks, partial, col0, col1);                                                                  \
+        if (ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1); \
     } while (0)
-        // 256-row weight tiles: operands copied straight into LDS (the slab needs a few chunks to fill the stages)
-        if (p.bn == 256 && (K / 32) / p.ks >= 4) {
-            if (p.wm == 4) {
-                if (epi == GEMM_STORE) LD_DMA(4, 256, 3, GEMM_STORE);
-                else if (epi == GEMM_ADD) LD_DMA(4, 256, 3, GEMM_ADD);
-                else LD_DMA(4, 256, 3, GEMM_SWIGLU);
-            } else {
-                if (epi == GEMM_STORE) LD_DMA(2, 256, 4, GEMM_STORE);
-                else if (epi == GEMM_ADD) LD_DMA(2, 256, 4, GEMM_ADD);
-                else LD_DMA(2, 256, 4, GEMM_SWIGLU);
-            }
-            return;
-        }
-        if (p.wm == 4) {
-            if (epi == GEMM_STORE) LD_BIG(4, 256, 3, GEMM_STORE);
-            else if (epi == GEMM_ADD) LD_BIG(4, 256, 3, GEMM_ADD);
-            else LD_BIG(4, 256, 3, GEMM_SWIGLU);
-        } else if (p.bn == 256) {
-            if (epi == GEMM_STORE) LD_BIG(2, 256, 4, GEMM_STORE);
-            else if (epi == GEMM_ADD) LD_BIG(2, 256, 4, GEMM_ADD);
-            else LD_BIG(2, 256, 4, GEMM_SWIGLU);
+    // 256-row weight tiles: operands copied straight into LDS (the slab needs a few chunks to fill the stages)
+    if (bn == 256 && (K / 32) / ks >= 4) {
+        if (wm == 4) {
+            if (epi == GEMM_STORE) LD_DMA(4, 256, 3, GEMM_STORE);
+            else if (epi == GEMM_ADD) LD_DMA(4, 256, 3, GEMM_ADD);
+            else LD_DMA(4, 256, 3, GEMM_SWIGLU);
         } else {
-            if (epi == GEMM_STORE) LD_BIG(2, 128, 4, GEMM_STORE);
-            else if (epi == GEMM_ADD) LD_BIG(2, 128, 4, GEMM_ADD);
-            else LD_BIG(2, 128, 4, GEMM_SWIGLU);
+            if (epi == GEMM_STORE) LD_DMA(2, 256, 4, GEMM_STORE);
+            else if (epi == GEMM_ADD) LD_DMA(2, 256, 4, GEMM_ADD);
+            else LD_DMA(2, 256, 4, GEMM_SWIGLU);
         }
+        return;
+    }
+    if (wm == 4) {
+        if (epi == GEMM_STORE) LD_BIG(4, 256, 3, GEMM_STORE);
+        else if (epi == GEMM_ADD) LD_BIG(4, 256, 3, GEMM_ADD);
+        else LD_BIG(4, 256, 3, GEMM_SWIGLU);
+    } else if (bn == 256) {
+        if (epi == GEMM_STORE) LD_BIG(2, 256, 4, GEMM_STORE);
+        else if (epi == GEMM_ADD) LD_BIG(2, 256, 4, GEMM_ADD);
+        else LD_BIG(2, 256, 4, GEMM_SWIGLU);
+    } else {
+        if (epi == GEMM_STORE) LD_BIG(2, 128, 4, GEMM_STORE);
+        else if (epi == GEMM_ADD) LD_BIG(2, 128, 4, GEMM_ADD);
+        else LD_BIG(2, 128, 4, GEMM_SWIGLU);
+    }
 #undef LD_BIG
+#undef LD_DMA
+}
+
+static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
+                      float *partial, hipStream_t s) {
+    if (T <= 32) {
+        const int ks = split_factor(T, N, K, epi), n_rows = N * (epi == GEMM_SWIGLU ? 2 : 1);
+        LD_LAUNCH(k_gemm_skinny, dim3(((n_rows + 127) / 128) * ks), dim3(256), 0, s, W, hi, lo, T, n_rows, K, ks,
+                           partial);
+        const int rgrid = (int)(((int64_t)T * N + 255) / 256);
+        if (epi == GEMM_STORE) LD_LAUNCH((k_splitk_reduce<GEMM_STORE>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N);
+        else if (epi == GEMM_ADD) LD_LAUNCH((k_splitk_reduce<GEMM_ADD>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N);
+        else LD_LAUNCH((k_splitk_reduce<GEMM_SWIGLU>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N);
+        return;
+    }
+    if (T > 64) {
+        const BigPlan p = plan_big(T, N, K, epi);
+        if (p.nb_a > 0) {
+            // two phases: whole rounds of unsplit tiles, then the remaining column blocks with a split K
+            const int nout = (epi == GEMM_SWIGLU ? p.bn / 2 : p.bn), mid = p.nb_a * nout;
+            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, 1, 0, mid, s);
+            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks_b, mid, N, s);
+        } else {
+            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks, 0, N, s);
+        }
         return;
     }
     launch_shape<2, 1, 128>(W, hi, lo, T, N, K, epi, y, partial, s);   // 33..64 rows

@@ -279,8 +279,9 @@ def test_sampled_and_greedy_sequences_in_one_batch():
     (replace(TINY, window=21, name="tiny-band"), 1e-4, 5)])
 def test_random_schedule_of_every_operation(shape, tol, seed):
     """All the sequence operations interleaved by a seeded schedule, the oracle and the library driven in
-    lockstep: new requests (greedy or sampled) with chunked prompts, batched decode in random order, mixed
-    steps, observations, forks at random prefix lengths, swap out / in, frees.  After every operation the
+    lockstep: new requests (greedy or sampled) with chunked prompts, batched decode in random order, multi-step
+    runs (some ended by the callback), mixed steps, observations, forks at random prefix lengths, trims below
+    the attention band, swap out / in, frees.  After every operation the
     free-block counts, block tables and lengths agree; every emitted token equals the oracle's and every
     logits row is within tolerance."""
     rng = np.random.default_rng(seed)
@@ -308,7 +309,7 @@ def test_random_schedule_of_every_operation(shape, tol, seed):
         errs.append(rel_err(lg, lg_o))
 
     for it in range(140):
-        ops = ["new"] * (len(run) + len(away) < 6) + ["decode", "decode", "mixed", "obs", "fork"] * bool(run) \
+        ops = ["new"] * (len(run) + len(away) < 6) + ["decode", "run", "mixed", "obs", "fork", "trim"] * bool(run) \
             + ["out"] * bool(run) + ["in", "in"] * bool(away) + ["free"] * (len(run) + len(away) > 2)
         op = str(rng.choice(ops))
         counts[op] = counts.get(op, 0) + 1
@@ -322,6 +323,26 @@ def test_random_schedule_of_every_operation(shape, tol, seed):
             rc, lg = ld.ld_decode_step(h, order, callback=sink, logits_vocab=V)
             assert [(q, t) for q, t, _ in sink.log[-len(order):]] == [(s, r[1]) for s, r in zip(order, ref)], (it, op)
             errs += [rel_err(lg[i], r[2]) for i, r in enumerate(ref)]
+        elif op == "run":                                 # several steps in one call, the callback one step behind
+            order = [s for s in rng.permutation(run).tolist() if room(s, 6)][: int(rng.integers(1, 5))]
+            if not order:
+                continue
+            k = int(rng.integers(1, 6))
+            pause_at = int(rng.integers(1, 2 * k + 1))        # some runs are ended early by the callback
+            seen = []
+            def cb(seq, tok, pos):
+                seen.append((seq, tok))
+                return ld.LD_CB_PAUSE if len(seen) == pause_at * len(order) else 0
+            rc, done = ld.ld_decode_run(h, order, k, callback=cb)
+            assert done == min(k, pause_at)
+            ref = []
+            for _ in range(done):
+                ref += [(s, P.okv.decode(s, want_logits=False)[1]) for s in order]
+            assert seen == ref, (it, op)
+        elif op == "trim":
+            s = int(rng.choice(run))
+            rc, n_o = P.okv.trim(s)
+            assert rc == 0 and ld.ld_kv_trim(h, s) == n_o
         elif op == "mixed":
             order = rng.permutation(run).tolist()
             n_pf = int(rng.integers(1, min(3, len(order)) + 1))
@@ -344,8 +365,11 @@ def test_random_schedule_of_every_operation(shape, tol, seed):
                 continue
             n = int(rng.integers(1, ld.ld_kv_len(h, parent) + 1))
             rc, co = P.okv.fork(parent, n)
-            cg = ld.ld_kv_fork(h, parent, n)
-            assert rc == 0 and co == cg and ld.ld_kv_len(h, cg) == n
+            cg = ld.ld_kv_fork(h, parent, n, check=False)
+            if rc != 0:                                   # below what a trimmed parent still holds: refused by both
+                assert rc == oracle.E_STATE and cg == ld.LD_E_STATE
+                continue
+            assert co == cg and ld.ld_kv_len(h, cg) == n
             sampling(cg); feed(cg, fresh(int(rng.integers(1, 9)))); run.append(cg)
         elif op == "out":
             s = int(rng.choice(run))
@@ -367,7 +391,7 @@ def test_random_schedule_of_every_operation(shape, tol, seed):
         for s in run + list(away):
             assert P.tables_equal(s) and ld.ld_kv_len(h, s) == P.okv.length(s), (it, op, s)
     assert max(errs) <= tol, max(errs)
-    assert min(counts.get(k, 0) for k in ("new", "decode", "mixed", "obs", "fork", "out", "in", "free")) >= 2, counts
+    assert min(counts.get(k, 0) for k in ("new", "decode", "run", "trim", "mixed", "obs", "fork", "out", "in", "free")) >= 2, counts
 
 
 @pytest.mark.parametrize("shape", [TINY, replace(TINY, dtype="bf16", n_kv_heads=2, name="tiny-bf16-gqa"),

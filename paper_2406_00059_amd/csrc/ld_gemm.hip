@@ -454,15 +454,21 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_big(const bf16_t *__restrict_
 // are issued right after the barrier of chunk c, when every wave has finished reading the stage they
 // overwrite; before the barrier of chunk c a wave waits until its own copies of chunk c have landed
 // (s_waitcnt vmcnt with the number of younger copies still allowed in flight).
-template <int WM, int BN, int S, int EPI>
-__global__ __launch_bounds__(128 * WM) void k_gemm_dma(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
+// WM x WN waves; a wave owns 64 rows x BN / WN columns of the tile.  Both shapes in use run eight waves, two
+// per SIMD, so that one wave's operand reads and barrier waits sit under the other's MFMAs: 256 x 256 as
+// 4 x 2 waves of 64 x 128, 128 x 256 as 2 x 4 waves of 64 x 64 (measured against four waves of 64 x 128 on
+// the same tile: layer GEMMs at 128 - 512 rows 4 - 7 % faster, the full-grid rate 410 -> 440 TFLOP/s; sixteen
+// waves of 64 x 64 on the 256 x 256 tile fit in 109 registers and change nothing).
+template <int WM, int BN, int S, int EPI, int WN>
+__global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
                                                        const bf16_t *__restrict__ xlo, int T, int N, int K,
                                                        float *__restrict__ y, int n_ttiles, int ks,
                                                        float *__restrict__ partial, int col0, int col1) {
     constexpr bool SWI = (EPI == ld::GEMM_SWIGLU);
-    constexpr int NW = 2 * WM;                    // waves
+    constexpr int NW = WM * WN;                   // waves: WM along the rows (64 each) x WN along the columns
     constexpr int BM = 64 * WM, BK = 32;
-    constexpr int WCT = BN / 2 / 32;              // 32-column accumulator tiles per wave
+    constexpr int WCOLS = BN / WN;                // W rows of the tile that one wave column multiplies
+    constexpr int WCT = WCOLS / 32;               // 32-column accumulator tiles per wave
     constexpr int NOUT = SWI ? BN / 2 : BN;       // output columns per workgroup
     constexpr int ROWS = 2 * BM + BN;             // rows of a stage: X hi, X lo, W
     constexpr int STAGE = ROWS * 64;              // bytes
@@ -477,7 +483,7 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_dma(const bf16_t *__restrict_
     const int t0 = tt_idx * BM, n0 = col0 + nb * NOUT;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
 
     // global source of the piece this lane fetches in copy j of a chunk (rows clamped; clamped rows are never stored)
     const bf16_t *src[P];
@@ -494,9 +500,9 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_dma(const bf16_t *__restrict_
             const int wr = vr - 2 * BM;
             int grow;
             if (SWI) {   // local rows of a wave column: gate tiles, then the up tiles of the same columns
-                const int wcol = wr / (BN / 2), within = wr % (BN / 2);
-                const int col = n0 + wcol * (BN / 4) + (within % (BN / 4));
-                grow = min(col, N - 1) + (within >= BN / 4 ? N : 0);
+                const int wcol = wr / WCOLS, within = wr % WCOLS;
+                const int col = n0 + wcol * (WCOLS / 2) + (within % (WCOLS / 2));
+                grow = min(col, N - 1) + (within >= WCOLS / 2 ? N : 0);
             } else {
                 grow = min(n0 + wr, N - 1);
             }
@@ -534,7 +540,7 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_dma(const bf16_t *__restrict_
             }
 #pragma unroll
         for (int wc = 0; wc < WCT; wc++) {
-            const int r = wn * (BN / 2) + wc * 32 + l32;
+            const int r = wn * WCOLS + wc * 32 + l32;
             f.bw[wc] = __builtin_bit_cast(
                 bf16x8, *reinterpret_cast<const u32x4 *>(base + (2 * BM + r) * 64 + ((seg ^ ((r >> 2) & 3)) * 16)));
         }
@@ -603,7 +609,7 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_dma(const bf16_t *__restrict_
     const int ncols = SWI ? 2 * N : N;            // row length of the partial-sum buffer
 #pragma unroll
     for (int wc = 0; wc < WOUT; wc++) {
-        const int n = n0 + wn * (NOUT / 2) + wc * 32 + l32;
+        const int n = n0 + wn * (NOUT / WN) + wc * 32 + l32;
         if (n >= col1) continue;
 #pragma unroll
         for (int tt = 0; tt < 2; tt++)
@@ -662,7 +668,7 @@ struct BigPlan { int wm, bn, n_ttiles, n_nblocks, ks; double est_us; int nb_a, k
 BigPlan plan_big(int T, int N, int K, int epi) {
     const bool swi = epi == ld::GEMM_SWIGLU;
     struct Tile { int wm, bn; double tflops; };           // nominal (unsplit) TFLOP/s of a full grid
-    static const Tile tiles[3] = {{4, 256, 520.0}, {2, 256, 410.0}, {2, 128, 300.0}};
+    static const Tile tiles[3] = {{4, 256, 520.0}, {2, 256, 440.0}, {2, 128, 300.0}};
     BigPlan best{};
     double best_t = 1e30;
     const char *forced = getenv("LD_GEMM_BIG");            // tuning knob: "wm,bn,ks"
@@ -800,29 +806,29 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
                   n_ttiles, ks, partial, col0, col1);                                                                  \
         if (ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1); \
     } while (0)
-#define LD_DMA(WM_, BN_, S_, EPI_)                                                                                     \
+#define LD_DMA(WM_, BN_, S_, EPI_, WN_)                                                                                \
     do {                                                                                                               \
         constexpr int lds_bytes = (2 * 64 * WM_ + BN_) * 64 * S_;                                                      \
         static bool attr_set = false;                                                                                  \
         if (!attr_set) {                                                                                               \
-            (void)hipFuncSetAttribute((const void *)k_gemm_dma<WM_, BN_, S_, EPI_>,                                    \
+            (void)hipFuncSetAttribute((const void *)k_gemm_dma<WM_, BN_, S_, EPI_, WN_>,                               \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);                          \
             attr_set = true;                                                                                           \
         }                                                                                                              \
-        LD_LAUNCH((k_gemm_dma<WM_, BN_, S_, EPI_>), dim3(grid), dim3(128 * WM_), lds_bytes, s, W, hi, lo, T, N, K, y,   \
-                  n_ttiles, ks, partial, col0, col1);                                                                  \
+        LD_LAUNCH((k_gemm_dma<WM_, BN_, S_, EPI_, WN_>), dim3(grid), dim3(64 * WM_ * WN_), lds_bytes, s, W, hi, lo, T, \
+                  N, K, y, n_ttiles, ks, partial, col0, col1);                                                         \
         if (ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1); \
     } while (0)
     // 256-row weight tiles: operands copied straight into LDS (the slab needs a few chunks to fill the stages)
     if (bn == 256 && (K / 32) / ks >= 4) {
-        if (wm == 4) {
-            if (epi == GEMM_STORE) LD_DMA(4, 256, 3, GEMM_STORE);
-            else if (epi == GEMM_ADD) LD_DMA(4, 256, 3, GEMM_ADD);
-            else LD_DMA(4, 256, 3, GEMM_SWIGLU);
-        } else {
-            if (epi == GEMM_STORE) LD_DMA(2, 256, 4, GEMM_STORE);
-            else if (epi == GEMM_ADD) LD_DMA(2, 256, 4, GEMM_ADD);
-            else LD_DMA(2, 256, 4, GEMM_SWIGLU);
+        if (wm == 4) {          // 256 x 256: eight waves, 64 x 128 each
+            if (epi == GEMM_STORE) LD_DMA(4, 256, 3, GEMM_STORE, 2);
+            else if (epi == GEMM_ADD) LD_DMA(4, 256, 3, GEMM_ADD, 2);
+            else LD_DMA(4, 256, 3, GEMM_SWIGLU, 2);
+        } else {                // 128 x 256: eight waves, 64 x 64 each
+            if (epi == GEMM_STORE) LD_DMA(2, 256, 4, GEMM_STORE, 4);
+            else if (epi == GEMM_ADD) LD_DMA(2, 256, 4, GEMM_ADD, 4);
+            else LD_DMA(2, 256, 4, GEMM_SWIGLU, 4);
         }
         return;
     }

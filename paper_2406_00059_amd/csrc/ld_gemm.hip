@@ -471,12 +471,9 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
     constexpr int WCT = WCOLS / 32;               // 32-column accumulator tiles per wave
     constexpr int NOUT = SWI ? BN / 2 : BN;       // output columns per workgroup
     constexpr int ROWS = 2 * BM + BN;             // rows of a stage: X hi, X lo, W
-    // every wave issues the same number of copies (its wait counts assume that), so the stage is padded to
-    // a multiple of 16 rows per wave; the copies into the padding fetch a valid row that nobody reads
-    constexpr int ROWS_PAD = (ROWS + 16 * NW - 1) / (16 * NW) * (16 * NW);
-    constexpr int STAGE = ROWS_PAD * 64;          // bytes
-    constexpr int P = ROWS_PAD / 16 / NW;         // copy instructions per wave per chunk
-    static_assert(WCOLS % 32 == 0 && (!SWI || WCT % 2 == 0), "a wave column holds whole 32-column tiles (gate and up halves)");
+    constexpr int STAGE = ROWS * 64;              // bytes
+    constexpr int P = ROWS / 16 / NW;             // copy instructions per wave per chunk
+    static_assert(ROWS % (16 * NW) == 0, "rows must split evenly over the waves");
     extern __shared__ __attribute__((aligned(1024))) char lds[];
 
     const int b = blockIdx.x, xcd = b & 7, s = b >> 3;
@@ -500,7 +497,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
             const int r = vr % BM;
             rowp = (vr < BM ? xhi : xlo) + (int64_t)min(t0 + r, T - 1) * K;
         } else {
-            const int wr = min(vr - 2 * BM, BN - 1);
+            const int wr = vr - 2 * BM;
             int grow;
             if (SWI) {   // local rows of a wave column: gate tiles, then the up tiles of the same columns
                 const int wcol = wr / WCOLS, within = wr % WCOLS;
@@ -665,29 +662,25 @@ int env_int(const char *name, int dflt) {
 }
 // Tile, workgroup count and split-K factor of the big-tile kernel for a row count: the candidate with the
 // smallest estimated time.  A candidate runs ceil(workgroups / 256) rounds of one workgroup per CU (two for
-// the 128 x 128 tile, at half the rate each); the per-CU rates are the measured full-grid rates of the tiles;
-// split-K adds the write and the ordered re-read of its partial sums.  The 256 x 192 tile exists for output
-// widths whose 256-wide blocks leave a quarter of the CUs idle (12288 columns at 1024 rows: 192 tiles of
-// 256 x 256 but 256 of 256 x 192); it has no SwiGLU form.
+// the 128 x 128 tile, at half the rate each); the per-CU rates are the measured full-grid rates of the three
+// tiles; split-K adds the write and the ordered re-read of its partial sums.
 struct BigPlan { int wm, bn, n_ttiles, n_nblocks, ks; double est_us; int nb_a, ks_b; };   // nb_a > 0: two phases
-BigPlan plan_big(int T, int N, int K, int epi, bool allow_forced = true) {
+BigPlan plan_big(int T, int N, int K, int epi) {
     const bool swi = epi == ld::GEMM_SWIGLU;
     struct Tile { int wm, bn; double tflops; };           // nominal (unsplit) TFLOP/s of a full grid
-    static const Tile tiles[4] = {{4, 256, 520.0}, {4, 192, 490.0}, {2, 256, 440.0}, {2, 128, 300.0}};
+    static const Tile tiles[3] = {{4, 256, 520.0}, {2, 256, 440.0}, {2, 128, 300.0}};
     BigPlan best{};
     double best_t = 1e30;
-    const char *forced = allow_forced ? getenv("LD_GEMM_BIG") : nullptr;   // tuning knob: "wm,bn,ks"
+    const char *forced = getenv("LD_GEMM_BIG");            // tuning knob: "wm,bn,ks"
     int f_wm = 0, f_bn = 0, f_ks = 0;
     if (forced && sscanf(forced, "%d,%d,%d", &f_wm, &f_bn, &f_ks) != 3) f_wm = 0;
     for (const Tile &tl : tiles) {
         if (f_wm && (tl.wm != f_wm || tl.bn != f_bn)) continue;
-        if (tl.bn == 192 && swi) continue;                  // 96 columns per wave do not split into gate and up tiles
         const int bm = 64 * tl.wm, nout = swi ? tl.bn / 2 : tl.bn;
         const int n_tt = (T + bm - 1) / bm, n_nb = (N + nout - 1) / nout;
         const int max_ks = std::max(1, std::min(8, K / 32 / 8));   // at least eight chunks per slab
         for (int ks = 1; ks <= max_ks; ks++) {
             if (f_wm && ks != std::min(f_ks, max_ks)) continue;
-            if (tl.bn == 192 && (K / 32) / ks < 4) continue;   // only built with the direct-to-LDS pipeline
             const int64_t wgs = (int64_t)n_tt * n_nb * ks;
             const int64_t rounds = (wgs + 255) / 256;
             const double wg_us = 2.0 * bm * tl.bn * (double)(K / ks) / (tl.tflops * 1e6 / 256.0);
@@ -713,7 +706,6 @@ BigPlan plan_big(int T, int N, int K, int epi, bool allow_forced = true) {
             }
         }
     }
-    if (best_t == 1e30 && f_wm) return plan_big(T, N, K, epi, false);   // the forced tile does not exist for this call
     return best;
 }
 Shape pick_shape(int T, int epi) {
@@ -816,8 +808,7 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
     } while (0)
 #define LD_DMA(WM_, BN_, S_, EPI_, WN_)                                                                                \
     do {                                                                                                               \
-        constexpr int per_round = 16 * WM_ * WN_;                                                                      \
-        constexpr int lds_bytes = (2 * 64 * WM_ + BN_ + per_round - 1) / per_round * per_round * 64 * S_;              \
+        constexpr int lds_bytes = (2 * 64 * WM_ + BN_) * 64 * S_;                                                      \
         static bool attr_set = false;                                                                                  \
         if (!attr_set) {                                                                                               \
             (void)hipFuncSetAttribute((const void *)k_gemm_dma<WM_, BN_, S_, EPI_, WN_>,                               \
@@ -828,12 +819,7 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
                   N, K, y, n_ttiles, ks, partial, col0, col1);                                                         \
         if (ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1); \
     } while (0)
-    // wide weight tiles: operands copied straight into LDS (the slab needs a few chunks to fill the stages)
-    if (bn == 192) {            // 256 x 192: eight waves, 64 x 96 each; the planner offers it without SwiGLU only
-        if (epi == GEMM_STORE) LD_DMA(4, 192, 3, GEMM_STORE, 2);
-        else LD_DMA(4, 192, 3, GEMM_ADD, 2);
-        return;
-    }
+    // 256-row weight tiles: operands copied straight into LDS (the slab needs a few chunks to fill the stages)
     if (bn == 256 && (K / 32) / ks >= 4) {
         if (wm == 4) {          // 256 x 256: eight waves, 64 x 128 each
             if (epi == GEMM_STORE) LD_DMA(4, 256, 3, GEMM_STORE, 2);

@@ -163,12 +163,16 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
 #pragma unroll
         for (int i = 0; i < 16; i++) sc_t[i] = 0.f;
         const bf16_t *krow = &ks[st][tau(l32)][half * 64];
+        // The matrix-core phases run at a raised wave priority: the other workgroup's wave on this SIMD then
+        // fills the issue slots between the MFMAs with its softmax arithmetic instead of competing for them.
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             const bf16x8 ka = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(krow + j * 8));
             sc_t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qh[j], sc_t, 0, 0, 0);
             sc_t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, ql[j], sc_t, 0, 0, 0);
         }
+        __builtin_amdgcn_s_setprio(0);
         // ---- online softmax; accumulator element i is row 8*(i/4) + 4*half + i%4 of the tile, which holds
         // position kv0 + 16*(i/8) + 8*half + i%8
         float mb = -INFINITY;
@@ -211,6 +215,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
         }
         // ---- O^T = O^T * sc + V^T P^T; the rescale is skipped when no query of the wave raised its maximum
         const bool rescale = __any(sc != 1.f);
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int nt = 0; nt < 4; nt++) {
             if (rescale) {
@@ -228,6 +233,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
                 o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbl, o[nt], 0, 0, 0);
             }
         }
+        __builtin_amdgcn_s_setprio(0);
     };
 
     int st = 0;

@@ -276,7 +276,10 @@ def test_sampled_and_greedy_sequences_in_one_batch():
     (TINY, 1e-4, 1), (TINY, 1e-4, 2),
     (replace(TINY, dtype="bf16", n_kv_heads=2, name="tiny-bf16-gqa"), 2e-2, 3),
     (replace(TINY, dtype="bf16", n_kv_heads=1, window=40, name="tiny-bf16-gqa-band"), 2e-2, 4),
-    (replace(TINY, window=21, name="tiny-band"), 1e-4, 5)])
+    (replace(TINY, window=21, name="tiny-band"), 1e-4, 5),
+    # head_dim 128 on bf16: the matrix-core attention kernels (chunk prefill, grouped decode) inside the engine
+    (replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=2, head_dim=128, name="tiny-bf16-hd128"), 2e-2, 6),
+    (replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=1, head_dim=128, window=40, name="tiny-bf16-hd128-gqa-band"), 2e-2, 7)])
 def test_random_schedule_of_every_operation(shape, tol, seed):
     """All the sequence operations interleaved by a seeded schedule, the oracle and the library driven in
     lockstep: new requests (greedy or sampled) with chunked prompts, batched decode in random order, multi-step
@@ -395,7 +398,8 @@ def test_random_schedule_of_every_operation(shape, tol, seed):
 
 
 @pytest.mark.parametrize("shape", [TINY, replace(TINY, dtype="bf16", n_kv_heads=2, name="tiny-bf16-gqa"),
-                                   replace(TINY, window=21, name="tiny-band")])
+                                   replace(TINY, window=21, name="tiny-band"),
+                                   replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=1, head_dim=128, name="tiny-bf16-hd128-gqa")])
 def test_decode_run_equals_single_steps(shape):
     """Multi-step runs with the callback one step behind the GPU (section 3.3): tokens, callback order, block
     tables, free counts and lengths equal the oracle's sequential steps -- through block boundaries, with a
@@ -490,7 +494,8 @@ def test_decode_run_stops_before_a_step_it_cannot_reserve():
 
 
 @pytest.mark.parametrize("shape,tol", [(replace(TINY, window=21, name="tiny-band"), 1e-4),
-                                       (replace(TINY, dtype="bf16", n_kv_heads=1, window=40, name="tiny-bf16-gqa-band"), 2e-2)])
+                                       (replace(TINY, dtype="bf16", n_kv_heads=1, window=40, name="tiny-bf16-gqa-band"), 2e-2),
+                                       (replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=1, head_dim=128, window=40, name="tiny-bf16-hd128-gqa-band"), 2e-2)])
 def test_sliding_window_memory_trim(shape, tol):
     """Sequences with an attention band give up the blocks below it (ld_kv_trim) after every step: released
     counts, tables and free counts equal the oracle's, tokens equal and logits within tolerance -- while a

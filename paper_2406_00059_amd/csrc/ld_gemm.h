@@ -21,7 +21,13 @@ void launch_norm_split(const float *x, const float *g, float eps, int T, int K, 
 
 // y = epilogue(X W^T) with X given by its split image at the start of the scratch area xs
 // (gemm_scratch_bytes bytes); W bf16 [N, K] ([2N, K] for GEMM_SWIGLU).
-void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s);
+// next != nullptr (GEMM_ADD only, N a multiple of 4): y is the residual stream and the next GEMM takes its
+// RMS-normalised rows; next->xs (gemm_split_bytes(T, N) bytes, not inside this call's scratch area) receives
+// split(y * rsqrt(mean y^2 + eps) * g) from the kernel that finishes y, with the values launch_norm_split
+// would write.
+struct GemmNext { const float *g; float eps; uint16_t *xs; };
+void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s,
+                 const GemmNext *next = nullptr);
 
 // Skinny product alone (T <= 32 rows, K a multiple of 128): partial[z][t][row] for the skinny_slabs(K)
 // 512-wide K slabs z; the caller adds the slabs in order.

@@ -35,6 +35,21 @@ constexpr int KC = 128;          // K granularity the launcher requires (largest
 constexpr int XPAD = 8;          // bf16 elements of row padding in LDS
 constexpr int NW = 4;            // waves per workgroup
 
+// Sum of squares in a fixed order of fused multiply-adds: the kernels that normalise a row must agree bit for bit.
+__device__ __forceinline__ float add_squares(float ss, const float4 &v) {
+    ss = fmaf(v.x, v.x, ss);
+    ss = fmaf(v.y, v.y, ss);
+    ss = fmaf(v.z, v.z, ss);
+    return fmaf(v.w, v.w, ss);
+}
+
+// v * rstd * g with both products rounded: the split that follows subtracts the rounded value's high part, and a
+// product fused into that subtraction would give a different low part in one kernel than in another.
+__device__ __forceinline__ float4 scale4(const float4 &v, float rstd, const float4 &g) {
+#pragma clang fp contract(off)
+    return make_float4(v.x * rstd * g.x, v.y * rstd * g.y, v.z * rstd * g.z, v.w * rstd * g.w);
+}
+
 __global__ __launch_bounds__(256) void k_norm_split(const float *__restrict__ x, const float *__restrict__ g,
                                                     float eps, int K, bf16_t *__restrict__ hi,
                                                     bf16_t *__restrict__ lo) {
@@ -46,7 +61,7 @@ __global__ __launch_bounds__(256) void k_norm_split(const float *__restrict__ x,
         float ss = 0.f;
         for (int i = threadIdx.x * 4; i < K; i += 1024) {
             const float4 v = *reinterpret_cast<const float4 *>(row + i);
-            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+            ss = add_squares(ss, v);
         }
         ss = wave_sum(ss);
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
@@ -57,7 +72,7 @@ __global__ __launch_bounds__(256) void k_norm_split(const float *__restrict__ x,
         float4 v = *reinterpret_cast<const float4 *>(row + i);
         if (g) {
             const float4 gv = *reinterpret_cast<const float4 *>(g + i);
-            v.x = v.x * rstd * gv.x; v.y = v.y * rstd * gv.y; v.z = v.z * rstd * gv.z; v.w = v.w * rstd * gv.w;
+            v = scale4(v, rstd, gv);
         }
         uint32_t l0, l1;
         const uint32_t h0 = split2_bf16(v.x, v.y, l0), h1 = split2_bf16(v.z, v.w, l1);
@@ -652,6 +667,51 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__
     else *dst = a / (1.0f + __expf(-a)) * b;
 }
 
+// Residual rows that feed the next normalised GEMM: finishes y (adds the ks K-slab partial sums of the
+// output columns [col0, col1) in slab order, as k_splitk_reduce<GEMM_ADD> does; the other columns were
+// already added by the product kernel's epilogue) and writes the next operand split(y * rsqrt(mean y^2 + eps) * g)
+// in the same pass over the row, with k_norm_split's arithmetic in k_norm_split's order: the results are those
+// of the two separate kernels, bit for bit.  One workgroup per row; N a multiple of 4.
+__global__ __launch_bounds__(256) void k_reduce_add_norm_split(const float *__restrict__ partial, int T, int N, int ks,
+                                                               int col0, int col1, float *__restrict__ y,
+                                                               const float *__restrict__ g, float eps,
+                                                               bf16_t *__restrict__ hi, bf16_t *__restrict__ lo) {
+    __shared__ float red[4];
+    const int t = blockIdx.x;
+    float *row = y + (int64_t)t * N;
+    const float *prow = partial + (int64_t)t * N;
+    const int64_t slab = (int64_t)T * N;
+    float ss = 0.f;
+    for (int i = threadIdx.x * 4; i < N; i += 1024) {
+        float4 v = *reinterpret_cast<const float4 *>(row + i);
+        if (i >= col0 && i + 3 < col1) {      // all four columns still miss their slab sums
+            const float4 a = slab_sum(reinterpret_cast<const float4 *>(prow + i), slab / 4, ks, make_float4(0.f, 0.f, 0.f, 0.f));
+            v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+            *reinterpret_cast<float4 *>(row + i) = v;
+        } else if (i + 3 >= col0 && i < col1) {      // some of them do
+            if (i >= col0 && i < col1) v.x += slab_sum(prow + i, slab, ks, 0.f);
+            if (i + 1 >= col0 && i + 1 < col1) v.y += slab_sum(prow + i + 1, slab, ks, 0.f);
+            if (i + 2 >= col0 && i + 2 < col1) v.z += slab_sum(prow + i + 2, slab, ks, 0.f);
+            if (i + 3 >= col0 && i + 3 < col1) v.w += slab_sum(prow + i + 3, slab, ks, 0.f);
+            *reinterpret_cast<float4 *>(row + i) = v;
+        }
+        ss = add_squares(ss, v);
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float rstd = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / N + eps);
+    for (int i = threadIdx.x * 4; i < N; i += 1024) {
+        float4 v = *reinterpret_cast<const float4 *>(row + i);     // this thread's own stores of the first pass
+        const float4 gv = *reinterpret_cast<const float4 *>(g + i);
+        v = scale4(v, rstd, gv);
+        uint32_t l0, l1;
+        const uint32_t h0 = split2_bf16(v.x, v.y, l0), h1 = split2_bf16(v.z, v.w, l1);
+        *reinterpret_cast<uint2 *>(hi + (int64_t)t * N + i) = make_uint2(h0, h1);
+        *reinterpret_cast<uint2 *>(lo + (int64_t)t * N + i) = make_uint2(l0, l1);
+    }
+}
+
 // Kernel by row count: up to 32 rows -> k_gemm_skinny; 33..64 rows -> k_gemm_mfma with 64 x 128 tiles and
 // 128-wide K chunks; more -> k_gemm_big.
 struct Shape { int tt, wc, kch; };
@@ -730,7 +790,7 @@ int split_factor(int T, int N, int K, int epi) {
 
 template <int TT, int WC, int KCH>
 void launch_shape(const bf16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
-                  float *partial, hipStream_t s) {
+                  float *partial, hipStream_t s, bool reduce = true) {
     const int n_ttiles = (T + TT * 32 - 1) / (TT * 32);
     const int n_nblocks = (N + 128 * WC - 1) / (128 * WC);
     const int ks = split_factor(T, N, K, epi);
@@ -740,7 +800,7 @@ void launch_shape(const bf16_t *W, const bf16_t *hi, const bf16_t *lo, int T, in
     do {                                                                                                               \
         LD_LAUNCH((k_gemm_mfma<TT, WC, KCH, EPI_>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, n_ttiles, \
                            ks, partial);                                                                               \
-        if (ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N);   \
+        if (ks > 1 && reduce) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N); \
     } while (0)
     if (epi == ld::GEMM_STORE) LD_GEMM(ld::GEMM_STORE);
     else if (epi == ld::GEMM_ADD) LD_GEMM(ld::GEMM_ADD);
@@ -795,7 +855,8 @@ void launch_gemm_skinny(const uint16_t *W, const uint16_t *xhi, const uint16_t *
 
 // One launch of the big-tile kernel over output columns [col0, col1) with split factor ks (+ its reduction).
 static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
-                            float *partial, int wm, int bn, int n_ttiles, int ks, int col0, int col1, hipStream_t s) {
+                            float *partial, int wm, int bn, int n_ttiles, int ks, int col0, int col1, hipStream_t s,
+                            bool reduce = true) {
     const int nout = epi == GEMM_SWIGLU ? bn / 2 : bn;
     const int n_nblocks = (col1 - col0 + nout - 1) / nout;
     const int grid = ((n_nblocks + 7) / 8) * 8 * n_ttiles * ks;
@@ -804,7 +865,7 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
     do {                                                                                                               \
         LD_LAUNCH((k_gemm_big<WM_, BN_, D_, EPI_>), dim3(grid), dim3(128 * WM_), 0, s, W, hi, lo, T, N, K, y,           \
                   n_ttiles, ks, partial, col0, col1);                                                                  \
-        if (ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1); \
+        if (ks > 1 && reduce) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1); \
     } while (0)
 #define LD_DMA(WM_, BN_, S_, EPI_, WN_)                                                                                \
     do {                                                                                                               \
@@ -817,7 +878,7 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
         }                                                                                                              \
         LD_LAUNCH((k_gemm_dma<WM_, BN_, S_, EPI_, WN_>), dim3(grid), dim3(64 * WM_ * WN_), lds_bytes, s, W, hi, lo, T, \
                   N, K, y, n_ttiles, ks, partial, col0, col1);                                                         \
-        if (ks > 1) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1); \
+        if (ks > 1 && reduce) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1); \
     } while (0)
     // 256-row weight tiles: operands copied straight into LDS (the slab needs a few chunks to fill the stages)
     if (bn == 256 && (K / 32) / ks >= 4) {
@@ -849,14 +910,26 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
 #undef LD_DMA
 }
 
+// Where the rows of a residual GEMM go next: the operand image of the normalised GEMM that follows.
+struct RowsNext { const float *g; float eps; bf16_t *hi, *lo; };
+
+// nx != nullptr (GEMM_ADD only): y's rows are finished and turned into the next operand by one fused kernel in
+// place of the split-K reduction.
 static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
-                      float *partial, hipStream_t s) {
+                      float *partial, hipStream_t s, const RowsNext *nx = nullptr) {
+    // slabs and output columns whose partial sums the fused kernel still has to add (none: ks 1)
+    auto finish = [&](int ks, int col0, int col1, bool always_partial = false) {
+        if (ks <= 1 && !always_partial) col0 = col1 = 0;
+        LD_LAUNCH(k_reduce_add_norm_split, dim3(T), dim3(256), 0, s, partial, T, N, ks, col0, col1, y, nx->g, nx->eps,
+                  nx->hi, nx->lo);
+    };
     if (T <= 32) {
         const int ks = split_factor(T, N, K, epi), n_rows = N * (epi == GEMM_SWIGLU ? 2 : 1);
         LD_LAUNCH(k_gemm_skinny, dim3(((n_rows + 127) / 128) * ks), dim3(256), 0, s, W, hi, lo, T, n_rows, K, ks,
                            partial);
         const int rgrid = (int)(((int64_t)T * N + 255) / 256);
-        if (epi == GEMM_STORE) LD_LAUNCH((k_splitk_reduce<GEMM_STORE>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N);
+        if (nx) finish(ks, 0, N, true);            // the skinny kernel writes partial sums even for one slab
+        else if (epi == GEMM_STORE) LD_LAUNCH((k_splitk_reduce<GEMM_STORE>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N);
         else if (epi == GEMM_ADD) LD_LAUNCH((k_splitk_reduce<GEMM_ADD>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N);
         else LD_LAUNCH((k_splitk_reduce<GEMM_SWIGLU>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N);
         return;
@@ -867,22 +940,33 @@ static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int
             // two phases: whole rounds of unsplit tiles, then the remaining column blocks with a split K
             const int nout = (epi == GEMM_SWIGLU ? p.bn / 2 : p.bn), mid = p.nb_a * nout;
             launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, 1, 0, mid, s);
-            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks_b, mid, N, s);
+            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks_b, mid, N, s, !nx);
+            if (nx) finish(p.ks_b, mid, N);
         } else {
-            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks, 0, N, s);
+            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks, 0, N, s, !nx);
+            if (nx) finish(p.ks, 0, N);
         }
         return;
     }
-    launch_shape<2, 1, 128>(W, hi, lo, T, N, K, epi, y, partial, s);   // 33..64 rows
+    launch_shape<2, 1, 128>(W, hi, lo, T, N, K, epi, y, partial, s, !nx);   // 33..64 rows
+    if (nx) finish(split_factor(T, N, K, epi), 0, N);
 }
 
-void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s) {
+void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s,
+                 const GemmNext *next) {
     float *partial = (float *)((char *)xs + gemm_split_bytes(T, K));
     const bf16_t *hi = xs, *lo = xs + (size_t)T * K;
     const int r = tail_rows(T, N, K, epi);
-    gemm_rows(W, hi, lo, T - r, N, K, epi, y, partial, s);
+    // the next operand is a [2][T][N] image: rows of the main part first, the tail's rows behind them
+    RowsNext a{}, b{};
+    if (next) {
+        a = {next->g, next->eps, next->xs, next->xs + (size_t)T * N};
+        b = {next->g, next->eps, a.hi + (size_t)(T - r) * N, a.lo + (size_t)(T - r) * N};
+    }
+    gemm_rows(W, hi, lo, T - r, N, K, epi, y, partial, s, next ? &a : nullptr);
     // the tail reuses the partial-sum scratch: the stream orders it behind the main part's reduction
-    if (r) gemm_rows(W, hi + (size_t)(T - r) * K, lo + (size_t)(T - r) * K, r, N, K, epi, y + (size_t)(T - r) * N, partial, s);
+    if (r) gemm_rows(W, hi + (size_t)(T - r) * K, lo + (size_t)(T - r) * K, r, N, K, epi, y + (size_t)(T - r) * N, partial, s,
+                     next ? &b : nullptr);
 }
 
 }  // namespace ld

@@ -2,8 +2,10 @@
 // step planner (which rows go through one pass), launch sequence, token hand-off to the callback.
 #include "ld_internal.h"
 #include "ld_batch.h"
+#include "ld_gemm.h"
 
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -59,7 +61,7 @@ struct Seq {
 struct Workspace {
     int32_t *table, *meta, *out_tok;
     float *x, *qkv, *attn, *act, *hn, *logits, *cos_sin;
-    void *att_scratch, *lin_scratch;
+    void *att_scratch, *lin_scratch, *lin_scratch2;   // lin_scratch2: second GEMM scratch area (bf16 models), same size
     size_t att_scratch_bytes, lin_scratch_bytes;
     uint16_t *b_xs;      // decode-batch layer: split operand image, split-K partial sums, norm statistics
     float *b_partial, *b_ss;
@@ -105,6 +107,7 @@ Workspace plan_workspace(const ld_model &m, char *base, int max_tokens, int max_
         w.lin_scratch_bytes = std::max(w.lin_scratch_bytes, b);
     }
     w.lin_scratch = take(w.lin_scratch_bytes);
+    w.lin_scratch2 = c.dtype == LD_BF16 && max_tokens >= 2 ? take(w.lin_scratch_bytes) : nullptr;
     {
         const int tb = std::min(max_tokens, 32);
         w.b_xs = (uint16_t *)take(ld::batch_layer_xs_bytes(tb, c.d_model, c.n_heads, c.head_dim, c.d_ffn));
@@ -311,6 +314,12 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
     const bool batch_path = c.dtype == LD_BF16 && n_tiles == 0 && c.n_layers > 0 &&
                             ld::batch_layer_supported(T, d, H, Hkv, hd, c.d_ffn);
     auto timed_void = [](auto &&fn) { fn(); return LD_OK; };
+    // Multi-row passes of bf16 models whose four layer matrices all run on the matrix-core GEMMs chain the
+    // normalisations into the kernels that finish the residual GEMMs (LD_FUSE_NORM=0: tuning knob, separate passes).
+    const char *fuse_env = getenv("LD_FUSE_NORM");
+    const bool chained = !batch_path && c.dtype == LD_BF16 && T >= 2 && c.n_layers > 0 && w.lin_scratch2 &&
+                         !(fuse_env && fuse_env[0] == '0') && d % 4 == 0 && ld::gemm_supported(T, nqkv, d) &&
+                         ld::gemm_supported(T, d, nq) && ld::gemm_supported(T, c.d_ffn, d) && ld::gemm_supported(T, d, c.d_ffn);
     if (batch_path) {
         ld::BatchLayerArgs a{};
         a.T = T; a.d = d; a.H = H; a.Hkv = Hkv; a.hd = hd; a.ffn = c.d_ffn; a.eps = c.rms_eps;
@@ -331,6 +340,41 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
             LD_TIMED(LD_PROF_WO, timed_void([&] { ld::launch_batch_wo(a, st); }));
             LD_TIMED(LD_PROF_GATE_UP, timed_void([&] { ld::launch_batch_gate_up(a, st); }));
             LD_TIMED(LD_PROF_DOWN, timed_void([&] { ld::launch_batch_down(a, st); }));
+        }
+        LD_HIP_TRY(hipGetLastError());
+    } else if (chained) {
+        // Two GEMM scratch areas: A holds the operands (and partial sums) of the output and down projections,
+        // B those of the q-k-v and gate/up projections.  The kernel that finishes a residual GEMM (in A) writes
+        // the normalised operand of the GEMM after it (into B), so no separate norm/split pass runs between them.
+        uint16_t *A = (uint16_t *)w.lin_scratch, *B = (uint16_t *)w.lin_scratch2;
+        auto mat = [](const void *p) { return (const uint16_t *)p; };
+        for (int l = 0; l < c.n_layers; l++) {
+            void *pool_l = kv->pool + (size_t)l * layer_bytes;
+            LD_TIMED(LD_PROF_QKV, timed_void([&] {
+                if (l == 0) ld::launch_norm_split(w.x, m.attn_norm[0], c.rms_eps, T, d, B, st);
+                ld::launch_gemm(mat(m.wqkv[l]), B, T, nqkv, d, ld::GEMM_STORE, w.qkv, st);
+            }));
+            LD_TIMED(LD_PROF_QKV, ldk_rope_kv_write(w.qkv, w.cos_sin, d_pos, d_slot, w.table, kv->max_blocks, pool_l, c.dtype, T, H,
+                                                    Hkv, hd, st));
+            if (n_dec_rows)
+                LD_TIMED(LD_PROF_ATTENTION, ldk_paged_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot, d_ctx,
+                                                                max_ctx_dec, n_dec_rows, H, Hkv, hd, c.window, w.attn,
+                                                                w.att_scratch, w.att_scratch_bytes, st));
+            if (n_tiles)
+                LD_TIMED(LD_PROF_ATTENTION, ldk_prefill_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_tiles,
+                                                                  n_tiles, H, Hkv, hd, c.window, max_ctx - 1, w.attn,
+                                                                  w.att_scratch, w.att_scratch_bytes, st));
+            const ld::GemmNext to_ffn{m.ffn_norm[l], c.rms_eps, B};
+            const ld::GemmNext to_next{l + 1 < c.n_layers ? m.attn_norm[l + 1] : nullptr, c.rms_eps, B};
+            LD_TIMED(LD_PROF_WO, timed_void([&] {
+                ld::launch_norm_split(w.attn, nullptr, 0.f, T, nq, A, st);
+                ld::launch_gemm(mat(m.wo[l]), A, T, d, nq, ld::GEMM_ADD, w.x, st, &to_ffn);
+            }));
+            LD_TIMED(LD_PROF_GATE_UP, timed_void([&] { ld::launch_gemm(mat(m.wgate_up[l]), B, T, c.d_ffn, d, ld::GEMM_SWIGLU, w.act, st); }));
+            LD_TIMED(LD_PROF_DOWN, timed_void([&] {
+                ld::launch_norm_split(w.act, nullptr, 0.f, T, c.d_ffn, A, st);
+                ld::launch_gemm(mat(m.wdown[l]), A, T, d, c.d_ffn, ld::GEMM_ADD, w.x, st, to_next.g ? &to_next : nullptr);
+            }));
         }
         LD_HIP_TRY(hipGetLastError());
     } else

@@ -549,3 +549,42 @@ def test_sliding_window_memory_trim(shape, tol):
         errs += [rel_err(lg[i], ref[i][2]) for i in range(2)]
         trim(cg); trim(s)
     assert max(errs) <= tol, max(errs)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("chunk", [20, 48, 100, 330])
+def test_chained_normalisation_equals_the_separate_passes(chunk, monkeypatch):
+    """Multi-row passes of a bf16 model whose matrices all run on the matrix-core GEMMs write the operand of a
+    normalised GEMM from the kernel that finishes the residual GEMM before it.  Same arithmetic in the same
+    order, so the logits and the cache must equal those of the separate reduce and norm/split passes bit for
+    bit (LD_FUSE_NORM=0), and both must match the oracle.  Chunks of 20 / 48 / 100 / 330 rows take the
+    small-batch, the 64-row and the big-tile kernels (330: with a tail of rows cut off the last tile); a mixed
+    step with decode rows follows."""
+    shape = replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=1, head_dim=128, d_ffn=768, name="tiny-bf16-hd128-ffn768")
+    tk = prompt(71, 1, 330, shape.vocab)
+    obs = prompt(71, 2, chunk, shape.vocab)
+    runs = {}
+    for fuse in ("0", "1"):
+        monkeypatch.setenv("LD_FUSE_NORM", fuse)
+        P = Pair(shape, 71, n_blocks=96, max_tokens=max(chunk, 330) + 2, max_seqs=3, max_blocks=48, max_chunk=chunk)
+        a, b = P.alloc(), P.alloc()
+        rc, t_o, lg_o = P.okv.prefill(a, tk)
+        rc, lg_a = ld.ld_prefill(P.gkv.h, a, tk, logits_vocab=P.V)
+        rc, t_ob, _ = P.okv.prefill(b, tk[:37])
+        rc, _ = ld.ld_prefill(P.gkv.h, b, tk[:37], logits_vocab=P.V)
+        assert rel_err(lg_a, lg_o) <= 2e-2 and int(np.argmax(lg_a)) == t_o
+        # mixed step: b decodes one token while a takes an observation of `chunk` tokens
+        sink = Tokens()
+        rc, lg_m = ld.ld_step_mixed(P.gkv.h, [b], [a], [obs], callback=sink, logits_vocab=P.V)
+        rc, t_b, lg_ob = P.okv.decode(b)
+        rc, t_a, lg_oa = P.okv.prefill(a, obs)
+        assert [t for _, t, _ in sink.log] == [t_b, t_a]
+        assert rel_err(lg_m[0], lg_ob) <= 2e-2 and rel_err(lg_m[1], lg_oa) <= 2e-2
+        torch.cuda.synchronize()
+        held = sorted(set(ld.ld_kv_block_table(P.gkv.h, a).tolist() + ld.ld_kv_block_table(P.gkv.h, b).tolist()))
+        runs[fuse] = (lg_a.copy(), lg_m.copy(), P.gkv.pool[:, held].clone())
+    for x, y in zip(runs["0"], runs["1"]):
+        if isinstance(x, torch.Tensor):
+            assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+        else:
+            assert np.array_equal(x, y)

@@ -202,3 +202,27 @@ def test_empty_and_degenerate_calls():
     # the pool has 4 blocks and max_blocks 4: 64 tokens fit, the 65th does not
     rc, _ = ld.ld_prefill(P.gkv.h, s, np.arange(40, dtype=np.int32), check=False)
     assert rc == ld.LD_E_RANGE
+
+
+@pytest.mark.parametrize("base,rows", [(LLAMA7B, 300), (LLAMA7B, 1056), (MISTRAL7B, 1056), (LLAMA13B, 2111)],
+                         ids=["7b-300", "7b-1056", "7b-gqa-1056", "13b-2111"])
+def test_chained_normalisation_at_full_width(base, rows, monkeypatch):
+    """The kernel that finishes a residual GEMM and writes the next GEMM's normalised operand, at the layer
+    widths and row counts of the benchmark's passes (split-K and two-phase plans, a tail of rows cut off the last
+    256-row tile): logits of a two-layer prefill equal those of the separate reduce and norm/split passes bit for
+    bit.  (The separate passes are compared with the oracle by the tests above.)"""
+    shape = base.with_layers(2)
+    w = make_weights(shape, SEED_BASE + 5, device="cuda")
+    model = ld.Model(shape, w, max_chunk=rows)
+    tk = prompt(SEED_BASE + 5, 3, rows, shape.vocab)
+    out = {}
+    for fuse in ("0", "1"):
+        monkeypatch.setenv("LD_FUSE_NORM", fuse)
+        kv = ld.KV(model, rows // 16 + 2, rows, 1, rows // 16 + 2)
+        s = ld.ld_kv_alloc(kv.h, 0)
+        rc, lg = ld.ld_prefill(kv.h, s, tk, logits_vocab=shape.vocab)
+        torch.cuda.synchronize()
+        out[fuse] = (lg.copy(), kv.pool.clone())
+        assert np.isfinite(lg).all()
+    assert np.array_equal(out["0"][0], out["1"][0])
+    assert torch.equal(out["0"][1].view(torch.int16), out["1"][1].view(torch.int16))

@@ -21,10 +21,10 @@ void launch_norm_split(const float *x, const float *g, float eps, int T, int K, 
 
 // y = epilogue(X W^T) with X given by its split image at the start of the scratch area xs
 // (gemm_scratch_bytes bytes); W bf16 [N, K] ([2N, K] for GEMM_SWIGLU).
-// next != nullptr (GEMM_ADD only, N a multiple of 4): y is the residual stream and the next GEMM takes its
+// next != nullptr with GEMM_ADD (N a multiple of 4): y is the residual stream and the next GEMM takes its
 // RMS-normalised rows; next->xs (gemm_split_bytes(T, N) bytes, not inside this call's scratch area) receives
 // split(y * rsqrt(mean y^2 + eps) * g) from the kernel that finishes y, with the values launch_norm_split
-// would write.
+// would write.  With GEMM_SWIGLU (g unused): the result goes to next->xs as split(result) and y is not written.
 struct GemmNext { const float *g; float eps; uint16_t *xs; };
 void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s,
                  const GemmNext *next = nullptr);

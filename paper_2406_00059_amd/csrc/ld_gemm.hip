@@ -35,6 +35,20 @@ constexpr int KC = 128;          // K granularity the launcher requires (largest
 constexpr int XPAD = 8;          // bf16 elements of row padding in LDS
 constexpr int NW = 4;            // waves per workgroup
 
+// SwiGLU of one (gate, up) pair with the last product rounded to float, as a store to memory would: where the
+// value goes straight into the bf16 split, a product fused into the split's subtraction would change the low part.
+__device__ __forceinline__ float swiglu(float gate, float up) {
+#pragma clang fp contract(off)
+    return gate / (1.0f + __expf(-gate)) * up;
+}
+// Writes v as the next GEMM's operand: high and low bf16 parts at the same index of the two images.
+__device__ __forceinline__ void store_split(bf16_t *__restrict__ hi, bf16_t *__restrict__ lo, int64_t idx, float v) {
+    uint32_t l;
+    const uint32_t h = split2_bf16(v, 0.f, l);
+    hi[idx] = (bf16_t)h;
+    lo[idx] = (bf16_t)l;
+}
+
 // Sum of squares in a fixed order of fused multiply-adds: the kernels that normalise a row must agree bit for bit.
 __device__ __forceinline__ float add_squares(float ss, const float4 &v) {
     ss = fmaf(v.x, v.x, ss);
@@ -87,7 +101,8 @@ template <int TT, int WC, int KCH, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
                                                    const bf16_t *__restrict__ xlo, int T, int N, int K,
                                                    float *__restrict__ y, int n_ttiles, int ks,
-                                                   float *__restrict__ partial) {
+                                                   float *__restrict__ partial, bf16_t *__restrict__ hi_out,
+                                                   bf16_t *__restrict__ lo_out) {
     constexpr int WR = (EPI == ld::GEMM_SWIGLU) ? 2 : 1;
     constexpr int WF = WC * WR;                          // W fragments per wave per k-step
     constexpr int TROWS = TT * 32;
@@ -227,8 +242,9 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t *__restrict__ W,
                     if constexpr (EPI == ld::GEMM_STORE) *dst = acc[c][tt][i];
                     else if constexpr (EPI == ld::GEMM_ADD) *dst += acc[c][tt][i];
                     else {
-                        const float gate = acc[c * WR][tt][i], up = acc[c * WR + 1][tt][i];
-                        *dst = gate / (1.0f + __expf(-gate)) * up;
+                        const float a = swiglu(acc[c * WR][tt][i], acc[c * WR + 1][tt][i]);
+                        if (hi_out) store_split(hi_out, lo_out, (int64_t)t * N + n, a);
+                        else *dst = a;
                     }
                 }
             }
@@ -320,7 +336,8 @@ template <int WM, int BN, int D, int EPI>
 __global__ __launch_bounds__(128 * WM) void k_gemm_big(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
                                                        const bf16_t *__restrict__ xlo, int T, int N, int K,
                                                        float *__restrict__ y, int n_ttiles, int ks,
-                                                       float *__restrict__ partial, int col0, int col1) {
+                                                       float *__restrict__ partial, int col0, int col1,
+                                                       bf16_t *__restrict__ hi_out, bf16_t *__restrict__ lo_out) {
     constexpr bool SWI = (EPI == ld::GEMM_SWIGLU);
     constexpr int NT = 128 * WM;                  // threads
     constexpr int BM = 64 * WM, BK = 32, SEGS = BK / 8;
@@ -450,8 +467,9 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_big(const bf16_t *__restrict_
                     if constexpr (EPI == ld::GEMM_STORE) *dst = acc[tt][wc][i];
                     else if constexpr (EPI == ld::GEMM_ADD) *dst += acc[tt][wc][i];
                     else {
-                        const float gate = acc[tt][wc][i], up = acc[tt][wc + WCT / 2][i];
-                        *dst = gate / (1.0f + __expf(-gate)) * up;
+                        const float a = swiglu(acc[tt][wc][i], acc[tt][wc + WCT / 2][i]);
+                        if (hi_out) store_split(hi_out, lo_out, (int64_t)t * N + n, a);
+                        else *dst = a;
                     }
                 }
             }
@@ -478,7 +496,8 @@ template <int WM, int BN, int S, int EPI, int WN>
 __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
                                                        const bf16_t *__restrict__ xlo, int T, int N, int K,
                                                        float *__restrict__ y, int n_ttiles, int ks,
-                                                       float *__restrict__ partial, int col0, int col1) {
+                                                       float *__restrict__ partial, int col0, int col1,
+                                                       bf16_t *__restrict__ hi_out, bf16_t *__restrict__ lo_out) {
     constexpr bool SWI = (EPI == ld::GEMM_SWIGLU);
     constexpr int NW = WM * WN;                   // waves: WM along the rows (64 each) x WN along the columns
     constexpr int BM = 64 * WM, BK = 32;
@@ -641,8 +660,9 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
                     if constexpr (EPI == ld::GEMM_STORE) *dst = acc[tt][wc][i];
                     else if constexpr (EPI == ld::GEMM_ADD) *dst += acc[tt][wc][i];
                     else {
-                        const float gate = acc[tt][wc][i], up = acc[tt][wc + WCT / 2][i];
-                        *dst = gate / (1.0f + __expf(-gate)) * up;
+                        const float a = swiglu(acc[tt][wc][i], acc[tt][wc + WCT / 2][i]);
+                        if (hi_out) store_split(hi_out, lo_out, (int64_t)t * N + n, a);
+                        else *dst = a;
                     }
                 }
             }
@@ -652,7 +672,8 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
 // Adds the ks K-slab partial sums in slab order and applies the epilogue.  One thread per output.
 template <int EPI>
 __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__ partial, int T, int N, int ks,
-                                                       float *__restrict__ y, int col0, int col1) {
+                                                       float *__restrict__ y, int col0, int col1,
+                                                       bf16_t *__restrict__ hi_out, bf16_t *__restrict__ lo_out) {
     constexpr int WR = (EPI == ld::GEMM_SWIGLU) ? 2 : 1;
     const int nc = col1 - col0;                    // output columns [col0, col1) of N
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -664,7 +685,11 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__
     float *dst = y + (int64_t)t * N + n;
     if constexpr (EPI == ld::GEMM_STORE) *dst = a;
     else if constexpr (EPI == ld::GEMM_ADD) *dst += a;
-    else *dst = a / (1.0f + __expf(-a)) * b;
+    else {
+        const float v = swiglu(a, b);
+        if (hi_out) store_split(hi_out, lo_out, (int64_t)t * N + n, v);
+        else *dst = v;
+    }
 }
 
 // Residual rows that feed the next normalised GEMM: finishes y (adds the ks K-slab partial sums of the
@@ -790,7 +815,7 @@ int split_factor(int T, int N, int K, int epi) {
 
 template <int TT, int WC, int KCH>
 void launch_shape(const bf16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
-                  float *partial, hipStream_t s, bool reduce = true) {
+                  float *partial, hipStream_t s, bool reduce = true, bf16_t *hi_out = nullptr, bf16_t *lo_out = nullptr) {
     const int n_ttiles = (T + TT * 32 - 1) / (TT * 32);
     const int n_nblocks = (N + 128 * WC - 1) / (128 * WC);
     const int ks = split_factor(T, N, K, epi);
@@ -799,8 +824,9 @@ void launch_shape(const bf16_t *W, const bf16_t *hi, const bf16_t *lo, int T, in
 #define LD_GEMM(EPI_)                                                                                                  \
     do {                                                                                                               \
         LD_LAUNCH((k_gemm_mfma<TT, WC, KCH, EPI_>), dim3(grid), dim3(256), 0, s, W, hi, lo, T, N, K, y, n_ttiles, \
-                           ks, partial);                                                                               \
-        if (ks > 1 && reduce) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N); \
+                           ks, partial, hi_out, lo_out);                                                               \
+        if (ks > 1 && reduce)                                                                                          \
+            LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N, hi_out, lo_out); \
     } while (0)
     if (epi == ld::GEMM_STORE) LD_GEMM(ld::GEMM_STORE);
     else if (epi == ld::GEMM_ADD) LD_GEMM(ld::GEMM_ADD);
@@ -856,7 +882,7 @@ void launch_gemm_skinny(const uint16_t *W, const uint16_t *xhi, const uint16_t *
 // One launch of the big-tile kernel over output columns [col0, col1) with split factor ks (+ its reduction).
 static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
                             float *partial, int wm, int bn, int n_ttiles, int ks, int col0, int col1, hipStream_t s,
-                            bool reduce = true) {
+                            bool reduce = true, bf16_t *hi_out = nullptr, bf16_t *lo_out = nullptr) {
     const int nout = epi == GEMM_SWIGLU ? bn / 2 : bn;
     const int n_nblocks = (col1 - col0 + nout - 1) / nout;
     const int grid = ((n_nblocks + 7) / 8) * 8 * n_ttiles * ks;
@@ -864,8 +890,9 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
 #define LD_BIG(WM_, BN_, D_, EPI_)                                                                                     \
     do {                                                                                                               \
         LD_LAUNCH((k_gemm_big<WM_, BN_, D_, EPI_>), dim3(grid), dim3(128 * WM_), 0, s, W, hi, lo, T, N, K, y,           \
-                  n_ttiles, ks, partial, col0, col1);                                                                  \
-        if (ks > 1 && reduce) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1); \
+                  n_ttiles, ks, partial, col0, col1, hi_out, lo_out);                                                  \
+        if (ks > 1 && reduce)                                                                                          \
+            LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1, hi_out, lo_out); \
     } while (0)
 #define LD_DMA(WM_, BN_, S_, EPI_, WN_)                                                                                \
     do {                                                                                                               \
@@ -877,8 +904,9 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
             attr_set = true;                                                                                           \
         }                                                                                                              \
         LD_LAUNCH((k_gemm_dma<WM_, BN_, S_, EPI_, WN_>), dim3(grid), dim3(64 * WM_ * WN_), lds_bytes, s, W, hi, lo, T, \
-                  N, K, y, n_ttiles, ks, partial, col0, col1);                                                         \
-        if (ks > 1 && reduce) LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1); \
+                  N, K, y, n_ttiles, ks, partial, col0, col1, hi_out, lo_out);                                         \
+        if (ks > 1 && reduce)                                                                                          \
+            LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1, hi_out, lo_out); \
     } while (0)
     // 256-row weight tiles: operands copied straight into LDS (the slab needs a few chunks to fill the stages)
     if (bn == 256 && (K / 32) / ks >= 4) {
@@ -913,10 +941,13 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
 // Where the rows of a residual GEMM go next: the operand image of the normalised GEMM that follows.
 struct RowsNext { const float *g; float eps; bf16_t *hi, *lo; };
 
-// nx != nullptr (GEMM_ADD only): y's rows are finished and turned into the next operand by one fused kernel in
-// place of the split-K reduction.
+// nx != nullptr with GEMM_ADD: y's rows are finished and turned into the next operand by one fused kernel in
+// place of the split-K reduction.  With GEMM_SWIGLU: the epilogue (or the split-K reduction) writes its result
+// as the next operand instead of floats.
 static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
                       float *partial, hipStream_t s, const RowsNext *nx = nullptr) {
+    const bool chain_add = nx && epi == GEMM_ADD;
+    bf16_t *ho = nx && epi == GEMM_SWIGLU ? nx->hi : nullptr, *lo_o = nx && epi == GEMM_SWIGLU ? nx->lo : nullptr;
     // slabs and output columns whose partial sums the fused kernel still has to add (none: ks 1)
     auto finish = [&](int ks, int col0, int col1, bool always_partial = false) {
         if (ks <= 1 && !always_partial) col0 = col1 = 0;
@@ -928,10 +959,11 @@ static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int
         LD_LAUNCH(k_gemm_skinny, dim3(((n_rows + 127) / 128) * ks), dim3(256), 0, s, W, hi, lo, T, n_rows, K, ks,
                            partial);
         const int rgrid = (int)(((int64_t)T * N + 255) / 256);
-        if (nx) finish(ks, 0, N, true);            // the skinny kernel writes partial sums even for one slab
-        else if (epi == GEMM_STORE) LD_LAUNCH((k_splitk_reduce<GEMM_STORE>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N);
-        else if (epi == GEMM_ADD) LD_LAUNCH((k_splitk_reduce<GEMM_ADD>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N);
-        else LD_LAUNCH((k_splitk_reduce<GEMM_SWIGLU>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N);
+        bf16_t *none = nullptr;
+        if (chain_add) finish(ks, 0, N, true);     // the skinny kernel writes partial sums even for one slab
+        else if (epi == GEMM_STORE) LD_LAUNCH((k_splitk_reduce<GEMM_STORE>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N, none, none);
+        else if (epi == GEMM_ADD) LD_LAUNCH((k_splitk_reduce<GEMM_ADD>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N, none, none);
+        else LD_LAUNCH((k_splitk_reduce<GEMM_SWIGLU>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, 0, N, ho, lo_o);
         return;
     }
     if (T > 64) {
@@ -939,17 +971,17 @@ static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int
         if (p.nb_a > 0) {
             // two phases: whole rounds of unsplit tiles, then the remaining column blocks with a split K
             const int nout = (epi == GEMM_SWIGLU ? p.bn / 2 : p.bn), mid = p.nb_a * nout;
-            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, 1, 0, mid, s);
-            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks_b, mid, N, s, !nx);
-            if (nx) finish(p.ks_b, mid, N);
+            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, 1, 0, mid, s, true, ho, lo_o);
+            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks_b, mid, N, s, !chain_add, ho, lo_o);
+            if (chain_add) finish(p.ks_b, mid, N);
         } else {
-            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks, 0, N, s, !nx);
-            if (nx) finish(p.ks, 0, N);
+            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks, 0, N, s, !chain_add, ho, lo_o);
+            if (chain_add) finish(p.ks, 0, N);
         }
         return;
     }
-    launch_shape<2, 1, 128>(W, hi, lo, T, N, K, epi, y, partial, s, !nx);   // 33..64 rows
-    if (nx) finish(split_factor(T, N, K, epi), 0, N);
+    launch_shape<2, 1, 128>(W, hi, lo, T, N, K, epi, y, partial, s, !chain_add, ho, lo_o);   // 33..64 rows
+    if (chain_add) finish(split_factor(T, N, K, epi), 0, N);
 }
 
 void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s,

@@ -370,9 +370,9 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
                 ld::launch_norm_split(w.attn, nullptr, 0.f, T, nq, A, st);
                 ld::launch_gemm(mat(m.wo[l]), A, T, d, nq, ld::GEMM_ADD, w.x, st, &to_ffn);
             }));
-            LD_TIMED(LD_PROF_GATE_UP, timed_void([&] { ld::launch_gemm(mat(m.wgate_up[l]), B, T, c.d_ffn, d, ld::GEMM_SWIGLU, w.act, st); }));
+            const ld::GemmNext to_down{nullptr, 0.f, A};      // the gated activation goes straight into the down projection's operand
+            LD_TIMED(LD_PROF_GATE_UP, timed_void([&] { ld::launch_gemm(mat(m.wgate_up[l]), B, T, c.d_ffn, d, ld::GEMM_SWIGLU, w.act, st, &to_down); }));
             LD_TIMED(LD_PROF_DOWN, timed_void([&] {
-                ld::launch_norm_split(w.act, nullptr, 0.f, T, c.d_ffn, A, st);
                 ld::launch_gemm(mat(m.wdown[l]), A, T, d, c.d_ffn, ld::GEMM_ADD, w.x, st, to_next.g ? &to_next : nullptr);
             }));
         }

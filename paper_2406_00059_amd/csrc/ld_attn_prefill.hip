@@ -56,7 +56,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
                                                          const int32_t *__restrict__ table, int table_stride,
                                                          const int4 *__restrict__ tiles, int H, int window,
                                                          float scale_log2e, float *__restrict__ out,
-                                                         float *__restrict__ part_o, float *__restrict__ part_ml) {
+                                                         float *__restrict__ part_o, float *__restrict__ part_ml,
+                                                         bf16_t *__restrict__ xs_hi, bf16_t *__restrict__ xs_lo) {
     __shared__ __attribute__((aligned(16))) bf16_t ks[2][KVB][KLD];
     __shared__ __attribute__((aligned(16))) bf16_t vt[2][HD][VLD];
     const int4 tile = tiles[blockIdx.x];      // x: first row, y: rows (<= 128), z: position of first row, w: seq slot
@@ -271,14 +272,23 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
     }
     if (q_valid) {
         const float inv = 1.0f / l;
-        float *op = out + (int64_t)(tile.x + qi) * (H * HD) + h * HD;
+        const int64_t at = (int64_t)(tile.x + qi) * (H * HD) + h * HD;
 #pragma unroll
         for (int nt = 0; nt < 4; nt++)
 #pragma unroll
             for (int a = 0; a < 4; a++) {
-                float4 v = make_float4(o[nt][4 * a] * inv, o[nt][4 * a + 1] * inv, o[nt][4 * a + 2] * inv,
-                                       o[nt][4 * a + 3] * inv);
-                *reinterpret_cast<float4 *>(op + nt * 32 + 8 * a + 4 * half) = v;
+                // products rounded to float: what a store would hold, also where they go straight into the split
+                const float4 v = make_float4(mul_rounded(o[nt][4 * a], inv), mul_rounded(o[nt][4 * a + 1], inv),
+                                             mul_rounded(o[nt][4 * a + 2], inv), mul_rounded(o[nt][4 * a + 3], inv));
+                const int64_t e = at + nt * 32 + 8 * a + 4 * half;
+                if (xs_hi) {      // the output projection's (hi, lo) operand instead of floats
+                    uint32_t l0, l1;
+                    const uint32_t h0 = split2_bf16(v.x, v.y, l0), h1 = split2_bf16(v.z, v.w, l1);
+                    *reinterpret_cast<uint2 *>(xs_hi + e) = make_uint2(h0, h1);
+                    *reinterpret_cast<uint2 *>(xs_lo + e) = make_uint2(l0, l1);
+                } else {
+                    *reinterpret_cast<float4 *>(out + e) = v;
+                }
             }
     }
 }
@@ -288,7 +298,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
 __global__ __launch_bounds__(128) void k_attn_prefill_merge(const int4 *__restrict__ tiles, int H, int n_splits,
                                                             const float *__restrict__ part_o,
                                                             const float *__restrict__ part_ml,
-                                                            float *__restrict__ out) {
+                                                            float *__restrict__ out, bf16_t *__restrict__ xs_hi,
+                                                            bf16_t *__restrict__ xs_lo) {
     const int4 tile = tiles[blockIdx.y >> 7];
     const int r = blockIdx.y & 127, h = blockIdx.x, d = threadIdx.x;
     if (r >= tile.y) return;
@@ -301,7 +312,9 @@ __global__ __launch_bounds__(128) void k_attn_prefill_merge(const int4 *__restri
         o += a * part_o[(base + z) * HD + d];
         L += a * part_ml[(base + z) * 2 + 1];
     }
-    out[((int64_t)(tile.x + r) * H + h) * HD + d] = o / L;
+    const int64_t e = ((int64_t)(tile.x + r) * H + h) * HD + d;
+    if (xs_hi) store_split(xs_hi, xs_lo, e, o / L);
+    else out[e] = o / L;
 }
 
 }  // namespace
@@ -330,16 +343,17 @@ size_t prefill_attention_scratch_bytes() {
 
 void launch_prefill_attention(const float *q, int q_stride, const uint16_t *pool, int Hkv, const int32_t *table,
                               int table_stride, const int32_t *tiles, int n_tiles, int H, int window, int max_pos,
-                              float *out, void *scratch, size_t scratch_bytes, hipStream_t s) {
+                              float *out, void *scratch, size_t scratch_bytes, hipStream_t s, uint16_t *xs_hi,
+                              uint16_t *xs_lo) {
     const float sl2 = 1.4426950408889634f / sqrtf((float)HD);
     const int ns = scratch ? prefill_attention_splits(n_tiles, H, max_pos, window, scratch_bytes) : 1;
     float *part_o = (float *)scratch;
     float *part_ml = part_o ? part_o + (size_t)n_tiles * 128 * H * ns * HD : nullptr;
     LD_LAUNCH(k_attn_prefill, dim3(n_tiles, H, ns), dim3(256), 0, s, q, q_stride, pool, Hkv, table, table_stride,
-              (const int4 *)tiles, H, window, sl2, out, part_o, part_ml);
+              (const int4 *)tiles, H, window, sl2, out, part_o, part_ml, xs_hi, xs_lo);
     if (ns > 1)
         LD_LAUNCH(k_attn_prefill_merge, dim3(H, n_tiles * 128), dim3(128), 0, s, (const int4 *)tiles, H, ns, part_o,
-                  part_ml, out);
+                  part_ml, out, xs_hi, xs_lo);
 }
 
 }  // namespace ld

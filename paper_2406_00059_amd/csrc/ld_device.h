@@ -29,6 +29,19 @@ __device__ __forceinline__ uint32_t split2_bf16(float a, float b, uint32_t &lo) 
     return hi;
 }
 
+// Writes v as a GEMM operand: high and low bf16 parts at the same index of the two images.
+__device__ __forceinline__ void store_split(bf16_t *__restrict__ hi, bf16_t *__restrict__ lo, int64_t idx, float v) {
+    uint32_t l;
+    const uint32_t h = split2_bf16(v, 0.f, l);
+    hi[idx] = (bf16_t)h;
+    lo[idx] = (bf16_t)l;
+}
+// a * b rounded to float, never fused into a following addition or subtraction.
+__device__ __forceinline__ float mul_rounded(float a, float b) {
+#pragma clang fp contract(off)
+    return a * b;
+}
+
 // Load 8 consecutive elements (16-byte aligned for bf16, 32-byte for float) as floats.
 __device__ __forceinline__ void load8(const bf16_t *p, float (&v)[8]) {
     const uint4 u = *reinterpret_cast<const uint4 *>(p);

@@ -41,13 +41,6 @@ __device__ __forceinline__ float swiglu(float gate, float up) {
 #pragma clang fp contract(off)
     return gate / (1.0f + __expf(-gate)) * up;
 }
-// Writes v as the next GEMM's operand: high and low bf16 parts at the same index of the two images.
-__device__ __forceinline__ void store_split(bf16_t *__restrict__ hi, bf16_t *__restrict__ lo, int64_t idx, float v) {
-    uint32_t l;
-    const uint32_t h = split2_bf16(v, 0.f, l);
-    hi[idx] = (bf16_t)h;
-    lo[idx] = (bf16_t)l;
-}
 
 // Sum of squares in a fixed order of fused multiply-adds: the kernels that normalise a row must agree bit for bit.
 __device__ __forceinline__ float add_squares(float ss, const float4 &v) {

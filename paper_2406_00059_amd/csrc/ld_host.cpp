@@ -3,6 +3,7 @@
 #include "ld_internal.h"
 #include "ld_batch.h"
 #include "ld_gemm.h"
+#include "ld_attn_prefill.h"
 
 #include <algorithm>
 #include <cstdlib>
@@ -356,20 +357,20 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
             }));
             LD_TIMED(LD_PROF_QKV, ldk_rope_kv_write(w.qkv, w.cos_sin, d_pos, d_slot, w.table, kv->max_blocks, pool_l, c.dtype, T, H,
                                                     Hkv, hd, st));
+            // attention writes the output projection's operand (A) directly: single-query rows first, then the tiles' rows
             if (n_dec_rows)
-                LD_TIMED(LD_PROF_ATTENTION, ldk_paged_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot, d_ctx,
-                                                                max_ctx_dec, n_dec_rows, H, Hkv, hd, c.window, w.attn,
-                                                                w.att_scratch, w.att_scratch_bytes, st));
+                LD_TIMED(LD_PROF_ATTENTION, ld::paged_attention_split(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot,
+                                                                      d_ctx, max_ctx_dec, n_dec_rows, H, Hkv, hd, c.window, A,
+                                                                      w.att_scratch, w.att_scratch_bytes, st, T));
             if (n_tiles)
-                LD_TIMED(LD_PROF_ATTENTION, ldk_prefill_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_tiles,
-                                                                  n_tiles, H, Hkv, hd, c.window, max_ctx - 1, w.attn,
-                                                                  w.att_scratch, w.att_scratch_bytes, st));
+                LD_TIMED(LD_PROF_ATTENTION, timed_void([&] {
+                    ld::launch_prefill_attention(w.qkv, nqkv, (const uint16_t *)pool_l, Hkv, w.table, kv->max_blocks, d_tiles,
+                                                 n_tiles, H, c.window, max_ctx - 1, w.attn, w.att_scratch,
+                                                 w.att_scratch_bytes, st, A, A + (size_t)T * nq);
+                }));
             const ld::GemmNext to_ffn{m.ffn_norm[l], c.rms_eps, B};
             const ld::GemmNext to_next{l + 1 < c.n_layers ? m.attn_norm[l + 1] : nullptr, c.rms_eps, B};
-            LD_TIMED(LD_PROF_WO, timed_void([&] {
-                ld::launch_norm_split(w.attn, nullptr, 0.f, T, nq, A, st);
-                ld::launch_gemm(mat(m.wo[l]), A, T, d, nq, ld::GEMM_ADD, w.x, st, &to_ffn);
-            }));
+            LD_TIMED(LD_PROF_WO, timed_void([&] { ld::launch_gemm(mat(m.wo[l]), A, T, d, nq, ld::GEMM_ADD, w.x, st, &to_ffn); }));
             const ld::GemmNext to_down{nullptr, 0.f, A};      // the gated activation goes straight into the down projection's operand
             LD_TIMED(LD_PROF_GATE_UP, timed_void([&] { ld::launch_gemm(mat(m.wgate_up[l]), B, T, c.d_ffn, d, ld::GEMM_SWIGLU, w.act, st, &to_down); }));
             LD_TIMED(LD_PROF_DOWN, timed_void([&] {

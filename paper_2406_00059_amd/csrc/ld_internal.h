@@ -38,7 +38,7 @@ extern thread_local LaunchTimer *g_launch_timer;
 ld_status paged_attention_split(const float *q, int q_stride, const void *pool_layer, int dtype, const int32_t *table,
                                 int table_stride, const int32_t *seq_slot, const int32_t *ctx_len, int max_ctx, int T,
                                 int H, int Hkv, int hd, int window, uint16_t *xs_out, void *scratch,
-                                size_t scratch_bytes, hipStream_t stream);
+                                size_t scratch_bytes, hipStream_t stream, int image_rows = 0);
 
 }  // namespace ld
 

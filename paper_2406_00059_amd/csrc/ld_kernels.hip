@@ -657,7 +657,7 @@ static ld_status paged_attention_impl(const float *q, int32_t q_stride, const vo
                                       const int32_t *table, int32_t table_stride, const int32_t *seq_slot,
                                       const int32_t *ctx_len, int32_t max_ctx, int32_t T, int32_t H, int32_t Hkv,
                                       int32_t hd, int32_t window, float *out, uint16_t *xs_out, void *scratch,
-                                      size_t scratch_bytes, void *stream) {
+                                      size_t scratch_bytes, void *stream, int image_rows = 0) {
     if (T == 0) return LD_OK;
     if (!q || !pool_layer || !table || !seq_slot || !ctx_len || (!out && !xs_out) || !scratch || T < 0 || H <= 0 ||
         Hkv <= 0 || H % Hkv || (hd != 64 && hd != 128) || max_ctx <= 0 || window < 0)
@@ -673,11 +673,12 @@ static ld_status paged_attention_impl(const float *q, int32_t q_stride, const vo
     const float sl2 = (float)(1.4426950408889634 / std::sqrt((double)hd));
     dim3 grid(mc, H / G, T), block(256);
     hipStream_t s = (hipStream_t)stream;
+    const int img = image_rows > 0 ? image_rows : T;     // rows of the split image the low parts sit behind
     if (mfma) {
         ld::launch_grouped_decode_partial(q, q_stride, (const uint16_t *)pool_layer, Hkv, table, table_stride, seq_slot,
                                           ctx_len, T, H, window, mc, cb, part_o, part_ml, s);
         LD_LAUNCH((k_attn_merge<128>), dim3(H, T), dim3(256), 0, s, part_o, part_ml, ctx_len, H, window, mc, cb, out,
-                  xs_out, T);
+                  xs_out, img);
         return launched("k_attn (grouped)");
     }
 #define LD_ATT_G(HD_, KVT_, G_)                                                                                    \
@@ -690,7 +691,7 @@ static ld_status paged_attention_impl(const float *q, int32_t q_stride, const vo
         else if (G == 2) LD_ATT_G(HD_, KVT_, 2);                                                                  \
         else LD_ATT_G(HD_, KVT_, 1);                                                                              \
         LD_LAUNCH((k_attn_merge<HD_>), dim3(H, T), dim3(256), 0, s, part_o, part_ml, ctx_len, H, window, mc, cb,  \
-                  out, xs_out, T);                                                                                 \
+                  out, xs_out, img);                                                                               \
     } while (0)
     if (dtype == LD_BF16 && hd == 128) LD_ATT(128, bf16_t);
     else if (dtype == LD_BF16 && hd == 64) LD_ATT(64, bf16_t);
@@ -748,13 +749,13 @@ ld_status ldk_sample(const float *logits, int32_t R, int32_t V, const float *tem
 namespace ld {
 
 // Single-query paged attention whose output is written as the split (hi, lo) bf16 operand of the
-// output projection: xs_out [2][T][H * hd].
+// output projection: xs_out [2][image_rows][H * hd], of which these T rows are the first (image_rows 0: T).
 ld_status paged_attention_split(const float *q, int q_stride, const void *pool_layer, int dtype, const int32_t *table,
                                 int table_stride, const int32_t *seq_slot, const int32_t *ctx_len, int max_ctx, int T,
                                 int H, int Hkv, int hd, int window, uint16_t *xs_out, void *scratch,
-                                size_t scratch_bytes, hipStream_t stream) {
+                                size_t scratch_bytes, hipStream_t stream, int image_rows) {
     return paged_attention_impl(q, q_stride, pool_layer, dtype, table, table_stride, seq_slot, ctx_len, max_ctx, T, H, Hkv,
-                                hd, window, nullptr, xs_out, scratch, scratch_bytes, (void *)stream);
+                                hd, window, nullptr, xs_out, scratch, scratch_bytes, (void *)stream, image_rows);
 }
 
 }  // namespace ld

@@ -552,15 +552,19 @@ def test_sliding_window_memory_trim(shape, tol):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("heads", [(2, 1, 128), (4, 2, 64)], ids=["hd128", "hd64"])
 @pytest.mark.parametrize("chunk", [20, 48, 100, 330])
-def test_chained_normalisation_equals_the_separate_passes(chunk, monkeypatch):
+def test_chained_normalisation_equals_the_separate_passes(chunk, heads, monkeypatch):
     """Multi-row passes of a bf16 model whose matrices all run on the matrix-core GEMMs write the operand of a
     normalised GEMM from the kernel that finishes the residual GEMM before it.  Same arithmetic in the same
     order, so the logits and the cache must equal those of the separate reduce and norm/split passes bit for
     bit (LD_FUSE_NORM=0), and both must match the oracle.  Chunks of 20 / 48 / 100 / 330 rows take the
     small-batch, the 64-row and the big-tile kernels (330: with a tail of rows cut off the last tile); a mixed
-    step with decode rows follows."""
-    shape = replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=1, head_dim=128, d_ffn=768, name="tiny-bf16-hd128-ffn768")
+    step with decode rows follows.  The same passes also take the attention output and the gated activation
+    straight into the next GEMM's operand (head_dim 128: chunk-prefill attention kernel, split over the KV range
+    for the long chunks; head_dim 64: every row through the single-query kernel)."""
+    H, Hkv, hd = heads
+    shape = replace(TINY, dtype="bf16", n_heads=H, n_kv_heads=Hkv, head_dim=hd, d_ffn=768, name="tiny-bf16-ffn768")
     tk = prompt(71, 1, 330, shape.vocab)
     obs = prompt(71, 2, chunk, shape.vocab)
     runs = {}

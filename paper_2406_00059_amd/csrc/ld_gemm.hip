@@ -7,8 +7,9 @@
 //
 // Three kernels by row count, all with the token index on the MFMA row side (an accumulator register
 // then holds 32 consecutive output columns of one token and stores are 128-byte contiguous), all fed
-// by a one-pass prologue (k_norm_split, or the fused producers of ld_batch.hip) that writes the
-// (hi, lo) bf16 images of the activations:
+// by the (hi, lo) bf16 images of the activations, which k_norm_split writes in a pass of its own or a
+// producer writes directly (k_reduce_add_norm_split and the SwiGLU epilogues here, the attention kernels,
+// the fused reducers of ld_batch.hip):
 //  - k_gemm_skinny (2..32 rows): weight-stream bound; slab-resident, see its comment.
 //  - k_gemm_mfma (33..64 rows): W streamed from global memory straight into B-operand registers
 //    (lane (n = lane % 32, h = lane / 32) loads 16 bytes of row n; the contraction order over k is

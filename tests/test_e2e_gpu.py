@@ -277,16 +277,19 @@ def test_sampled_and_greedy_sequences_in_one_batch():
     (replace(TINY, dtype="bf16", n_kv_heads=2, name="tiny-bf16-gqa"), 2e-2, 3),
     (replace(TINY, dtype="bf16", n_kv_heads=1, window=40, name="tiny-bf16-gqa-band"), 2e-2, 4),
     (replace(TINY, window=21, name="tiny-band"), 1e-4, 5),
-    # head_dim 128 on bf16: the matrix-core attention kernels (chunk prefill, grouped decode) inside the engine
-    (replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=2, head_dim=128, name="tiny-bf16-hd128"), 2e-2, 6),
-    (replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=1, head_dim=128, window=40, name="tiny-bf16-hd128-gqa-band"), 2e-2, 7)])
+    # head_dim 128 and an FFN width the matrix-core GEMMs take, on bf16: the matrix-core attention kernels (chunk
+    # prefill, grouped decode) and the chained multi-row passes inside the engine
+    (replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=2, head_dim=128, d_ffn=768, name="tiny-bf16-hd128"), 2e-2, 6),
+    (replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=1, head_dim=128, d_ffn=768, window=40, name="tiny-bf16-hd128-gqa-band"), 2e-2, 8)])
 def test_random_schedule_of_every_operation(shape, tol, seed):
     """All the sequence operations interleaved by a seeded schedule, the oracle and the library driven in
     lockstep: new requests (greedy or sampled) with chunked prompts, batched decode in random order, multi-step
     runs (some ended by the callback), mixed steps, observations, forks at random prefix lengths, trims below
     the attention band, swap out / in, frees.  After every operation the
     free-block counts, block tables and lengths agree; every emitted token equals the oracle's and every
-    logits row is within tolerance."""
+    logits row is within tolerance.  (Token equality needs schedules without a near-tie: seed 7 on the last shape
+    reaches a step whose two best logits differ by 1.9e-6 of the largest one in the oracle, less than float32
+    summation order decides, and is not used.)"""
     rng = np.random.default_rng(seed)
     P = Pair(shape, 16 + seed, n_blocks=64, max_tokens=64, max_seqs=6, max_blocks=10, max_chunk=16)
     h, V = P.gkv.h, shape.vocab
@@ -399,7 +402,7 @@ def test_random_schedule_of_every_operation(shape, tol, seed):
 
 @pytest.mark.parametrize("shape", [TINY, replace(TINY, dtype="bf16", n_kv_heads=2, name="tiny-bf16-gqa"),
                                    replace(TINY, window=21, name="tiny-band"),
-                                   replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=1, head_dim=128, name="tiny-bf16-hd128-gqa")])
+                                   replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=1, head_dim=128, d_ffn=768, name="tiny-bf16-hd128-gqa")])
 def test_decode_run_equals_single_steps(shape):
     """Multi-step runs with the callback one step behind the GPU (section 3.3): tokens, callback order, block
     tables, free counts and lengths equal the oracle's sequential steps -- through block boundaries, with a
@@ -495,7 +498,7 @@ def test_decode_run_stops_before_a_step_it_cannot_reserve():
 
 @pytest.mark.parametrize("shape,tol", [(replace(TINY, window=21, name="tiny-band"), 1e-4),
                                        (replace(TINY, dtype="bf16", n_kv_heads=1, window=40, name="tiny-bf16-gqa-band"), 2e-2),
-                                       (replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=1, head_dim=128, window=40, name="tiny-bf16-hd128-gqa-band"), 2e-2)])
+                                       (replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=1, head_dim=128, d_ffn=768, window=40, name="tiny-bf16-hd128-gqa-band"), 2e-2)])
 def test_sliding_window_memory_trim(shape, tol):
     """Sequences with an attention band give up the blocks below it (ld_kv_trim) after every step: released
     counts, tables and free counts equal the oracle's, tokens equal and logits within tolerance -- while a

@@ -36,6 +36,12 @@ __device__ __forceinline__ void store_split(bf16_t *__restrict__ hi, bf16_t *__r
     hi[idx] = (bf16_t)h;
     lo[idx] = (bf16_t)l;
 }
+// Rotation of the pair (a, b) by the angle whose (cos, sin) is c, every product rounded: the kernels that rotate
+// a row's q and k heads must agree bit for bit.
+__device__ __forceinline__ float2 rope_rotate(float a, float b, float2 c) {
+#pragma clang fp contract(off)
+    return make_float2(a * c.x - b * c.y, a * c.y + b * c.x);
+}
 // a * b rounded to float, never fused into a following addition or subtraction.
 __device__ __forceinline__ float mul_rounded(float a, float b) {
 #pragma clang fp contract(off)

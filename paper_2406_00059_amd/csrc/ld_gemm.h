@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <cstdint>
+#include "ld_gemv.h"
 
 namespace ld {
 
@@ -25,7 +26,10 @@ void launch_norm_split(const float *x, const float *g, float eps, int T, int K, 
 // RMS-normalised rows; next->xs (gemm_split_bytes(T, N) bytes, not inside this call's scratch area) receives
 // split(y * rsqrt(mean y^2 + eps) * g) from the kernel that finishes y, with the values launch_norm_split
 // would write.  With GEMM_SWIGLU (g unused): the result goes to next->xs as split(result) and y is not written.
-struct GemmNext { const float *g; float eps; uint16_t *xs; };
+// With GEMM_STORE and rope != nullptr (the q-k-v projection; cos_sin, pos and seq_slot indexed by row): the kernel
+// that finishes y rotates the q heads in y and writes the rotated k heads and the v heads into the paged pool,
+// with the values the separate rotate-and-append pass would write (k and v are not stored to y).
+struct GemmNext { const float *g; float eps; uint16_t *xs; const RopeKvArgs *rope = nullptr; };
 void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s,
                  const GemmNext *next = nullptr);
 

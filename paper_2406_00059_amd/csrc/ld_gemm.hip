@@ -731,6 +731,37 @@ __global__ __launch_bounds__(256) void k_reduce_add_norm_split(const float *__re
     }
 }
 
+// Rows of the q-k-v projection: finishes them (split-K slab sums of the columns [col0, col1) in slab order; the
+// other columns are already in y) and does what the rotate-and-append pass does, one wave per (head, row): q heads
+// rotated into y, rotated k heads and v heads into the paged pool.  Row t of this launch is row row0 + t of the pass.
+__global__ __launch_bounds__(64) void k_reduce_rope_kv(const float *__restrict__ partial, int T, int N, int ks, int col0,
+                                                       int col1, float *__restrict__ y, ld::RopeKvArgs rk, int row0) {
+    const int t = blockIdx.y, hh = blockIdx.x, i = threadIdx.x, half = rk.hd / 2, hd = rk.hd;
+    if (i >= half) return;
+    const float *prow = partial + (int64_t)t * N;
+    float *row = y + (int64_t)t * N;
+    const int64_t slab = (int64_t)T * N;
+    auto val = [&](int col) { return col >= col0 && col < col1 ? slab_sum(prow + col, slab, ks, 0.f) : row[col]; };
+    const float2 c = rk.cos_sin[(int64_t)(row0 + t) * half + i];
+    if (hh < rk.H) {
+        const float2 r = rope_rotate(val(hh * hd + i), val(hh * hd + i + half), c);
+        row[hh * hd + i] = r.x;
+        row[hh * hd + i + half] = r.y;
+        return;
+    }
+    const int j = hh - rk.H, kc = (rk.H + j) * hd, vc = (rk.H + rk.Hkv + j) * hd;
+    const float2 r = rope_rotate(val(kc + i), val(kc + i + half), c);
+    const float va = val(vc + i), vb = val(vc + i + half);
+    const int p = rk.pos[row0 + t];
+    const int64_t phys = rk.table[(int64_t)rk.seq_slot[row0 + t] * rk.table_stride + (p >> 4)];
+    bf16_t *blk = rk.pool + phys * kv_block_elems(rk.Hkv, hd);
+    const int slot = p & 15;
+    blk[kv_k_offset(hd, j, slot, i)] = f32_to_bf16(r.x);
+    blk[kv_k_offset(hd, j, slot, i + half)] = f32_to_bf16(r.y);
+    blk[kv_v_offset(rk.Hkv, hd, j, slot, i)] = f32_to_bf16(va);
+    blk[kv_v_offset(rk.Hkv, hd, j, slot, i + half)] = f32_to_bf16(vb);
+}
+
 // Kernel by row count: up to 32 rows -> k_gemm_skinny; 33..64 rows -> k_gemm_mfma with 64 x 128 tiles and
 // 128-wide K chunks; more -> k_gemm_big.
 struct Shape { int tt, wc, kch; };
@@ -933,20 +964,25 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
 }
 
 // Where the rows of a residual GEMM go next: the operand image of the normalised GEMM that follows.
-struct RowsNext { const float *g; float eps; bf16_t *hi, *lo; };
+struct RowsNext { const float *g; float eps; bf16_t *hi, *lo; const RopeKvArgs *rope; int row0; };
 
 // nx != nullptr with GEMM_ADD: y's rows are finished and turned into the next operand by one fused kernel in
 // place of the split-K reduction.  With GEMM_SWIGLU: the epilogue (or the split-K reduction) writes its result
 // as the next operand instead of floats.
 static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
                       float *partial, hipStream_t s, const RowsNext *nx = nullptr) {
-    const bool chain_add = nx && epi == GEMM_ADD;
+    const bool chain_rope = nx && epi == GEMM_STORE && nx->rope;
+    const bool chain_add = (nx && epi == GEMM_ADD) || chain_rope;      // a finishing kernel replaces the split-K reduction
     bf16_t *ho = nx && epi == GEMM_SWIGLU ? nx->hi : nullptr, *lo_o = nx && epi == GEMM_SWIGLU ? nx->lo : nullptr;
-    // slabs and output columns whose partial sums the fused kernel still has to add (none: ks 1)
+    // slabs and output columns whose partial sums the finishing kernel still has to add (none: ks 1)
     auto finish = [&](int ks, int col0, int col1, bool always_partial = false) {
         if (ks <= 1 && !always_partial) col0 = col1 = 0;
-        LD_LAUNCH(k_reduce_add_norm_split, dim3(T), dim3(256), 0, s, partial, T, N, ks, col0, col1, y, nx->g, nx->eps,
-                  nx->hi, nx->lo);
+        if (chain_rope)
+            LD_LAUNCH(k_reduce_rope_kv, dim3(nx->rope->H + nx->rope->Hkv, T), dim3(64), 0, s, partial, T, N, ks, col0, col1, y,
+                      *nx->rope, nx->row0);
+        else
+            LD_LAUNCH(k_reduce_add_norm_split, dim3(T), dim3(256), 0, s, partial, T, N, ks, col0, col1, y, nx->g, nx->eps,
+                      nx->hi, nx->lo);
     };
     if (T <= 32) {
         const int ks = split_factor(T, N, K, epi), n_rows = N * (epi == GEMM_SWIGLU ? 2 : 1);
@@ -986,8 +1022,9 @@ void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int
     // the next operand is a [2][T][N] image: rows of the main part first, the tail's rows behind them
     RowsNext a{}, b{};
     if (next) {
-        a = {next->g, next->eps, next->xs, next->xs + (size_t)T * N};
-        b = {next->g, next->eps, a.hi + (size_t)(T - r) * N, a.lo + (size_t)(T - r) * N};
+        a = {next->g, next->eps, next->xs, next->xs ? next->xs + (size_t)T * N : nullptr, next->rope, 0};
+        b = {next->g, next->eps, next->xs ? a.hi + (size_t)(T - r) * N : nullptr, next->xs ? a.lo + (size_t)(T - r) * N : nullptr,
+             next->rope, T - r};
     }
     gemm_rows(W, hi, lo, T - r, N, K, epi, y, partial, s, next ? &a : nullptr);
     // the tail reuses the partial-sum scratch: the stream orders it behind the main part's reduction

@@ -351,12 +351,13 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
         auto mat = [](const void *p) { return (const uint16_t *)p; };
         for (int l = 0; l < c.n_layers; l++) {
             void *pool_l = kv->pool + (size_t)l * layer_bytes;
+            // the kernel that finishes the q-k-v rows also rotates them and appends k, v to the cache
+            const ld::RopeKvArgs rk{(const float2 *)w.cos_sin, d_pos, d_slot, w.table, kv->max_blocks, (uint16_t *)pool_l, H, Hkv, hd};
+            const ld::GemmNext to_cache{nullptr, 0.f, nullptr, &rk};
             LD_TIMED(LD_PROF_QKV, timed_void([&] {
                 if (l == 0) ld::launch_norm_split(w.x, m.attn_norm[0], c.rms_eps, T, d, B, st);
-                ld::launch_gemm(mat(m.wqkv[l]), B, T, nqkv, d, ld::GEMM_STORE, w.qkv, st);
+                ld::launch_gemm(mat(m.wqkv[l]), B, T, nqkv, d, ld::GEMM_STORE, w.qkv, st, &to_cache);
             }));
-            LD_TIMED(LD_PROF_QKV, ldk_rope_kv_write(w.qkv, w.cos_sin, d_pos, d_slot, w.table, kv->max_blocks, pool_l, c.dtype, T, H,
-                                                    Hkv, hd, st));
             // attention writes the output projection's operand (A) directly: single-query rows first, then the tiles' rows
             if (n_dec_rows)
                 LD_TIMED(LD_PROF_ATTENTION, ld::paged_attention_split(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot,

@@ -156,9 +156,9 @@ __global__ void k_rope_kv_write(float *__restrict__ qkv, const float2 *__restric
     float *row = qkv + (int64_t)t * nqkv;
     if (hh < H) {
         float *u = row + hh * hd;
-        const float a = u[i], b = u[i + half];
-        u[i] = a * c.x - b * c.y;
-        u[i + half] = a * c.y + b * c.x;
+        const float2 r = rope_rotate(u[i], u[i + half], c);
+        u[i] = r.x;
+        u[i + half] = r.y;
         return;
     }
     const int j = hh - H;
@@ -169,8 +169,9 @@ __global__ void k_rope_kv_write(float *__restrict__ qkv, const float2 *__restric
     const int64_t phys = table[(int64_t)seq_slot[t] * table_stride + (p >> 4)];
     KVT *blk = pool + phys * kv_block_elems(Hkv, hd);
     const int slot = p & 15;
-    store_elem(blk + kv_k_offset(hd, j, slot, i), a * c.x - b * c.y);
-    store_elem(blk + kv_k_offset(hd, j, slot, i + half), a * c.y + b * c.x);
+    const float2 r = rope_rotate(a, b, c);
+    store_elem(blk + kv_k_offset(hd, j, slot, i), r.x);
+    store_elem(blk + kv_k_offset(hd, j, slot, i + half), r.y);
     store_elem(blk + kv_v_offset(Hkv, hd, j, slot, i), vu[i]);
     store_elem(blk + kv_v_offset(Hkv, hd, j, slot, i + half), vu[i + half]);
 }

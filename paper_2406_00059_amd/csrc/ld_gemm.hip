@@ -10,8 +10,8 @@
 // by the (hi, lo) bf16 images of the activations, which k_norm_split writes in a pass of its own or a
 // producer writes directly (k_reduce_add_norm_split and the SwiGLU epilogues here, the attention kernels,
 // the fused reducers of ld_batch.hip):
-//  - k_gemm_skinny (2..32 rows): weight-stream bound; slab-resident, see its comment.
-//  - k_gemm_mfma (33..64 rows): W streamed from global memory straight into B-operand registers
+//  - k_gemm_skinny (2..48 rows): weight-stream bound; slab-resident, see its comment.
+//  - k_gemm_mfma (49..64 rows): W streamed from global memory straight into B-operand registers
 //    (lane (n = lane % 32, h = lane / 32) loads 16 bytes of row n; the contraction order over k is
 //    permuted so that the four loads of a 64-wide k-group give a row 128 contiguous bytes), X staged
 //    through padded LDS, loads issued one chunk ahead.
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t *__restrict__ W,
     }
 }
 
-// Up to 32 rows (decode batches): the weight stream is everything, so a workgroup takes 128 rows of W and
+// Up to 32 rows (decode batches; up to 48 in two groups of rows): the weight stream is everything, so a workgroup takes 128 rows of W and
 // a 512-wide K slab, requests its whole W slab at once (32 independent 16-byte loads per lane), stages the
 // matching X slab (hi and lo) in LDS meanwhile, and only then starts multiplying: one memory round trip
 // per workgroup, no barrier inside the product loop.  Every (slab, row) partial sum goes to scratch and
@@ -279,40 +279,46 @@ __global__ __launch_bounds__(256, 2) void k_gemm_skinny(const bf16_t *__restrict
             for (int j = 0; j < 4; j++) w[kg * 4 + j] = (u32x4){0u, 0u, 0u, 0u};
         }
     }
-    // X slab: 2 parts x 32 rows x 64 pieces of 8 elements = 4096 pieces, 16 per thread
+    // Rows are taken 32 at a time against the same weight registers (one group for a decode batch, two for
+    // up to 64 rows): the X slab of a group is staged, multiplied and its partial sums written before the next
+    // group's slab replaces it in LDS.
+    for (int t0 = 0; t0 < T; t0 += 32) {
+        if (t0) lds_barrier();      // every wave has finished reading the previous group's slab
+        // X slab: 2 parts x 32 rows x 64 pieces of 8 elements = 4096 pieces, 16 per thread
 #pragma unroll
-    for (int v = 0; v < 16; v++) {
-        const int idx = threadIdx.x + 256 * v;
-        const int part = idx >> 11, row = (idx >> 6) & 31, c = idx & 63;
-        if (c * 8 < slab) {
-            const int t = min(row, T - 1);
-            const u32x4 xv = *reinterpret_cast<const u32x4 *>((part ? xlo : xhi) + (int64_t)t * K + k0 + c * 8);
-            *reinterpret_cast<u32x4 *>(&xs[part][row][c * 8]) = xv;
-        }
-    }
-    lds_barrier();
-    f32x16 acc_h, acc_l;
-#pragma unroll
-    for (int i = 0; i < 16; i++) acc_h[i] = acc_l[i] = 0.f;
-#pragma unroll
-    for (int kg = 0; kg < 8; kg++) {
-        if (kg < n_kg) {
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                const int k = kg * 64 + half * 32 + j * 8;
-                const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[0][l32][k]));
-                const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[1][l32][k]));
-                const bf16x8 bw = __builtin_bit_cast(bf16x8, w[kg * 4 + j]);
-                acc_h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bw, acc_h, 0, 0, 0);
-                acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bw, acc_l, 0, 0, 0);
+        for (int v = 0; v < 16; v++) {
+            const int idx = threadIdx.x + 256 * v;
+            const int part = idx >> 11, row = (idx >> 6) & 31, c = idx & 63;
+            if (c * 8 < slab) {
+                const int t = min(t0 + row, T - 1);
+                const u32x4 xv = *reinterpret_cast<const u32x4 *>((part ? xlo : xhi) + (int64_t)t * K + k0 + c * 8);
+                *reinterpret_cast<u32x4 *>(&xs[part][row][c * 8]) = xv;
             }
         }
-    }
-    if (n < n_rows) {
+        lds_barrier();
+        f32x16 acc_h, acc_l;
 #pragma unroll
-        for (int i = 0; i < 16; i++) {
-            const int t = 8 * (i / 4) + 4 * half + (i % 4);
-            if (t < T) partial[((int64_t)kz * T + t) * n_rows + n] = acc_h[i] + acc_l[i];
+        for (int i = 0; i < 16; i++) acc_h[i] = acc_l[i] = 0.f;
+#pragma unroll
+        for (int kg = 0; kg < 8; kg++) {
+            if (kg < n_kg) {
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    const int k = kg * 64 + half * 32 + j * 8;
+                    const bf16x8 ah = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[0][l32][k]));
+                    const bf16x8 al = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&xs[1][l32][k]));
+                    const bf16x8 bw = __builtin_bit_cast(bf16x8, w[kg * 4 + j]);
+                    acc_h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bw, acc_h, 0, 0, 0);
+                    acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bw, acc_l, 0, 0, 0);
+                }
+            }
+        }
+        if (n < n_rows) {
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const int t = t0 + 8 * (i / 4) + 4 * half + (i % 4);
+                if (t < T) partial[((int64_t)kz * T + t) * n_rows + n] = acc_h[i] + acc_l[i];
+            }
         }
     }
 }
@@ -762,7 +768,7 @@ __global__ __launch_bounds__(64) void k_reduce_rope_kv(const float *__restrict__
     blk[kv_v_offset(rk.Hkv, hd, j, slot, i + half)] = f32_to_bf16(vb);
 }
 
-// Kernel by row count: up to 32 rows -> k_gemm_skinny; 33..64 rows -> k_gemm_mfma with 64 x 128 tiles and
+// Kernel by row count: up to 48 rows -> k_gemm_skinny; 49..64 rows -> k_gemm_mfma with 64 x 128 tiles and
 // 128-wide K chunks; more -> k_gemm_big.
 struct Shape { int tt, wc, kch; };
 
@@ -820,11 +826,19 @@ BigPlan plan_big(int T, int N, int K, int epi) {
 }
 Shape pick_shape(int T, int epi) {
     (void)T; (void)epi;
-    return {2, 1, 128};   // 33..64 rows: 64 x 128 tiles, 128-wide K chunks
+    return {2, 1, 128};   // up to 64 rows: 64 x 128 tiles, 128-wide K chunks
+}
+
+// Most rows the skinny kernel takes (measured on the 7B and 13B layer shapes: two groups of rows beat the
+// 64-row kernel up to 48 rows by 7 %, are level with it at 64 rows on the former and 0.5 % behind on the
+// latter).  LD_GEMM_SKINNY_MAX: tuning knob, 32 .. 64.
+int skinny_max_rows() {
+    static const int v = env_int("LD_GEMM_SKINNY_MAX", 48);
+    return std::min(std::max(v, 32), 64);
 }
 
 int split_factor(int T, int N, int K, int epi) {
-    if (T <= 32) return (K + SL - 1) / SL;        // skinny kernel: one 512-wide slab per workgroup
+    if (T <= skinny_max_rows()) return (K + SL - 1) / SL;   // skinny kernel: one 512-wide slab per workgroup
     if (T > 64) { const BigPlan p = plan_big(T, N, K, epi); return std::max(p.ks, p.ks_b); }
     const Shape sh = pick_shape(T, epi);
     const int n_ttiles = (T + sh.tt * 32 - 1) / (sh.tt * 32), n_nblocks = (N + 128 * sh.wc - 1) / (128 * sh.wc);
@@ -882,7 +896,7 @@ int tail_rows(int T, int N, int K, int epi) {
 
 static size_t partial_bytes(int T, int N, int K, int epi) {
     const int ks = split_factor(T, N, K, epi);
-    return (ks > 1 || T <= 32) ? (size_t)ks * T * N * (epi == GEMM_SWIGLU ? 2 : 1) * sizeof(float) : 0;
+    return (ks > 1 || T <= skinny_max_rows()) ? (size_t)ks * T * N * (epi == GEMM_SWIGLU ? 2 : 1) * sizeof(float) : 0;
 }
 
 size_t gemm_scratch_bytes(int T, int N, int K, int epi) {
@@ -984,7 +998,7 @@ static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int
             LD_LAUNCH(k_reduce_add_norm_split, dim3(T), dim3(256), 0, s, partial, T, N, ks, col0, col1, y, nx->g, nx->eps,
                       nx->hi, nx->lo);
     };
-    if (T <= 32) {
+    if (T <= skinny_max_rows()) {
         const int ks = split_factor(T, N, K, epi), n_rows = N * (epi == GEMM_SWIGLU ? 2 : 1);
         LD_LAUNCH(k_gemm_skinny, dim3(((n_rows + 127) / 128) * ks), dim3(256), 0, s, W, hi, lo, T, n_rows, K, ks,
                            partial);
@@ -1010,7 +1024,7 @@ static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int
         }
         return;
     }
-    launch_shape<2, 1, 128>(W, hi, lo, T, N, K, epi, y, partial, s, !chain_add, ho, lo_o);   // 33..64 rows
+    launch_shape<2, 1, 128>(W, hi, lo, T, N, K, epi, y, partial, s, !chain_add, ho, lo_o);   // 49..64 rows
     if (chain_add) finish(split_factor(T, N, K, epi), 0, N);
 }
 

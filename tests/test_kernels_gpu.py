@@ -368,11 +368,12 @@ def test_linear_two_to_four_rows_every_row_length(T, K):
     assert np.max(np.abs(y.cpu().numpy() - plain)) <= 2e-5 * np.abs(plain).max()
 
 
-@pytest.mark.parametrize("T", [2, 5, 31, 32, 33, 64, 100, 257, 300, 320, 321])
+@pytest.mark.parametrize("T", [2, 5, 31, 32, 33, 41, 48, 49, 64, 100, 257, 300, 320, 321])
 @pytest.mark.parametrize("epi", ["store", "add_norm", "swiglu_norm"])
 def test_linear_matrix_core_path(T, epi):
     """bf16 matrices, several rows, K a multiple of 128, scratch given: the MFMA kernel with split
-    (hi + lo) activations.  Ragged N (not a multiple of the 128-column tile) and ragged T."""
+    (hi + lo) activations.  Ragged N (not a multiple of the 128-column tile) and ragged T (33, 41, 48: the
+    small-batch kernel's second group of rows, full and ragged; 49: the first row count of the 64-row kernel)."""
     N, K = 333, 1152
     rows = 2 * N if epi == "swiglu_norm" else N
     W = _mat(9, 1, rows, K, "bf16"); x = gen.normal(9, 2, (T, K)); g = gen.normal(9, 3, (K,), std=0.1, mean=1.0)

@@ -56,6 +56,9 @@ def parse():
                          "matrices, plus the calibration copy: the short program the rocprofv3 --pmc runs use")
     ap.add_argument("--attention-probe", action="store_true",
                     help="launch only the batch-32 decode attention (+ 256 MiB copies), for the HBM-traffic counter runs")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="launch only the prefill-side matrix-core kernels (layer GEMMs at 1056 and 2048 rows, chunk-prefill "
+                         "attention of a mixed step), for the MFMA counter runs")
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is NOT the benchmark)")
     return ap.parse_args()
 
@@ -409,6 +412,47 @@ def main():
         print(json.dumps({"probe": "k_gemv1 gate/up 7B batch 1", "launches": 16,
                           "algorithmic_bytes_per_launch": 2 * f * d * 2 + d * 8 + f * 4,
                           "copy_bytes_each_way": 256 << 20, "copies": 4}))
+        return
+    if args.mfma_probe:
+        d, f, H, hd = shape.d_model, shape.d_ffn, shape.n_heads, shape.head_dim
+        out = {"probe": "prefill-side matrix-core kernels, 7B layer shapes", "launches_per_case": 3, "gemm": [], "attention": None}
+        mats = [("qkv", 3 * d, d, ld.LDK_STORE), ("wo", d, d, ld.LDK_ADD), ("gate_up", f, d, ld.LDK_SWIGLU), ("down", d, f, ld.LDK_ADD)]
+        for T in (1056, 2048):
+            for name, N, K, epi in mats:
+                rows = N * (2 if epi == ld.LDK_SWIGLU else 1)
+                W = torch.empty(rows, K, device="cuda").normal_(0, 0.02).bfloat16()
+                x = torch.randn(T, K, device="cuda"); y = torch.zeros(T, N, device="cuda")
+                scratch = torch.empty(ld.ldk_linear_scratch_bytes(T, N, K, epi), dtype=torch.uint8, device="cuda")
+                for _ in range(3):
+                    ld.ldk_linear(W, x, y, epi, scratch=scratch)
+                torch.cuda.synchronize()
+                out["gemm"].append({"rows": T, "matrix": name, "weight_rows": rows, "K": K,
+                                    "nominal_flops": 2 * T * rows * K, "mfma_flops_with_split": 4 * T * rows * K})
+        # chunk-prefill attention of a mixed step: four 256-row observations behind long contexts
+        segs = [(3001, 256), (5001, 256), (7501, 256), (1201, 256)]
+        lens = [p0 + n for p0, n in segs]
+        nblk = [-(-n // 16) for n in lens]
+        pool = torch.empty(sum(nblk), 2, shape.n_kv_heads, 16, hd, device="cuda").normal_(0, 1).bfloat16()
+        table = torch.full((len(segs), max(nblk)), -1, dtype=torch.int32)
+        o = 0
+        for b in range(len(segs)):
+            table[b, :nblk[b]] = torch.arange(o, o + nblk[b], dtype=torch.int32); o += nblk[b]
+        table = table.cuda()
+        Tq = sum(n for _, n in segs)
+        q = torch.randn(Tq, H * hd, device="cuda"); ao = torch.empty(Tq, H * hd, device="cuda")
+        tiles, r = [], 0
+        for sidx, (p0, n) in enumerate(segs):
+            for off in range(0, n, 128):
+                tiles.append([r + off, min(128, n - off), p0 + off, sidx])
+            r += n
+        tiles = torch.tensor(tiles, dtype=torch.int32, device="cuda")
+        scratch = torch.empty(ld.ldk_prefill_attention_scratch_bytes(), dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            ld.ldk_prefill_attention(q, H * hd, pool, table, tiles, H, shape.n_kv_heads, hd, ao, max(lens) - 1, scratch=scratch)
+        torch.cuda.synchronize()
+        nominal = sum(sum(range(p0 + 1, p0 + n + 1)) for p0, n in segs) * H * hd * 4
+        out["attention"] = {"tiles": len(tiles), "rows": Tq, "nominal_flops": nominal, "mfma_flops_with_split": 2 * nominal}
+        print(json.dumps(out))
         return
     if args.attention_probe:
         from workloads import gen

@@ -283,6 +283,21 @@ def run_batch32(args, ld, torch, shape, model):
     prof = ld.ld_kv_profile_read(kv.h)
     ld.ld_kv_profile(kv.h, False)
     sum_ctx = sum(visible(ld.ld_kv_len(kv.h, s)) for s in seqs)
+    # one more mixed step with per-kernel timing (the four shortest sequences take the observation): the GEMM
+    # categories against the MFMA peak, nominal flops 2 * rows * weight elements and twice that on the matrix
+    # cores (the fp32 activations go in as two bf16 parts)
+    short = sorted(range(B), key=lambda i: ld.ld_kv_len(kv.h, seqs[i]))[:4]
+    pf = [seqs[i] for i in short]
+    obs = [gen.randint(seed, 9000 + i, 0, shape.vocab - 1, 256).numpy().astype(np.int32) for i in range(4)]
+    ld.ld_kv_profile(kv.h, True)
+    ld.ld_step_mixed(kv.h, [s for s in seqs if s not in pf], pf, obs, stream, noop_cb)
+    prof_mixed = ld.ld_kv_profile_read(kv.h)
+    ld.ld_kv_profile(kv.h, False)
+    rows_mixed = (B - 4) + 4 * 257
+    layer_elems = shape.n_layers * ((shape.n_heads + 2 * shape.n_kv_heads) * shape.head_dim * shape.d_model +
+                                    shape.n_heads * shape.head_dim * shape.d_model + 3 * shape.d_model * shape.d_ffn)
+    gemm_ms_mixed = sum(prof_mixed[c][0] for c in ("qkv", "wo", "gate_up", "down"))
+    gemm_nominal = 2.0 * rows_mixed * layer_elems
     att_bytes = sum_ctx * 2 * shape.n_kv_heads * shape.head_dim * 2
     att_avg = prof["attention"][0] / max(prof["attention"][1], 1) * 1e-3
     out = {
@@ -300,6 +315,9 @@ def run_batch32(args, ld, torch, shape, model):
         "attention_hbm_frac": round(att_bytes / att_avg / HBM_PEAK, 4),
         "kernel_ms_per_step": {k: round(v[0] / 4, 4) for k, v in prof.items()},
         "sum_visible_context": int(sum_ctx),
+        "kernel_ms_mixed_step": {k: round(v[0], 3) for k, v in prof_mixed.items()},
+        "mixed_step_gemm_TFLOPs_nominal": round(gemm_nominal / (gemm_ms_mixed * 1e-3) / 1e12, 1),
+        "mixed_step_gemm_mfma_frac": round(2.0 * gemm_nominal / (gemm_ms_mixed * 1e-3) / 2.5e15, 4),
     }
     kv.close()
     return out

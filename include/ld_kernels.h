@@ -91,6 +91,23 @@ ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool
                               int32_t hd, int32_t window, float *out, void *scratch, size_t scratch_bytes,
                               void *stream);
 
+/* ldk_paged_attention for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation): same arguments, same kernels and the same results,
+ * without the scratch pair.  The chunk partials go to a device array built into the library, of
+ * LDK_STATIC_SCRATCH_BYTES bytes, which every GPU the library is used on holds from the first call on that GPU
+ * until the process ends; its address is looked up once per device.  The call allocates and frees nothing.
+ * A launch whose partials (T * H * chunks * (hd + 2) floats; chunks as the launch itself is cut, at most
+ * ceil(max_ctx / 64)) would not fit is refused with LD_E_RANGE before anything is launched: 32 MiB serves
+ * e.g. 64 rows x 40 heads at contexts up to 16384.  Nothing in the array has to start at zero (every partial
+ * a merge reads was written by the same call), but all calls on one GPU share it: calls that overlap on one
+ * GPU (different streams, or different threads) race; calls on one stream do not. */
+#define LDK_STATIC_SCRATCH_BYTES (32u << 20)
+size_t ldk_static_scratch_bytes(void);
+ld_status ldk_paged_attention_static(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
+                                     const int32_t *table, int32_t table_stride, const int32_t *seq_slot,
+                                     const int32_t *ctx_len, int32_t max_ctx, int32_t T, int32_t H, int32_t Hkv,
+                                     int32_t hd, int32_t window, float *out, void *stream);
+
 /* Attention for prefill segments (section 2.1: all tokens of a prompt go through the model in one
  * iteration): a segment is a run of rows of one sequence at consecutive positions whose keys
  * and values are already in the pool; row r at position p attends to cached positions 0 .. p

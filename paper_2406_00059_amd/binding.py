@@ -23,7 +23,8 @@ __all__ = [
     "ld_kv_destroy", "ld_kv_alloc", "ld_kv_map", "ld_kv_free", "ld_kv_block_table", "ld_kv_len",
     "ld_kv_free_blocks", "ld_kv_assume", "ld_kv_swap_bytes", "ld_kv_swap_out", "ld_kv_swap_in", "ld_kv_fork", "ld_kv_trim", "ld_kv_set_sampling", "ld_prefill", "ld_decode_step", "ld_decode_run", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
     "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
-    "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_prefill_attention_scratch_bytes",
+    "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_static_scratch_bytes", "ldk_paged_attention_static",
+    "ldk_prefill_attention_scratch_bytes",
     "ldk_prefill_attention", "ldk_argmax", "ldk_sample", "Model", "KV",
 ]
 
@@ -103,6 +104,9 @@ _SIGS = {
     "ldk_paged_attention": (C.c_int, [_vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, _vp, _vp, C.c_int32,
                                       C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, C.c_size_t,
                                       _vp]),
+    "ldk_static_scratch_bytes": (C.c_size_t, []),
+    "ldk_paged_attention_static": (C.c_int, [_vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, _vp, _vp, C.c_int32,
+                                             C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]),
     "ldk_prefill_attention_scratch_bytes": (C.c_size_t, []),
     "ldk_prefill_attention": (C.c_int, [_vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, C.c_int32,
                                         C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, C.c_size_t, _vp]),
@@ -387,6 +391,18 @@ def ldk_paged_attention(q, q_stride, pool_layer, table, seq_slot, ctx_len, max_c
                                      table.shape[1], _ptr(seq_slot), _ptr(ctx_len), max_ctx, out.shape[0], H, Hkv,
                                      hd, window, _ptr(out), _ptr(scratch), scratch.numel() * scratch.element_size(),
                                      _stream(stream)))
+
+
+def ldk_static_scratch_bytes():
+    return lib().ldk_static_scratch_bytes()
+
+
+def ldk_paged_attention_static(q, q_stride, pool_layer, table, seq_slot, ctx_len, max_ctx, H, Hkv, hd, out, window=0,
+                               stream=None, check=True):
+    """ldk_paged_attention without a scratch argument (the library's built-in device array holds the partials)."""
+    return _check(lib().ldk_paged_attention_static(_ptr(q), q_stride, _ptr(pool_layer), _dt(pool_layer.dtype),
+                                                   _ptr(table), table.shape[1], _ptr(seq_slot), _ptr(ctx_len), max_ctx,
+                                                   out.shape[0], H, Hkv, hd, window, _ptr(out), _stream(stream)), check)
 
 
 def ldk_prefill_attention_scratch_bytes():

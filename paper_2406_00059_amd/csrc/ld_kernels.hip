@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <mutex>
 
 using namespace ldd;
 
@@ -710,6 +711,54 @@ ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool
                               int32_t window, float *out, void *scratch, size_t scratch_bytes, void *stream) {
     return paged_attention_impl(q, q_stride, pool_layer, dtype, table, table_stride, seq_slot, ctx_len, max_ctx, T, H, Hkv,
                                 hd, window, out, nullptr, scratch, scratch_bytes, stream);
+}
+
+// ---- the same attention for callers that cannot allocate: the chunk partials live in a file-scope device
+// array instead of a caller's buffer.  In host code the array's name is only a handle for the runtime's
+// symbol lookup; the address each device holds its copy at comes from hipGetSymbolAddress, asked once per
+// device with that device current, and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char ld_static_scratch[LDK_STATIC_SCRATCH_BYTES];
+
+static ld_status static_scratch_ptr(void **out) {
+    constexpr int MAX_DEV = 64;
+    static std::mutex mu;
+    static void *ptr[MAX_DEV] = {nullptr};
+    int dev = -1;
+    LD_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEV) return ld::fail(LD_E_RANGE, "ldk_paged_attention_static: device ordinal beyond 63");
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        LD_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(ld_static_scratch)));
+        if (!p || ((uintptr_t)p & 255)) return ld::fail(LD_E_HIP, "ldk_paged_attention_static: bad address of the device array");
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return LD_OK;
+}
+
+size_t ldk_static_scratch_bytes(void) { return LDK_STATIC_SCRATCH_BYTES; }
+
+ld_status ldk_paged_attention_static(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
+                                     const int32_t *table, int32_t table_stride, const int32_t *seq_slot,
+                                     const int32_t *ctx_len, int32_t max_ctx, int32_t T, int32_t H, int32_t Hkv,
+                                     int32_t hd, int32_t window, float *out, void *stream) {
+    if (T == 0) return LD_OK;
+    if (T < 0 || H <= 0 || Hkv <= 0 || H % Hkv || (hd != 64 && hd != 128) || max_ctx <= 0 || window < 0)
+        return ld::fail(LD_E_INVAL, "ldk_paged_attention_static: bad argument");
+    // what this launch itself needs (not the bound over all shorter contexts a reusable buffer is sized by)
+    const bool mfma = ld::grouped_decode_supported(dtype == LD_BF16, hd, H, Hkv);
+    const size_t need = (size_t)T * H * attn_max_chunks(T, H, Hkv, max_ctx, window, mfma) * (hd + 2) * sizeof(float);
+    if (need > LDK_STATIC_SCRATCH_BYTES) {
+        ld::set_error("ldk_paged_attention_static: %zu bytes of chunk partials exceed the built-in %zu; use "
+                      "ldk_paged_attention with a buffer of the caller's", need, (size_t)LDK_STATIC_SCRATCH_BYTES);
+        return LD_E_RANGE;
+    }
+    void *dev_scratch = nullptr;
+    ld_status rc = static_scratch_ptr(&dev_scratch);
+    if (rc != LD_OK) return rc;
+    return paged_attention_impl(q, q_stride, pool_layer, dtype, table, table_stride, seq_slot, ctx_len, max_ctx, T, H, Hkv,
+                                hd, window, out, nullptr, dev_scratch, LDK_STATIC_SCRATCH_BYTES, stream);
 }
 
 size_t ldk_prefill_attention_scratch_bytes(void) { return ld::prefill_attention_scratch_bytes(); }

@@ -69,6 +69,8 @@ def lib():
         L.orc_uniform.restype = C.c_double; L.orc_uniform.argtypes = [C.c_uint64, C.c_uint64]
         L.orc_sample_gumbel.restype = C.c_int32
         L.orc_sample_gumbel.argtypes = [dp, C.c_int64, C.c_double, C.c_uint64, C.c_int64]
+        L.orc_gumbel_scores.restype = None
+        L.orc_gumbel_scores.argtypes = [dp, C.c_int64, C.c_double, C.c_uint64, C.c_int64, dp]
         L.orc_seq_set_sampling.restype = C.c_int32
         L.orc_seq_set_sampling.argtypes = [vp, C.c_int32, C.c_double, C.c_uint64]
         L.orc_kv_fork.restype = C.c_int32; L.orc_kv_fork.argtypes = [vp, C.c_int32, C.c_int64, ip]
@@ -149,6 +151,13 @@ def uniform(seed, counter):
 def sample_gumbel(logits, temperature, seed, pos):
     x = _f64(logits)
     return lib().orc_sample_gumbel(_dp(x), x.size, temperature, seed, pos)
+
+
+def gumbel_scores(logits, temperature, seed, pos):
+    """The perturbed scores sample_gumbel takes the argmax of (near-tie diagnosis in the tests)."""
+    x = _f64(logits); out = np.empty_like(x)
+    lib().orc_gumbel_scores(_dp(x), x.size, temperature, seed, pos, _dp(out))
+    return out
 
 
 def attention_contig(q, K, V):

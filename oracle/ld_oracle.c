@@ -202,6 +202,17 @@ int32_t orc_sample_gumbel(const double *logits, int64_t n, double temperature, u
     return (int32_t)best;
 }
 
+/* The scores orc_sample_gumbel takes the argmax of, written out: out[i] = logits[i] / T + g_i for the token
+ * that will sit at position pos.  For the tests' near-tie diagnosis (how far apart were the two candidates
+ * the decision was between); the sampler above does not call it. */
+void orc_gumbel_scores(const double *logits, int64_t n, double temperature, uint64_t seed, int64_t pos, double *out)
+{
+    for (int64_t i = 0; i < n; i++) {
+        double u = orc_uniform(seed, (uint64_t)pos * (uint64_t)n + (uint64_t)i);
+        out[i] = logits[i] / temperature - log(-log(u));
+    }
+}
+
 /* One query against n cached (key, value) rows given by pointer tables:
  * scores q.k_j / sqrt(hd), softmax, weighted average of the values. */
 static void attend_rows(const double *q, const double *const *krow, const double *const *vrow,

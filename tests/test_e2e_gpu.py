@@ -10,7 +10,7 @@ import torch
 import oracle
 import paper_2406_00059_amd as ld
 from workloads import TINY, LLAMA7B, SEED_BASE, gen
-from helpers import Pair, Tokens, prompt, rel_err
+from helpers import NearTies, Pair, Tokens, prompt, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -272,6 +272,10 @@ def test_sampled_and_greedy_sequences_in_one_batch():
     assert [t for _, t, _ in solo.log] == toks[a]
 
 
+_HD128_BAND = replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=1, head_dim=128, d_ffn=768, window=40,
+                      name="tiny-bf16-hd128-gqa-band")
+
+
 @pytest.mark.parametrize("shape,tol,seed", [
     (TINY, 1e-4, 1), (TINY, 1e-4, 2),
     (replace(TINY, dtype="bf16", n_kv_heads=2, name="tiny-bf16-gqa"), 2e-2, 3),
@@ -280,21 +284,25 @@ def test_sampled_and_greedy_sequences_in_one_batch():
     # head_dim 128 and an FFN width the matrix-core GEMMs take, on bf16: the matrix-core attention kernels (chunk
     # prefill, grouped decode) and the chained multi-row passes inside the engine
     (replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=2, head_dim=128, d_ffn=768, name="tiny-bf16-hd128"), 2e-2, 6),
-    (replace(TINY, dtype="bf16", n_heads=2, n_kv_heads=1, head_dim=128, d_ffn=768, window=40, name="tiny-bf16-hd128-gqa-band"), 2e-2, 8)])
+    # schedules that reach a near-tie (two candidates closer in the oracle than the logits error decides)
+    (_HD128_BAND, 2e-2, 7), (_HD128_BAND, 2e-2, 8), (_HD128_BAND, 2e-2, 219), (_HD128_BAND, 2e-2, 375)])
 def test_random_schedule_of_every_operation(shape, tol, seed):
     """All the sequence operations interleaved by a seeded schedule, the oracle and the library driven in
     lockstep: new requests (greedy or sampled) with chunked prompts, batched decode in random order, multi-step
     runs (some ended by the callback), mixed steps, observations, forks at random prefix lengths, trims below
     the attention band, swap out / in, frees.  After every operation the
-    free-block counts, block tables and lengths agree; every emitted token equals the oracle's and every
-    logits row is within tolerance.  (Token equality needs schedules without a near-tie: seed 7 on the last shape
-    reaches a step whose two best logits differ by 1.9e-6 of the largest one in the oracle, less than float32
-    summation order decides, and is not used.)"""
+    free-block counts, block tables and lengths agree; every logits row is within tolerance; every emitted
+    token equals the oracle's, or the mismatch is a near-tie by the rule of helpers.NearTies (the oracle's
+    own scores of the two candidates are closer than twice the row's measured logits error), in which case it
+    is logged and the library's pending token is set to the oracle's (a sequence that flips inside a
+    multi-step run has gone on with its own token and is retired on both sides).  Seeds 7, 219 and 375 of
+    the last shape each reach such a step."""
     rng = np.random.default_rng(seed)
     P = Pair(shape, 16 + seed, n_blocks=64, max_tokens=64, max_seqs=6, max_blocks=10, max_chunk=16)
     h, V = P.gkv.h, shape.vocab
     run, away = [], {}                                   # decodable sequences; swapped ones -> (host buffer, oracle store)
     sink, errs, stream, counts = Tokens(), [], [0], {}
+    ties, samp = NearTies(), {}
 
     def fresh(n):
         stream[0] += 1
@@ -307,12 +315,29 @@ def test_random_schedule_of_every_operation(shape, tol, seed):
         t = float(rng.choice([0.0, 0.0, 0.6, 1.0]))
         sd = int(rng.integers(0, 2 ** 63))
         assert P.okv.set_sampling(s, t, sd) == 0 and ld.ld_kv_set_sampling(h, s, t, sd) == 0
+        samp[s] = (t, sd)
 
-    def feed(s, toks):
-        rc, t, lg_o = P.okv.prefill(s, toks)
+    def emitted(where, order, ref, lg):
+        """The last len(order) callbacks against the oracle's (status, token, logits) per sequence."""
+        got = sink.log[-len(order):]
+        assert [q for q, _, _ in got] == order, where
+        for i, (s, r) in enumerate(zip(order, ref)):
+            assert r[0] == 0
+            errs.append(rel_err(lg[i], r[2]))
+            e_abs = ties.measured(lg[i], r[2])
+            if got[i][1] != r[1]:
+                ties.check(where + (s,), r[2], r[1], got[i][1], e_abs, samp[s][0], samp[s][1], int(P.okv.length(s)))
+                ld.ld_kv_assume(h, s, 0, r[1])           # go on from the oracle's token
+
+    def feed(s, toks, where):
+        ref = P.okv.prefill(s, toks)
         rc_g, lg = ld.ld_prefill(h, s, toks, callback=sink, logits_vocab=V)
-        assert rc == 0 and sink.last() == [t]
-        errs.append(rel_err(lg, lg_o))
+        emitted(where, [s], [ref], lg[None])
+
+    def retire(s):
+        assert P.okv.free(s) == 0
+        ld.ld_kv_free(h, s)
+        run.remove(s) if s in run else away.pop(s)
 
     for it in range(140):
         ops = ["new"] * (len(run) + len(away) < 6) + ["decode", "run", "mixed", "obs", "fork", "trim"] * bool(run) \
@@ -320,15 +345,14 @@ def test_random_schedule_of_every_operation(shape, tol, seed):
         op = str(rng.choice(ops))
         counts[op] = counts.get(op, 0) + 1
         if op == "new":
-            s = P.alloc(); sampling(s); feed(s, fresh(int(rng.integers(1, 45)))); run.append(s)
+            s = P.alloc(); sampling(s); feed(s, fresh(int(rng.integers(1, 45))), (it, op)); run.append(s)
         elif op == "decode":
             order = [s for s in rng.permutation(run).tolist() if room(s, 0)][: int(rng.integers(1, 7))]
             if not order:
                 continue
             ref = [P.okv.decode(s) for s in order]
             rc, lg = ld.ld_decode_step(h, order, callback=sink, logits_vocab=V)
-            assert [(q, t) for q, t, _ in sink.log[-len(order):]] == [(s, r[1]) for s, r in zip(order, ref)], (it, op)
-            errs += [rel_err(lg[i], r[2]) for i, r in enumerate(ref)]
+            emitted((it, op), order, ref, lg)
         elif op == "run":                                 # several steps in one call, the callback one step behind
             order = [s for s in rng.permutation(run).tolist() if room(s, 6)][: int(rng.integers(1, 5))]
             if not order:
@@ -340,11 +364,18 @@ def test_random_schedule_of_every_operation(shape, tol, seed):
                 seen.append((seq, tok))
                 return ld.LD_CB_PAUSE if len(seen) == pause_at * len(order) else 0
             rc, done = ld.ld_decode_run(h, order, k, callback=cb)
-            assert done == min(k, pause_at)
-            ref = []
-            for _ in range(done):
-                ref += [(s, P.okv.decode(s, want_logits=False)[1]) for s in order]
-            assert seen == ref, (it, op)
+            assert done == min(k, pause_at) and [q for q, _ in seen] == order * done, (it, op)
+            flipped = set()
+            for j in range(done):
+                for i, s in enumerate(order):
+                    rc_o, t_o, lg_o = P.okv.decode(s)
+                    if s not in flipped and seen[j * len(order) + i][1] != t_o:
+                        # the call returns no logits: the rule uses the largest row error measured so far
+                        ties.check((it, op, s, j), lg_o, t_o, seen[j * len(order) + i][1], None, samp[s][0], samp[s][1],
+                                   int(P.okv.length(s)))
+                        flipped.add(s)
+            for s in flipped:
+                retire(s)
         elif op == "trim":
             s = int(rng.choice(run))
             rc, n_o = P.okv.trim(s)
@@ -359,12 +390,11 @@ def test_random_schedule_of_every_operation(shape, tol, seed):
             obs = [fresh(int(rng.integers(1, 13))) for _ in pf]
             ref = [P.okv.decode(s) for s in dec] + [P.okv.prefill(s, o) for s, o in zip(pf, obs)]
             rc, lg = ld.ld_step_mixed(h, dec, pf, obs, callback=sink, logits_vocab=V)
-            assert [(q, t) for q, t, _ in sink.log[-len(ref):]] == [(s, r[1]) for s, r in zip(dec + pf, ref)], (it, op)
-            errs += [rel_err(lg[i], r[2]) for i, r in enumerate(ref)]
+            emitted((it, op), dec + pf, ref, lg)
         elif op == "obs":
             s = int(rng.choice(run))
             if room(s, 40):
-                feed(s, fresh(int(rng.integers(1, 41))))
+                feed(s, fresh(int(rng.integers(1, 41))), (it, op))
         elif op == "fork":
             parent = int(rng.choice(run))
             if len(run) + len(away) >= 6:
@@ -376,7 +406,7 @@ def test_random_schedule_of_every_operation(shape, tol, seed):
                 assert rc == oracle.E_STATE and cg == ld.LD_E_STATE
                 continue
             assert co == cg and ld.ld_kv_len(h, cg) == n
-            sampling(cg); feed(cg, fresh(int(rng.integers(1, 9)))); run.append(cg)
+            sampling(cg); feed(cg, fresh(int(rng.integers(1, 9))), (it, op)); run.append(cg)
         elif op == "out":
             s = int(rng.choice(run))
             host = torch.empty(ld.ld_kv_swap_bytes(h, s), dtype=torch.uint8, pin_memory=bool(rng.integers(0, 2)))
@@ -389,14 +419,13 @@ def test_random_schedule_of_every_operation(shape, tol, seed):
             assert P.okv.swap_in(s, store) == 0 and ld.ld_kv_swap_in(h, s, host) == 0
             run.append(s)
         elif op == "free":
-            s = int(rng.choice(run + list(away)))
-            assert P.okv.free(s) == 0
-            ld.ld_kv_free(h, s)
-            run.remove(s) if s in run else away.pop(s)
+            retire(int(rng.choice(run + list(away))))
         assert ld.ld_kv_free_blocks(h) == P.okv.free_blocks(), (it, op)
         for s in run + list(away):
             assert P.tables_equal(s) and ld.ld_kv_len(h, s) == P.okv.length(s), (it, op, s)
     assert max(errs) <= tol, max(errs)
+    print(f"schedule {shape.name}/{seed}: max logits rel err {max(errs):.2e}, near-ties {len(ties.cases)}")
+    assert len(ties.cases) <= 2, ties.cases                  # near-ties are rare events, not a way past the check
     assert min(counts.get(k, 0) for k in ("new", "decode", "run", "trim", "mixed", "obs", "fork", "out", "in", "free")) >= 2, counts
 
 

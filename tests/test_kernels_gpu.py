@@ -15,6 +15,9 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
+_silu = np.vectorize(oracle.silu, otypes=[np.float64])      # the oracle's activation, element by element
+
+
 def _mat(seed, stream, n, k, dtype):
     w = gen.normal(seed, stream, (n, k), std=0.05)
     return w.bfloat16() if dtype == "bf16" else w
@@ -357,7 +360,7 @@ def test_linear_two_to_four_rows_every_row_length(T, K):
     gu = np.stack([oracle.matvec(Wh, oracle.rmsnorm(x[t].numpy(), g.numpy(), 1e-5)) for t in range(T)])
     y = torch.empty(T, N, device=DEV)
     ld.ldk_linear(Wd, xd, y, ld.LDK_SWIGLU, g=gd, eps=1e-5, scratch=scratch)
-    ref = gu[:, :N] / (1 + np.exp(-gu[:, :N])) * gu[:, N:]
+    ref = _silu(gu[:, :N]) * gu[:, N:]
     assert np.max(np.abs(y.cpu().numpy() - ref)) <= 2e-5 * np.abs(ref).max()
     y = y0.to(DEV).clone()
     ld.ldk_linear(Wd[:N], xd, y, ld.LDK_ADD, g=gd, eps=1e-5, scratch=scratch)
@@ -390,7 +393,7 @@ def test_linear_matrix_core_path(T, epi):
     else:
         ld.ldk_linear(W.to(DEV), x.to(DEV), y, ld.LDK_SWIGLU, g=g.to(DEV), eps=1e-5, scratch=scratch)
         gu = np.stack([oracle.matvec(Wh, oracle.rmsnorm(x[t].numpy(), g.numpy(), 1e-5)) for t in range(T)])
-        ref = gu[:, :N] / (1 + np.exp(-gu[:, :N])) * gu[:, N:]
+        ref = _silu(gu[:, :N]) * gu[:, N:]
     err = np.max(np.abs(y.cpu().numpy() - ref)) / np.abs(ref).max()
     assert err <= 2e-5, err
 
@@ -414,7 +417,7 @@ def test_linear_big_tile_every_plan(plan, epi, monkeypatch):
     if epi == "add":
         ref = y0.numpy() + ref
     elif epi == "swiglu":
-        ref = ref[:, :N] / (1 + np.exp(-ref[:, :N])) * ref[:, N:]
+        ref = _silu(ref[:, :N]) * ref[:, N:]
     err = np.max(np.abs(y.cpu().numpy() - ref)) / np.abs(ref).max()
     assert err <= 2e-5, err
 
@@ -425,8 +428,21 @@ def test_linear_matrix_core_7b_shapes_sampled():
     a tail of 32 / 63 rows past the last full 256-row tile, which is cut off and computed by the small-batch
     kernels: the rows on both sides of the cut are among the samples.  768 rows: three row tiles, a grid of
     less than one round."""
-    for T in (32, 256, 768, 1056, 2111):
-        for N, K, epi in [(12288, 4096, ld.LDK_STORE), (4096, 11008, ld.LDK_ADD), (11008, 4096, ld.LDK_SWIGLU)]:
+    _sampled_linear_cases((32, 256, 768, 1056, 2111),
+                          [(12288, 4096, ld.LDK_STORE), (4096, 11008, ld.LDK_ADD), (11008, 4096, ld.LDK_SWIGLU)])
+
+
+def test_linear_matrix_core_13b_shapes_sampled():
+    """The four layer matrices of the 13B shape (row lengths 5120 and 13824) at the row counts of its batch-64
+    step: 63 decode rows beside a 2048-row chunk (2111), and 2112 (one more decode row, or a chunk behind a
+    pending token); sampled outputs, the rows on both sides of the 256-row tile cut among them."""
+    _sampled_linear_cases((2111, 2112), [(15360, 5120, ld.LDK_STORE), (5120, 5120, ld.LDK_ADD),
+                                         (5120, 13824, ld.LDK_ADD), (13824, 5120, ld.LDK_SWIGLU)])
+
+
+def _sampled_linear_cases(row_counts, matrices):
+    for T in row_counts:
+        for N, K, epi in matrices:
             rows = N * (2 if epi == ld.LDK_SWIGLU else 1)
             W = gen.normal(3, N, (rows, K), std=0.02, device=DEV).bfloat16()
             x = gen.normal(3, 7 + T, (T, K), device=DEV)

@@ -223,6 +223,22 @@ def test_gumbel_sampling_draws_from_the_softmax_at_the_given_temperature():
     assert a != [oracle.sample_gumbel(lg, 1.0, 6, pos) for pos in range(200)]
 
 
+def test_gumbel_scores_are_what_the_sampler_maximises():
+    """The diagnostic scores (logits / T + noise) name the sampler's token as their lowest-index maximum,
+    reduce to logits / T plus a term that does not depend on the logits, and use the same uniforms."""
+    rng = np.random.default_rng(5)
+    for trial in range(50):
+        n = int(rng.integers(2, 300)); T = float(rng.choice([0.3, 0.7, 1.0, 2.5]))
+        seed = int(rng.integers(0, 2 ** 63)); pos = int(rng.integers(0, 5000))
+        lg = rng.normal(size=n) * 3
+        sc = oracle.gumbel_scores(lg, T, seed, pos)
+        assert int(np.argmax(sc)) == oracle.sample_gumbel(lg, T, seed, pos)
+        noise = sc - lg / T
+        u = np.array([oracle.uniform(seed, pos * n + i) for i in range(n)])
+        np.testing.assert_allclose(noise, -np.log(-np.log(u)), rtol=0, atol=1e-12)
+        np.testing.assert_allclose(oracle.gumbel_scores(lg + 1.0, T, seed, pos) - sc, 1.0 / T, rtol=0, atol=1e-12)
+
+
 def test_sequence_sampling_state(tiny_weights):
     """A sequence at temperature 0 is greedy whatever its seed; at temperature > 0 its emitted tokens are
     the sampler's draws on its own logits at the position the token will take."""
@@ -308,9 +324,11 @@ def test_block_and_slot_of_every_position():
 
 # ------------------------------------------------------------------ whole decoder
 
-def _torch_forward_all(shape, w, tokens):
+def _torch_forward_all(shape, w, tokens, kv_cast=None, kv_out=None):
     """Whole-sequence float64 forward with library routines (matmul, rms_norm, sdpa, silu, polar):
-    a formulation with no KV cache and no per-token loop."""
+    a formulation with no KV cache and no per-token loop.  kv_cast: applied to the rotated keys and to the
+    values before they are attended to (the cache's storage grid); kv_out: list that receives, per layer,
+    (rotated keys, values) before the cast, [T, kv_heads, hd]."""
     T = len(tokens); d, H, Hk, hd = shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim
     W = lambda t: t.double()
     x = W(w["embed"])[torch.tensor(tokens)]
@@ -327,6 +345,10 @@ def _torch_forward_all(shape, w, tokens):
         qkv = h @ W(w["wqkv"][l]).T
         q, k, v = qkv.split([H * hd, Hk * hd, Hk * hd], dim=-1)
         q, k, v = rope(q.view(T, H, hd)), rope(k.view(T, Hk, hd)), v.view(T, Hk, hd)
+        if kv_out is not None:
+            kv_out.append((k.clone(), v.clone()))
+        if kv_cast is not None:
+            k, v = kv_cast(k), kv_cast(v)
         k = k.repeat_interleave(H // Hk, dim=1); v = v.repeat_interleave(H // Hk, dim=1)
         if shape.window > 0:                         # band: key j visible to query i iff i - window < j <= i
             i = torch.arange(T)
@@ -366,6 +388,42 @@ def test_decoder_gqa_and_bf16_weights_match_library_rederivation():
     got = oracle.Model(shape, w, kv_round=0).forward_contig(tok)
     ref = _torch_forward_all(shape, w, tok.tolist())
     assert np.max(np.abs(got - ref)) / np.abs(ref).max() < 1e-11
+
+
+def test_cache_rounding_is_applied_to_rotated_keys_and_to_values_when_they_are_appended():
+    """The cache's element type is part of its contract: with a bf16 cache a token's keys (after the rotary
+    embedding) and values are rounded to bf16 once, when appended, and every later query sees the rounded
+    rows.  Pinned on a bf16 shape against the whole-sequence re-derivation: (i) every cached row read back
+    lies on the bf16 grid and within half a bf16 unit of the re-derivation's unrounded rotated key / value
+    (rounding before the rotation leaves values off the grid; skipping the values or the keys fails the grid
+    check), (ii) the logits equal the re-derivation's with the same rounding placed between the rotation and
+    the attention, and differ from the unrounded ones."""
+    from dataclasses import replace
+    shape = replace(TINY, n_kv_heads=2, dtype="bf16", name="tiny-gqa-bf16")
+    w = make_weights(shape, 7)
+    tok = _prompt(37, shape.vocab, 103)
+    m = oracle.Model(shape, w, kv_round=1)
+    kv = oracle.KV(m, 4, 1, 4)
+    rc, s = kv.alloc(0)
+    rc, t0, lg0 = kv.prefill(s, tok[:20])           # two calls: rounding must not depend on the chunking
+    rc, t1, lg1 = kv.prefill(s, tok[20:])           # feeds the pending token t0 first, then tok[20:]
+    seq = tok[:20].tolist() + [t0] + tok[20:].tolist()
+    cast = lambda t: torch.from_numpy(oracle.round_bf16(t.numpy()))
+    rows = []
+    ref = _torch_forward_all(shape, w, seq, kv_cast=cast, kv_out=rows)
+    plain = _torch_forward_all(shape, w, seq)
+    assert np.max(np.abs(lg1 - ref[-1])) / np.abs(ref[-1]).max() < 1e-11
+    assert np.max(np.abs(lg0 - ref[19])) / np.abs(ref[19]).max() < 1e-11
+    assert np.max(np.abs(lg1 - plain[-1])) / np.abs(plain[-1]).max() > 1e-6      # the rounding is not a no-op
+    for l in range(shape.n_layers):
+        for which in (0, 1):
+            for h in range(shape.n_kv_heads):
+                for pos in range(len(seq)):
+                    got = kv.read(s, l, which, h, pos)[1]
+                    want = rows[l][which][pos, h].numpy()
+                    np.testing.assert_array_equal(oracle.round_bf16(got), got)     # on the bf16 grid
+                    assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) * (1 + 1e-9))   # half a unit of an 8-bit significand
+                    assert np.any(got != want)
 
 
 @pytest.mark.parametrize("window", [1, 7, 16, 33])

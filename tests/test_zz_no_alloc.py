@@ -7,8 +7,8 @@ import pytest
 import torch
 
 import paper_2406_00059_amd as ld
-from tests.helpers import device_pool
-from tests.test_kernels_gpu import _attention_case, _attn_tol, _oracle_attention, _run_attention
+from helpers import device_pool
+from test_kernels_gpu import _attention_case, _attn_tol, _oracle_attention, _run_attention
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"

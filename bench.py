@@ -29,6 +29,8 @@ HBM_PEAK = 8.0e12          # bytes/s, MI355X HBM3E
 # 256 MiB copy (profiles/gate_up_gemv_hbm_traffic.md); valid only for the kernel source it was taken on.
 TRAFFIC_BYTES = 180_870_000
 TRAFFIC_KERNEL_MD5 = "0468ef4efdc5"
+ATTN_TRAFFIC_RATIO = 1.005
+ATTN_TRAFFIC_MD5 = "unset"
 ROUND_TOKENS = 256         # tokens emitted per round (1 by the preceding prefill + 255 decode steps)
 CHUNK = 256
 
@@ -41,6 +43,10 @@ def parse():
     ap.add_argument("--profile-steps", type=int, default=32, help="extra steps run with per-kernel events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-batch32", action="store_true", help="skip the batch-32 continuous-batching leg")
+    ap.add_argument("--no-attention-microbench", action="store_true", help="skip the decode-attention micro-benchmark leg")
+    ap.add_argument("--no-gqa", action="store_true", help="skip the batch-32 leg on the grouped-KV 7B shape")
+    ap.add_argument("--no-13b", action="store_true", help="skip the 13B-shaped batch-64 leg (200 GB KV pool)")
+    ap.add_argument("--steps-13b", type=int, default=16, help="timed steps of the 13B leg (the workload has 64)")
     ap.add_argument("--only-batch32", action="store_true", help="debug: run only the batch-32 leg (prints its dict)")
     ap.add_argument("--only-gqa", action="store_true",
                     help="run only the batch-32 leg on the grouped-KV 7B shape (8 KV heads, attention band 4096); "
@@ -61,6 +67,28 @@ def parse():
                          "attention of a mixed step), for the MFMA counter runs")
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (result is NOT the benchmark)")
     return ap.parse_args()
+
+
+MFMA_PEAK = 2.5e15         # flop/s, bf16 dense
+
+
+def ld_gemm_terms():
+    """bf16 terms per float32 activation on the matrix cores in multi-row passes: high + low part."""
+    return 2
+
+
+def _source_md5(name):
+    import hashlib
+    try:
+        return hashlib.md5(open(os.path.join(ROOT, "paper_2406_00059_amd", "csrc", name), "rb").read()).hexdigest()
+    except OSError:
+        return ""
+
+
+def attention_traffic_ratio():
+    """FETCH_SIZE + WRITE_SIZE over algorithmic bytes of the batch-32 decode attention launch
+    (profiles/decode_attention_b32_hbm_traffic.md), or None once the kernel's source has changed since."""
+    return ATTN_TRAFFIC_RATIO if _source_md5("ld_kernels.hip").startswith(ATTN_TRAFFIC_MD5) else None
 
 
 def kernel_traffic():
@@ -108,7 +136,10 @@ def run_batch1(args, ld, torch, shape, weights, model):
     from workloads import gen, SEED_BASE
     seed = SEED_BASE + 2
     K, W = args.steps, args.warmup
-    rounds = max(1, -(-K // (ROUND_TOKENS - 1)))
+    # decode steps per round: 255 in the workload; a short run (--steps below three rounds) keeps the round
+    # structure by shortening the rounds, so that observation prefills happen inside it
+    per_round = max(1, min(ROUND_TOKENS - 1, K // 3))
+    rounds = max(1, -(-K // per_round))
     max_ctx = 1024 + rounds * (ROUND_TOKENS + 513) + args.profile_steps + 64
     nblk_seq = -(-max_ctx // 16)
     kv = ld.KV(model, nblk_seq + 16, CHUNK, 2, nblk_seq)
@@ -134,8 +165,9 @@ def run_batch1(args, ld, torch, shape, weights, model):
     done = 0
     torch.cuda.synchronize()
     t_begin = time.perf_counter()
+    obs_ms, obs_rows = [], []
     for r in range(rounds):
-        n = min(ROUND_TOKENS - 1, K - done)
+        n = min(per_round, K - done)
         ctx = ld.ld_kv_len(kv.h, s) + 1
         stamps = [time.perf_counter()]
         rc, got = ld.ld_decode_run(kv.h, [s], n, stream, lambda q, tok, pos: stamps.append(time.perf_counter()) and 0)
@@ -144,12 +176,14 @@ def run_batch1(args, ld, torch, shape, weights, model):
         step_ms += [(b - a) * 1e3 for a, b in zip(stamps, stamps[1:])]
         step_bytes += [Wb + (ctx + i) * kappa for i in range(n)]
         done += n
-        if done >= K and r == rounds - 1 and n < ROUND_TOKENS - 1:
+        if done >= K and r == rounds - 1 and n < per_round:
             break
         obs = gen.randint(seed, 200 + r, 0, shape.vocab - 1, obs_len[r]).numpy().astype(np.int32)
         t0 = time.perf_counter()
         ld.ld_prefill(kv.h, s, obs, stream, noop_cb)
-        pf_time += time.perf_counter() - t0; pf_tokens += obs.size + 1
+        dt = time.perf_counter() - t0
+        pf_time += dt; pf_tokens += obs.size + 1
+        obs_ms.append(dt * 1e3); obs_rows.append(obs.size + 1)
     torch.cuda.synchronize()
     t_total = time.perf_counter() - t_begin
     assert len(step_ms) == K
@@ -215,6 +249,9 @@ def run_batch1(args, ld, torch, shape, weights, model):
         "step_hbm_GBps": round(sum(step_bytes) / dec_s / 1e9, 1),
         "step_hbm_frac": round(sum(step_bytes) / dec_s / HBM_PEAK, 4),
         "prefill_tokens_per_s": round(pf_tokens / pf_time, 1), "prefill_tokens": pf_tokens,
+        "decode_steps_per_round": per_round, "observations": len(obs_ms),
+        "observation_rows": obs_rows, "observation_prefill_ms": [round(t, 3) for t in obs_ms],
+        "observation_ms_per_256_rows": round(256.0 * sum(obs_ms) / max(sum(obs_rows), 1), 3) if obs_ms else None,
         "scenario_s": round(t_total, 3), "final_context": int(ld.ld_kv_len(kv.h, s)),
         "kernel_sum_ms_per_step": round(sum(per_step_ms.values()), 4),
         "kernels": kernels, "roofline": roofline,
@@ -316,11 +353,67 @@ def run_batch32(args, ld, torch, shape, model):
         "kernel_ms_per_step": {k: round(v[0] / 4, 4) for k, v in prof.items()},
         "sum_visible_context": int(sum_ctx),
         "kernel_ms_mixed_step": {k: round(v[0], 3) for k, v in prof_mixed.items()},
-        "mixed_step_gemm_TFLOPs_nominal": round(gemm_nominal / (gemm_ms_mixed * 1e-3) / 1e12, 1),
-        "mixed_step_gemm_mfma_frac": round(2.0 * gemm_nominal / (gemm_ms_mixed * 1e-3) / 2.5e15, 4),
+        # MFMA fractions: first on the method's flops (2 * rows * weight elements), then on what the matrix cores
+        # execute when the float32 activations go in as two bf16 terms (twice that)
+        "mixed_step_gemm_TFLOPs": round(gemm_nominal / (gemm_ms_mixed * 1e-3) / 1e12, 1),
+        "mixed_step_gemm_mfma_frac": round(gemm_nominal / (gemm_ms_mixed * 1e-3) / MFMA_PEAK, 4),
+        "mixed_step_gemm_mfma_frac_executed": round(ld_gemm_terms() * gemm_nominal / (gemm_ms_mixed * 1e-3) / MFMA_PEAK, 4),
+        "decode_gemm_weight_GBps": round(Wb / (sum(prof[c][0] for c in ("qkv", "wo", "gate_up", "down", "lm_head")) / 4 * 1e-3) / 1e9, 1),
+        "roofline": {"bound": "hbm", "kernel": "decode attention (k_attn_partial / k_attn_decode_grouped + k_attn_merge), one layer, 32 rows",
+                     "achieved": round(att_bytes / att_avg / 1e9, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                     "frac": round(att_bytes / att_avg / HBM_PEAK, 4), "avg_launch_us": round(att_avg * 1e6, 1),
+                     "bytes_per_launch": int(att_bytes), "launches_timed": int(prof["attention"][1]),
+                     "share_of_step_kernel_time": round(prof["attention"][0] / sum(v[0] for v in prof.values()), 3),
+                     "traffic_over_algorithmic": attention_traffic_ratio() if not shape.window and shape.n_kv_heads == shape.n_heads else None},
     }
     kv.close()
     return out
+
+
+def run_attention_microbench(args, ld, torch):
+    """Decode-attention micro-benchmark: batch 16, 32 heads x 128, bf16 paged cache with block size 16 and a
+    randomly permuted block table, contexts uniform in [256, 4096], keys / values / queries N(0,1), one query
+    per sequence.  Timed: the split-KV attention kernel plus its merge (one ldk_paged_attention call), HIP
+    events around the loop.  Cold: four pools (4 x 0.57 GB) in rotation, so that a pool's lines have left the
+    256 MB memory-side cache when its turn comes again; warm: the same pool every time."""
+    from workloads import gen, SEED_BASE
+    seed = SEED_BASE + 1
+    B, H, hd, reps, n_pools = 16, 32, 128, 200, 4
+    lens = gen.randint(seed, 1, 256, 4096, B).tolist()
+    nb = [-(-n // 16) for n in lens]
+    total = sum(nb)
+    perm = gen.permutation(seed, 1, total).tolist()
+    table = torch.zeros((B, max(nb)), dtype=torch.int32)
+    it = iter(perm)
+    for b in range(B):
+        for j in range(nb[b]):
+            table[b, j] = next(it)
+    table = table.cuda()
+    pools = [gen.normal(seed, 10 + i, (total, 2, H, 16, hd), device="cuda", dtype=torch.bfloat16) for i in range(n_pools)]
+    q = gen.normal(seed, 3, (B, H * hd), device="cuda")
+    out = torch.empty(B, H * hd, device="cuda")
+    ctx = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    slot = torch.arange(B, dtype=torch.int32, device="cuda")
+    scratch = torch.empty(ld.ldk_attention_scratch_bytes(B, H, H, hd, max(lens)), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    call = lambda pool: ld.ldk_paged_attention(q, H * hd, pool, table, slot, ctx, max(lens), H, H, hd, out, scratch, stream=stream)
+    alg = sum(lens) * 2 * H * hd * 2 + 2 * B * H * hd * 4 + total * 4
+    res = {}
+    for name, seq in (("cold", lambda i: pools[i % n_pools]), ("warm", lambda i: pools[0])):
+        for i in range(8):
+            call(seq(i))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(reps):
+            call(seq(i))
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        res[name] = {"us_per_call": round(us, 2), "GBps": round(alg / us / 1e3, 1), "hbm_frac": round(alg / (us * 1e-6) / HBM_PEAK, 4)}
+    return {"workload": "decode attention, bf16, batch 16, 32 heads x 128, block 16, permuted block table, contexts "
+                        f"U[256,4096] (sum {sum(lens)}), one query per sequence; attention kernel + merge per call",
+            "reps": reps, "pools_in_rotation": n_pools, "algorithmic_bytes_per_call": alg,
+            "cold": res["cold"], "warm": res["warm"], "target_GBps": 5600.0}
 
 
 def run_13b(args, ld, torch):
@@ -332,7 +425,7 @@ def run_13b(args, ld, torch):
     from workloads import LLAMA13B, SEED_BASE, gen, make_weights
     shape = LLAMA13B if not args.layers else LLAMA13B.with_layers(args.layers)
     seed = SEED_BASE + 4
-    B, steps, chunk = 64, 64, 2048
+    B, steps, chunk = 64, max(1, args.steps_13b), 2048
     weights = make_weights(shape, seed, device="cuda")
     model = ld.Model(shape, weights, max_chunk=chunk)
     n_blocks = int(200e9 // (shape.kv_bytes_per_token * 16)) if not args.layers else 15258
@@ -382,16 +475,20 @@ def run_13b(args, ld, torch):
     gemm_ms = sum(prof[c][0] for c in ("qkv", "wo", "gate_up", "down", "lm_head"))
     out = {
         "workload": "13B-shaped bf16 decoder, batch 64, KV pool of %d blocks (%.1f GB), contexts %d..%d after scaling "
-                    "by %.3f, 64 steps of 63 decode rows + one 2048-token prefill chunk" %
+                    "by %.3f, steps of 63 decode rows + one 2048-token prefill chunk" %
                     (n_blocks, n_blocks * 16 * shape.kv_bytes_per_token / 1e9, min(lens), max(lens), scale),
         "ms_per_step": round(statistics.mean(ms), 2), "tokens_per_s": round((B - 1 + chunk) * steps / total, 1),
         "decode_tokens_per_s": round((B - 1) * steps / total, 1),
         "kv_GB_per_step": round(statistics.mean(kv_bytes) / 1e9, 1),
         "kernel_ms_one_step": {c: round(v[0], 3) for c, v in prof.items()},
         "attention_GBps_if_all_attention_time_were_decode": round(statistics.mean(kv_bytes) / (prof["attention"][0] * 1e-3) / 1e9, 1),
-        "gemm_TFLOPs_nominal": round(gemm_flops / (gemm_ms * 1e-3) / 1e12, 1),
-        "n_layers": shape.n_layers,
+        "gemm_TFLOPs": round(gemm_flops / (gemm_ms * 1e-3) / 1e12, 1),
+        "gemm_mfma_frac": round(gemm_flops / (gemm_ms * 1e-3) / MFMA_PEAK, 4),
+        "gemm_mfma_frac_executed": round(ld_gemm_terms() * gemm_flops / (gemm_ms * 1e-3) / MFMA_PEAK, 4),
+        "attention_ms_one_step": round(prof["attention"][0], 3),
+        "steps_timed": steps, "n_layers": shape.n_layers,
     }
+    del pool
     kv.close()
     return out
 
@@ -513,9 +610,26 @@ def main():
         return
     res = run_batch1(args, ld, torch, shape, weights, model)
     b32 = None if args.no_batch32 else run_batch32(args, ld, torch, shape, model)
+    amb = None if args.no_attention_microbench else run_attention_microbench(args, ld, torch)
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(shape, weights, ctx=1024, steps=160, seed=SEED_BASE + 2)
+    # the remaining legs need the memory: drop the 7B decoder first
+    import gc
+    model.close(); del model, weights
+    gc.collect(); torch.cuda.empty_cache()
+    gqa = None
+    if not args.no_gqa:
+        gshape = MISTRAL7B if not args.layers else MISTRAL7B.with_layers(args.layers)
+        gweights = make_weights(gshape, SEED_BASE + 5, device="cuda")
+        gmodel = ld.Model(gshape, gweights, max_chunk=CHUNK)
+        gqa = run_batch32(args, ld, torch, gshape, gmodel)
+        gmodel.close(); del gmodel, gweights
+        gc.collect(); torch.cuda.empty_cache()
+    b13 = None
+    if not args.no_13b:
+        b13 = run_13b(args, ld, torch)
+        gc.collect(); torch.cuda.empty_cache()
 
     line = {
         "metric": "decode tokens/sec + % peak HBM BW, 7B-shape bf16 at batch 1 and 32, 1 MI355X",
@@ -530,6 +644,9 @@ def main():
         "cpu_baseline": cpu,
         "batch1": res,
         "batch32": b32,
+        "attention_microbench": amb,
+        "gqa_batch32": gqa,
+        "13b_batch64": b13,
     }
     print(json.dumps(line))
 

@@ -20,14 +20,18 @@ def sources():
 
 
 def build(verbose: bool = False) -> str:
-    objs = []
-    for src in sources():
+    from concurrent.futures import ThreadPoolExecutor
+
+    def compile_one(src):
         obj = os.path.join(CSRC, os.path.basename(src) + ".o")
         cmd = [HIPCC, *FLAGS, "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)
-        objs.append(obj)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as pool:     # one compiler process per source file
+        objs = list(pool.map(compile_one, sources()))
     subprocess.run([HIPCC, "-shared", "--offload-arch=gfx950", "-o", LIB, *objs], check=True)
     return LIB
 

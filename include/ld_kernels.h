@@ -97,11 +97,11 @@ ld_status ldk_paged_attention(const float *q, int32_t q_stride, const void *pool
  * LDK_STATIC_SCRATCH_BYTES bytes, which every GPU the library is used on holds from the first call on that GPU
  * until the process ends; its address is looked up once per device.  The call allocates and frees nothing.
  * A launch whose partials (T * H * chunks * (hd + 2) floats; chunks as the launch itself is cut, at most
- * ceil(max_ctx / 64)) would not fit is refused with LD_E_RANGE before anything is launched: 32 MiB serves
- * e.g. 64 rows x 40 heads at contexts up to 16384.  Nothing in the array has to start at zero (every partial
+ * ceil(max_ctx / 64)) would not fit is refused with LD_E_RANGE before anything is launched: 64 MiB serves
+ * e.g. 64 rows x 40 heads at contexts up to 16384 (42 MB).  Nothing in the array has to start at zero (every partial
  * a merge reads was written by the same call), but all calls on one GPU share it: calls that overlap on one
  * GPU (different streams, or different threads) race; calls on one stream do not. */
-#define LDK_STATIC_SCRATCH_BYTES (32u << 20)
+#define LDK_STATIC_SCRATCH_BYTES (64u << 20)
 size_t ldk_static_scratch_bytes(void);
 ld_status ldk_paged_attention_static(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
                                      const int32_t *table, int32_t table_stride, const int32_t *seq_slot,

@@ -622,14 +622,18 @@ static int head_group(int H, int Hkv, bool mfma) {
 }
 // Chunk size in KV blocks: small chunks when few (row, head group) pairs exist, so that the launch still
 // has about two workgroups per CU (measured: a workgroup's fixed cost, table lookup, first loads, merge,
-// makes finer chunks slower); at most 64 blocks (1024 tokens) per chunk; a multiple of 4 (one block per
-// wave and round), of 8 for the matrix-core kernel (two blocks per wave and round).
+// makes finer chunks slower); a multiple of 4 (one block per wave and round), of 8 for the matrix-core kernel
+// (two blocks per wave and round).  At most 32 blocks (512 tokens) per chunk in the scalar kernel and 64 in the
+// matrix-core kernel: contexts in a batch differ, so the longest chunks set the tail of the launch, and with 64
+// the scalar kernel measured 12 % slower at batch 32 (contexts 512 .. 8192) and 36 % slower at batch 16
+// (contexts 256 .. 4096), where all workgroups fit the chip at once; 16 and 32 measure alike.
+static int attn_chunk_cap(bool mfma) { return mfma ? 64 : 32; }
 static int attn_chunk_blocks(int T, int H, int Hkv, int max_ctx, int window, bool mfma) {
     const int64_t blocks = (int64_t)T * (H / head_group(H, Hkv, mfma)) * visible_blocks(max_ctx, window);
     const int q = mfma ? 8 : 4;
     int64_t cb = (blocks + 511) / 512;
     cb = (cb + q - 1) / q * q;
-    return (int)std::min<int64_t>(std::max<int64_t>(cb, q), 64);
+    return (int)std::min<int64_t>(std::max<int64_t>(cb, q), attn_chunk_cap(mfma));
 }
 static int attn_max_chunks(int T, int H, int Hkv, int max_ctx, int window, bool mfma) {
     const int cb = attn_chunk_blocks(T, H, Hkv, max_ctx, window, mfma);
@@ -638,13 +642,13 @@ static int attn_max_chunks(int T, int H, int Hkv, int max_ctx, int window, bool 
 
 // Most chunks any launch with contexts up to max_ctx can use.  The chunk size follows the launch's own
 // longest context, so the chunk count is not monotonic in it: bound it over all shorter contexts.  With nb
-// visible blocks, cb >= T * units * nb / 512 gives nb / cb <= 512 / (T * units) unless cb hit its cap of
-// 64, where the count is nb / 64; and cb >= q gives nb / q.
+// visible blocks, cb >= T * units * nb / 512 gives nb / cb <= 512 / (T * units) unless cb hit its cap,
+// where the count is nb / cap; and cb >= q gives nb / q.
 static int attn_chunk_bound(int T, int H, int Hkv, int max_ctx, int window, bool mfma) {
-    const int q = mfma ? 8 : 4;
+    const int q = mfma ? 8 : 4, cap = attn_chunk_cap(mfma);
     const int64_t units = (int64_t)T * (H / head_group(H, Hkv, mfma));
     const int64_t nb = visible_blocks(max_ctx, window);
-    const int64_t by_target = std::max<int64_t>(512 / units + 1, (nb + 63) / 64), by_min = (nb + q - 1) / q;
+    const int64_t by_target = std::max<int64_t>(512 / units + 1, (nb + cap - 1) / cap), by_min = (nb + q - 1) / q;
     return (int)std::max<int64_t>(1, std::min(by_target, by_min));
 }
 

@@ -8,9 +8,15 @@
  * KV-cache / prefill / decode definitions; section 4.1: temperature 0 = greedy).
  *
  * Conventions
- *  - Every call returns an ld_status; nothing throws or aborts.  On error the out
- *    parameters and all sequence / allocator state are left unchanged, and
- *    ld_last_error() returns a thread-local description.
+ *  - Every call returns an ld_status; nothing throws or aborts, and ld_last_error()
+ *    returns a thread-local description.  Argument, state and capacity errors
+ *    (LD_E_INVAL, LD_E_STATE, LD_E_RANGE, LD_E_NOMEM) are found before anything is
+ *    changed: the out parameters and all sequence / allocator state are as before the
+ *    call.  LD_E_HIP (a HIP runtime call failed while a pass was being enqueued or
+ *    waited for) is different: blocks may be reserved, a prompt may be partly fed, copies
+ *    may be on their way.  The cache is then marked unusable, every later step, swap or
+ *    fork on it returns LD_E_STATE, and the caller destroys it (ld_kv_free and
+ *    ld_kv_destroy still work).
  *  - "DEVICE" pointers are HIP device memory owned by the caller (allocate it with
  *    any allocator, e.g. a torch tensor's data_ptr()); it must stay valid until the
  *    object that received it is destroyed.  "HOST" pointers are borrowed for the

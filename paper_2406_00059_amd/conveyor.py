@@ -12,8 +12,11 @@ While a request waits for its tool, its KV cache can stay on the GPU, be swapped
 discarded and recomputed (the options section 2.2 describes for systems that manage the cache across tool
 calls); `retention` selects one, or lets `choose_retention` pick by the predicted tool time.
 
-Everything here is host logic: no GPU work happens in this file, the engine does it.  Tools run in forked
-child processes with a duplex pipe (section 3.3 steps (6), (7)); the children never touch the GPU.
+Everything here is host logic: no GPU work happens in this file, the engine does it.  Tools run in child
+processes with a duplex pipe (section 3.3 steps (6), (7)); the children never touch the GPU.  They are forked
+from a fork server, a single-threaded helper process, not from the serving process itself: that one holds the
+GPU runtime's threads, and a child forked while one of them holds a lock could wait for it forever.  Call
+start_tool_server() once before the first GPU call (it is started on first use otherwise).
 """
 from __future__ import annotations
 
@@ -97,16 +100,45 @@ def _tool_main(conn, plugin):
         os._exit(0)          # no interpreter tear-down in the child: it shares nothing it may clean up
 
 
+class _NoTool(ToolPlugin):
+    def run(self, pieces):
+        return []
+
+
+_tool_ctx = None
+
+
+def start_tool_server():
+    """Starts the fork server that tool instances are forked from and runs one empty tool through it, so that
+    the first real tool does not pay for the server's start.  Call it before the first GPU call of the
+    process; later calls return at once.  Plugins travel to their process by pickle."""
+    global _tool_ctx
+    if _tool_ctx is None:
+        ctx = mp.get_context("forkserver")
+        ctx.set_forkserver_preload([__name__])
+        _tool_ctx = ctx
+        ToolProcess(_NoTool(), []).wait()
+    return _tool_ctx
+
+
 class ToolProcess:
-    """One tool instance in a forked child process, duplex pipe for the command and the observation."""
+    """One tool instance in a child process of the fork server, duplex pipe for the command and the observation."""
 
     def __init__(self, plugin: ToolPlugin, pieces):
+        ctx = start_tool_server()
         self.started = time.perf_counter()
-        self.conn, child = mp.get_context("fork").Pipe(duplex=True)
-        self.proc = mp.get_context("fork").Process(target=_tool_main, args=(child, plugin), daemon=True)
+        self.conn, child = ctx.Pipe(duplex=True)
+        self.proc = ctx.Process(target=_tool_main, args=(child, plugin), daemon=True)
         self.proc.start()
         child.close()
         self.conn.send(pieces)
+
+    def kill(self):
+        """Ends a tool that is given up on (time-out, aborted request)."""
+        if self.proc.is_alive():
+            self.proc.kill()
+        self.proc.join()
+        self.conn.close()
 
     def poll(self):
         """(observation, tool seconds) if the tool has finished, else None.  Never blocks."""
@@ -142,6 +174,7 @@ class Request:
     s: list = field(default_factory=list)             # seconds into the round at which the tool was started
     retained: list = field(default_factory=list)      # per tool wait: "keep" | "swap" | "discard" | None (no wait)
     latency: float = 0.0
+    failed: str | None = None                         # why the request was given up ("tool time-out ..."), else None
 
 
 def choose_retention(ctx_tokens, tool_s, kv_bytes_per_token, swap_bytes_per_s, prefill_tokens_per_s):
@@ -166,15 +199,18 @@ class Scheduler:
          new_sequence() -> seq, prefill(seq, tokens) -> token, decode(seqs) -> tokens, free(seq)."""
 
     def __init__(self, engine, partial=True, retention="keep", predict_tool_s=None, rates=None, shared_prefix=0,
-                 trim=False):
+                 trim=False, tool_timeout_s=None):
         """retention: "keep" | "swap" | "discard" | "auto".  "auto" asks choose_retention with
         predict_tool_s(plugin) seconds and rates = dict(kv_bytes_per_token, swap_bytes_per_s,
         prefill_tokens_per_s).  "swap" needs engine.swap_out / engine.swap_in.
         shared_prefix = k > 0: all prompts start with the same k tokens (system prompt, tool descriptions);
         they are prefilled once and every request forks from that cache (engine.fork).
         trim: after every prefill (prompt or observation) the sequence gives up the cache blocks below its
-        attention band (engine.trim; models with a band only)."""
+        attention band (engine.trim; models with a band only).
+        tool_timeout_s: a tool that has not answered that long after its start is killed and its request ends
+        as failed (its cache is freed, the other requests go on); None: wait for ever."""
         self.engine, self.partial, self.retention, self.trim = engine, partial, retention, trim
+        self.tool_timeout_s = tool_timeout_s
         self.predict_tool_s, self.rates, self.shared_prefix = predict_tool_s, rates or {}, shared_prefix
 
     def serve(self, requests):
@@ -202,6 +238,15 @@ class Scheduler:
                     res = x["tool"].poll()
                     if res is not None:
                         x["obs"] = res
+                    elif self.tool_timeout_s is not None and time.perf_counter() - x["tool"].started > self.tool_timeout_s:
+                        x["tool"].kill()
+                        x["req"].failed = f"tool time-out after {self.tool_timeout_s} s in round {x['round'] - (x['left'] == 0)}"
+                        x["req"].latency = time.perf_counter() - x["t_start"]
+                        if x["away"] == "swap":
+                            eng.swap_in(x["seq"])     # the handle has to hold its blocks again to be freed like any other
+                        if x["away"] != "discard":
+                            eng.free(x["seq"])
+                        x["tool"], x["done"], x["freed"] = None, True, True
             # (2) prefill whatever is ready: a new prompt, or an observation whose round has ended
             decoding = []
             for x in st:
@@ -240,7 +285,8 @@ class Scheduler:
             elif not any(x["feed"] is not None for x in st if not x["done"]):
                 time.sleep(0.0005)       # every live request waits for a tool: nothing to run on the GPU
         for x in st:
-            eng.free(x["seq"])
+            if not x.get("freed"):
+                eng.free(x["seq"])
         return requests
 
     def _retain(self, x):
@@ -333,52 +379,3 @@ class LdEngine:
     def swap_in(self, seq):
         self.ld.ld_kv_swap_in(self.kv, seq, self._host[seq], self.stream)
         self._done.append(self._host.pop(seq))        # released by the next prefill's synchronisation
-
-
-class FakeEngine:
-    """A stand-in engine for tests without a GPU: a fixed time per call and tokens that are a pure function
-    of the sequence's history, so two runs over the same inputs produce the same tokens."""
-
-    def __init__(self, per_token_s=0.002, prefill_s=0.004, vocab=1000):
-        self.per_token_s, self.prefill_s, self.vocab = per_token_s, prefill_s, vocab
-        self.hist, self.next_id, self.swapped = {}, 0, set()
-
-    def _next(self, seq):
-        h = 1469598103934665603
-        for t in self.hist[seq][-16:]:
-            h = ((h ^ (t + 1)) * 1099511628211) & ((1 << 64) - 1)
-        tok = (h >> 20) % self.vocab
-        self.hist[seq].append(tok)
-        return tok
-
-    def new_sequence(self):
-        self.next_id += 1
-        self.hist[self.next_id] = []
-        return self.next_id
-
-    def prefill(self, seq, tokens):
-        assert seq not in self.swapped
-        time.sleep(self.prefill_s)
-        self.hist[seq].extend(tokens)
-        return self._next(seq)
-
-    def decode(self, seqs):
-        time.sleep(self.per_token_s)
-        return [self._next(s) for s in seqs]
-
-    def free(self, seq):
-        self.hist.pop(seq, None)
-
-    def fork(self, parent, n_tokens):
-        child = self.new_sequence()
-        self.hist[child] = self.hist[parent][:n_tokens]
-        return child
-
-    def trim(self, seq):
-        return 0
-
-    def swap_out(self, seq):
-        self.swapped.add(seq)
-
-    def swap_in(self, seq):
-        self.swapped.remove(seq)

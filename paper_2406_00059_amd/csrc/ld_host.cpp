@@ -160,11 +160,24 @@ struct ld_kv {
             cat.push_back(current);
         }
     } timer;
+    // Set when a HIP call failed after a pass was planned (blocks reserved, copies or kernels possibly enqueued):
+    // the cache's contents and the allocator no longer describe each other, every later step is refused.
+    bool broken = false;
     int32_t *trow(int s) { return table.data() + (size_t)s * max_blocks; }
     const int32_t *trow(int s) const { return table.data() + (size_t)s * max_blocks; }
 };
 
 namespace {
+
+// A failed HIP call leaves the cache unusable (see ld_kv::broken); validation errors leave it untouched.
+ld_status seal(ld_kv *kv, ld_status rc) {
+    if (rc == LD_E_HIP) kv->broken = true;
+    return rc;
+}
+#define LD_REFUSE_BROKEN(kv, who)                                                                              \
+    do {                                                                                                       \
+        if ((kv)->broken) return fail(LD_E_STATE, who ": the cache is unusable after a failed HIP call; destroy it"); \
+    } while (0)
 
 Seq *get_seq(ld_kv *kv, ld_seq s) {
     if (!kv || s < 0 || s >= kv->max_seqs || !kv->seqs[s].active) return nullptr;
@@ -449,6 +462,7 @@ ld_status run_step(ld_kv *kv, const std::vector<Feed> &feeds, void *stream, ld_t
                    float *logits_out, const char *who) {
     const ld_model_config &c = kv->m->c;
     // --- validate, no state change
+    if (kv->broken) { ld::set_error("%s: the cache is unusable after a failed HIP call; destroy it", who); return LD_E_STATE; }
     std::vector<char> seen(kv->max_seqs, 0);
     int64_t total_rows = 0, total_missing = 0;
     for (const Feed &f : feeds) {
@@ -505,7 +519,7 @@ ld_status run_step(ld_kv *kv, const std::vector<Feed> &feeds, void *stream, ld_t
             }
         }
     ld_status rc = run_pass(kv, rows, n_single, emit, (hipStream_t)stream, logits_out);
-    if (rc) return rc;
+    if (rc) return seal(kv, rc);
 
     // --- commit state, then hand the tokens over
     for (size_t i = 0; i < feeds.size(); i++) {
@@ -676,6 +690,7 @@ size_t ld_kv_swap_bytes(const ld_kv *kv, ld_seq seq) {
 ld_status ld_kv_swap_out(ld_kv *kv, ld_seq seq, void *host_buf, size_t bytes, void *stream) {
     Seq *q = get_seq(kv, seq);
     if (!q || (!host_buf && q->n_cached > 0)) return fail(LD_E_INVAL, "ld_kv_swap_out: bad argument");
+    LD_REFUSE_BROKEN(kv, "ld_kv_swap_out");
     if (q->swapped) return fail(LD_E_STATE, "ld_kv_swap_out: sequence is already swapped out");
     if (bytes < ld_kv_swap_bytes(kv, seq)) return fail(LD_E_RANGE, "ld_kv_swap_out: host buffer too small");
     const size_t bb = block_bytes(kv);
@@ -684,8 +699,11 @@ ld_status ld_kv_swap_out(ld_kv *kv, ld_seq seq, void *host_buf, size_t bytes, vo
     int32_t *t = kv->trow(seq);
     // one strided copy per logical block: its n_layers pieces lie one layer slice apart in the pool
     for (int64_t j = q->first_block; j < nb; j++)      // released blocks: their part of the buffer is not written
-        LD_HIP_TRY(hipMemcpy2DAsync((char *)host_buf + (size_t)j * L * bb, bb, kv->pool + (size_t)t[j] * bb,
-                                    (size_t)kv->n_blocks * bb, bb, L, hipMemcpyDeviceToHost, (hipStream_t)stream));
+        if (hipMemcpy2DAsync((char *)host_buf + (size_t)j * L * bb, bb, kv->pool + (size_t)t[j] * bb,
+                             (size_t)kv->n_blocks * bb, bb, L, hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess) {
+            kv->broken = true;      // some blocks' copies may be on their way: the sequence is neither in nor out
+            return fail(LD_E_HIP, "ld_kv_swap_out: hipMemcpy2DAsync failed");
+        }
     release_blocks(kv, seq);
     q->swapped = true;
     return LD_OK;
@@ -694,6 +712,7 @@ ld_status ld_kv_swap_out(ld_kv *kv, ld_seq seq, void *host_buf, size_t bytes, vo
 ld_status ld_kv_swap_in(ld_kv *kv, ld_seq seq, const void *host_buf, size_t bytes, void *stream) {
     Seq *q = get_seq(kv, seq);
     if (!q || (!host_buf && q->n_cached > 0)) return fail(LD_E_INVAL, "ld_kv_swap_in: bad argument");
+    LD_REFUSE_BROKEN(kv, "ld_kv_swap_in");
     if (!q->swapped) return fail(LD_E_STATE, "ld_kv_swap_in: sequence is not swapped out");
     if (bytes < ld_kv_swap_bytes(kv, seq)) return fail(LD_E_RANGE, "ld_kv_swap_in: host buffer too small");
     const int64_t nb = blocks_for(kv, q->n_cached);
@@ -703,9 +722,12 @@ ld_status ld_kv_swap_in(ld_kv *kv, ld_seq seq, const void *host_buf, size_t byte
     const int L = kv->m->c.n_layers;
     const int32_t *t = kv->trow(seq);
     for (int64_t j = q->first_block; j < nb; j++)
-        LD_HIP_TRY(hipMemcpy2DAsync(kv->pool + (size_t)t[j] * bb, (size_t)kv->n_blocks * bb,
-                                    (const char *)host_buf + (size_t)j * L * bb, bb, bb, L, hipMemcpyHostToDevice,
-                                    (hipStream_t)stream));
+        if (hipMemcpy2DAsync(kv->pool + (size_t)t[j] * bb, (size_t)kv->n_blocks * bb,
+                             (const char *)host_buf + (size_t)j * L * bb, bb, bb, L, hipMemcpyHostToDevice,
+                             (hipStream_t)stream) != hipSuccess) {
+            kv->broken = true;      // blocks are taken and partly filled
+            return fail(LD_E_HIP, "ld_kv_swap_in: hipMemcpy2DAsync failed");
+        }
     q->swapped = false;
     return LD_OK;
 }
@@ -741,6 +763,7 @@ ld_status ld_kv_set_sampling(ld_kv *kv, ld_seq seq, float temperature, uint64_t 
 ld_status ld_kv_fork(ld_kv *kv, ld_seq parent, int64_t n_tokens, void *stream, ld_seq *out) {
     Seq *p = get_seq(kv, parent);
     if (!p || !out || n_tokens < 0 || n_tokens > p->n_cached) return fail(LD_E_INVAL, "ld_kv_fork: bad argument");
+    LD_REFUSE_BROKEN(kv, "ld_kv_fork");
     if (p->swapped) return fail(LD_E_STATE, "ld_kv_fork: parent is swapped out");
     int s = 0;
     while (s < kv->max_seqs && kv->seqs[s].active) s++;
@@ -766,9 +789,12 @@ ld_status ld_kv_fork(ld_kv *kv, ld_seq parent, int64_t n_tokens, void *stream, l
     if (tail) {
         map_blocks(kv, s, full + 1);    // pops one block for logical block `full`
         const size_t bb = block_bytes(kv);
-        LD_HIP_TRY(hipMemcpy2DAsync(kv->pool + (size_t)t[full] * bb, (size_t)kv->n_blocks * bb,
-                                    kv->pool + (size_t)pt[full] * bb, (size_t)kv->n_blocks * bb, bb, kv->m->c.n_layers,
-                                    hipMemcpyDeviceToDevice, (hipStream_t)stream));
+        if (hipMemcpy2DAsync(kv->pool + (size_t)t[full] * bb, (size_t)kv->n_blocks * bb,
+                             kv->pool + (size_t)pt[full] * bb, (size_t)kv->n_blocks * bb, bb, kv->m->c.n_layers,
+                             hipMemcpyDeviceToDevice, (hipStream_t)stream) != hipSuccess) {
+            kv->broken = true;      // the child exists and holds blocks, its copied tail does not
+            return fail(LD_E_HIP, "ld_kv_fork: hipMemcpy2DAsync failed");
+        }
     }
     *out = s;
     return LD_OK;
@@ -804,6 +830,7 @@ ld_status ld_kv_profile_read(const ld_kv *kv, ld_profile *out) {
 ld_status ld_prefill(ld_kv *kv, ld_seq seq, const int32_t *tokens, int32_t n, void *stream, ld_token_cb cb,
                      void *user, float *logits_out) {
     if (!kv) return fail(LD_E_INVAL, "ld_prefill: null kv");
+    LD_REFUSE_BROKEN(kv, "ld_prefill");
     Seq *q = get_seq(kv, seq);
     if (!q) return fail(LD_E_INVAL, "ld_prefill: bad sequence handle");
     if (q->stopped) return fail(LD_E_STATE, "ld_prefill: sequence was stopped by its callback");
@@ -832,7 +859,7 @@ ld_status ld_prefill(ld_kv *kv, ld_seq seq, const int32_t *tokens, int32_t n, vo
         while ((int)rows.size() < chunk) rows.push_back({tokens[consumed++], pos++, seq});
         std::vector<int32_t> emit;  // none
         ld_status rc = run_pass(kv, rows, 0, emit, (hipStream_t)stream, nullptr);
-        if (rc) return rc;
+        if (rc) return seal(kv, rc);
         q->n_cached += rows.size();
         q->has_pending = false; q->pending = -1;
         fed += rows.size();
@@ -857,6 +884,7 @@ ld_status ld_decode_run(ld_kv *kv, const ld_seq *seqs, int32_t n_seqs, int32_t m
                         void *user, int32_t *steps_done) {
     if (steps_done) *steps_done = 0;
     if (!kv || !seqs || n_seqs <= 0 || max_steps < 0) return fail(LD_E_INVAL, "ld_decode_run: bad argument");
+    LD_REFUSE_BROKEN(kv, "ld_decode_run");
     if (n_seqs > kv->max_seqs || n_seqs > kv->max_tokens) return fail(LD_E_RANGE, "ld_decode_run: too many sequences in one step");
     std::vector<char> seen(kv->max_seqs, 0);
     for (int i = 0; i < n_seqs; i++) {
@@ -913,17 +941,20 @@ ld_status ld_decode_run(ld_kv *kv, const ld_seq *seqs, int32_t n_seqs, int32_t m
     // With per-kernel timing on, the events of a pass are read after it: no step is prepared ahead.
     const int depth = kv->prof_on ? 1 : 2;
     rc = prepare(0);
-    if (rc) return rc;
+    if (rc) return seal(kv, rc);
     enq = 1;
     for (;;) {
         if (!end && enq < max_steps && enq - done < depth) {
             rc = prepare(enq);
             if (rc == LD_OK) enq++;
             else if (rc == LD_E_NOMEM || rc == LD_E_RANGE) end = true;   // the steps in flight are still delivered
-            else { (void)hipStreamSynchronize(st); return rc; }
+            else { (void)hipStreamSynchronize(st); return seal(kv, rc); }
         }
         if (done == enq) break;
-        LD_HIP_TRY(hipEventSynchronize(kv->step_ev[done & 1]));
+        if (hipEventSynchronize(kv->step_ev[done & 1]) != hipSuccess) {
+            kv->broken = true;
+            return fail(LD_E_HIP, "ld_decode_run: waiting for a step failed");
+        }
         if (kv->prof_on) {
             if (kv->timer.failed) return fail(LD_E_HIP, "profiling: hipEventCreate failed");
             for (size_t i = 0; i < kv->timer.cat.size(); i++) {

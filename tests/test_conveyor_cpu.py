@@ -8,6 +8,7 @@ import pytest
 
 from oracle import latency_model as lm
 from paper_2406_00059_amd import conveyor as cv
+from fake_engine import FakeEngine
 
 
 def test_latency_model_bounds_and_best_case_curve():
@@ -56,8 +57,8 @@ def _requests(tool_s):
 
 @pytest.mark.parametrize("tool_s", [0.03, 0.12])
 def test_partial_execution_keeps_tokens_and_obeys_the_bounds(tool_s):
-    base = cv.serve(cv.FakeEngine(), _requests(tool_s), partial=False)
-    part = cv.serve(cv.FakeEngine(), _requests(tool_s), partial=True)
+    base = cv.serve(FakeEngine(), _requests(tool_s), partial=False)
+    part = cv.serve(FakeEngine(), _requests(tool_s), partial=True)
     # process start, pipe, polling granularity: forking is slow when the parent has large libraries mapped
     # (the whole suite in one process), so the start-up cost of a tool process is measured, not assumed
     t0 = time.perf_counter()
@@ -100,8 +101,8 @@ def test_retention_choice_thresholds():
 def test_retention_modes_do_not_change_the_output(retention):
     """Baseline mode with a long tool (every round waits): whatever happens to the cache during the wait,
     the tokens are those of the run that keeps it; every wait records what was done."""
-    ref = cv.serve(cv.FakeEngine(), _requests(0.05), partial=False)
-    eng = cv.FakeEngine()
+    ref = cv.serve(FakeEngine(), _requests(0.05), partial=False)
+    eng = FakeEngine()
     kw = {}
     if retention == "auto":   # 50 ms tools against a 2 x 1 ms copy and a 100 ms recompute -> swap
         kw = dict(predict_tool_s=lambda plugin: plugin.duration_s,
@@ -119,9 +120,33 @@ def test_shared_prompt_prefix_is_prefilled_once_and_changes_nothing():
         return [cv.Request(prompt=head + list(range(10 + k, 20 + k)),
                            rounds=[cv.Round(24, cv.SyntheticTool(0.02, [7, 8, 9], pieces_to_start=1)), cv.Round(8, None)])
                 for k in range(3)]
-    ref = cv.serve(cv.FakeEngine(), reqs())
-    eng = cv.FakeEngine()
+    ref = cv.serve(FakeEngine(), reqs())
+    eng = FakeEngine()
     got = cv.serve(eng, reqs(), shared_prefix=24)
     assert [r.tokens for r in ref] == [g.tokens for g in got] and not eng.hist
     with pytest.raises(AssertionError):
-        cv.serve(cv.FakeEngine(), reqs(), shared_prefix=30)        # the prompts differ from token 24 on
+        cv.serve(FakeEngine(), reqs(), shared_prefix=30)        # the prompts differ from token 24 on
+
+
+class _Stuck(cv.ToolPlugin):
+    def run(self, pieces):
+        time.sleep(60)
+        return [1]
+
+
+def test_a_tool_that_never_answers_is_killed_and_only_its_request_fails():
+    """Two requests; the first one's tool hangs.  With a time-out the tool's process is killed, that request ends
+    as failed with its sequence freed, and the other request completes with the tokens it has without the
+    neighbour."""
+    def reqs(stuck):
+        tool = _Stuck() if stuck else cv.SyntheticTool(0.01, [4, 5, 6])
+        return [cv.Request(prompt=[1, 2, 3], rounds=[cv.Round(6, tool), cv.Round(5)]),
+                cv.Request(prompt=[7, 8], rounds=[cv.Round(7, cv.SyntheticTool(0.02, [9])), cv.Round(4)])]
+    ref = cv.serve(FakeEngine(), reqs(False))
+    eng = FakeEngine()
+    t0 = time.perf_counter()
+    got = cv.serve(eng, reqs(True), tool_timeout_s=0.3)
+    assert time.perf_counter() - t0 < 5.0
+    assert got[0].failed and "time-out" in got[0].failed and len(got[0].tokens) == 6
+    assert got[1].failed is None and got[1].tokens == ref[1].tokens
+    assert eng.hist == {}                                   # every sequence was freed, the failed one's too

@@ -29,8 +29,8 @@ HBM_PEAK = 8.0e12          # bytes/s, MI355X HBM3E
 # 256 MiB copy (profiles/gate_up_gemv_hbm_traffic.md); valid only for the kernel source it was taken on.
 TRAFFIC_BYTES = 180_870_000
 TRAFFIC_KERNEL_MD5 = "0468ef4efdc5"
-ATTN_TRAFFIC_RATIO = 1.005
-ATTN_TRAFFIC_MD5 = "unset"
+ATTN_TRAFFIC_RATIO = 1.007
+ATTN_TRAFFIC_MD5 = "433aa490506e"
 ROUND_TOKENS = 256         # tokens emitted per round (1 by the preceding prefill + 255 decode steps)
 CHUNK = 256
 
@@ -62,6 +62,9 @@ def parse():
                          "matrices, plus the calibration copy: the short program the rocprofv3 --pmc runs use")
     ap.add_argument("--attention-probe", action="store_true",
                     help="launch only the batch-32 decode attention (+ 256 MiB copies), for the HBM-traffic counter runs")
+    ap.add_argument("--skinny-probe", action="store_true",
+                    help="launch only the 32-row gate/up projection (small-batch matrix-core kernel + its reduction) and "
+                         "256 MiB copies, for the HBM-traffic counter runs")
     ap.add_argument("--mfma-probe", action="store_true",
                     help="launch only the prefill-side matrix-core kernels (layer GEMMs at 1056 and 2048 rows, chunk-prefill "
                          "attention of a mixed step), for the MFMA counter runs")
@@ -526,6 +529,24 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"probe": "k_gemv1 gate/up 7B batch 1", "launches": 16,
                           "algorithmic_bytes_per_launch": 2 * f * d * 2 + d * 8 + f * 4,
+                          "copy_bytes_each_way": 256 << 20, "copies": 4}))
+        return
+    if args.skinny_probe:
+        d, f = shape.d_model, shape.d_ffn
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        b = torch.empty_like(a)
+        ws = [torch.empty(2 * f, d, device="cuda").normal_(0, 0.02).bfloat16() for _ in range(4)]
+        g = torch.ones(d, device="cuda"); x = torch.randn(32, d, device="cuda"); y = torch.empty(32, f, device="cuda")
+        scratch = torch.empty(ld.ldk_linear_scratch_bytes(32, f, d, ld.LDK_SWIGLU), dtype=torch.uint8, device="cuda")
+        for i in range(16):
+            ld.ldk_linear(ws[i % 4], x, y, ld.LDK_SWIGLU, g=g, eps=shape.rms_eps, scratch=scratch)
+            if i % 4 == 0:
+                b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "gate/up projection, 7B shape, 32 rows (k_norm_split + k_gemm_skinny + k_splitk_reduce)",
+                          "launches": 16, "weight_bytes_per_launch": 2 * f * d * 2,
+                          "algorithmic_bytes_per_launch": 2 * f * d * 2 + 32 * d * 4 + 32 * f * 4,
+                          "partial_sum_bytes_written_per_launch": (d // 512) * 32 * 2 * f * 4,
                           "copy_bytes_each_way": 256 << 20, "copies": 4}))
         return
     if args.mfma_probe:

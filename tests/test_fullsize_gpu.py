@@ -354,16 +354,19 @@ def test_13b_width_batch64_and_2048_row_chunk_over_a_200GB_sized_pool():
 
 @pytest.mark.parametrize("base", [LLAMA7B, MISTRAL7B], ids=["mha", "gqa-band"])
 def test_7b_width_batch32_continuous_batching_with_mixed_step(base):
-    """The batch-32 workload at 7B layer width and reduced depth (2 layers): contexts uniform in
-    [512, 8192] (injected), pure decode steps and a mixed step in which 4 sequences get a 256-token
-    observation chunk (257 rows with the pending token) prefilled in the same pass.  All 32 sequences'
-    tokens every step; logits within 2e-2.  Second case: 32 query heads on 8 KV heads and an attention
-    band of 4096 positions (about half of the contexts are longer than the band)."""
+    """The batch-32 workload at 7B layer width and reduced depth (2 layers), all 32 sequences against the oracle:
+    contexts uniform in [512, 8192] (injected), pure decode steps and mixed steps in which 4 sequences get a
+    256-token observation chunk (257 rows with the pending token) prefilled in the same pass.  First case: the
+    first 32 steps of the workload, mixed steps at 16 and 32.  Second case: 32 query heads on 8 KV heads and
+    an attention band of 4096 positions (about half of the contexts are longer than the band), 6 steps with
+    the mixed step at 4 and the sliding-window memory trimmed before steps 3 and 4.  Tokens of every
+    sequence at every step (near-ties by the rule of helpers.NearTies); logits within 2e-2."""
     shape = base.with_layers(2)
     seed = SEED_BASE + 3
     B = 32
+    n_steps, mixed_at = (32, (16, 32)) if not shape.window else (6, (4,))
     lens = gen.randint(seed, 1, 512, 8192, B).tolist()
-    extra = 8 + 257
+    extra = n_steps + 3 + 257 * len(mixed_at)
     nblk = sum((n + extra + 15) // 16 for n in lens) + 8
     P = Pair(shape, seed, n_blocks=nblk, max_tokens=(B - 4) + 4 * 257, max_seqs=B, max_blocks=(8192 + extra) // 16 + 2,
              gen_device="cuda")
@@ -371,8 +374,8 @@ def test_7b_width_batch32_continuous_batching_with_mixed_step(base):
     pend = gen.randint(seed, 2, 0, shape.vocab - 1, B).tolist()
     for b, s in enumerate(seqs):
         inject_history(P, s, lens[b], seed, 1000 + b, pending=pend[b])
-    errs = []
-    for step in range(1, 7):
+    errs, ties = [], NearTies()
+    for step in range(1, n_steps + 1):
         sink = Tokens()
         if step in (3, 4) and shape.window:
             # sliding-window memory: every sequence gives up the blocks below its band, before a decode step and
@@ -385,10 +388,10 @@ def test_7b_width_batch32_continuous_batching_with_mixed_step(base):
             assert ld.ld_kv_free_blocks(P.gkv.h) == P.okv.free_blocks()
             if step == 3:       # two steps in: each sequence holds n + 2 positions
                 assert n_rel == sum(max(0, n + 2 - shape.window + 1) // 16 for n in lens) > 1000
-        if step == 4:
+        if step in mixed_at:
             pick = gen.permutation(seed, 3000 + step, B)[:4].tolist()
             pf = [seqs[i] for i in pick]; dec = [s for s in seqs if s not in pf]
-            obs = [prompt(seed, 4000 + i, 256, shape.vocab) for i in range(4)]
+            obs = [prompt(seed, 4000 + 8 * step + i, 256, shape.vocab) for i in range(4)]
             rc, lg = ld.ld_step_mixed(P.gkv.h, dec, pf, obs, callback=sink, logits_vocab=P.V)
             order = dec + pf
             ref = [P.okv.decode(s) for s in dec] + [P.okv.prefill(s, o) for s, o in zip(pf, obs)]
@@ -399,9 +402,11 @@ def test_7b_width_batch32_continuous_batching_with_mixed_step(base):
         assert [q for q, _, _ in sink.log] == order
         for i, (rc_o, t_o, lg_o) in enumerate(ref):
             errs.append(rel_err(lg[i], lg_o))
-            assert sink.log[i][1] == t_o, (step, i, errs[-1])
-    print("batch 32: max logits rel err", max(errs))
-    assert max(errs) <= 2e-2
+            if sink.log[i][1] != t_o:
+                ties.check((step, order[i]), lg_o, t_o, sink.log[i][1], ties.measured(lg[i], lg_o))
+                ld.ld_kv_assume(P.gkv.h, order[i], 0, t_o)
+    print(f"batch 32, {n_steps} steps: max logits rel err", max(errs), "near-ties", ties.cases)
+    assert max(errs) <= 2e-2 and len(ties.cases) <= 2
     # three more steps the way the benchmark issues them (one multi-step run over all 32 sequences)
     ref = []
     for _ in range(3):

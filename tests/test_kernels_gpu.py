@@ -250,14 +250,14 @@ def test_paged_attention_grouped_band_serving_shape_sampled():
     assert err <= 2e-5, err
 
 
-def test_paged_attention_microbench_shape_sampled():
-    """Batch 16, 32 heads x 128, contexts uniform in [256, 4096], permuted block table: every
-    (sequence, head) output of 4 sampled sequences against the oracle."""
+def test_paged_attention_microbench_shape():
+    """Batch 16, 32 heads x 128, contexts uniform in [256, 4096] (the benchmark's draw), permuted block table:
+    every (sequence, head) output against the oracle."""
     lens = gen.randint(20240601, 1, 256, 4096, 16).tolist()
     table, pool, q = _attention_case(20240601, lens, 32, 32, 128, "bf16")
     got = _run_attention(table, pool, q, lens, 32, 32, 128)
     assert np.isfinite(got).all()
-    rows = [0, 5, int(np.argmax(lens)), int(np.argmin(lens))]
+    rows = list(range(16))
     ref = _oracle_attention(table, pool, q, lens, 32, 128, rows=rows)
     err = np.max(np.abs(got[rows] - ref)) / np.abs(ref).max()
     assert err <= 2e-5, err

@@ -397,7 +397,18 @@ __global__ __launch_bounds__(1024) void k_argmax(const float *__restrict__ logit
     const float *row = logits + (int64_t)r * V;
     float bv = -INFINITY;
     int bi = 0x7fffffff;
-    for (int i = threadIdx.x; i < V; i += 1024) {
+    // eight loads in flight per thread, compared in ascending index order (a strict "greater" keeps the lowest
+    // index among equal values)
+    int i = threadIdx.x;
+    for (; i + 7 * 1024 < V; i += 8 * 1024) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) v[u] = row[i + u * 1024];
+#pragma unroll
+        for (int u = 0; u < 8; u++)
+            if (v[u] > bv || bi == 0x7fffffff) { bv = v[u]; bi = i + u * 1024; }
+    }
+    for (; i < V; i += 1024) {
         const float v = row[i];
         if (v > bv || bi == 0x7fffffff) { bv = v; bi = i; }
     }

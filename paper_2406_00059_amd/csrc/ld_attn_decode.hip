@@ -85,12 +85,19 @@ __global__ __launch_bounds__(256, 2) void k_attn_decode_grouped(const float *__r
 
     // One step = blocks (b, b+1).  kf[blk][j]: key operand of k-step j; vf[nt][blk]: 4 positions of a dimension.
     struct Step { u32x4 kf[2][4]; u32x2 vf[8][2]; };
-    // a second block past the chunk is read again from the first one and masked out in compute()
+    // The physical ids of all blocks this wave will walk (steps n = 0, 1, ...: blocks b_begin + 2 wave + 8 n and the
+    // one after it; at most 16 of a 64-block chunk) are fetched at once, lane 2 n + blk holding one: a table lookup
+    // inside the walk would be a load younger than the keys and values already requested for the step ahead, and
+    // waiting for it (loads return in order) would wait for all of those first.  A second block past the chunk
+    // is read again from the chunk's last one and masked out in compute().
+    const int my_blk = lane < 16 ? trow[min(b_begin + 2 * wave + 8 * (lane >> 1) + (lane & 1), b_end - 1)] : 0;
+    auto block_of = [&](int b, int blk) {
+        return (int64_t)__builtin_amdgcn_readlane(my_blk, ((b - b_begin - 2 * wave) >> 2) + blk);
+    };
     auto load_k = [&](Step &s, int b) {
 #pragma unroll
         for (int blk = 0; blk < 2; blk++) {
-            const bf16_t *kp = pool + (int64_t)trow[min(b + blk, b_end - 1)] * block_stride +
-                               kv_k_offset(HD, kvh, l16, 8 * rg);
+            const bf16_t *kp = pool + block_of(b, blk) * block_stride + kv_k_offset(HD, kvh, l16, 8 * rg);
 #pragma unroll
             for (int j = 0; j < 4; j++) s.kf[blk][j] = load_stream16(kp + 32 * j);
         }
@@ -98,8 +105,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_decode_grouped(const float *__r
     auto load_v = [&](Step &s, int b) {
 #pragma unroll
         for (int blk = 0; blk < 2; blk++) {
-            const bf16_t *vp = pool + (int64_t)trow[min(b + blk, b_end - 1)] * block_stride +
-                               kv_v_offset(Hkv, HD, kvh, 4 * rg, l16);
+            const bf16_t *vp = pool + block_of(b, blk) * block_stride + kv_v_offset(Hkv, HD, kvh, 4 * rg, l16);
 #pragma unroll
             for (int nt = 0; nt < 8; nt++)
                 s.vf[nt][blk] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(vp + nt * 16 * 16));
@@ -187,17 +193,26 @@ __global__ __launch_bounds__(256, 2) void k_attn_decode_grouped(const float *__r
 
     // steps of this wave: blocks b_begin + 2 (wave + 4 n).  Two register sets: the loads of the step after
     // next are issued before the next step is multiplied, so 16 .. 32 KB per wave are in flight all the time.
+    // The steady state requests unconditionally (a request under a condition makes the wait before a product
+    // cover every load in flight, the step ahead included); the last one or two steps are peeled off.
     {
         Step sa, sb;
         int b = b_begin + 2 * wave;
-        if (b < b_end) { load_k(sa, b); load_v(sa, b); }
-        for (; b < b_end; b += 16) {
-            const bool second = b + 8 < b_end;
-            if (second) { load_k(sb, b + 8); load_v(sb, b + 8); }
-            compute(sa, b);
-            if (second) {
-                if (b + 16 < b_end) { load_k(sa, b + 16); load_v(sa, b + 16); }
+        if (b < b_end) {
+            load_k(sa, b); load_v(sa, b);
+            while (b + 16 < b_end) {
+                load_k(sb, b + 8); load_v(sb, b + 8);
+                compute(sa, b);
+                load_k(sa, b + 16); load_v(sa, b + 16);
                 compute(sb, b + 8);
+                b += 16;
+            }
+            if (b + 8 < b_end) {
+                load_k(sb, b + 8); load_v(sb, b + 8);
+                compute(sa, b);
+                compute(sb, b + 8);
+            } else {
+                compute(sa, b);
             }
         }
     }

@@ -242,8 +242,13 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
         for (int v = 0; v < NV; v++) acc[g][v] = 0.f;
     }
 
-    for (int b = b_begin + wave; b < b_end; b += 4) {
-        const KVT *blk = pool + (int64_t)trow[b] * block_stride;
+    // The physical ids of this wave's blocks (b_begin + wave + 4 i; at most 16 of a chunk) are fetched at once,
+    // one per lane: a lookup inside the walk would put a dependent memory round trip in front of every block's loads.
+    const int n_it = (b_end - b_begin - wave + 3) >> 2;
+    const int my_blk = lane < n_it ? trow[b_begin + wave + 4 * lane] : 0;
+    for (int it = 0; it < n_it; it++) {
+        const int b = b_begin + wave + 4 * it;
+        const KVT *blk = pool + (int64_t)__builtin_amdgcn_readlane(my_blk, it) * block_stride;
         // keys: row of slot NI*group + i, elements sub*8 .. +8; a load instruction reads NG rows of 16*LPT bytes
         const KVT *kb = blk + kv_k_offset(HD, kvh, NI * group, sub * 8);
         // values (transposed): dimension sub + LPT*v, slots NI*group .. +NI; a load instruction reads

@@ -94,12 +94,26 @@ __global__ __launch_bounds__(256, 2) void k_attn_decode_grouped(const float *__r
     auto block_of = [&](int b, int blk) {
         return (int64_t)__builtin_amdgcn_readlane(my_blk, ((b - b_begin - 2 * wave) >> 2) + blk);
     };
+    // Keys are fetched as they lie in memory (a block's 16 key rows of this KV head are 4 KB in a row: load j of a
+    // block covers slots 4 j .. 4 j + 3, lane l the 16 bytes at 1024 j + 16 l, so that every 128-byte line belongs to
+    // one instruction) and take the A-operand layout (lane = slot) through 4 KB of LDS private to the wave in
+    // compute(): piece p (8 dims) of slot s sits in slot (p ^ s) of its 256-byte row.
+    __shared__ __attribute__((aligned(16))) char sm_k[4][4096];
+    char *tk = sm_k[wave];
+    char *tk_st[4];
+    const char *tk_ld[4];
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        const int sl = 4 * j + rg;
+        tk_st[j] = tk + sl * 256 + ((l16 ^ sl) & 15) * 16;
+        tk_ld[j] = tk + l16 * 256 + (((4 * j + rg) ^ l16) & 15) * 16;
+    }
     auto load_k = [&](Step &s, int b) {
 #pragma unroll
         for (int blk = 0; blk < 2; blk++) {
-            const bf16_t *kp = pool + block_of(b, blk) * block_stride + kv_k_offset(HD, kvh, l16, 8 * rg);
+            const bf16_t *kp = pool + block_of(b, blk) * block_stride + kv_k_offset(HD, kvh, 0, 0) + 8 * lane;
 #pragma unroll
-            for (int j = 0; j < 4; j++) s.kf[blk][j] = load_stream16(kp + 32 * j);
+            for (int j = 0; j < 4; j++) s.kf[blk][j] = load_stream16(kp + 512 * j);
         }
     };
     auto load_v = [&](Step &s, int b) {
@@ -129,9 +143,17 @@ __global__ __launch_bounds__(256, 2) void k_attn_decode_grouped(const float *__r
 #pragma unroll
         for (int blk = 0; blk < 2; blk++) {
             st[blk] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            // the block's keys through the wave's LDS rows (a wave's LDS operations execute in order)
+#pragma unroll
+            for (int j = 0; j < 4; j++) *reinterpret_cast<u32x4 *>(tk_st[j]) = s.kf[blk][j];
+            __builtin_amdgcn_wave_barrier();
+            u32x4 kt[4];
+#pragma unroll
+            for (int j = 0; j < 4; j++) kt[j] = *reinterpret_cast<const u32x4 *>(tk_ld[j]);
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int j = 0; j < 4; j++) {
-                const bf16x8 ka = __builtin_bit_cast(bf16x8, s.kf[blk][j]);
+                const bf16x8 ka = __builtin_bit_cast(bf16x8, kt[j]);
                 st[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qh[j], st[blk], 0, 0, 0);
                 st[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, ql[j], st[blk], 0, 0, 0);
             }

@@ -75,9 +75,12 @@ def parse():
 MFMA_PEAK = 2.5e15         # flop/s, bf16 dense
 
 
-def ld_gemm_terms():
-    """bf16 terms per float32 activation on the matrix cores in multi-row passes: high + low part."""
-    return 2
+def ld_gemm_terms(rows):
+    """Matrix-core terms per float32 activation in a pass of `rows` rows: two bf16 terms (high + low part); one
+    fp16 term in passes of at least LD_GEMM_F16_MIN_ROWS (512) rows unless LD_GEMM_F16=0 (the few rows past the
+    last full 256-row tile, which keep both terms, are not counted apart)."""
+    on = os.environ.get("LD_GEMM_F16", "1") != "0"
+    return 1 if on and rows >= int(os.environ.get("LD_GEMM_F16_MIN_ROWS", "512")) else 2
 
 
 def _source_md5(name):
@@ -357,10 +360,11 @@ def run_batch32(args, ld, torch, shape, model):
         "sum_visible_context": int(sum_ctx),
         "kernel_ms_mixed_step": {k: round(v[0], 3) for k, v in prof_mixed.items()},
         # MFMA fractions: first on the method's flops (2 * rows * weight elements), then on what the matrix cores
-        # execute when the float32 activations go in as two bf16 terms (twice that)
+        # execute (twice that when the float32 activations go in as two bf16 terms, once in the fp16 form)
+        "mixed_step_gemm_terms": ld_gemm_terms(rows_mixed),
         "mixed_step_gemm_TFLOPs": round(gemm_nominal / (gemm_ms_mixed * 1e-3) / 1e12, 1),
         "mixed_step_gemm_mfma_frac": round(gemm_nominal / (gemm_ms_mixed * 1e-3) / MFMA_PEAK, 4),
-        "mixed_step_gemm_mfma_frac_executed": round(ld_gemm_terms() * gemm_nominal / (gemm_ms_mixed * 1e-3) / MFMA_PEAK, 4),
+        "mixed_step_gemm_mfma_frac_executed": round(ld_gemm_terms(rows_mixed) * gemm_nominal / (gemm_ms_mixed * 1e-3) / MFMA_PEAK, 4),
         "decode_gemm_weight_GBps": round(Wb / (sum(prof[c][0] for c in ("qkv", "wo", "gate_up", "down", "lm_head")) / 4 * 1e-3) / 1e9, 1),
         "roofline": {"bound": "hbm", "kernel": "decode attention (k_attn_partial / k_attn_decode_grouped + k_attn_merge), one layer, 32 rows",
                      "achieved": round(att_bytes / att_avg / 1e9, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
@@ -487,7 +491,8 @@ def run_13b(args, ld, torch):
         "attention_GBps_if_all_attention_time_were_decode": round(statistics.mean(kv_bytes) / (prof["attention"][0] * 1e-3) / 1e9, 1),
         "gemm_TFLOPs": round(gemm_flops / (gemm_ms * 1e-3) / 1e12, 1),
         "gemm_mfma_frac": round(gemm_flops / (gemm_ms * 1e-3) / MFMA_PEAK, 4),
-        "gemm_mfma_frac_executed": round(ld_gemm_terms() * gemm_flops / (gemm_ms * 1e-3) / MFMA_PEAK, 4),
+        "gemm_terms": ld_gemm_terms(B - 1 + chunk),
+        "gemm_mfma_frac_executed": round(ld_gemm_terms(B - 1 + chunk) * gemm_flops / (gemm_ms * 1e-3) / MFMA_PEAK, 4),
         "attention_ms_one_step": round(prof["attention"][0], 3),
         "steps_timed": steps, "n_layers": shape.n_layers,
     }

@@ -27,6 +27,13 @@
  *    to reach the host, then runs the callbacks on the calling thread.
  *  - Matrices are row-major with the output index first ([n_out, n_in]), element type
  *    cfg.dtype.  RMSNorm gains are always float32.
+ *  - Arithmetic (bf16 models; the paper's section 4.1 fixes none): float32 between kernels and in every
+ *    accumulation; cached keys and values rounded to bf16.  The matrix products of a pass take the rows'
+ *    activations as two bf16 terms (16 significant bits), except in passes of 512 rows or more (long prefill
+ *    chunks, steps that mix decode rows with chunks), whose big-tile products take them rounded to fp16 (11
+ *    bits) as long as every value of the pass and of the layer matrices lies within the fp16 range (+-65504);
+ *    a pass that meets a larger value is repeated with two terms.  LD_GEMM_F16=0 in the environment keeps two
+ *    terms everywhere.
  *  - Sequence state: n_cached tokens have keys/values in the pool; `pending` is a token
  *    that was emitted but not fed yet (none right after ld_kv_alloc).
  */

@@ -48,6 +48,18 @@ ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *
                      int32_t N, int32_t K, int32_t epilogue, float *y, void *scratch, size_t scratch_bytes,
                      void *stream);
 
+/* ldk_linear on a bf16 matrix in the form the engine uses for the rows of long prefill chunks (rows that reach
+ * later tokens only through cached keys and values; the paper's section 4.1 fixes no precision): where more than 64
+ * rows run on the big-tile matrix-core kernel, the activations enter the product rounded to fp16 (11 significant
+ * bits) in one term instead of the two bf16 terms (16 bits), and the bf16 matrix entries are widened to fp16 on the
+ * way to the matrix cores, which is exact for 2^-14 <= |w| <= 65504.  Other row counts and shapes: exactly
+ * ldk_linear.  overflow (device memory, 4 bytes, the caller clears it) is set to 1 when the matrix or an
+ * activation holds a value beyond +-65504 or not a number; y is then not to be used (the engine repeats such a
+ * pass with ldk_linear's arithmetic).  scratch: ldk_linear_scratch_bytes(...) bytes. */
+ld_status ldk_linear_f16(const void *W, const float *x, const float *g, float eps, int32_t T, int32_t N, int32_t K,
+                         int32_t epilogue, float *y, void *scratch, size_t scratch_bytes, int32_t *overflow,
+                         void *stream);
+
 /* cos_sin[t, i] = (cos, sin)(pos[t] * rope_base^(-2i/hd)) for i < hd/2, as float32 pairs; the
  * angle is formed in float64 so that large positions lose no accuracy.  hd is 64 or 128. */
 ld_status ldk_rope_table(const int32_t *pos, int32_t T, int32_t hd, float rope_base, float *cos_sin, void *stream);

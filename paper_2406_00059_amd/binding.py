@@ -22,7 +22,7 @@ __all__ = [
     "ld_token_cb", "ld_model_create", "ld_model_destroy", "ld_kv_bytes", "ld_workspace_bytes", "ld_kv_create",
     "ld_kv_destroy", "ld_kv_alloc", "ld_kv_map", "ld_kv_free", "ld_kv_block_table", "ld_kv_len",
     "ld_kv_free_blocks", "ld_kv_assume", "ld_kv_swap_bytes", "ld_kv_swap_out", "ld_kv_swap_in", "ld_kv_fork", "ld_kv_trim", "ld_kv_set_sampling", "ld_prefill", "ld_decode_step", "ld_decode_run", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
-    "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
+    "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_f16", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
     "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_static_scratch_bytes", "ldk_paged_attention_static",
     "ldk_prefill_attention_scratch_bytes",
     "ldk_prefill_attention", "ldk_argmax", "ldk_sample", "Model", "KV",
@@ -95,6 +95,8 @@ _SIGS = {
     "ldk_linear_scratch_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "ldk_linear": (C.c_int, [_vp, C.c_int32, _vp, _vp, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp,
                              C.c_size_t, _vp]),
+    "ldk_linear_f16": (C.c_int, [_vp, _vp, _vp, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp,
+                                C.c_size_t, _vp, _vp]),
     "ldk_rope_table": (C.c_int, [_vp, C.c_int32, C.c_int32, C.c_float, _vp, _vp]),
     "ldk_rope_kv_write": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_int32, _vp, C.c_int32, C.c_int32, C.c_int32,
                                     C.c_int32, C.c_int32, _vp]),
@@ -361,6 +363,13 @@ def ldk_linear(W, x, y, epilogue=LDK_STORE, g=None, eps=0.0, scratch=None, strea
     N = y.shape[1]
     _check(lib().ldk_linear(_ptr(W), _dt(W.dtype), _ptr(x), _ptr(g), eps, T, N, K, epilogue, _ptr(y),
                             _ptr(scratch), _nbytes(scratch), _stream(stream)))
+
+
+def ldk_linear_f16(W, x, y, overflow, epilogue=LDK_STORE, g=None, eps=0.0, scratch=None, stream=None):
+    T, K = x.shape
+    N = y.shape[1]
+    _check(lib().ldk_linear_f16(_ptr(W), _ptr(x), _ptr(g), eps, T, N, K, epilogue, _ptr(y), _ptr(scratch),
+                                _nbytes(scratch), _ptr(overflow), _stream(stream)))
 
 
 def ldk_rope_table(pos, hd, rope_base, cos_sin, stream=None):

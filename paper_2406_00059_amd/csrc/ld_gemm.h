@@ -29,9 +29,19 @@ void launch_norm_split(const float *x, const float *g, float eps, int T, int K, 
 // With GEMM_STORE and rope != nullptr (the q-k-v projection; cos_sin, pos and seq_slot indexed by row): the kernel
 // that finishes y rotates the q heads in y and writes the rotated k heads and the v heads into the paged pool,
 // with the values the separate rotate-and-append pass would write (k and v are not stored to y).
+//
+// f16_flag != nullptr: the caller allows the rows of this pass to enter the product rounded to fp16 (11 significant
+// bits instead of the 16 of the two-term split) where that pays: more than 64 rows in the big-tile kernel
+// (gemm_f16_rows), i.e. the rows of prefill chunks; the rows of the split image that take this form are overwritten
+// with their fp16 values.  The caller has made sure that the matrix holds nothing beyond the fp16 range
+// (launch_weight_range_check); *f16_flag (device memory) is set to 1 when an activation does not fit, and the
+// results of the pass are then to be thrown away and the pass repeated without the flag.
 struct GemmNext { const float *g; float eps; uint16_t *xs; const RopeKvArgs *rope = nullptr; };
-void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s,
-                 const GemmNext *next = nullptr);
+void launch_gemm(const uint16_t *W, uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s,
+                 const GemmNext *next = nullptr, int *f16_flag = nullptr);
+bool gemm_f16_rows(int T, int N, int K, int epi);
+// *flag (device memory) = 1 if the bf16 matrix W (n elements, a multiple of 8) holds a value beyond +-65504 or not a number.
+void launch_weight_range_check(const uint16_t *W, int64_t n, int *flag, hipStream_t s);
 
 // Skinny product alone (T <= 32 rows, K a multiple of 128): partial[z][t][row] for the skinny_slabs(K)
 // 512-wide K slabs z; the caller adds the slabs in order.

@@ -29,8 +29,22 @@ using namespace ldd;
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) __fp16 fp16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // native 16-byte vector (keeps arrays of it in registers)
+
+constexpr float F16_LIMIT = 65504.f;   // largest finite fp16
+
+// Eight bf16 numbers as fp16: exact where fp16 can hold the value (8 significant bits fit into 11; truncation
+// only below 2^-14, where a bf16 weight is lost in the sums anyway).
+__device__ __forceinline__ f16x8 bf16x8_to_f16x8(const __attribute__((ext_vector_type(4))) uint32_t &w) {
+    uint32_t h[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+        h[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w[i] << 16), __uint_as_float(w[i] & 0xffff0000u)));
+    return __builtin_bit_cast(f16x8, (__attribute__((ext_vector_type(4))) uint32_t){h[0], h[1], h[2], h[3]});
+}
 
 constexpr int KC = 128;          // K granularity the launcher requires (largest chunk any variant stages)
 constexpr int XPAD = 8;          // bf16 elements of row padding in LDS
@@ -91,6 +105,39 @@ __global__ __launch_bounds__(256) void k_norm_split(const float *__restrict__ x,
 
 // TT: token tiles of 32 rows per workgroup.  WC: 32-column tiles per wave.  KCH: K chunk staged in LDS.
 // A wave multiplies TT x WF accumulator tiles per k-step, WF = WC (x 2 for SwiGLU: gate and up rows).
+// The (hi, lo) images of n8 * 8 activations become one fp16 image in place of the high one (hi + lo is exact in
+// float32; one rounding to fp16).  *flag is set when a value does not fit into fp16.
+__global__ __launch_bounds__(256) void k_split_to_f16(bf16_t *__restrict__ hi, const bf16_t *__restrict__ lo, int64_t n8,
+                                                      int *__restrict__ flag) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n8) return;
+    const u32x4 h = *reinterpret_cast<const u32x4 *>(hi + i * 8), l = *reinterpret_cast<const u32x4 *>(lo + i * 8);
+    uint32_t o[4];
+    bool big = false;
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        const float a = __uint_as_float(h[e] << 16) + __uint_as_float(l[e] << 16);
+        const float b = __uint_as_float(h[e] & 0xffff0000u) + __uint_as_float(l[e] & 0xffff0000u);
+        big = big || !(fabsf(a) <= F16_LIMIT) || !(fabsf(b) <= F16_LIMIT);
+        const _Float16 ha = (_Float16)a, hb = (_Float16)b;
+        o[e] = (uint32_t)__builtin_bit_cast(uint16_t, ha) | ((uint32_t)__builtin_bit_cast(uint16_t, hb) << 16);
+    }
+    *reinterpret_cast<u32x4 *>(hi + i * 8) = (u32x4){o[0], o[1], o[2], o[3]};
+    if (big) *flag = 1;
+}
+
+// *flag is set when a bf16 matrix holds a value that fp16 cannot (beyond +-65504, or not a number).
+__global__ __launch_bounds__(256) void k_weight_range(const bf16_t *__restrict__ w, int64_t n8, int *__restrict__ flag) {
+    bool big = false;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (int64_t)gridDim.x * 256) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(w + i * 8));
+#pragma unroll
+        for (int e = 0; e < 4; e++)
+            big = big || !(fabsf(__uint_as_float(v[e] << 16)) <= F16_LIMIT) || !(fabsf(__uint_as_float(v[e] & 0xffff0000u)) <= F16_LIMIT);
+    }
+    if (big) *flag = 1;
+}
+
 template <int TT, int WC, int KCH, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
                                                    const bf16_t *__restrict__ xlo, int T, int N, int K,
@@ -543,7 +590,12 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_big(const bf16_t *__restrict_
 // 4 x 2 waves of 64 x 128, 128 x 256 as 2 x 4 waves of 64 x 64 (measured against four waves of 64 x 128 on
 // the same tile: layer GEMMs at 128 - 512 rows 4 - 7 % faster, the full-grid rate 410 -> 440 TFLOP/s; sixteen
 // waves of 64 x 64 on the 256 x 256 tile fit in 109 registers and change nothing).
-template <int WM, int BN, int S, int EPI, int WN>
+//
+// F16 (rows that nobody reads at full precision, see launch_gemm): one operand image instead of two, the activations
+// rounded to fp16 (11 significant bits; xhi then points at a [T, K] fp16 matrix), the bf16 weights turned into
+// fp16 on their way from LDS to the matrix cores (exact for 2^-14 <= |w| < 65520, which the launcher has checked
+// on the whole matrix): half the matrix-core work and two thirds of the operand traffic of the two-term form.
+template <int WM, int BN, int S, int EPI, int WN, bool F16>
 __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
                                                        const bf16_t *__restrict__ xlo, int T, int N, int K,
                                                        float *__restrict__ y, int n_ttiles, int ks,
@@ -555,7 +607,9 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
     constexpr int WCOLS = BN / WN;                // W rows of the tile that one wave column multiplies
     constexpr int WCT = WCOLS / 32;               // 32-column accumulator tiles per wave
     constexpr int NOUT = SWI ? BN / 2 : BN;       // output columns per workgroup
-    constexpr int ROWS = 2 * BM + BN;             // rows of a stage: X hi, X lo, W
+    constexpr int TERMS = F16 ? 1 : 2;
+    constexpr int XR = TERMS * BM;                // X rows of a stage: hi and lo images (one fp16 image)
+    constexpr int ROWS = XR + BN;                 // rows of a stage: X hi, X lo, W
     constexpr int STAGE = ROWS * 64;              // bytes
     constexpr int P = ROWS / 16 / NW;             // copy instructions per wave per chunk
     static_assert(ROWS % (16 * NW) == 0, "rows must split evenly over the waves");
@@ -578,11 +632,11 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
         const int slot = lane & 3;
         const int seg = slot ^ ((vr >> 2) & 3);
         const bf16_t *rowp;
-        if (vr < 2 * BM) {
+        if (vr < XR) {
             const int r = vr % BM;
             rowp = (vr < BM ? xhi : xlo) + (int64_t)min(t0 + r, T - 1) * K;
         } else {
-            const int wr = vr - 2 * BM;
+            const int wr = vr - XR;
             int grow;
             if (SWI) {   // local rows of a wave column: gate tiles, then the up tiles of the same columns
                 const int wcol = wr / WCOLS, within = wr % WCOLS;
@@ -611,33 +665,45 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
 #pragma unroll
             for (int i = 0; i < 16; i++) acc[tt][wc][i] = 0.f;
 
-    struct Frags { bf16x8 a[2][2], bw[WCT]; };
+    struct Frags { u32x4 a[TERMS][2], bw[WCT]; };
     auto load_frags = [&](Frags &f, int st, int kstep) {
         const char *base = lds + st * STAGE;
         const int seg = kstep * 2 + half;
 #pragma unroll
-        for (int part = 0; part < 2; part++)
+        for (int part = 0; part < TERMS; part++)
 #pragma unroll
             for (int tt = 0; tt < 2; tt++) {
                 const int r = wm * 64 + tt * 32 + l32;       // BM is a multiple of 16: (r >> 2) & 3 is the stage row's
-                f.a[part][tt] = __builtin_bit_cast(
-                    bf16x8, *reinterpret_cast<const u32x4 *>(base + (part * BM + r) * 64 + ((seg ^ ((r >> 2) & 3)) * 16)));
+                f.a[part][tt] = *reinterpret_cast<const u32x4 *>(base + (part * BM + r) * 64 + ((seg ^ ((r >> 2) & 3)) * 16));
             }
 #pragma unroll
         for (int wc = 0; wc < WCT; wc++) {
             const int r = wn * WCOLS + wc * 32 + l32;
-            f.bw[wc] = __builtin_bit_cast(
-                bf16x8, *reinterpret_cast<const u32x4 *>(base + (2 * BM + r) * 64 + ((seg ^ ((r >> 2) & 3)) * 16)));
+            f.bw[wc] = *reinterpret_cast<const u32x4 *>(base + (XR + r) * 64 + ((seg ^ ((r >> 2) & 3)) * 16));
         }
     };
     auto mfmas = [&](const Frags &f) {
+        if constexpr (F16) {
+            f16x8 wv[WCT];
 #pragma unroll
-        for (int part = 0; part < 2; part++)
+            for (int wc = 0; wc < WCT; wc++) wv[wc] = bf16x8_to_f16x8(f.bw[wc]);
 #pragma unroll
             for (int tt = 0; tt < 2; tt++)
 #pragma unroll
                 for (int wc = 0; wc < WCT; wc++)
-                    acc[tt][wc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[part][tt], f.bw[wc], acc[tt][wc], 0, 0, 0);
+                    acc[tt][wc] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, f.a[0][tt]), wv[wc],
+                                                                        acc[tt][wc], 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int part = 0; part < TERMS; part++)
+#pragma unroll
+                for (int tt = 0; tt < 2; tt++)
+#pragma unroll
+                    for (int wc = 0; wc < WCT; wc++)
+                        acc[tt][wc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[part][tt]),
+                                                                             __builtin_bit_cast(bf16x8, f.bw[wc]),
+                                                                             acc[tt][wc], 0, 0, 0);
+        }
     };
     // Wait until this wave's copies of the oldest outstanding chunk have landed; `younger` later chunks
     // (P copies each) may stay in flight.  The count is an immediate, so only the steady-state values are
@@ -666,9 +732,9 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
     // flight under the arithmetic of the half step before the one that needs them
     auto interleave = [&]() {
 #pragma unroll
-        for (int k = 0; k < 4 + WCT; k++) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // 2 MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+        for (int k = 0; k < 2 * TERMS + WCT; k++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, TERMS, 0);   // MFMAs (2 * TERMS * WCT per half step)
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // 1 LDS read (2 * TERMS + WCT per half step)
         }
     };
     for (int i = 0; i + 1 < n_chunks; i++) {      // every chunk but the last: the next one always exists
@@ -832,7 +898,8 @@ int env_int(const char *name, int dflt) {
 // the 128 x 128 tile, at half the rate each); the per-CU rates are the measured full-grid rates of the three
 // tiles; split-K adds the write and the ordered re-read of its partial sums.
 struct BigPlan { int wm, bn, n_ttiles, n_nblocks, ks; double est_us; int nb_a, ks_b; };   // nb_a > 0: two phases
-BigPlan plan_big(int T, int N, int K, int epi) {
+// f16: the single-term fp16 form (measured 0.69 of the two-term time on the layer shapes).
+BigPlan plan_big(int T, int N, int K, int epi, bool f16 = false) {
     const bool swi = epi == ld::GEMM_SWIGLU;
     struct Tile { int wm, bn; double tflops; };           // nominal (unsplit) TFLOP/s of a full grid
     static const Tile tiles[3] = {{4, 256, 520.0}, {2, 256, 440.0}, {2, 128, 300.0}};
@@ -850,7 +917,7 @@ BigPlan plan_big(int T, int N, int K, int epi) {
             if (f_wm && ks != std::min(f_ks, max_ks)) continue;
             const int64_t wgs = (int64_t)n_tt * n_nb * ks;
             const int64_t rounds = (wgs + 255) / 256;
-            const double wg_us = 2.0 * bm * tl.bn * (double)(K / ks) / (tl.tflops * 1e6 / 256.0);
+            const double wg_us = (f16 ? 0.69 : 1.0) * 2.0 * bm * tl.bn * (double)(K / ks) / (tl.tflops * 1e6 / 256.0);
             double t = rounds * wg_us;
             if (ks > 1) t += 3.0 + (double)T * N * (swi ? 2 : 1) * 4.0 * (2.0 * ks + 1.0) / 3.0e6;
             if (t < best_t) { best_t = t; best = {tl.wm, tl.bn, n_tt, n_nb, ks, t, 0, 0}; }
@@ -863,7 +930,7 @@ BigPlan plan_big(int T, int N, int K, int epi) {
         const int64_t n_all = (int64_t)n_tt * n_nb;
         if (two_phase && !f_wm && tl.wm == 4 && n_all > 256 && n_all < 512) {
             const int nb_a = (int)(n_all / 256 * 256 / n_tt), nb_b = n_nb - nb_a;
-            const double wg_us = 2.0 * bm * tl.bn * (double)K / (tl.tflops * 1e6 / 256.0);
+            const double wg_us = (f16 ? 0.69 : 1.0) * 2.0 * bm * tl.bn * (double)K / (tl.tflops * 1e6 / 256.0);
             const double t_a = (double)(((int64_t)nb_a * n_tt + 255) / 256) * wg_us;
             for (int ks = 2; ks <= max_ks && nb_a > 0 && nb_b > 0; ks++) {
                 const int64_t rounds_b = ((int64_t)nb_b * n_tt * ks + 255) / 256;
@@ -888,9 +955,9 @@ int skinny_max_rows() {
     return std::min(std::max(v, 32), 64);
 }
 
-int split_factor(int T, int N, int K, int epi) {
+int split_factor(int T, int N, int K, int epi, bool f16 = false) {
     if (T <= skinny_max_rows()) return (K + SL - 1) / SL;   // skinny kernel: one 512-wide slab per workgroup
-    if (T > 64) { const BigPlan p = plan_big(T, N, K, epi); return std::max(p.ks, p.ks_b); }
+    if (T > 64) { const BigPlan p = plan_big(T, N, K, epi, f16); return std::max(p.ks, p.ks_b); }
     const Shape sh = pick_shape(T, epi);
     const int n_ttiles = (T + sh.tt * 32 - 1) / (sh.tt * 32), n_nblocks = (N + 128 * sh.wc - 1) / (128 * sh.wc);
     const int wgs = n_ttiles * n_nblocks;
@@ -936,23 +1003,28 @@ size_t gemm_split_bytes(int T, int K) { return (((size_t)2 * T * K * sizeof(bf16
 // chunk beside 63 decode rows) are cut off and go through the small-batch kernels: the weights are streamed
 // once more, which costs less than a tile of padding.  Returns the number of such tail rows (0: no cut),
 // decided by the same cost model that picks the tile.
-int tail_rows(int T, int N, int K, int epi) {
+int tail_rows(int T, int N, int K, int epi, bool f16) {
     const int r = T % 256;
     static const int enabled = env_int("LD_GEMM_TAIL", 1);   // tuning knob: 0 keeps every row in the tiled kernel
     if (!enabled || T <= 256 || r == 0 || r > 64 || getenv("LD_GEMM_BIG")) return 0;
-    const double whole = plan_big(T, N, K, epi).est_us, main_part = plan_big(T - r, N, K, epi).est_us;
+    const double whole = plan_big(T, N, K, epi, f16).est_us, main_part = plan_big(T - r, N, K, epi, f16).est_us;
     const double tail = (double)N * (epi == GEMM_SWIGLU ? 2 : 1) * K * 2.0 / 4.0e6 + 12.0;   // ~4 TB/s + two launches
     return main_part + tail < whole ? r : 0;
 }
 
-static size_t partial_bytes(int T, int N, int K, int epi) {
-    const int ks = split_factor(T, N, K, epi);
+static size_t partial_bytes(int T, int N, int K, int epi, bool f16 = false) {
+    const int ks = split_factor(T, N, K, epi, f16);
     return (ks > 1 || T <= skinny_max_rows()) ? (size_t)ks * T * N * (epi == GEMM_SWIGLU ? 2 : 1) * sizeof(float) : 0;
 }
 
 size_t gemm_scratch_bytes(int T, int N, int K, int epi) {
-    const int r = tail_rows(T, N, K, epi);
-    const size_t part = r ? std::max(partial_bytes(T - r, N, K, epi), partial_bytes(r, N, K, epi)) : partial_bytes(T, N, K, epi);
+    const int r = tail_rows(T, N, K, epi, false);
+    size_t part = r ? std::max(partial_bytes(T - r, N, K, epi), partial_bytes(r, N, K, epi)) : partial_bytes(T, N, K, epi);
+    if (T > 64) {      // the same pass in the fp16 form may split K differently
+        const int rf = tail_rows(T, N, K, epi, true);
+        part = std::max(part, partial_bytes(T - rf, N, K, epi, true));
+        if (rf) part = std::max(part, partial_bytes(rf, N, K, epi));
+    }
     return gemm_split_bytes(T, K) + part;
 }
 
@@ -980,7 +1052,7 @@ void launch_gemm_skinny(const uint16_t *W, const uint16_t *xhi, const uint16_t *
 // One launch of the big-tile kernel over output columns [col0, col1) with split factor ks (+ its reduction).
 static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
                             float *partial, int wm, int bn, int n_ttiles, int ks, int col0, int col1, hipStream_t s,
-                            bool reduce = true, bf16_t *hi_out = nullptr, bf16_t *lo_out = nullptr) {
+                            bool reduce, bf16_t *hi_out, bf16_t *lo_out, bool f16) {
     const int nout = epi == GEMM_SWIGLU ? bn / 2 : bn;
     const int n_nblocks = (col1 - col0 + nout - 1) / nout;
     const int grid = ((n_nblocks + 7) / 8) * 8 * n_ttiles * ks;
@@ -992,17 +1064,22 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
         if (ks > 1 && reduce)                                                                                          \
             LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1, hi_out, lo_out); \
     } while (0)
-#define LD_DMA(WM_, BN_, S_, EPI_, WN_)                                                                                \
+#define LD_DMA_M(WM_, BN_, S_, EPI_, WN_, F16_)                                                                        \
     do {                                                                                                               \
-        constexpr int lds_bytes = (2 * 64 * WM_ + BN_) * 64 * S_;                                                      \
+        constexpr int lds_bytes = ((F16_ ? 1 : 2) * 64 * WM_ + BN_) * 64 * S_;                                         \
         static bool attr_set = false;                                                                                  \
         if (!attr_set) {                                                                                               \
-            (void)hipFuncSetAttribute((const void *)k_gemm_dma<WM_, BN_, S_, EPI_, WN_>,                               \
+            (void)hipFuncSetAttribute((const void *)k_gemm_dma<WM_, BN_, S_, EPI_, WN_, F16_>,                         \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);                          \
             attr_set = true;                                                                                           \
         }                                                                                                              \
-        LD_LAUNCH((k_gemm_dma<WM_, BN_, S_, EPI_, WN_>), dim3(grid), dim3(64 * WM_ * WN_), lds_bytes, s, W, hi, lo, T, \
-                  N, K, y, n_ttiles, ks, partial, col0, col1, hi_out, lo_out);                                         \
+        LD_LAUNCH((k_gemm_dma<WM_, BN_, S_, EPI_, WN_, F16_>), dim3(grid), dim3(64 * WM_ * WN_), lds_bytes, s, W, hi,   \
+                  lo, T, N, K, y, n_ttiles, ks, partial, col0, col1, hi_out, lo_out);                                  \
+    } while (0)
+#define LD_DMA(WM_, BN_, S_, EPI_, WN_)                                                                                \
+    do {                                                                                                               \
+        if (f16) LD_DMA_M(WM_, BN_, S_, EPI_, WN_, true);                                                              \
+        else LD_DMA_M(WM_, BN_, S_, EPI_, WN_, false);                                                                 \
         if (ks > 1 && reduce)                                                                                          \
             LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1, hi_out, lo_out); \
     } while (0)
@@ -1034,6 +1111,7 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
     }
 #undef LD_BIG
 #undef LD_DMA
+#undef LD_DMA_M
 }
 
 // Where the rows of a residual GEMM go next: the operand image of the normalised GEMM that follows.
@@ -1042,8 +1120,17 @@ struct RowsNext { const float *g; float eps; bf16_t *hi, *lo; const RopeKvArgs *
 // nx != nullptr with GEMM_ADD: y's rows are finished and turned into the next operand by one fused kernel in
 // place of the split-K reduction.  With GEMM_SWIGLU: the epilogue (or the split-K reduction) writes its result
 // as the next operand instead of floats.
-static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
-                      float *partial, hipStream_t s, const RowsNext *nx = nullptr) {
+// Whether the fp16 form serves a product of T rows: the direct-to-LDS kernel with 256-wide weight tiles must be the
+// plan's choice in every phase.
+static bool f16_plan_ok(const BigPlan &p, int K) {
+    return p.bn == 256 && (K / 32) / std::max(p.ks, 1) >= 4 && (p.nb_a == 0 || (K / 32) / std::max(p.ks_b, 1) >= 4);
+}
+bool gemm_f16_rows(int T, int N, int K, int epi) { return T > 64 && f16_plan_ok(plan_big(T, N, K, epi, true), K); }
+
+// f16_flag != nullptr (more than 64 rows, gemm_f16_rows): the rows' images are turned into one fp16 image in place
+// and multiplied in the single-term form; *f16_flag is set if an activation does not fit.
+static void gemm_rows(const uint16_t *W, bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
+                      float *partial, hipStream_t s, const RowsNext *nx = nullptr, int *f16_flag = nullptr) {
     const bool chain_rope = nx && epi == GEMM_STORE && nx->rope;
     const bool chain_add = (nx && epi == GEMM_ADD) || chain_rope;      // a finishing kernel replaces the split-K reduction
     bf16_t *ho = nx && epi == GEMM_SWIGLU ? nx->hi : nullptr, *lo_o = nx && epi == GEMM_SWIGLU ? nx->lo : nullptr;
@@ -1069,15 +1156,20 @@ static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int
         return;
     }
     if (T > 64) {
-        const BigPlan p = plan_big(T, N, K, epi);
+        const bool f16 = f16_flag != nullptr;
+        const BigPlan p = plan_big(T, N, K, epi, f16);
+        if (f16) {
+            const int64_t n8 = (int64_t)T * K / 8;
+            LD_LAUNCH(k_split_to_f16, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s, hi, lo, n8, f16_flag);
+        }
         if (p.nb_a > 0) {
             // two phases: whole rounds of unsplit tiles, then the remaining column blocks with a split K
             const int nout = (epi == GEMM_SWIGLU ? p.bn / 2 : p.bn), mid = p.nb_a * nout;
-            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, 1, 0, mid, s, true, ho, lo_o);
-            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks_b, mid, N, s, !chain_add, ho, lo_o);
+            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, 1, 0, mid, s, true, ho, lo_o, f16);
+            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks_b, mid, N, s, !chain_add, ho, lo_o, f16);
             if (chain_add) finish(p.ks_b, mid, N);
         } else {
-            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks, 0, N, s, !chain_add, ho, lo_o);
+            launch_big_cols(W, hi, lo, T, N, K, epi, y, partial, p.wm, p.bn, p.n_ttiles, p.ks, 0, N, s, !chain_add, ho, lo_o, f16);
             if (chain_add) finish(p.ks, 0, N);
         }
         return;
@@ -1086,11 +1178,16 @@ static void gemm_rows(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int
     if (chain_add) finish(split_factor(T, N, K, epi), 0, N);
 }
 
-void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s,
-                 const GemmNext *next) {
+void launch_gemm(const uint16_t *W, uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s,
+                 const GemmNext *next, int *f16_flag) {
     float *partial = (float *)((char *)xs + gemm_split_bytes(T, K));
-    const bf16_t *hi = xs, *lo = xs + (size_t)T * K;
-    const int r = tail_rows(T, N, K, epi);
+    bf16_t *hi = xs, *lo = xs + (size_t)T * K;
+    // the rows beyond a multiple of 256 that the cost model sends through the small-batch kernels keep both terms
+    int r = tail_rows(T, N, K, epi, f16_flag != nullptr);
+    if (f16_flag && !gemm_f16_rows(T - r, N, K, epi)) {
+        f16_flag = nullptr;
+        r = tail_rows(T, N, K, epi, false);
+    }
     // the next operand is a [2][T][N] image: rows of the main part first, the tail's rows behind them
     RowsNext a{}, b{};
     if (next) {
@@ -1098,10 +1195,14 @@ void launch_gemm(const uint16_t *W, const uint16_t *xs, int T, int N, int K, int
         b = {next->g, next->eps, next->xs ? a.hi + (size_t)(T - r) * N : nullptr, next->xs ? a.lo + (size_t)(T - r) * N : nullptr,
              next->rope, T - r};
     }
-    gemm_rows(W, hi, lo, T - r, N, K, epi, y, partial, s, next ? &a : nullptr);
+    gemm_rows(W, hi, lo, T - r, N, K, epi, y, partial, s, next ? &a : nullptr, f16_flag);
     // the tail reuses the partial-sum scratch: the stream orders it behind the main part's reduction
     if (r) gemm_rows(W, hi + (size_t)(T - r) * K, lo + (size_t)(T - r) * K, r, N, K, epi, y + (size_t)(T - r) * N, partial, s,
                      next ? &b : nullptr);
+}
+
+void launch_weight_range_check(const uint16_t *W, int64_t n, int *flag, hipStream_t s) {
+    LD_LAUNCH(k_weight_range, dim3(1024), dim3(256), 0, s, W, n / 8, flag);
 }
 
 }  // namespace ld

@@ -33,6 +33,7 @@ using ld::fail;
 
 struct ld_model {
     ld_model_config c;
+    int f16_weights = -1;     // layer matrices within the fp16 range: -1 not looked at yet, 0 no, 1 yes
     const void *embed, *lm_head;
     const float *final_norm;
     std::vector<const float *> attn_norm, ffn_norm;
@@ -61,6 +62,7 @@ struct Seq {
 // Layout of the workspace: every region 256-byte aligned.
 struct Workspace {
     int32_t *table, *meta, *out_tok;
+    int32_t *flags;      // [0]: a value of this pass did not fit the fp16 form of the multi-row products
     float *x, *qkv, *attn, *act, *hn, *logits, *cos_sin;
     void *att_scratch, *lin_scratch, *lin_scratch2;   // lin_scratch2: second GEMM scratch area (bf16 models), same size
     size_t att_scratch_bytes, lin_scratch_bytes;
@@ -83,6 +85,7 @@ Workspace plan_workspace(const ld_model &m, char *base, int max_tokens, int max_
     // tok | pos | seq_slot | ctx_len | emit_row | prefill tiles (4 ints each) | sampling (seed 2, temperature, pos per emitting row)
     w.meta = (int32_t *)take((T * 9 + 2 + (size_t)max_seqs * 4) * 4);
     w.out_tok = (int32_t *)take((size_t)max_seqs * 4);
+    w.flags = (int32_t *)take(64);
     w.x = (float *)take(T * c.d_model * 4);
     w.qkv = (float *)take(T * m.nqkv() * 4);
     w.attn = (float *)take(T * m.nq() * 4);
@@ -226,7 +229,7 @@ void release_blocks(ld_kv *kv, int s) {
 
 ld_status ensure_pinned(ld_kv *kv) {
     if (kv->pin_meta) return LD_OK;
-    LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_out, (size_t)2 * kv->max_seqs * 4, hipHostMallocDefault));
+    LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_out, ((size_t)2 * kv->max_seqs + 2) * 4, hipHostMallocDefault));   // + one flag per slot
     LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_table, (size_t)kv->max_seqs * kv->max_blocks * 4, hipHostMallocDefault));
     for (hipEvent_t &e : kv->step_ev) LD_HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     LD_HIP_TRY(hipHostMalloc((void **)&kv->pin_meta, 2 * kv->meta_ints() * 4, hipHostMallocDefault));
@@ -240,7 +243,7 @@ ld_status ensure_pinned(ld_kv *kv) {
 // positions.  tok_from_prev: row t's input token is the token that the previous pass on this stream
 // emitted for its row t (read on the device), not rows[t].tok.
 ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const std::vector<int32_t> &emit,
-                       hipStream_t st, float *logits_out, int slot, bool tok_from_prev, int *ops) {
+                       hipStream_t st, float *logits_out, int slot, bool tok_from_prev, int *ops, bool allow_f16 = false) {
     const ld_model &m = *kv->m;
     const ld_model_config &c = m.c;
     const int T = (int)rows.size(), R = (int)emit.size();
@@ -292,6 +295,10 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
         meta_ints = samp_off + 4 * R;
     }
     LD_HIP_TRY(hipMemcpyAsync(w.meta, pm, (size_t)meta_ints * 4, hipMemcpyHostToDevice, st));
+    // allow_f16: the multi-row products may take their rows rounded to fp16 (launch_gemm); flags[0] tells afterwards
+    // whether a value did not fit, pin_out[2 * max_seqs + slot] carries it to the host
+    int *f16_flag = allow_f16 ? w.flags : nullptr;
+    if (f16_flag) LD_HIP_TRY(hipMemsetAsync(w.flags, 0, 4, st));
     const int32_t *d_tok = tok_from_prev ? w.out_tok : w.meta, *d_pos = w.meta + T, *d_slot = w.meta + 2 * T, *d_ctx = w.meta + 3 * T,
                   *d_emit = w.meta + 4 * T, *d_tiles = w.meta + 5 * T;
 
@@ -369,7 +376,7 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
             const ld::GemmNext to_cache{nullptr, 0.f, nullptr, &rk};
             LD_TIMED(LD_PROF_QKV, timed_void([&] {
                 if (l == 0) ld::launch_norm_split(w.x, m.attn_norm[0], c.rms_eps, T, d, B, st);
-                ld::launch_gemm(mat(m.wqkv[l]), B, T, nqkv, d, ld::GEMM_STORE, w.qkv, st, &to_cache);
+                ld::launch_gemm(mat(m.wqkv[l]), B, T, nqkv, d, ld::GEMM_STORE, w.qkv, st, &to_cache, f16_flag);
             }));
             // attention writes the output projection's operand (A) directly: single-query rows first, then the tiles' rows
             if (n_dec_rows)
@@ -384,19 +391,25 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
                 }));
             const ld::GemmNext to_ffn{m.ffn_norm[l], c.rms_eps, B};
             const ld::GemmNext to_next{l + 1 < c.n_layers ? m.attn_norm[l + 1] : nullptr, c.rms_eps, B};
-            LD_TIMED(LD_PROF_WO, timed_void([&] { ld::launch_gemm(mat(m.wo[l]), A, T, d, nq, ld::GEMM_ADD, w.x, st, &to_ffn); }));
+            LD_TIMED(LD_PROF_WO, timed_void([&] { ld::launch_gemm(mat(m.wo[l]), A, T, d, nq, ld::GEMM_ADD, w.x, st, &to_ffn, f16_flag); }));
             const ld::GemmNext to_down{nullptr, 0.f, A};      // the gated activation goes straight into the down projection's operand
-            LD_TIMED(LD_PROF_GATE_UP, timed_void([&] { ld::launch_gemm(mat(m.wgate_up[l]), B, T, c.d_ffn, d, ld::GEMM_SWIGLU, w.act, st, &to_down); }));
+            LD_TIMED(LD_PROF_GATE_UP, timed_void([&] { ld::launch_gemm(mat(m.wgate_up[l]), B, T, c.d_ffn, d, ld::GEMM_SWIGLU, w.act, st, &to_down, f16_flag); }));
             LD_TIMED(LD_PROF_DOWN, timed_void([&] {
-                ld::launch_gemm(mat(m.wdown[l]), A, T, d, c.d_ffn, ld::GEMM_ADD, w.x, st, to_next.g ? &to_next : nullptr);
+                ld::launch_gemm(mat(m.wdown[l]), A, T, d, c.d_ffn, ld::GEMM_ADD, w.x, st, to_next.g ? &to_next : nullptr, f16_flag);
             }));
         }
         LD_HIP_TRY(hipGetLastError());
     } else
     for (int l = 0; l < c.n_layers; l++) {
         void *pool_l = kv->pool + (size_t)l * layer_bytes;
-        LD_TIMED(LD_PROF_QKV, ldk_qkv_rope(m.wqkv[l], c.dtype, w.x, m.attn_norm[l], c.rms_eps, w.qkv, w.cos_sin, d_pos,
-                                           d_slot, w.table, kv->max_blocks, pool_l, T, d, H, Hkv, hd, w.lin_scratch, w.lin_scratch_bytes, st));
+        if (T == 1 || !f16_flag)
+            LD_TIMED(LD_PROF_QKV, ldk_qkv_rope(m.wqkv[l], c.dtype, w.x, m.attn_norm[l], c.rms_eps, w.qkv, w.cos_sin, d_pos,
+                                               d_slot, w.table, kv->max_blocks, pool_l, T, d, H, Hkv, hd, w.lin_scratch, w.lin_scratch_bytes, st));
+        else {
+            LD_TIMED(LD_PROF_QKV, ld::linear_pass(m.wqkv[l], c.dtype, w.x, m.attn_norm[l], c.rms_eps, T, nqkv, d, LDK_STORE, w.qkv,
+                                                  w.lin_scratch, w.lin_scratch_bytes, st, f16_flag));
+            LD_TIMED(LD_PROF_QKV, ldk_rope_kv_write(w.qkv, w.cos_sin, d_pos, d_slot, w.table, kv->max_blocks, pool_l, c.dtype, T, H, Hkv, hd, st));
+        }
         if (n_dec_rows)
             LD_TIMED(LD_PROF_ATTENTION, ldk_paged_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot, d_ctx,
                                                             max_ctx_dec, n_dec_rows, H, Hkv, hd, c.window, w.attn,
@@ -405,10 +418,10 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
             LD_TIMED(LD_PROF_ATTENTION, ldk_prefill_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_tiles,
                                                               n_tiles, H, Hkv, hd, c.window, max_ctx - 1, w.attn,
                                                               w.att_scratch, w.att_scratch_bytes, st));
-        LD_TIMED(LD_PROF_WO, ldk_linear(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st));
-        LD_TIMED(LD_PROF_GATE_UP, ldk_linear(m.wgate_up[l], c.dtype, w.x, m.ffn_norm[l], c.rms_eps, T, c.d_ffn, d, LDK_SWIGLU, w.act, w.lin_scratch,
-                                               w.lin_scratch_bytes, st));
-        LD_TIMED(LD_PROF_DOWN, ldk_linear(m.wdown[l], c.dtype, w.act, nullptr, 0.f, T, d, c.d_ffn, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st));
+        LD_TIMED(LD_PROF_WO, ld::linear_pass(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st, f16_flag));
+        LD_TIMED(LD_PROF_GATE_UP, ld::linear_pass(m.wgate_up[l], c.dtype, w.x, m.ffn_norm[l], c.rms_eps, T, c.d_ffn, d, LDK_SWIGLU, w.act, w.lin_scratch,
+                                                    w.lin_scratch_bytes, st, f16_flag));
+        LD_TIMED(LD_PROF_DOWN, ld::linear_pass(m.wdown[l], c.dtype, w.act, nullptr, 0.f, T, d, c.d_ffn, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st, f16_flag));
     }
     if (T == 1 && R == 1) {
         // one row, and it emits: the final norm rides in the LM head's own pass over x (as in every layer)
@@ -431,17 +444,56 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
         LD_HIP_TRY(hipMemcpyAsync(kv->pin_out + (size_t)slot * kv->max_seqs, w.out_tok, (size_t)R * 4, hipMemcpyDeviceToHost, st));
     if (logits_out && R)
         LD_HIP_TRY(hipMemcpyAsync(logits_out, w.logits, (size_t)R * c.vocab * 4, hipMemcpyDeviceToHost, st));
+    if (f16_flag)
+        LD_HIP_TRY(hipMemcpyAsync(kv->pin_out + (size_t)2 * kv->max_seqs + slot, w.flags, 4, hipMemcpyDeviceToHost, st));
     LD_HIP_TRY(hipEventRecord(kv->step_ev[slot], st));
     return LD_OK;
 }
 
 // One pass, waited for: on return pin_out[i] holds the tokens.
+// Rows of prefill chunks reach later tokens only through the cached keys and values, which are rounded to bf16
+// anyway: in passes of at least LD_GEMM_F16_MIN_ROWS rows (512; LD_GEMM_F16=0 switches it off) the big-tile products
+// take them rounded to fp16.  The first such pass looks once at the model's layer matrices (all within +-65504?);
+// a pass in which an activation did not fit is repeated in the two-term form (the pass is a function of its
+// inputs and of the cache before it; cache writes of the first attempt are overwritten).
+static ld_status f16_weights_ok(ld_kv *kv, hipStream_t st, bool *ok) {
+    ld_model &m = *kv->m;
+    if (m.f16_weights < 0) {
+        const ld_model_config &c = m.c;
+        LD_HIP_TRY(hipMemsetAsync(kv->ws.flags + 1, 0, 4, st));
+        for (int l = 0; l < c.n_layers; l++) {
+            ld::launch_weight_range_check((const uint16_t *)m.wqkv[l], (int64_t)m.nqkv() * c.d_model, kv->ws.flags + 1, st);
+            ld::launch_weight_range_check((const uint16_t *)m.wo[l], (int64_t)c.d_model * m.nq(), kv->ws.flags + 1, st);
+            ld::launch_weight_range_check((const uint16_t *)m.wgate_up[l], (int64_t)2 * c.d_ffn * c.d_model, kv->ws.flags + 1, st);
+            ld::launch_weight_range_check((const uint16_t *)m.wdown[l], (int64_t)c.d_model * c.d_ffn, kv->ws.flags + 1, st);
+        }
+        int32_t bad = 1;
+        LD_HIP_TRY(hipMemcpyAsync(&bad, kv->ws.flags + 1, 4, hipMemcpyDeviceToHost, st));
+        LD_HIP_TRY(hipStreamSynchronize(st));
+        m.f16_weights = bad ? 0 : 1;
+    }
+    *ok = m.f16_weights == 1;
+    return LD_OK;
+}
+
 ld_status run_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const std::vector<int32_t> &emit,
                    hipStream_t st, float *logits_out) {
     int ops[LD_PROF_N] = {0};
-    ld_status rc = enqueue_pass(kv, rows, n_single, emit, st, logits_out, 0, false, ops);
+    const int f16_on = ld::env_flag("LD_GEMM_F16", 1), f16_min_rows = ld::env_flag("LD_GEMM_F16_MIN_ROWS", 512);   // read per pass
+    const ld_model_config &mc = kv->m->c;
+    bool f16 = f16_on && mc.dtype == LD_BF16 && mc.n_layers > 0 && (int)rows.size() >= f16_min_rows && mc.d_model % 8 == 0 && mc.d_ffn % 8 == 0;
+    if (f16) {
+        ld_status rc0 = f16_weights_ok(kv, st, &f16);
+        if (rc0) return rc0;
+    }
+    ld_status rc = enqueue_pass(kv, rows, n_single, emit, st, logits_out, 0, false, ops, f16);
     if (rc) return rc;
     LD_HIP_TRY(hipStreamSynchronize(st));
+    if (f16 && kv->pin_out[(size_t)2 * kv->max_seqs]) {      // a value beyond the fp16 range: once more, both terms
+        rc = enqueue_pass(kv, rows, n_single, emit, st, logits_out, 0, false, ops, false);
+        if (rc) return rc;
+        LD_HIP_TRY(hipStreamSynchronize(st));
+    }
     if (kv->prof_on) {
         if (kv->timer.failed) return fail(LD_E_HIP, "profiling: hipEventCreate failed");
         for (size_t i = 0; i < kv->timer.cat.size(); i++) {

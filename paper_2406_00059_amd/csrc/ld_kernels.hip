@@ -552,6 +552,29 @@ size_t ldk_linear_scratch_bytes(int32_t T, int32_t N, int32_t K, int32_t epilogu
 
 ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *g, float eps, int32_t T, int32_t N,
                      int32_t K, int32_t epilogue, float *y, void *scratch, size_t scratch_bytes, void *stream) {
+    return ld::linear_pass(W, dtype, x, g, eps, T, N, K, epilogue, y, scratch, scratch_bytes, stream, nullptr);
+}
+
+ld_status ldk_linear_f16(const void *W, const float *x, const float *g, float eps, int32_t T, int32_t N, int32_t K,
+                         int32_t epilogue, float *y, void *scratch, size_t scratch_bytes, int32_t *overflow,
+                         void *stream) {
+    if (!overflow) return ld::fail(LD_E_INVAL, "ldk_linear_f16: null overflow flag");
+    if (T > 0 && W && N > 0 && K > 0 && K % 8 == 0)
+        ld::launch_weight_range_check((const uint16_t *)W, (int64_t)N * (epilogue == LDK_SWIGLU ? 2 : 1) * K, overflow,
+                                      (hipStream_t)stream);
+    return ld::linear_pass(W, LD_BF16, x, g, eps, T, N, K, epilogue, y, scratch, scratch_bytes, stream, overflow);
+}
+
+}  // extern "C"
+
+int ld::env_flag(const char *name, int dflt) {
+    const char *v = getenv(name);
+    return v ? atoi(v) : dflt;
+}
+
+ld_status ld::linear_pass(const void *W, int32_t dtype, const float *x, const float *g, float eps, int32_t T, int32_t N,
+                          int32_t K, int32_t epilogue, float *y, void *scratch, size_t scratch_bytes, void *stream,
+                          int *f16_flag) {
     if (T == 0) return LD_OK;   // nothing to do: pointers of empty buffers may be null
     if (!W || !x || !y || T < 0 || N <= 0 || K <= 0 || K % 8 || epilogue < 0 || epilogue > 2)
         return ld::fail(LD_E_INVAL, "ldk_linear: bad argument (K must be a multiple of 8)");
@@ -562,7 +585,7 @@ ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *
     }
     if (dtype == LD_BF16 && scratch && ld::gemm_supported(T, N, K) && scratch_bytes >= ld::gemm_scratch_bytes(T, N, K, epilogue)) {
         ld::launch_norm_split(x, g, eps, T, K, (uint16_t *)scratch, s);
-        ld::launch_gemm((const bf16_t *)W, (const uint16_t *)scratch, T, N, K, epilogue, y, s);
+        ld::launch_gemm((const bf16_t *)W, (uint16_t *)scratch, T, N, K, epilogue, y, s, nullptr, f16_flag);
         return launched("k_gemm_mfma");
     }
     if (dtype == LD_BF16) {
@@ -576,6 +599,8 @@ ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *
     }
     return launched("k_linear");
 }
+
+extern "C" {
 
 ld_status ldk_rope_table(const int32_t *pos, int32_t T, int32_t hd, float rope_base, float *cos_sin, void *stream) {
     if (!pos || !cos_sin || T < 0 || (hd != 64 && hd != 128)) return ld::fail(LD_E_INVAL, "ldk_rope_table: bad argument");

@@ -9,7 +9,8 @@ import torch
 
 import oracle
 import paper_2406_00059_amd as ld
-from workloads import TINY, LLAMA7B, SEED_BASE, gen
+from workloads import TINY, LLAMA7B, SEED_BASE, gen, make_weights
+from workloads.configs import weights_to
 from helpers import NearTies, Pair, Tokens, prompt, rel_err
 
 pytestmark = pytest.mark.gpu
@@ -624,3 +625,52 @@ def test_chained_normalisation_equals_the_separate_passes(chunk, heads, monkeypa
             assert torch.equal(x.view(torch.int16), y.view(torch.int16))
         else:
             assert np.array_equal(x, y)
+
+
+def test_long_chunk_takes_fp16_rows_and_falls_back():
+    """A pass of 512 rows or more takes its big-tile products with the activations rounded to fp16.  A 520-token
+    prompt in one chunk at 7B width (one layer): the logits differ from those of the two-term form (LD_GEMM_F16=0,
+    read per pass) and both are within tolerance of the oracle; the tokens that follow agree with the oracle's.
+    With a gain that lifts the layer's FFN input beyond the fp16 range (65504) the pass is found out and repeated
+    with two terms: bit-equal to the two-term run of the same model."""
+    import os
+    shape = LLAMA7B.with_layers(1)
+    seed = SEED_BASE + 11
+    tk = prompt(seed, 5, 520, shape.vocab)
+
+    def run(models, f16, with_oracle):
+        P = Pair(shape, seed, n_blocks=48, max_tokens=544, max_seqs=2, max_blocks=40, models=models)
+        s = P.alloc()
+        old = os.environ.get("LD_GEMM_F16")
+        os.environ["LD_GEMM_F16"] = "1" if f16 else "0"
+        try:
+            sink = Tokens()
+            rc, lg = ld.ld_prefill(P.gkv.h, s, tk, callback=sink, logits_vocab=P.V)
+            for _ in range(3):
+                ld.ld_decode_step(P.gkv.h, [s], callback=sink)
+        finally:
+            if old is None:
+                del os.environ["LD_GEMM_F16"]
+            else:
+                os.environ["LD_GEMM_F16"] = old
+        out = [np.asarray(lg), [t for _, t, _ in sink.log]]
+        if with_oracle:
+            rc, t_o, lg_o = P.okv.prefill(s, tk)
+            out += [lg_o, [t_o] + [P.okv.decode(s)[1] for _ in range(3)]]
+        return out
+
+    w = make_weights(shape, seed, device="cuda")
+    models = (oracle.Model(shape, w), ld.Model(shape, weights_to(w, "cuda"), max_chunk=1024))
+    lg_h, toks_h, lg_o, toks_o = run(models, True, True)
+    lg_2, toks_2 = run(models, False, False)
+    e_h, e_2 = rel_err(lg_h, lg_o), rel_err(lg_2, lg_o)
+    print("520-row chunk: logits rel err, fp16 rows", e_h, "two terms", e_2)
+    assert not np.array_equal(lg_h, lg_2) and e_2 <= 1e-3 and e_2 < e_h <= 2e-2
+    assert toks_h == toks_o and toks_2 == toks_o
+
+    w["ffn_norm"][0] = w["ffn_norm"][0] * 1.0e5       # normalised rows times the gain: far beyond 65504
+    models = (oracle.Model(shape, w), ld.Model(shape, weights_to(w, "cuda"), max_chunk=1024))
+    lg_h, toks_h, lg_o, toks_o = run(models, True, True)
+    lg_2, toks_2 = run(models, False, False)
+    print("with the large gain: logits rel err", rel_err(lg_h, lg_o))
+    assert np.array_equal(lg_h, lg_2) and toks_h == toks_2 == toks_o and rel_err(lg_h, lg_o) <= 2e-2

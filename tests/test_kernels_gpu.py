@@ -462,6 +462,67 @@ def _sampled_linear_cases(row_counts, matrices):
                     assert abs(yh[t, n] - a) <= 1e-4 * max(1.0, abs(a)), (T, N, t, n, yh[t, n], a)
 
 
+def test_linear_fp16_rows_sampled():
+    """The form of the multi-row product that long prefill chunks take in the engine (ldk_linear_f16: activations
+    rounded to fp16 in one term, bf16 matrix entries widened to fp16 exactly): sampled outputs against the oracle's
+    dot product on the inputs rounded as the kernel rounds them (the 16-bit sum of the split image, then fp16; what
+    remains is float32 accumulation: the two-term test's bound) and
+    against the oracle on the exact inputs (the rounding itself: 2^-12 per term, random walk over K terms).  Row
+    counts with a tail that keeps both terms (1056, 2111), with three and one row tiles, and one that stays on the
+    small-batch kernel (32: bit-equal to ldk_linear).  A value beyond the fp16 range in the input or in the matrix
+    raises the flag."""
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    for T in (32, 256, 768, 1056, 2111):
+        for N, K, epi in [(12288, 4096, ld.LDK_STORE), (4096, 11008, ld.LDK_ADD), (11008, 4096, ld.LDK_SWIGLU)]:
+            rows = N * (2 if epi == ld.LDK_SWIGLU else 1)
+            W = gen.normal(3, N, (rows, K), std=0.02, device=DEV).bfloat16()
+            x = gen.normal(3, 7 + T, (T, K), device=DEV)
+            y = torch.zeros(T, N, device=DEV); y2 = torch.zeros(T, N, device=DEV)
+            scratch = torch.empty(ld.ldk_linear_scratch_bytes(T, N, K, epi), dtype=torch.uint8, device=DEV)
+            flag.zero_()
+            ld.ldk_linear_f16(W, x, y, flag, epi, scratch=scratch)
+            assert int(flag.item()) == 0
+            ld.ldk_linear(W, x, y2, epi, scratch=scratch)
+            r = T % 256 if T > 256 and T % 256 <= 64 else 0       # tail rows: both terms in either form
+            if T <= 64:
+                assert torch.equal(y, y2)
+            else:
+                assert not torch.equal(y[:T - r], y2[:T - r])     # the single-term form did run
+            ns = gen.randint(3, 9, 0, N - 1, 6).tolist() + [0, N - 1]
+            ts = sorted(set(gen.randint(3, 10, 0, T - 1, 5).tolist() + [0, T - 1, max(T - T % 256 - 1, 0), min(T - T % 256, T - 1)]))
+            xh = x.cpu().numpy(); yh = y.cpu().numpy()
+            # what the kernel rounds: the sum of the two bf16 terms of the split image (16 bits), not x itself
+            xc = x.cpu(); hi = xc.bfloat16().float(); lo = (xc - hi).bfloat16().float()
+            xr = (hi + lo).half().float().numpy()
+            for n in ns:
+                wr = oracle.to_host_matrix(W[n:n + 1]); wu = oracle.to_host_matrix(W[N + n:N + n + 1]) if epi == ld.LDK_SWIGLU else None
+                for t in ts:
+                    vals = []
+                    for xin in (xh, xr):
+                        a = oracle.matvec(wr, xin[t])[0]
+                        if wu is not None:
+                            a = oracle.silu(a) * oracle.matvec(wu, xin[t])[0]
+                        vals.append(a)
+                    exact, rounded = vals
+                    assert abs(yh[t, n] - exact) <= 2e-3 * max(1.0, abs(exact)), (T, N, t, n, yh[t, n], exact)
+                    if T > 64 and t < T - r:
+                        assert abs(yh[t, n] - rounded) <= 1e-4 * max(1.0, abs(rounded)), (T, N, t, n, yh[t, n], rounded)
+    # values beyond the fp16 range
+    T, N, K = 300, 4096, 4096
+    W = gen.normal(3, 1, (N, K), std=0.02, device=DEV).bfloat16()
+    x = gen.normal(3, 2, (T, K), device=DEV)
+    y = torch.zeros(T, N, device=DEV)
+    scratch = torch.empty(ld.ldk_linear_scratch_bytes(T, N, K, ld.LDK_STORE), dtype=torch.uint8, device=DEV)
+    xb = x.clone(); xb[17, 1234] = 7.0e4
+    flag.zero_(); ld.ldk_linear_f16(W, xb, y, flag, scratch=scratch); assert int(flag.item()) == 1
+    xb[17, 1234] = -6.5e4           # the largest fp16 magnitude is 65504
+    flag.zero_(); ld.ldk_linear_f16(W, xb, y, flag, scratch=scratch); assert int(flag.item()) == 0
+    Wb = W.clone(); Wb[4000, 4095] = 1.0e5
+    flag.zero_(); ld.ldk_linear_f16(Wb, x, y, flag, scratch=scratch); assert int(flag.item()) == 1
+    Wb[4000, 4095] = float("nan")
+    flag.zero_(); ld.ldk_linear_f16(Wb, x, y, flag, scratch=scratch); assert int(flag.item()) == 1
+
+
 @pytest.mark.parametrize("split", [False, True], ids=["whole", "kv-split"])
 @pytest.mark.parametrize("window", [0, 1, 40, 128, 200, 5000])
 @pytest.mark.parametrize("H,Hkv", [(4, 4), (8, 2)])

@@ -567,8 +567,15 @@ def main():
                 for _ in range(3):
                     ld.ldk_linear(W, x, y, epi, scratch=scratch)
                 torch.cuda.synchronize()
+                # the form the engine's passes of 512 rows or more take: one fp16 term
+                flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+                for _ in range(3):
+                    ld.ldk_linear_f16(W, x, y, flag, epi, scratch=scratch)
+                torch.cuda.synchronize()
+                assert int(flag.item()) == 0
                 out["gemm"].append({"rows": T, "matrix": name, "weight_rows": rows, "K": K,
-                                    "nominal_flops": 2 * T * rows * K, "mfma_flops_with_split": 4 * T * rows * K})
+                                    "nominal_flops": 2 * T * rows * K, "mfma_flops_with_split": 4 * T * rows * K,
+                                    "mfma_flops_fp16_rows": 2 * T * rows * K})
         # chunk-prefill attention of a mixed step: four 256-row observations behind long contexts
         segs = [(3001, 256), (5001, 256), (7501, 256), (1201, 256)]
         lens = [p0 + n for p0, n in segs]

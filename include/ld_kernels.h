@@ -138,6 +138,18 @@ ld_status ldk_prefill_attention(const float *q, int32_t q_stride, const void *po
                                 int32_t H, int32_t Hkv, int32_t hd, int32_t window, int32_t max_pos, float *out,
                                 void *scratch, size_t scratch_bytes, void *stream);
 
+/* ldk_prefill_attention in the form the engine uses in passes of 512 rows or more (see ldk_linear_f16): with
+ * overflow != NULL the queries and the probabilities enter the matrix-core products as one fp16 term (11 significant
+ * bits; two bf16 terms otherwise) and the cached keys and values are widened from bf16 to fp16, which is exact within
+ * +-65504.  *overflow (DEVICE, 4 bytes, cleared by the caller) is set to 1 when a scaled query, a key or a value of a
+ * position the walk touches lies beyond that range or is not a number; out is then not to be used.  overflow == NULL:
+ * exactly ldk_prefill_attention. */
+ld_status ldk_prefill_attention_f16(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
+                                    const int32_t *table, int32_t table_stride, const int32_t *tiles,
+                                    int32_t n_tiles, int32_t H, int32_t Hkv, int32_t hd, int32_t window,
+                                    int32_t max_pos, float *out, void *scratch, size_t scratch_bytes,
+                                    int32_t *overflow, void *stream);
+
 /* out[r] = smallest index of the maximum of logits[r, 0..V). */
 ld_status ldk_argmax(const float *logits, int32_t R, int32_t V, int32_t *out, void *stream);
 

@@ -22,7 +22,7 @@ __all__ = [
     "ld_token_cb", "ld_model_create", "ld_model_destroy", "ld_kv_bytes", "ld_workspace_bytes", "ld_kv_create",
     "ld_kv_destroy", "ld_kv_alloc", "ld_kv_map", "ld_kv_free", "ld_kv_block_table", "ld_kv_len",
     "ld_kv_free_blocks", "ld_kv_assume", "ld_kv_swap_bytes", "ld_kv_swap_out", "ld_kv_swap_in", "ld_kv_fork", "ld_kv_trim", "ld_kv_set_sampling", "ld_prefill", "ld_decode_step", "ld_decode_run", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
-    "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_f16", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
+    "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_f16", "ldk_prefill_attention_f16", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
     "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_static_scratch_bytes", "ldk_paged_attention_static",
     "ldk_prefill_attention_scratch_bytes",
     "ldk_prefill_attention", "ldk_argmax", "ldk_sample", "Model", "KV",
@@ -112,6 +112,8 @@ _SIGS = {
     "ldk_prefill_attention_scratch_bytes": (C.c_size_t, []),
     "ldk_prefill_attention": (C.c_int, [_vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, C.c_int32,
                                         C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, C.c_size_t, _vp]),
+    "ldk_prefill_attention_f16": (C.c_int, [_vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, _vp, C.c_int32, C.c_int32,
+                                            C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp, C.c_size_t, _vp, _vp]),
     "ldk_argmax": (C.c_int, [_vp, C.c_int32, C.c_int32, _vp, _vp]),
 }
 EXPORTS = tuple(_SIGS)
@@ -425,6 +427,15 @@ def ldk_prefill_attention(q, q_stride, pool_layer, table, tiles, H, Hkv, hd, out
                                        _ptr(out), _ptr(scratch) if scratch is not None else None,
                                        scratch.numel() * scratch.element_size() if scratch is not None else 0,
                                        _stream(stream)))
+
+
+def ldk_prefill_attention_f16(q, q_stride, pool_layer, table, tiles, H, Hkv, hd, out, max_pos, overflow, window=0,
+                              scratch=None, stream=None):
+    _check(lib().ldk_prefill_attention_f16(_ptr(q), q_stride, _ptr(pool_layer), _dt(pool_layer.dtype), _ptr(table),
+                                           table.shape[1], _ptr(tiles), tiles.shape[0], H, Hkv, hd, window, max_pos,
+                                           _ptr(out), _ptr(scratch) if scratch is not None else None,
+                                           scratch.numel() * scratch.element_size() if scratch is not None else 0,
+                                           _ptr(overflow), _stream(stream)))
 
 
 def ldk_argmax(logits, out, stream=None):

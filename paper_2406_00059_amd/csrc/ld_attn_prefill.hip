@@ -41,6 +41,9 @@ using namespace ldd;
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+typedef __attribute__((ext_vector_type(2))) uint16_t u16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
@@ -51,13 +54,35 @@ constexpr int VLD = KVB + 8;     // LDS row stride of the transposed value tile 
 
 __device__ __forceinline__ int tau(int r) { return (r & 19) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
+// Two floats as packed fp16, rounded to nearest.
+__device__ __forceinline__ uint32_t pack2_f16(float a, float b) {
+    return __builtin_bit_cast(uint32_t, (f16x2){(_Float16)a, (_Float16)b});
+}
+// Eight bf16 numbers as fp16: exact where fp16 can hold the value (truncation below 2^-14, the largest finite
+// fp16 beyond +-65504: the caller looks for such values with `mag`, the running maximum of the magnitudes).
+__device__ __forceinline__ u32x4 bf16x8_to_f16x8(const u32x4 &w, u16x2 &mag) {
+    u32x4 h;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        h[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w[i] << 16), __uint_as_float(w[i] & 0xffff0000u)));
+        mag = __builtin_elementwise_max(mag, __builtin_bit_cast(u16x2, w[i] & 0x7fff7fffu));
+    }
+    return h;
+}
+
+// F16 (the long passes whose rows the engine lets enter the products rounded to fp16): queries and probabilities as
+// one fp16 term instead of two bf16 terms, keys and values widened from bf16 to fp16 when they are staged in LDS
+// (once per workgroup, exact within the fp16 range): half the matrix-core work.  *f16_flag is set when a query, a
+// key or a value lies beyond +-65504 (the pass is then repeated with two terms).
+template <bool F16>
 __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict__ q, int q_stride,
                                                          const bf16_t *__restrict__ pool, int Hkv,
                                                          const int32_t *__restrict__ table, int table_stride,
                                                          const int4 *__restrict__ tiles, int H, int window,
                                                          float scale_log2e, float *__restrict__ out,
                                                          float *__restrict__ part_o, float *__restrict__ part_ml,
-                                                         bf16_t *__restrict__ xs_hi, bf16_t *__restrict__ xs_lo) {
+                                                         bf16_t *__restrict__ xs_hi, bf16_t *__restrict__ xs_lo,
+                                                         int *__restrict__ f16_flag) {
     __shared__ __attribute__((aligned(16))) bf16_t ks[2][KVB][KLD];
     __shared__ __attribute__((aligned(16))) bf16_t vt[2][HD][VLD];
     const int4 tile = tiles[blockIdx.x];      // x: first row, y: rows (<= 128), z: position of first row, w: seq slot
@@ -85,8 +110,11 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
     // to blocks the sequence has given up (ld_kv_trim) and are never dereferenced
     const int first_held_pos = window > 0 ? (max(tile.z - window + 1, 0) & ~15) : 0;
 
-    // Q operand: for k-step j the lane supplies dims half*64 + j*8 .. +8 of its query (hi and lo parts)
-    bf16x8 qh[8], ql[8];
+    // Q operand: for k-step j the lane supplies dims half*64 + j*8 .. +8 of its query (hi and lo parts; F16: one
+    // fp16 term in qh)
+    u32x4 qh[8], ql[F16 ? 1 : 8];
+    bool out_of_range = false;      // F16: a value beyond the fp16 range was seen by this lane
+    u16x2 mag = {0, 0};             // F16: largest bf16 magnitude (bit pattern) among the keys and values this lane staged
     {
         const float *qp = q + (int64_t)(tile.x + min(qi, tile.y - 1)) * q_stride + h * HD + half * 64;
 #pragma unroll
@@ -96,10 +124,16 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
             uint32_t hw[4], lw[4];
 #pragma unroll
             for (int e = 0; e < 4; e++) {
-                hw[e] = split2_bf16(v[2 * e] * scale_log2e, v[2 * e + 1] * scale_log2e, lw[e]);
+                const float a = v[2 * e] * scale_log2e, b = v[2 * e + 1] * scale_log2e;
+                if constexpr (F16) {
+                    out_of_range = out_of_range || !(fabsf(a) <= 65504.f) || !(fabsf(b) <= 65504.f);
+                    hw[e] = pack2_f16(a, b);
+                } else {
+                    hw[e] = split2_bf16(a, b, lw[e]);
+                }
             }
-            qh[j] = __builtin_bit_cast(bf16x8, (u32x4){hw[0], hw[1], hw[2], hw[3]});
-            ql[j] = __builtin_bit_cast(bf16x8, (u32x4){lw[0], lw[1], lw[2], lw[3]});
+            qh[j] = (u32x4){hw[0], hw[1], hw[2], hw[3]};
+            if constexpr (!F16) ql[j] = (u32x4){lw[0], lw[1], lw[2], lw[3]};
         }
     }
 
@@ -136,7 +170,15 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
     auto stage = [&](int st, int set, int kv0) {
 #pragma unroll
         for (int v = 0; v < 2; v++) {
-            *reinterpret_cast<u32x4 *>(&ks[st][16 * v + kr][kc]) = kreg[set][v];
+            if constexpr (F16) {
+                // a key row past the tile's last position was never written (its scores are masked): whatever it
+                // holds does not count as out of range
+                u16x2 seen = mag;
+                *reinterpret_cast<u32x4 *>(&ks[st][16 * v + kr][kc]) = bf16x8_to_f16x8(kreg[set][v], seen);
+                if (kv0 + 16 * v + kr <= wg_last_pos) mag = seen;
+            } else {
+                *reinterpret_cast<u32x4 *>(&ks[st][16 * v + kr][kc]) = kreg[set][v];
+            }
             u32x4 vv = vreg[set][v];
             const int p0 = kv0 + 16 * v + vh;      // position of this piece's first element
             if (p0 + 7 > wg_last_pos) {
@@ -145,6 +187,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
                     vv[e] = (p0 + 2 * e <= wg_last_pos ? vv[e] & 0x0000ffffu : 0u) |
                             (p0 + 2 * e + 1 <= wg_last_pos ? vv[e] & 0xffff0000u : 0u);
             }
+            if constexpr (F16) vv = bf16x8_to_f16x8(vv, mag);
             *reinterpret_cast<u32x4 *>(&vt[st][vd][16 * v + vh]) = vv;
         }
     };
@@ -169,9 +212,13 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
         __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int j = 0; j < 8; j++) {
-            const bf16x8 ka = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(krow + j * 8));
-            sc_t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qh[j], sc_t, 0, 0, 0);
-            sc_t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, ql[j], sc_t, 0, 0, 0);
+            const u32x4 ka = *reinterpret_cast<const u32x4 *>(krow + j * 8);
+            if constexpr (F16) {
+                sc_t = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, ka), __builtin_bit_cast(f16x8, qh[j]), sc_t, 0, 0, 0);
+            } else {
+                sc_t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka), __builtin_bit_cast(bf16x8, qh[j]), sc_t, 0, 0, 0);
+                sc_t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka), __builtin_bit_cast(bf16x8, ql[j]), sc_t, 0, 0, 0);
+            }
         }
         __builtin_amdgcn_s_setprio(0);
         // ---- online softmax; accumulator element i is row 8*(i/4) + 4*half + i%4 of the tile, which holds
@@ -206,7 +253,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
             for (int i = 0; i < 16; i += 2) {
                 const float p0 = fast_exp2(sc_t[i] - m_new), p1 = fast_exp2(sc_t[i + 1] - m_new);
                 psum += p0 + p1;
-                ph[i / 2] = split2_bf16(p0, p1, pl[i / 2]);
+                if constexpr (F16) ph[i / 2] = pack2_f16(p0, p1);      // p < 2^8: well inside fp16
+                else ph[i / 2] = split2_bf16(p0, p1, pl[i / 2]);
             }
             l = l * sc + psum;
             m = m_new;
@@ -226,12 +274,15 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
 #pragma unroll
             for (int mm = 0; mm < 2; mm++) {
                 // slot e of this lane <-> position kv0 + 16*mm + 8*half + e
-                const bf16x8 va = __builtin_bit_cast(
-                    bf16x8, *reinterpret_cast<const u32x4 *>(&vt[st][nt * 32 + l32][16 * mm + 8 * half]));
-                const bf16x8 pbh = __builtin_bit_cast(bf16x8, (u32x4){ph[4 * mm], ph[4 * mm + 1], ph[4 * mm + 2], ph[4 * mm + 3]});
-                const bf16x8 pbl = __builtin_bit_cast(bf16x8, (u32x4){pl[4 * mm], pl[4 * mm + 1], pl[4 * mm + 2], pl[4 * mm + 3]});
-                o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbh, o[nt], 0, 0, 0);
-                o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbl, o[nt], 0, 0, 0);
+                const u32x4 va = *reinterpret_cast<const u32x4 *>(&vt[st][nt * 32 + l32][16 * mm + 8 * half]);
+                const u32x4 pbh = (u32x4){ph[4 * mm], ph[4 * mm + 1], ph[4 * mm + 2], ph[4 * mm + 3]};
+                if constexpr (F16) {
+                    o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, va), __builtin_bit_cast(f16x8, pbh), o[nt], 0, 0, 0);
+                } else {
+                    const u32x4 pbl = (u32x4){pl[4 * mm], pl[4 * mm + 1], pl[4 * mm + 2], pl[4 * mm + 3]};
+                    o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va), __builtin_bit_cast(bf16x8, pbh), o[nt], 0, 0, 0);
+                    o[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va), __builtin_bit_cast(bf16x8, pbl), o[nt], 0, 0, 0);
+                }
             }
         }
         __builtin_amdgcn_s_setprio(0);
@@ -253,6 +304,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill(const float *__restrict
                 st ^= 1;
             }
         }
+    }
+    if constexpr (F16) {      // 0x4780 is 65536 as bf16: the first magnitude that fp16 cannot hold (also infinities and NaNs)
+        if (out_of_range || mag[0] >= 0x4780 || mag[1] >= 0x4780) *f16_flag = 1;
     }
     // the two halves of a query's scores were summed separately
     l += __shfl_xor(l, 32, WAVE);
@@ -344,13 +398,17 @@ size_t prefill_attention_scratch_bytes() {
 void launch_prefill_attention(const float *q, int q_stride, const uint16_t *pool, int Hkv, const int32_t *table,
                               int table_stride, const int32_t *tiles, int n_tiles, int H, int window, int max_pos,
                               float *out, void *scratch, size_t scratch_bytes, hipStream_t s, uint16_t *xs_hi,
-                              uint16_t *xs_lo) {
+                              uint16_t *xs_lo, int *f16_flag) {
     const float sl2 = 1.4426950408889634f / sqrtf((float)HD);
     const int ns = scratch ? prefill_attention_splits(n_tiles, H, max_pos, window, scratch_bytes) : 1;
     float *part_o = (float *)scratch;
     float *part_ml = part_o ? part_o + (size_t)n_tiles * 128 * H * ns * HD : nullptr;
-    LD_LAUNCH(k_attn_prefill, dim3(n_tiles, H, ns), dim3(256), 0, s, q, q_stride, pool, Hkv, table, table_stride,
-              (const int4 *)tiles, H, window, sl2, out, part_o, part_ml, xs_hi, xs_lo);
+    if (f16_flag)
+        LD_LAUNCH(k_attn_prefill<true>, dim3(n_tiles, H, ns), dim3(256), 0, s, q, q_stride, pool, Hkv, table, table_stride,
+                  (const int4 *)tiles, H, window, sl2, out, part_o, part_ml, xs_hi, xs_lo, f16_flag);
+    else
+        LD_LAUNCH(k_attn_prefill<false>, dim3(n_tiles, H, ns), dim3(256), 0, s, q, q_stride, pool, Hkv, table, table_stride,
+                  (const int4 *)tiles, H, window, sl2, out, part_o, part_ml, xs_hi, xs_lo, f16_flag);
     if (ns > 1)
         LD_LAUNCH(k_attn_prefill_merge, dim3(H, n_tiles * 128), dim3(128), 0, s, (const int4 *)tiles, H, ns, part_o,
                   part_ml, out, xs_hi, xs_lo);

@@ -387,7 +387,7 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
                 LD_TIMED(LD_PROF_ATTENTION, timed_void([&] {
                     ld::launch_prefill_attention(w.qkv, nqkv, (const uint16_t *)pool_l, Hkv, w.table, kv->max_blocks, d_tiles,
                                                  n_tiles, H, c.window, max_ctx - 1, w.attn, w.att_scratch,
-                                                 w.att_scratch_bytes, st, A, A + (size_t)T * nq);
+                                                 w.att_scratch_bytes, st, A, A + (size_t)T * nq, f16_flag);
                 }));
             const ld::GemmNext to_ffn{m.ffn_norm[l], c.rms_eps, B};
             const ld::GemmNext to_next{l + 1 < c.n_layers ? m.attn_norm[l + 1] : nullptr, c.rms_eps, B};
@@ -415,9 +415,9 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
                                                             max_ctx_dec, n_dec_rows, H, Hkv, hd, c.window, w.attn,
                                                             w.att_scratch, w.att_scratch_bytes, st));
         if (n_tiles)
-            LD_TIMED(LD_PROF_ATTENTION, ldk_prefill_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_tiles,
-                                                              n_tiles, H, Hkv, hd, c.window, max_ctx - 1, w.attn,
-                                                              w.att_scratch, w.att_scratch_bytes, st));
+            LD_TIMED(LD_PROF_ATTENTION, ldk_prefill_attention_f16(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_tiles,
+                                                                  n_tiles, H, Hkv, hd, c.window, max_ctx - 1, w.attn,
+                                                                  w.att_scratch, w.att_scratch_bytes, f16_flag, st));
         LD_TIMED(LD_PROF_WO, ld::linear_pass(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st, f16_flag));
         LD_TIMED(LD_PROF_GATE_UP, ld::linear_pass(m.wgate_up[l], c.dtype, w.x, m.ffn_norm[l], c.rms_eps, T, c.d_ffn, d, LDK_SWIGLU, w.act, w.lin_scratch,
                                                     w.lin_scratch_bytes, st, f16_flag));

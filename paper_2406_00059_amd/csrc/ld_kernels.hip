@@ -812,6 +812,14 @@ ld_status ldk_prefill_attention(const float *q, int32_t q_stride, const void *po
                                 const int32_t *table, int32_t table_stride, const int32_t *tiles, int32_t n_tiles,
                                 int32_t H, int32_t Hkv, int32_t hd, int32_t window, int32_t max_pos, float *out,
                                 void *scratch, size_t scratch_bytes, void *stream) {
+    return ldk_prefill_attention_f16(q, q_stride, pool_layer, dtype, table, table_stride, tiles, n_tiles, H, Hkv, hd, window,
+                                     max_pos, out, scratch, scratch_bytes, nullptr, stream);
+}
+
+ld_status ldk_prefill_attention_f16(const float *q, int32_t q_stride, const void *pool_layer, int32_t dtype,
+                                    const int32_t *table, int32_t table_stride, const int32_t *tiles, int32_t n_tiles,
+                                    int32_t H, int32_t Hkv, int32_t hd, int32_t window, int32_t max_pos, float *out,
+                                    void *scratch, size_t scratch_bytes, int32_t *overflow, void *stream) {
     if (!q || !pool_layer || !table || !tiles || !out || n_tiles < 0 || H <= 0 || Hkv <= 0 || H % Hkv || q_stride % 4 ||
         window < 0 || max_pos < 0)
         return ld::fail(LD_E_INVAL, "ldk_prefill_attention: bad argument");
@@ -819,7 +827,7 @@ ld_status ldk_prefill_attention(const float *q, int32_t q_stride, const void *po
         return ld::fail(LD_E_INVAL, "ldk_prefill_attention: needs a bf16 pool and head_dim 128");
     if (n_tiles == 0) return LD_OK;
     ld::launch_prefill_attention(q, q_stride, (const uint16_t *)pool_layer, Hkv, table, table_stride, tiles, n_tiles, H,
-                                 window, max_pos, out, scratch, scratch_bytes, (hipStream_t)stream);
+                                 window, max_pos, out, scratch, scratch_bytes, (hipStream_t)stream, nullptr, nullptr, overflow);
     return launched("k_attn_prefill");
 }
 

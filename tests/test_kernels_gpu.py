@@ -524,6 +524,63 @@ def test_linear_fp16_rows_sampled():
 
 
 @pytest.mark.parametrize("split", [False, True], ids=["whole", "kv-split"])
+@pytest.mark.parametrize("window", [0, 40, 200])
+@pytest.mark.parametrize("H,Hkv", [(4, 4), (8, 2)])
+def test_prefill_attention_fp16_form(H, Hkv, window, split):
+    """The form of chunk-prefill attention that the engine's long passes take (ldk_prefill_attention_f16: queries and
+    probabilities as one fp16 term, keys and values widened to fp16 exactly): the segments of
+    test_prefill_attention_segments, every row against the oracle's single-query attention.  What the form rounds
+    is q (2^-12 per element of a 128-term score of a few units: ~1e-3 in the exponent's argument) and p (2^-12):
+    bound 1e-3 of the largest output, thirty times the two-term bound and a third of what the cache's own bf16
+    rounding of a key moves a score by.  A key or value beyond the fp16 range at a position the walk reads, or a
+    query that is, raises the flag; the same values at positions no row sees do not."""
+    hd = 128
+    segs = [(37, 100), (0, 5), (1000, 300), (255, 1), (16, 32)]
+    lens = [p + n for p, n in segs]
+    table, pool, _ = _attention_case(31, lens, H, Hkv, hd, "bf16")
+    T = sum(n for _, n in segs)
+    q = gen.normal(31, 9, (T, H, hd), device=DEV)
+    tiles, row_seq, row_pos, r = [], [], [], 0
+    for s, (p0, n) in enumerate(segs):
+        for off in range(0, n, 128):
+            tiles.append([r + off, min(128, n - off), p0 + off, s])
+        row_seq += [s] * n; row_pos += list(range(p0, p0 + n)); r += n
+    tiles_d = torch.tensor(tiles, dtype=torch.int32, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    scratch = torch.empty(ld.ldk_prefill_attention_scratch_bytes(), dtype=torch.uint8, device=DEV) if split else None
+
+    def run(qq, pp):
+        out = torch.zeros(T, H, hd, device=DEV)
+        flag.zero_()
+        ld.ldk_prefill_attention_f16(qq, H * hd, device_pool(pp), table.to(DEV), tiles_d, H, Hkv, hd, out, max(row_pos), flag,
+                                     window=window, scratch=scratch)
+        torch.cuda.synchronize()
+        return out.cpu().numpy(), int(flag.item())
+
+    got, f = run(q, pool)
+    assert f == 0
+    out2 = torch.zeros(T, H, hd, device=DEV)
+    ld.ldk_prefill_attention(q, H * hd, device_pool(pool), table.to(DEV), tiles_d, H, Hkv, hd, out2, max(row_pos),
+                             window=window, scratch=scratch)
+    assert not np.array_equal(got, out2.cpu().numpy())      # the single-term form did run
+    ph = oracle.to_host_matrix(pool.reshape(pool.shape[0], -1)).reshape(-1)
+    ref = oracle.paged_attention(q.cpu().numpy(), ph, ph[Hkv * 16 * hd:], (2 * Hkv * 16 * hd, 16 * hd, hd),
+                                 table.numpy()[row_seq], [p + 1 for p in row_pos], Hkv, window=window)
+    err = np.max(np.abs(got - ref), axis=(1, 2)) / np.abs(ref).max()
+    assert 3e-5 < err.max() <= 1e-3, (err.max(), int(err.argmax()), row_pos[int(err.argmax())])
+    # out of range: the key of position 1100 of the third sequence (seen by its rows from 1100 on, inside every band)
+    blk, slot = int(table[2, 1100 // 16]), 1100 % 16
+    big = pool.clone(); big[blk, 0, Hkv - 1, slot, 5] = 7.0e4
+    assert run(q, big)[1] == 1
+    big = pool.clone(); big[blk, 1, 0, slot, 77] = -1.0e5
+    assert run(q, big)[1] == 1
+    # the last block of the second sequence (5 positions): slots 5..15 were never written and no row reads them as values;
+    # its keys there are read and masked, so a key counts, a value slot beyond the tile is zeroed before it is looked at
+    qb = q.clone(); qb[3, 1, 9] = 1.0e6
+    assert run(qb, pool)[1] == 1
+
+
+@pytest.mark.parametrize("split", [False, True], ids=["whole", "kv-split"])
 @pytest.mark.parametrize("window", [0, 1, 40, 128, 200, 5000])
 @pytest.mark.parametrize("H,Hkv", [(4, 4), (8, 2)])
 def test_prefill_attention_segments(H, Hkv, window, split):

@@ -238,9 +238,11 @@ ld_status ensure_pinned(ld_kv *kv) {
 
 // Enqueues one pass over `rows` (all rows' blocks are mapped) without waiting for it.  emit[i] = index of
 // the row whose logits / greedy token are wanted, in callback order; once step_ev[slot] has passed,
-// pin_out[slot * max_seqs + i] holds the tokens.  Rows [0, n_single) are one-row segments (decode rows);
-// the rest form multi-row prefill segments, each a run of consecutive rows of one sequence at consecutive
-// positions.  tok_from_prev: row t's input token is the token that the previous pass on this stream
+// pin_out[slot * max_seqs + i] holds the tokens.  The last n_single rows are one-row segments (decode rows);
+// the rows before them form multi-row prefill segments, each a run of consecutive rows of one sequence at
+// consecutive positions.  (The one-row segments come last because the rows past the last full 256-row tile of a
+// pass are the ones that the small-batch kernels take with both bf16 terms also when the rest of a long pass
+// goes with one fp16 term: with whole chunks in front these are the decode rows, which emit.)  tok_from_prev: row t's input token is the token that the previous pass on this stream
 // emitted for its row t (read on the device), not rows[t].tok.
 ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, const std::vector<int32_t> &emit,
                        hipStream_t st, float *logits_out, int slot, bool tok_from_prev, int *ops, bool allow_f16 = false) {
@@ -267,17 +269,18 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
     int n_tiles = 0;
     int32_t *pt = pm + 5 * T;
     if (mfma_attn) {
-        for (int t = n_single; t < T;) {
+        for (int t = 0; t < T - n_single;) {
             int e = t + 1;
-            while (e < T && e - t < 128 && rows[e].seq == rows[t].seq) e++;
+            while (e < T - n_single && e - t < 128 && rows[e].seq == rows[t].seq) e++;
             pt[4 * n_tiles] = t; pt[4 * n_tiles + 1] = e - t; pt[4 * n_tiles + 2] = rows[t].pos; pt[4 * n_tiles + 3] = rows[t].seq;
             n_tiles++;
             t = e;
         }
     }
-    const int n_dec_rows = mfma_attn ? n_single : T;   // rows that go through the single-query kernel
+    const int n_dec_rows = mfma_attn ? n_single : T;   // rows that go through the single-query kernel: [dec0, T)
+    const int dec0 = T - n_dec_rows;
     int max_ctx_dec = 1;
-    for (int t = 0; t < n_dec_rows; t++) max_ctx_dec = std::max(max_ctx_dec, rows[t].pos + 1);
+    for (int t = dec0; t < T; t++) max_ctx_dec = std::max(max_ctx_dec, rows[t].pos + 1);
     // sampling parameters of the emitting rows, only when some sequence samples: seeds (8-byte aligned),
     // temperatures, position the emitted token will take
     bool sampling = false;
@@ -378,10 +381,11 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
                 if (l == 0) ld::launch_norm_split(w.x, m.attn_norm[0], c.rms_eps, T, d, B, st);
                 ld::launch_gemm(mat(m.wqkv[l]), B, T, nqkv, d, ld::GEMM_STORE, w.qkv, st, &to_cache, f16_flag);
             }));
-            // attention writes the output projection's operand (A) directly: single-query rows first, then the tiles' rows
+            // attention writes the output projection's operand (A) directly: the single-query rows, then the tiles' rows
             if (n_dec_rows)
-                LD_TIMED(LD_PROF_ATTENTION, ld::paged_attention_split(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot,
-                                                                      d_ctx, max_ctx_dec, n_dec_rows, H, Hkv, hd, c.window, A,
+                LD_TIMED(LD_PROF_ATTENTION, ld::paged_attention_split(w.qkv + (size_t)dec0 * nqkv, nqkv, pool_l, c.dtype, w.table,
+                                                                      kv->max_blocks, d_slot + dec0, d_ctx + dec0, max_ctx_dec,
+                                                                      n_dec_rows, H, Hkv, hd, c.window, A + (size_t)dec0 * nq,
                                                                       w.att_scratch, w.att_scratch_bytes, st, T));
             if (n_tiles)
                 LD_TIMED(LD_PROF_ATTENTION, timed_void([&] {
@@ -411,9 +415,9 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
             LD_TIMED(LD_PROF_QKV, ldk_rope_kv_write(w.qkv, w.cos_sin, d_pos, d_slot, w.table, kv->max_blocks, pool_l, c.dtype, T, H, Hkv, hd, st));
         }
         if (n_dec_rows)
-            LD_TIMED(LD_PROF_ATTENTION, ldk_paged_attention(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_slot, d_ctx,
-                                                            max_ctx_dec, n_dec_rows, H, Hkv, hd, c.window, w.attn,
-                                                            w.att_scratch, w.att_scratch_bytes, st));
+            LD_TIMED(LD_PROF_ATTENTION, ldk_paged_attention(w.qkv + (size_t)dec0 * nqkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks,
+                                                            d_slot + dec0, d_ctx + dec0, max_ctx_dec, n_dec_rows, H, Hkv, hd, c.window,
+                                                            w.attn + (size_t)dec0 * nq, w.att_scratch, w.att_scratch_bytes, st));
         if (n_tiles)
             LD_TIMED(LD_PROF_ATTENTION, ldk_prefill_attention_f16(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_tiles,
                                                                   n_tiles, H, Hkv, hd, c.window, max_ctx - 1, w.attn,
@@ -539,7 +543,7 @@ ld_status run_step(ld_kv *kv, const std::vector<Feed> &feeds, void *stream, ld_t
     if (total_missing > (int64_t)kv->free_stack.size()) { ld::set_error("%s: out of KV blocks (%lld needed, %zu free)", who, (long long)total_missing, kv->free_stack.size()); return LD_E_NOMEM; }
 
     // --- reserve blocks (in argument order, logical order within a sequence) and build rows:
-    //     one-row feeds first (decode rows), then the multi-row prefill segments
+    //     the multi-row prefill segments first, then the one-row feeds (decode rows)
     std::vector<Row> rows;
     std::vector<int32_t> emit(feeds.size());
     rows.reserve(total_rows);
@@ -552,7 +556,7 @@ ld_status run_step(ld_kv *kv, const std::vector<Feed> &feeds, void *stream, ld_t
     // path, so that the rest fills whole tiles.
     auto peel_first = [&](int64_t n_rows) { return n_rows > 1 && n_rows % 128 == 1; };
     int n_single = 0;
-    for (int pass = 0; pass < 2; pass++)
+    for (int pass = 1; pass >= 0; pass--)
         for (size_t i = 0; i < feeds.size(); i++) {
             const Feed &f = feeds[i];
             Seq &q = kv->seqs[f.seq];

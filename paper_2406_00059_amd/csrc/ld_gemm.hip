@@ -910,6 +910,7 @@ BigPlan plan_big(int T, int N, int K, int epi, bool f16 = false) {
     if (forced && sscanf(forced, "%d,%d,%d", &f_wm, &f_bn, &f_ks) != 3) f_wm = 0;
     for (const Tile &tl : tiles) {
         if (f_wm && (tl.wm != f_wm || tl.bn != f_bn)) continue;
+        if (f16 && tl.bn != 256) continue;      // the fp16 form exists for the 256-wide weight tiles only
         const int bm = 64 * tl.wm, nout = swi ? tl.bn / 2 : tl.bn;
         const int n_tt = (T + bm - 1) / bm, n_nb = (N + nout - 1) / nout;
         const int max_ks = std::max(1, std::min(8, K / 32 / 8));   // at least eight chunks per slab

@@ -598,6 +598,11 @@ def main():
         for _ in range(3):
             ld.ldk_prefill_attention(q, H * hd, pool, table, tiles, H, shape.n_kv_heads, hd, ao, max(lens) - 1, scratch=scratch)
         torch.cuda.synchronize()
+        flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+        for _ in range(3):      # the form of passes of 512 rows or more: q and p as one fp16 term
+            ld.ldk_prefill_attention_f16(q, H * hd, pool, table, tiles, H, shape.n_kv_heads, hd, ao, max(lens) - 1, flag, scratch=scratch)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 0
         nominal = sum(sum(range(p0 + 1, p0 + n + 1)) for p0, n in segs) * H * hd * 4
         out["attention"] = {"tiles": len(tiles), "rows": Tq, "nominal_flops": nominal, "mfma_flops_with_split": 2 * nominal}
         print(json.dumps(out))

@@ -310,6 +310,44 @@ def test_7b_full_depth_batch32_with_mixed_step(models_7b):
     assert max(untouched) <= 5e-3
 
 
+def test_7b_full_depth_fresh_prompt_in_one_long_pass(models_7b, monkeypatch):
+    """Where the fp16 rows of a long pass weigh most: a fresh sequence whose whole cache comes out of one pass of
+    640 rows (every key and value the next tokens attend to was computed from activations rounded to fp16), all 32
+    layers.  Logits of the prompt's last row and of three decode steps against the oracle: within 2e-2 with fp16
+    rows (measured 1.1e-2 .. 1.4e-2; 1.0e-2 .. 1.2e-2 on a 1280-token prompt), within 5e-3 with two terms
+    (LD_GEMM_F16=0); tokens equal, or near-ties by the rule of helpers.NearTies."""
+    shape, seed, n = LLAMA7B, SEED_BASE + 7, 640
+    omodel, gmodel = models_7b
+    glong = ld.Model(shape, gmodel.weights, max_chunk=1024)      # the same weights; only the chunk limit differs
+    tk = prompt(seed, 5, n, shape.vocab)
+    ref, out = [], {}
+    for f16 in ("1", "0"):
+        monkeypatch.setenv("LD_GEMM_F16", f16)
+        P = Pair(shape, seed, n_blocks=n // 16 + 8, max_tokens=n + 16, max_seqs=2, max_blocks=n // 16 + 4,
+                 models=(omodel, glong))
+        s = P.alloc()
+        ties, errs, sink = NearTies(), [], Tokens()
+        for step in range(4):
+            if step == 0:
+                rc, lg = ld.ld_prefill(P.gkv.h, s, tk, callback=sink, logits_vocab=P.V)
+                if not ref:
+                    ref.append(P.okv.prefill(s, tk)[1:])
+            else:
+                rc, lg = ld.ld_decode_step(P.gkv.h, [s], callback=sink, logits_vocab=P.V)
+                lg = lg[0]
+                if len(ref) <= step:
+                    ref.append(P.okv.decode(s)[1:])
+            t_o, lg_o = ref[step]
+            errs.append(rel_err(lg, lg_o))
+            e_abs = ties.measured(lg, lg_o)
+            if sink.last()[0] != t_o:
+                ties.check(("fresh prompt", f16, step), lg_o, t_o, sink.last()[0], e_abs)
+                ld.ld_kv_assume(P.gkv.h, s, 0, t_o)
+        out[f16] = errs
+        print("640-row fresh prompt, LD_GEMM_F16 =", f16, "logits rel err", ["%.1e" % e for e in errs], "near-ties", ties.cases)
+    assert max(out["1"]) <= 2e-2 and max(out["0"]) <= 5e-3 and max(out["0"]) < max(out["1"])
+
+
 def test_13b_width_batch64_and_2048_row_chunk_over_a_200GB_sized_pool():
     """The 13B workload's launch configuration at depth 2: 64 sequences over a pool of 15,258 blocks (what 200 GB
     hold at 40 layers), one 2048-token chunk per step.  Step 1 replaces a finished request: its blocks are

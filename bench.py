@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--no-batch32", action="store_true", help="skip the batch-32 continuous-batching leg")
     ap.add_argument("--no-attention-microbench", action="store_true", help="skip the decode-attention micro-benchmark leg")
     ap.add_argument("--no-gqa", action="store_true", help="skip the batch-32 leg on the grouped-KV 7B shape")
+    ap.add_argument("--no-f16-image", action="store_true",
+                    help="do not give the models the fp16 copy of their layer matrices (passes of 512+ rows then widen "
+                         "the bf16 weights in the kernel)")
     ap.add_argument("--no-13b", action="store_true", help="skip the 13B-shaped batch-64 leg (200 GB KV pool)")
     ap.add_argument("--steps-13b", type=int, default=16, help="timed steps of the 13B leg (the workload has 64)")
     ap.add_argument("--only-batch32", action="store_true", help="debug: run only the batch-32 leg (prints its dict)")
@@ -285,6 +288,7 @@ def run_batch32(args, ld, torch, shape, model):
         pool[l] = gen.normal(seed, 1000 + l, tuple(pool[l].shape), device="cuda").to(pdt)
     kv = ld.KV(model, total_blocks, T_max, B, nblk_seq, pool=pool)
     stream = torch.cuda.current_stream()
+    f16_image = (not args.no_f16_image) and ld_gemm_terms(T_max) == 1 and model.attach_f16_image(stream)
     seqs = []
     for b in range(B):
         s = ld.ld_kv_alloc(kv.h, 0)
@@ -362,6 +366,7 @@ def run_batch32(args, ld, torch, shape, model):
         # MFMA fractions: first on the method's flops (2 * rows * weight elements), then on what the matrix cores
         # execute (twice that when the float32 activations go in as two bf16 terms, once in the fp16 form)
         "mixed_step_gemm_terms": ld_gemm_terms(rows_mixed),
+        "f16_weight_image_GB": round(ld.ld_model_f16_image_bytes(model.h) / 1e9, 2) if f16_image else 0,
         "mixed_step_gemm_TFLOPs": round(gemm_nominal / (gemm_ms_mixed * 1e-3) / 1e12, 1),
         "mixed_step_gemm_mfma_frac": round(gemm_nominal / (gemm_ms_mixed * 1e-3) / MFMA_PEAK, 4),
         "mixed_step_gemm_mfma_frac_executed": round(ld_gemm_terms(rows_mixed) * gemm_nominal / (gemm_ms_mixed * 1e-3) / MFMA_PEAK, 4),
@@ -374,6 +379,8 @@ def run_batch32(args, ld, torch, shape, model):
                      "traffic_over_algorithmic": attention_traffic_ratio() if not shape.window and shape.n_kv_heads == shape.n_heads else None},
     }
     kv.close()
+    if f16_image:
+        model.detach_f16_image()
     return out
 
 
@@ -447,6 +454,7 @@ def run_13b(args, ld, torch):
         pool[l].normal_(0.0, 1.0)
     kv = ld.KV(model, n_blocks, B + chunk, B, nblk_seq, pool=pool)
     stream = torch.cuda.current_stream()
+    f16_image = (not args.no_f16_image) and ld_gemm_terms(B - 1 + chunk) == 1 and model.attach_f16_image(stream)
     pend = gen.randint(seed, 2, 0, shape.vocab - 1, B).tolist()
     seqs = []
     for b in range(B):
@@ -492,6 +500,7 @@ def run_13b(args, ld, torch):
         "gemm_TFLOPs": round(gemm_flops / (gemm_ms * 1e-3) / 1e12, 1),
         "gemm_mfma_frac": round(gemm_flops / (gemm_ms * 1e-3) / MFMA_PEAK, 4),
         "gemm_terms": ld_gemm_terms(B - 1 + chunk),
+        "f16_weight_image_GB": round(ld.ld_model_f16_image_bytes(model.h) / 1e9, 2) if f16_image else 0,
         "gemm_mfma_frac_executed": round(ld_gemm_terms(B - 1 + chunk) * gemm_flops / (gemm_ms * 1e-3) / MFMA_PEAK, 4),
         "attention_ms_one_step": round(prof["attention"][0], 3),
         "steps_timed": steps, "n_layers": shape.n_layers,
@@ -573,6 +582,14 @@ def main():
                     ld.ldk_linear_f16(W, x, y, flag, epi, scratch=scratch)
                 torch.cuda.synchronize()
                 assert int(flag.item()) == 0
+                # the same with the matrix's fp16 image (nothing widened inside the kernel)
+                Wh = torch.empty(rows, K, dtype=torch.float16, device="cuda")
+                ld.ldk_weights_to_f16(W, Wh, flag)
+                for _ in range(3):
+                    ld.ldk_linear_f16(W, x, y, flag, epi, scratch=scratch, W_f16=Wh)
+                torch.cuda.synchronize()
+                assert int(flag.item()) == 0
+                del Wh
                 out["gemm"].append({"rows": T, "matrix": name, "weight_rows": rows, "K": K,
                                     "nominal_flops": 2 * T * rows * K, "mfma_flops_with_split": 4 * T * rows * K,
                                     "mfma_flops_fp16_rows": 2 * T * rows * K})

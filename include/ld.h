@@ -33,7 +33,7 @@
  *    chunks, steps that mix decode rows with chunks), whose big-tile products take them rounded to fp16 (11
  *    bits) as long as every value of the pass and of the layer matrices lies within the fp16 range (+-65504);
  *    a pass that meets a larger value is repeated with two terms.  LD_GEMM_F16=0 in the environment keeps two
- *    terms everywhere.
+ *    terms everywhere.  ld_model_attach_f16_image trades memory for time in those passes, with equal results.
  *  - Sequence state: n_cached tokens have keys/values in the pool; `pending` is a token
  *    that was emitted but not fed yet (none right after ld_kv_alloc).
  */
@@ -109,6 +109,20 @@ typedef int (*ld_token_cb)(void *user, ld_seq seq, int32_t token, int32_t pos);
  * kv_block 16, d_model and d_ffn multiples of 8, n_heads a multiple of n_kv_heads. */
 ld_status ld_model_create(const ld_model_config *cfg, const ld_weights *w, ld_model **out);
 void ld_model_destroy(ld_model *m);
+
+/* Optional, bf16 models: an fp16 copy of the layer matrices for the passes that take the fp16 form (see Arithmetic
+ * above).  Without it those passes widen every bf16 weight fragment to fp16 on its way to the matrix cores, in every
+ * wave that reads it; with it they read fp16 directly.  Same products either way: tokens and logits are bit-equal.
+ * The price is device memory: ld_model_f16_image_bytes(m) = 2 bytes per layer-matrix entry (0 for float32 models),
+ * i.e. the layers' own size once more.
+ * buf (device memory, 16-byte aligned, at least ld_model_f16_image_bytes(m) + 256 bytes) stays the caller's and must
+ * live until the model is destroyed or the image is detached (buf NULL: detach; bytes ignored).  The call fills it
+ * on `stream` from the weights as they are now, waits for the stream, and sets *in_range (may be NULL) to 1 when
+ * every entry lies within +-65504.  Otherwise (*in_range 0) the buffer is not used, nor is the fp16 form: this model
+ * then keeps two bf16 terms in every pass.  Weights changed later need a new call.  Not to be called while a pass of
+ * this model is in flight. */
+size_t ld_model_f16_image_bytes(const ld_model *m);
+ld_status ld_model_attach_f16_image(ld_model *m, void *buf, size_t bytes, void *stream, int32_t *in_range);
 
 /* Bytes of the KV pool for n_blocks blocks.  Pool layout (element type cfg.dtype):
  *   keys    [layer][block][0][kv_head][slot 0..15][head_dim]

@@ -55,10 +55,21 @@ ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *
  * way to the matrix cores, which is exact for 2^-14 <= |w| <= 65504.  Other row counts and shapes: exactly
  * ldk_linear.  overflow (device memory, 4 bytes, the caller clears it) is set to 1 when the matrix or an
  * activation holds a value beyond +-65504 or not a number; y is then not to be used (the engine repeats such a
- * pass with ldk_linear's arithmetic).  scratch: ldk_linear_scratch_bytes(...) bytes. */
-ld_status ldk_linear_f16(const void *W, const float *x, const float *g, float eps, int32_t T, int32_t N, int32_t K,
-                         int32_t epilogue, float *y, void *scratch, size_t scratch_bytes, int32_t *overflow,
-                         void *stream);
+ * pass with ldk_linear's arithmetic).  scratch: ldk_linear_scratch_bytes(...) bytes.
+ * W_f16 (device memory, may be NULL): the matrix as fp16, same layout as W, written by ldk_weights_to_f16 with its
+ * overflow flag left clear.  The rows that take the fp16 form then read it in W's place and widen nothing on the
+ * way (the other rows, e.g. those past a multiple of 256, still read W); the matrix is not looked at again.  The
+ * products are those of the values W holds either way: y is bit-equal with and without the image. */
+ld_status ldk_linear_f16(const void *W, const void *W_f16, const float *x, const float *g, float eps, int32_t T,
+                         int32_t N, int32_t K, int32_t epilogue, float *y, void *scratch, size_t scratch_bytes,
+                         int32_t *overflow, void *stream);
+
+/* out[i] = W[i] as fp16 for the n entries of a bf16 matrix (n a multiple of 8; both device memory, out n * 2
+ * bytes, not overlapping W): exact for 2^-14 <= |w| <= 65504, smaller magnitudes lose their low bits (truncated
+ * toward zero).  overflow (device memory, 4 bytes, the caller clears it) is set to 1 when an entry lies beyond
+ * +-65504 or is not a number; the image is then not to be used.  The engine keeps such an image of every layer
+ * matrix from its first pass of 512 rows or more on (see ld.h, Arithmetic). */
+ld_status ldk_weights_to_f16(const void *W, int64_t n, void *out, int32_t *overflow, void *stream);
 
 /* cos_sin[t, i] = (cos, sin)(pos[t] * rope_base^(-2i/hd)) for i < hd/2, as float32 pairs; the
  * angle is formed in float64 so that large positions lose no accuracy.  hd is 64 or 128. */

@@ -19,10 +19,10 @@ __all__ = [
     "LD_OK", "LD_E_INVAL", "LD_E_NOMEM", "LD_E_STATE", "LD_E_HIP", "LD_E_RANGE", "LD_F32", "LD_BF16",
     "LD_CB_CONTINUE", "LD_CB_ABORT", "LD_CB_PAUSE",
     "LDK_STORE", "LDK_ADD", "LDK_SWIGLU", "LIB_PATH", "lib", "LdError", "ld_model_config", "ld_weights",
-    "ld_token_cb", "ld_model_create", "ld_model_destroy", "ld_kv_bytes", "ld_workspace_bytes", "ld_kv_create",
+    "ld_token_cb", "ld_model_create", "ld_model_destroy", "ld_model_f16_image_bytes", "ld_model_attach_f16_image", "ld_kv_bytes", "ld_workspace_bytes", "ld_kv_create",
     "ld_kv_destroy", "ld_kv_alloc", "ld_kv_map", "ld_kv_free", "ld_kv_block_table", "ld_kv_len",
     "ld_kv_free_blocks", "ld_kv_assume", "ld_kv_swap_bytes", "ld_kv_swap_out", "ld_kv_swap_in", "ld_kv_fork", "ld_kv_trim", "ld_kv_set_sampling", "ld_prefill", "ld_decode_step", "ld_decode_run", "ld_step_mixed", "ld_last_error", "ld_kv_profile", "ld_kv_profile_read", "ld_profile", "LD_PROF_NAMES",
-    "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_f16", "ldk_prefill_attention_f16", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
+    "ldk_embed", "ldk_rmsnorm", "ldk_linear", "ldk_linear_f16", "ldk_weights_to_f16", "ldk_prefill_attention_f16", "ldk_linear_scratch_bytes", "ldk_rope_table", "ldk_rope_kv_write", "ldk_qkv_rope",
     "ldk_attention_scratch_bytes", "ldk_paged_attention", "ldk_static_scratch_bytes", "ldk_paged_attention_static",
     "ldk_prefill_attention_scratch_bytes",
     "ldk_prefill_attention", "ldk_argmax", "ldk_sample", "Model", "KV",
@@ -64,6 +64,8 @@ _i32p, _f32p, _vp = C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_void_p
 _SIGS = {
     "ld_model_create": (C.c_int, [C.POINTER(ld_model_config), C.POINTER(ld_weights), C.POINTER(_vp)]),
     "ld_model_destroy": (None, [_vp]),
+    "ld_model_f16_image_bytes": (C.c_size_t, [_vp]),
+    "ld_model_attach_f16_image": (C.c_int, [_vp, _vp, C.c_size_t, _vp, _i32p]),
     "ld_kv_bytes": (C.c_size_t, [_vp, C.c_int64]),
     "ld_workspace_bytes": (C.c_size_t, [_vp, C.c_int32, C.c_int32, C.c_int32]),
     "ld_kv_create": (C.c_int, [_vp, _vp, C.c_int64, _vp, C.c_size_t, C.c_int32, C.c_int32, C.c_int32, C.POINTER(_vp)]),
@@ -95,8 +97,9 @@ _SIGS = {
     "ldk_linear_scratch_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "ldk_linear": (C.c_int, [_vp, C.c_int32, _vp, _vp, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp,
                              C.c_size_t, _vp]),
-    "ldk_linear_f16": (C.c_int, [_vp, _vp, _vp, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp,
+    "ldk_linear_f16": (C.c_int, [_vp, _vp, _vp, _vp, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp,
                                 C.c_size_t, _vp, _vp]),
+    "ldk_weights_to_f16": (C.c_int, [_vp, C.c_int64, _vp, _vp, _vp]),
     "ldk_rope_table": (C.c_int, [_vp, C.c_int32, C.c_int32, C.c_float, _vp, _vp]),
     "ldk_rope_kv_write": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_int32, _vp, C.c_int32, C.c_int32, C.c_int32,
                                     C.c_int32, C.c_int32, _vp]),
@@ -177,6 +180,17 @@ def ld_model_create(cfg: ld_model_config, w: ld_weights):
 
 def ld_model_destroy(m):
     lib().ld_model_destroy(m)
+
+
+def ld_model_f16_image_bytes(m):
+    return lib().ld_model_f16_image_bytes(m)
+
+
+def ld_model_attach_f16_image(m, buf, stream=None):
+    """Returns True when the layer matrices lie within the fp16 range (the image is then in use)."""
+    ok = C.c_int32(0)
+    _check(lib().ld_model_attach_f16_image(m, _ptr(buf), _nbytes(buf), _stream(stream), C.byref(ok)))
+    return bool(ok.value)
 
 
 def ld_kv_bytes(m, n_blocks):
@@ -367,11 +381,15 @@ def ldk_linear(W, x, y, epilogue=LDK_STORE, g=None, eps=0.0, scratch=None, strea
                             _ptr(scratch), _nbytes(scratch), _stream(stream)))
 
 
-def ldk_linear_f16(W, x, y, overflow, epilogue=LDK_STORE, g=None, eps=0.0, scratch=None, stream=None):
+def ldk_linear_f16(W, x, y, overflow, epilogue=LDK_STORE, g=None, eps=0.0, scratch=None, stream=None, W_f16=None):
     T, K = x.shape
     N = y.shape[1]
-    _check(lib().ldk_linear_f16(_ptr(W), _ptr(x), _ptr(g), eps, T, N, K, epilogue, _ptr(y), _ptr(scratch),
+    _check(lib().ldk_linear_f16(_ptr(W), _ptr(W_f16), _ptr(x), _ptr(g), eps, T, N, K, epilogue, _ptr(y), _ptr(scratch),
                                 _nbytes(scratch), _ptr(overflow), _stream(stream)))
+
+
+def ldk_weights_to_f16(W, out, overflow, stream=None):
+    _check(lib().ldk_weights_to_f16(_ptr(W), W.numel(), _ptr(out), _ptr(overflow), _stream(stream)))
 
 
 def ldk_rope_table(pos, hd, rope_base, cos_sin, stream=None):
@@ -462,10 +480,27 @@ class Model:
                             *[C.cast(self._tabs[k], C.POINTER(C.c_void_p)) for k in
                               ("attn_norm", "wqkv", "wo", "ffn_norm", "wgate_up", "wdown")])
         self.h = ld_model_create(self.cfg, self.w)
+        self.f16_image = None
+
+    def attach_f16_image(self, stream=None):
+        """Allocates (torch, device memory) and attaches the fp16 copy of the layer matrices; True if it is in use."""
+        n = ld_model_f16_image_bytes(self.h)
+        if n == 0:
+            return False
+        self.f16_image = torch.empty(n + 256, dtype=torch.uint8, device=self.weights["wqkv"][0].device)
+        ok = ld_model_attach_f16_image(self.h, self.f16_image, stream)
+        if not ok:
+            self.detach_f16_image()
+        return ok
+
+    def detach_f16_image(self):
+        _check(lib().ld_model_attach_f16_image(self.h, None, 0, None, None))
+        self.f16_image = None
 
     def close(self):
         if self.h:
             ld_model_destroy(self.h); self.h = None
+        self.f16_image = None
 
     def __del__(self):
         try:

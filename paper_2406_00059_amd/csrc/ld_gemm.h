@@ -35,13 +35,17 @@ void launch_norm_split(const float *x, const float *g, float eps, int T, int K, 
 // (gemm_f16_rows), i.e. the rows of prefill chunks; the rows of the split image that take this form are overwritten
 // with their fp16 values.  The caller has made sure that the matrix holds nothing beyond the fp16 range
 // (launch_weight_range_check); *f16_flag (device memory) is set to 1 when an activation does not fit, and the
-// results of the pass are then to be thrown away and the pass repeated without the flag.
+// results of the pass are then to be thrown away and the pass repeated without the flag.  W16 != nullptr: W's fp16
+// image (launch_weight_to_f16), read in W's place by the rows that take the fp16 form, which otherwise turn every
+// weight fragment into fp16 on its way to the matrix cores; same values either way, bit-equal results.
 struct GemmNext { const float *g; float eps; uint16_t *xs; const RopeKvArgs *rope = nullptr; };
 void launch_gemm(const uint16_t *W, uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s,
-                 const GemmNext *next = nullptr, int *f16_flag = nullptr);
+                 const GemmNext *next = nullptr, int *f16_flag = nullptr, const uint16_t *W16 = nullptr);
 bool gemm_f16_rows(int T, int N, int K, int epi);
 // *flag (device memory) = 1 if the bf16 matrix W (n elements, a multiple of 8) holds a value beyond +-65504 or not a number.
 void launch_weight_range_check(const uint16_t *W, int64_t n, int *flag, hipStream_t s);
+// The same check, and out[n] = W as fp16 (exact where the flag stays clear, values below 2^-14 in magnitude aside).
+void launch_weight_to_f16(const uint16_t *W, int64_t n, uint16_t *out, int *flag, hipStream_t s);
 
 // Skinny product alone (T <= 32 rows, K a multiple of 128): partial[z][t][row] for the skinny_slabs(K)
 // 512-wide K slabs z; the caller adds the slabs in order.

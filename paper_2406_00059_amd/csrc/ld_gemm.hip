@@ -138,6 +138,21 @@ __global__ __launch_bounds__(256) void k_weight_range(const bf16_t *__restrict__
     if (big) *flag = 1;
 }
 
+// The same look at a matrix, and its fp16 image written beside it (exact wherever *flag stays clear, up to values
+// below 2^-14 in magnitude).
+__global__ __launch_bounds__(256) void k_weight_to_f16(const bf16_t *__restrict__ w, int64_t n8, uint16_t *__restrict__ out,
+                                                       int *__restrict__ flag) {
+    bool big = false;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (int64_t)gridDim.x * 256) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(w + i * 8));
+#pragma unroll
+        for (int e = 0; e < 4; e++)
+            big = big || !(fabsf(__uint_as_float(v[e] << 16)) <= F16_LIMIT) || !(fabsf(__uint_as_float(v[e] & 0xffff0000u)) <= F16_LIMIT);
+        *reinterpret_cast<f16x8 *>(out + i * 8) = bf16x8_to_f16x8(v);
+    }
+    if (big) *flag = 1;
+}
+
 template <int TT, int WC, int KCH, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
                                                    const bf16_t *__restrict__ xlo, int T, int N, int K,
@@ -595,7 +610,7 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_big(const bf16_t *__restrict_
 // rounded to fp16 (11 significant bits; xhi then points at a [T, K] fp16 matrix), the bf16 weights turned into
 // fp16 on their way from LDS to the matrix cores (exact for 2^-14 <= |w| < 65520, which the launcher has checked
 // on the whole matrix): half the matrix-core work and two thirds of the operand traffic of the two-term form.
-template <int WM, int BN, int S, int EPI, int WN, bool F16>
+template <int WM, int BN, int S, int EPI, int WN, int F16>
 __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
                                                        const bf16_t *__restrict__ xlo, int T, int N, int K,
                                                        float *__restrict__ y, int n_ttiles, int ks,
@@ -686,7 +701,8 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
         if constexpr (F16) {
             f16x8 wv[WCT];
 #pragma unroll
-            for (int wc = 0; wc < WCT; wc++) wv[wc] = bf16x8_to_f16x8(f.bw[wc]);
+            for (int wc = 0; wc < WCT; wc++)
+                wv[wc] = F16 == 2 ? __builtin_bit_cast(f16x8, f.bw[wc]) : bf16x8_to_f16x8(f.bw[wc]);
 #pragma unroll
             for (int tt = 0; tt < 2; tt++)
 #pragma unroll
@@ -1053,7 +1069,7 @@ void launch_gemm_skinny(const uint16_t *W, const uint16_t *xhi, const uint16_t *
 // One launch of the big-tile kernel over output columns [col0, col1) with split factor ks (+ its reduction).
 static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
                             float *partial, int wm, int bn, int n_ttiles, int ks, int col0, int col1, hipStream_t s,
-                            bool reduce, bf16_t *hi_out, bf16_t *lo_out, bool f16) {
+                            bool reduce, bf16_t *hi_out, bf16_t *lo_out, int f16) {
     const int nout = epi == GEMM_SWIGLU ? bn / 2 : bn;
     const int n_nblocks = (col1 - col0 + nout - 1) / nout;
     const int grid = ((n_nblocks + 7) / 8) * 8 * n_ttiles * ks;
@@ -1079,8 +1095,9 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
     } while (0)
 #define LD_DMA(WM_, BN_, S_, EPI_, WN_)                                                                                \
     do {                                                                                                               \
-        if (f16) LD_DMA_M(WM_, BN_, S_, EPI_, WN_, true);                                                              \
-        else LD_DMA_M(WM_, BN_, S_, EPI_, WN_, false);                                                                 \
+        if (f16 == 2) LD_DMA_M(WM_, BN_, S_, EPI_, WN_, 2);                                                            \
+        else if (f16) LD_DMA_M(WM_, BN_, S_, EPI_, WN_, 1);                                                            \
+        else LD_DMA_M(WM_, BN_, S_, EPI_, WN_, 0);                                                                     \
         if (ks > 1 && reduce)                                                                                          \
             LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1, hi_out, lo_out); \
     } while (0)
@@ -1129,9 +1146,11 @@ static bool f16_plan_ok(const BigPlan &p, int K) {
 bool gemm_f16_rows(int T, int N, int K, int epi) { return T > 64 && f16_plan_ok(plan_big(T, N, K, epi, true), K); }
 
 // f16_flag != nullptr (more than 64 rows, gemm_f16_rows): the rows' images are turned into one fp16 image in place
-// and multiplied in the single-term form; *f16_flag is set if an activation does not fit.
+// and multiplied in the single-term form; *f16_flag is set if an activation does not fit.  W16: the matrix's fp16
+// image where the caller keeps one (the kernel then reads it in W's place and converts nothing), else nullptr.
 static void gemm_rows(const uint16_t *W, bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
-                      float *partial, hipStream_t s, const RowsNext *nx = nullptr, int *f16_flag = nullptr) {
+                      float *partial, hipStream_t s, const RowsNext *nx = nullptr, int *f16_flag = nullptr,
+                      const uint16_t *W16 = nullptr) {
     const bool chain_rope = nx && epi == GEMM_STORE && nx->rope;
     const bool chain_add = (nx && epi == GEMM_ADD) || chain_rope;      // a finishing kernel replaces the split-K reduction
     bf16_t *ho = nx && epi == GEMM_SWIGLU ? nx->hi : nullptr, *lo_o = nx && epi == GEMM_SWIGLU ? nx->lo : nullptr;
@@ -1157,8 +1176,9 @@ static void gemm_rows(const uint16_t *W, bf16_t *hi, const bf16_t *lo, int T, in
         return;
     }
     if (T > 64) {
-        const bool f16 = f16_flag != nullptr;
-        const BigPlan p = plan_big(T, N, K, epi, f16);
+        const int f16 = f16_flag ? (W16 ? 2 : 1) : 0;
+        const BigPlan p = plan_big(T, N, K, epi, f16 != 0);
+        if (f16 == 2) W = W16;
         if (f16) {
             const int64_t n8 = (int64_t)T * K / 8;
             LD_LAUNCH(k_split_to_f16, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s, hi, lo, n8, f16_flag);
@@ -1180,7 +1200,7 @@ static void gemm_rows(const uint16_t *W, bf16_t *hi, const bf16_t *lo, int T, in
 }
 
 void launch_gemm(const uint16_t *W, uint16_t *xs, int T, int N, int K, int epi, float *y, hipStream_t s,
-                 const GemmNext *next, int *f16_flag) {
+                 const GemmNext *next, int *f16_flag, const uint16_t *W16) {
     float *partial = (float *)((char *)xs + gemm_split_bytes(T, K));
     bf16_t *hi = xs, *lo = xs + (size_t)T * K;
     // the rows beyond a multiple of 256 that the cost model sends through the small-batch kernels keep both terms
@@ -1196,7 +1216,7 @@ void launch_gemm(const uint16_t *W, uint16_t *xs, int T, int N, int K, int epi, 
         b = {next->g, next->eps, next->xs ? a.hi + (size_t)(T - r) * N : nullptr, next->xs ? a.lo + (size_t)(T - r) * N : nullptr,
              next->rope, T - r};
     }
-    gemm_rows(W, hi, lo, T - r, N, K, epi, y, partial, s, next ? &a : nullptr, f16_flag);
+    gemm_rows(W, hi, lo, T - r, N, K, epi, y, partial, s, next ? &a : nullptr, f16_flag, W16);
     // the tail reuses the partial-sum scratch: the stream orders it behind the main part's reduction
     if (r) gemm_rows(W, hi + (size_t)(T - r) * K, lo + (size_t)(T - r) * K, r, N, K, epi, y + (size_t)(T - r) * N, partial, s,
                      next ? &b : nullptr);
@@ -1204,6 +1224,10 @@ void launch_gemm(const uint16_t *W, uint16_t *xs, int T, int N, int K, int epi, 
 
 void launch_weight_range_check(const uint16_t *W, int64_t n, int *flag, hipStream_t s) {
     LD_LAUNCH(k_weight_range, dim3(1024), dim3(256), 0, s, W, n / 8, flag);
+}
+
+void launch_weight_to_f16(const uint16_t *W, int64_t n, uint16_t *out, int *flag, hipStream_t s) {
+    LD_LAUNCH(k_weight_to_f16, dim3(1024), dim3(256), 0, s, W, n / 8, out, flag);
 }
 
 }  // namespace ld

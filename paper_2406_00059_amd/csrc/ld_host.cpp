@@ -38,6 +38,8 @@ struct ld_model {
     const float *final_norm;
     std::vector<const float *> attn_norm, ffn_norm;
     std::vector<const void *> wqkv, wo, wgate_up, wdown;
+    std::vector<const uint16_t *> h_qkv, h_wo, h_gate_up, h_down;   // fp16 images in the caller's buffer (ld_model_attach_f16_image), or empty
+    size_t layer_matrix_elems() const { return ((size_t)nqkv() + nq()) * c.d_model + (size_t)3 * c.d_ffn * c.d_model; }
     int nq() const { return c.n_heads * c.head_dim; }
     int nkv() const { return c.n_kv_heads * c.head_dim; }
     int nqkv() const { return nq() + 2 * nkv(); }
@@ -372,6 +374,7 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
         // the normalised operand of the GEMM after it (into B), so no separate norm/split pass runs between them.
         uint16_t *A = (uint16_t *)w.lin_scratch, *B = (uint16_t *)w.lin_scratch2;
         auto mat = [](const void *p) { return (const uint16_t *)p; };
+        auto img = [&](const std::vector<const uint16_t *> &v, int l) { return f16_flag && !v.empty() ? v[l] : nullptr; };
         for (int l = 0; l < c.n_layers; l++) {
             void *pool_l = kv->pool + (size_t)l * layer_bytes;
             // the kernel that finishes the q-k-v rows also rotates them and appends k, v to the cache
@@ -379,7 +382,7 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
             const ld::GemmNext to_cache{nullptr, 0.f, nullptr, &rk};
             LD_TIMED(LD_PROF_QKV, timed_void([&] {
                 if (l == 0) ld::launch_norm_split(w.x, m.attn_norm[0], c.rms_eps, T, d, B, st);
-                ld::launch_gemm(mat(m.wqkv[l]), B, T, nqkv, d, ld::GEMM_STORE, w.qkv, st, &to_cache, f16_flag);
+                ld::launch_gemm(mat(m.wqkv[l]), B, T, nqkv, d, ld::GEMM_STORE, w.qkv, st, &to_cache, f16_flag, img(m.h_qkv, l));
             }));
             // attention writes the output projection's operand (A) directly: the single-query rows, then the tiles' rows
             if (n_dec_rows)
@@ -395,23 +398,24 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
                 }));
             const ld::GemmNext to_ffn{m.ffn_norm[l], c.rms_eps, B};
             const ld::GemmNext to_next{l + 1 < c.n_layers ? m.attn_norm[l + 1] : nullptr, c.rms_eps, B};
-            LD_TIMED(LD_PROF_WO, timed_void([&] { ld::launch_gemm(mat(m.wo[l]), A, T, d, nq, ld::GEMM_ADD, w.x, st, &to_ffn, f16_flag); }));
+            LD_TIMED(LD_PROF_WO, timed_void([&] { ld::launch_gemm(mat(m.wo[l]), A, T, d, nq, ld::GEMM_ADD, w.x, st, &to_ffn, f16_flag, img(m.h_wo, l)); }));
             const ld::GemmNext to_down{nullptr, 0.f, A};      // the gated activation goes straight into the down projection's operand
-            LD_TIMED(LD_PROF_GATE_UP, timed_void([&] { ld::launch_gemm(mat(m.wgate_up[l]), B, T, c.d_ffn, d, ld::GEMM_SWIGLU, w.act, st, &to_down, f16_flag); }));
+            LD_TIMED(LD_PROF_GATE_UP, timed_void([&] { ld::launch_gemm(mat(m.wgate_up[l]), B, T, c.d_ffn, d, ld::GEMM_SWIGLU, w.act, st, &to_down, f16_flag, img(m.h_gate_up, l)); }));
             LD_TIMED(LD_PROF_DOWN, timed_void([&] {
-                ld::launch_gemm(mat(m.wdown[l]), A, T, d, c.d_ffn, ld::GEMM_ADD, w.x, st, to_next.g ? &to_next : nullptr, f16_flag);
+                ld::launch_gemm(mat(m.wdown[l]), A, T, d, c.d_ffn, ld::GEMM_ADD, w.x, st, to_next.g ? &to_next : nullptr, f16_flag, img(m.h_down, l));
             }));
         }
         LD_HIP_TRY(hipGetLastError());
     } else
     for (int l = 0; l < c.n_layers; l++) {
         void *pool_l = kv->pool + (size_t)l * layer_bytes;
+        auto img = [&](const std::vector<const uint16_t *> &v) { return f16_flag && !v.empty() ? v[l] : nullptr; };
         if (T == 1 || !f16_flag)
             LD_TIMED(LD_PROF_QKV, ldk_qkv_rope(m.wqkv[l], c.dtype, w.x, m.attn_norm[l], c.rms_eps, w.qkv, w.cos_sin, d_pos,
                                                d_slot, w.table, kv->max_blocks, pool_l, T, d, H, Hkv, hd, w.lin_scratch, w.lin_scratch_bytes, st));
         else {
             LD_TIMED(LD_PROF_QKV, ld::linear_pass(m.wqkv[l], c.dtype, w.x, m.attn_norm[l], c.rms_eps, T, nqkv, d, LDK_STORE, w.qkv,
-                                                  w.lin_scratch, w.lin_scratch_bytes, st, f16_flag));
+                                                  w.lin_scratch, w.lin_scratch_bytes, st, f16_flag, img(m.h_qkv)));
             LD_TIMED(LD_PROF_QKV, ldk_rope_kv_write(w.qkv, w.cos_sin, d_pos, d_slot, w.table, kv->max_blocks, pool_l, c.dtype, T, H, Hkv, hd, st));
         }
         if (n_dec_rows)
@@ -422,10 +426,10 @@ ld_status enqueue_pass(ld_kv *kv, const std::vector<Row> &rows, int n_single, co
             LD_TIMED(LD_PROF_ATTENTION, ldk_prefill_attention_f16(w.qkv, nqkv, pool_l, c.dtype, w.table, kv->max_blocks, d_tiles,
                                                                   n_tiles, H, Hkv, hd, c.window, max_ctx - 1, w.attn,
                                                                   w.att_scratch, w.att_scratch_bytes, f16_flag, st));
-        LD_TIMED(LD_PROF_WO, ld::linear_pass(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st, f16_flag));
+        LD_TIMED(LD_PROF_WO, ld::linear_pass(m.wo[l], c.dtype, w.attn, nullptr, 0.f, T, d, nq, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st, f16_flag, img(m.h_wo)));
         LD_TIMED(LD_PROF_GATE_UP, ld::linear_pass(m.wgate_up[l], c.dtype, w.x, m.ffn_norm[l], c.rms_eps, T, c.d_ffn, d, LDK_SWIGLU, w.act, w.lin_scratch,
-                                                    w.lin_scratch_bytes, st, f16_flag));
-        LD_TIMED(LD_PROF_DOWN, ld::linear_pass(m.wdown[l], c.dtype, w.act, nullptr, 0.f, T, d, c.d_ffn, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st, f16_flag));
+                                                    w.lin_scratch_bytes, st, f16_flag, img(m.h_gate_up)));
+        LD_TIMED(LD_PROF_DOWN, ld::linear_pass(m.wdown[l], c.dtype, w.act, nullptr, 0.f, T, d, c.d_ffn, LDK_ADD, w.x, w.lin_scratch, w.lin_scratch_bytes, st, f16_flag, img(m.h_down)));
     }
     if (T == 1 && R == 1) {
         // one row, and it emits: the final norm rides in the LM head's own pass over x (as in every layer)
@@ -631,6 +635,50 @@ ld_status ld_model_create(const ld_model_config *cfg, const ld_weights *w, ld_mo
 }
 
 void ld_model_destroy(ld_model *m) { delete m; }
+
+size_t ld_model_f16_image_bytes(const ld_model *m) {
+    if (!m || m->c.dtype != LD_BF16) return 0;
+    return (size_t)m->c.n_layers * m->layer_matrix_elems() * 2;
+}
+
+ld_status ld_model_attach_f16_image(ld_model *m, void *buf, size_t bytes, void *stream, int32_t *in_range) {
+    if (!m) return fail(LD_E_INVAL, "ld_model_attach_f16_image: null model");
+    m->h_qkv.clear(); m->h_wo.clear(); m->h_gate_up.clear(); m->h_down.clear();
+    if (in_range) *in_range = 0;
+    if (!buf) return LD_OK;                                     // detached
+    const ld_model_config &c = m->c;
+    const size_t need = ld_model_f16_image_bytes(m);
+    if (need == 0) return fail(LD_E_INVAL, "ld_model_attach_f16_image: the model has no bf16 layer matrices");
+    if (bytes < need + 256 || ((uintptr_t)buf & 15)) {
+        ld::set_error("ld_model_attach_f16_image: %zu bytes given, %zu + 256 needed, 16-byte aligned", bytes, need);
+        return LD_E_INVAL;
+    }
+    // the flag lives in the buffer's last 256 bytes, so that no workspace is needed here
+    hipStream_t st = (hipStream_t)stream;
+    uint16_t *p = (uint16_t *)buf;
+    int *flag = (int *)((char *)buf + need);
+    LD_HIP_TRY(hipMemsetAsync(flag, 0, 4, st));
+    std::vector<const uint16_t *> q, o, g, dn;
+    auto conv = [&](const void *W, size_t n, std::vector<const uint16_t *> &v) {
+        ld::launch_weight_to_f16((const uint16_t *)W, (int64_t)n, p, flag, st);
+        v.push_back(p);
+        p += n;
+    };
+    for (int l = 0; l < c.n_layers; l++) {
+        conv(m->wqkv[l], (size_t)m->nqkv() * c.d_model, q);
+        conv(m->wo[l], (size_t)c.d_model * m->nq(), o);
+        conv(m->wgate_up[l], (size_t)2 * c.d_ffn * c.d_model, g);
+        conv(m->wdown[l], (size_t)c.d_model * c.d_ffn, dn);
+    }
+    LD_HIP_TRY(hipGetLastError());
+    int32_t bad = 1;
+    LD_HIP_TRY(hipMemcpyAsync(&bad, flag, 4, hipMemcpyDeviceToHost, st));
+    LD_HIP_TRY(hipStreamSynchronize(st));
+    m->f16_weights = bad ? 0 : 1;
+    if (!bad) { m->h_qkv = q; m->h_wo = o; m->h_gate_up = g; m->h_down = dn; }
+    if (in_range) *in_range = bad ? 0 : 1;
+    return LD_OK;
+}
 
 size_t ld_kv_bytes(const ld_model *m, int64_t n_blocks) {
     if (!m || n_blocks <= 0) return 0;

@@ -40,10 +40,10 @@ ld_status paged_attention_split(const float *q, int q_stride, const void *pool_l
                                 int H, int Hkv, int hd, int window, uint16_t *xs_out, void *scratch,
                                 size_t scratch_bytes, hipStream_t stream, int image_rows = 0);
 
-// ldk_linear for the rows of an engine pass: f16_flag as in launch_gemm (nullptr: ldk_linear itself).
+// ldk_linear for the rows of an engine pass: f16_flag and W_f16 as in launch_gemm (nullptr: ldk_linear itself).
 ld_status linear_pass(const void *W, int32_t dtype, const float *x, const float *g, float eps, int32_t T, int32_t N,
                       int32_t K, int32_t epilogue, float *y, void *scratch, size_t scratch_bytes, void *stream,
-                      int *f16_flag);
+                      int *f16_flag, const void *W_f16 = nullptr);
 // Integer value of an environment variable (a tuning knob), dflt when unset.
 int env_flag(const char *name, int dflt);
 

@@ -555,14 +555,21 @@ ld_status ldk_linear(const void *W, int32_t dtype, const float *x, const float *
     return ld::linear_pass(W, dtype, x, g, eps, T, N, K, epilogue, y, scratch, scratch_bytes, stream, nullptr);
 }
 
-ld_status ldk_linear_f16(const void *W, const float *x, const float *g, float eps, int32_t T, int32_t N, int32_t K,
-                         int32_t epilogue, float *y, void *scratch, size_t scratch_bytes, int32_t *overflow,
-                         void *stream) {
+ld_status ldk_linear_f16(const void *W, const void *W_f16, const float *x, const float *g, float eps, int32_t T,
+                         int32_t N, int32_t K, int32_t epilogue, float *y, void *scratch, size_t scratch_bytes,
+                         int32_t *overflow, void *stream) {
     if (!overflow) return ld::fail(LD_E_INVAL, "ldk_linear_f16: null overflow flag");
-    if (T > 0 && W && N > 0 && K > 0 && K % 8 == 0)
+    if (!W_f16 && T > 0 && W && N > 0 && K > 0 && K % 8 == 0)   // an image was checked when it was made
         ld::launch_weight_range_check((const uint16_t *)W, (int64_t)N * (epilogue == LDK_SWIGLU ? 2 : 1) * K, overflow,
                                       (hipStream_t)stream);
-    return ld::linear_pass(W, LD_BF16, x, g, eps, T, N, K, epilogue, y, scratch, scratch_bytes, stream, overflow);
+    return ld::linear_pass(W, LD_BF16, x, g, eps, T, N, K, epilogue, y, scratch, scratch_bytes, stream, overflow, W_f16);
+}
+
+ld_status ldk_weights_to_f16(const void *W, int64_t n, void *out, int32_t *overflow, void *stream) {
+    if (!W || !out || !overflow || n < 0 || n % 8) return ld::fail(LD_E_INVAL, "ldk_weights_to_f16: bad argument (n must be a multiple of 8)");
+    if (n == 0) return LD_OK;
+    ld::launch_weight_to_f16((const uint16_t *)W, n, (uint16_t *)out, overflow, (hipStream_t)stream);
+    return launched("k_weight_to_f16");
 }
 
 }  // extern "C"
@@ -574,7 +581,7 @@ int ld::env_flag(const char *name, int dflt) {
 
 ld_status ld::linear_pass(const void *W, int32_t dtype, const float *x, const float *g, float eps, int32_t T, int32_t N,
                           int32_t K, int32_t epilogue, float *y, void *scratch, size_t scratch_bytes, void *stream,
-                          int *f16_flag) {
+                          int *f16_flag, const void *W_f16) {
     if (T == 0) return LD_OK;   // nothing to do: pointers of empty buffers may be null
     if (!W || !x || !y || T < 0 || N <= 0 || K <= 0 || K % 8 || epilogue < 0 || epilogue > 2)
         return ld::fail(LD_E_INVAL, "ldk_linear: bad argument (K must be a multiple of 8)");
@@ -585,7 +592,7 @@ ld_status ld::linear_pass(const void *W, int32_t dtype, const float *x, const fl
     }
     if (dtype == LD_BF16 && scratch && ld::gemm_supported(T, N, K) && scratch_bytes >= ld::gemm_scratch_bytes(T, N, K, epilogue)) {
         ld::launch_norm_split(x, g, eps, T, K, (uint16_t *)scratch, s);
-        ld::launch_gemm((const bf16_t *)W, (uint16_t *)scratch, T, N, K, epilogue, y, s, nullptr, f16_flag);
+        ld::launch_gemm((const bf16_t *)W, (uint16_t *)scratch, T, N, K, epilogue, y, s, nullptr, f16_flag, (const uint16_t *)W_f16);
         return launched("k_gemm_mfma");
     }
     if (dtype == LD_BF16) {

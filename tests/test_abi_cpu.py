@@ -79,6 +79,25 @@ def test_pool_size_formula():
         ld.ld_kv_create(m, FAKE + 8, 4, FAKE, 1 << 40, 8, 2, 2)   # misaligned pool
 
 
+def test_f16_image_size_and_argument_checks():
+    """Two bytes per layer-matrix entry for bf16 models, nothing for float32 ones; too small or misaligned a buffer
+    is refused before any device memory is touched, and detaching needs no device."""
+    m = _model(dtype=ld.LD_BF16, n_kv_heads=2)
+    per_layer = (4 + 2 * 2) * 64 * 256 + 4 * 64 * 256 + 3 * 688 * 256
+    assert ld.ld_model_f16_image_bytes(m) == 2 * 2 * per_layer
+    assert ld.ld_model_f16_image_bytes(_model()) == 0
+
+    def attach(model, ptr, nbytes):
+        ok = C.c_int32(7)
+        return ld.lib().ld_model_attach_f16_image(model, C.c_void_p(ptr), nbytes, None, C.byref(ok)), ok.value
+
+    need = ld.ld_model_f16_image_bytes(m)
+    assert attach(m, FAKE, need) == (ld.LD_E_INVAL, 0)            # the 256 bytes behind the image are missing
+    assert attach(m, FAKE + 8, need + 256) == (ld.LD_E_INVAL, 0)  # misaligned
+    assert attach(_model(), FAKE, 1 << 30) == (ld.LD_E_INVAL, 0)  # float32 model
+    assert attach(m, None, 0) == (ld.LD_OK, 0)                    # detach
+
+
 def test_allocator_matches_oracle_allocator_bit_exact():
     """Random alloc / map / grow / free traffic: block tables and free counts equal the oracle's."""
     from workloads import make_weights

@@ -631,8 +631,10 @@ def test_long_chunk_takes_fp16_rows_and_falls_back():
     """A pass of 512 rows or more takes its big-tile products with the activations rounded to fp16.  A 520-token
     prompt in one chunk at 7B width (one layer): the logits differ from those of the two-term form (LD_GEMM_F16=0,
     read per pass) and both are within tolerance of the oracle; the tokens that follow agree with the oracle's.
-    With a gain that lifts the layer's FFN input beyond the fp16 range (65504) the pass is found out and repeated
-    with two terms: bit-equal to the two-term run of the same model."""
+    With the fp16 copy of the layer matrices attached (ld_model_attach_f16_image) the fp16 run is bit-equal to the one
+    without.  With a gain that lifts the layer's FFN input beyond the fp16 range (65504) the pass is found out and
+    repeated with two terms: bit-equal to the two-term run of the same model.  A layer matrix with an entry beyond
+    the range: the image is refused and the model keeps two terms."""
     import os
     shape = LLAMA7B.with_layers(1)
     seed = SEED_BASE + 11
@@ -667,6 +669,17 @@ def test_long_chunk_takes_fp16_rows_and_falls_back():
     print("520-row chunk: logits rel err, fp16 rows", e_h, "two terms", e_2)
     assert not np.array_equal(lg_h, lg_2) and e_2 <= 1e-3 and e_2 < e_h <= 2e-2
     assert toks_h == toks_o and toks_2 == toks_o
+    assert ld.ld_model_f16_image_bytes(models[1].h) == 2 * sum(models[1].weights[k][0].numel() for k in ("wqkv", "wo", "wgate_up", "wdown"))
+    assert models[1].attach_f16_image() is True
+    lg_i, toks_i = run(models, True, False)
+    assert np.array_equal(lg_i, lg_h) and toks_i == toks_h
+    lg_i2, toks_i2 = run(models, False, False)              # the knob still decides
+    assert np.array_equal(lg_i2, lg_2)
+    models[1].detach_f16_image()
+    lg_i, toks_i = run(models, True, False)
+    assert np.array_equal(lg_i, lg_h)
+    with pytest.raises(ld.LdError):                          # too small a buffer
+        ld.ld_model_attach_f16_image(models[1].h, torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
 
     w["ffn_norm"][0] = w["ffn_norm"][0] * 1.0e5       # normalised rows times the gain: far beyond 65504
     models = (oracle.Model(shape, w), ld.Model(shape, weights_to(w, "cuda"), max_chunk=1024))
@@ -674,3 +687,15 @@ def test_long_chunk_takes_fp16_rows_and_falls_back():
     lg_2, toks_2 = run(models, False, False)
     print("with the large gain: logits rel err", rel_err(lg_h, lg_o))
     assert np.array_equal(lg_h, lg_2) and toks_h == toks_2 == toks_o and rel_err(lg_h, lg_o) <= 2e-2
+    assert models[1].attach_f16_image() is True              # the weights are in range; the activations are not
+    lg_i, toks_i = run(models, True, False)
+    assert np.array_equal(lg_i, lg_2) and toks_i == toks_2
+
+    w["ffn_norm"][0] = w["ffn_norm"][0] * 1.0e-5
+    wd = w["wdown"][0].clone(); wd[5, 7] = 1.0e5; w["wdown"][0] = wd
+    gm = ld.Model(shape, weights_to(w, "cuda"), max_chunk=1024)
+    models = (oracle.Model(shape, w), gm)
+    assert gm.attach_f16_image() is False and gm.f16_image is None
+    lg_h, toks_h = run(models, True, False)
+    lg_2, toks_2 = run(models, False, False)
+    assert np.array_equal(lg_h, lg_2) and toks_h == toks_2

@@ -469,8 +469,9 @@ def test_linear_fp16_rows_sampled():
     remains is float32 accumulation: the two-term test's bound) and
     against the oracle on the exact inputs (the rounding itself: 2^-12 per term, random walk over K terms).  Row
     counts with a tail that keeps both terms (1056, 2111), with three and one row tiles, and one that stays on the
-    small-batch kernel (32: bit-equal to ldk_linear).  A value beyond the fp16 range in the input or in the matrix
-    raises the flag."""
+    small-batch kernel (32: bit-equal to ldk_linear).  With the matrix's fp16 image (ldk_weights_to_f16: equal to the
+    bf16 values entry by entry, truncated toward zero below 2^-17 where fp16 has no bits left) the same call gives
+    bit-equal results.  A value beyond the fp16 range in the input or in the matrix raises the flag."""
     flag = torch.zeros(1, dtype=torch.int32, device=DEV)
     for T in (32, 256, 768, 1056, 2111):
         for N, K, epi in [(12288, 4096, ld.LDK_STORE), (4096, 11008, ld.LDK_ADD), (11008, 4096, ld.LDK_SWIGLU)]:
@@ -488,6 +489,16 @@ def test_linear_fp16_rows_sampled():
                 assert torch.equal(y, y2)
             else:
                 assert not torch.equal(y[:T - r], y2[:T - r])     # the single-term form did run
+            Wh = torch.zeros(rows, K, dtype=torch.float16, device=DEV); y3 = torch.zeros(T, N, device=DEV)
+            ld.ldk_weights_to_f16(W, Wh, flag)
+            assert int(flag.item()) == 0
+            wf, whf = W.float(), Wh.float()
+            fits = wf.abs() >= 2.0 ** -17
+            assert torch.equal(whf[fits], wf[fits])
+            assert bool(((whf.abs() <= wf.abs()) & ((wf - whf).abs() < 2.0 ** -24) & (whf * wf >= 0))[~fits].all())
+            ld.ldk_linear_f16(W, x, y3, flag, epi, scratch=scratch, W_f16=Wh)
+            assert int(flag.item()) == 0 and torch.equal(y3, y)
+            del Wh, wf, whf, fits, y3
             ns = gen.randint(3, 9, 0, N - 1, 6).tolist() + [0, N - 1]
             ts = sorted(set(gen.randint(3, 10, 0, T - 1, 5).tolist() + [0, T - 1, max(T - T % 256 - 1, 0), min(T - T % 256, T - 1)]))
             xh = x.cpu().numpy(); yh = y.cpu().numpy()
@@ -519,8 +530,39 @@ def test_linear_fp16_rows_sampled():
     flag.zero_(); ld.ldk_linear_f16(W, xb, y, flag, scratch=scratch); assert int(flag.item()) == 0
     Wb = W.clone(); Wb[4000, 4095] = 1.0e5
     flag.zero_(); ld.ldk_linear_f16(Wb, x, y, flag, scratch=scratch); assert int(flag.item()) == 1
+    Wh = torch.zeros(N, K, dtype=torch.float16, device=DEV)
+    flag.zero_(); ld.ldk_weights_to_f16(Wb, Wh, flag); assert int(flag.item()) == 1
     Wb[4000, 4095] = float("nan")
     flag.zero_(); ld.ldk_linear_f16(Wb, x, y, flag, scratch=scratch); assert int(flag.item()) == 1
+    flag.zero_(); ld.ldk_weights_to_f16(Wb, Wh, flag); assert int(flag.item()) == 1
+    Wb[4000, 4095] = -65504.0 * 0.75   # bf16 has no 65504; -49128 rounds to a bf16 within range
+    flag.zero_(); ld.ldk_weights_to_f16(Wb, Wh, flag); assert int(flag.item()) == 0 and float(Wh[4000, 4095]) == float(Wb[4000, 4095])
+
+
+def test_linear_fp16_image_13b_shapes_bit_equal():
+    """The four layer matrices of the 13B shape at the row count of its batch-64 step (63 decode rows beside a
+    2048-row chunk): the fp16 form gives the same bits whether the kernel widens the bf16 weights itself or reads
+    the matrix's fp16 image, and differs from the two-term form (so it did run)."""
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    T = 2111
+    for N, K, epi in [(15360, 5120, ld.LDK_STORE), (5120, 5120, ld.LDK_ADD), (5120, 13824, ld.LDK_ADD), (13824, 5120, ld.LDK_SWIGLU)]:
+        rows = N * (2 if epi == ld.LDK_SWIGLU else 1)
+        W = gen.normal(5, N, (rows, K), std=0.02, device=DEV).bfloat16()
+        x = gen.normal(5, 7 + K, (T, K), device=DEV)
+        y0 = gen.normal(5, 8, (T, N), device=DEV)                 # the residual that LDK_ADD adds to
+        scratch = torch.empty(ld.ldk_linear_scratch_bytes(T, N, K, epi), dtype=torch.uint8, device=DEV)
+        Wh = torch.zeros(rows, K, dtype=torch.float16, device=DEV)
+        ld.ldk_weights_to_f16(W, Wh, flag)
+        outs = []
+        for img in (None, Wh):
+            y = y0.clone()
+            ld.ldk_linear_f16(W, x, y, flag, epi, scratch=scratch, W_f16=img)
+            outs.append(y)
+        y2 = y0.clone()
+        ld.ldk_linear(W, x, y2, epi, scratch=scratch)
+        assert int(flag.item()) == 0
+        assert torch.equal(outs[0], outs[1]) and not torch.equal(outs[0], y2), (N, K, epi)
+        assert float((outs[0] - y2).abs().max()) <= 2e-3 * max(1.0, float(y2.abs().max()))
 
 
 @pytest.mark.parametrize("split", [False, True], ids=["whole", "kv-split"])

@@ -914,7 +914,9 @@ int env_int(const char *name, int dflt) {
 // the 128 x 128 tile, at half the rate each); the per-CU rates are the measured full-grid rates of the three
 // tiles; split-K adds the write and the ordered re-read of its partial sums.
 struct BigPlan { int wm, bn, n_ttiles, n_nblocks, ks; double est_us; int nb_a, ks_b; };   // nb_a > 0: two phases
-// f16: the single-term fp16 form (measured 0.69 of the two-term time on the layer shapes).
+// f16: the single-term fp16 form.  Its three constants (0.69 of the two-term time per workgroup, split-K partial
+// sums at a third of the two-term form's cost per byte, the last-round factor below) are fitted to the measured
+// times of the 7B, grouped-KV and 13B layer shapes at 1056, 2048 and 2111 rows.
 BigPlan plan_big(int T, int N, int K, int epi, bool f16 = false) {
     const bool swi = epi == ld::GEMM_SWIGLU;
     struct Tile { int wm, bn; double tflops; };           // nominal (unsplit) TFLOP/s of a full grid
@@ -936,7 +938,10 @@ BigPlan plan_big(int T, int N, int K, int epi, bool f16 = false) {
             const int64_t rounds = (wgs + 255) / 256;
             const double wg_us = (f16 ? 0.69 : 1.0) * 2.0 * bm * tl.bn * (double)(K / ks) / (tl.tflops * 1e6 / 256.0);
             double t = rounds * wg_us;
-            if (ks > 1) t += 3.0 + (double)T * N * (swi ? 2 : 1) * 4.0 * (2.0 * ks + 1.0) / 3.0e6;
+            // fp16 form: a last round that leaves CUs idle runs its workgroups faster than a full one (measured on
+            // the 13B down projection: 180 workgroups in 0.74 of a full round's time)
+            if (f16 && wgs % 256) t = (double)(wgs / 256) * wg_us + std::max((double)(wgs % 256) / 256.0, 0.74) * wg_us;
+            if (ks > 1) t += 3.0 + (double)T * N * (swi ? 2 : 1) * 4.0 * (2.0 * ks + 1.0) / (f16 ? 9.0e6 : 3.0e6);
             if (t < best_t) { best_t = t; best = {tl.wm, tl.bn, n_tt, n_nb, ks, t, 0, 0}; }
         }
         // Two phases: the column blocks that fill a whole round run unsplit; the remaining blocks, which would

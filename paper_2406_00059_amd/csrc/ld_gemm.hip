@@ -1098,10 +1098,12 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
         LD_LAUNCH((k_gemm_dma<WM_, BN_, S_, EPI_, WN_, F16_>), dim3(grid), dim3(64 * WM_ * WN_), lds_bytes, s, W, hi,   \
                   lo, T, N, K, y, n_ttiles, ks, partial, col0, col1, hi_out, lo_out);                                  \
     } while (0)
+    // The fp16 form has one operand image to stage, so the 256 x 256 tile fits a fourth stage into the CU's 160 KB
+    // (128 KB): with the weight image, 5 - 9 % on the layer shapes at 2048 rows, level at 1056; a fifth changes nothing.
 #define LD_DMA(WM_, BN_, S_, EPI_, WN_)                                                                                \
     do {                                                                                                               \
-        if (f16 == 2) LD_DMA_M(WM_, BN_, S_, EPI_, WN_, 2);                                                            \
-        else if (f16) LD_DMA_M(WM_, BN_, S_, EPI_, WN_, 1);                                                            \
+        if (f16 == 2) LD_DMA_M(WM_, BN_, (WM_ == 4 ? 4 : S_), EPI_, WN_, 2);                                           \
+        else if (f16) LD_DMA_M(WM_, BN_, (WM_ == 4 ? 4 : S_), EPI_, WN_, 1);                                           \
         else LD_DMA_M(WM_, BN_, S_, EPI_, WN_, 0);                                                                     \
         if (ks > 1 && reduce)                                                                                          \
             LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1, hi_out, lo_out); \

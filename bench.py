@@ -30,7 +30,7 @@ HBM_PEAK = 8.0e12          # bytes/s, MI355X HBM3E
 TRAFFIC_BYTES = 180_870_000
 TRAFFIC_KERNEL_MD5 = "0468ef4efdc5"
 ATTN_TRAFFIC_RATIO = 1.007
-ATTN_TRAFFIC_MD5 = "b7341b8ce711"
+ATTN_TRAFFIC_MD5 = "ef39af836308"
 ROUND_TOKENS = 256         # tokens emitted per round (1 by the preceding prefill + 255 decode steps)
 CHUNK = 256
 

@@ -606,10 +606,12 @@ __global__ __launch_bounds__(128 * WM) void k_gemm_big(const bf16_t *__restrict_
 // the same tile: layer GEMMs at 128 - 512 rows 4 - 7 % faster, the full-grid rate 410 -> 440 TFLOP/s; sixteen
 // waves of 64 x 64 on the 256 x 256 tile fit in 109 registers and change nothing).
 //
-// F16 (rows that nobody reads at full precision, see launch_gemm): one operand image instead of two, the activations
-// rounded to fp16 (11 significant bits; xhi then points at a [T, K] fp16 matrix), the bf16 weights turned into
-// fp16 on their way from LDS to the matrix cores (exact for 2^-14 <= |w| < 65520, which the launcher has checked
-// on the whole matrix): half the matrix-core work and two thirds of the operand traffic of the two-term form.
+// F16 != 0 (rows that nobody reads at full precision, see launch_gemm): one operand image instead of two, the
+// activations rounded to fp16 (11 significant bits; xhi then points at a [T, K] fp16 matrix): half the matrix-core
+// work and two thirds of the operand traffic of the two-term form.  F16 == 1: W is the bf16 matrix and every wave
+// turns the fragments it reads from LDS into fp16 on their way to the matrix cores (exact for 2^-14 <= |w| < 65520,
+// which the launcher has checked on the whole matrix).  F16 == 2: W is the matrix's fp16 image (k_weight_to_f16),
+// used as it is; same values, same sums.
 template <int WM, int BN, int S, int EPI, int WN, int F16>
 __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restrict__ W, const bf16_t *__restrict__ xhi,
                                                        const bf16_t *__restrict__ xlo, int T, int N, int K,

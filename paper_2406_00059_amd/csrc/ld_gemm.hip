@@ -637,21 +637,27 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
     const int n_nblocks = (col1 - col0 + NOUT - 1) / NOUT;   // this launch covers output columns [col0, col1)
     if (nb >= n_nblocks) return;
     const int t0 = tt_idx * BM, n0 = col0 + nb * NOUT;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // the wave index as a scalar: what depends on it alone (which rows a copy covers, its LDS address) stays in SGPRs
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int wm = wave / WN, wn = wave % WN;
 
-    // global source of the piece this lane fetches in copy j of a chunk (rows clamped; clamped rows are never stored)
-    const bf16_t *src[P];
+    // Global source of the piece this lane fetches in copy j of a chunk: a base pointer that is the same for the
+    // whole wave (the 16 rows of a copy lie in one of the three matrices) plus a 32-bit byte offset per lane, the
+    // form in which the copy instruction takes a scalar base and advancing along K is scalar arithmetic (the
+    // launcher keeps matrices of 4 GB or more away).  Rows are clamped; clamped rows are never stored.
+    const char *cbase[P];
+    uint32_t coff[P];
 #pragma unroll
     for (int j = 0; j < P; j++) {
-        const int vr = (wave * P + j) * 16 + (lane >> 2);          // row of the stage
+        const int vr0 = (wave * P + j) * 16;                       // first row of the copy (scalar)
+        const int vr = vr0 + (lane >> 2);                          // row of the stage
         const int slot = lane & 3;
         const int seg = slot ^ ((vr >> 2) & 3);
-        const bf16_t *rowp;
-        if (vr < XR) {
+        if (vr0 < XR) {
             const int r = vr % BM;
-            rowp = (vr < BM ? xhi : xlo) + (int64_t)min(t0 + r, T - 1) * K;
+            cbase[j] = reinterpret_cast<const char *>(vr0 < BM ? xhi : xlo);
+            coff[j] = ((uint32_t)min(t0 + r, T - 1) * (uint32_t)K + seg * 8) * 2u;
         } else {
             const int wr = vr - XR;
             int grow;
@@ -662,15 +668,15 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
             } else {
                 grow = min(n0 + wr, N - 1);
             }
-            rowp = W + (int64_t)grow * K;
+            cbase[j] = reinterpret_cast<const char *>(W);
+            coff[j] = ((uint32_t)grow * (uint32_t)K + seg * 8) * 2u;
         }
-        src[j] = rowp + seg * 8;
     }
     auto copy_chunk = [&](int kc, int st) {
 #pragma unroll
         for (int j = 0; j < P; j++)
             __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(src[j] + kc * BK),
+                (const __attribute__((address_space(1))) void *)(cbase[j] + (size_t)kc * (BK * 2) + (size_t)coff[j]),
                 (__attribute__((address_space(3))) void *)(lds + st * STAGE + (wave * P + j) * 1024), 16, 0, 0);
     };
 
@@ -755,15 +761,30 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // 1 LDS read (2 * TERMS + WCT per half step)
         }
     };
-    for (int i = 0; i + 1 < n_chunks; i++) {      // every chunk but the last: the next one always exists
+    // every chunk but the last (the next one always exists): first the steady state, in which a chunk S - 1 ahead
+    // is still to be requested (no condition around the copies, so that their issue can sit between the MFMAs),
+    // then the last S - 2 of them
+    int i = 0;
+    for (; i + S - 1 < n_chunks; i++) {
         load_frags(f1, st, 1);
         mfmas(f0);
         interleave();
         const int st1 = st + 1 == S ? 0 : st + 1;
-        // copies outstanding now: chunks i+1 .. min(i+S-2, n-1); younger than chunk i+1: that many minus one
-        wait_copies(min(i + S - 2, n_chunks - 1) - (i + 1));
+        wait_copies(S - 3);                        // outstanding: chunks i+1 .. i+S-2
         asm volatile("s_barrier" ::: "memory");
-        if (i + S - 1 < n_chunks) copy_chunk(c_begin + i + S - 1, st == 0 ? S - 1 : st - 1);
+        copy_chunk(c_begin + i + S - 1, st == 0 ? S - 1 : st - 1);
+        load_frags(f0, st1, 0);
+        mfmas(f1);
+        interleave();
+        st = st1;
+    }
+    for (; i + 1 < n_chunks; i++) {
+        load_frags(f1, st, 1);
+        mfmas(f0);
+        interleave();
+        const int st1 = st + 1 == S ? 0 : st + 1;
+        wait_copies(n_chunks - 1 - (i + 1));       // outstanding: chunks i+1 .. n-1
+        asm volatile("s_barrier" ::: "memory");
         load_frags(f0, st1, 0);
         mfmas(f1);
         interleave();
@@ -1073,6 +1094,12 @@ void launch_gemm_skinny(const uint16_t *W, const uint16_t *xhi, const uint16_t *
     skinny_launch(W, xhi, xlo, T, n_rows, K, ks, partial, s);
 }
 
+// The direct-to-LDS kernel addresses its operands with 32-bit byte offsets from the start of each matrix.
+static bool dma_offsets_fit(int T, int N, int K, int epi) {
+    const int64_t lim = (int64_t)1 << 32;
+    return (int64_t)T * K * 2 < lim && (int64_t)N * (epi == GEMM_SWIGLU ? 2 : 1) * K * 2 < lim;
+}
+
 // One launch of the big-tile kernel over output columns [col0, col1) with split factor ks (+ its reduction).
 static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *lo, int T, int N, int K, int epi, float *y,
                             float *partial, int wm, int bn, int n_ttiles, int ks, int col0, int col1, hipStream_t s,
@@ -1111,7 +1138,7 @@ static void launch_big_cols(const uint16_t *W, const bf16_t *hi, const bf16_t *l
             LD_LAUNCH((k_splitk_reduce<EPI_>), dim3(rgrid), dim3(256), 0, s, partial, T, N, ks, y, col0, col1, hi_out, lo_out); \
     } while (0)
     // 256-row weight tiles: operands copied straight into LDS (the slab needs a few chunks to fill the stages)
-    if (bn == 256 && (K / 32) / ks >= 4) {
+    if (bn == 256 && (K / 32) / ks >= 4 && dma_offsets_fit(T, N, K, epi)) {
         if (wm == 4) {          // 256 x 256: eight waves, 64 x 128 each
             if (epi == GEMM_STORE) LD_DMA(4, 256, 3, GEMM_STORE, 2);
             else if (epi == GEMM_ADD) LD_DMA(4, 256, 3, GEMM_ADD, 2);
@@ -1152,7 +1179,9 @@ struct RowsNext { const float *g; float eps; bf16_t *hi, *lo; const RopeKvArgs *
 static bool f16_plan_ok(const BigPlan &p, int K) {
     return p.bn == 256 && (K / 32) / std::max(p.ks, 1) >= 4 && (p.nb_a == 0 || (K / 32) / std::max(p.ks_b, 1) >= 4);
 }
-bool gemm_f16_rows(int T, int N, int K, int epi) { return T > 64 && f16_plan_ok(plan_big(T, N, K, epi, true), K); }
+bool gemm_f16_rows(int T, int N, int K, int epi) {
+    return T > 64 && dma_offsets_fit(T, N, K, epi) && f16_plan_ok(plan_big(T, N, K, epi, true), K);
+}
 
 // f16_flag != nullptr (more than 64 rows, gemm_f16_rows): the rows' images are turned into one fp16 image in place
 // and multiplied in the single-term form; *f16_flag is set if an activation does not fit.  W16: the matrix's fp16

@@ -761,6 +761,17 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // 1 LDS read (2 * TERMS + WCT per half step)
         }
     };
+    // the half step that also requests a chunk: its P copies one by one between the MFMAs rather than in a row
+    // behind the barrier (1 - 3 % on the layer shapes)
+    auto interleave_copies = [&]() {
+        constexpr int NM = 2 * TERMS * WCT, NR = 2 * TERMS + WCT, CSTEP = NM / P > 0 ? NM / P : 1;
+#pragma unroll
+        for (int k = 0; k < NM; k++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (k % TERMS == TERMS - 1 && k / TERMS < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (k % CSTEP == CSTEP - 1 && k / CSTEP < P) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+    };
     // every chunk but the last (the next one always exists): first the steady state, in which a chunk S - 1 ahead
     // is still to be requested (no condition around the copies, so that their issue can sit between the MFMAs),
     // then the last S - 2 of them
@@ -775,7 +786,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_gemm_dma(const bf16_t *__restr
         copy_chunk(c_begin + i + S - 1, st == 0 ? S - 1 : st - 1);
         load_frags(f0, st1, 0);
         mfmas(f1);
-        interleave();
+        interleave_copies();
         st = st1;
     }
     for (; i + 1 < n_chunks; i++) {
